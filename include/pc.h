@@ -1,0 +1,178 @@
+/*
+ * pc.h - C ABI of the choreographed-attention library for AMD MI355X (gfx950).
+ *
+ * The library implements the attention step of Prompt Choreography
+ * (arXiv 2512.23049): a dynamic, global, append-only KV cache of messages, and
+ * attention calls whose query tokens attend over an arbitrary, reordered subset
+ * of cached messages, each placed at a caller-chosen start position (gaps and
+ * overlaps allowed), with many parallel calls batched (Sec. 2.1 "Core Idea",
+ * Sec. 2.3 "A Prompt Choreography API", Sec. 2.4 "Managing the KV Cache").
+ *
+ * The unit of this interface is tensors, not text: the caller (an LLM layer)
+ * supplies K/V of a new message and the query rows; tokenisation, sampling and
+ * the rest of the model are outside.
+ *
+ * Conventions
+ *  - Every function returns an int32 status: PC_OK (0) or a negative PC_ERR_*.
+ *    pc_last_error() returns a NUL-terminated description owned by the cache
+ *    (valid until the next failing call on that cache).  Nothing throws.
+ *  - Pointers named k, v, q, out, lse, kv_slot, kv_pos are DEVICE pointers owned
+ *    by the caller.  All other pointers are HOST pointers; list arguments are
+ *    copied before the function returns, so the caller may free them at once.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All
+ *    device work is enqueued on it and is stream-ordered; no function waits for
+ *    the device, except that a workspace may be (re)allocated on first use of a
+ *    larger batch shape.  Calls on one cache must come from one thread at a time
+ *    and on one stream (or on streams the caller orders with events).
+ *  - Errors that the host can detect (unknown id, capacity, bad shapes, positions
+ *    out of range) are returned BEFORE anything is enqueued.
+ *  - Message ids are 0, 1, 2, ... in append order (Sec. 2.4: ids map to
+ *    contiguous physical spans of the cache).
+ */
+#ifndef PC_H_
+#define PC_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define PC_OK               0
+#define PC_ERR_INVALID_ARG (-1)
+#define PC_ERR_BAD_MSG_ID  (-2)
+#define PC_ERR_NO_SPACE    (-3)
+#define PC_ERR_SHAPE       (-4)
+#define PC_ERR_HIP         (-5)
+
+#define PC_F32  0
+#define PC_BF16 1
+
+/* "omitted offset": the position right after the end of the preceding list entry
+ * (Sec. 2.3: "Any omitted offset defaults to the position immediately after the
+ * end of the preceding parent message").  For the first entry it means 0; for the
+ * new message it means right after the last list entry (0 if the list is empty). */
+#define PC_POS_AUTO INT32_MIN
+
+/* Every message starts at a slot that is a multiple of this (cache layout rule:
+ * message i starts at the first such slot at or after the end of message i-1's
+ * reserved span; message 0 starts at slot 0). */
+#define PC_SLOT_ALIGN 32
+
+/* pc_config.flags */
+#define PC_FLAG_HOST_ONLY 1u  /* no device memory, no launches: validation, allocation
+                                 and position resolution only (k/v/q/out are ignored) */
+
+typedef struct pc_cache pc_cache;
+
+typedef struct {
+    int32_t  n_q_heads;        /* H_q  (multiple of n_kv_heads)                          */
+    int32_t  n_kv_heads;       /* H_kv                                                  */
+    int32_t  head_dim;         /* D: 64 or 128                                          */
+    int32_t  dtype;            /* PC_F32 | PC_BF16: type of k, v, q, out and of storage */
+    float    rope_theta;       /* RoPE base, e.g. 1e4 or 5e5                            */
+    float    softmax_scale;    /* 0 -> 1/sqrt(D)                                        */
+    int64_t  capacity_tokens;  /* slots in the cache (rounded up to PC_SLOT_ALIGN)      */
+    int32_t  max_messages;
+    int32_t  max_position;     /* every token / query position p obeys |p| <= this      */
+    uint32_t flags;
+    void    *arena;            /* optional caller-owned DEVICE memory for K/V storage,  */
+    size_t   arena_bytes;      /*   >= pc_cache_storage_bytes(cfg); NULL -> hipMalloc   */
+} pc_config;
+
+/* Bytes of device memory the K/V storage needs for this configuration. */
+size_t  pc_cache_storage_bytes(const pc_config *cfg);
+
+/* Create / destroy the global cache (Sec. 2.4: pre-allocated, append-only store of
+ * K and V for every cached token plus the message -> span map).  One attention
+ * layer per cache object. */
+int32_t pc_cache_create(const pc_config *cfg, pc_cache **out);
+int32_t pc_cache_destroy(pc_cache *c);
+const char *pc_last_error(const pc_cache *c);
+
+/* Append one message (Sec. 2.3: prefill/decode "append a newly encoded message to
+ * the global KV cache and return a unique new identifier"; Sec. 2.4: new messages go
+ * at the end of the occupied part of the cache).
+ *   k, v     device, [len, n_kv_heads, head_dim] contiguous, cache dtype; k is the
+ *            UNROTATED key (no positional rotation applied by the caller).
+ *   reserve  slots to reserve for the message (0 or < len means len).
+ *   msg_id   receives the new id.
+ * The fused append kernel stores K turned to its in-message index (delta-rotated
+ * form) and V in the tile layout the attention kernels read. */
+int32_t pc_append_message(pc_cache *c, const void *k, const void *v, int32_t len,
+                          int32_t reserve, int32_t *msg_id, void *stream);
+
+/* One parent of a call: message id and the position of its first token
+ * (Sec. 2.3 `parents` and `offsets`). */
+typedef struct { int32_t msg_id; int32_t start_pos; } pc_sel;
+
+/* One attention call (Sec. 2.3 prefill/decode; Sec. 2.4 "Dynamic Masking": the new
+ * message's tokens see all tokens of `sel` and the earlier tokens of their own
+ * message; nothing else).
+ *   sel/n_sel   parents in list order; repeats allowed; any order of positions.
+ *   self_msg    id of the (already appended) new message, or -1 for none.
+ *   self_start  position of its first token (Sec. 2.3 `new_offset`) or PC_POS_AUTO.
+ *   n_q         number of query rows, >= 1; row r is the (len(self) - n_q + r)-th
+ *               token of the new message and sees own tokens up to and including
+ *               itself (prefill: n_q = len; decode: n_q = 1).  With self_msg = -1
+ *               the rows see the parents only.
+ *   q_pos       host, n_q positions of the query rows, or NULL for
+ *               self_start + token index. */
+typedef struct {
+    const pc_sel  *sel;
+    int32_t        n_sel;
+    int32_t        self_msg;
+    int32_t        self_start;
+    int32_t        n_q;
+    const int32_t *q_pos;
+} pc_call;
+
+/* Batched choreographed attention (Sec. 2.4 "Parallel API Calls": a list of calls
+ * that each see exactly what they list).
+ *   q    device, [sum n_q, n_q_heads, head_dim], rows packed in call order, unrotated.
+ *   out  device, same shape and dtype as q.
+ *   lse  device, optional fp32 [sum n_q, n_q_heads]: natural-log sum of exp(scores).
+ * A row with nothing visible yields zeros and -inf. */
+int32_t pc_attend(pc_cache *c, const pc_call *calls, int32_t n_calls,
+                  const void *q, void *out, float *lse, void *stream);
+
+/* Parity/debug: the expanded gather table and position map of one call, in list
+ * order then the new message: kv_slot[i] = physical slot, kv_pos[i] = logical
+ * position (the (m, j) metadata of Sec. 2.4 in gathered form).  kv_slot / kv_pos:
+ * device int32 arrays with room for *n_kv entries on entry is NOT required: the
+ * function writes the count to *n_kv and fills the arrays only if cap >= count
+ * (pass cap = 0 and NULL arrays to query the count). */
+int32_t pc_build_tables(pc_cache *c, const pc_call *call, int32_t *kv_slot, int32_t *kv_pos,
+                        int64_t cap, int64_t *n_kv, void *stream);
+
+/* Host-side resolution of a call: starts_out[n_sel] receives each parent's resolved
+ * start position, *self_start_out the new message's, *n_kv the gathered token count.
+ * Any output pointer may be NULL. */
+int32_t pc_resolve_call(pc_cache *c, const pc_call *call, int32_t *starts_out,
+                        int32_t *self_start_out, int64_t *n_kv);
+
+/* Message and cache bookkeeping (Sec. 2.4: count of cached tokens, id -> span). */
+int32_t pc_message_info(pc_cache *c, int32_t msg_id, int32_t *len, int64_t *slot_start,
+                        int32_t *reserved);
+int32_t pc_cache_info(pc_cache *c, int32_t *n_messages, int64_t *slots_used,
+                      int64_t *capacity_slots);
+
+/* Kernel timing for benchmarks.  When enabled, every kernel the library launches is
+ * bracketed by events on the caller's stream.  pc_profile_read waits for the stream
+ * work recorded so far, then returns per-kernel-class totals since the last reset.
+ * Classes: 0 append, 1 plan builder, 2 prefill attention, 3 decode attention,
+ * 4 split merge, 5 fp32 attention, 6 table expansion. */
+#define PC_N_KERNEL_CLASSES 7
+int32_t pc_profile_enable(pc_cache *c, int32_t on);
+int32_t pc_profile_read(pc_cache *c, double ms_total[PC_N_KERNEL_CLASSES],
+                        int64_t launches[PC_N_KERNEL_CLASSES], int32_t reset);
+
+/* Tuning knobs (0 keeps the default): KV tiles (of 32 keys) per split for decode
+ * and for prefill work items. */
+int32_t pc_set_tuning(pc_cache *c, int32_t decode_tiles_per_split, int32_t prefill_tiles_per_split);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PC_H_ */

@@ -1,0 +1,71 @@
+// Structures shared by the host side of the library and its kernels.
+#ifndef PC_INTERNAL_H_
+#define PC_INTERNAL_H_
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#define PC_TILE 32            // keys per KV tile; equals the slot alignment, so a
+                              // tile never straddles two messages
+#define PC_VGROUP 8           // V is stored key-transposed in groups of 8 slots
+
+// Device copy of one message-table entry (Sec. 2.4: message id -> physical span).
+struct PcMsgEntry {
+    int32_t slot_start;       // first slot (multiple of PC_TILE)
+    int32_t len;              // tokens stored
+};
+
+// One call of a batch as staged by the host.
+struct PcCallDesc {
+    int32_t sel_off;          // first entry in the packed (msg, start) list
+    int32_t n_sel;
+    int32_t self_msg;         // -1: none
+    int32_t self_start;       // resolved
+    int32_t n_q;
+    int32_t q_off;            // first packed query row
+    int32_t seg_off;          // first segment of this call in the segment arrays
+    int32_t n_seg;            // n_sel + (self_msg >= 0)
+    int32_t self_len;         // tokens in the new message (0 if none)
+    int32_t n_splits;         // KV splits of this call's work items
+    int32_t part_off;         // first partial row (units of rows) when n_splits > 1
+    int32_t pad;
+};
+
+// A gathered segment = one whole message placed at pos_start (built on device).
+struct PcSegment {
+    int32_t slot_start;
+    int32_t len;
+    int32_t pos_start;
+    int32_t tile_off;         // KV tiles of this call before this segment
+};
+
+// One workgroup's share of an attention launch.
+struct PcItem {
+    int32_t call;
+    int32_t unit0;            // prefill: first row unit of the workgroup; decode: 0
+    int32_t tile_begin;       // KV tile range [begin, end) within the call
+    int32_t tile_end;
+    int32_t split;            // split index within the call
+    int32_t pad[3];
+};
+
+// Everything an attention kernel needs, passed by value.
+struct PcLaunch {
+    const PcCallDesc *calls;
+    const PcSegment  *segs;
+    const float2     *rot_seg;    // [total_seg][D/2] (cos, sin)(pos_start * theta_i)
+    const float2     *rot_q;      // [total_q][D/2]   (cos, sin)(q_pos * theta_i)
+    const PcItem     *items;
+    const void       *k_store;    // [H_kv][slots][D]            K turned to its in-message index
+    const void       *v_store;    // bf16: [H_kv][slots/8][D][8] ; f32: [H_kv][slots][D]
+    const void       *q;          // [total_q][H_q][D]
+    void             *out;        // [total_q][H_q][D]
+    float            *lse;        // [total_q][H_q] or null
+    float            *part_o;     // [part rows][H_q][D]   un-normalised partial outputs
+    float            *part_ml;    // [part rows][H_q][2]   running max (scaled log2 domain), sum
+    int64_t           slots;      // capacity in slots (stride between KV heads)
+    int32_t           n_q_heads, n_kv_heads;
+    float             scale_log2; // softmax scale * log2(e)
+};
+
+#endif

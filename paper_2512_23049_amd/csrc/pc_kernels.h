@@ -1,0 +1,29 @@
+// Launch wrappers of the kernels (internal to the library).
+#ifndef PC_KERNELS_H_
+#define PC_KERNELS_H_
+
+#include "pc_internal.h"
+
+void pc_launch_append(int dtype, const void *k, const void *v, int len, int n_kv_heads, int D,
+                      int64_t slot_start, int64_t slots, const double *inv_freq, void *k_store,
+                      void *v_store, PcMsgEntry *table, int msg_id, hipStream_t st);
+
+void pc_launch_build_plan(const PcCallDesc *calls, int n_calls, const int2 *sel, const int32_t *q_pos,
+                          const PcMsgEntry *table, const double *inv_freq, int half, int total_seg,
+                          int total_q, PcSegment *segs, int32_t *seg_kvoff, float2 *rot_seg,
+                          float2 *rot_q, hipStream_t st);
+
+void pc_launch_expand_tables(const PcSegment *segs, const int32_t *seg_kvoff, int n_seg, int64_t n_kv,
+                             int32_t *kv_slot, int32_t *kv_pos, hipStream_t st);
+
+void pc_launch_merge(int dtype, const PcCallDesc *calls, const int32_t *row_call, int total_q,
+                     const float *part_o, const float *part_ml, void *out, float *lse, int n_q_heads,
+                     int D, hipStream_t st);
+
+void pc_launch_attend_f32(const PcLaunch &L, const int32_t *row_call, int total_q, int D, hipStream_t st);
+
+// bf16 MFMA kernels (D = 128)
+void pc_launch_decode_bf16(const PcLaunch &L, int n_items, hipStream_t st);
+void pc_launch_prefill_bf16(const PcLaunch &L, int n_items, int waves, hipStream_t st);
+
+#endif

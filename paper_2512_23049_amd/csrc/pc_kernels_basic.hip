@@ -1,0 +1,413 @@
+// Cache append, plan builder, table expansion, split merge and the fp32 attention
+// kernel.  gfx950 only.
+#include "pc_kernels.h"
+
+#include <hip/hip_bf16.h>
+
+// ----------------------------------------------------------------------------------
+// K1: fused cache append (Sec. 2.4: new messages are appended at the end of the
+// occupied part of the cache; the i-th token's key is turned to a position by RoPE).
+// Stored form: the key of in-message token t is turned by t (delta-rotated form), so
+// that placing the message at offset s later only needs the query turned by -s.
+// blockIdx.y == 0: K part, one thread per (token, 2 adjacent frequency pairs... ) see below
+// blockIdx.y == 1: V part, one thread per (group of 8 tokens, kv head, 2 adjacent dims)
+// ----------------------------------------------------------------------------------
+template <typename T> struct Pair2;
+template <> struct Pair2<__hip_bfloat16> {
+    using type = uint32_t;
+    __device__ static float lo(uint32_t u) { return __uint_as_float(u << 16); }
+    __device__ static float hi(uint32_t u) { return __uint_as_float(u & 0xFFFF0000u); }
+    __device__ static uint32_t pack(float a, float b) {
+        __hip_bfloat16 x = __float2bfloat16(a), y = __float2bfloat16(b);
+        return (uint32_t)(*reinterpret_cast<uint16_t *>(&x)) |
+               ((uint32_t)(*reinterpret_cast<uint16_t *>(&y)) << 16);
+    }
+};
+
+__global__ __launch_bounds__(256) void pc_append_bf16_kernel(
+    const uint16_t *__restrict__ k, const uint16_t *__restrict__ v, int len, int n_kv_heads, int D,
+    int64_t slot_start, int64_t slots, const double *__restrict__ inv_freq,
+    uint16_t *__restrict__ k_store, uint16_t *__restrict__ v_store,
+    PcMsgEntry *__restrict__ table, int msg_id)
+{
+    const int half = D / 2;
+    const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (blockIdx.y == 0) {
+        if (tid == 0) { table[msg_id].slot_start = (int32_t)slot_start; table[msg_id].len = len; }
+        // thread = (token t, pair index i0 = 2*j): handles frequency pairs i0 and i0+1
+        const int per_tok = half / 2;
+        if (tid >= (int64_t)len * per_tok) return;
+        const int t = (int)(tid / per_tok);
+        const int i0 = 2 * (int)(tid % per_tok);
+        double s0, c0, s1, c1;
+        sincos((double)t * inv_freq[i0], &s0, &c0);
+        sincos((double)t * inv_freq[i0 + 1], &s1, &c1);
+        const float fc0 = (float)c0, fs0 = (float)s0, fc1 = (float)c1, fs1 = (float)s1;
+        using P = Pair2<__hip_bfloat16>;
+        for (int h = 0; h < n_kv_heads; ++h) {
+            const uint16_t *src = k + ((int64_t)t * n_kv_heads + h) * D;
+            const uint32_t lo = *reinterpret_cast<const uint32_t *>(src + i0);
+            const uint32_t hi = *reinterpret_cast<const uint32_t *>(src + half + i0);
+            const float a0 = P::lo(lo), a1 = P::hi(lo), b0 = P::lo(hi), b1 = P::hi(hi);
+            uint16_t *dst = k_store + ((int64_t)h * slots + slot_start + t) * D;
+            *reinterpret_cast<uint32_t *>(dst + i0) = P::pack(a0 * fc0 - b0 * fs0, a1 * fc1 - b1 * fs1);
+            *reinterpret_cast<uint32_t *>(dst + half + i0) = P::pack(a0 * fs0 + b0 * fc0, a1 * fs1 + b1 * fc1);
+        }
+    } else {
+        // thread = (token group tg, head h, dim pair d0): 8 tokens x 2 dims, zero padded
+        const int dp = D / 2;
+        const int n_groups = (len + PC_VGROUP - 1) / PC_VGROUP;
+        if (tid >= (int64_t)n_groups * n_kv_heads * dp) return;
+        const int d0 = 2 * (int)(tid % dp);
+        const int h = (int)((tid / dp) % n_kv_heads);
+        const int tg = (int)(tid / ((int64_t)dp * n_kv_heads));
+        uint16_t a[PC_VGROUP], b[PC_VGROUP];
+#pragma unroll
+        for (int j = 0; j < PC_VGROUP; ++j) {
+            const int t = tg * PC_VGROUP + j;
+            uint32_t u = 0;
+            if (t < len) u = *reinterpret_cast<const uint32_t *>(v + ((int64_t)t * n_kv_heads + h) * D + d0);
+            a[j] = (uint16_t)(u & 0xFFFFu);
+            b[j] = (uint16_t)(u >> 16);
+        }
+        uint16_t *dst = v_store + (((int64_t)h * (slots / PC_VGROUP) + slot_start / PC_VGROUP + tg) * D + d0) * PC_VGROUP;
+        uint4 wa, wb;
+        wa.x = a[0] | ((uint32_t)a[1] << 16); wa.y = a[2] | ((uint32_t)a[3] << 16);
+        wa.z = a[4] | ((uint32_t)a[5] << 16); wa.w = a[6] | ((uint32_t)a[7] << 16);
+        wb.x = b[0] | ((uint32_t)b[1] << 16); wb.y = b[2] | ((uint32_t)b[3] << 16);
+        wb.z = b[4] | ((uint32_t)b[5] << 16); wb.w = b[6] | ((uint32_t)b[7] << 16);
+        *reinterpret_cast<uint4 *>(dst) = wa;
+        *reinterpret_cast<uint4 *>(dst + PC_VGROUP) = wb;
+    }
+}
+
+__global__ __launch_bounds__(256) void pc_append_f32_kernel(
+    const float *__restrict__ k, const float *__restrict__ v, int len, int n_kv_heads, int D,
+    int64_t slot_start, int64_t slots, const double *__restrict__ inv_freq,
+    float *__restrict__ k_store, float *__restrict__ v_store,
+    PcMsgEntry *__restrict__ table, int msg_id)
+{
+    const int half = D / 2;
+    const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (blockIdx.y == 0) {
+        if (tid == 0) { table[msg_id].slot_start = (int32_t)slot_start; table[msg_id].len = len; }
+        if (tid >= (int64_t)len * half) return;
+        const int t = (int)(tid / half);
+        const int i = (int)(tid % half);
+        double s, c;
+        sincos((double)t * inv_freq[i], &s, &c);
+        const float fc = (float)c, fs = (float)s;
+        for (int h = 0; h < n_kv_heads; ++h) {
+            const float *src = k + ((int64_t)t * n_kv_heads + h) * D;
+            const float a = src[i], b = src[i + half];
+            float *dst = k_store + ((int64_t)h * slots + slot_start + t) * D;
+            dst[i] = a * fc - b * fs;
+            dst[i + half] = a * fs + b * fc;
+        }
+    } else {
+        if (tid >= (int64_t)len * n_kv_heads * D) return;
+        const int d = (int)(tid % D);
+        const int h = (int)((tid / D) % n_kv_heads);
+        const int t = (int)(tid / ((int64_t)D * n_kv_heads));
+        v_store[((int64_t)h * slots + slot_start + t) * D + d] = v[tid];
+    }
+}
+
+void pc_launch_append(int dtype, const void *k, const void *v, int len, int n_kv_heads, int D,
+                      int64_t slot_start, int64_t slots, const double *inv_freq, void *k_store,
+                      void *v_store, PcMsgEntry *table, int msg_id, hipStream_t st)
+{
+    if (dtype == 1) {
+        const int64_t nk = (int64_t)len * (D / 4);
+        const int64_t nv = (int64_t)((len + PC_VGROUP - 1) / PC_VGROUP) * n_kv_heads * (D / 2);
+        const int64_t n = nk > nv ? nk : nv;
+        dim3 grid((unsigned)((n + 255) / 256), 2);
+        pc_append_bf16_kernel<<<grid, 256, 0, st>>>((const uint16_t *)k, (const uint16_t *)v, len, n_kv_heads, D,
+                                                    slot_start, slots, inv_freq, (uint16_t *)k_store,
+                                                    (uint16_t *)v_store, table, msg_id);
+    } else {
+        const int64_t nk = (int64_t)len * (D / 2);
+        const int64_t nv = (int64_t)len * n_kv_heads * D;
+        const int64_t n = nk > nv ? nk : nv;
+        dim3 grid((unsigned)((n + 255) / 256), 2);
+        pc_append_f32_kernel<<<grid, 256, 0, st>>>((const float *)k, (const float *)v, len, n_kv_heads, D,
+                                                   slot_start, slots, inv_freq, (float *)k_store,
+                                                   (float *)v_store, table, msg_id);
+    }
+}
+
+// ----------------------------------------------------------------------------------
+// K2: plan builder.  Blocks [0, n_calls): per call, look each listed message up in the
+// device message table and scan lengths into the segment list (Sec. 2.4 "Dynamic
+// Masking": what a call sees is computed on the fly from message membership; here in
+// gather form).  Blocks [n_calls, ...): rotation tables (cos, sin)(p * theta_i) for
+// every segment start and every query row, in fp64 rounded to fp32 (Sec. 2.4
+// "Position Updates": a lookup table of rotations).
+// ----------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void pc_build_plan_kernel(
+    const PcCallDesc *__restrict__ calls, int n_calls, const int2 *__restrict__ sel,
+    const int32_t *__restrict__ q_pos, const PcMsgEntry *__restrict__ table,
+    const double *__restrict__ inv_freq, int half, int total_seg, int total_q,
+    PcSegment *__restrict__ segs, int32_t *__restrict__ seg_kvoff,
+    float2 *__restrict__ rot_seg, float2 *__restrict__ rot_q)
+{
+    __shared__ int s_len[256];
+    __shared__ int s_tiles[256];
+    __shared__ int s_carry[2];
+    if ((int)blockIdx.x < n_calls) {
+        const PcCallDesc cd = calls[blockIdx.x];
+        if (threadIdx.x == 0) { s_carry[0] = 0; s_carry[1] = 0; }
+        __syncthreads();
+        for (int base = 0; base < cd.n_seg; base += 256) {
+            const int e = base + threadIdx.x;
+            int len = 0, slot = 0, pos = 0;
+            if (e < cd.n_seg) {
+                int m, p;
+                if (e < cd.n_sel) { const int2 s = sel[cd.sel_off + e]; m = s.x; p = s.y; }
+                else { m = cd.self_msg; p = cd.self_start; }
+                const PcMsgEntry me = table[m];
+                len = me.len; slot = me.slot_start; pos = p;
+            }
+            const int tiles = (len + PC_TILE - 1) / PC_TILE;
+            s_len[threadIdx.x] = len;
+            s_tiles[threadIdx.x] = tiles;
+            __syncthreads();
+            // Hillis-Steele inclusive scan over the 256 entries of this chunk
+            for (int off = 1; off < 256; off <<= 1) {
+                int a = 0, b = 0;
+                if ((int)threadIdx.x >= off) { a = s_len[threadIdx.x - off]; b = s_tiles[threadIdx.x - off]; }
+                __syncthreads();
+                s_len[threadIdx.x] += a;
+                s_tiles[threadIdx.x] += b;
+                __syncthreads();
+            }
+            const int c_len = s_carry[0], c_tiles = s_carry[1];
+            if (e < cd.n_seg) {
+                PcSegment sg;
+                sg.slot_start = slot; sg.len = len; sg.pos_start = pos;
+                sg.tile_off = c_tiles + s_tiles[threadIdx.x] - tiles;
+                segs[cd.seg_off + e] = sg;
+                seg_kvoff[cd.seg_off + e] = c_len + s_len[threadIdx.x] - len;
+            }
+            __syncthreads();
+            if (threadIdx.x == 255) { s_carry[0] = c_len + s_len[255]; s_carry[1] = c_tiles + s_tiles[255]; }
+            __syncthreads();
+        }
+        return;
+    }
+    // rotation tables: entity = segment (position from the staged lists) or query row
+    const int64_t tid = (int64_t)(blockIdx.x - n_calls) * 256 + threadIdx.x;
+    const int64_t n_ent = (int64_t)total_seg + total_q;
+    if (tid >= n_ent * half) return;
+    const int ent = (int)(tid / half);
+    const int i = (int)(tid % half);
+    int pos;
+    if (ent < total_seg) {
+        // find the call that owns this segment (calls are few; segments are laid out call by call)
+        int lo = 0, hi = n_calls - 1;
+        while (lo < hi) {
+            const int mid = (lo + hi + 1) >> 1;
+            if (calls[mid].seg_off <= ent) lo = mid; else hi = mid - 1;
+        }
+        const PcCallDesc cd = calls[lo];
+        const int e = ent - cd.seg_off;
+        pos = (e < cd.n_sel) ? sel[cd.sel_off + e].y : cd.self_start;
+    } else {
+        pos = q_pos[ent - total_seg];
+    }
+    double s, c;
+    sincos((double)pos * inv_freq[i], &s, &c);
+    const float2 r = make_float2((float)c, (float)s);
+    if (ent < total_seg) rot_seg[(int64_t)ent * half + i] = r;
+    else rot_q[(int64_t)(ent - total_seg) * half + i] = r;
+}
+
+void pc_launch_build_plan(const PcCallDesc *calls, int n_calls, const int2 *sel, const int32_t *q_pos,
+                          const PcMsgEntry *table, const double *inv_freq, int half, int total_seg,
+                          int total_q, PcSegment *segs, int32_t *seg_kvoff, float2 *rot_seg,
+                          float2 *rot_q, hipStream_t st)
+{
+    const int64_t n_rot = ((int64_t)total_seg + total_q) * half;
+    const unsigned grid = (unsigned)(n_calls + (n_rot + 255) / 256);
+    pc_build_plan_kernel<<<grid, 256, 0, st>>>(calls, n_calls, sel, q_pos, table, inv_freq, half, total_seg,
+                                               total_q, segs, seg_kvoff, rot_seg, rot_q);
+}
+
+// ----------------------------------------------------------------------------------
+// Expanded gather table / position map of one call (the (m, j) metadata of Sec. 2.4 in
+// gathered form): token i of the gathered sequence -> physical slot and logical position.
+// ----------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void pc_expand_tables_kernel(
+    const PcSegment *__restrict__ segs, const int32_t *__restrict__ seg_kvoff, int n_seg, int64_t n_kv,
+    int32_t *__restrict__ kv_slot, int32_t *__restrict__ kv_pos)
+{
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n_kv) return;
+    int lo = 0, hi = n_seg - 1;
+    while (lo < hi) {                      // last segment whose first token is <= i and non-empty
+        const int mid = (lo + hi + 1) >> 1;
+        if (seg_kvoff[mid] <= i) lo = mid; else hi = mid - 1;
+    }
+    const PcSegment sg = segs[lo];
+    const int t = (int)(i - seg_kvoff[lo]);
+    kv_slot[i] = sg.slot_start + t;
+    kv_pos[i] = sg.pos_start + t;
+}
+
+void pc_launch_expand_tables(const PcSegment *segs, const int32_t *seg_kvoff, int n_seg, int64_t n_kv,
+                             int32_t *kv_slot, int32_t *kv_pos, hipStream_t st)
+{
+    if (n_kv <= 0) return;
+    pc_expand_tables_kernel<<<(unsigned)((n_kv + 255) / 256), 256, 0, st>>>(segs, seg_kvoff, n_seg, n_kv,
+                                                                           kv_slot, kv_pos);
+}
+
+// ----------------------------------------------------------------------------------
+// K5: merge of KV splits.  Each split s of a row holds an un-normalised output acc_s,
+// a running maximum m_s (scaled log2 domain) and a sum l_s; the result is
+//   m = max m_s,  l = sum l_s 2^(m_s - m),  O = sum acc_s 2^(m_s - m) / l
+// evaluated in split order (deterministic; no atomics).
+// ----------------------------------------------------------------------------------
+template <typename OutT>
+__global__ __launch_bounds__(256) void pc_merge_kernel(
+    const PcCallDesc *__restrict__ calls, const int32_t *__restrict__ row_call,
+    const float *__restrict__ part_o, const float *__restrict__ part_ml, OutT *__restrict__ out,
+    float *__restrict__ lse, int n_q_heads, int D)
+{
+    const int R = blockIdx.x;
+    const PcCallDesc cd = calls[row_call[R]];
+    if (cd.n_splits <= 1) return;
+    const int r = R - cd.q_off;
+    const int n = n_q_heads * D;
+    for (int idx = threadIdx.x; idx < n; idx += blockDim.x) {
+        const int h = idx / D;
+        float m = -INFINITY;
+        for (int s = 0; s < cd.n_splits; ++s) {
+            const int64_t pr = (int64_t)cd.part_off + (int64_t)s * cd.n_q + r;
+            m = fmaxf(m, part_ml[(pr * n_q_heads + h) * 2]);
+        }
+        float l = 0.f, o = 0.f;
+        if (m > -INFINITY) {
+            for (int s = 0; s < cd.n_splits; ++s) {
+                const int64_t pr = (int64_t)cd.part_off + (int64_t)s * cd.n_q + r;
+                const float ms = part_ml[(pr * n_q_heads + h) * 2];
+                const float w = (ms > -INFINITY) ? exp2f(ms - m) : 0.f;
+                l += part_ml[(pr * n_q_heads + h) * 2 + 1] * w;
+                o += part_o[pr * n + idx] * w;
+            }
+        }
+        const float res = (l > 0.f) ? o / l : 0.f;
+        if constexpr (sizeof(OutT) == 2) {
+            __hip_bfloat16 b = __float2bfloat16(res);
+            out[(int64_t)R * n + idx] = *reinterpret_cast<uint16_t *>(&b);
+        } else {
+            out[(int64_t)R * n + idx] = res;
+        }
+        if (lse && (idx % D) == 0)
+            lse[(int64_t)R * n_q_heads + h] = (l > 0.f) ? (m + log2f(l)) * 0.6931471805599453f : -INFINITY;
+    }
+}
+
+void pc_launch_merge(int dtype, const PcCallDesc *calls, const int32_t *row_call, int total_q,
+                     const float *part_o, const float *part_ml, void *out, float *lse, int n_q_heads,
+                     int D, hipStream_t st)
+{
+    if (total_q <= 0) return;
+    if (dtype == 1)
+        pc_merge_kernel<uint16_t><<<total_q, 256, 0, st>>>(calls, row_call, part_o, part_ml, (uint16_t *)out, lse, n_q_heads, D);
+    else
+        pc_merge_kernel<float><<<total_q, 256, 0, st>>>(calls, row_call, part_o, part_ml, (float *)out, lse, n_q_heads, D);
+}
+
+// ----------------------------------------------------------------------------------
+// K6: fp32 attention, one wave per (query row, query head).  Plain vector arithmetic,
+// meant for fp32 caches (small reference-precision configurations).
+// For each segment the query is turned by (q_pos - segment start) and dotted with the
+// stored keys; online softmax per lane over the keys that lane visits; lanes are
+// combined at the end.
+// ----------------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(64) void pc_attend_f32_kernel(PcLaunch L, const int32_t *__restrict__ row_call)
+{
+    constexpr int HALF = D / 2;
+    __shared__ float s_qhat[D];
+    __shared__ float s_qe[D];
+    __shared__ float s_red[64 * (D + 1)];
+    const int R = blockIdx.x, h = blockIdx.y, lane = threadIdx.x;
+    const PcCallDesc cd = L.calls[row_call[R]];
+    const int r = R - cd.q_off;
+    const int g = L.n_q_heads / L.n_kv_heads;
+    const int kh = h / g;
+    const float *q = (const float *)L.q + ((int64_t)R * L.n_q_heads + h) * D;
+    for (int i = lane; i < HALF; i += 64) {
+        const float2 cs = L.rot_q[(int64_t)R * HALF + i];
+        const float a = q[i], b = q[i + HALF];
+        s_qhat[i] = a * cs.x - b * cs.y;
+        s_qhat[i + HALF] = a * cs.y + b * cs.x;
+    }
+    __syncthreads();
+    const float *kbase = (const float *)L.k_store + (int64_t)kh * L.slots * D;
+    const float *vbase = (const float *)L.v_store + (int64_t)kh * L.slots * D;
+    float m = -INFINITY, l = 0.f;
+    float acc[D];
+#pragma unroll
+    for (int d = 0; d < D; ++d) acc[d] = 0.f;
+    for (int e = 0; e < cd.n_seg; ++e) {
+        const PcSegment sg = L.segs[cd.seg_off + e];
+        int n_vis = sg.len;
+        if (cd.self_msg >= 0 && e == cd.n_seg - 1) {
+            const int lim = cd.self_len - cd.n_q + r + 1;
+            n_vis = lim < n_vis ? lim : n_vis;
+        }
+        if (n_vis <= 0) continue;
+        __syncthreads();
+        for (int i = lane; i < HALF; i += 64) {
+            const float2 cs = L.rot_seg[(int64_t)(cd.seg_off + e) * HALF + i];
+            const float a = s_qhat[i], b = s_qhat[i + HALF];
+            s_qe[i] = a * cs.x + b * cs.y;              // turn by -pos_start
+            s_qe[i + HALF] = -a * cs.y + b * cs.x;
+        }
+        __syncthreads();
+        for (int t = lane; t < n_vis; t += 64) {
+            const float *kr = kbase + (int64_t)(sg.slot_start + t) * D;
+            float s = 0.f;
+#pragma unroll 8
+            for (int d = 0; d < D; ++d) s = fmaf(s_qe[d], kr[d], s);
+            s *= L.scale_log2;
+            const float mn = fmaxf(m, s);
+            const float alpha = exp2f(m - mn);          // m = -inf -> 0
+            const float p = exp2f(s - mn);
+            l = l * alpha + p;
+            const float *vr = vbase + (int64_t)(sg.slot_start + t) * D;
+#pragma unroll
+            for (int d = 0; d < D; ++d) acc[d] = fmaf(acc[d], alpha, p * vr[d]);
+            m = mn;
+        }
+    }
+    // combine the 64 lanes
+    float mw = m;
+    for (int off = 32; off > 0; off >>= 1) mw = fmaxf(mw, __shfl_xor(mw, off));
+    const float w = (m > -INFINITY) ? exp2f(m - mw) : 0.f;
+    float lw = l * w;
+    for (int off = 32; off > 0; off >>= 1) lw += __shfl_xor(lw, off);
+    __syncthreads();
+#pragma unroll
+    for (int d = 0; d < D; ++d) s_red[lane * (D + 1) + d] = acc[d] * w;
+    __syncthreads();
+    float *out = (float *)L.out + ((int64_t)R * L.n_q_heads + h) * D;
+    for (int d = lane; d < D; d += 64) {
+        float o = 0.f;
+        for (int j = 0; j < 64; ++j) o += s_red[j * (D + 1) + d];
+        out[d] = (lw > 0.f) ? o / lw : 0.f;
+    }
+    if (L.lse && lane == 0)
+        L.lse[(int64_t)R * L.n_q_heads + h] = (lw > 0.f) ? (mw + log2f(lw)) * 0.6931471805599453f : -INFINITY;
+}
+
+void pc_launch_attend_f32(const PcLaunch &L, const int32_t *row_call, int total_q, int D, hipStream_t st)
+{
+    if (total_q <= 0) return;
+    dim3 grid(total_q, L.n_q_heads);
+    if (D == 64) pc_attend_f32_kernel<64><<<grid, 64, 0, st>>>(L, row_call);
+    else pc_attend_f32_kernel<128><<<grid, 64, 0, st>>>(L, row_call);
+}

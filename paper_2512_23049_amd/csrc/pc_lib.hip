@@ -1,0 +1,568 @@
+// Host side of the library: message table, slot allocator, validation, position
+// resolution, work-item planning, staging and kernel launches.
+#include "../../include/pc.h"
+#include "pc_kernels.h"
+
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+namespace {
+
+struct HostMsg { int64_t slot_start; int32_t len; int32_t reserve; };
+
+struct StageSlot { void *host = nullptr; size_t cap = 0; hipEvent_t ev = nullptr; bool used = false; };
+
+struct ProfRec { int cls; hipEvent_t a, b; };
+
+constexpr int N_STAGE = 4;
+constexpr int MAX_SPLITS = 128;
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+}  // namespace
+
+struct pc_cache {
+    pc_config cfg;
+    bool host_only = false;
+    int D = 0, half = 0, g = 0;
+    int64_t slots = 0;
+    size_t esize = 0;
+    float scale = 0.f;
+    std::vector<HostMsg> msgs;
+    int64_t next_slot = 0;
+    // device
+    void *storage = nullptr; bool owns_storage = false;
+    void *k_store = nullptr, *v_store = nullptr;
+    PcMsgEntry *table_dev = nullptr;
+    double *inv_freq_dev = nullptr;
+    void *ws = nullptr; size_t ws_cap = 0;
+    StageSlot stage[N_STAGE]; int stage_next = 0;
+    // profiling
+    bool prof = false;
+    std::vector<ProfRec> prof_recs;
+    std::vector<hipEvent_t> ev_pool;
+    double prof_ms[PC_N_KERNEL_CLASSES] = {0};
+    int64_t prof_n[PC_N_KERNEL_CLASSES] = {0};
+    // tuning
+    int decode_tiles_per_split = 0, prefill_tiles_per_split = 0;
+    std::string err;
+};
+
+namespace {
+
+int32_t fail(pc_cache *c, int32_t code, const char *fmt, ...)
+{
+    if (c) {
+        char buf[512];
+        va_list ap; va_start(ap, fmt); vsnprintf(buf, sizeof buf, fmt, ap); va_end(ap);
+        c->err = buf;
+    }
+    return code;
+}
+
+#define PC_HIP(c, expr)                                                                        \
+    do { hipError_t e_ = (expr);                                                               \
+         if (e_ != hipSuccess) return fail((c), PC_ERR_HIP, "%s: %s", #expr, hipGetErrorString(e_)); } while (0)
+
+size_t storage_bytes(const pc_config *cfg)
+{
+    const int64_t slots = (int64_t)align_up((size_t)std::max<int64_t>(cfg->capacity_tokens, 1), PC_SLOT_ALIGN);
+    const size_t es = cfg->dtype == PC_BF16 ? 2 : 4;
+    return 2 * (size_t)slots * cfg->n_kv_heads * cfg->head_dim * es;
+}
+
+struct ProfScope {
+    pc_cache *c; int cls; hipStream_t st; hipEvent_t a = nullptr, b = nullptr;
+    ProfScope(pc_cache *c_, int cls_, hipStream_t st_) : c(c_), cls(cls_), st(st_) {
+        if (!c->prof) return;
+        auto get = [&]() { hipEvent_t e = nullptr;
+            if (!c->ev_pool.empty()) { e = c->ev_pool.back(); c->ev_pool.pop_back(); }
+            else if (hipEventCreate(&e) != hipSuccess) e = nullptr;
+            return e; };
+        a = get(); b = get();
+        if (a) (void)hipEventRecord(a, st);
+    }
+    ~ProfScope() {
+        if (!c->prof || !a || !b) return;
+        (void)hipEventRecord(b, st);
+        c->prof_recs.push_back({cls, a, b});
+    }
+};
+
+void prof_collect(pc_cache *c)
+{
+    for (auto &r : c->prof_recs) {
+        (void)hipEventSynchronize(r.b);
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, r.a, r.b) == hipSuccess) { c->prof_ms[r.cls] += ms; c->prof_n[r.cls] += 1; }
+        c->ev_pool.push_back(r.a); c->ev_pool.push_back(r.b);
+    }
+    c->prof_recs.clear();
+}
+
+// ---- validated, resolved form of one call -------------------------------------------
+struct Resolved {
+    std::vector<int2> sel;        // (msg, resolved start)
+    int32_t self_msg = -1, self_start = 0, self_len = 0, n_q = 0;
+    std::vector<int32_t> q_pos;
+    int64_t n_kv = 0;
+    int32_t tiles = 0;            // KV tiles incl. the new message
+};
+
+int32_t resolve_call(pc_cache *c, const pc_call *call, int idx, Resolved &out)
+{
+    if (!call) return fail(c, PC_ERR_INVALID_ARG, "call %d: null", idx);
+    if (call->n_sel < 0 || (call->n_sel > 0 && !call->sel))
+        return fail(c, PC_ERR_INVALID_ARG, "call %d: bad parent list", idx);
+    if (call->n_q < 1) return fail(c, PC_ERR_INVALID_ARG, "call %d: n_q = %d must be >= 1", idx, call->n_q);
+    const int64_t maxp = c->cfg.max_position;
+    const int n_msgs = (int)c->msgs.size();
+    out.sel.resize(call->n_sel);
+    int64_t nxt = 0, n_kv = 0, tiles = 0;
+    for (int e = 0; e < call->n_sel; ++e) {
+        const int32_t m = call->sel[e].msg_id;
+        if (m < 0 || m >= n_msgs) return fail(c, PC_ERR_BAD_MSG_ID, "call %d: parent %d names unknown message %d", idx, e, m);
+        const int64_t len = c->msgs[m].len;
+        const int64_t s = call->sel[e].start_pos == PC_POS_AUTO ? nxt : (int64_t)call->sel[e].start_pos;
+        if (s < -maxp || s + len - 1 > maxp)
+            return fail(c, PC_ERR_INVALID_ARG, "call %d: parent %d spans positions [%lld, %lld], limit is +-%lld", idx, e,
+                        (long long)s, (long long)(s + len - 1), (long long)maxp);
+        out.sel[e] = make_int2(m, (int)s);
+        nxt = s + len; n_kv += len; tiles += (len + PC_TILE - 1) / PC_TILE;
+    }
+    out.self_msg = -1; out.self_len = 0;
+    int64_t s_self = call->self_start == PC_POS_AUTO ? nxt : (int64_t)call->self_start;
+    if (call->self_msg >= 0) {
+        if (call->self_msg >= n_msgs) return fail(c, PC_ERR_BAD_MSG_ID, "call %d: new message id %d unknown", idx, call->self_msg);
+        out.self_msg = call->self_msg;
+        out.self_len = c->msgs[call->self_msg].len;
+        if (call->n_q > out.self_len)
+            return fail(c, PC_ERR_SHAPE, "call %d: n_q = %d exceeds the new message's %d tokens", idx, call->n_q, out.self_len);
+        if (s_self < -maxp || s_self + out.self_len - 1 > maxp)
+            return fail(c, PC_ERR_INVALID_ARG, "call %d: new message spans positions beyond +-%lld", idx, (long long)maxp);
+        n_kv += out.self_len; tiles += (out.self_len + PC_TILE - 1) / PC_TILE;
+    } else if (call->self_msg != -1) {
+        return fail(c, PC_ERR_BAD_MSG_ID, "call %d: self_msg must be -1 or a message id", idx);
+    } else if (s_self < -maxp || s_self + call->n_q - 1 > maxp) {
+        return fail(c, PC_ERR_INVALID_ARG, "call %d: query positions beyond +-%lld", idx, (long long)maxp);
+    }
+    out.self_start = (int32_t)s_self;
+    out.n_q = call->n_q;
+    out.q_pos.resize(call->n_q);
+    const int64_t tok0 = out.self_msg >= 0 ? out.self_len - call->n_q : 0;
+    for (int r = 0; r < call->n_q; ++r) {
+        const int64_t p = call->q_pos ? (int64_t)call->q_pos[r] : s_self + tok0 + r;
+        if (p < -maxp || p > maxp) return fail(c, PC_ERR_INVALID_ARG, "call %d: query position %lld beyond +-%lld", idx, (long long)p, (long long)maxp);
+        out.q_pos[r] = (int32_t)p;
+    }
+    if (n_kv > INT32_MAX / 2) return fail(c, PC_ERR_SHAPE, "call %d: gathers %lld tokens, too many", idx, (long long)n_kv);
+    out.n_kv = n_kv; out.tiles = (int32_t)tiles;
+    return PC_OK;
+}
+
+int32_t ensure_ws(pc_cache *c, size_t bytes, hipStream_t st)
+{
+    if (bytes <= c->ws_cap) return PC_OK;
+    PC_HIP(c, hipStreamSynchronize(st));
+    PC_HIP(c, hipDeviceSynchronize());
+    if (c->ws) PC_HIP(c, hipFree(c->ws));
+    c->ws = nullptr; c->ws_cap = 0;
+    const size_t cap = align_up(bytes + bytes / 4, 1 << 20);
+    PC_HIP(c, hipMalloc(&c->ws, cap));
+    c->ws_cap = cap;
+    return PC_OK;
+}
+
+int32_t stage_acquire(pc_cache *c, size_t bytes, StageSlot **out)
+{
+    StageSlot &s = c->stage[c->stage_next];
+    c->stage_next = (c->stage_next + 1) % N_STAGE;
+    if (s.used) PC_HIP(c, hipEventSynchronize(s.ev));
+    if (!s.ev) PC_HIP(c, hipEventCreateWithFlags(&s.ev, hipEventDisableTiming));
+    if (bytes > s.cap) {
+        if (s.host) PC_HIP(c, hipHostFree(s.host));
+        s.host = nullptr; s.cap = 0;
+        const size_t cap = align_up(bytes * 2, 4096);
+        PC_HIP(c, hipHostMalloc(&s.host, cap, hipHostMallocDefault));
+        s.cap = cap;
+    }
+    *out = &s;
+    return PC_OK;
+}
+
+// layout of the staged (host -> device) block and of the device-built block
+struct PlanLayout {
+    size_t calls, sel, q_pos, row_call, items_dec, items_pre, h2d_bytes;
+    size_t segs, seg_kvoff, rot_seg, rot_q, part_o, part_ml, total;
+};
+
+PlanLayout make_layout(int n_calls, int total_sel, int total_q, int total_seg, int n_dec, int n_pre,
+                       int64_t part_rows, int H_q, int D)
+{
+    PlanLayout L{};
+    size_t o = 0;
+    auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes, 256); return at; };
+    L.calls = take(sizeof(PcCallDesc) * (size_t)std::max(n_calls, 1));
+    L.sel = take(sizeof(int2) * (size_t)std::max(total_sel, 1));
+    L.q_pos = take(sizeof(int32_t) * (size_t)std::max(total_q, 1));
+    L.row_call = take(sizeof(int32_t) * (size_t)std::max(total_q, 1));
+    L.items_dec = take(sizeof(PcItem) * (size_t)std::max(n_dec, 1));
+    L.items_pre = take(sizeof(PcItem) * (size_t)std::max(n_pre, 1));
+    L.h2d_bytes = o;
+    L.segs = take(sizeof(PcSegment) * (size_t)std::max(total_seg, 1));
+    L.seg_kvoff = take(sizeof(int32_t) * (size_t)std::max(total_seg, 1));
+    L.rot_seg = take(sizeof(float2) * (size_t)std::max(total_seg, 1) * (D / 2));
+    L.rot_q = take(sizeof(float2) * (size_t)std::max(total_q, 1) * (D / 2));
+    L.part_o = take(sizeof(float) * (size_t)std::max<int64_t>(part_rows, 1) * H_q * D);
+    L.part_ml = take(sizeof(float) * (size_t)std::max<int64_t>(part_rows, 1) * H_q * 2);
+    L.total = o;
+    return L;
+}
+
+}  // namespace
+
+// =====================================================================================
+extern "C" {
+
+size_t pc_cache_storage_bytes(const pc_config *cfg)
+{
+    if (!cfg || cfg->n_kv_heads <= 0 || cfg->head_dim <= 0) return 0;
+    return storage_bytes(cfg);
+}
+
+int32_t pc_cache_create(const pc_config *cfg, pc_cache **out)
+{
+    if (!cfg || !out) return PC_ERR_INVALID_ARG;
+    *out = nullptr;
+    if (cfg->n_q_heads <= 0 || cfg->n_kv_heads <= 0 || cfg->n_q_heads % cfg->n_kv_heads) return PC_ERR_SHAPE;
+    if (cfg->head_dim != 64 && cfg->head_dim != 128) return PC_ERR_SHAPE;
+    if (cfg->dtype != PC_F32 && cfg->dtype != PC_BF16) return PC_ERR_INVALID_ARG;
+    if (cfg->dtype == PC_BF16 && cfg->head_dim != 128) return PC_ERR_SHAPE;
+    if (cfg->dtype == PC_BF16 && cfg->n_q_heads / cfg->n_kv_heads > 16) return PC_ERR_SHAPE;
+    if (cfg->capacity_tokens <= 0 || cfg->max_messages <= 0 || !(cfg->rope_theta > 0.f)) return PC_ERR_INVALID_ARG;
+    pc_cache *c = new pc_cache();
+    c->cfg = *cfg;
+    if (c->cfg.max_position <= 0) c->cfg.max_position = 1 << 24;
+    c->host_only = (cfg->flags & PC_FLAG_HOST_ONLY) != 0;
+    c->D = cfg->head_dim; c->half = c->D / 2; c->g = cfg->n_q_heads / cfg->n_kv_heads;
+    c->slots = (int64_t)align_up((size_t)cfg->capacity_tokens, PC_SLOT_ALIGN);
+    if (c->slots > INT32_MAX) { delete c; return PC_ERR_SHAPE; }
+    c->esize = cfg->dtype == PC_BF16 ? 2 : 4;
+    c->scale = cfg->softmax_scale > 0.f ? cfg->softmax_scale : 1.0f / std::sqrt((float)c->D);
+    c->msgs.reserve((size_t)cfg->max_messages);
+    *out = c;
+    if (c->host_only) return PC_OK;
+
+    const size_t bytes = storage_bytes(cfg);
+    auto bail = [&](int32_t code) { pc_cache_destroy(c); *out = nullptr; return code; };
+    if (cfg->arena) {
+        if (cfg->arena_bytes < bytes || ((uintptr_t)cfg->arena & 255)) return bail(PC_ERR_NO_SPACE);
+        c->storage = cfg->arena;
+    } else {
+        if (hipMalloc(&c->storage, bytes) != hipSuccess) return bail(PC_ERR_HIP);
+        c->owns_storage = true;
+    }
+    // zero once: slots past a message's end inside its last tile are read (and masked)
+    if (hipMemset(c->storage, 0, bytes) != hipSuccess) return bail(PC_ERR_HIP);
+    c->k_store = c->storage;
+    c->v_store = (char *)c->storage + bytes / 2;
+    if (hipMalloc((void **)&c->table_dev, sizeof(PcMsgEntry) * (size_t)cfg->max_messages) != hipSuccess) return bail(PC_ERR_HIP);
+    if (hipMemset(c->table_dev, 0, sizeof(PcMsgEntry) * (size_t)cfg->max_messages) != hipSuccess) return bail(PC_ERR_HIP);
+    std::vector<double> f((size_t)c->half);
+    for (int i = 0; i < c->half; ++i) f[i] = std::pow((double)cfg->rope_theta, -2.0 * i / c->D);
+    if (hipMalloc((void **)&c->inv_freq_dev, sizeof(double) * f.size()) != hipSuccess) return bail(PC_ERR_HIP);
+    if (hipMemcpy(c->inv_freq_dev, f.data(), sizeof(double) * f.size(), hipMemcpyHostToDevice) != hipSuccess) return bail(PC_ERR_HIP);
+    if (hipDeviceSynchronize() != hipSuccess) return bail(PC_ERR_HIP);
+    return PC_OK;
+}
+
+int32_t pc_cache_destroy(pc_cache *c)
+{
+    if (!c) return PC_ERR_INVALID_ARG;
+    if (!c->host_only) {
+        (void)hipDeviceSynchronize();
+        prof_collect(c);
+        for (auto e : c->ev_pool) (void)hipEventDestroy(e);
+        for (auto &s : c->stage) { if (s.host) (void)hipHostFree(s.host); if (s.ev) (void)hipEventDestroy(s.ev); }
+        if (c->ws) (void)hipFree(c->ws);
+        if (c->inv_freq_dev) (void)hipFree(c->inv_freq_dev);
+        if (c->table_dev) (void)hipFree(c->table_dev);
+        if (c->owns_storage && c->storage) (void)hipFree(c->storage);
+    }
+    delete c;
+    return PC_OK;
+}
+
+const char *pc_last_error(const pc_cache *c) { return c ? c->err.c_str() : "null cache"; }
+
+int32_t pc_append_message(pc_cache *c, const void *k, const void *v, int32_t len, int32_t reserve,
+                          int32_t *msg_id, void *stream)
+{
+    if (!c) return PC_ERR_INVALID_ARG;
+    if (len < 1) return fail(c, PC_ERR_INVALID_ARG, "append: len = %d must be >= 1", len);
+    if (!c->host_only && (!k || !v)) return fail(c, PC_ERR_INVALID_ARG, "append: null k or v");
+    if (!msg_id) return fail(c, PC_ERR_INVALID_ARG, "append: null msg_id");
+    if ((int64_t)c->msgs.size() >= c->cfg.max_messages)
+        return fail(c, PC_ERR_NO_SPACE, "append: message table full (%d)", c->cfg.max_messages);
+    const int32_t res = std::max(reserve, len);
+    const int64_t start = c->next_slot;
+    if (start + res > c->slots)
+        return fail(c, PC_ERR_NO_SPACE, "append: needs slots [%lld, %lld), capacity %lld", (long long)start,
+                    (long long)(start + res), (long long)c->slots);
+    const int id = (int)c->msgs.size();
+    if (!c->host_only) {
+        hipStream_t st = (hipStream_t)stream;
+        ProfScope ps(c, 0, st);
+        pc_launch_append(c->cfg.dtype, k, v, len, c->cfg.n_kv_heads, c->D, start, c->slots, c->inv_freq_dev,
+                         c->k_store, c->v_store, c->table_dev, id, st);
+        PC_HIP(c, hipGetLastError());
+    }
+    c->msgs.push_back({start, len, res});
+    c->next_slot = (int64_t)align_up((size_t)(start + res), PC_SLOT_ALIGN);
+    *msg_id = id;
+    return PC_OK;
+}
+
+int32_t pc_resolve_call(pc_cache *c, const pc_call *call, int32_t *starts_out, int32_t *self_start_out, int64_t *n_kv)
+{
+    if (!c) return PC_ERR_INVALID_ARG;
+    Resolved r;
+    const int32_t rc = resolve_call(c, call, 0, r);
+    if (rc != PC_OK) return rc;
+    if (starts_out) for (size_t e = 0; e < r.sel.size(); ++e) starts_out[e] = r.sel[e].y;
+    if (self_start_out) *self_start_out = r.self_start;
+    if (n_kv) *n_kv = r.n_kv;
+    return PC_OK;
+}
+
+int32_t pc_message_info(pc_cache *c, int32_t msg_id, int32_t *len, int64_t *slot_start, int32_t *reserved)
+{
+    if (!c) return PC_ERR_INVALID_ARG;
+    if (msg_id < 0 || msg_id >= (int)c->msgs.size()) return fail(c, PC_ERR_BAD_MSG_ID, "unknown message %d", msg_id);
+    if (len) *len = c->msgs[msg_id].len;
+    if (slot_start) *slot_start = c->msgs[msg_id].slot_start;
+    if (reserved) *reserved = c->msgs[msg_id].reserve;
+    return PC_OK;
+}
+
+int32_t pc_cache_info(pc_cache *c, int32_t *n_messages, int64_t *slots_used, int64_t *capacity_slots)
+{
+    if (!c) return PC_ERR_INVALID_ARG;
+    if (n_messages) *n_messages = (int32_t)c->msgs.size();
+    if (slots_used) *slots_used = c->next_slot;
+    if (capacity_slots) *capacity_slots = c->slots;
+    return PC_OK;
+}
+
+int32_t pc_profile_enable(pc_cache *c, int32_t on)
+{
+    if (!c) return PC_ERR_INVALID_ARG;
+    if (c->host_only) return fail(c, PC_ERR_INVALID_ARG, "profiling needs a device cache");
+    c->prof = on != 0;
+    return PC_OK;
+}
+
+int32_t pc_profile_read(pc_cache *c, double ms_total[PC_N_KERNEL_CLASSES], int64_t launches[PC_N_KERNEL_CLASSES], int32_t reset)
+{
+    if (!c) return PC_ERR_INVALID_ARG;
+    if (c->host_only) return fail(c, PC_ERR_INVALID_ARG, "profiling needs a device cache");
+    prof_collect(c);
+    for (int i = 0; i < PC_N_KERNEL_CLASSES; ++i) {
+        if (ms_total) ms_total[i] = c->prof_ms[i];
+        if (launches) launches[i] = c->prof_n[i];
+        if (reset) { c->prof_ms[i] = 0; c->prof_n[i] = 0; }
+    }
+    return PC_OK;
+}
+
+int32_t pc_set_tuning(pc_cache *c, int32_t decode_tiles_per_split, int32_t prefill_tiles_per_split)
+{
+    if (!c || decode_tiles_per_split < 0 || prefill_tiles_per_split < 0) return PC_ERR_INVALID_ARG;
+    c->decode_tiles_per_split = decode_tiles_per_split;
+    c->prefill_tiles_per_split = prefill_tiles_per_split;
+    return PC_OK;
+}
+
+// -------------------------------------------------------------------------------------
+// shared by pc_attend and pc_build_tables: validate, plan, stage, run the plan builder
+// -------------------------------------------------------------------------------------
+struct Planned {
+    PlanLayout lay;
+    int n_calls = 0, total_sel = 0, total_q = 0, total_seg = 0, n_dec = 0, n_pre = 0, pre_waves = 4;
+    bool any_split = false;
+    std::vector<Resolved> res;
+};
+
+static int32_t plan_and_stage(pc_cache *c, const pc_call *calls, int32_t n_calls, bool want_items,
+                              hipStream_t st, Planned &P)
+{
+    P.n_calls = n_calls;
+    P.res.resize((size_t)n_calls);
+    for (int i = 0; i < n_calls; ++i) {
+        const int32_t rc = resolve_call(c, &calls[i], i, P.res[i]);
+        if (rc != PC_OK) return rc;
+        P.total_sel += (int)P.res[i].sel.size();
+        P.total_q += P.res[i].n_q;
+        P.total_seg += (int)P.res[i].sel.size() + (P.res[i].self_msg >= 0 ? 1 : 0);
+    }
+    const int g = c->g, H_kv = c->cfg.n_kv_heads;
+    const bool bf16 = c->cfg.dtype == PC_BF16;
+    // work-group shape of the prefill kernel: `waves` row units (32 rows x 1 q head) per group
+    P.pre_waves = (g >= 8) ? 8 : 4;
+    std::vector<PcCallDesc> cds((size_t)n_calls);
+    std::vector<PcItem> dec, pre;
+    int64_t part_rows = 0;
+    int sel_off = 0, q_off = 0, seg_off = 0;
+    // first pass: how many prefill groups without splitting (to decide on KV splits)
+    int64_t pre_groups = 0;
+    if (want_items && bf16)
+        for (auto &r : P.res)
+            if (r.n_q * g > 16) pre_groups += (int64_t)(((r.n_q + 31) / 32) * g + P.pre_waves - 1) / P.pre_waves * H_kv;
+    for (int i = 0; i < n_calls; ++i) {
+        Resolved &r = P.res[i];
+        PcCallDesc &cd = cds[i];
+        cd.sel_off = sel_off; cd.n_sel = (int)r.sel.size(); cd.self_msg = r.self_msg; cd.self_start = r.self_start;
+        cd.n_q = r.n_q; cd.q_off = q_off; cd.seg_off = seg_off; cd.n_seg = cd.n_sel + (r.self_msg >= 0 ? 1 : 0);
+        cd.self_len = r.self_len; cd.n_splits = 1; cd.part_off = 0; cd.pad = 0;
+        sel_off += cd.n_sel; q_off += cd.n_q; seg_off += cd.n_seg;
+        if (!want_items || !bf16) continue;
+        const int T = r.tiles;
+        if (r.n_q * g <= 16) {                       // decode-shaped: all rows x heads of a KV head in one wave
+            const int per = c->decode_tiles_per_split > 0 ? c->decode_tiles_per_split : 48;
+            int ns = std::max(1, std::min(MAX_SPLITS, (T + per - 1) / per));
+            const int chunk = std::max(1, (T + ns - 1) / ns);
+            ns = std::max(1, (T + chunk - 1) / chunk);
+            cd.n_splits = ns;
+            for (int s = 0; s < ns; ++s) {
+                PcItem it{}; it.call = i; it.unit0 = 0; it.tile_begin = s * chunk; it.tile_end = std::min(T, (s + 1) * chunk); it.split = s;
+                dec.push_back(it);
+            }
+        } else {
+            const int units = ((r.n_q + 31) / 32) * g;
+            const int groups = (units + P.pre_waves - 1) / P.pre_waves;
+            int ns = 1;
+            if (c->prefill_tiles_per_split > 0) ns = (T + c->prefill_tiles_per_split - 1) / c->prefill_tiles_per_split;
+            else if (pre_groups < 512) ns = (int)std::min<int64_t>((512 + pre_groups - 1) / pre_groups, std::max(1, T / 16));
+            ns = std::max(1, std::min(MAX_SPLITS, ns));
+            const int chunk = std::max(1, (T + ns - 1) / ns);
+            ns = std::max(1, (T + chunk - 1) / chunk);
+            cd.n_splits = ns;
+            for (int gidx = 0; gidx < groups; ++gidx)
+                for (int s = 0; s < ns; ++s) {
+                    PcItem it{}; it.call = i; it.unit0 = gidx * P.pre_waves; it.tile_begin = s * chunk; it.tile_end = std::min(T, (s + 1) * chunk); it.split = s;
+                    pre.push_back(it);
+                }
+        }
+        if (cd.n_splits > 1) { cd.part_off = (int32_t)part_rows; part_rows += (int64_t)cd.n_splits * cd.n_q; P.any_split = true; }
+    }
+    if (part_rows > INT32_MAX) return fail(c, PC_ERR_SHAPE, "attend: partial buffer too large");
+    P.n_dec = (int)dec.size(); P.n_pre = (int)pre.size();
+    P.lay = make_layout(n_calls, P.total_sel, P.total_q, P.total_seg, P.n_dec, P.n_pre, part_rows, c->cfg.n_q_heads, c->D);
+    if (c->host_only) return PC_OK;
+
+    int32_t rc = ensure_ws(c, P.lay.total, st);
+    if (rc != PC_OK) return rc;
+    StageSlot *slot = nullptr;
+    rc = stage_acquire(c, P.lay.h2d_bytes, &slot);
+    if (rc != PC_OK) return rc;
+    char *h = (char *)slot->host;
+    std::memcpy(h + P.lay.calls, cds.data(), sizeof(PcCallDesc) * cds.size());
+    int2 *hs = (int2 *)(h + P.lay.sel);
+    int32_t *hq = (int32_t *)(h + P.lay.q_pos), *hr = (int32_t *)(h + P.lay.row_call);
+    for (int i = 0; i < n_calls; ++i) {
+        const Resolved &r = P.res[i];
+        if (!r.sel.empty()) std::memcpy(hs + cds[i].sel_off, r.sel.data(), sizeof(int2) * r.sel.size());
+        std::memcpy(hq + cds[i].q_off, r.q_pos.data(), sizeof(int32_t) * r.q_pos.size());
+        for (int q = 0; q < r.n_q; ++q) hr[cds[i].q_off + q] = i;
+    }
+    if (!dec.empty()) std::memcpy(h + P.lay.items_dec, dec.data(), sizeof(PcItem) * dec.size());
+    if (!pre.empty()) std::memcpy(h + P.lay.items_pre, pre.data(), sizeof(PcItem) * pre.size());
+    PC_HIP(c, hipMemcpyAsync(c->ws, h, P.lay.h2d_bytes, hipMemcpyHostToDevice, st));
+    PC_HIP(c, hipEventRecord(slot->ev, st));
+    slot->used = true;
+    {
+        ProfScope ps(c, 1, st);
+        char *w = (char *)c->ws;
+        pc_launch_build_plan((const PcCallDesc *)(w + P.lay.calls), n_calls, (const int2 *)(w + P.lay.sel),
+                             (const int32_t *)(w + P.lay.q_pos), c->table_dev, c->inv_freq_dev, c->half, P.total_seg,
+                             P.total_q, (PcSegment *)(w + P.lay.segs), (int32_t *)(w + P.lay.seg_kvoff),
+                             (float2 *)(w + P.lay.rot_seg), (float2 *)(w + P.lay.rot_q), st);
+        PC_HIP(c, hipGetLastError());
+    }
+    return PC_OK;
+}
+
+int32_t pc_attend(pc_cache *c, const pc_call *calls, int32_t n_calls, const void *q, void *out, float *lse, void *stream)
+{
+    if (!c) return PC_ERR_INVALID_ARG;
+    if (n_calls < 0 || (n_calls > 0 && !calls)) return fail(c, PC_ERR_INVALID_ARG, "attend: bad call list");
+    if (n_calls == 0) return PC_OK;
+    if (!c->host_only && (!q || !out)) return fail(c, PC_ERR_INVALID_ARG, "attend: null q or out");
+    hipStream_t st = (hipStream_t)stream;
+    Planned P;
+    const int32_t rc = plan_and_stage(c, calls, n_calls, true, st, P);
+    if (rc != PC_OK || c->host_only) return rc;
+
+    char *w = (char *)c->ws;
+    PcLaunch L{};
+    L.calls = (const PcCallDesc *)(w + P.lay.calls);
+    L.segs = (const PcSegment *)(w + P.lay.segs);
+    L.rot_seg = (const float2 *)(w + P.lay.rot_seg);
+    L.rot_q = (const float2 *)(w + P.lay.rot_q);
+    L.k_store = c->k_store; L.v_store = c->v_store; L.q = q; L.out = out; L.lse = lse;
+    L.part_o = (float *)(w + P.lay.part_o); L.part_ml = (float *)(w + P.lay.part_ml);
+    L.slots = c->slots; L.n_q_heads = c->cfg.n_q_heads; L.n_kv_heads = c->cfg.n_kv_heads;
+    L.scale_log2 = c->scale * 1.4426950408889634f;
+    const int32_t *row_call = (const int32_t *)(w + P.lay.row_call);
+    if (c->cfg.dtype == PC_F32) {
+        ProfScope ps(c, 5, st);
+        pc_launch_attend_f32(L, row_call, P.total_q, c->D, st);
+        PC_HIP(c, hipGetLastError());
+        return PC_OK;
+    }
+    if (P.n_pre > 0) {
+        ProfScope ps(c, 2, st);
+        L.items = (const PcItem *)(w + P.lay.items_pre);
+        pc_launch_prefill_bf16(L, P.n_pre, P.pre_waves, st);
+        PC_HIP(c, hipGetLastError());
+    }
+    if (P.n_dec > 0) {
+        ProfScope ps(c, 3, st);
+        L.items = (const PcItem *)(w + P.lay.items_dec);
+        pc_launch_decode_bf16(L, P.n_dec, st);
+        PC_HIP(c, hipGetLastError());
+    }
+    if (P.any_split) {
+        ProfScope ps(c, 4, st);
+        pc_launch_merge(c->cfg.dtype, L.calls, row_call, P.total_q, L.part_o, L.part_ml, out, lse, c->cfg.n_q_heads, c->D, st);
+        PC_HIP(c, hipGetLastError());
+    }
+    return PC_OK;
+}
+
+int32_t pc_build_tables(pc_cache *c, const pc_call *call, int32_t *kv_slot, int32_t *kv_pos, int64_t cap,
+                        int64_t *n_kv, void *stream)
+{
+    if (!c) return PC_ERR_INVALID_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    Planned P;
+    const int32_t rc = plan_and_stage(c, call, 1, false, st, P);
+    if (rc != PC_OK) return rc;
+    const int64_t n = P.res[0].n_kv;
+    if (n_kv) *n_kv = n;
+    if (c->host_only || cap < n || n == 0) return PC_OK;
+    if (!kv_slot || !kv_pos) return fail(c, PC_ERR_INVALID_ARG, "build_tables: null output with cap > 0");
+    ProfScope ps(c, 6, st);
+    char *w = (char *)c->ws;
+    pc_launch_expand_tables((const PcSegment *)(w + P.lay.segs), (const int32_t *)(w + P.lay.seg_kvoff), P.total_seg, n,
+                            kv_slot, kv_pos, st);
+    PC_HIP(c, hipGetLastError());
+    return PC_OK;
+}
+
+}  // extern "C"

@@ -8,8 +8,8 @@ def cache_lists(w, upto_event=None):
         if upto_event is not None and i >= upto_event:
             break
         if e.kind == "append":
-            ks.append(e.k.astype(np.float64))
-            vs.append(e.v.astype(np.float64))
+            ks.append(e.k)      # float32 holding exactly representable values; the
+            vs.append(e.v)      # oracle widens what it gathers to fp64
     return ks, vs
 
 
@@ -38,3 +38,24 @@ def read_golden(path):
     if mask:
         out["mask"] = np.asarray(mask, dtype=bool)
     return out
+
+
+def oracle_for_event(w, ev_index, rows_per_call=None, calls_subset=None):
+    """Oracle outputs for the attend event at w.events[ev_index].
+
+    rows_per_call: None (all rows) or a function n_q -> list of row indices.
+    calls_subset: None (all calls) or a list of call indices.
+    Returns a list of (call_index, row_indices, out, lse)."""
+    from oracle import choreo_oracle as orc
+    ks, vs = cache_lists(w, upto_event=ev_index)
+    ev = w.events[ev_index]
+    offs = np.concatenate([[0], np.cumsum([c.n_q for c in ev.calls])]).astype(int)
+    res = []
+    for ci, c in enumerate(ev.calls):
+        if calls_subset is not None and ci not in calls_subset:
+            continue
+        rows = list(range(c.n_q)) if rows_per_call is None else list(rows_per_call(c.n_q))
+        o, l = orc.attend_call(ks, vs, c.sel, c.self_msg, c.self_start, c.n_q, c.q_pos,
+                               ev.q[offs[ci]:offs[ci + 1]], w.rope_theta, rows=rows)
+        res.append((ci, np.asarray(rows, dtype=int) + offs[ci], o, l))
+    return res

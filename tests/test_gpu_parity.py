@@ -1,0 +1,263 @@
+"""GPU parity: the HIP path, called through the C ABI, against the fp64 CPU oracle on the
+same seeded inputs.  Tolerances: fp32 max-abs 1e-4; bf16 max-abs 2e-2 and mean-abs 1e-3;
+gather tables / position maps bit-exact."""
+import sys
+
+import numpy as np
+import pytest
+
+import pc_inputs as gen
+from tests.helpers import attend_events, oracle_for_event
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": dict(max_abs=1e-4, mean_abs=1e-5, lse=1e-4),
+       "bf16": dict(max_abs=2e-2, mean_abs=1e-3, lse=2e-2)}
+
+
+def say(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def hip():
+    import torch
+    from paper_2512_23049_amd import harness
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    return harness
+
+
+def run_and_compare(hip, w, rows_per_call=None, calls_subset=None, events=None, tuning=None):
+    import torch
+    cache = hip.make_cache(w)
+    if tuning:
+        cache.set_tuning(*tuning)
+    dw = hip.DeviceWorkload(w)
+    say(f"[run] {w.name} dtype={w.dtype} Hq={w.n_q_heads} Hkv={w.n_kv_heads} D={w.head_dim} "
+        f"msgs={w.n_messages} attends={len(attend_events(w))}")
+    res = dw.run(cache)
+    torch.cuda.synchronize()
+    tol = TOL[w.dtype]
+    worst = 0.0
+    for k, (ei, ev) in enumerate(attend_events(w)):
+        if events is not None and k not in events:
+            continue
+        out = res[k][0].float().cpu().numpy()
+        lse = res[k][1].cpu().numpy()
+        assert np.isfinite(out).all()
+        for ci, rows, o, l in oracle_for_event(w, ei, rows_per_call, calls_subset):
+            d = np.abs(out[rows] - o)
+            say(f"  event {k} call {ci}: rows={len(rows)} max_abs={d.max() if d.size else 0:.3e} "
+                f"mean_abs={d.mean() if d.size else 0:.3e}")
+            assert d.size == 0 or d.max() <= tol["max_abs"]
+            assert d.size == 0 or d.mean() <= tol["mean_abs"]
+            fin = np.isfinite(l)
+            assert np.array_equal(np.isfinite(lse[rows]), fin)
+            assert np.array_equal(np.isneginf(lse[rows]), np.isneginf(l))
+            if fin.any():
+                assert np.abs(lse[rows][fin] - l[fin]).max() <= tol["lse"]
+            worst = max(worst, d.max() if d.size else 0.0)
+    cache.close()
+    return worst
+
+
+def tables_check(hip, w, max_calls=None):
+    import torch
+    from oracle import choreo_oracle as orc
+    from paper_2512_23049_amd import PC_SLOT_ALIGN
+    # append lengths only matter: use a host-side walk of the same events on a device cache
+    cache = hip.make_cache(w)
+    dw = hip.DeviceWorkload(w)
+    lens, reserves = [], []
+    n_checked = 0
+    for s, e in zip(dw.steps, w.events):
+        if s[0] == "append":
+            cache.append_message(s[1].data_ptr(), s[2].data_ptr(), s[3], s[4])
+            lens.append(s[3]); reserves.append(max(s[3], s[4]))
+            continue
+        for ci, c in enumerate(e.calls):
+            if max_calls is not None and ci >= max_calls:
+                break
+            exp_slot, exp_pos = orc.tables_for_call(c, lens, reserves, PC_SLOT_ALIGN)
+            n = cache.build_tables(c, 0, 0, 0)
+            assert n == exp_slot.shape[0]
+            slot = torch.full((max(n, 1),), -7, dtype=torch.int32, device="cuda:0")
+            pos = torch.full((max(n, 1),), -7, dtype=torch.int32, device="cuda:0")
+            n2 = cache.build_tables(c, slot.data_ptr(), pos.data_ptr(), n)
+            torch.cuda.synchronize()
+            assert n2 == n
+            assert np.array_equal(slot.cpu().numpy()[:n], exp_slot)
+            assert np.array_equal(pos.cpu().numpy()[:n], exp_pos)
+            n_checked += 1
+    cache.close()
+    say(f"[tables] {w.name}: {n_checked} calls bit-exact")
+
+
+# ------------------------------------------------------------------ config 1 (fp32)
+def test_config1_tiny_fp32(hip):
+    w = gen.tiny_fp32()
+    tables_check(hip, w)
+    run_and_compare(hip, w)
+
+
+@pytest.mark.parametrize("seed", [101, 102])
+def test_small_random_fp32(hip, seed):
+    w = gen.small_random(seed, dtype="f32", n_q_heads=4, n_kv_heads=2, head_dim=64, len_hi=100)
+    tables_check(hip, w)
+    run_and_compare(hip, w)
+
+
+def test_small_random_fp32_d128(hip):
+    w = gen.small_random(103, dtype="f32", n_q_heads=6, n_kv_heads=2, head_dim=128, len_hi=70, max_q=20)
+    run_and_compare(hip, w)
+
+
+# ------------------------------------------------------------- bf16, small and ragged
+@pytest.mark.parametrize("seed,hq,hkv", [(201, 8, 2), (202, 16, 2), (203, 4, 4), (204, 6, 3), (205, 32, 2)])
+def test_small_random_bf16(hip, seed, hq, hkv):
+    w = gen.small_random(seed, dtype="bf16", n_q_heads=hq, n_kv_heads=hkv, head_dim=128)
+    tables_check(hip, w)
+    run_and_compare(hip, w)
+
+
+@pytest.mark.parametrize("tuning", [(1, 1), (3, 2), (1000, 1000)])
+def test_small_random_bf16_split_settings(hip, tuning):
+    # KV splits of 1 tile, a few tiles, and no splitting must all agree with the oracle
+    w = gen.small_random(211, dtype="bf16", n_q_heads=8, n_kv_heads=2, head_dim=128, len_hi=200, max_q=90)
+    run_and_compare(hip, w, tuning=tuning)
+
+
+def test_edge_cases_bf16(hip):
+    from pc_inputs import Call, Event, Workload, POS_AUTO
+    rng = np.random.default_rng(9)
+    w = Workload("edges", 8, 2, 128, "bf16", 10000.0)
+
+    def app(L, reserve=0):
+        k = gen.round_to_bf16(rng.standard_normal((L, 2, 128), dtype=np.float32))
+        v = gen.round_to_bf16(rng.standard_normal((L, 2, 128), dtype=np.float32))
+        w.events.append(Event("append", k=k, v=v, reserve=reserve))
+        return w.n_messages - 1
+    ids = [app(L) for L in (1, 31, 32, 33, 64, 65, 7, 8, 9)] + [app(5, reserve=100)]
+    far = (1 << 24) - 70
+    calls = [
+        Call([], -1, 0, 3, np.array([5, 6, 7], dtype=np.int32)),              # nothing visible
+        Call([], ids[0], POS_AUTO, 1, None),                                   # one own token only
+        Call([(ids[2], 0)], ids[3], POS_AUTO, 33, None),                       # exact-tile parent, 33-row self
+        Call([(ids[1], -far), (ids[5], far - 65)], ids[4], 0, 64, None),       # extreme positions
+        Call([(ids[6], 0), (ids[6], 0), (ids[7], 0), (ids[8], 0)], ids[9], 3, 5, None),  # repeats, overlap
+        Call([(ids[4], POS_AUTO)] * 5, -1, POS_AUTO, 40, None),                # parents only, AUTO rows
+        Call([(ids[3], 10)], ids[3], 10, 33, None),                            # new message also a parent
+    ]
+    q = gen.round_to_bf16(rng.standard_normal((sum(c.n_q for c in calls), 8, 128), dtype=np.float32))
+    w.events.append(Event("attend", calls=calls, q=q))
+    tables_check(hip, w)
+    run_and_compare(hip, w)
+
+
+def test_empty_batch_and_errors(hip):
+    import torch
+    from paper_2512_23049_amd import PcError, PC_ERR_BAD_MSG_ID, PC_ERR_SHAPE, PC_ERR_NO_SPACE
+    from pc_inputs import Call
+    w = gen.small_random(5, dtype="bf16", n_q_heads=8, n_kv_heads=2, head_dim=128, n_msgs=3, n_calls=1)
+    cache = hip.make_cache(w)
+    dw = hip.DeviceWorkload(w)
+    for s in dw.steps:
+        if s[0] == "append":
+            cache.append_message(s[1].data_ptr(), s[2].data_ptr(), s[3], s[4])
+    q = torch.zeros((4, 8, 128), dtype=torch.bfloat16, device="cuda:0")
+    out = torch.ones_like(q)
+    cache.attend([], q.data_ptr(), out.data_ptr())                  # no calls: nothing happens
+    torch.cuda.synchronize()
+    assert (out == 1).all()
+    with pytest.raises(PcError) as ei:
+        cache.attend([Call([(7, 0)], -1, 0, 1, None)], q.data_ptr(), out.data_ptr())
+    assert ei.value.code == PC_ERR_BAD_MSG_ID
+    L0 = cache.message_info(0)[0]
+    with pytest.raises(PcError) as ei:
+        cache.attend([Call([], 0, 0, L0 + 1, None)], q.data_ptr(), out.data_ptr())
+    assert ei.value.code == PC_ERR_SHAPE
+    with pytest.raises(PcError) as ei:
+        big = torch.zeros((10 ** 6, 2, 128), dtype=torch.bfloat16, device="cuda:0")
+        cache.append_message(big.data_ptr(), big.data_ptr(), 10 ** 6)
+    assert ei.value.code == PC_ERR_NO_SPACE
+    torch.cuda.synchronize()
+    assert (out == 1).all()                                          # failed calls enqueue nothing
+    cache.close()
+
+
+# ---------------------------------------------- scaled-down shapes of configs 2-5 (all rows)
+def test_config2_scaled(hip):
+    w = gen.single_prefill(n_msgs=24, len_lo=40, len_hi=300, n_sel=6, n_new=200)
+    tables_check(hip, w)
+    run_and_compare(hip, w)
+
+
+def test_config3_scaled(hip):
+    w = gen.parallel_decode(n_calls=12, sys_len=300, n_pool=20, len_lo=50, len_hi=200, n_sel=4, tail_len=64)
+    tables_check(hip, w)
+    run_and_compare(hip, w)
+
+
+def test_config4_scaled(hip):
+    w = gen.multi_agent_rounds(n_agents=3, n_rounds=3, msg_len=70)
+    tables_check(hip, w)
+    run_and_compare(hip, w)
+
+
+def test_config5_scaled(hip):
+    w = gen.long_context(n_msgs=40, len_lo=30, len_hi=120, target_tokens=2500, n_decode=5, n_prefill_q=150)
+    tables_check(hip, w)
+    run_and_compare(hip, w)
+
+
+# ------------------------------- full sizes, launch configuration of the benchmark, sampled
+def _sample_rows(n_q):
+    if n_q <= 8:
+        return list(range(n_q))
+    return sorted({0, 1, 31, 32, 33, n_q // 2, n_q - 2, n_q - 1} & set(range(n_q)))
+
+
+def test_config2_full_sampled(hip):
+    w = gen.single_prefill()
+    tables_check(hip, w)
+    run_and_compare(hip, w, rows_per_call=_sample_rows)
+
+
+def test_config3_full_sampled(hip):
+    w = gen.parallel_decode()
+    tables_check(hip, w, max_calls=8)
+    run_and_compare(hip, w, calls_subset=[0, 1, 31, 63])
+
+
+def test_config4_full_sampled(hip):
+    w = gen.multi_agent_rounds()
+    run_and_compare(hip, w, rows_per_call=lambda n: [0, 100, n - 1], calls_subset=[0, 5], events=[0, 1, 5])
+
+
+def test_config5_full_sampled(hip):
+    w = gen.long_context()
+    tables_check(hip, w, max_calls=2)
+    run_and_compare(hip, w, rows_per_call=lambda n: [0] if n == 1 else [0, 777, n - 1], calls_subset=[0, 17, 32])
+
+
+# --------------------------------------------------- properties that hold at any size
+def test_shift_and_permutation_on_gpu(hip):
+    import torch
+    from pc_inputs import Call
+    w = gen.single_prefill(n_msgs=12, len_lo=20, len_hi=90, n_sel=5, n_new=48)
+    ev = w.events[-1]
+    c0 = ev.calls[0]
+    shifted = Call([(m, s + 4096) for m, s in c0.sel], c0.self_msg, c0.self_start + 4096, c0.n_q, None)
+    perm = Call(list(reversed(c0.sel)), c0.self_msg, c0.self_start, c0.n_q, None)
+    ev.calls = [c0, shifted, perm]
+    ev.q = np.concatenate([ev.q, ev.q, ev.q], axis=0)
+    cache = hip.make_cache(w)
+    dw = hip.DeviceWorkload(w)
+    (out, lse), = dw.run(cache)
+    torch.cuda.synchronize()
+    o = out.float().cpu().numpy().reshape(3, c0.n_q, w.n_q_heads, w.head_dim)
+    # same stored keys, same arithmetic up to the rounding of the turned queries
+    assert np.abs(o[0] - o[1]).max() <= 2e-2 and np.abs(o[0] - o[1]).mean() <= 1e-3
+    assert np.abs(o[0] - o[2]).max() <= 2e-2 and np.abs(o[0] - o[2]).mean() <= 1e-3
+    cache.close()
