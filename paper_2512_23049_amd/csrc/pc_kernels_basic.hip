@@ -268,55 +268,53 @@ void pc_launch_expand_tables(const PcSegment *segs, const int32_t *seg_kvoff, in
 //   m = max m_s,  l = sum l_s 2^(m_s - m),  O = sum acc_s 2^(m_s - m) / l
 // evaluated in split order (deterministic; no atomics).
 // ----------------------------------------------------------------------------------
-template <typename OutT>
-__global__ __launch_bounds__(256) void pc_merge_kernel(
+template <typename OutT, int D>
+__global__ __launch_bounds__(D) void pc_merge_kernel(
     const PcCallDesc *__restrict__ calls, const int32_t *__restrict__ row_call,
-    const float *__restrict__ part_o, const float *__restrict__ part_ml, OutT *__restrict__ out,
-    float *__restrict__ lse, int n_q_heads, int D)
+    const int32_t *__restrict__ merge_rows, const float *__restrict__ part_o,
+    const float *__restrict__ part_ml, OutT *__restrict__ out, float *__restrict__ lse, int n_q_heads)
 {
-    const int R = blockIdx.x;
+    const int R = merge_rows[blockIdx.x], h = blockIdx.y, d = threadIdx.x;
     const PcCallDesc cd = calls[row_call[R]];
-    if (cd.n_splits <= 1) return;
     const int r = R - cd.q_off;
-    const int n = n_q_heads * D;
-    for (int idx = threadIdx.x; idx < n; idx += blockDim.x) {
-        const int h = idx / D;
-        float m = -INFINITY;
+    const int64_t pr0 = (int64_t)cd.part_off + r;
+    float m = -INFINITY;
+    for (int s = 0; s < cd.n_splits; ++s)
+        m = fmaxf(m, part_ml[((pr0 + (int64_t)s * cd.n_q) * n_q_heads + h) * 2]);
+    float l = 0.f, o = 0.f;
+    if (m > -INFINITY) {
         for (int s = 0; s < cd.n_splits; ++s) {
-            const int64_t pr = (int64_t)cd.part_off + (int64_t)s * cd.n_q + r;
-            m = fmaxf(m, part_ml[(pr * n_q_heads + h) * 2]);
+            const int64_t pr = pr0 + (int64_t)s * cd.n_q;
+            const float ms = part_ml[(pr * n_q_heads + h) * 2];
+            const float w = (ms > -INFINITY) ? exp2f(ms - m) : 0.f;
+            l += part_ml[(pr * n_q_heads + h) * 2 + 1] * w;
+            o += part_o[(pr * n_q_heads + h) * D + d] * w;
         }
-        float l = 0.f, o = 0.f;
-        if (m > -INFINITY) {
-            for (int s = 0; s < cd.n_splits; ++s) {
-                const int64_t pr = (int64_t)cd.part_off + (int64_t)s * cd.n_q + r;
-                const float ms = part_ml[(pr * n_q_heads + h) * 2];
-                const float w = (ms > -INFINITY) ? exp2f(ms - m) : 0.f;
-                l += part_ml[(pr * n_q_heads + h) * 2 + 1] * w;
-                o += part_o[pr * n + idx] * w;
-            }
-        }
-        const float res = (l > 0.f) ? o / l : 0.f;
-        if constexpr (sizeof(OutT) == 2) {
-            __hip_bfloat16 b = __float2bfloat16(res);
-            out[(int64_t)R * n + idx] = *reinterpret_cast<uint16_t *>(&b);
-        } else {
-            out[(int64_t)R * n + idx] = res;
-        }
-        if (lse && (idx % D) == 0)
-            lse[(int64_t)R * n_q_heads + h] = (l > 0.f) ? (m + log2f(l)) * 0.6931471805599453f : -INFINITY;
     }
+    const float res = (l > 0.f) ? o / l : 0.f;
+    const int64_t oi = ((int64_t)R * n_q_heads + h) * D + d;
+    if constexpr (sizeof(OutT) == 2) {
+        __hip_bfloat16 b = __float2bfloat16(res);
+        out[oi] = *reinterpret_cast<uint16_t *>(&b);
+    } else {
+        out[oi] = res;
+    }
+    if (lse && d == 0)
+        lse[(int64_t)R * n_q_heads + h] = (l > 0.f) ? (m + log2f(l)) * 0.6931471805599453f : -INFINITY;
 }
 
-void pc_launch_merge(int dtype, const PcCallDesc *calls, const int32_t *row_call, int total_q,
-                     const float *part_o, const float *part_ml, void *out, float *lse, int n_q_heads,
-                     int D, hipStream_t st)
+void pc_launch_merge(int dtype, const PcCallDesc *calls, const int32_t *row_call, const int32_t *merge_rows,
+                     int n_merge_rows, const float *part_o, const float *part_ml, void *out, float *lse,
+                     int n_q_heads, int D, hipStream_t st)
 {
-    if (total_q <= 0) return;
-    if (dtype == 1)
-        pc_merge_kernel<uint16_t><<<total_q, 256, 0, st>>>(calls, row_call, part_o, part_ml, (uint16_t *)out, lse, n_q_heads, D);
+    if (n_merge_rows <= 0) return;
+    dim3 grid(n_merge_rows, n_q_heads);
+    if (dtype == 1 && D == 128)
+        pc_merge_kernel<uint16_t, 128><<<grid, 128, 0, st>>>(calls, row_call, merge_rows, part_o, part_ml, (uint16_t *)out, lse, n_q_heads);
+    else if (dtype == 0 && D == 128)
+        pc_merge_kernel<float, 128><<<grid, 128, 0, st>>>(calls, row_call, merge_rows, part_o, part_ml, (float *)out, lse, n_q_heads);
     else
-        pc_merge_kernel<float><<<total_q, 256, 0, st>>>(calls, row_call, part_o, part_ml, (float *)out, lse, n_q_heads, D);
+        pc_merge_kernel<float, 64><<<grid, 64, 0, st>>>(calls, row_call, merge_rows, part_o, part_ml, (float *)out, lse, n_q_heads);
 }
 
 // ----------------------------------------------------------------------------------

@@ -68,9 +68,9 @@ __global__ __launch_bounds__(256) void pc_decode_bf16_kernel(PcLaunch L)
     __shared__ float s_acc[4][PC_D][17];
     __shared__ float s_m[4][16], s_l[4][16];
 
-    const PcItem item = L.items[blockIdx.x];
+    const int kh = blockIdx.x % L.n_kv_heads;          // consecutive workgroups (one per XCD) take different KV heads
+    const PcItem item = L.items[blockIdx.x / L.n_kv_heads];
     const PcCallDesc cd = L.calls[item.call];
-    const int kh = blockIdx.y;
     const int g = L.n_q_heads / L.n_kv_heads;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int n = lane & 15, a = lane >> 4;
@@ -250,7 +250,7 @@ __global__ __launch_bounds__(256) void pc_decode_bf16_kernel(PcLaunch L)
 void pc_launch_decode_bf16(const PcLaunch &L, int n_items, hipStream_t st)
 {
     if (n_items <= 0) return;
-    dim3 grid(n_items, L.n_kv_heads);
+    dim3 grid((unsigned)n_items * L.n_kv_heads);
     pc_decode_bf16_kernel<<<grid, 256, 0, st>>>(L);
 }
 
@@ -259,20 +259,34 @@ void pc_launch_decode_bf16(const PcLaunch &L, int n_items, hipStream_t st)
 // 32 query rows of one query head (units are numbered head-fastest, so the g heads that
 // share the KV head sit in one workgroup and share every staged K/V tile).  32-key tiles
 // are staged through LDS, double buffered; each wave runs 32x32x16 MFMAs against them.
+// Softmax runs in the log2 domain with a lazily updated reference maximum: the running
+// reference only moves (and the accumulators are only rescaled) when a tile's maximum
+// exceeds it by more than 2^8, so the common tile costs one fma + one exp per score.
 // ----------------------------------------------------------------------------------------
 #define KROW 272        // bytes per K row in LDS (256 + 16 padding: conflict-free 16 B reads)
 #define KTILE_BYTES (32 * KROW)
 #define VTILE_BYTES (4 * PC_D * 16)
+#define LAZY_LOG2 8.0f
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+__device__ __forceinline__ float max_across_halves(float x)
+{
+    // lanes l and l^32 hold the two halves of one column
+    auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
 
 template <int NW>
 __global__ __launch_bounds__(NW * 64) void pc_prefill_bf16_kernel(PcLaunch L)
 {
     __shared__ __attribute__((aligned(16))) unsigned char s_k[2][KTILE_BYTES];
     __shared__ __attribute__((aligned(16))) unsigned char s_v[2][VTILE_BYTES];
+    __shared__ __attribute__((aligned(16))) float2 s_rot[2][PC_D / 2];
 
-    const PcItem item = L.items[blockIdx.x];
+    const int kh = blockIdx.x % L.n_kv_heads;
+    const PcItem item = L.items[blockIdx.x / L.n_kv_heads];
     const PcCallDesc cd = L.calls[item.call];
-    const int kh = blockIdx.y;
     const int g = L.n_q_heads / L.n_kv_heads;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int n = lane & 31, hh = lane >> 5;
@@ -287,10 +301,12 @@ __global__ __launch_bounds__(NW * 64) void pc_prefill_bf16_kernel(PcLaunch L)
     const int h = kh * g + uj;
     const int self_seg = cd.self_msg >= 0 ? cd.n_seg - 1 : -1;
     const int self_lim = cd.self_len - cd.n_q + row;     // last own token this row sees
-    // last own token any row of this wave / of the whole workgroup sees
-    const int wave_lim = cd.self_len - cd.n_q + min(32 * ub + 31, cd.n_q - 1);
+    // first / last own token limits over the rows of this wave, last over the workgroup
+    const int wave_lim_lo = cd.self_len - cd.n_q + 32 * ub;
+    const int wave_lim_hi = cd.self_len - cd.n_q + min(32 * ub + 31, cd.n_q - 1);
     const int last_unit = min(item.unit0 + NW - 1, n_units - 1);
     const int wg_lim = cd.self_len - cd.n_q + min(32 * (last_unit / g) + 31, cd.n_q - 1);
+    const float c_log2 = L.scale_log2;
 
     // query turned by its own position, fp32: element (ks, j) is dim 16*ks + 8*hh + j
     float qh[8][8];
@@ -317,14 +333,13 @@ __global__ __launch_bounds__(NW * 64) void pc_prefill_bf16_kernel(PcLaunch L)
 
     // tiles this workgroup walks: its split's range, cut at the causal limit of its last row
     int tile_end = item.tile_end;
-    int self_tile_off = 0;
     if (self_seg >= 0) {
-        self_tile_off = L.segs[cd.seg_off + self_seg].tile_off;
-        tile_end = min(tile_end, self_tile_off + (wg_lim + PC_TILE) / PC_TILE);   // ceil((wg_lim+1)/32)
+        const int self_tile_off = L.segs[cd.seg_off + self_seg].tile_off;
+        tile_end = min(tile_end, self_tile_off + (wg_lim + PC_TILE) / PC_TILE);
     }
     int tile = item.tile_begin;
 
-    float m_run = -INFINITY, l_run = 0.f;
+    float m_ref = -INFINITY, l_run = 0.f;
     f32x16 acc[4];
 #pragma unroll
     for (int db = 0; db < 4; ++db)
@@ -351,53 +366,55 @@ __global__ __launch_bounds__(NW * 64) void pc_prefill_bf16_kernel(PcLaunch L)
         }
     };
 
-    // global -> register staging of one tile: 512 16-byte chunks of K, 512 of V
+    // global -> register staging of one tile: 512 16-byte chunks of K, 512 of V, and (when the
+    // tile opens a new segment) the segment's 512-byte rotation table
     constexpr int CH = 512 / (NW * 64);
-    uint4 stg_k[CH], stg_v[CH];
-    auto g_load = [&](int slot0) {
+    uint4 stg_k[CH], stg_v[CH], stg_r;
+    auto g_load = [&](int slot0, int seg, bool new_seg) {
 #pragma unroll
         for (int i = 0; i < CH; ++i) {
             const int c = threadIdx.x + i * NW * 64;
             stg_k[i] = ldg16(kb + (int64_t)slot0 * 256 + c * 16);
             stg_v[i] = ldg16(vb + (int64_t)slot0 * 256 + c * 16);
         }
+        if (new_seg && threadIdx.x < 32)
+            stg_r = ldg16((const unsigned char *)(L.rot_seg + (int64_t)(cd.seg_off + seg) * (PC_D / 2)) + threadIdx.x * 16);
     };
-    auto s_store = [&](int buf) {
+    auto s_store = [&](int buf, bool new_seg) {
 #pragma unroll
         for (int i = 0; i < CH; ++i) {
             const int c = threadIdx.x + i * NW * 64;
             *reinterpret_cast<uint4 *>(&s_k[buf][(c >> 4) * KROW + (c & 15) * 16]) = stg_k[i];
             *reinterpret_cast<uint4 *>(&s_v[buf][c * 16]) = stg_v[i];
         }
+        if (new_seg && threadIdx.x < 32)
+            *reinterpret_cast<uint4 *>((unsigned char *)&s_rot[buf][0] + threadIdx.x * 16) = stg_r;
     };
 
-    int cur_seg = -1;
     bf16x8 qop[8];
     // K row read by this lane for MFMA row (lane & 31): rows are permuted so that the score
     // registers 0..7 / 8..15 of a lane are keys 8*hh + 0..7 / 16 + 8*hh + 0..7
-    const int mrow = n;
-    const int krow = 16 * (mrow >> 4) + 8 * ((mrow >> 2) & 1) + 4 * ((mrow >> 3) & 1) + (mrow & 3);
+    const int krow = 16 * (n >> 4) + 8 * ((n >> 2) & 1) + 4 * ((n >> 3) & 1) + (n & 3);
 
-    auto compute = [&](int buf, int seg, int key0, int valid) {
-        if (seg != cur_seg) {
-            cur_seg = seg;
-            const float2 *rs = L.rot_seg + (int64_t)(cd.seg_off + seg) * (PC_D / 2) + 8 * hh;
+    auto turn_query = [&](int buf) {           // query turned by -segment start, as bf16 MFMA operands
+        const float4 *rs = reinterpret_cast<const float4 *>(&s_rot[buf][8 * hh]);
 #pragma unroll
-            for (int ks = 0; ks < 4; ++ks) {
-                uint32_t lo[4], hi[4];
+        for (int ks = 0; ks < 4; ++ks) {
+            uint32_t lo[4], hi[4];
 #pragma unroll
-                for (int j = 0; j < 8; j += 2) {
-                    const float2 c0 = rs[16 * ks + j], c1 = rs[16 * ks + j + 1];
-                    const float x0 = qh[ks][j], y0 = qh[ks + 4][j], x1 = qh[ks][j + 1], y1 = qh[ks + 4][j + 1];
-                    lo[j >> 1] = pack_bf16(x0 * c0.x + y0 * c0.y, x1 * c1.x + y1 * c1.y);
-                    hi[j >> 1] = pack_bf16(y0 * c0.x - x0 * c0.y, y1 * c1.x - x1 * c1.y);
-                }
-                qop[ks] = __builtin_bit_cast(bf16x8, make_uint4(lo[0], lo[1], lo[2], lo[3]));
-                qop[ks + 4] = __builtin_bit_cast(bf16x8, make_uint4(hi[0], hi[1], hi[2], hi[3]));
+            for (int j = 0; j < 8; j += 2) {
+                const float4 cc = rs[(16 * ks + j) >> 1];      // (cos, sin) of pairs j and j+1
+                const float x0 = qh[ks][j], y0 = qh[ks + 4][j], x1 = qh[ks][j + 1], y1 = qh[ks + 4][j + 1];
+                lo[j >> 1] = pack_bf16(x0 * cc.x + y0 * cc.y, x1 * cc.z + y1 * cc.w);
+                hi[j >> 1] = pack_bf16(y0 * cc.x - x0 * cc.y, y1 * cc.z - x1 * cc.w);
             }
+            qop[ks] = __builtin_bit_cast(bf16x8, make_uint4(lo[0], lo[1], lo[2], lo[3]));
+            qop[ks + 4] = __builtin_bit_cast(bf16x8, make_uint4(hi[0], hi[1], hi[2], hi[3]));
         }
-        const bool is_self = seg == self_seg;
-        if (!unit_ok || (is_self && key0 > wave_lim)) return;     // nothing visible to this wave
+    };
+
+    auto compute = [&](int buf, bool is_self, int key0, int valid) {
+        if (!unit_ok || (is_self && key0 > wave_lim_hi)) return;     // nothing visible to this wave
         f32x16 s;
 #pragma unroll
         for (int r = 0; r < 16; ++r) s[r] = 0.f;
@@ -408,24 +425,32 @@ __global__ __launch_bounds__(NW * 64) void pc_prefill_bf16_kernel(PcLaunch L)
             s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qop[ks], s, 0, 0, 0);
         }
         // register r of this lane is key 16*(r/8) + 8*hh + (r%8) of column n
-        const int lim = is_self ? min(valid, self_lim - key0 + 1) : valid;
-        float mx = -INFINITY;
+        if (valid < PC_TILE || (is_self && key0 + PC_TILE - 1 > wave_lim_lo)) {
+            const int lim = is_self ? min(valid, self_lim - key0 + 1) : valid;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int key = 16 * (r >> 3) + 8 * hh + (r & 7);
-            const float v = s[r] * L.scale_log2;
-            s[r] = (key < lim) ? v : -INFINITY;
-            mx = fmaxf(mx, s[r]);
+            for (int r = 0; r < 16; ++r) {
+                const int key = 16 * (r >> 3) + 8 * hh + (r & 7);
+                s[r] = (key < lim) ? s[r] : -INFINITY;
+            }
         }
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
-        const float m_new = fmaxf(m_run, mx);
-        const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
-        const float alpha = exp2f(m_run - m_safe);
+        float mx = fmaxf(s[0], s[1]);
+#pragma unroll
+        for (int r = 2; r < 16; r += 2) mx = fmaxf(mx, fmaxf(s[r], s[r + 1]));
+        mx = max_across_halves(mx) * c_log2;
+        const bool need = mx > m_ref + LAZY_LOG2;
+        if (__builtin_amdgcn_ballot_w64(need) != 0) {
+            const float m_new = need ? mx : m_ref;
+            const float alpha = need ? fast_exp2(m_ref - m_new) : 1.f;
+            l_run *= alpha;
+#pragma unroll
+            for (int db = 0; db < 4; ++db) acc[db] *= alpha;
+            m_ref = m_new;
+        }
+        const float neg_m = (m_ref == -INFINITY) ? 0.f : -m_ref;
         float ps = 0.f;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) { s[r] = exp2f(s[r] - m_safe); ps += s[r]; }
-        l_run = l_run * alpha + ps;
-        m_run = m_new;
+        for (int r = 0; r < 16; ++r) { s[r] = fast_exp2(fmaf(s[r], c_log2, neg_m)); ps += s[r]; }
+        l_run += ps;
         bf16x8 pop[2];
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks)
@@ -434,7 +459,6 @@ __global__ __launch_bounds__(NW * 64) void pc_prefill_bf16_kernel(PcLaunch L)
         const unsigned char *vr = &s_v[buf][(hh * PC_D + n) * 16];
 #pragma unroll
         for (int db = 0; db < 4; ++db) {
-            acc[db] *= alpha;
 #pragma unroll
             for (int ks = 0; ks < 2; ++ks) {
                 const bf16x8 va = *reinterpret_cast<const bf16x8 *>(vr + ((2 * ks) * PC_D + 32 * db) * 16);
@@ -446,28 +470,34 @@ __global__ __launch_bounds__(NW * 64) void pc_prefill_bf16_kernel(PcLaunch L)
     if (tile < tile_end) {
         seek(tile);
         int seg = e, key0 = (tile - sg.tile_off) * PC_TILE, valid = min(PC_TILE, sg.len - key0);
-        g_load(sg.slot_start + key0);
-        s_store(0);
+        bool fresh = true;                         // the current tile opens a segment (for this workgroup)
+        g_load(sg.slot_start + key0, seg, true);
+        s_store(0, true);
         __syncthreads();
         int buf = 0;
         while (tile < tile_end) {
             const bool more = tile + 1 < tile_end;
-            int nseg = 0, nkey0 = 0, nvalid = 0;
+            int nseg = seg, nkey0 = 0, nvalid = 0;
             if (more) {
                 seek(tile + 1);
                 nseg = e; nkey0 = (tile + 1 - sg.tile_off) * PC_TILE; nvalid = min(PC_TILE, sg.len - nkey0);
-                g_load(sg.slot_start + nkey0);
+                g_load(sg.slot_start + nkey0, nseg, nseg != seg);
             }
-            compute(buf, seg, key0, valid);
-            if (more) s_store(buf ^ 1);
+            if (fresh) turn_query(buf);
+            compute(buf, seg == self_seg, key0, valid);
+            if (more) s_store(buf ^ 1, nseg != seg);
             __syncthreads();
+            fresh = nseg != seg;
             buf ^= 1; seg = nseg; key0 = nkey0; valid = nvalid;
             ++tile;
         }
     }
 
     // epilogue: this lane holds, for row n, dims 32*db + 8*(r/4) + 4*hh + (r%4)
-    l_run += __shfl_xor(l_run, 32);
+    {
+        auto r2 = __builtin_amdgcn_permlane32_swap(__float_as_uint(l_run), __float_as_uint(l_run), false, false);
+        l_run = __uint_as_float(r2[0]) + __uint_as_float(r2[1]);
+    }
     if (!row_ok) return;
     if (cd.n_splits == 1) {
         const float inv = l_run > 0.f ? 1.f / l_run : 0.f;
@@ -483,7 +513,7 @@ __global__ __launch_bounds__(NW * 64) void pc_prefill_bf16_kernel(PcLaunch L)
                 *reinterpret_cast<uint2 *>(o + d) = w;
             }
         if (L.lse && hh == 0)
-            L.lse[(int64_t)R * L.n_q_heads + h] = (l_run > 0.f) ? (m_run + log2f(l_run)) * 0.6931471805599453f : -INFINITY;
+            L.lse[(int64_t)R * L.n_q_heads + h] = (l_run > 0.f) ? (m_ref + log2f(l_run)) * 0.6931471805599453f : -INFINITY;
     } else {
         const int64_t pr = (int64_t)cd.part_off + (int64_t)item.split * cd.n_q + row;
         float *o = L.part_o + (pr * L.n_q_heads + h) * PC_D;
@@ -494,14 +524,14 @@ __global__ __launch_bounds__(NW * 64) void pc_prefill_bf16_kernel(PcLaunch L)
                 const int d = 32 * db + 8 * q4 + 4 * hh;
                 *reinterpret_cast<float4 *>(o + d) = make_float4(acc[db][4 * q4], acc[db][4 * q4 + 1], acc[db][4 * q4 + 2], acc[db][4 * q4 + 3]);
             }
-        if (hh == 0) { L.part_ml[(pr * L.n_q_heads + h) * 2] = m_run; L.part_ml[(pr * L.n_q_heads + h) * 2 + 1] = l_run; }
+        if (hh == 0) { L.part_ml[(pr * L.n_q_heads + h) * 2] = m_ref; L.part_ml[(pr * L.n_q_heads + h) * 2 + 1] = l_run; }
     }
 }
 
 void pc_launch_prefill_bf16(const PcLaunch &L, int n_items, int waves, hipStream_t st)
 {
     if (n_items <= 0) return;
-    dim3 grid(n_items, L.n_kv_heads);
+    dim3 grid((unsigned)n_items * L.n_kv_heads);
     if (waves == 8) pc_prefill_bf16_kernel<8><<<grid, 512, 0, st>>>(L);
     else pc_prefill_bf16_kernel<4><<<grid, 256, 0, st>>>(L);
 }

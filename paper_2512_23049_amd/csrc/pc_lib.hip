@@ -197,7 +197,7 @@ int32_t stage_acquire(pc_cache *c, size_t bytes, StageSlot **out)
 
 // layout of the staged (host -> device) block and of the device-built block
 struct PlanLayout {
-    size_t calls, sel, q_pos, row_call, items_dec, items_pre, h2d_bytes;
+    size_t calls, sel, q_pos, row_call, merge_rows, items_dec, items_pre, h2d_bytes;
     size_t segs, seg_kvoff, rot_seg, rot_q, part_o, part_ml, total;
 };
 
@@ -211,6 +211,7 @@ PlanLayout make_layout(int n_calls, int total_sel, int total_q, int total_seg, i
     L.sel = take(sizeof(int2) * (size_t)std::max(total_sel, 1));
     L.q_pos = take(sizeof(int32_t) * (size_t)std::max(total_q, 1));
     L.row_call = take(sizeof(int32_t) * (size_t)std::max(total_q, 1));
+    L.merge_rows = take(sizeof(int32_t) * (size_t)std::max(total_q, 1));
     L.items_dec = take(sizeof(PcItem) * (size_t)std::max(n_dec, 1));
     L.items_pre = take(sizeof(PcItem) * (size_t)std::max(n_pre, 1));
     L.h2d_bytes = o;
@@ -394,7 +395,7 @@ int32_t pc_set_tuning(pc_cache *c, int32_t decode_tiles_per_split, int32_t prefi
 struct Planned {
     PlanLayout lay;
     int n_calls = 0, total_sel = 0, total_q = 0, total_seg = 0, n_dec = 0, n_pre = 0, pre_waves = 4;
-    bool any_split = false;
+    int n_merge_rows = 0;
     std::vector<Resolved> res;
 };
 
@@ -458,7 +459,7 @@ static int32_t plan_and_stage(pc_cache *c, const pc_call *calls, int32_t n_calls
                     pre.push_back(it);
                 }
         }
-        if (cd.n_splits > 1) { cd.part_off = (int32_t)part_rows; part_rows += (int64_t)cd.n_splits * cd.n_q; P.any_split = true; }
+        if (cd.n_splits > 1) { cd.part_off = (int32_t)part_rows; part_rows += (int64_t)cd.n_splits * cd.n_q; }
     }
     if (part_rows > INT32_MAX) return fail(c, PC_ERR_SHAPE, "attend: partial buffer too large");
     P.n_dec = (int)dec.size(); P.n_pre = (int)pre.size();
@@ -473,12 +474,14 @@ static int32_t plan_and_stage(pc_cache *c, const pc_call *calls, int32_t n_calls
     char *h = (char *)slot->host;
     std::memcpy(h + P.lay.calls, cds.data(), sizeof(PcCallDesc) * cds.size());
     int2 *hs = (int2 *)(h + P.lay.sel);
-    int32_t *hq = (int32_t *)(h + P.lay.q_pos), *hr = (int32_t *)(h + P.lay.row_call);
+    int32_t *hq = (int32_t *)(h + P.lay.q_pos), *hr = (int32_t *)(h + P.lay.row_call), *hm = (int32_t *)(h + P.lay.merge_rows);
     for (int i = 0; i < n_calls; ++i) {
         const Resolved &r = P.res[i];
         if (!r.sel.empty()) std::memcpy(hs + cds[i].sel_off, r.sel.data(), sizeof(int2) * r.sel.size());
         std::memcpy(hq + cds[i].q_off, r.q_pos.data(), sizeof(int32_t) * r.q_pos.size());
         for (int q = 0; q < r.n_q; ++q) hr[cds[i].q_off + q] = i;
+        if (cds[i].n_splits > 1)
+            for (int q = 0; q < r.n_q; ++q) hm[P.n_merge_rows++] = cds[i].q_off + q;
     }
     if (!dec.empty()) std::memcpy(h + P.lay.items_dec, dec.data(), sizeof(PcItem) * dec.size());
     if (!pre.empty()) std::memcpy(h + P.lay.items_pre, pre.data(), sizeof(PcItem) * pre.size());
@@ -537,9 +540,10 @@ int32_t pc_attend(pc_cache *c, const pc_call *calls, int32_t n_calls, const void
         pc_launch_decode_bf16(L, P.n_dec, st);
         PC_HIP(c, hipGetLastError());
     }
-    if (P.any_split) {
+    if (P.n_merge_rows > 0) {
         ProfScope ps(c, 4, st);
-        pc_launch_merge(c->cfg.dtype, L.calls, row_call, P.total_q, L.part_o, L.part_ml, out, lse, c->cfg.n_q_heads, c->D, st);
+        pc_launch_merge(c->cfg.dtype, L.calls, row_call, (const int32_t *)(w + P.lay.merge_rows), P.n_merge_rows, L.part_o,
+                        L.part_ml, out, lse, c->cfg.n_q_heads, c->D, st);
         PC_HIP(c, hipGetLastError());
     }
     return PC_OK;

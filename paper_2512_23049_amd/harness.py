@@ -19,11 +19,11 @@ def to_device(x: np.ndarray, dtype_name: str, device="cuda:0") -> torch.Tensor:
     return torch.from_numpy(np.ascontiguousarray(x)).to(device=device, dtype=torch_dtype(dtype_name))
 
 
-def make_cache(w, slack_tokens: int = 0, **kw) -> Cache:
+def make_cache(w, slack_tokens: int = 0, extra_messages: int = 0, **kw) -> Cache:
     reserves = w.message_reserves()
     cap = sum(((r + 31) // 32) * 32 for r in reserves) + 32 + slack_tokens
     return Cache(w.n_q_heads, w.n_kv_heads, w.head_dim, PC_BF16 if w.dtype == "bf16" else PC_F32,
-                 w.rope_theta, cap, max(len(reserves), 1) + 8, **kw)
+                 w.rope_theta, cap, max(len(reserves), 1) + 8 + extra_messages, **kw)
 
 
 class DeviceWorkload:
