@@ -277,6 +277,8 @@ __device__ __forceinline__ float max_across_halves(float x)
     return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
 }
 
+#define SGB(mask, n) __builtin_amdgcn_sched_group_barrier(mask, n, 0)
+
 template <int NW>
 __global__ __launch_bounds__(NW * 64) void pc_prefill_bf16_kernel(PcLaunch L)
 {
@@ -301,9 +303,7 @@ __global__ __launch_bounds__(NW * 64) void pc_prefill_bf16_kernel(PcLaunch L)
     const int h = kh * g + uj;
     const int self_seg = cd.self_msg >= 0 ? cd.n_seg - 1 : -1;
     const int self_lim = cd.self_len - cd.n_q + row;     // last own token this row sees
-    // first / last own token limits over the rows of this wave, last over the workgroup
-    const int wave_lim_lo = cd.self_len - cd.n_q + 32 * ub;
-    const int wave_lim_hi = cd.self_len - cd.n_q + min(32 * ub + 31, cd.n_q - 1);
+    const int wave_lim_lo = cd.self_len - cd.n_q + 32 * ub;       // ... the wave's first row sees
     const int last_unit = min(item.unit0 + NW - 1, n_units - 1);
     const int wg_lim = cd.self_len - cd.n_q + min(32 * (last_unit / g) + 31, cd.n_q - 1);
     const float c_log2 = L.scale_log2;
@@ -337,19 +337,21 @@ __global__ __launch_bounds__(NW * 64) void pc_prefill_bf16_kernel(PcLaunch L)
         const int self_tile_off = L.segs[cd.seg_off + self_seg].tile_off;
         tile_end = min(tile_end, self_tile_off + (wg_lim + PC_TILE) / PC_TILE);
     }
-    int tile = item.tile_begin;
+    const int tile0 = item.tile_begin;
+    const int T = tile_end - tile0;
 
-    float m_ref = -INFINITY, l_run = 0.f;
+    float m_ref = -INFINITY, neg_m = 0.f, l_run = 0.f;
     f32x16 acc[4];
 #pragma unroll
     for (int db = 0; db < 4; ++db)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[db][r] = 0.f;
 
-    // segment cursor (uniform over the workgroup)
+    // segment cursor (uniform over the workgroup); tiles are described in non-decreasing order
     int e = 0, seg_tiles_end = 0;
     PcSegment sg = {0, 0, 0, 0};
-    auto seek = [&](int t) {
+    struct Desc { int seg, key0, valid, slot0; bool fresh; };
+    auto describe = [&](int t, int prev_seg) {
         while (t >= seg_tiles_end) {
             if (seg_tiles_end == 0) {
                 int lo = 0, hi = cd.n_seg - 1;
@@ -364,37 +366,49 @@ __global__ __launch_bounds__(NW * 64) void pc_prefill_bf16_kernel(PcLaunch L)
             sg = L.segs[cd.seg_off + e];
             seg_tiles_end = sg.tile_off + (sg.len + PC_TILE - 1) / PC_TILE;
         }
+        Desc d;
+        d.seg = e; d.key0 = (t - sg.tile_off) * PC_TILE; d.valid = min(PC_TILE, sg.len - d.key0);
+        d.slot0 = sg.slot_start + d.key0; d.fresh = e != prev_seg;
+        return d;
     };
 
-    // global -> register staging of one tile: 512 16-byte chunks of K, 512 of V, and (when the
-    // tile opens a new segment) the segment's 512-byte rotation table
+    // global -> register -> LDS staging: 512 16-byte chunks per K tile and per V tile, plus the
+    // 512-byte rotation table of a segment when a K tile opens it
     constexpr int CH = 512 / (NW * 64);
     uint4 stg_k[CH], stg_v[CH], stg_r;
-    auto g_load = [&](int slot0, int seg, bool new_seg) {
+    auto g_load_k = [&](const Desc &d) {
 #pragma unroll
-        for (int i = 0; i < CH; ++i) {
-            const int c = threadIdx.x + i * NW * 64;
-            stg_k[i] = ldg16(kb + (int64_t)slot0 * 256 + c * 16);
-            stg_v[i] = ldg16(vb + (int64_t)slot0 * 256 + c * 16);
-        }
-        if (new_seg && threadIdx.x < 32)
-            stg_r = ldg16((const unsigned char *)(L.rot_seg + (int64_t)(cd.seg_off + seg) * (PC_D / 2)) + threadIdx.x * 16);
+        for (int i = 0; i < CH; ++i) stg_k[i] = ldg16(kb + (int64_t)d.slot0 * 256 + (threadIdx.x + i * NW * 64) * 16);
+        if (d.fresh && threadIdx.x < 32)
+            stg_r = ldg16((const unsigned char *)(L.rot_seg + (int64_t)(cd.seg_off + d.seg) * (PC_D / 2)) + threadIdx.x * 16);
     };
-    auto s_store = [&](int buf, bool new_seg) {
+    auto g_load_v = [&](const Desc &d) {
+#pragma unroll
+        for (int i = 0; i < CH; ++i) stg_v[i] = ldg16(vb + (int64_t)d.slot0 * 256 + (threadIdx.x + i * NW * 64) * 16);
+    };
+    auto s_store_k = [&](int buf, bool fresh) {
 #pragma unroll
         for (int i = 0; i < CH; ++i) {
             const int c = threadIdx.x + i * NW * 64;
             *reinterpret_cast<uint4 *>(&s_k[buf][(c >> 4) * KROW + (c & 15) * 16]) = stg_k[i];
+        }
+        if (fresh && threadIdx.x < 32)
+            *reinterpret_cast<uint4 *>((unsigned char *)&s_rot[buf][0] + threadIdx.x * 16) = stg_r;
+    };
+    auto s_store_v = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < CH; ++i) {
+            const int c = threadIdx.x + i * NW * 64;
             *reinterpret_cast<uint4 *>(&s_v[buf][c * 16]) = stg_v[i];
         }
-        if (new_seg && threadIdx.x < 32)
-            *reinterpret_cast<uint4 *>((unsigned char *)&s_rot[buf][0] + threadIdx.x * 16) = stg_r;
     };
 
     bf16x8 qop[8];
     // K row read by this lane for MFMA row (lane & 31): rows are permuted so that the score
     // registers 0..7 / 8..15 of a lane are keys 8*hh + 0..7 / 16 + 8*hh + 0..7
     const int krow = 16 * (n >> 4) + 8 * ((n >> 2) & 1) + 4 * ((n >> 3) & 1) + (n & 3);
+    const int k_lane_off = krow * KROW + hh * 16;
+    const int v_lane_off = (hh * PC_D + n) * 16;
 
     auto turn_query = [&](int buf) {           // query turned by -segment start, as bf16 MFMA operands
         const float4 *rs = reinterpret_cast<const float4 *>(&s_rot[buf][8 * hh]);
@@ -413,20 +427,13 @@ __global__ __launch_bounds__(NW * 64) void pc_prefill_bf16_kernel(PcLaunch L)
         }
     };
 
-    auto compute = [&](int buf, bool is_self, int key0, int valid) {
-        if (!unit_ok || (is_self && key0 > wave_lim_hi)) return;     // nothing visible to this wave
-        f32x16 s;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) s[r] = 0.f;
-        const unsigned char *kr = &s_k[buf][krow * KROW + hh * 16];
-#pragma unroll
-        for (int ks = 0; ks < 8; ++ks) {
-            const bf16x8 ka = *reinterpret_cast<const bf16x8 *>(kr + ks * 32);
-            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qop[ks], s, 0, 0, 0);
-        }
-        // register r of this lane is key 16*(r/8) + 8*hh + (r%8) of column n
-        if (valid < PC_TILE || (is_self && key0 + PC_TILE - 1 > wave_lim_lo)) {
-            const int lim = is_self ? min(valid, self_lim - key0 + 1) : valid;
+    // after the scores of a tile are complete: mask what this row may not see, take the column
+    // maximum, and move the reference maximum (rescaling the accumulators) only when needed.
+    // Register r of this lane is key 16*(r/8) + 8*hh + (r%8) of column n.
+    auto prep = [&](f32x16 &s, const Desc &d) {
+        const bool is_self = d.seg == self_seg;
+        if (d.valid < PC_TILE || (is_self && d.key0 + PC_TILE - 1 > wave_lim_lo)) {
+            const int lim = is_self ? min(d.valid, self_lim - d.key0 + 1) : d.valid;
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int key = 16 * (r >> 3) + 8 * hh + (r & 7);
@@ -445,51 +452,80 @@ __global__ __launch_bounds__(NW * 64) void pc_prefill_bf16_kernel(PcLaunch L)
 #pragma unroll
             for (int db = 0; db < 4; ++db) acc[db] *= alpha;
             m_ref = m_new;
-        }
-        const float neg_m = (m_ref == -INFINITY) ? 0.f : -m_ref;
-        float ps = 0.f;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) { s[r] = fast_exp2(fmaf(s[r], c_log2, neg_m)); ps += s[r]; }
-        l_run += ps;
-        bf16x8 pop[2];
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks)
-            pop[ks] = __builtin_bit_cast(bf16x8, make_uint4(pack_bf16(s[8 * ks], s[8 * ks + 1]), pack_bf16(s[8 * ks + 2], s[8 * ks + 3]),
-                                                           pack_bf16(s[8 * ks + 4], s[8 * ks + 5]), pack_bf16(s[8 * ks + 6], s[8 * ks + 7])));
-        const unsigned char *vr = &s_v[buf][(hh * PC_D + n) * 16];
-#pragma unroll
-        for (int db = 0; db < 4; ++db) {
-#pragma unroll
-            for (int ks = 0; ks < 2; ++ks) {
-                const bf16x8 va = *reinterpret_cast<const bf16x8 *>(vr + ((2 * ks) * PC_D + 32 * db) * 16);
-                acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pop[ks], acc[db], 0, 0, 0);
-            }
+            neg_m = (m_ref == -INFINITY) ? 0.f : -m_ref;
         }
     };
 
-    if (tile < tile_end) {
-        seek(tile);
-        int seg = e, key0 = (tile - sg.tile_off) * PC_TILE, valid = min(PC_TILE, sg.len - key0);
-        bool fresh = true;                         // the current tile opens a segment (for this workgroup)
-        g_load(sg.slot_start + key0, seg, true);
-        s_store(0, true);
+    if (T > 0) {
+        const int last = tile_end - 1;
+        Desc d0 = describe(tile0, -1);
+        Desc d1 = describe(min(tile0 + 1, last), d0.seg);
+        g_load_k(d0); g_load_v(d0);
+        s_store_k(0, true); s_store_v(0);
+        g_load_k(d1);
+        s_store_k(1, d1.fresh);
         __syncthreads();
-        int buf = 0;
-        while (tile < tile_end) {
-            const bool more = tile + 1 < tile_end;
-            int nseg = seg, nkey0 = 0, nvalid = 0;
-            if (more) {
-                seek(tile + 1);
-                nseg = e; nkey0 = (tile + 1 - sg.tile_off) * PC_TILE; nvalid = min(PC_TILE, sg.len - nkey0);
-                g_load(sg.slot_start + nkey0, nseg, nseg != seg);
+        turn_query(0);
+        f32x16 sc;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sc[r] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks)
+            sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8 *>(&s_k[0][k_lane_off + ks * 32]), qop[ks], sc, 0, 0, 0);
+        prep(sc, d0);
+
+        for (int i = 0; i < T; ++i) {
+            const Desc d2 = describe(min(tile0 + i + 2, last), d1.seg);
+            g_load_k(d2);
+            g_load_v(d1);
+            const int kbuf = (i + 1) & 1, vbuf = i & 1;
+            if (d1.fresh) turn_query(kbuf);
+
+            // ---- scores of tile i+1 (MFMA) overlapped with the exponentials of tile i (VALU)
+            const unsigned char *kr = &s_k[kbuf][k_lane_off];
+            const unsigned char *vr = &s_v[vbuf][v_lane_off];
+            f32x16 sn;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) sn[r] = 0.f;
+            float p[16];
+            float ps = 0.f;
+            uint32_t pw[8];
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) {
+                const bf16x8 ka = *reinterpret_cast<const bf16x8 *>(kr + ks * 32);
+                sn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qop[ks], sn, 0, 0, 0);
+                p[ks] = fast_exp2(fmaf(sc[ks], c_log2, neg_m));
+                ps += p[ks];
+                if (ks & 1) pw[ks >> 1] = pack_bf16(p[ks - 1], p[ks]);
             }
-            if (fresh) turn_query(buf);
-            compute(buf, seg == self_seg, key0, valid);
-            if (more) s_store(buf ^ 1, nseg != seg);
+            const bf16x8 pop0 = __builtin_bit_cast(bf16x8, make_uint4(pw[0], pw[1], pw[2], pw[3]));
+            // ---- first half of P.V overlapped with the second half of the exponentials
+#pragma unroll
+            for (int db = 0; db < 4; ++db) {
+                const bf16x8 va = *reinterpret_cast<const bf16x8 *>(vr + (32 * db) * 16);
+                acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pop0, acc[db], 0, 0, 0);
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    const int r = 8 + 2 * db + j;
+                    p[r] = fast_exp2(fmaf(sc[r], c_log2, neg_m));
+                    ps += p[r];
+                }
+                pw[4 + db] = pack_bf16(p[8 + 2 * db], p[9 + 2 * db]);
+            }
+            const bf16x8 pop1 = __builtin_bit_cast(bf16x8, make_uint4(pw[4], pw[5], pw[6], pw[7]));
+#pragma unroll
+            for (int db = 0; db < 4; ++db) {
+                const bf16x8 va = *reinterpret_cast<const bf16x8 *>(vr + (2 * PC_D + 32 * db) * 16);
+                acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pop1, acc[db], 0, 0, 0);
+            }
+            l_run += ps;
+
+            s_store_k(i & 1, d2.fresh);
+            s_store_v((i + 1) & 1);
             __syncthreads();
-            fresh = nseg != seg;
-            buf ^= 1; seg = nseg; key0 = nkey0; valid = nvalid;
-            ++tile;
+            if (i + 1 < T) prep(sn, d1);
+            sc = sn;
+            d0 = d1; d1 = d2;
         }
     }
 

@@ -1,0 +1,155 @@
+"""CPU-side tests of the C-ABI library: it loads, exports every symbol the header
+declares, and its host logic (allocator, validation, offset resolution) agrees with the
+oracle's statement of the same rules.  Uses host-only caches: no GPU call is made."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import choreo_oracle as orc
+from pc_inputs import POS_AUTO, Call, small_random
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def pc():
+    import paper_2512_23049_amd as m
+    if not os.path.exists(m.binding.LIB_PATH):
+        from paper_2512_23049_amd import build
+        build.build()
+    return m
+
+
+def host_cache(pc, **kw):
+    args = dict(n_q_heads=8, n_kv_heads=2, head_dim=128, dtype=pc.PC_BF16, rope_theta=1e4,
+                capacity_tokens=4096, max_messages=64, flags=pc.PC_FLAG_HOST_ONLY)
+    args.update(kw)
+    return pc.Cache(**args)
+
+
+def test_every_declared_symbol_is_exported(pc):
+    hdr = open(os.path.join(ROOT, "include", "pc.h")).read()
+    names = set(re.findall(r"\b(pc_[a-z_]+)\s*\(", hdr))
+    assert {"pc_cache_create", "pc_append_message", "pc_attend", "pc_build_tables"} <= names
+    lib = ctypes.CDLL(pc.binding.LIB_PATH)
+    for n in sorted(names):
+        assert hasattr(lib, n), n
+
+
+def test_header_constants_match_binding(pc):
+    hdr = open(os.path.join(ROOT, "include", "pc.h")).read()
+    assert int(re.search(r"#define PC_SLOT_ALIGN (\d+)", hdr).group(1)) == pc.PC_SLOT_ALIGN
+    for name in ("PC_ERR_INVALID_ARG", "PC_ERR_BAD_MSG_ID", "PC_ERR_NO_SPACE", "PC_ERR_SHAPE", "PC_ERR_HIP"):
+        assert int(re.search(r"#define %s\s+\((-\d+)\)" % name, hdr).group(1)) == getattr(pc, name)
+
+
+def test_ids_are_sequential_and_slots_follow_the_layout_rule(pc):
+    c = host_cache(pc)
+    lens = [3, 32, 33, 1, 64, 100]
+    reserves = [0, 0, 40, 70, 0, 0]
+    ids = [c.append_message(0, 0, L, r) for L, r in zip(lens, reserves)]
+    assert ids == list(range(len(lens)))
+    eff = [max(L, r) for L, r in zip(lens, reserves)]
+    exp = orc.slot_starts(eff, pc.PC_SLOT_ALIGN)
+    for i, (L, r) in enumerate(zip(lens, eff)):
+        assert c.message_info(i) == (L, exp[i], r)
+    n, used, cap = c.cache_info()
+    assert n == len(lens) and cap == 4096 and used % pc.PC_SLOT_ALIGN == 0 and used >= exp[-1] + 100
+
+
+def test_capacity_and_table_limits(pc):
+    c = host_cache(pc, capacity_tokens=100, max_messages=3)
+    _, _, cap = c.cache_info()
+    assert cap == 128                                     # rounded up to the slot alignment
+    c.append_message(0, 0, 64)
+    with pytest.raises(pc.PcError) as ei:
+        c.append_message(0, 0, 65)                        # slots [64, 129) > 128
+    assert ei.value.code == pc.PC_ERR_NO_SPACE
+    c.append_message(0, 0, 10)
+    c.append_message(0, 0, 10)
+    with pytest.raises(pc.PcError) as ei:
+        c.append_message(0, 0, 1)
+    assert ei.value.code == pc.PC_ERR_NO_SPACE
+    with pytest.raises(pc.PcError) as ei:
+        c.append_message(0, 0, 0)
+    assert ei.value.code == pc.PC_ERR_INVALID_ARG
+
+
+def test_bad_configurations_are_rejected(pc):
+    for kw in (dict(n_q_heads=6, n_kv_heads=4), dict(head_dim=96), dict(dtype=7), dict(capacity_tokens=0),
+               dict(max_messages=0), dict(rope_theta=0.0), dict(dtype=pc.PC_BF16, head_dim=64)):
+        with pytest.raises(pc.PcError):
+            host_cache(pc, **kw)
+    # the device path refuses to work without a GPU instead of falling back
+    import torch
+    if not torch.cuda.is_available():
+        with pytest.raises(pc.PcError) as ei:
+            pc.Cache(8, 2, 128, pc.PC_BF16, 1e4, 1024, 8)
+        assert ei.value.code == pc.PC_ERR_HIP
+
+
+def test_offset_resolution_matches_the_oracle_rule(pc):
+    rng = np.random.default_rng(0)
+    c = host_cache(pc)
+    lens = [int(x) for x in rng.integers(1, 90, size=12)]
+    for L in lens:
+        c.append_message(0, 0, L)
+    for trial in range(50):
+        n_sel = int(rng.integers(0, 7))
+        sel = [(int(rng.integers(0, 12)), POS_AUTO if rng.random() < 0.4 else int(rng.integers(-500, 500)))
+               for _ in range(n_sel)]
+        m_self = int(rng.integers(0, 12)) if rng.random() < 0.7 else -1
+        s_self = POS_AUTO if rng.random() < 0.5 else int(rng.integers(-500, 500))
+        call = Call(sel, m_self, s_self, 1, None)
+        starts, got_self, n_kv = c.resolve_call(call)
+        exp_sel, exp_self = orc.resolve_positions(sel, lens, s_self)
+        assert starts == [s for _, s in exp_sel]
+        assert got_self == exp_self
+        assert n_kv == sum(lens[m] for m, _ in sel) + (lens[m_self] if m_self >= 0 else 0)
+        assert c.build_tables(call, 0, 0, 0) == n_kv     # host-only: count only
+
+
+def test_call_validation(pc):
+    c = host_cache(pc, max_position=1000)
+    c.append_message(0, 0, 10)
+    c.append_message(0, 0, 20)
+    bad = [
+        (Call([(2, 0)], -1, 0, 1, None), pc.PC_ERR_BAD_MSG_ID),
+        (Call([(-1, 0)], -1, 0, 1, None), pc.PC_ERR_BAD_MSG_ID),
+        (Call([], 5, 0, 1, None), pc.PC_ERR_BAD_MSG_ID),
+        (Call([], -2, 0, 1, None), pc.PC_ERR_BAD_MSG_ID),
+        (Call([], 0, 0, 11, None), pc.PC_ERR_SHAPE),            # more rows than own tokens
+        (Call([], 0, 0, 0, None), pc.PC_ERR_INVALID_ARG),
+        (Call([(1, 990)], -1, 0, 1, None), pc.PC_ERR_INVALID_ARG),   # 990 + 19 > 1000
+        (Call([(1, -1001)], -1, 0, 1, None), pc.PC_ERR_INVALID_ARG),
+        (Call([], 0, 995, 1, None), pc.PC_ERR_INVALID_ARG),
+        (Call([], -1, 0, 1, np.array([1001], dtype=np.int32)), pc.PC_ERR_INVALID_ARG),
+    ]
+    for call, code in bad:
+        with pytest.raises(pc.PcError) as ei:
+            c.resolve_call(call)
+        assert ei.value.code == code, (call, ei.value)
+        with pytest.raises(pc.PcError) as ei:
+            c.attend([call], 0, 0)
+        assert ei.value.code == code
+    # legal corner cases: same message twice, new message also a parent, parent after the query
+    c.resolve_call(Call([(1, 0), (1, 0), (0, 900)], 0, 5, 10, None))
+    c.attend([Call([(1, 0)], 0, POS_AUTO, 3, None)], 0, 0)          # host-only: validates and plans only
+    c.attend([], 0, 0)
+
+
+def test_host_plan_accepts_the_generated_workloads(pc):
+    w = small_random(77, n_q_heads=8, n_kv_heads=2)
+    c = host_cache(pc)
+    for e in w.events:
+        if e.kind == "append":
+            c.append_message(0, 0, int(e.k.shape[0]), int(e.reserve))
+        else:
+            c.attend(e.calls, 0, 0)
+            lens, res = w.message_lengths(), w.message_reserves()
+            for call in e.calls:
+                slot, pos = orc.tables_for_call(call, lens, res, pc.PC_SLOT_ALIGN)
+                assert c.build_tables(call, 0, 0, 0) == slot.shape[0]
