@@ -6,7 +6,10 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpc.so")
-SOURCES = ["pc_lib.hip", "pc_kernels_basic.hip", "pc_kernels_mfma.hip"]
+SOURCES = ["pc_lib.hip", "pc_kernels_basic.hip", "pc_kernels_mfma.hip", "pc_kernels_prefill.hip"]
+# the prefill kernel never produces NaNs in its max reductions: let the compiler drop the
+# canonicalising v_max x, x in front of every fmax
+FILE_FLAGS = {"pc_kernels_prefill.hip": ["-fno-honor-nans"]}
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-result"]
@@ -19,7 +22,7 @@ def build(verbose: bool = False, extra=()):
     procs = []
     for s in SOURCES:
         o = os.path.join(CSRC, s.replace(".hip", ".o"))
-        cmd = [hipcc, *FLAGS, *extra, "-c", os.path.join(CSRC, s), "-o", o]
+        cmd = [hipcc, *FLAGS, *FILE_FLAGS.get(s, []), *extra, "-c", os.path.join(CSRC, s), "-o", o]
         if verbose:
             print(" ".join(cmd), flush=True)
         procs.append((cmd, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))

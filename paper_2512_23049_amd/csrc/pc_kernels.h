@@ -24,6 +24,6 @@ void pc_launch_attend_f32(const PcLaunch &L, const int32_t *row_call, int total_
 
 // bf16 MFMA kernels (D = 128)
 void pc_launch_decode_bf16(const PcLaunch &L, int n_items, hipStream_t st);
-void pc_launch_prefill_bf16(const PcLaunch &L, int n_items, int waves, hipStream_t st);
+void pc_launch_prefill_bf16(const PcLaunch &L, int n_items, hipStream_t st);
 
 #endif

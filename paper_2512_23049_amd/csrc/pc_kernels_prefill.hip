@@ -1,0 +1,457 @@
+// K3: bf16 MFMA prefill attention for gfx950.
+//
+// Work decomposition.  A row unit is 32 query rows of one query head; units of a (call, KV
+// head) are numbered head-fastest.  A workgroup is 8 waves = 8 consecutive units (two waves
+// per SIMD), so the heads that share a KV head sit in one workgroup and share every staged
+// K/V tile.
+//
+// Formulation (shared with the decode kernel): S^T = K~ . Q^T and O^T = V^T . P^T, so a query
+// row's softmax statistics live in one lane column and P goes from the first MFMA's
+// accumulators to the second MFMA's B operand without leaving registers.
+//
+// Vector-ALU diet.  On this chip the softmax costs about as many cycles as the MFMAs, so the
+// loop keeps it to the essentials: the softmax scale (times log2 e) is folded into the turned
+// queries; the running reference maximum enters as the C operand of the first score MFMA, so
+// the scores arrive already shifted and one v_exp per score is all that is left; the
+// reference only moves (and the accumulators are only rescaled) when a tile's maximum
+// exceeds it by more than 2^8.
+//
+// Overlap.  The two waves that share a SIMD run the same work in different rotations: waves
+// 0-3 do scores(i), softmax(i), P.V(i) in iteration i, waves 4-7 do P.V(i-1), scores(i),
+// softmax(i), so that one wave's softmax (vector ALU) runs beside the other's MFMAs.
+//
+// Staging.  K and V tiles go global -> LDS directly (global_load_lds, 16 bytes per lane, no
+// staging registers) into rings of 4 slots; K(i+3) and V(i+2) are requested at the top of
+// iteration i and only K(i+2), V(i+1) must have landed at its closing barrier.  A direct
+// load writes 1 KB of consecutive LDS per wave, so K rows cannot be padded; instead the 16-byte
+// chunks of row r are stored at chunk position (c ^ (r & 15)), which keeps the fragment reads
+// (16 rows x one logical chunk) free of bank conflicts.
+//
+// Position: keys are stored turned to their in-message index; per segment the queries are
+// turned by (q_pos - segment start) from an fp32 master copy, half in registers and half in
+// LDS (Sec. 2.4 "Position Updates", applied to the query side).  The kernel uses no
+// accumulation registers on purpose: with all 256 registers of a wave in one file the MFMA
+// results are read by the vector ALU without copies.
+#include "pc_mfma_common.h"
+
+#include <type_traits>
+
+#define TILE_BYTES 8192
+#define RING 4
+#define LAZY_LOG2 8.0f
+#define SEGWIN 512
+#define SB() __builtin_amdgcn_sched_barrier(0)
+#ifdef PC_EXP_NOMFMA
+__device__ __forceinline__ f32x16 fake_mfma(bf16x8 a, bf16x8 b, f32x16 c) { c[0] += (float)a[0] * (float)b[0]; return c; }
+#define MFMA32(a, b, c) fake_mfma(a, b, c)
+#else
+#define MFMA32(a, b, c) __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0)
+#endif
+
+#ifdef PC_EXP_NOEXP
+__device__ __forceinline__ float fast_exp2(float x) { return x; }
+#else
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+#endif
+
+__device__ __forceinline__ float max_across_halves(float x)
+{
+    // lanes l and l^32 hold the two halves of one column
+    auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float sum_across_halves(float x)
+{
+    auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+// one 16-byte-per-lane direct load: lane l's 16 bytes land at lds_wave_base + 16*l
+__device__ __forceinline__ void dma16(const void *gsrc, void *lds_wave_base)
+{
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)gsrc,
+                                     (__attribute__((address_space(3))) void *)lds_wave_base, 16, 0, 0);
+}
+
+template <int I> using IC = std::integral_constant<int, I>;
+
+__global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
+{
+    __shared__ __attribute__((aligned(1024))) unsigned char s_k[RING][TILE_BYTES];
+    __shared__ __attribute__((aligned(1024))) unsigned char s_v[RING][TILE_BYTES];
+    __shared__ __attribute__((aligned(1024))) float2 s_rot[RING][PC_D / 2];
+    __shared__ __attribute__((aligned(16))) float4 s_qm[8][8][64];    // upper half (dims 64..127) of the fp32 query master
+    __shared__ __attribute__((aligned(16))) PcSegment s_seg[SEGWIN];  // window of this call's segment list
+
+    const int kh = blockIdx.x % L.n_kv_heads;          // consecutive workgroups (one per XCD) take different KV heads
+    const PcItem item = L.items[blockIdx.x / L.n_kv_heads];
+    const PcCallDesc cd = L.calls[item.call];
+    const int g = L.n_q_heads / L.n_kv_heads;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int n = lane & 31, hh = lane >> 5;
+    const int n_units = ((cd.n_q + 31) >> 5) * g;
+    const int unit = item.unit0 + wave;
+    const bool unit_ok = unit < n_units;
+    const int ub = unit_ok ? unit / g : 0;               // 32-row block
+    const int uj = unit_ok ? unit - ub * g : 0;          // head within the group
+    const int h = kh * g + uj;
+    const int self_seg = cd.self_msg >= 0 ? cd.n_seg - 1 : -1;
+    const int tok0 = cd.self_len - cd.n_q;               // own token index of query row 0
+    const int last_unit = min(item.unit0 + 7, n_units - 1);
+    const int wg_lim = tok0 + min(32 * (last_unit / g) + 31, cd.n_q - 1);   // last own token any row here sees
+    const int row = 32 * ub + n;
+    const bool row_ok = unit_ok && row < cd.n_q;
+    const int Rg = cd.q_off + (row_ok ? row : 0);
+    const int self_lim = tok0 + row;                     // last own token this row sees
+    const int blk_lim_lo = tok0 + 32 * ub;               // ... the wave's first row sees
+
+    // query turned by its own position and scaled by softmax_scale * log2(e), fp32; element
+    // (ks, j) is dim 16*ks + 8*hh + j.  Lower half in registers, upper half in LDS (read back
+    // once per segment).
+    float qm[4][8];
+    {
+        const uint16_t *qp = (const uint16_t *)L.q + ((int64_t)Rg * L.n_q_heads + h) * PC_D + 8 * hh;
+        const float2 *rq = L.rot_q + (int64_t)Rg * (PC_D / 2) + 8 * hh;
+        const float sc = row_ok ? L.scale_log2 : 0.f;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            uint4 lo = ldg16(qp + 16 * ks), hi = ldg16(qp + 16 * ks + 64);
+            const uint32_t lw[4] = {lo.x, lo.y, lo.z, lo.w}, hw[4] = {hi.x, hi.y, hi.z, hi.w};
+            float yy[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const float x = ((j & 1) ? bf_hi(lw[j >> 1]) : bf_lo(lw[j >> 1])) * sc;
+                const float y = ((j & 1) ? bf_hi(hw[j >> 1]) : bf_lo(hw[j >> 1])) * sc;
+                const float2 cs = rq[16 * ks + j];
+                qm[ks][j] = x * cs.x - y * cs.y;
+                yy[j] = x * cs.y + y * cs.x;
+            }
+            s_qm[wave][2 * ks][lane] = make_float4(yy[0], yy[1], yy[2], yy[3]);
+            s_qm[wave][2 * ks + 1][lane] = make_float4(yy[4], yy[5], yy[6], yy[7]);
+        }
+    }
+
+    const unsigned char *kb = (const unsigned char *)L.k_store + (int64_t)kh * L.slots * PC_D * 2;
+    const unsigned char *vb = (const unsigned char *)L.v_store + (int64_t)kh * L.slots * PC_D * 2;
+
+    // tiles this workgroup walks: its split's range, cut at the causal limit of its last row
+    int tile_end = item.tile_end;
+    if (self_seg >= 0) {
+        const int self_tile_off = L.segs[cd.seg_off + self_seg].tile_off;
+        tile_end = min(tile_end, self_tile_off + (wg_lim + PC_TILE) / PC_TILE);
+    }
+    const int tile0 = item.tile_begin;
+    const int T = tile_end - tile0;
+
+    // softmax state of this lane's column.  Probabilities are 2^(score - m_ref) with scores in
+    // the log2 domain.  m_ref starts at 0 and moves only when it has to: when a tile's maximum
+    // exceeds it by more than 2^8, or when the first scores seen lie more than 2^8 below it.  For
+    // ordinary attention logits it never moves, and then no lane of the wave needs to shift its
+    // scores at all (`shifted` is false) and a score costs one v_exp, one add and half a convert.
+    float m_ref = 0.f, thr_lo = -LAZY_LOG2, l_run = 0.f;
+    bool shifted = false;                                // some lane of this wave has m_ref != 0
+    f32x16 acc[4];
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[db][r] = 0.f;
+
+    // segment cursor (uniform over the workgroup); tiles are described in non-decreasing order.
+    // The segment list is read through a window held in LDS: a global load inside the loop
+    // would make the compiler wait for every outstanding direct load at each tile.
+    int e = 0, seg_tiles_end = 0, seg_base = 0;
+    PcSegment sg = {0, 0, 0, 0};
+    struct Desc { int seg, key0, valid, slot0; bool fresh; };
+    auto load_window = [&](int first) {
+        for (int j = threadIdx.x; j < SEGWIN && first + j < cd.n_seg; j += 512) s_seg[j] = L.segs[cd.seg_off + first + j];
+        seg_base = first;
+    };
+    if (T > 0) {                                         // first segment of this work item
+        int lo = 0, hi = cd.n_seg - 1;
+        while (lo < hi) {
+            const int mid = (lo + hi + 1) >> 1;
+            if (L.segs[cd.seg_off + mid].tile_off <= tile0) lo = mid; else hi = mid - 1;
+        }
+        e = __builtin_amdgcn_readfirstlane(lo) - 1;      // describe() steps onto it
+        load_window(e + 1);
+        __syncthreads();
+    }
+    auto describe = [&](int t, int prev_seg) {
+        while (t >= seg_tiles_end) {
+            ++e;
+            if (e - seg_base >= SEGWIN) {                // uniform: every wave asks for the same tile here
+                __syncthreads();
+                load_window(e);
+                __syncthreads();
+            }
+            const int4 v = *reinterpret_cast<const int4 *>(&s_seg[e - seg_base]);
+            sg.slot_start = __builtin_amdgcn_readfirstlane(v.x);
+            sg.len = __builtin_amdgcn_readfirstlane(v.y);
+            sg.pos_start = __builtin_amdgcn_readfirstlane(v.z);
+            sg.tile_off = __builtin_amdgcn_readfirstlane(v.w);
+            seg_tiles_end = sg.tile_off + (sg.len + PC_TILE - 1) / PC_TILE;
+        }
+        Desc d;
+        d.seg = e; d.key0 = (t - sg.tile_off) * PC_TILE; d.valid = min(PC_TILE, sg.len - d.key0);
+        d.slot0 = sg.slot_start + d.key0; d.fresh = e != prev_seg;
+        return d;
+    };
+
+    // direct global -> LDS requests.  A tile is 512 16-byte chunks, one per thread.  Chunk
+    // position p of a K tile holds logical chunk (p & 15) ^ ((p >> 4) & 15) of row p >> 4.
+    const int k_src_off = (threadIdx.x >> 4) * 256 + (((threadIdx.x & 15) ^ ((threadIdx.x >> 4) & 15)) << 4);
+    auto dma_k = [&](const Desc &d, int slot) {         // the rotation table first: it must be the oldest request
+        if (d.fresh && threadIdx.x < 32)
+            dma16((const unsigned char *)(L.rot_seg + (int64_t)(cd.seg_off + d.seg) * (PC_D / 2)) + threadIdx.x * 16, &s_rot[slot][0]);
+        dma16(kb + (int64_t)d.slot0 * 256 + k_src_off, &s_k[slot][wave * 1024]);
+    };
+    auto dma_v = [&](const Desc &d, int slot) {
+        dma16(vb + (int64_t)d.slot0 * 256 + threadIdx.x * 16, &s_v[slot][wave * 1024]);
+    };
+
+    bf16x8 qop[8];
+    // K row read by this lane for MFMA row (lane & 31): rows are permuted so that the score
+    // registers 0..7 / 8..15 of a lane are keys 8*hh + 0..7 / 16 + 8*hh + 0..7
+    const int krow = 16 * (n >> 4) + 8 * ((n >> 2) & 1) + 4 * ((n >> 3) & 1) + (n & 3);
+    const unsigned char *k_rd[8];                        // fragment ks of ring slot 0
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) k_rd[ks] = &s_k[0][krow * 256 + (((2 * ks + hh) ^ (krow & 15)) << 4)];
+    const unsigned char *v_rd = &s_v[0][(hh * PC_D + n) * 16];
+
+    // turn the queries by -segment start (table in s_rot[slot]) into bf16 MFMA operands
+    auto turn_query = [&](int slot) {
+        const float4 *rs = reinterpret_cast<const float4 *>(&s_rot[slot][8 * hh]);
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            uint32_t lo[4], hi[4];
+#pragma unroll
+            for (int j4 = 0; j4 < 2; ++j4) {
+                const float4 c0 = rs[(16 * ks + 4 * j4) >> 1];          // (cos, sin) of pairs 4*j4, 4*j4+1
+                const float4 c1 = rs[((16 * ks + 4 * j4) >> 1) + 1];    // ... 4*j4+2, 4*j4+3
+                const float x0 = qm[ks][4 * j4], x1 = qm[ks][4 * j4 + 1], x2 = qm[ks][4 * j4 + 2], x3 = qm[ks][4 * j4 + 3];
+                const float4 yv = s_qm[wave][2 * ks + j4][lane];
+                const float y0 = yv.x, y1 = yv.y, y2 = yv.z, y3 = yv.w;
+                lo[2 * j4] = pack_bf16(x0 * c0.x + y0 * c0.y, x1 * c0.z + y1 * c0.w);
+                hi[2 * j4] = pack_bf16(y0 * c0.x - x0 * c0.y, y1 * c0.z - x1 * c0.w);
+                lo[2 * j4 + 1] = pack_bf16(x2 * c1.x + y2 * c1.y, x3 * c1.z + y3 * c1.w);
+                hi[2 * j4 + 1] = pack_bf16(y2 * c1.x - x2 * c1.y, y3 * c1.z - x3 * c1.w);
+            }
+            qop[ks] = __builtin_bit_cast(bf16x8, make_uint4(lo[0], lo[1], lo[2], lo[3]));
+            qop[ks + 4] = __builtin_bit_cast(bf16x8, make_uint4(hi[0], hi[1], hi[2], hi[3]));
+        }
+    };
+
+    // K / V fragments of ring slot `slot` as MFMA A operands.  One register set `fr` of 8
+    // fragments is recycled: as soon as an MFMA has consumed fr[j], the fragment the NEXT MFMA
+    // phase needs is requested into it, so LDS latency hides behind the current phase.
+    auto kfrag = [&](int slot, int ks) { return *reinterpret_cast<const bf16x8 *>(k_rd[ks] + slot * TILE_BYTES); };
+    // V fragment f: d block f & 3, key step f >> 2
+    auto vfrag = [&](int slot, int f) { return *reinterpret_cast<const bf16x8 *>(v_rd + slot * TILE_BYTES + (((f >> 2) * 2) * PC_D + 32 * (f & 3)) * 16); };
+    bf16x8 fr[8];
+    // scores (log2 domain) of the tile whose K fragments are in fr; refills fr with the V
+    // fragments of ring slot v_slot
+    auto scores = [&](int v_slot) {
+        f32x16 s;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s[r] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {
+            s = MFMA32(fr[ks], qop[ks], s);
+            fr[ks] = vfrag(v_slot, ks);
+        }
+        return s;
+    };
+    // mask what a row may not see (ragged tile end, causal limit in the new message), take the
+    // column maximum and re-base when needed.  Register r is key 16*(r/8) + 8*hh + (r%8).
+    auto prep = [&](f32x16 &s, const Desc &d) {
+        const bool is_self = d.seg == self_seg;
+        if (d.valid < PC_TILE || (is_self && d.key0 + PC_TILE - 1 > blk_lim_lo)) {
+            const int lim = is_self ? min(d.valid, self_lim - d.key0 + 1) : d.valid;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int key = 16 * (r >> 3) + 8 * hh + (r & 7);
+                s[r] = (key < lim) ? s[r] : -INFINITY;
+            }
+        }
+        if (shifted) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) s[r] -= m_ref;
+        }
+        float mx = __builtin_fmaxf(s[0], s[1]);
+#pragma unroll
+        for (int r = 2; r < 16; r += 2) mx = __builtin_fmaxf(mx, __builtin_fmaxf(s[r], s[r + 1]));
+        mx = max_across_halves(mx);                      // relative to m_ref
+        const bool seen = mx > -INFINITY;
+        const bool need = mx > LAZY_LOG2 || (seen && mx < thr_lo);
+        thr_lo = seen ? -INFINITY : thr_lo;
+        if (__builtin_amdgcn_ballot_w64(need) != 0) {
+            const float shift = need ? mx : 0.f;
+            const float alpha = fast_exp2(-shift);       // > 1 only while nothing has been accumulated
+            l_run *= alpha;
+#pragma unroll
+            for (int db = 0; db < 4; ++db) acc[db] *= alpha;
+            m_ref += shift;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) s[r] -= shift;
+            shifted = __builtin_amdgcn_ballot_w64(m_ref != 0.f) != 0;
+        }
+    };
+    // probabilities as bf16 MFMA operands (two key steps of 16), row sum accumulated
+    auto softmax = [&](const f32x16 &s, bf16x8 &p0, bf16x8 &p1) {
+        float e[16], ps = 0.f;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { e[r] = fast_exp2(s[r]); ps += e[r]; }
+        l_run += ps;
+        p0 = __builtin_bit_cast(bf16x8, make_uint4(pack_bf16(e[0], e[1]), pack_bf16(e[2], e[3]), pack_bf16(e[4], e[5]), pack_bf16(e[6], e[7])));
+        p1 = __builtin_bit_cast(bf16x8, make_uint4(pack_bf16(e[8], e[9]), pack_bf16(e[10], e[11]), pack_bf16(e[12], e[13]), pack_bf16(e[14], e[15])));
+    };
+    // O^T += V^T . P^T with the V fragments in fr; refills fr with the K fragments of k_slot
+    auto pv = [&](int k_slot, const bf16x8 &p0, const bf16x8 &p1) {
+#pragma unroll
+        for (int f = 0; f < 8; ++f) {
+            acc[f & 3] = MFMA32(fr[f], (f >> 2) ? p1 : p0, acc[f & 3]);
+            fr[f] = kfrag(k_slot, f);
+        }
+    };
+    auto pv_last = [&](const bf16x8 &p0, const bf16x8 &p1) {
+#pragma unroll
+        for (int f = 0; f < 8; ++f) acc[f & 3] = MFMA32(fr[f], (f >> 2) ? p1 : p0, acc[f & 3]);
+    };
+
+    if (T > 0) {
+        const int last = tile_end - 1;
+        Desc d0 = describe(tile0, -1);
+        Desc d1 = describe(min(tile0 + 1, last), d0.seg);
+        Desc d2 = describe(min(tile0 + 2, last), d1.seg);
+        dma_k(d0, 0); dma_v(d0, 0);
+        dma_k(d1, 1); dma_v(d1, 1);
+        dma_k(d2, 2);
+        __builtin_amdgcn_s_waitcnt(0x0F70);              // vmcnt(0)
+        __syncthreads();
+
+#ifdef PC_EXP_TIMING
+        long long tacc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+        long long tprev = clock64();
+#define TICK(k) { const long long tn = clock64(); tacc[k] += tn - tprev; tprev = tn; }
+#else
+#define TICK(k)
+#endif
+#pragma unroll
+        for (int f = 0; f < 8; ++f) fr[f] = kfrag(0, f);
+        bf16x8 p0, p1;                                   // probabilities carried to the next iteration (waves 4-7)
+        const bool late_pv = wave >= 4;                  // this wave multiplies P.V one iteration late
+        // one tile; u = i mod RING is a compile-time constant so that ring slots are immediates
+        auto iteration = [&](auto uc, int i) {
+            constexpr int u = decltype(uc)::value;
+            constexpr int s0 = u, s1 = (u + 1) % RING, s2 = (u + 2) % RING, s3 = (u + 3) % RING;
+            const Desc d3 = describe(min(tile0 + i + 3, last), d2.seg);
+#ifndef PC_EXP_NOLOAD
+            dma_k(d3, s3);
+            dma_v(d2, s2);
+#endif
+            TICK(0)
+            if (late_pv) {                               // fr holds V(i-1) fragments (K(0) fragments at i = 0)
+                if (i > 0) pv(s0, p0, p1);
+                TICK(1)
+#ifndef PC_EXP_NOTURN
+                if (d0.fresh) turn_query(s0);
+#endif
+                TICK(2)
+                f32x16 s = scores(s0);
+                TICK(3)
+#ifndef PC_EXP_NOSOFTMAX
+                prep(s, d0);
+                TICK(4)
+                softmax(s, p0, p1);
+#else
+                p0 = __builtin_bit_cast(bf16x8, make_uint4(__float_as_uint(s[0]), __float_as_uint(s[5]), 3, 4)); p1 = p0;
+#endif
+                TICK(5)
+            } else {                                     // fr holds K(i) fragments
+#ifndef PC_EXP_NOTURN
+                if (d0.fresh) turn_query(s0);
+#endif
+                TICK(2)
+                f32x16 s = scores(s0);
+                TICK(3)
+#ifndef PC_EXP_NOSOFTMAX
+                prep(s, d0);
+                TICK(4)
+                softmax(s, p0, p1);
+#else
+                p0 = __builtin_bit_cast(bf16x8, make_uint4(__float_as_uint(s[0]), __float_as_uint(s[5]), 3, 4)); p1 = p0;
+#endif
+                TICK(5)
+                pv(s1, p0, p1);
+                TICK(1)
+            }
+            // K(i+2), V(i+1) (requested one iteration ago) must have landed; this iteration's
+            // requests (K and V, preceded by at most one rotation table) may stay in flight
+            __builtin_amdgcn_s_waitcnt(0x0F72);          // vmcnt(2)
+            TICK(6)
+#ifndef PC_EXP_NOBARRIER
+            __syncthreads();
+#endif
+            TICK(7)
+            d0 = d1; d1 = d2; d2 = d3;
+        };
+        int i = 0;
+        for (; i < T; i += RING) {
+            iteration(IC<0>{}, i);
+            if (i + 1 >= T) { i += 1; break; }
+            iteration(IC<1>{}, i + 1);
+            if (i + 2 >= T) { i += 2; break; }
+            iteration(IC<2>{}, i + 2);
+            if (i + 3 >= T) { i += 3; break; }
+            iteration(IC<3>{}, i + 3);
+        }
+        __builtin_amdgcn_s_waitcnt(0x0F70);              // drain outstanding direct loads
+#ifdef PC_EXP_TIMING
+        if (blockIdx.x == 8 && lane == 0 && (wave == 0 || wave == 4))
+            printf("wave %d T=%d cycles/iter: dma+desc %lld pv %lld turn %lld scores %lld prep %lld softmax %lld vmwait %lld barrier %lld\n", wave, T,
+                   tacc[0] / T, tacc[1] / T, tacc[2] / T, tacc[3] / T, tacc[4] / T, tacc[5] / T, tacc[6] / T, tacc[7] / T);
+#endif
+        if (late_pv) pv_last(p0, p1);                    // the last tile's P.V (its V fragments are in fr)
+    }
+
+    // epilogue: a lane holds, for its row, dims 32*db + 8*(r/4) + 4*hh + (r%4)
+    const float l = sum_across_halves(l_run);
+    if (!row_ok) return;
+    if (cd.n_splits == 1) {
+        const float inv = l > 0.f ? 1.f / l : 0.f;
+        uint16_t *o = (uint16_t *)L.out + ((int64_t)Rg * L.n_q_heads + h) * PC_D;
+#pragma unroll
+        for (int db = 0; db < 4; ++db)
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) {
+                const int d = 32 * db + 8 * q4 + 4 * hh;
+                uint2 w;
+                w.x = pack_bf16(acc[db][4 * q4] * inv, acc[db][4 * q4 + 1] * inv);
+                w.y = pack_bf16(acc[db][4 * q4 + 2] * inv, acc[db][4 * q4 + 3] * inv);
+                *reinterpret_cast<uint2 *>(o + d) = w;
+            }
+        if (L.lse && hh == 0)
+            L.lse[(int64_t)Rg * L.n_q_heads + h] = (l > 0.f) ? (m_ref + log2f(l)) * 0.6931471805599453f : -INFINITY;
+    } else {
+        const int64_t pr = (int64_t)cd.part_off + (int64_t)item.split * cd.n_q + row;
+        float *o = L.part_o + (pr * L.n_q_heads + h) * PC_D;
+#pragma unroll
+        for (int db = 0; db < 4; ++db)
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) {
+                const int d = 32 * db + 8 * q4 + 4 * hh;
+                *reinterpret_cast<float4 *>(o + d) = make_float4(acc[db][4 * q4], acc[db][4 * q4 + 1], acc[db][4 * q4 + 2], acc[db][4 * q4 + 3]);
+            }
+        if (hh == 0) {
+            L.part_ml[(pr * L.n_q_heads + h) * 2] = (l > 0.f) ? m_ref : -INFINITY;
+            L.part_ml[(pr * L.n_q_heads + h) * 2 + 1] = l;
+        }
+    }
+}
+
+void pc_launch_prefill_bf16(const PcLaunch &L, int n_items, hipStream_t st)
+{
+    if (n_items <= 0) return;
+    dim3 grid((unsigned)n_items * L.n_kv_heads);
+    pc_prefill_bf16_kernel<<<grid, 512, 0, st>>>(L);
+}

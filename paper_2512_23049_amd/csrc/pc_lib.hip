@@ -413,8 +413,8 @@ static int32_t plan_and_stage(pc_cache *c, const pc_call *calls, int32_t n_calls
     }
     const int g = c->g, H_kv = c->cfg.n_kv_heads;
     const bool bf16 = c->cfg.dtype == PC_BF16;
-    // work-group shape of the prefill kernel: `waves` row units (32 rows x 1 q head) per group
-    P.pre_waves = (g >= 8) ? 8 : 4;
+    // work-group shape of the prefill kernel: 8 row units (32 rows x 1 q head each) per group
+    P.pre_waves = 8;
     std::vector<PcCallDesc> cds((size_t)n_calls);
     std::vector<PcItem> dec, pre;
     int64_t part_rows = 0;
@@ -448,7 +448,7 @@ static int32_t plan_and_stage(pc_cache *c, const pc_call *calls, int32_t n_calls
             const int groups = (units + P.pre_waves - 1) / P.pre_waves;
             int ns = 1;
             if (c->prefill_tiles_per_split > 0) ns = (T + c->prefill_tiles_per_split - 1) / c->prefill_tiles_per_split;
-            else if (pre_groups < 512) ns = (int)std::min<int64_t>((512 + pre_groups - 1) / pre_groups, std::max(1, T / 16));
+            else if (pre_groups < 256) ns = (int)std::min<int64_t>((256 + pre_groups - 1) / pre_groups, std::max(1, T / 16));
             ns = std::max(1, std::min(MAX_SPLITS, ns));
             const int chunk = std::max(1, (T + ns - 1) / ns);
             ns = std::max(1, (T + chunk - 1) / chunk);
@@ -531,7 +531,7 @@ int32_t pc_attend(pc_cache *c, const pc_call *calls, int32_t n_calls, const void
     if (P.n_pre > 0) {
         ProfScope ps(c, 2, st);
         L.items = (const PcItem *)(w + P.lay.items_pre);
-        pc_launch_prefill_bf16(L, P.n_pre, P.pre_waves, st);
+        pc_launch_prefill_bf16(L, P.n_pre, st);
         PC_HIP(c, hipGetLastError());
     }
     if (P.n_dec > 0) {
