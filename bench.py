@@ -170,7 +170,7 @@ def main():
                                "messages (%d keys) + causal 512-token new message; step = append new message + pc_attend"
                                % vp[0][1],
                    "flops_per_step": flops},
-        "roofline": {"bound": "mfma", "kernel": "pc_prefill_bf16_kernel<4>",
+        "roofline": {"bound": "mfma", "kernel": "pc_prefill_bf16_kernel",
                      "achieved": (flops / (k_pre * 1e-6) / 1e12) if k_pre else None, "peak": MFMA_BF16_PEAK_TFLOPS,
                      "unit": "TFLOP/s", "frac": (flops / (k_pre * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS) if k_pre else None,
                      "traffic": None, "avg_kernel_us": k_pre},

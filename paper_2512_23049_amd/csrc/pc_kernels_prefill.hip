@@ -21,8 +21,9 @@
 // softmax(i), so that one wave's softmax (vector ALU) runs beside the other's MFMAs.
 //
 // Staging.  K and V tiles go global -> LDS directly (global_load_lds, 16 bytes per lane, no
-// staging registers) into rings of 4 slots; K(i+3) and V(i+2) are requested at the top of
-// iteration i and only K(i+2), V(i+1) must have landed at its closing barrier.  A direct
+// staging registers) into rings of 5 slots; K(i+4) and V(i+3) are requested at the top of
+// iteration i and only K(i+2), V(i+1) must have landed at its closing barrier, so a request
+// has two to three iterations to complete.  A direct
 // load writes 1 KB of consecutive LDS per wave, so K rows cannot be padded; instead the 16-byte
 // chunks of row r are stored at chunk position (c ^ (r & 15)), which keeps the fragment reads
 // (16 rows x one logical chunk) free of bank conflicts.
@@ -37,7 +38,7 @@
 #include <type_traits>
 
 #define TILE_BYTES 8192
-#define RING 4
+#define RING 5
 #define LAZY_LOG2 8.0f
 #define SEGWIN 512
 #define SB() __builtin_amdgcn_sched_barrier(0)
@@ -244,9 +245,18 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
     // K / V fragments of ring slot `slot` as MFMA A operands.  One register set `fr` of 8
     // fragments is recycled: as soon as an MFMA has consumed fr[j], the fragment the NEXT MFMA
     // phase needs is requested into it, so LDS latency hides behind the current phase.
+#ifdef PC_EXP_NOFRAG
+    bf16x8 zfrag; for (int j = 0; j < 8; ++j) zfrag[j] = (__bf16)(float)(lane + j);
+    auto kfrag = [&](int slot, int ks) { return zfrag; };
+#else
     auto kfrag = [&](int slot, int ks) { return *reinterpret_cast<const bf16x8 *>(k_rd[ks] + slot * TILE_BYTES); };
+#endif
     // V fragment f: d block f & 3, key step f >> 2
+#ifdef PC_EXP_NOFRAG
+    auto vfrag = [&](int slot, int f) { return zfrag; };
+#else
     auto vfrag = [&](int slot, int f) { return *reinterpret_cast<const bf16x8 *>(v_rd + slot * TILE_BYTES + (((f >> 2) * 2) * PC_D + 32 * (f & 3)) * 16); };
+#endif
     bf16x8 fr[8];
     // scores (log2 domain) of the tile whose K fragments are in fr; refills fr with the V
     // fragments of ring slot v_slot
@@ -323,9 +333,11 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
         Desc d0 = describe(tile0, -1);
         Desc d1 = describe(min(tile0 + 1, last), d0.seg);
         Desc d2 = describe(min(tile0 + 2, last), d1.seg);
+        Desc d3 = describe(min(tile0 + 3, last), d2.seg);
         dma_k(d0, 0); dma_v(d0, 0);
         dma_k(d1, 1); dma_v(d1, 1);
-        dma_k(d2, 2);
+        dma_k(d2, 2); dma_v(d2, 2);
+        dma_k(d3, 3);
         __builtin_amdgcn_s_waitcnt(0x0F70);              // vmcnt(0)
         __syncthreads();
 
@@ -343,11 +355,11 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
         // one tile; u = i mod RING is a compile-time constant so that ring slots are immediates
         auto iteration = [&](auto uc, int i) {
             constexpr int u = decltype(uc)::value;
-            constexpr int s0 = u, s1 = (u + 1) % RING, s2 = (u + 2) % RING, s3 = (u + 3) % RING;
-            const Desc d3 = describe(min(tile0 + i + 3, last), d2.seg);
+            constexpr int s0 = u, s1 = (u + 1) % RING, s3 = (u + 3) % RING, s4 = (u + 4) % RING;
+            const Desc d4 = describe(min(tile0 + i + 4, last), d3.seg);
 #ifndef PC_EXP_NOLOAD
-            dma_k(d3, s3);
-            dma_v(d2, s2);
+            dma_k(d4, s4);
+            dma_v(d3, s3);
 #endif
             TICK(0)
             if (late_pv) {                               // fr holds V(i-1) fragments (K(0) fragments at i = 0)
@@ -385,15 +397,16 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
                 pv(s1, p0, p1);
                 TICK(1)
             }
-            // K(i+2), V(i+1) (requested one iteration ago) must have landed; this iteration's
-            // requests (K and V, preceded by at most one rotation table) may stay in flight
-            __builtin_amdgcn_s_waitcnt(0x0F72);          // vmcnt(2)
+            // K(i+2), V(i+1) (requested two iterations ago) must have landed; the requests of this
+            // and the previous iteration (K and V each, rotation tables issued before them) may
+            // stay in flight
+            __builtin_amdgcn_s_waitcnt(0x0F74);          // vmcnt(4)
             TICK(6)
 #ifndef PC_EXP_NOBARRIER
             __syncthreads();
 #endif
             TICK(7)
-            d0 = d1; d1 = d2; d2 = d3;
+            d0 = d1; d1 = d2; d2 = d3; d3 = d4;
         };
         int i = 0;
         for (; i < T; i += RING) {
@@ -404,6 +417,8 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
             iteration(IC<2>{}, i + 2);
             if (i + 3 >= T) { i += 3; break; }
             iteration(IC<3>{}, i + 3);
+            if (i + 4 >= T) { i += 4; break; }
+            iteration(IC<4>{}, i + 4);
         }
         __builtin_amdgcn_s_waitcnt(0x0F70);              // drain outstanding direct loads
 #ifdef PC_EXP_TIMING
