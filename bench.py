@@ -142,6 +142,9 @@ def main():
     ap.add_argument("--skip-extras", action="store_true")
     ap.add_argument("--skip-cpu", action="store_true")
     ap.add_argument("--only", default="", help="comma list of sections: prefill,decode,long,rounds")
+    ap.add_argument("--copy-probe-mib", type=int, default=0,
+                    help="also launch one plain device copy of this many MiB (reference for scaling rocprofv3 "
+                         "FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
@@ -154,6 +157,13 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs the MI355X"
     only = set(x for x in args.only.split(",") if x)
     bytes_per_token = None
+    if args.copy_probe_mib > 0:
+        src = torch.ones(args.copy_probe_mib << 18, dtype=torch.float32, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---------------------------------------------------------------- headline: prefill
     w2 = gen.single_prefill()
