@@ -28,7 +28,7 @@ struct PcCallDesc {
     int32_t self_len;         // tokens in the new message (0 if none)
     int32_t n_splits;         // KV splits of this call's work items
     int32_t part_off;         // first partial row (units of rows) when n_splits > 1
-    int32_t pad;
+    int32_t tile_off;         // first entry of this call in the tile table
 };
 
 // A gathered segment = one whole message placed at pos_start (built on device).
@@ -37,6 +37,16 @@ struct PcSegment {
     int32_t len;
     int32_t pos_start;
     int32_t tile_off;         // KV tiles of this call before this segment
+};
+
+// One 32-key KV tile of a call's gathered sequence (built on device from the segments).
+#define PC_TILE_FRESH 0x100   // first tile of its segment
+#define PC_TILE_SELF  0x200   // tile of the new message (causal limit applies)
+struct PcTile {
+    int32_t slot0;            // first physical slot of the tile (multiple of PC_TILE)
+    int32_t key0;             // in-message index of its first token
+    int32_t seg;              // segment index within the call
+    int32_t valid_flags;      // low byte: tokens that exist (1..32); PC_TILE_* flags above
 };
 
 // One workgroup's share of an attention launch.
@@ -56,6 +66,7 @@ struct PcLaunch {
     const float2     *rot_seg;    // [total_seg][D/2] (cos, sin)(pos_start * theta_i)
     const float2     *rot_q;      // [total_q][D/2]   (cos, sin)(q_pos * theta_i)
     const PcItem     *items;
+    const PcTile     *tiles;      // [total tiles] per-call tile tables
     const void       *k_store;    // [H_kv][slots][D]            K turned to its in-message index
     const void       *v_store;    // bf16: [H_kv][slots/8][D][8] ; f32: [H_kv][slots][D]
     const void       *q;          // [total_q][H_q][D]

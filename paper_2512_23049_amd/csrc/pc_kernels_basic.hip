@@ -149,7 +149,7 @@ __global__ __launch_bounds__(256) void pc_build_plan_kernel(
     const int32_t *__restrict__ q_pos, const PcMsgEntry *__restrict__ table,
     const double *__restrict__ inv_freq, int half, int total_seg, int total_q,
     PcSegment *__restrict__ segs, int32_t *__restrict__ seg_kvoff,
-    float2 *__restrict__ rot_seg, float2 *__restrict__ rot_q)
+    float2 *__restrict__ rot_seg, float2 *__restrict__ rot_q, PcTile *__restrict__ tiles)
 {
     __shared__ int s_len[256];
     __shared__ int s_tiles[256];
@@ -193,6 +193,26 @@ __global__ __launch_bounds__(256) void pc_build_plan_kernel(
             if (threadIdx.x == 255) { s_carry[0] = c_len + s_len[255]; s_carry[1] = c_tiles + s_tiles[255]; }
             __syncthreads();
         }
+        // tile table of this call: one entry per 32-key tile, in gathered order (the segment
+        // entries written above by this block are visible after the barrier)
+        const int n_tiles = s_carry[1];
+        const PcSegment *sg = segs + cd.seg_off;
+        for (int t = threadIdx.x; t < n_tiles; t += 256) {
+            int lo = 0, hi = cd.n_seg - 1;
+            while (lo < hi) {
+                const int mid = (lo + hi + 1) >> 1;
+                if (sg[mid].tile_off <= t) lo = mid; else hi = mid - 1;
+            }
+            const PcSegment g = sg[lo];
+            PcTile tl;
+            tl.key0 = (t - g.tile_off) * PC_TILE;
+            tl.slot0 = g.slot_start + tl.key0;
+            tl.seg = lo;
+            const int valid = g.len - tl.key0 < PC_TILE ? g.len - tl.key0 : PC_TILE;
+            tl.valid_flags = valid | (t == g.tile_off ? PC_TILE_FRESH : 0) |
+                             ((cd.self_msg >= 0 && lo == cd.n_seg - 1) ? PC_TILE_SELF : 0);
+            tiles[cd.tile_off + t] = tl;
+        }
         return;
     }
     // rotation tables: entity = segment (position from the staged lists) or query row
@@ -225,12 +245,12 @@ __global__ __launch_bounds__(256) void pc_build_plan_kernel(
 void pc_launch_build_plan(const PcCallDesc *calls, int n_calls, const int2 *sel, const int32_t *q_pos,
                           const PcMsgEntry *table, const double *inv_freq, int half, int total_seg,
                           int total_q, PcSegment *segs, int32_t *seg_kvoff, float2 *rot_seg,
-                          float2 *rot_q, hipStream_t st)
+                          float2 *rot_q, PcTile *tiles, hipStream_t st)
 {
     const int64_t n_rot = ((int64_t)total_seg + total_q) * half;
     const unsigned grid = (unsigned)(n_calls + (n_rot + 255) / 256);
     pc_build_plan_kernel<<<grid, 256, 0, st>>>(calls, n_calls, sel, q_pos, table, inv_freq, half, total_seg,
-                                               total_q, segs, seg_kvoff, rot_seg, rot_q);
+                                               total_q, segs, seg_kvoff, rot_seg, rot_q, tiles);
 }
 
 // ----------------------------------------------------------------------------------

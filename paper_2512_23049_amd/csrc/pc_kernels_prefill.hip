@@ -40,7 +40,6 @@
 #define TILE_BYTES 8192
 #define RING 5
 #define LAZY_LOG2 8.0f
-#define SEGWIN 512
 #define SB() __builtin_amdgcn_sched_barrier(0)
 #ifdef PC_EXP_NOMFMA
 __device__ __forceinline__ f32x16 fake_mfma(bf16x8 a, bf16x8 b, f32x16 c) { c[0] += (float)a[0] * (float)b[0]; return c; }
@@ -67,12 +66,18 @@ __device__ __forceinline__ float sum_across_halves(float x)
     return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
-// one 16-byte-per-lane direct load: lane l's 16 bytes land at lds_wave_base + 16*l
-__device__ __forceinline__ void dma16(const void *gsrc, void *lds_wave_base)
+// One 16-byte-per-lane direct load: lane l's 16 bytes land at lds_wave_base + 16*l.  Written
+// as assembly on purpose: the compiler then keeps no record of the LDS write, so it neither
+// drains every outstanding request (vmcnt(0)) in front of later LDS reads of the same array nor
+// at barriers; completion is awaited explicitly with s_waitcnt vmcnt(n) where the ring needs it.
+__device__ __forceinline__ void dma16(const void *gsrc, const void *lds_wave_base)
 {
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)gsrc,
-                                     (__attribute__((address_space(3))) void *)lds_wave_base, 16, 0, 0);
+    const unsigned base = __builtin_amdgcn_readfirstlane((unsigned)(size_t)lds_wave_base);
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(base), "v"(gsrc) : "memory", "m0");
 }
+// workgroup barrier without the fence __syncthreads() implies (which would wait for every
+// outstanding direct load); LDS accesses are not moved across it
+__device__ __forceinline__ void ring_barrier() { asm volatile("s_barrier" ::: "memory"); }
 
 template <int I> using IC = std::integral_constant<int, I>;
 
@@ -82,7 +87,6 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
     __shared__ __attribute__((aligned(1024))) unsigned char s_v[RING][TILE_BYTES];
     __shared__ __attribute__((aligned(1024))) float2 s_rot[RING][PC_D / 2];
     __shared__ __attribute__((aligned(16))) float4 s_qm[8][8][64];    // upper half (dims 64..127) of the fp32 query master
-    __shared__ __attribute__((aligned(16))) PcSegment s_seg[SEGWIN];  // window of this call's segment list
 
     const int kh = blockIdx.x % L.n_kv_heads;          // consecutive workgroups (one per XCD) take different KV heads
     const PcItem item = L.items[blockIdx.x / L.n_kv_heads];
@@ -157,44 +161,16 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[db][r] = 0.f;
 
-    // segment cursor (uniform over the workgroup); tiles are described in non-decreasing order.
-    // The segment list is read through a window held in LDS: a global load inside the loop
-    // would make the compiler wait for every outstanding direct load at each tile.
-    int e = 0, seg_tiles_end = 0, seg_base = 0;
-    PcSegment sg = {0, 0, 0, 0};
-    struct Desc { int seg, key0, valid, slot0; bool fresh; };
-    auto load_window = [&](int first) {
-        for (int j = threadIdx.x; j < SEGWIN && first + j < cd.n_seg; j += 512) s_seg[j] = L.segs[cd.seg_off + first + j];
-        seg_base = first;
-    };
-    if (T > 0) {                                         // first segment of this work item
-        int lo = 0, hi = cd.n_seg - 1;
-        while (lo < hi) {
-            const int mid = (lo + hi + 1) >> 1;
-            if (L.segs[cd.seg_off + mid].tile_off <= tile0) lo = mid; else hi = mid - 1;
-        }
-        e = __builtin_amdgcn_readfirstlane(lo) - 1;      // describe() steps onto it
-        load_window(e + 1);
-        __syncthreads();
-    }
-    auto describe = [&](int t, int prev_seg) {
-        while (t >= seg_tiles_end) {
-            ++e;
-            if (e - seg_base >= SEGWIN) {                // uniform: every wave asks for the same tile here
-                __syncthreads();
-                load_window(e);
-                __syncthreads();
-            }
-            const int4 v = *reinterpret_cast<const int4 *>(&s_seg[e - seg_base]);
-            sg.slot_start = __builtin_amdgcn_readfirstlane(v.x);
-            sg.len = __builtin_amdgcn_readfirstlane(v.y);
-            sg.pos_start = __builtin_amdgcn_readfirstlane(v.z);
-            sg.tile_off = __builtin_amdgcn_readfirstlane(v.w);
-            seg_tiles_end = sg.tile_off + (sg.len + PC_TILE - 1) / PC_TILE;
-        }
+    // tile descriptors come from the per-call tile table the plan builder wrote; they are
+    // fetched with scalar loads a few tiles ahead (uniform over the workgroup)
+    struct Desc { int seg, key0, valid, slot0; bool fresh, is_self; };
+    const PcTile *tile_tab = L.tiles + cd.tile_off;
+    auto describe = [&](int t) {
+        typedef int i32x4 __attribute__((ext_vector_type(4)));
+        const i32x4 v = *reinterpret_cast<const __attribute__((address_space(4))) i32x4 *>(reinterpret_cast<uintptr_t>(tile_tab + t));
         Desc d;
-        d.seg = e; d.key0 = (t - sg.tile_off) * PC_TILE; d.valid = min(PC_TILE, sg.len - d.key0);
-        d.slot0 = sg.slot_start + d.key0; d.fresh = e != prev_seg;
+        d.slot0 = v.x; d.key0 = v.y; d.seg = v.z; d.valid = v.w & 0xFF;
+        d.fresh = (v.w & PC_TILE_FRESH) != 0; d.is_self = (v.w & PC_TILE_SELF) != 0;
         return d;
     };
 
@@ -274,7 +250,7 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
     // mask what a row may not see (ragged tile end, causal limit in the new message), take the
     // column maximum and re-base when needed.  Register r is key 16*(r/8) + 8*hh + (r%8).
     auto prep = [&](f32x16 &s, const Desc &d) {
-        const bool is_self = d.seg == self_seg;
+        const bool is_self = d.is_self;
         if (d.valid < PC_TILE || (is_self && d.key0 + PC_TILE - 1 > blk_lim_lo)) {
             const int lim = is_self ? min(d.valid, self_lim - d.key0 + 1) : d.valid;
 #pragma unroll
@@ -330,10 +306,12 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
 
     if (T > 0) {
         const int last = tile_end - 1;
-        Desc d0 = describe(tile0, -1);
-        Desc d1 = describe(min(tile0 + 1, last), d0.seg);
-        Desc d2 = describe(min(tile0 + 2, last), d1.seg);
-        Desc d3 = describe(min(tile0 + 3, last), d2.seg);
+        Desc d0 = describe(tile0);
+        d0.fresh = true;                                 // a split may start in the middle of a segment
+        Desc d1 = describe(min(tile0 + 1, last));
+        Desc d2 = describe(min(tile0 + 2, last));
+        Desc d3 = describe(min(tile0 + 3, last));
+        Desc d4 = describe(min(tile0 + 4, last));
         dma_k(d0, 0); dma_v(d0, 0);
         dma_k(d1, 1); dma_v(d1, 1);
         dma_k(d2, 2); dma_v(d2, 2);
@@ -356,7 +334,7 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
         auto iteration = [&](auto uc, int i) {
             constexpr int u = decltype(uc)::value;
             constexpr int s0 = u, s1 = (u + 1) % RING, s3 = (u + 3) % RING, s4 = (u + 4) % RING;
-            const Desc d4 = describe(min(tile0 + i + 4, last), d3.seg);
+            const Desc d5 = describe(min(tile0 + i + 5, last));     // used one iteration from now
 #ifndef PC_EXP_NOLOAD
             dma_k(d4, s4);
             dma_v(d3, s3);
@@ -403,10 +381,10 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
             __builtin_amdgcn_s_waitcnt(0x0F74);          // vmcnt(4)
             TICK(6)
 #ifndef PC_EXP_NOBARRIER
-            __syncthreads();
+            ring_barrier();
 #endif
             TICK(7)
-            d0 = d1; d1 = d2; d2 = d3; d3 = d4;
+            d0 = d1; d1 = d2; d2 = d3; d3 = d4; d4 = d5;
         };
         int i = 0;
         for (; i < T; i += RING) {

@@ -198,11 +198,11 @@ int32_t stage_acquire(pc_cache *c, size_t bytes, StageSlot **out)
 // layout of the staged (host -> device) block and of the device-built block
 struct PlanLayout {
     size_t calls, sel, q_pos, row_call, merge_rows, items_dec, items_pre, h2d_bytes;
-    size_t segs, seg_kvoff, rot_seg, rot_q, part_o, part_ml, total;
+    size_t segs, seg_kvoff, rot_seg, rot_q, tiles, part_o, part_ml, total;
 };
 
 PlanLayout make_layout(int n_calls, int total_sel, int total_q, int total_seg, int n_dec, int n_pre,
-                       int64_t part_rows, int H_q, int D)
+                       int64_t part_rows, int64_t total_tiles, int H_q, int D)
 {
     PlanLayout L{};
     size_t o = 0;
@@ -219,6 +219,7 @@ PlanLayout make_layout(int n_calls, int total_sel, int total_q, int total_seg, i
     L.seg_kvoff = take(sizeof(int32_t) * (size_t)std::max(total_seg, 1));
     L.rot_seg = take(sizeof(float2) * (size_t)std::max(total_seg, 1) * (D / 2));
     L.rot_q = take(sizeof(float2) * (size_t)std::max(total_q, 1) * (D / 2));
+    L.tiles = take(sizeof(PcTile) * (size_t)std::max<int64_t>(total_tiles, 1));
     L.part_o = take(sizeof(float) * (size_t)std::max<int64_t>(part_rows, 1) * H_q * D);
     L.part_ml = take(sizeof(float) * (size_t)std::max<int64_t>(part_rows, 1) * H_q * 2);
     L.total = o;
@@ -417,7 +418,7 @@ static int32_t plan_and_stage(pc_cache *c, const pc_call *calls, int32_t n_calls
     P.pre_waves = 8;
     std::vector<PcCallDesc> cds((size_t)n_calls);
     std::vector<PcItem> dec, pre;
-    int64_t part_rows = 0;
+    int64_t part_rows = 0, total_tiles = 0;
     int sel_off = 0, q_off = 0, seg_off = 0;
     // first pass: how many prefill groups without splitting (to decide on KV splits)
     int64_t pre_groups = 0;
@@ -429,7 +430,8 @@ static int32_t plan_and_stage(pc_cache *c, const pc_call *calls, int32_t n_calls
         PcCallDesc &cd = cds[i];
         cd.sel_off = sel_off; cd.n_sel = (int)r.sel.size(); cd.self_msg = r.self_msg; cd.self_start = r.self_start;
         cd.n_q = r.n_q; cd.q_off = q_off; cd.seg_off = seg_off; cd.n_seg = cd.n_sel + (r.self_msg >= 0 ? 1 : 0);
-        cd.self_len = r.self_len; cd.n_splits = 1; cd.part_off = 0; cd.pad = 0;
+        cd.self_len = r.self_len; cd.n_splits = 1; cd.part_off = 0; cd.tile_off = (int32_t)total_tiles;
+        total_tiles += r.tiles;
         sel_off += cd.n_sel; q_off += cd.n_q; seg_off += cd.n_seg;
         if (!want_items || !bf16) continue;
         const int T = r.tiles;
@@ -463,7 +465,8 @@ static int32_t plan_and_stage(pc_cache *c, const pc_call *calls, int32_t n_calls
     }
     if (part_rows > INT32_MAX) return fail(c, PC_ERR_SHAPE, "attend: partial buffer too large");
     P.n_dec = (int)dec.size(); P.n_pre = (int)pre.size();
-    P.lay = make_layout(n_calls, P.total_sel, P.total_q, P.total_seg, P.n_dec, P.n_pre, part_rows, c->cfg.n_q_heads, c->D);
+    if (total_tiles > INT32_MAX / 2) return fail(c, PC_ERR_SHAPE, "attend: too many KV tiles");
+    P.lay = make_layout(n_calls, P.total_sel, P.total_q, P.total_seg, P.n_dec, P.n_pre, part_rows, total_tiles, c->cfg.n_q_heads, c->D);
     if (c->host_only) return PC_OK;
 
     int32_t rc = ensure_ws(c, P.lay.total, st);
@@ -494,7 +497,7 @@ static int32_t plan_and_stage(pc_cache *c, const pc_call *calls, int32_t n_calls
         pc_launch_build_plan((const PcCallDesc *)(w + P.lay.calls), n_calls, (const int2 *)(w + P.lay.sel),
                              (const int32_t *)(w + P.lay.q_pos), c->table_dev, c->inv_freq_dev, c->half, P.total_seg,
                              P.total_q, (PcSegment *)(w + P.lay.segs), (int32_t *)(w + P.lay.seg_kvoff),
-                             (float2 *)(w + P.lay.rot_seg), (float2 *)(w + P.lay.rot_q), st);
+                             (float2 *)(w + P.lay.rot_seg), (float2 *)(w + P.lay.rot_q), (PcTile *)(w + P.lay.tiles), st);
         PC_HIP(c, hipGetLastError());
     }
     return PC_OK;
@@ -517,6 +520,7 @@ int32_t pc_attend(pc_cache *c, const pc_call *calls, int32_t n_calls, const void
     L.segs = (const PcSegment *)(w + P.lay.segs);
     L.rot_seg = (const float2 *)(w + P.lay.rot_seg);
     L.rot_q = (const float2 *)(w + P.lay.rot_q);
+    L.tiles = (const PcTile *)(w + P.lay.tiles);
     L.k_store = c->k_store; L.v_store = c->v_store; L.q = q; L.out = out; L.lse = lse;
     L.part_o = (float *)(w + P.lay.part_o); L.part_ml = (float *)(w + P.lay.part_ml);
     L.slots = c->slots; L.n_q_heads = c->cfg.n_q_heads; L.n_kv_heads = c->cfg.n_kv_heads;
