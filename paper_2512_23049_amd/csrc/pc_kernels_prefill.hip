@@ -11,10 +11,11 @@
 //
 // Vector-ALU diet.  On this chip the softmax costs about as many cycles as the MFMAs, so the
 // loop keeps it to the essentials: the softmax scale (times log2 e) is folded into the turned
-// queries; the running reference maximum enters as the C operand of the first score MFMA, so
-// the scores arrive already shifted and one v_exp per score is all that is left; the
-// reference only moves (and the accumulators are only rescaled) when a tile's maximum
-// exceeds it by more than 2^8.
+// queries; probabilities are 2^(score - m_ref) with a reference m_ref that starts at 0 and only
+// moves (and the accumulators are only rescaled) when a tile's maximum exceeds it by more than
+// 2^8 or the first scores of a row lie more than 2^8 below it.  While no lane of a wave has
+// moved its reference the scores are not shifted at all, so a score costs one v_exp, one add
+// and half a convert.
 //
 // Overlap.  The two waves that share a SIMD run the same work in different rotations: waves
 // 0-3 do scores(i), softmax(i), P.V(i) in iteration i, waves 4-7 do P.V(i-1), scores(i),
@@ -23,10 +24,12 @@
 // Staging.  K and V tiles go global -> LDS directly (global_load_lds, 16 bytes per lane, no
 // staging registers) into rings of 5 slots; K(i+4) and V(i+3) are requested at the top of
 // iteration i and only K(i+2), V(i+1) must have landed at its closing barrier, so a request
-// has two to three iterations to complete.  A direct
-// load writes 1 KB of consecutive LDS per wave, so K rows cannot be padded; instead the 16-byte
-// chunks of row r are stored at chunk position (c ^ (r & 15)), which keeps the fragment reads
-// (16 rows x one logical chunk) free of bank conflicts.
+// has two to three iterations to complete.  A direct load writes 1 KB of consecutive LDS per
+// wave, so K rows cannot be padded; instead the 16-byte chunks of row r are stored at chunk
+// position (c ^ (r & 15)), which keeps the fragment reads (16 rows x one logical chunk) free
+// of bank conflicts.  Which tile comes next (physical slot, in-message index, segment, ragged
+// length) is read from the per-call tile table the plan builder wrote, with scalar loads
+// issued five tiles ahead.
 //
 // Position: keys are stored turned to their in-message index; per segment the queries are
 // turned by (q_pos - segment start) from an fp32 master copy, half in registers and half in
@@ -40,19 +43,9 @@
 #define TILE_BYTES 8192
 #define RING 5
 #define LAZY_LOG2 8.0f
-#define SB() __builtin_amdgcn_sched_barrier(0)
-#ifdef PC_EXP_NOMFMA
-__device__ __forceinline__ f32x16 fake_mfma(bf16x8 a, bf16x8 b, f32x16 c) { c[0] += (float)a[0] * (float)b[0]; return c; }
-#define MFMA32(a, b, c) fake_mfma(a, b, c)
-#else
 #define MFMA32(a, b, c) __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0)
-#endif
 
-#ifdef PC_EXP_NOEXP
-__device__ __forceinline__ float fast_exp2(float x) { return x; }
-#else
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
-#endif
 
 __device__ __forceinline__ float max_across_halves(float x)
 {
@@ -70,10 +63,10 @@ __device__ __forceinline__ float sum_across_halves(float x)
 // as assembly on purpose: the compiler then keeps no record of the LDS write, so it neither
 // drains every outstanding request (vmcnt(0)) in front of later LDS reads of the same array nor
 // at barriers; completion is awaited explicitly with s_waitcnt vmcnt(n) where the ring needs it.
-__device__ __forceinline__ void dma16(const void *gsrc, const void *lds_wave_base)
+__device__ __forceinline__ void dma16(const void *gbase_uniform, unsigned lane_off, unsigned lds_wave_base)
 {
-    const unsigned base = __builtin_amdgcn_readfirstlane((unsigned)(size_t)lds_wave_base);
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(base), "v"(gsrc) : "memory", "m0");
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 ::"s"(lds_wave_base), "v"(lane_off), "s"(gbase_uniform) : "memory", "m0");
 }
 // workgroup barrier without the fence __syncthreads() implies (which would wait for every
 // outstanding direct load); LDS accesses are not moved across it
@@ -165,34 +158,57 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
     // fetched with scalar loads a few tiles ahead (uniform over the workgroup)
     struct Desc { int seg, key0, valid, slot0; bool fresh, is_self; };
     const PcTile *tile_tab = L.tiles + cd.tile_off;
-    auto describe = [&](int t) {
-        typedef int i32x4 __attribute__((ext_vector_type(4)));
-        const i32x4 v = *reinterpret_cast<const __attribute__((address_space(4))) i32x4 *>(reinterpret_cast<uintptr_t>(tile_tab + t));
+    typedef int i32x4 __attribute__((ext_vector_type(4)));
+    auto decode = [&](const i32x4 &v) {
         Desc d;
         d.slot0 = v.x; d.key0 = v.y; d.seg = v.z; d.valid = v.w & 0xFF;
         d.fresh = (v.w & PC_TILE_FRESH) != 0; d.is_self = (v.w & PC_TILE_SELF) != 0;
         return d;
     };
+    auto describe = [&](int t) {
+        const i32x4 v = *reinterpret_cast<const __attribute__((address_space(4))) i32x4 *>(reinterpret_cast<uintptr_t>(tile_tab + t));
+        return decode(v);
+    };
+    // The same load in two halves, so that a whole iteration lies between request and use: the
+    // compiler would wait for the data right behind the load.  The request is invisible to the
+    // compiler's wait counting, which stays correct for its own LDS reads (an extra outstanding
+    // scalar load only makes those waits stricter); await_desc waits for everything.
+    auto request_desc = [&](int t) {
+        i32x4 v;
+        asm volatile("s_load_dwordx4 %0, %1, 0x0" : "=&s"(v) : "s"(tile_tab + t));
+        return v;
+    };
+    auto await_desc = [&](i32x4 &v) { asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(v)); };
 
     // direct global -> LDS requests.  A tile is 512 16-byte chunks, one per thread.  Chunk
     // position p of a K tile holds logical chunk (p & 15) ^ ((p >> 4) & 15) of row p >> 4.
-    const int k_src_off = (threadIdx.x >> 4) * 256 + (((threadIdx.x & 15) ^ ((threadIdx.x >> 4) & 15)) << 4);
+    const unsigned k_src_off = (threadIdx.x >> 4) * 256 + (((threadIdx.x & 15) ^ ((threadIdx.x >> 4) & 15)) << 4);
+    const unsigned v_src_off = threadIdx.x * 16;
+    const unsigned wave_lds = __builtin_amdgcn_readfirstlane(wave) * 1024;
+    const unsigned lds_k = (unsigned)(size_t)&s_k[0][0] + wave_lds, lds_v = (unsigned)(size_t)&s_v[0][0] + wave_lds;
+    const unsigned lds_rot = (unsigned)(size_t)&s_rot[0][0];
+    const unsigned char *rot_base = (const unsigned char *)(L.rot_seg + (int64_t)cd.seg_off * (PC_D / 2));
     auto dma_k = [&](const Desc &d, int slot) {         // the rotation table first: it must be the oldest request
         if (d.fresh && threadIdx.x < 32)
-            dma16((const unsigned char *)(L.rot_seg + (int64_t)(cd.seg_off + d.seg) * (PC_D / 2)) + threadIdx.x * 16, &s_rot[slot][0]);
-        dma16(kb + (int64_t)d.slot0 * 256 + k_src_off, &s_k[slot][wave * 1024]);
+            dma16(rot_base + (int64_t)d.seg * (PC_D / 2) * sizeof(float2), threadIdx.x * 16, lds_rot + slot * (unsigned)sizeof(s_rot[0]));
+        dma16(kb + (int64_t)d.slot0 * 256, k_src_off, lds_k + slot * TILE_BYTES);
     };
     auto dma_v = [&](const Desc &d, int slot) {
-        dma16(vb + (int64_t)d.slot0 * 256 + threadIdx.x * 16, &s_v[slot][wave * 1024]);
+        dma16(vb + (int64_t)d.slot0 * 256, v_src_off, lds_v + slot * TILE_BYTES);
     };
 
     bf16x8 qop[8];
     // K row read by this lane for MFMA row (lane & 31): rows are permuted so that the score
     // registers 0..7 / 8..15 of a lane are keys 8*hh + 0..7 / 16 + 8*hh + 0..7
     const int krow = 16 * (n >> 4) + 8 * ((n >> 2) & 1) + 4 * ((n >> 3) & 1) + (n & 3);
-    const unsigned char *k_rd[8];                        // fragment ks of ring slot 0
+    // LDS addresses of fragment ks in ring slot 0, kept as eight ready-made registers (the empty
+    // asm stops the compiler from re-deriving them with an add in front of every read)
+    unsigned k_rd[8];
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) k_rd[ks] = &s_k[0][krow * 256 + (((2 * ks + hh) ^ (krow & 15)) << 4)];
+    for (int ks = 0; ks < 8; ++ks) {
+        k_rd[ks] = (unsigned)(size_t)&s_k[0][krow * 256 + (((2 * ks + hh) ^ (krow & 15)) << 4)];
+        asm volatile("" : "+v"(k_rd[ks]));
+    }
     const unsigned char *v_rd = &s_v[0][(hh * PC_D + n) * 16];
 
     // turn the queries by -segment start (table in s_rot[slot]) into bf16 MFMA operands
@@ -221,22 +237,16 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
     // K / V fragments of ring slot `slot` as MFMA A operands.  One register set `fr` of 8
     // fragments is recycled: as soon as an MFMA has consumed fr[j], the fragment the NEXT MFMA
     // phase needs is requested into it, so LDS latency hides behind the current phase.
-#ifdef PC_EXP_NOFRAG
-    bf16x8 zfrag; for (int j = 0; j < 8; ++j) zfrag[j] = (__bf16)(float)(lane + j);
-    auto kfrag = [&](int slot, int ks) { return zfrag; };
-#else
-    auto kfrag = [&](int slot, int ks) { return *reinterpret_cast<const bf16x8 *>(k_rd[ks] + slot * TILE_BYTES); };
-#endif
+    typedef const __attribute__((address_space(3))) bf16x8 *lds_frag_ptr;
+    auto kfrag = [&](int slot, int ks) { return *(lds_frag_ptr)(k_rd[ks] + slot * TILE_BYTES); };
     // V fragment f: d block f & 3, key step f >> 2
-#ifdef PC_EXP_NOFRAG
-    auto vfrag = [&](int slot, int f) { return zfrag; };
-#else
     auto vfrag = [&](int slot, int f) { return *reinterpret_cast<const bf16x8 *>(v_rd + slot * TILE_BYTES + (((f >> 2) * 2) * PC_D + 32 * (f & 3)) * 16); };
-#endif
     bf16x8 fr[8];
     // scores (log2 domain) of the tile whose K fragments are in fr; refills fr with the V
     // fragments of ring slot v_slot
-    auto scores = [&](int v_slot) {
+    // `between` runs after the second MFMA has been issued (the direct loads of a later tile are
+    // requested there: spread over the iteration, they do not queue up behind each other)
+    auto scores = [&](int v_slot, auto between) {
         f32x16 s;
 #pragma unroll
         for (int r = 0; r < 16; ++r) s[r] = 0.f;
@@ -244,6 +254,18 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
         for (int ks = 0; ks < 8; ++ks) {
             s = MFMA32(fr[ks], qop[ks], s);
             fr[ks] = vfrag(v_slot, ks);
+            if (ks == 1) between();
+        }
+        return s;
+    };
+    auto scores_only = [&](auto between) {
+        f32x16 s;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s[r] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {
+            s = MFMA32(fr[ks], qop[ks], s);
+            if (ks == 1) between();
         }
         return s;
     };
@@ -292,12 +314,22 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
         p1 = __builtin_bit_cast(bf16x8, make_uint4(pack_bf16(e[8], e[9]), pack_bf16(e[10], e[11]), pack_bf16(e[12], e[13]), pack_bf16(e[14], e[15])));
     };
     // O^T += V^T . P^T with the V fragments in fr; refills fr with the K fragments of k_slot
-    auto pv = [&](int k_slot, const bf16x8 &p0, const bf16x8 &p1) {
+    auto pv = [&](int k_slot, const bf16x8 &p0, const bf16x8 &p1, auto between) {
 #pragma unroll
         for (int f = 0; f < 8; ++f) {
             acc[f & 3] = MFMA32(fr[f], (f >> 2) ? p1 : p0, acc[f & 3]);
             fr[f] = kfrag(k_slot, f);
+            if (f == 1) between();
         }
+    };
+    auto carry_p = [&](f32x16 &c, const bf16x8 &p0, const bf16x8 &p1) {
+        const uint4 a = __builtin_bit_cast(uint4, p0), b = __builtin_bit_cast(uint4, p1);
+        c[0] = __uint_as_float(a.x); c[1] = __uint_as_float(a.y); c[2] = __uint_as_float(a.z); c[3] = __uint_as_float(a.w);
+        c[4] = __uint_as_float(b.x); c[5] = __uint_as_float(b.y); c[6] = __uint_as_float(b.z); c[7] = __uint_as_float(b.w);
+    };
+    auto carried_p = [&](const f32x16 &c, bf16x8 &p0, bf16x8 &p1) {
+        p0 = __builtin_bit_cast(bf16x8, make_uint4(__float_as_uint(c[0]), __float_as_uint(c[1]), __float_as_uint(c[2]), __float_as_uint(c[3])));
+        p1 = __builtin_bit_cast(bf16x8, make_uint4(__float_as_uint(c[4]), __float_as_uint(c[5]), __float_as_uint(c[6]), __float_as_uint(c[7])));
     };
     auto pv_last = [&](const bf16x8 &p0, const bf16x8 &p1) {
 #pragma unroll
@@ -319,71 +351,56 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
         __builtin_amdgcn_s_waitcnt(0x0F70);              // vmcnt(0)
         __syncthreads();
 
-#ifdef PC_EXP_TIMING
-        long long tacc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-        long long tprev = clock64();
-#define TICK(k) { const long long tn = clock64(); tacc[k] += tn - tprev; tprev = tn; }
-#else
-#define TICK(k)
-#endif
 #pragma unroll
         for (int f = 0; f < 8; ++f) fr[f] = kfrag(0, f);
-        bf16x8 p0, p1;                                   // probabilities carried to the next iteration (waves 4-7)
-        const bool late_pv = wave >= 4;                  // this wave multiplies P.V one iteration late
+        // state carried to the next iteration: the raw scores of the next tile (waves 4-7) or,
+        // in its first 8 registers, the probabilities of this tile as MFMA operands (waves 0-3)
+        f32x16 sc;
+        const bool second = wave >= 4;                   // the wave of a SIMD that starts an iteration with its softmax
+        if (second) {
+            turn_query(0);
+            sc = scores_only([] {});
+        }
         // one tile; u = i mod RING is a compile-time constant so that ring slots are immediates
         auto iteration = [&](auto uc, int i) {
             constexpr int u = decltype(uc)::value;
             constexpr int s0 = u, s1 = (u + 1) % RING, s3 = (u + 3) % RING, s4 = (u + 4) % RING;
-            const Desc d5 = describe(min(tile0 + i + 5, last));     // used one iteration from now
-#ifndef PC_EXP_NOLOAD
-            dma_k(d4, s4);
-            dma_v(d3, s3);
-#endif
-            TICK(0)
-            if (late_pv) {                               // fr holds V(i-1) fragments (K(0) fragments at i = 0)
-                if (i > 0) pv(s0, p0, p1);
-                TICK(1)
-#ifndef PC_EXP_NOTURN
+            i32x4 raw5 = request_desc(min(tile0 + i + 5, last));     // first used two iterations from now
+            auto req_k = [&] { dma_k(d4, s4); };
+            auto req_v = [&] { dma_v(d3, s3); };
+            bf16x8 p0, p1;
+            if (second) {                                // softmax(i), P.V(i), scores(i+1)
+#pragma unroll
+                for (int f = 0; f < 8; ++f) fr[f] = vfrag(s0, f);
+                prep(sc, d0);
+                softmax(sc, p0, p1);
+                pv(s1, p0, p1, req_k);
+                if (i + 1 < T) {
+                    if (d1.fresh) turn_query(s1);
+                    sc = scores_only(req_v);
+                } else {
+                    req_v();
+                }
+            } else {                                     // P.V(i-1), scores(i), softmax(i)
+                if (i > 0) {
+                    carried_p(sc, p0, p1);
+                    pv(s0, p0, p1, req_k);
+                } else {
+                    req_k();
+                }
                 if (d0.fresh) turn_query(s0);
-#endif
-                TICK(2)
-                f32x16 s = scores(s0);
-                TICK(3)
-#ifndef PC_EXP_NOSOFTMAX
+                f32x16 s = scores(s0, req_v);
                 prep(s, d0);
-                TICK(4)
                 softmax(s, p0, p1);
-#else
-                p0 = __builtin_bit_cast(bf16x8, make_uint4(__float_as_uint(s[0]), __float_as_uint(s[5]), 3, 4)); p1 = p0;
-#endif
-                TICK(5)
-            } else {                                     // fr holds K(i) fragments
-#ifndef PC_EXP_NOTURN
-                if (d0.fresh) turn_query(s0);
-#endif
-                TICK(2)
-                f32x16 s = scores(s0);
-                TICK(3)
-#ifndef PC_EXP_NOSOFTMAX
-                prep(s, d0);
-                TICK(4)
-                softmax(s, p0, p1);
-#else
-                p0 = __builtin_bit_cast(bf16x8, make_uint4(__float_as_uint(s[0]), __float_as_uint(s[5]), 3, 4)); p1 = p0;
-#endif
-                TICK(5)
-                pv(s1, p0, p1);
-                TICK(1)
+                carry_p(sc, p0, p1);
             }
+            await_desc(raw5);
+            const Desc d5 = decode(raw5);
             // K(i+2), V(i+1) (requested two iterations ago) must have landed; the requests of this
             // and the previous iteration (K and V each, rotation tables issued before them) may
             // stay in flight
             __builtin_amdgcn_s_waitcnt(0x0F74);          // vmcnt(4)
-            TICK(6)
-#ifndef PC_EXP_NOBARRIER
             ring_barrier();
-#endif
-            TICK(7)
             d0 = d1; d1 = d2; d2 = d3; d3 = d4; d4 = d5;
         };
         int i = 0;
@@ -399,12 +416,12 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
             iteration(IC<4>{}, i + 4);
         }
         __builtin_amdgcn_s_waitcnt(0x0F70);              // drain outstanding direct loads
-#ifdef PC_EXP_TIMING
-        if (blockIdx.x == 8 && lane == 0 && (wave == 0 || wave == 4))
-            printf("wave %d T=%d cycles/iter: dma+desc %lld pv %lld turn %lld scores %lld prep %lld softmax %lld vmwait %lld barrier %lld\n", wave, T,
-                   tacc[0] / T, tacc[1] / T, tacc[2] / T, tacc[3] / T, tacc[4] / T, tacc[5] / T, tacc[6] / T, tacc[7] / T);
-#endif
-        if (late_pv) pv_last(p0, p1);                    // the last tile's P.V (its V fragments are in fr)
+        if (!second) {
+            bf16x8 p0, p1;
+            carried_p(sc, p0, p1);
+            pv_last(p0, p1);
+        }
+//                   // the last tile's P.V (its V fragments are in fr)
     }
 
     // epilogue: a lane holds, for its row, dims 32*db + 8*(r/4) + 4*hh + (r%4)
