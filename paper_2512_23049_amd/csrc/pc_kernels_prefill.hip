@@ -190,11 +190,11 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
     const unsigned char *rot_base = (const unsigned char *)(L.rot_seg + (int64_t)cd.seg_off * (PC_D / 2));
     auto dma_k = [&](const Desc &d, int slot) {         // the rotation table first: it must be the oldest request
         if (d.fresh && threadIdx.x < 32)
-            dma16(rot_base + (int64_t)d.seg * (PC_D / 2) * sizeof(float2), threadIdx.x * 16, lds_rot + slot * (unsigned)sizeof(s_rot[0]));
-        dma16(kb + (int64_t)d.slot0 * 256, k_src_off, lds_k + slot * TILE_BYTES);
+            dma16(rot_base + (int64_t)__builtin_amdgcn_readfirstlane(d.seg) * (PC_D / 2) * sizeof(float2), threadIdx.x * 16, lds_rot + slot * (unsigned)sizeof(s_rot[0]));
+        dma16(kb + (int64_t)__builtin_amdgcn_readfirstlane(d.slot0) * 256, k_src_off, lds_k + slot * TILE_BYTES);
     };
     auto dma_v = [&](const Desc &d, int slot) {
-        dma16(vb + (int64_t)d.slot0 * 256, v_src_off, lds_v + slot * TILE_BYTES);
+        dma16(vb + (int64_t)__builtin_amdgcn_readfirstlane(d.slot0) * 256, v_src_off, lds_v + slot * TILE_BYTES);
     };
 
     bf16x8 qop[8];
@@ -242,36 +242,12 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
     // V fragment f: d block f & 3, key step f >> 2
     auto vfrag = [&](int slot, int f) { return *reinterpret_cast<const bf16x8 *>(v_rd + slot * TILE_BYTES + (((f >> 2) * 2) * PC_D + 32 * (f & 3)) * 16); };
     bf16x8 fr[8];
-    // scores (log2 domain) of the tile whose K fragments are in fr; refills fr with the V
-    // fragments of ring slot v_slot
-    // `between` runs after the second MFMA has been issued (the direct loads of a later tile are
-    // requested there: spread over the iteration, they do not queue up behind each other)
-    auto scores = [&](int v_slot, auto between) {
-        f32x16 s;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) s[r] = 0.f;
-#pragma unroll
-        for (int ks = 0; ks < 8; ++ks) {
-            s = MFMA32(fr[ks], qop[ks], s);
-            fr[ks] = vfrag(v_slot, ks);
-            if (ks == 1) between();
-        }
-        return s;
-    };
-    auto scores_only = [&](auto between) {
-        f32x16 s;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) s[r] = 0.f;
-#pragma unroll
-        for (int ks = 0; ks < 8; ++ks) {
-            s = MFMA32(fr[ks], qop[ks], s);
-            if (ks == 1) between();
-        }
-        return s;
-    };
-    // mask what a row may not see (ragged tile end, causal limit in the new message), take the
-    // column maximum and re-base when needed.  Register r is key 16*(r/8) + 8*hh + (r%8).
-    auto prep = [&](f32x16 &s, const Desc &d) {
+
+    // ---- the softmax in two parts, each written to run in the shadow of eight MFMAs ----
+    // Part 1 of a tile: mask what a row may not see (ragged tile end, causal limit in the new
+    // message) and shift by the reference if some lane has moved it; both are rare and wave
+    // uniform.  Register r of the scores is key 16*(r/8) + 8*hh + (r%8).
+    auto mask_and_shift = [&](f32x16 &s, const Desc &d) {
         const bool is_self = d.is_self;
         if (d.valid < PC_TILE || (is_self && d.key0 + PC_TILE - 1 > blk_lim_lo)) {
             const int lim = is_self ? min(d.valid, self_lim - d.key0 + 1) : d.valid;
@@ -285,10 +261,9 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
 #pragma unroll
             for (int r = 0; r < 16; ++r) s[r] -= m_ref;
         }
-        float mx = __builtin_fmaxf(s[0], s[1]);
-#pragma unroll
-        for (int r = 2; r < 16; r += 2) mx = __builtin_fmaxf(mx, __builtin_fmaxf(s[r], s[r + 1]));
-        mx = max_across_halves(mx);                      // relative to m_ref
+    };
+    // ... then, given the column maximum mx (relative to m_ref), move the reference if needed
+    auto rebase = [&](f32x16 &s, float mx) {
         const bool seen = mx > -INFINITY;
         const bool need = mx > LAZY_LOG2 || (seen && mx < thr_lo);
         thr_lo = seen ? -INFINITY : thr_lo;
@@ -304,36 +279,62 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
             shifted = __builtin_amdgcn_ballot_w64(m_ref != 0.f) != 0;
         }
     };
-    // probabilities as bf16 MFMA operands (two key steps of 16), row sum accumulated
-    auto softmax = [&](const f32x16 &s, bf16x8 &p0, bf16x8 &p1) {
-        float e[16], ps = 0.f;
+    auto col_max = [&](const f32x16 &s) {
+        float mx = __builtin_fmaxf(s[0], s[1]);
 #pragma unroll
-        for (int r = 0; r < 16; ++r) { e[r] = fast_exp2(s[r]); ps += e[r]; }
-        l_run += ps;
-        p0 = __builtin_bit_cast(bf16x8, make_uint4(pack_bf16(e[0], e[1]), pack_bf16(e[2], e[3]), pack_bf16(e[4], e[5]), pack_bf16(e[6], e[7])));
-        p1 = __builtin_bit_cast(bf16x8, make_uint4(pack_bf16(e[8], e[9]), pack_bf16(e[10], e[11]), pack_bf16(e[12], e[13]), pack_bf16(e[14], e[15])));
+        for (int r = 2; r < 16; r += 2) mx = __builtin_fmaxf(mx, __builtin_fmaxf(s[r], s[r + 1]));
+        return max_across_halves(mx);
     };
-    // O^T += V^T . P^T with the V fragments in fr; refills fr with the K fragments of k_slot
-    auto pv = [&](int k_slot, const bf16x8 &p0, const bf16x8 &p1, auto between) {
+
+    // Phase A of an iteration: the scores of the NEXT tile (K fragments in fr, MFMA chain into a
+    // fresh accumulator) while the vector ALU turns the finished scores `s` of THIS tile into
+    // probabilities (one v_exp pair, two adds and one convert per MFMA).  Each consumed K
+    // fragment register is refilled with a V fragment of this tile (ring slot v_slot).
+    // `between` runs after the second MFMA: the direct loads of a later tile are requested there.
+    auto phase_a = [&](int v_slot, const f32x16 &s, bf16x8 &p0, bf16x8 &p1, auto between) {
+        f32x16 sn;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sn[r] = 0.f;
+        float ps = 0.f;
+        uint32_t pk[8];
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {
+            sn = MFMA32(fr[ks], qop[ks], sn);
+            fr[ks] = vfrag(v_slot, ks);
+            if (ks == 1) between();
+            const float e0 = fast_exp2(s[2 * ks]), e1 = fast_exp2(s[2 * ks + 1]);
+            ps += e0;
+            ps += e1;
+            pk[ks] = pack_bf16(e0, e1);
+            asm volatile("" : "+v"(pk[ks]), "+v"(ps));    // keeps this step's vector work from sinking below phase A
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);
+            __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);
+        }
+        l_run += ps;
+        p0 = __builtin_bit_cast(bf16x8, make_uint4(pk[0], pk[1], pk[2], pk[3]));
+        p1 = __builtin_bit_cast(bf16x8, make_uint4(pk[4], pk[5], pk[6], pk[7]));
+        return sn;
+    };
+    // Phase B: O^T += V^T . P^T of this tile (V fragments in fr, refilled with the K fragments
+    // of ring slot k_slot) while the vector ALU takes the column maximum of the next tile's
+    // scores sn; afterwards the reference moves if it has to (after the MFMAs: the accumulators
+    // they update are relative to the old reference).
+    auto phase_b = [&](int k_slot, const bf16x8 &p0, const bf16x8 &p1, f32x16 &sn, const Desc &dn, auto between) {
+        mask_and_shift(sn, dn);
+        float mx = 0.f;
 #pragma unroll
         for (int f = 0; f < 8; ++f) {
             acc[f & 3] = MFMA32(fr[f], (f >> 2) ? p1 : p0, acc[f & 3]);
             fr[f] = kfrag(k_slot, f);
             if (f == 1) between();
+            mx = f == 0 ? __builtin_fmaxf(sn[0], sn[1]) : __builtin_fmaxf(mx, __builtin_fmaxf(sn[2 * f], sn[2 * f + 1]));
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x002, 1, 0);
         }
-    };
-    auto carry_p = [&](f32x16 &c, const bf16x8 &p0, const bf16x8 &p1) {
-        const uint4 a = __builtin_bit_cast(uint4, p0), b = __builtin_bit_cast(uint4, p1);
-        c[0] = __uint_as_float(a.x); c[1] = __uint_as_float(a.y); c[2] = __uint_as_float(a.z); c[3] = __uint_as_float(a.w);
-        c[4] = __uint_as_float(b.x); c[5] = __uint_as_float(b.y); c[6] = __uint_as_float(b.z); c[7] = __uint_as_float(b.w);
-    };
-    auto carried_p = [&](const f32x16 &c, bf16x8 &p0, bf16x8 &p1) {
-        p0 = __builtin_bit_cast(bf16x8, make_uint4(__float_as_uint(c[0]), __float_as_uint(c[1]), __float_as_uint(c[2]), __float_as_uint(c[3])));
-        p1 = __builtin_bit_cast(bf16x8, make_uint4(__float_as_uint(c[4]), __float_as_uint(c[5]), __float_as_uint(c[6]), __float_as_uint(c[7])));
-    };
-    auto pv_last = [&](const bf16x8 &p0, const bf16x8 &p1) {
-#pragma unroll
-        for (int f = 0; f < 8; ++f) acc[f & 3] = MFMA32(fr[f], (f >> 2) ? p1 : p0, acc[f & 3]);
+        rebase(sn, max_across_halves(mx));
     };
 
     if (T > 0) {
@@ -344,84 +345,82 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
         Desc d2 = describe(min(tile0 + 2, last));
         Desc d3 = describe(min(tile0 + 3, last));
         Desc d4 = describe(min(tile0 + 4, last));
+        Desc d5 = describe(min(tile0 + 5, last));
         dma_k(d0, 0); dma_v(d0, 0);
         dma_k(d1, 1); dma_v(d1, 1);
         dma_k(d2, 2); dma_v(d2, 2);
-        dma_k(d3, 3);
+        dma_k(d3, 3); dma_v(d3, 3);
+        dma_k(d4, 4);
         __builtin_amdgcn_s_waitcnt(0x0F70);              // vmcnt(0)
         __syncthreads();
 
+        // tile 0: scores and softmax part 1, nothing to overlap with yet; leaves the K fragments
+        // of tile 1 in fr
 #pragma unroll
         for (int f = 0; f < 8; ++f) fr[f] = kfrag(0, f);
-        // state carried to the next iteration: the raw scores of the next tile (waves 4-7) or,
-        // in its first 8 registers, the probabilities of this tile as MFMA operands (waves 0-3)
-        f32x16 sc;
-        const bool second = wave >= 4;                   // the wave of a SIMD that starts an iteration with its softmax
-        if (second) {
-            turn_query(0);
-            sc = scores_only([] {});
+        turn_query(0);
+        f32x16 sc;                                       // scores of the current tile, part 1 done
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sc[r] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {
+            sc = MFMA32(fr[ks], qop[ks], sc);
+            fr[ks] = kfrag(1, ks);
         }
-        // one tile; u = i mod RING is a compile-time constant so that ring slots are immediates
+        mask_and_shift(sc, d0);
+        rebase(sc, col_max(sc));
+        // every wave has read tile 0's K before any wave overwrites its slot with tile 5's
+        __builtin_amdgcn_s_waitcnt(0xC07F);              // lgkmcnt(0)
+        ring_barrier();
+
+        // Iteration i (tiles i and i+1); u = i mod RING is a compile-time constant so that ring
+        // slots are immediates.  On entry: sc = scores of tile i (part 1 done), fr = K fragments
+        // of tile i+1, d1..d5 = descriptors of tiles i+1..i+5.  K(i+2) and V(i) are in LDS.
         auto iteration = [&](auto uc, int i) {
             constexpr int u = decltype(uc)::value;
-            constexpr int s0 = u, s1 = (u + 1) % RING, s3 = (u + 3) % RING, s4 = (u + 4) % RING;
-            i32x4 raw5 = request_desc(min(tile0 + i + 5, last));     // first used two iterations from now
-            auto req_k = [&] { dma_k(d4, s4); };
-            auto req_v = [&] { dma_v(d3, s3); };
+            constexpr int s0 = u, s1 = (u + 1) % RING, s2 = (u + 2) % RING, s4 = (u + 4) % RING;
+            i32x4 raw6 = request_desc(min(tile0 + i + 6, last));     // first used in the next iteration's requests
+            if (d1.fresh) turn_query(s1);
             bf16x8 p0, p1;
-            if (second) {                                // softmax(i), P.V(i), scores(i+1)
-#pragma unroll
-                for (int f = 0; f < 8; ++f) fr[f] = vfrag(s0, f);
-                prep(sc, d0);
-                softmax(sc, p0, p1);
-                pv(s1, p0, p1, req_k);
-                if (i + 1 < T) {
-                    if (d1.fresh) turn_query(s1);
-                    sc = scores_only(req_v);
-                } else {
-                    req_v();
-                }
-            } else {                                     // P.V(i-1), scores(i), softmax(i)
-                if (i > 0) {
-                    carried_p(sc, p0, p1);
-                    pv(s0, p0, p1, req_k);
-                } else {
-                    req_k();
-                }
-                if (d0.fresh) turn_query(s0);
-                f32x16 s = scores(s0, req_v);
-                prep(s, d0);
-                softmax(s, p0, p1);
-                carry_p(sc, p0, p1);
-            }
-            await_desc(raw5);
-            const Desc d5 = decode(raw5);
-            // K(i+2), V(i+1) (requested two iterations ago) must have landed; the requests of this
-            // and the previous iteration (K and V each, rotation tables issued before them) may
-            // stay in flight
+            f32x16 sn = phase_a(s0, sc, p0, p1, [&] { dma_k(d5, s0); });     // K(i+5) takes the slot of K(i)
+            phase_b(s2, p0, p1, sn, d1, [&] { dma_v(d4, s4); });             // V(i+4) takes the slot of V(i-1)
+            sc = sn;
+            await_desc(raw6);                            // also: every LDS read of this iteration has completed
+            const Desc d6 = decode(raw6);
+            // K(i+3), V(i+1) (requested two and three iterations ago) must have landed; the requests
+            // of this and the previous iteration (a K and a V each, rotation tables in front of
+            // their K) may stay in flight
             __builtin_amdgcn_s_waitcnt(0x0F74);          // vmcnt(4)
             ring_barrier();
-            d0 = d1; d1 = d2; d2 = d3; d3 = d4; d4 = d5;
+            d1 = d2; d2 = d3; d3 = d4; d4 = d5; d5 = d6;
         };
-        int i = 0;
-        for (; i < T; i += RING) {
+        const int n_it = T - 1;
+        for (int i = 0; i < n_it; i += RING) {
             iteration(IC<0>{}, i);
-            if (i + 1 >= T) { i += 1; break; }
+            if (i + 1 >= n_it) break;
             iteration(IC<1>{}, i + 1);
-            if (i + 2 >= T) { i += 2; break; }
+            if (i + 2 >= n_it) break;
             iteration(IC<2>{}, i + 2);
-            if (i + 3 >= T) { i += 3; break; }
+            if (i + 3 >= n_it) break;
             iteration(IC<3>{}, i + 3);
-            if (i + 4 >= T) { i += 4; break; }
+            if (i + 4 >= n_it) break;
             iteration(IC<4>{}, i + 4);
         }
         __builtin_amdgcn_s_waitcnt(0x0F70);              // drain outstanding direct loads
-        if (!second) {
-            bf16x8 p0, p1;
-            carried_p(sc, p0, p1);
-            pv_last(p0, p1);
+        // the last tile: softmax part 2 and P.V with nothing to overlap with
+        {
+            const unsigned char *vl = v_rd + ((T - 1) % RING) * TILE_BYTES;
+#pragma unroll
+            for (int f = 0; f < 8; ++f) fr[f] = *reinterpret_cast<const bf16x8 *>(vl + (((f >> 2) * 2) * PC_D + 32 * (f & 3)) * 16);
+            float e[16], ps = 0.f;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) { e[r] = fast_exp2(sc[r]); ps += e[r]; }
+            l_run += ps;
+            const bf16x8 p0 = __builtin_bit_cast(bf16x8, make_uint4(pack_bf16(e[0], e[1]), pack_bf16(e[2], e[3]), pack_bf16(e[4], e[5]), pack_bf16(e[6], e[7])));
+            const bf16x8 p1 = __builtin_bit_cast(bf16x8, make_uint4(pack_bf16(e[8], e[9]), pack_bf16(e[10], e[11]), pack_bf16(e[12], e[13]), pack_bf16(e[14], e[15])));
+#pragma unroll
+            for (int f = 0; f < 8; ++f) acc[f & 3] = MFMA32(fr[f], (f >> 2) ? p1 : p0, acc[f & 3]);
         }
-//                   // the last tile's P.V (its V fragments are in fr)
     }
 
     // epilogue: a lane holds, for its row, dims 32*db + 8*(r/4) + 4*hh + (r%4)
