@@ -212,7 +212,7 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
     const unsigned char *v_rd = &s_v[0][(hh * PC_D + n) * 16];
 
     // turn the queries by -segment start (table in s_rot[slot]) into bf16 MFMA operands
-    auto turn_query = [&](int slot) {
+    auto turn_query = [&](int slot) __attribute__((always_inline)) {
         const float4 *rs = reinterpret_cast<const float4 *>(&s_rot[slot][8 * hh]);
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
@@ -247,9 +247,9 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
     // Part 1 of a tile: mask what a row may not see (ragged tile end, causal limit in the new
     // message) and shift by the reference if some lane has moved it; both are rare and wave
     // uniform.  Register r of the scores is key 16*(r/8) + 8*hh + (r%8).
-    auto mask_and_shift = [&](f32x16 &s, const Desc &d) {
+    auto mask_and_shift = [&](f32x16 &s, const Desc &d) __attribute__((always_inline)) {
         const bool is_self = d.is_self;
-        if (d.valid < PC_TILE || (is_self && d.key0 + PC_TILE - 1 > blk_lim_lo)) {
+        if (__builtin_expect(d.valid < PC_TILE || (is_self && d.key0 + PC_TILE - 1 > blk_lim_lo), 0)) {
             const int lim = is_self ? min(d.valid, self_lim - d.key0 + 1) : d.valid;
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
@@ -257,17 +257,17 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
                 s[r] = (key < lim) ? s[r] : -INFINITY;
             }
         }
-        if (shifted) {
+        if (__builtin_expect(shifted, 0)) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) s[r] -= m_ref;
         }
     };
     // ... then, given the column maximum mx (relative to m_ref), move the reference if needed
-    auto rebase = [&](f32x16 &s, float mx) {
+    auto rebase = [&](f32x16 &s, float mx) __attribute__((always_inline)) {
         const bool seen = mx > -INFINITY;
         const bool need = mx > LAZY_LOG2 || (seen && mx < thr_lo);
         thr_lo = seen ? -INFINITY : thr_lo;
-        if (__builtin_amdgcn_ballot_w64(need) != 0) {
+        if (__builtin_expect(__builtin_amdgcn_ballot_w64(need) != 0, 0)) {
             const float shift = need ? mx : 0.f;
             const float alpha = fast_exp2(-shift);       // > 1 only while nothing has been accumulated
             l_run *= alpha;
@@ -380,7 +380,7 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
             constexpr int u = decltype(uc)::value;
             constexpr int s0 = u, s1 = (u + 1) % RING, s2 = (u + 2) % RING, s4 = (u + 4) % RING;
             i32x4 raw6 = request_desc(min(tile0 + i + 6, last));     // first used in the next iteration's requests
-            if (d1.fresh) turn_query(s1);
+            if (__builtin_expect(d1.fresh, 0)) turn_query(s1);
             bf16x8 p0, p1;
             f32x16 sn = phase_a(s0, sc, p0, p1, [&] { dma_k(d5, s0); });     // K(i+5) takes the slot of K(i)
             phase_b(s2, p0, p1, sn, d1, [&] { dma_v(d4, s4); });             // V(i+4) takes the slot of V(i-1)
