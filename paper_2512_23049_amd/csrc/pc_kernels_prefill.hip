@@ -101,7 +101,7 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
     const bool row_ok = unit_ok && row < cd.n_q;
     const int Rg = cd.q_off + (row_ok ? row : 0);
     const int self_lim = tok0 + row;                     // last own token this row sees
-    const int blk_lim_lo = tok0 + 32 * ub;               // ... the wave's first row sees
+    const int blk_lim_lo = __builtin_amdgcn_readfirstlane(tok0 + 32 * ub);   // ... the wave's first row sees (wave uniform)
 
     // query turned by its own position and scaled by softmax_scale * log2(e), fp32; element
     // (ks, j) is dim 16*ks + 8*hh + j.  Lower half in registers, upper half in LDS (read back
@@ -156,13 +156,20 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
 
     // tile descriptors come from the per-call tile table the plan builder wrote; they are
     // fetched with scalar loads a few tiles ahead (uniform over the workgroup)
-    struct Desc { int seg, key0, valid, slot0; bool fresh, is_self; };
+    struct Desc {                                        // as in the table: 4 scalar registers per tile
+        int slot0, key0, seg, flags;
+        // (read through readfirstlane: the values are wave uniform, which the compiler cannot
+        // see for the ones that arrive through request_desc)
+        __device__ int valid() const { return __builtin_amdgcn_readfirstlane(flags) & 0xFF; }
+        __device__ bool fresh() const { return (__builtin_amdgcn_readfirstlane(flags) & PC_TILE_FRESH) != 0; }
+        __device__ bool is_self() const { return (__builtin_amdgcn_readfirstlane(flags) & PC_TILE_SELF) != 0; }
+        __device__ int key() const { return __builtin_amdgcn_readfirstlane(key0); }
+    };
     const PcTile *tile_tab = L.tiles + cd.tile_off;
     typedef int i32x4 __attribute__((ext_vector_type(4)));
     auto decode = [&](const i32x4 &v) {
         Desc d;
-        d.slot0 = v.x; d.key0 = v.y; d.seg = v.z; d.valid = v.w & 0xFF;
-        d.fresh = (v.w & PC_TILE_FRESH) != 0; d.is_self = (v.w & PC_TILE_SELF) != 0;
+        d.slot0 = v.x; d.key0 = v.y; d.seg = v.z; d.flags = v.w;
         return d;
     };
     auto describe = [&](int t) {
@@ -189,7 +196,7 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
     const unsigned lds_rot = (unsigned)(size_t)&s_rot[0][0];
     const unsigned char *rot_base = (const unsigned char *)(L.rot_seg + (int64_t)cd.seg_off * (PC_D / 2));
     auto dma_k = [&](const Desc &d, int slot) {         // the rotation table first: it must be the oldest request
-        if (d.fresh && threadIdx.x < 32)
+        if (d.fresh() && threadIdx.x < 32)
             dma16(rot_base + (int64_t)__builtin_amdgcn_readfirstlane(d.seg) * (PC_D / 2) * sizeof(float2), threadIdx.x * 16, lds_rot + slot * (unsigned)sizeof(s_rot[0]));
         dma16(kb + (int64_t)__builtin_amdgcn_readfirstlane(d.slot0) * 256, k_src_off, lds_k + slot * TILE_BYTES);
     };
@@ -248,9 +255,9 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
     // message) and shift by the reference if some lane has moved it; both are rare and wave
     // uniform.  Register r of the scores is key 16*(r/8) + 8*hh + (r%8).
     auto mask_and_shift = [&](f32x16 &s, const Desc &d) __attribute__((always_inline)) {
-        const bool is_self = d.is_self;
-        if (__builtin_expect(d.valid < PC_TILE || (is_self && d.key0 + PC_TILE - 1 > blk_lim_lo), 0)) {
-            const int lim = is_self ? min(d.valid, self_lim - d.key0 + 1) : d.valid;
+        const bool is_self = d.is_self();
+        if (__builtin_expect(d.valid() < PC_TILE || (is_self && d.key() + PC_TILE - 1 > blk_lim_lo), 0)) {
+            const int lim = is_self ? min(d.valid(), self_lim - d.key() + 1) : d.valid();
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int key = 16 * (r >> 3) + 8 * hh + (r & 7);
@@ -262,12 +269,16 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
             for (int r = 0; r < 16; ++r) s[r] -= m_ref;
         }
     };
-    // ... then, given the column maximum mx (relative to m_ref), move the reference if needed
+    // ... then, given the column maximum mx (relative to m_ref), move the reference if needed.
+    // The test is three compares whose lane masks are combined on the scalar side.
     auto rebase = [&](f32x16 &s, float mx) __attribute__((always_inline)) {
+        const uint64_t above = __builtin_amdgcn_ballot_w64(mx > LAZY_LOG2);
+        const uint64_t below = __builtin_amdgcn_ballot_w64(mx < thr_lo);
         const bool seen = mx > -INFINITY;
-        const bool need = mx > LAZY_LOG2 || (seen && mx < thr_lo);
+        const uint64_t need_mask = above | (below & __builtin_amdgcn_ballot_w64(seen));
         thr_lo = seen ? -INFINITY : thr_lo;
-        if (__builtin_expect(__builtin_amdgcn_ballot_w64(need) != 0, 0)) {
+        if (__builtin_expect(need_mask != 0, 0)) {
+            const bool need = (need_mask >> lane) & 1;
             const float shift = need ? mx : 0.f;
             const float alpha = fast_exp2(-shift);       // > 1 only while nothing has been accumulated
             l_run *= alpha;
@@ -286,53 +297,81 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
         return max_across_halves(mx);
     };
 
-    // Phase A of an iteration: the scores of the NEXT tile (K fragments in fr, MFMA chain into a
-    // fresh accumulator) while the vector ALU turns the finished scores `s` of THIS tile into
-    // probabilities (one v_exp pair, two adds and one convert per MFMA).  Each consumed K
-    // fragment register is refilled with a V fragment of this tile (ring slot v_slot).
-    // `between` runs after the second MFMA: the direct loads of a later tile are requested there.
-    auto phase_a = [&](int v_slot, const f32x16 &s, bf16x8 &p0, bf16x8 &p1, auto between) {
+    // An iteration is two runs of eight MFMAs with the vector ALU work of the softmax placed in
+    // their shadow, a few instructions behind each MFMA (the sched_group_barrier calls pin that
+    // order).  e^x of score register r, added to the row sum; odd r completes a bf16 pair.
+    float ps;
+    uint32_t pk[8];
+    float ev[16];
+    auto expo = [&](const f32x16 &s, int r) __attribute__((always_inline)) {
+        ev[r] = fast_exp2(s[r]);
+        ps += ev[r];
+        if (r & 1) {
+            pk[r >> 1] = pack_bf16(ev[r - 1], ev[r]);
+            asm volatile("" : "+v"(pk[r >> 1]), "+v"(ps));    // keeps the vector work from sinking below its MFMA
+        }
+    };
+    // Phase A: the scores of the NEXT tile (K fragments in fr, one MFMA chain into a fresh
+    // accumulator) beside the first 12 exponentials of THIS tile's finished scores `s`.  Each
+    // consumed K fragment register is refilled with a V fragment of this tile (ring slot
+    // v_slot).  `between` runs after the second MFMA: the direct loads of a later tile are
+    // requested there, not all at one point of the iteration.
+    auto phase_a = [&](int v_slot, const f32x16 &s, auto between) __attribute__((always_inline)) {
         f32x16 sn;
 #pragma unroll
         for (int r = 0; r < 16; ++r) sn[r] = 0.f;
-        float ps = 0.f;
-        uint32_t pk[8];
+        ps = 0.f;
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) {
             sn = MFMA32(fr[ks], qop[ks], sn);
             fr[ks] = vfrag(v_slot, ks);
             if (ks == 1) between();
-            const float e0 = fast_exp2(s[2 * ks]), e1 = fast_exp2(s[2 * ks + 1]);
-            ps += e0;
-            ps += e1;
-            pk[ks] = pack_bf16(e0, e1);
-            asm volatile("" : "+v"(pk[ks]), "+v"(ps));    // keeps this step's vector work from sinking below phase A
+#pragma unroll
+            for (int r = (3 * ks) / 2; r < (3 * ks + 3) / 2; ++r) expo(s, r);
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);
-            __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);
+            if (ks & 1) {
+                __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);
+            } else {
+                __builtin_amdgcn_sched_group_barrier(0x400, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);
+            }
         }
-        l_run += ps;
-        p0 = __builtin_bit_cast(bf16x8, make_uint4(pk[0], pk[1], pk[2], pk[3]));
-        p1 = __builtin_bit_cast(bf16x8, make_uint4(pk[4], pk[5], pk[6], pk[7]));
         return sn;
     };
     // Phase B: O^T += V^T . P^T of this tile (V fragments in fr, refilled with the K fragments
-    // of ring slot k_slot) while the vector ALU takes the column maximum of the next tile's
-    // scores sn; afterwards the reference moves if it has to (after the MFMAs: the accumulators
-    // they update are relative to the old reference).
-    auto phase_b = [&](int k_slot, const bf16x8 &p0, const bf16x8 &p1, f32x16 &sn, const Desc &dn, auto between) {
+    // of ring slot k_slot).  Its first two MFMAs cover the last 4 exponentials (the second key
+    // step's probabilities are first needed by the fifth MFMA), the others the column maximum of
+    // the next tile's scores sn and the test whether the reference has to move.  It moves after
+    // the MFMAs: the accumulators they update are relative to the old reference.
+    auto phase_b = [&](int k_slot, const f32x16 &s, f32x16 &sn, const Desc &dn, auto between) __attribute__((always_inline)) {
         mask_and_shift(sn, dn);
+        const bf16x8 p0 = __builtin_bit_cast(bf16x8, make_uint4(pk[0], pk[1], pk[2], pk[3]));
         float mx = 0.f;
 #pragma unroll
-        for (int f = 0; f < 8; ++f) {
-            acc[f & 3] = MFMA32(fr[f], (f >> 2) ? p1 : p0, acc[f & 3]);
+        for (int f = 0; f < 4; ++f) {
+            acc[f] = MFMA32(fr[f], p0, acc[f]);
             fr[f] = kfrag(k_slot, f);
             if (f == 1) between();
-            mx = f == 0 ? __builtin_fmaxf(sn[0], sn[1]) : __builtin_fmaxf(mx, __builtin_fmaxf(sn[2 * f], sn[2 * f + 1]));
+            if (f < 2) { expo(s, 12 + 2 * f); expo(s, 13 + 2 * f); }
+            else mx = f == 2 ? __builtin_fmaxf(__builtin_fmaxf(sn[0], sn[1]), __builtin_fmaxf(sn[2], sn[3]))
+                             : __builtin_fmaxf(mx, __builtin_fmaxf(__builtin_fmaxf(sn[4], sn[5]), __builtin_fmaxf(sn[6], sn[7])));
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x002, 1, 0);
+            if (f < 2) __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);
+            __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);
+        }
+        l_run += ps;
+        const bf16x8 p1 = __builtin_bit_cast(bf16x8, make_uint4(pk[4], pk[5], pk[6], pk[7]));
+#pragma unroll
+        for (int f = 4; f < 8; ++f) {
+            acc[f & 3] = MFMA32(fr[f], p1, acc[f & 3]);
+            fr[f] = kfrag(k_slot, f);
+            if (f < 6) mx = __builtin_fmaxf(mx, __builtin_fmaxf(__builtin_fmaxf(sn[4 * f - 8], sn[4 * f - 7]), __builtin_fmaxf(sn[4 * f - 6], sn[4 * f - 5])));
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
         }
         rebase(sn, max_across_halves(mx));
     };
@@ -340,7 +379,7 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
     if (T > 0) {
         const int last = tile_end - 1;
         Desc d0 = describe(tile0);
-        d0.fresh = true;                                 // a split may start in the middle of a segment
+        d0.flags |= PC_TILE_FRESH;                                 // a split may start in the middle of a segment
         Desc d1 = describe(min(tile0 + 1, last));
         Desc d2 = describe(min(tile0 + 2, last));
         Desc d3 = describe(min(tile0 + 3, last));
@@ -380,16 +419,19 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
             constexpr int u = decltype(uc)::value;
             constexpr int s0 = u, s1 = (u + 1) % RING, s2 = (u + 2) % RING, s4 = (u + 4) % RING;
             i32x4 raw6 = request_desc(min(tile0 + i + 6, last));     // first used in the next iteration's requests
-            if (__builtin_expect(d1.fresh, 0)) turn_query(s1);
-            bf16x8 p0, p1;
-            f32x16 sn = phase_a(s0, sc, p0, p1, [&] { dma_k(d5, s0); });     // K(i+5) takes the slot of K(i)
-            phase_b(s2, p0, p1, sn, d1, [&] { dma_v(d4, s4); });             // V(i+4) takes the slot of V(i-1)
-            sc = sn;
-            await_desc(raw6);                            // also: every LDS read of this iteration has completed
+            if (__builtin_expect(d1.fresh(), 0)) turn_query(s1);
+            f32x16 sn = phase_a(s0, sc, [&] { dma_k(d5, s0); });             // K(i+5) takes the slot of K(i)
+            // the descriptor is awaited here, where the wait costs nothing: it waits for every LDS
+            // read too, and the V fragments requested during phase A arrived while its vector work
+            // finished
+            await_desc(raw6);
             const Desc d6 = decode(raw6);
+            phase_b(s2, sc, sn, d1, [&] { dma_v(d4, s4); });                 // V(i+4) takes the slot of V(i-1)
+            sc = sn;
             // K(i+3), V(i+1) (requested two and three iterations ago) must have landed; the requests
             // of this and the previous iteration (a K and a V each, rotation tables in front of
-            // their K) may stay in flight
+            // their K) may stay in flight.  The K fragment reads of phase B may still be in flight
+            // too: their slot is not written again before the barrier after next.
             __builtin_amdgcn_s_waitcnt(0x0F74);          // vmcnt(4)
             ring_barrier();
             d1 = d2; d2 = d3; d3 = d4; d4 = d5; d5 = d6;
