@@ -41,6 +41,19 @@ def visible_pairs(w, ev):
     return out
 
 
+def measured_traffic(kernel, workload):
+    """HBM bytes per launch (fetch + write) from the committed rocprofv3 counter summary, or None."""
+    path = os.path.join(ROOT, "profiles", "attention_kernels_hbm_traffic.txt")
+    try:
+        for ln in open(path):
+            f = ln.strip().split(",")
+            if len(f) >= 6 and f[0].startswith(kernel) and f[5] == workload:
+                return (float(f[3]) + float(f[4])) * 1e6
+    except OSError:
+        pass
+    return None
+
+
 def time_steps(fn, steps, warmup, torch):
     for _ in range(warmup):
         fn()
@@ -183,7 +196,7 @@ def main():
         "roofline": {"bound": "mfma", "kernel": "pc_prefill_bf16_kernel",
                      "achieved": (flops / (k_pre * 1e-6) / 1e12) if k_pre else None, "peak": MFMA_BF16_PEAK_TFLOPS,
                      "unit": "TFLOP/s", "frac": (flops / (k_pre * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS) if k_pre else None,
-                     "traffic": None, "avg_kernel_us": k_pre},
+                     "traffic": measured_traffic("pc_prefill_bf16_kernel", "single_prefill"), "avg_kernel_us": k_pre},
         "kernels_us": {k: v["avg_us"] for k, v in kern.items()},
         "ms_per_step_with_kernel_events": sec_prof * 1e3,
     }
@@ -216,7 +229,7 @@ def main():
             "roofline": {"bound": "hbm", "kernel": "pc_decode_bf16_kernel",
                          "achieved": (b_logical / (k_dec * 1e-6) / 1e9) if k_dec else None, "peak": HBM_PEAK_GBS,
                          "unit": "GB/s", "frac": (b_logical / (k_dec * 1e-6) / 1e9 / HBM_PEAK_GBS) if k_dec else None,
-                         "traffic": None, "avg_kernel_us": k_dec},
+                         "traffic": measured_traffic("pc_decode_bf16_kernel", "parallel_decode"), "avg_kernel_us": k_dec},
             "kernels_us": {k: v["avg_us"] for k, v in kern.items()},
         }
         if not args.skip_cpu:
