@@ -59,6 +59,14 @@ struct PcItem {
     int32_t pad[3];
 };
 
+// One output row whose KV splits the merge kernel combines (staged by the host).
+struct PcMergeRow {
+    int32_t row;              // packed query row
+    int32_t part_row0;        // partial row of split 0 (split s is n_q rows further)
+    int32_t n_splits;
+    int32_t n_q;
+};
+
 // Everything an attention kernel needs, passed by value.
 struct PcLaunch {
     const PcCallDesc *calls;
@@ -72,7 +80,7 @@ struct PcLaunch {
     const void       *q;          // [total_q][H_q][D]
     void             *out;        // [total_q][H_q][D]
     float            *lse;        // [total_q][H_q] or null
-    float            *part_o;     // [part rows][H_q][D]   un-normalised partial outputs
+    uint16_t         *part_o;     // [part rows][H_q][D]   partial outputs, each normalised by its own sum, fp16
     float            *part_ml;    // [part rows][H_q][2]   running max (scaled log2 domain), sum
     int64_t           slots;      // capacity in slots (stride between KV heads)
     int32_t           n_q_heads, n_kv_heads;

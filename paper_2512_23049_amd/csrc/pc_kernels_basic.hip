@@ -283,58 +283,67 @@ void pc_launch_expand_tables(const PcSegment *segs, const int32_t *seg_kvoff, in
 }
 
 // ----------------------------------------------------------------------------------
-// K5: merge of KV splits.  Each split s of a row holds an un-normalised output acc_s,
-// a running maximum m_s (scaled log2 domain) and a sum l_s; the result is
-//   m = max m_s,  l = sum l_s 2^(m_s - m),  O = sum acc_s 2^(m_s - m) / l
-// evaluated in split order (deterministic; no atomics).
+// K5: merge of KV splits.  Each split s of a row holds its own normalised output O_s
+// (fp16), a running maximum m_s (scaled log2 domain) and a sum l_s; the result is
+//   m = max m_s,  w_s = l_s 2^(m_s - m),  l = sum w_s,  O = sum w_s O_s / l
+// taken in split order (deterministic; no atomics), four splits at a time with the
+// running maximum carried from one group of four to the next.
+// One wave per (row, head), a lane owns two of the 128 dimensions.  The kernel is bound by
+// the latency of its dependent loads, so there are only two levels of them: the row's
+// descriptor, then the sums and outputs of four splits together.
 // ----------------------------------------------------------------------------------
-template <typename OutT, int D>
-__global__ __launch_bounds__(D) void pc_merge_kernel(
-    const PcCallDesc *__restrict__ calls, const int32_t *__restrict__ row_call,
-    const int32_t *__restrict__ merge_rows, const float *__restrict__ part_o,
-    const float *__restrict__ part_ml, OutT *__restrict__ out, float *__restrict__ lse, int n_q_heads)
+__global__ __launch_bounds__(256) void pc_merge_kernel(
+    const PcMergeRow *__restrict__ merge_rows, const uint16_t *__restrict__ part_o,
+    const float *__restrict__ part_ml, uint16_t *__restrict__ out, float *__restrict__ lse, int n_q_heads,
+    int n_pairs)
 {
-    const int R = merge_rows[blockIdx.x], h = blockIdx.y, d = threadIdx.x;
-    const PcCallDesc cd = calls[row_call[R]];
-    const int r = R - cd.q_off;
-    const int64_t pr0 = (int64_t)cd.part_off + r;
-    float m = -INFINITY;
-    for (int s = 0; s < cd.n_splits; ++s)
-        m = fmaxf(m, part_ml[((pr0 + (int64_t)s * cd.n_q) * n_q_heads + h) * 2]);
-    float l = 0.f, o = 0.f;
-    if (m > -INFINITY) {
-        for (int s = 0; s < cd.n_splits; ++s) {
-            const int64_t pr = pr0 + (int64_t)s * cd.n_q;
-            const float ms = part_ml[(pr * n_q_heads + h) * 2];
-            const float w = (ms > -INFINITY) ? exp2f(ms - m) : 0.f;
-            l += part_ml[(pr * n_q_heads + h) * 2 + 1] * w;
-            o += part_o[(pr * n_q_heads + h) * D + d] * w;
+    constexpr int D = 128;
+    const int pair = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+    if (pair >= n_pairs) return;
+    const int h = pair % n_q_heads;
+    const PcMergeRow mr = merge_rows[pair / n_q_heads];
+    float m = -INFINITY, l = 0.f, o0 = 0.f, o1 = 0.f;
+    for (int s0 = 0; s0 < mr.n_splits; s0 += 4) {
+        float2 ml[4];
+        uint32_t v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int s = min(s0 + u, mr.n_splits - 1);
+            const int64_t pr = (int64_t)mr.part_row0 + (int64_t)s * mr.n_q;
+            ml[u] = *reinterpret_cast<const float2 *>(part_ml + (pr * n_q_heads + h) * 2);
+            v[u] = *reinterpret_cast<const uint32_t *>(part_o + (pr * n_q_heads + h) * D + 2 * lane);
+        }
+        float m_new = m;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) m_new = fmaxf(m_new, ml[u].x);          // (a repeated last split changes nothing)
+        if (m_new == -INFINITY) continue;
+        const float keep = (m > -INFINITY) ? exp2f(m - m_new) : 0.f;
+        l *= keep; o0 *= keep; o1 *= keep;
+        m = m_new;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {                    // in split order
+            if (s0 + u >= mr.n_splits) break;
+            const float w = (ml[u].x > -INFINITY) ? ml[u].y * exp2f(ml[u].x - m) : 0.f;
+            l += w;
+            o0 += (float)__builtin_bit_cast(_Float16, (uint16_t)(v[u] & 0xFFFF)) * w;
+            o1 += (float)__builtin_bit_cast(_Float16, (uint16_t)(v[u] >> 16)) * w;
         }
     }
-    const float res = (l > 0.f) ? o / l : 0.f;
-    const int64_t oi = ((int64_t)R * n_q_heads + h) * D + d;
-    if constexpr (sizeof(OutT) == 2) {
-        __hip_bfloat16 b = __float2bfloat16(res);
-        out[oi] = *reinterpret_cast<uint16_t *>(&b);
-    } else {
-        out[oi] = res;
-    }
-    if (lse && d == 0)
-        lse[(int64_t)R * n_q_heads + h] = (l > 0.f) ? (m + log2f(l)) * 0.6931471805599453f : -INFINITY;
+    const float inv = (l > 0.f) ? 1.f / l : 0.f;
+    __hip_bfloat16 b0 = __float2bfloat16(o0 * inv), b1 = __float2bfloat16(o1 * inv);
+    const uint32_t packed = (uint32_t)*reinterpret_cast<uint16_t *>(&b0) | ((uint32_t)*reinterpret_cast<uint16_t *>(&b1) << 16);
+    *reinterpret_cast<uint32_t *>(out + ((int64_t)mr.row * n_q_heads + h) * D + 2 * lane) = packed;
+    if (lse && lane == 0)
+        lse[(int64_t)mr.row * n_q_heads + h] = (l > 0.f) ? (m + log2f(l)) * 0.6931471805599453f : -INFINITY;
 }
 
-void pc_launch_merge(int dtype, const PcCallDesc *calls, const int32_t *row_call, const int32_t *merge_rows,
-                     int n_merge_rows, const float *part_o, const float *part_ml, void *out, float *lse,
-                     int n_q_heads, int D, hipStream_t st)
+// only bf16 caches with D = 128 split their work (the fp32 kernel never does)
+void pc_launch_merge(int dtype, const PcMergeRow *merge_rows, int n_merge_rows, const uint16_t *part_o,
+                     const float *part_ml, void *out, float *lse, int n_q_heads, int D, hipStream_t st)
 {
-    if (n_merge_rows <= 0) return;
-    dim3 grid(n_merge_rows, n_q_heads);
-    if (dtype == 1 && D == 128)
-        pc_merge_kernel<uint16_t, 128><<<grid, 128, 0, st>>>(calls, row_call, merge_rows, part_o, part_ml, (uint16_t *)out, lse, n_q_heads);
-    else if (dtype == 0 && D == 128)
-        pc_merge_kernel<float, 128><<<grid, 128, 0, st>>>(calls, row_call, merge_rows, part_o, part_ml, (float *)out, lse, n_q_heads);
-    else
-        pc_merge_kernel<float, 64><<<grid, 64, 0, st>>>(calls, row_call, merge_rows, part_o, part_ml, (float *)out, lse, n_q_heads);
+    if (n_merge_rows <= 0 || dtype != 1 || D != 128) return;
+    const int n_pairs = n_merge_rows * n_q_heads;
+    pc_merge_kernel<<<(n_pairs + 3) / 4, 256, 0, st>>>(merge_rows, part_o, part_ml, (uint16_t *)out, lse, n_q_heads, n_pairs);
 }
 
 // ----------------------------------------------------------------------------------

@@ -221,7 +221,7 @@ __global__ __launch_bounds__(256) void pc_decode_bf16_kernel(PcLaunch L)
             if (L.lse && d == 0) L.lse[Rr * L.n_q_heads + hq] = (l > 0.f) ? (mm + log2f(l)) * 0.6931471805599453f : -INFINITY;
         } else {
             const int64_t pr = (int64_t)cd.part_off + (int64_t)item.split * cd.n_q + r;
-            L.part_o[(pr * L.n_q_heads + hq) * PC_D + d] = o;
+            L.part_o[(pr * L.n_q_heads + hq) * PC_D + d] = to_f16(l > 0.f ? o / l : 0.f);
             if (d == 0) { L.part_ml[(pr * L.n_q_heads + hq) * 2] = mm; L.part_ml[(pr * L.n_q_heads + hq) * 2 + 1] = l; }
         }
     }

@@ -485,13 +485,17 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
             L.lse[(int64_t)Rg * L.n_q_heads + h] = (l > 0.f) ? (m_ref + log2f(l)) * 0.6931471805599453f : -INFINITY;
     } else {
         const int64_t pr = (int64_t)cd.part_off + (int64_t)item.split * cd.n_q + row;
-        float *o = L.part_o + (pr * L.n_q_heads + h) * PC_D;
+        uint16_t *o = L.part_o + (pr * L.n_q_heads + h) * PC_D;
+        const float inv = l > 0.f ? 1.f / l : 0.f;
 #pragma unroll
         for (int db = 0; db < 4; ++db)
 #pragma unroll
             for (int q4 = 0; q4 < 4; ++q4) {
                 const int d = 32 * db + 8 * q4 + 4 * hh;
-                *reinterpret_cast<float4 *>(o + d) = make_float4(acc[db][4 * q4], acc[db][4 * q4 + 1], acc[db][4 * q4 + 2], acc[db][4 * q4 + 3]);
+                uint2 w;
+                w.x = pack_f16(acc[db][4 * q4] * inv, acc[db][4 * q4 + 1] * inv);
+                w.y = pack_f16(acc[db][4 * q4 + 2] * inv, acc[db][4 * q4 + 3] * inv);
+                *reinterpret_cast<uint2 *>(o + d) = w;
             }
         if (hh == 0) {
             L.part_ml[(pr * L.n_q_heads + h) * 2] = (l > 0.f) ? m_ref : -INFINITY;

@@ -211,7 +211,7 @@ PlanLayout make_layout(int n_calls, int total_sel, int total_q, int total_seg, i
     L.sel = take(sizeof(int2) * (size_t)std::max(total_sel, 1));
     L.q_pos = take(sizeof(int32_t) * (size_t)std::max(total_q, 1));
     L.row_call = take(sizeof(int32_t) * (size_t)std::max(total_q, 1));
-    L.merge_rows = take(sizeof(int32_t) * (size_t)std::max(total_q, 1));
+    L.merge_rows = take(sizeof(PcMergeRow) * (size_t)std::max(total_q, 1));
     L.items_dec = take(sizeof(PcItem) * (size_t)std::max(n_dec, 1));
     L.items_pre = take(sizeof(PcItem) * (size_t)std::max(n_pre, 1));
     L.h2d_bytes = o;
@@ -220,7 +220,7 @@ PlanLayout make_layout(int n_calls, int total_sel, int total_q, int total_seg, i
     L.rot_seg = take(sizeof(float2) * (size_t)std::max(total_seg, 1) * (D / 2));
     L.rot_q = take(sizeof(float2) * (size_t)std::max(total_q, 1) * (D / 2));
     L.tiles = take(sizeof(PcTile) * (size_t)std::max<int64_t>(total_tiles, 1));
-    L.part_o = take(sizeof(float) * (size_t)std::max<int64_t>(part_rows, 1) * H_q * D);
+    L.part_o = take(sizeof(uint16_t) * (size_t)std::max<int64_t>(part_rows, 1) * H_q * D);
     L.part_ml = take(sizeof(float) * (size_t)std::max<int64_t>(part_rows, 1) * H_q * 2);
     L.total = o;
     return L;
@@ -477,14 +477,15 @@ static int32_t plan_and_stage(pc_cache *c, const pc_call *calls, int32_t n_calls
     char *h = (char *)slot->host;
     std::memcpy(h + P.lay.calls, cds.data(), sizeof(PcCallDesc) * cds.size());
     int2 *hs = (int2 *)(h + P.lay.sel);
-    int32_t *hq = (int32_t *)(h + P.lay.q_pos), *hr = (int32_t *)(h + P.lay.row_call), *hm = (int32_t *)(h + P.lay.merge_rows);
+    int32_t *hq = (int32_t *)(h + P.lay.q_pos), *hr = (int32_t *)(h + P.lay.row_call);
+    PcMergeRow *hm = (PcMergeRow *)(h + P.lay.merge_rows);
     for (int i = 0; i < n_calls; ++i) {
         const Resolved &r = P.res[i];
         if (!r.sel.empty()) std::memcpy(hs + cds[i].sel_off, r.sel.data(), sizeof(int2) * r.sel.size());
         std::memcpy(hq + cds[i].q_off, r.q_pos.data(), sizeof(int32_t) * r.q_pos.size());
         for (int q = 0; q < r.n_q; ++q) hr[cds[i].q_off + q] = i;
         if (cds[i].n_splits > 1)
-            for (int q = 0; q < r.n_q; ++q) hm[P.n_merge_rows++] = cds[i].q_off + q;
+            for (int q = 0; q < r.n_q; ++q) hm[P.n_merge_rows++] = PcMergeRow{cds[i].q_off + q, cds[i].part_off + q, cds[i].n_splits, r.n_q};
     }
     if (!dec.empty()) std::memcpy(h + P.lay.items_dec, dec.data(), sizeof(PcItem) * dec.size());
     if (!pre.empty()) std::memcpy(h + P.lay.items_pre, pre.data(), sizeof(PcItem) * pre.size());
@@ -522,7 +523,7 @@ int32_t pc_attend(pc_cache *c, const pc_call *calls, int32_t n_calls, const void
     L.rot_q = (const float2 *)(w + P.lay.rot_q);
     L.tiles = (const PcTile *)(w + P.lay.tiles);
     L.k_store = c->k_store; L.v_store = c->v_store; L.q = q; L.out = out; L.lse = lse;
-    L.part_o = (float *)(w + P.lay.part_o); L.part_ml = (float *)(w + P.lay.part_ml);
+    L.part_o = (uint16_t *)(w + P.lay.part_o); L.part_ml = (float *)(w + P.lay.part_ml);
     L.slots = c->slots; L.n_q_heads = c->cfg.n_q_heads; L.n_kv_heads = c->cfg.n_kv_heads;
     L.scale_log2 = c->scale * 1.4426950408889634f;
     const int32_t *row_call = (const int32_t *)(w + P.lay.row_call);
@@ -546,8 +547,8 @@ int32_t pc_attend(pc_cache *c, const pc_call *calls, int32_t n_calls, const void
     }
     if (P.n_merge_rows > 0) {
         ProfScope ps(c, 4, st);
-        pc_launch_merge(c->cfg.dtype, L.calls, row_call, (const int32_t *)(w + P.lay.merge_rows), P.n_merge_rows, L.part_o,
-                        L.part_ml, out, lse, c->cfg.n_q_heads, c->D, st);
+        pc_launch_merge(c->cfg.dtype, (const PcMergeRow *)(w + P.lay.merge_rows), P.n_merge_rows, L.part_o, L.part_ml, out, lse,
+                        c->cfg.n_q_heads, c->D, st);
         PC_HIP(c, hipGetLastError());
     }
     return PC_OK;
