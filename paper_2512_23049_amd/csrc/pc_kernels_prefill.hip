@@ -47,6 +47,7 @@
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+__device__ __forceinline__ float max3(float a, float b, float c) { return __builtin_fmaxf(__builtin_fmaxf(a, b), c); }
 __device__ __forceinline__ float max_across_halves(float x)
 {
     // lanes l and l^32 hold the two halves of one column
@@ -105,9 +106,9 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
 
     // query turned by its own position and scaled by softmax_scale * log2(e), fp32; element
     // (ks, j) is dim 16*ks + 8*hh + j.  Lower half in registers, upper half in LDS (read back
-    // once per segment).
+    // once per segment).  Filled while the first tiles are on their way.
     float qm[4][8];
-    {
+    auto load_query = [&]() __attribute__((always_inline)) {
         const uint16_t *qp = (const uint16_t *)L.q + ((int64_t)Rg * L.n_q_heads + h) * PC_D + 8 * hh;
         const float2 *rq = L.rot_q + (int64_t)Rg * (PC_D / 2) + 8 * hh;
         const float sc = row_ok ? L.scale_log2 : 0.f;
@@ -127,7 +128,7 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
             s_qm[wave][2 * ks][lane] = make_float4(yy[0], yy[1], yy[2], yy[3]);
             s_qm[wave][2 * ks + 1][lane] = make_float4(yy[4], yy[5], yy[6], yy[7]);
         }
-    }
+    };
 
     const unsigned char *kb = (const unsigned char *)L.k_store + (int64_t)kh * L.slots * PC_D * 2;
     const unsigned char *vb = (const unsigned char *)L.v_store + (int64_t)kh * L.slots * PC_D * 2;
@@ -355,8 +356,8 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
             fr[f] = kfrag(k_slot, f);
             if (f == 1) between();
             if (f < 2) { expo(s, 12 + 2 * f); expo(s, 13 + 2 * f); }
-            else mx = f == 2 ? __builtin_fmaxf(__builtin_fmaxf(sn[0], sn[1]), __builtin_fmaxf(sn[2], sn[3]))
-                             : __builtin_fmaxf(mx, __builtin_fmaxf(__builtin_fmaxf(sn[4], sn[5]), __builtin_fmaxf(sn[6], sn[7])));
+            else if (f == 2) mx = max3(max3(sn[0], sn[1], sn[2]), sn[3], sn[4]);     // three-input maxima: 8 for 16 scores
+            else mx = max3(max3(mx, sn[5], sn[6]), sn[7], sn[8]);
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
             if (f < 2) __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);
@@ -368,7 +369,8 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
         for (int f = 4; f < 8; ++f) {
             acc[f & 3] = MFMA32(fr[f], p1, acc[f & 3]);
             fr[f] = kfrag(k_slot, f);
-            if (f < 6) mx = __builtin_fmaxf(mx, __builtin_fmaxf(__builtin_fmaxf(sn[4 * f - 8], sn[4 * f - 7]), __builtin_fmaxf(sn[4 * f - 6], sn[4 * f - 5])));
+            if (f == 4) mx = max3(max3(mx, sn[9], sn[10]), sn[11], sn[12]);
+            if (f == 5) mx = max3(max3(mx, sn[13], sn[14]), sn[15], sn[15]);
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
             __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
@@ -390,6 +392,7 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
         dma_k(d2, 2); dma_v(d2, 2);
         dma_k(d3, 3); dma_v(d3, 3);
         dma_k(d4, 4);
+        load_query();
         __builtin_amdgcn_s_waitcnt(0x0F70);              // vmcnt(0)
         __syncthreads();
 
