@@ -154,7 +154,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--skip-extras", action="store_true")
     ap.add_argument("--skip-cpu", action="store_true")
-    ap.add_argument("--only", default="", help="comma list of sections: prefill,decode,long,rounds")
+    ap.add_argument("--only", default="", help="comma list of sections: decode,long,rounds,reposition")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="also launch one plain device copy of this many MiB (reference for scaling rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE counters)")
@@ -286,6 +286,51 @@ def main():
             "workload": "configs[3]: 8 agents x 6 rounds, 48 appends of 256 tokens interleaved with 6 batched prefills",
             "ms_per_sequence": sec4 * 1e3, "tflops_incl_appends": f4 / sec4 / 1e12, "flops": f4, "reps": reps}
         del w4
+
+    # ------------------------------------------------ position updates vs. in-kernel rotation
+    if not args.skip_extras and (not only or "reposition" in only):
+        from paper_2512_23049_amd.binding import marshal_calls
+        w5 = gen.long_context(n_decode=0)
+        cache = harness.make_cache(w5)
+        dw = harness.DeviceWorkload(w5)
+        dw.run(cache)
+        torch.cuda.synchronize()
+        att = [s_ for s_ in dw.steps if s_[0] == "attend"][-1]
+        _, calls, mc, q, out, lse = att
+        call = calls[0]
+        lens = w5.message_lengths()
+        starts, s_self, _ = cache.resolve_call(call)
+        reps = max(3, min(args.steps, 10))
+
+        def attend_only():
+            cache.attend(calls, q.data_ptr(), out.data_ptr(), 0, 0, mc)
+        t_before = time_steps(attend_only, reps, 2, torch)
+        cache.profile_enable(True)
+        cache.profile_read(reset=True)
+        moved = [(m, st_) for (m, _), st_ in zip(call.sel, starts)] + [(call.self_msg, s_self)]
+        t0 = time.perf_counter()
+        for m, st_ in moved:
+            cache.reposition(m, st_)
+        torch.cuda.synchronize()
+        t_move = time.perf_counter() - t0
+        prof = cache.profile_read(reset=True)
+        cache.profile_enable(False)
+        t_after = time_steps(attend_only, reps, 2, torch)
+        pairs5 = sum(v[3] for v in visible_pairs(w5, w5.events[-1]))
+        f5 = 4.0 * w5.head_dim * w5.n_q_heads * pairs5
+        k_bytes = sum(lens[m] for m, _ in moved) * w5.n_kv_heads * w5.head_dim * 2
+        line.setdefault("extras", {})["reposition"] = {
+            "workload": "configs[4] prefill call alone (2048 rows over ~64k tokens in ~410 messages of 64-256 tokens): "
+                        "pc_attend with every parent at base 0 (queries turned per parent), then pc_reposition of "
+                        "every parent to the start the call gives it, then the same pc_attend (one turn in all)",
+            "attend_ms_before": t_before * 1e3, "attend_ms_after": t_after * 1e3,
+            "tflops_before": f5 / t_before / 1e12, "tflops_after": f5 / t_after / 1e12,
+            "messages_moved": len(moved), "reposition_ms_total_host_clock": t_move * 1e3,
+            "reposition_kernel_us_avg": (prof["reposition"][0] / prof["reposition"][1] * 1e3) if prof["reposition"][1] else None,
+            "reposition_bytes_read_plus_written": 2 * k_bytes,
+        }
+        cache.close()
+        del w5
 
     line["context"] = ("paper reports whole-workflow ratios only: 2.0-6.2x faster time-to-first-token and up to 2.2x "
                        "end-to-end vs prefix caching (Llama-3.1-8B; one A100-80GB is the only GPU the paper names); "

@@ -137,12 +137,26 @@ typedef struct {
 int32_t pc_attend(pc_cache *c, const pc_call *calls, int32_t n_calls,
                   const void *q, void *out, float *lse, void *stream);
 
+/* In-place position update of a cached message (Sec. 2.4 "Position Updates": the
+ * paper's mechanism, a rotation of the cached keys through a table of the D/2
+ * rotations for the move).  The stored key of token t, so far turned to position
+ * base + t (base = 0 after pc_append_message), is turned to new_base + t; one read
+ * and one write of the message's K, V untouched, stream-ordered.
+ * What pc_attend computes does not change (a call may still place the message
+ * anywhere: the difference start_pos - base is applied to the queries), except for
+ * one more rounding of the keys to the cache dtype per move.  What changes is the
+ * cost: consecutive parents of a call whose start_pos - base agree (all zero when
+ * every parent sits where it was last repositioned to) share one turn of the queries.
+ * Errors: unknown id, |new_base| > max_position.  new_base equal to the current base
+ * launches nothing. */
+int32_t pc_reposition(pc_cache *c, int32_t msg_id, int32_t new_base, void *stream);
+
 /* Parity/debug: the expanded gather table and position map of one call, in list
  * order then the new message: kv_slot[i] = physical slot, kv_pos[i] = logical
- * position (the (m, j) metadata of Sec. 2.4 in gathered form).  kv_slot / kv_pos:
- * device int32 arrays with room for *n_kv entries on entry is NOT required: the
- * function writes the count to *n_kv and fills the arrays only if cap >= count
- * (pass cap = 0 and NULL arrays to query the count). */
+ * position (the (m, j) metadata of Sec. 2.4 in gathered form).  kv_slot and kv_pos
+ * are device int32 arrays of `cap` entries each.  The function writes the number of
+ * gathered tokens to *n_kv and fills the arrays only if cap >= that number (pass
+ * cap = 0 and NULL arrays to query the count). */
 int32_t pc_build_tables(pc_cache *c, const pc_call *call, int32_t *kv_slot, int32_t *kv_pos,
                         int64_t cap, int64_t *n_kv, void *stream);
 
@@ -155,6 +169,9 @@ int32_t pc_resolve_call(pc_cache *c, const pc_call *call, int32_t *starts_out,
 /* Message and cache bookkeeping (Sec. 2.4: count of cached tokens, id -> span). */
 int32_t pc_message_info(pc_cache *c, int32_t msg_id, int32_t *len, int64_t *slot_start,
                         int32_t *reserved);
+/* *base_pos: the position the message's stored keys are currently turned to (see
+ * pc_reposition). */
+int32_t pc_message_base(pc_cache *c, int32_t msg_id, int32_t *base_pos);
 int32_t pc_cache_info(pc_cache *c, int32_t *n_messages, int64_t *slots_used,
                       int64_t *capacity_slots);
 
@@ -162,8 +179,8 @@ int32_t pc_cache_info(pc_cache *c, int32_t *n_messages, int64_t *slots_used,
  * bracketed by events on the caller's stream.  pc_profile_read waits for the stream
  * work recorded so far, then returns per-kernel-class totals since the last reset.
  * Classes: 0 append, 1 plan builder, 2 prefill attention, 3 decode attention,
- * 4 split merge, 5 fp32 attention, 6 table expansion. */
-#define PC_N_KERNEL_CLASSES 7
+ * 4 split merge, 5 fp32 attention, 6 table expansion, 7 reposition. */
+#define PC_N_KERNEL_CLASSES 8
 int32_t pc_profile_enable(pc_cache *c, int32_t on);
 int32_t pc_profile_read(pc_cache *c, double ms_total[PC_N_KERNEL_CLASSES],
                         int64_t launches[PC_N_KERNEL_CLASSES], int32_t reset);

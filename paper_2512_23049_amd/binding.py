@@ -20,8 +20,8 @@ PC_F32, PC_BF16 = 0, 1
 PC_POS_AUTO = -(2 ** 31)
 PC_SLOT_ALIGN = 32
 PC_FLAG_HOST_ONLY = 1
-PC_N_KERNEL_CLASSES = 7
-KERNEL_CLASSES = ("append", "plan", "prefill", "decode", "merge", "attend_f32", "expand")
+PC_N_KERNEL_CLASSES = 8
+KERNEL_CLASSES = ("append", "plan", "prefill", "decode", "merge", "attend_f32", "expand", "reposition")
 
 
 class pc_config(C.Structure):
@@ -70,6 +70,10 @@ def lib():
         L.pc_resolve_call.argtypes = [vp, C.POINTER(pc_call), C.POINTER(i32), C.POINTER(i32), C.POINTER(i64)]
         L.pc_message_info.restype = i32
         L.pc_message_info.argtypes = [vp, i32, C.POINTER(i32), C.POINTER(i64), C.POINTER(i32)]
+        L.pc_message_base.restype = i32
+        L.pc_message_base.argtypes = [vp, i32, C.POINTER(i32)]
+        L.pc_reposition.restype = i32
+        L.pc_reposition.argtypes = [vp, i32, i32, vp]
         L.pc_cache_info.restype = i32
         L.pc_cache_info.argtypes = [vp, C.POINTER(i32), C.POINTER(i64), C.POINTER(i64)]
         L.pc_profile_enable.restype = i32
@@ -171,6 +175,14 @@ class Cache:
         ln, st, rs = C.c_int32(0), C.c_int64(0), C.c_int32(0)
         self._check(lib().pc_message_info(self.h, msg_id, C.byref(ln), C.byref(st), C.byref(rs)))
         return ln.value, st.value, rs.value
+
+    def message_base(self, msg_id: int) -> int:
+        b = C.c_int32(0)
+        self._check(lib().pc_message_base(self.h, msg_id, C.byref(b)))
+        return b.value
+
+    def reposition(self, msg_id: int, new_base: int, stream: int = 0):
+        self._check(lib().pc_reposition(self.h, msg_id, new_base, stream))
 
     def cache_info(self):
         n, used, cap = C.c_int32(0), C.c_int64(0), C.c_int64(0)

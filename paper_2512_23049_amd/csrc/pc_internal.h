@@ -13,6 +13,9 @@
 struct PcMsgEntry {
     int32_t slot_start;       // first slot (multiple of PC_TILE)
     int32_t len;              // tokens stored
+    int32_t base_pos;         // the stored key of token t is turned to position base_pos + t
+                              // (0 after an append; moved by pc_reposition)
+    int32_t pad;
 };
 
 // One call of a batch as staged by the host.
@@ -35,12 +38,15 @@ struct PcCallDesc {
 struct PcSegment {
     int32_t slot_start;
     int32_t len;
-    int32_t pos_start;
+    int32_t pos_start;        // position the call assigns to the message's first token
     int32_t tile_off;         // KV tiles of this call before this segment
+    int32_t rot_pos;          // pos_start - the message's stored base: what the queries are turned back by
+    int32_t same_rot;         // 1: rot_pos equals that of the segment before (no new turn of the queries)
+    int32_t pad[2];
 };
 
 // One 32-key KV tile of a call's gathered sequence (built on device from the segments).
-#define PC_TILE_FRESH 0x100   // first tile of its segment
+#define PC_TILE_FRESH 0x100   // first tile of a segment whose query rotation differs from the one before
 #define PC_TILE_SELF  0x200   // tile of the new message (causal limit applies)
 struct PcTile {
     int32_t slot0;            // first physical slot of the tile (multiple of PC_TILE)

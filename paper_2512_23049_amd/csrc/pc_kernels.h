@@ -8,6 +8,11 @@ void pc_launch_append(int dtype, const void *k, const void *v, int len, int n_kv
                       int64_t slot_start, int64_t slots, const double *inv_freq, void *k_store,
                       void *v_store, PcMsgEntry *table, int msg_id, hipStream_t st);
 
+// turn the stored keys of one message by delta positions, in place
+void pc_launch_reposition(int dtype, int len, int n_kv_heads, int D, int64_t slot_start, int64_t slots, int delta,
+                          int new_base, const double *inv_freq, void *k_store, PcMsgEntry *table, int msg_id,
+                          hipStream_t st);
+
 void pc_launch_build_plan(const PcCallDesc *calls, int n_calls, const int2 *sel, const int32_t *q_pos,
                           const PcMsgEntry *table, const double *inv_freq, int half, int total_seg,
                           int total_q, PcSegment *segs, int32_t *seg_kvoff, float2 *rot_seg,

@@ -33,7 +33,7 @@ __global__ __launch_bounds__(256) void pc_append_bf16_kernel(
     const int half = D / 2;
     const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (blockIdx.y == 0) {
-        if (tid == 0) { table[msg_id].slot_start = (int32_t)slot_start; table[msg_id].len = len; }
+        if (tid == 0) { table[msg_id].slot_start = (int32_t)slot_start; table[msg_id].len = len; table[msg_id].base_pos = 0; }
         // thread = (token t, pair index i0 = 2*j): handles frequency pairs i0 and i0+1
         const int per_tok = half / 2;
         if (tid >= (int64_t)len * per_tok) return;
@@ -90,7 +90,7 @@ __global__ __launch_bounds__(256) void pc_append_f32_kernel(
     const int half = D / 2;
     const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (blockIdx.y == 0) {
-        if (tid == 0) { table[msg_id].slot_start = (int32_t)slot_start; table[msg_id].len = len; }
+        if (tid == 0) { table[msg_id].slot_start = (int32_t)slot_start; table[msg_id].len = len; table[msg_id].base_pos = 0; }
         if (tid >= (int64_t)len * half) return;
         const int t = (int)(tid / half);
         const int i = (int)(tid % half);
@@ -137,6 +137,63 @@ void pc_launch_append(int dtype, const void *k, const void *v, int len, int n_kv
 }
 
 // ----------------------------------------------------------------------------------
+// In-place position update of one cached message (Sec. 2.4 "Position Updates"): every
+// stored key is turned by `delta` more positions, with a table of the D/2 rotations
+// (cos, sin)(delta * theta_i) built once per block in fp64.  V is not touched.
+// thread = (token t, KV head h, frequency pair i0 = 2*j): handles pairs i0 and i0+1.
+// ----------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void pc_reposition_kernel(
+    int len, int n_kv_heads, int D, int64_t slot_start, int64_t slots, int delta, int new_base,
+    const double *__restrict__ inv_freq, T *__restrict__ k_store, PcMsgEntry *__restrict__ table, int msg_id)
+{
+    __shared__ float2 s_lut[64];
+    const int half = D / 2;
+    if ((int)threadIdx.x < half) {
+        double s, c;
+        sincos((double)delta * inv_freq[threadIdx.x], &s, &c);
+        s_lut[threadIdx.x] = make_float2((float)c, (float)s);
+    }
+    __syncthreads();
+    const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (tid == 0) table[msg_id].base_pos = new_base;
+    const int per_row = half / 2;
+    if (tid >= (int64_t)len * n_kv_heads * per_row) return;
+    const int i0 = 2 * (int)(tid % per_row);
+    const int h = (int)((tid / per_row) % n_kv_heads);
+    const int t = (int)(tid / ((int64_t)per_row * n_kv_heads));
+    const float2 r0 = s_lut[i0], r1 = s_lut[i0 + 1];
+    T *row = k_store + ((int64_t)h * slots + slot_start + t) * D;
+    if constexpr (sizeof(T) == 2) {
+        using P = Pair2<__hip_bfloat16>;
+        const uint32_t lo = *reinterpret_cast<const uint32_t *>(row + i0);
+        const uint32_t hi = *reinterpret_cast<const uint32_t *>(row + half + i0);
+        const float a0 = P::lo(lo), a1 = P::hi(lo), b0 = P::lo(hi), b1 = P::hi(hi);
+        *reinterpret_cast<uint32_t *>(row + i0) = P::pack(a0 * r0.x - b0 * r0.y, a1 * r1.x - b1 * r1.y);
+        *reinterpret_cast<uint32_t *>(row + half + i0) = P::pack(a0 * r0.y + b0 * r0.x, a1 * r1.y + b1 * r1.x);
+    } else {
+        const float a0 = row[i0], a1 = row[i0 + 1], b0 = row[half + i0], b1 = row[half + i0 + 1];
+        row[i0] = a0 * r0.x - b0 * r0.y; row[i0 + 1] = a1 * r1.x - b1 * r1.y;
+        row[half + i0] = a0 * r0.y + b0 * r0.x; row[half + i0 + 1] = a1 * r1.y + b1 * r1.x;
+    }
+}
+
+void pc_launch_reposition(int dtype, int len, int n_kv_heads, int D, int64_t slot_start, int64_t slots, int delta,
+                          int new_base, const double *inv_freq, void *k_store, PcMsgEntry *table, int msg_id,
+                          hipStream_t st)
+{
+    const int64_t n = (int64_t)len * n_kv_heads * (D / 4);
+    const unsigned grid = (unsigned)((n + 255) / 256);
+    if (grid == 0) return;
+    if (dtype == 1)
+        pc_reposition_kernel<uint16_t><<<grid, 256, 0, st>>>(len, n_kv_heads, D, slot_start, slots, delta, new_base, inv_freq,
+                                                             (uint16_t *)k_store, table, msg_id);
+    else
+        pc_reposition_kernel<float><<<grid, 256, 0, st>>>(len, n_kv_heads, D, slot_start, slots, delta, new_base, inv_freq,
+                                                          (float *)k_store, table, msg_id);
+}
+
+// ----------------------------------------------------------------------------------
 // K2: plan builder.  Blocks [0, n_calls): per call, look each listed message up in the
 // device message table and scan lengths into the segment list (Sec. 2.4 "Dynamic
 // Masking": what a call sees is computed on the fly from message membership; here in
@@ -154,20 +211,22 @@ __global__ __launch_bounds__(256) void pc_build_plan_kernel(
     __shared__ int s_len[256];
     __shared__ int s_tiles[256];
     __shared__ int s_carry[2];
+    __shared__ int s_rot[257];                           // query rotation (position - stored base) of the chunk's segments
     if ((int)blockIdx.x < n_calls) {
         const PcCallDesc cd = calls[blockIdx.x];
-        if (threadIdx.x == 0) { s_carry[0] = 0; s_carry[1] = 0; }
+        if (threadIdx.x == 0) { s_carry[0] = 0; s_carry[1] = 0; s_rot[0] = 0; }
         __syncthreads();
         for (int base = 0; base < cd.n_seg; base += 256) {
             const int e = base + threadIdx.x;
-            int len = 0, slot = 0, pos = 0;
+            int len = 0, slot = 0, pos = 0, rot = 0;
             if (e < cd.n_seg) {
                 int m, p;
                 if (e < cd.n_sel) { const int2 s = sel[cd.sel_off + e]; m = s.x; p = s.y; }
                 else { m = cd.self_msg; p = cd.self_start; }
                 const PcMsgEntry me = table[m];
-                len = me.len; slot = me.slot_start; pos = p;
+                len = me.len; slot = me.slot_start; pos = p; rot = p - me.base_pos;
             }
+            s_rot[threadIdx.x + 1] = rot;                // s_rot[0]: last segment of the chunk before
             const int tiles = (len + PC_TILE - 1) / PC_TILE;
             s_len[threadIdx.x] = len;
             s_tiles[threadIdx.x] = tiles;
@@ -186,11 +245,14 @@ __global__ __launch_bounds__(256) void pc_build_plan_kernel(
                 PcSegment sg;
                 sg.slot_start = slot; sg.len = len; sg.pos_start = pos;
                 sg.tile_off = c_tiles + s_tiles[threadIdx.x] - tiles;
+                sg.rot_pos = rot;
+                sg.same_rot = (e > 0 && s_rot[threadIdx.x] == rot) ? 1 : 0;
+                sg.pad[0] = sg.pad[1] = 0;
                 segs[cd.seg_off + e] = sg;
                 seg_kvoff[cd.seg_off + e] = c_len + s_len[threadIdx.x] - len;
             }
             __syncthreads();
-            if (threadIdx.x == 255) { s_carry[0] = c_len + s_len[255]; s_carry[1] = c_tiles + s_tiles[255]; }
+            if (threadIdx.x == 255) { s_carry[0] = c_len + s_len[255]; s_carry[1] = c_tiles + s_tiles[255]; s_rot[0] = rot; }
             __syncthreads();
         }
         // tile table of this call: one entry per 32-key tile, in gathered order (the segment
@@ -209,7 +271,7 @@ __global__ __launch_bounds__(256) void pc_build_plan_kernel(
             tl.slot0 = g.slot_start + tl.key0;
             tl.seg = lo;
             const int valid = g.len - tl.key0 < PC_TILE ? g.len - tl.key0 : PC_TILE;
-            tl.valid_flags = valid | (t == g.tile_off ? PC_TILE_FRESH : 0) |
+            tl.valid_flags = valid | ((t == g.tile_off && !g.same_rot) ? PC_TILE_FRESH : 0) |
                              ((cd.self_msg >= 0 && lo == cd.n_seg - 1) ? PC_TILE_SELF : 0);
             tiles[cd.tile_off + t] = tl;
         }
@@ -231,7 +293,10 @@ __global__ __launch_bounds__(256) void pc_build_plan_kernel(
         }
         const PcCallDesc cd = calls[lo];
         const int e = ent - cd.seg_off;
-        pos = (e < cd.n_sel) ? sel[cd.sel_off + e].y : cd.self_start;
+        int m;
+        if (e < cd.n_sel) { const int2 s = sel[cd.sel_off + e]; m = s.x; pos = s.y; }
+        else { m = cd.self_msg; pos = cd.self_start; }
+        pos -= table[m].base_pos;                        // the stored key of token t already sits at base_pos + t
     } else {
         pos = q_pos[ent - total_seg];
     }

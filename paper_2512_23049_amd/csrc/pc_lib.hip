@@ -13,7 +13,7 @@
 
 namespace {
 
-struct HostMsg { int64_t slot_start; int32_t len; int32_t reserve; };
+struct HostMsg { int64_t slot_start; int32_t len; int32_t reserve; int32_t base_pos; };
 
 struct StageSlot { void *host = nullptr; size_t cap = 0; hipEvent_t ev = nullptr; bool used = false; };
 
@@ -324,7 +324,7 @@ int32_t pc_append_message(pc_cache *c, const void *k, const void *v, int32_t len
                          c->k_store, c->v_store, c->table_dev, id, st);
         PC_HIP(c, hipGetLastError());
     }
-    c->msgs.push_back({start, len, res});
+    c->msgs.push_back({start, len, res, 0});
     c->next_slot = (int64_t)align_up((size_t)(start + res), PC_SLOT_ALIGN);
     *msg_id = id;
     return PC_OK;
@@ -349,6 +349,35 @@ int32_t pc_message_info(pc_cache *c, int32_t msg_id, int32_t *len, int64_t *slot
     if (len) *len = c->msgs[msg_id].len;
     if (slot_start) *slot_start = c->msgs[msg_id].slot_start;
     if (reserved) *reserved = c->msgs[msg_id].reserve;
+    return PC_OK;
+}
+
+int32_t pc_message_base(pc_cache *c, int32_t msg_id, int32_t *base_pos)
+{
+    if (!c) return PC_ERR_INVALID_ARG;
+    if (msg_id < 0 || msg_id >= (int)c->msgs.size()) return fail(c, PC_ERR_BAD_MSG_ID, "unknown message %d", msg_id);
+    if (base_pos) *base_pos = c->msgs[msg_id].base_pos;
+    return PC_OK;
+}
+
+int32_t pc_reposition(pc_cache *c, int32_t msg_id, int32_t new_base, void *stream)
+{
+    if (!c) return PC_ERR_INVALID_ARG;
+    if (msg_id < 0 || msg_id >= (int)c->msgs.size()) return fail(c, PC_ERR_BAD_MSG_ID, "reposition: unknown message %d", msg_id);
+    if (new_base > c->cfg.max_position || new_base < -c->cfg.max_position)
+        return fail(c, PC_ERR_INVALID_ARG, "reposition: position %d outside [-%d, %d]", new_base, c->cfg.max_position,
+                    c->cfg.max_position);
+    HostMsg &m = c->msgs[(size_t)msg_id];
+    const int64_t delta = (int64_t)new_base - m.base_pos;
+    if (delta == 0) return PC_OK;
+    if (!c->host_only) {
+        hipStream_t st = (hipStream_t)stream;
+        ProfScope ps(c, 7, st);
+        pc_launch_reposition(c->cfg.dtype, m.len, c->cfg.n_kv_heads, c->D, m.slot_start, c->slots, (int)delta, new_base,
+                             c->inv_freq_dev, c->k_store, c->table_dev, msg_id, st);
+        PC_HIP(c, hipGetLastError());
+    }
+    m.base_pos = new_base;
     return PC_OK;
 }
 

@@ -153,3 +153,23 @@ def test_host_plan_accepts_the_generated_workloads(pc):
             for call in e.calls:
                 slot, pos = orc.tables_for_call(call, lens, res, pc.PC_SLOT_ALIGN)
                 assert c.build_tables(call, 0, 0, 0) == slot.shape[0]
+
+
+def test_reposition_bookkeeping_on_a_host_only_cache(pc):
+    c = host_cache(pc, max_position=500)
+    a = c.append_message(0, 0, 40)
+    b = c.append_message(0, 0, 7)
+    assert c.message_base(a) == 0 and c.message_base(b) == 0
+    c.reposition(a, 123)
+    c.reposition(b, -500)
+    assert c.message_base(a) == 123 and c.message_base(b) == -500
+    # a move changes neither the span nor what a call resolves to
+    assert c.message_info(a)[:2] == (40, 0)
+    starts, s_self, n = c.resolve_call(Call([(a, POS_AUTO), (b, POS_AUTO)], -1, 0, 1, np.array([0], dtype=np.int32)))
+    assert starts == [0, 40] and n == 47
+    with pytest.raises(pc.PcError) as ei:
+        c.reposition(a, 501)
+    assert ei.value.code == pc.PC_ERR_INVALID_ARG
+    with pytest.raises(pc.PcError) as ei:
+        c.reposition(9, 0)
+    assert ei.value.code == pc.PC_ERR_BAD_MSG_ID

@@ -73,6 +73,22 @@ def test_delta_rotation_identity():
     assert abs(lhs - rhs) < 1e-10
 
 
+def test_position_updates_compose():
+    # Sec. 2.4 "Position Updates": a cached key already turned to position a is moved to
+    # position b by one more rotation of (b - a); moves compose and a move back restores it.
+    k = RNG.standard_normal((7, 2, 64))
+    t = np.arange(7)
+    at_a = orc.rope(k, 40 + t, 1e4)
+    moved = orc.rope(at_a, np.full(7, 1000 - 40), 1e4)
+    assert np.abs(moved - orc.rope(k, 1000 + t, 1e4)).max() < 1e-10
+    back = orc.rope(moved, np.full(7, -(1000 - 40)), 1e4)
+    assert np.abs(back - at_a).max() < 1e-10
+    # a rotation keeps every (i, i + D/2) pair's length: the textbook property of a plane rotation
+    n0 = k[..., :32] ** 2 + k[..., 32:] ** 2
+    n1 = moved[..., :32] ** 2 + moved[..., 32:] ** 2
+    assert np.abs(n0 - n1).max() < 1e-10
+
+
 # ---------------------------------------------------------------- brute force
 @pytest.mark.parametrize("seed", [0, 1, 2])
 def test_brute_force_agrees_on_tiny_inputs(seed):
