@@ -154,7 +154,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--skip-extras", action="store_true")
     ap.add_argument("--skip-cpu", action="store_true")
-    ap.add_argument("--only", default="", help="comma list of sections: decode,long,rounds,reposition")
+    ap.add_argument("--only", default="", help="comma list of sections: decode,long,rounds,loop,reposition")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="also launch one plain device copy of this many MiB (reference for scaling rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE counters)")
@@ -202,8 +202,9 @@ def main():
     }
     if not args.skip_cpu:
         line["cpu_baseline"] = cpu_baseline(
-            w2, {"calls": [0], "rows": lambda n: list(range(0, n, 2)),
-                 "desc": "configs[1], every 2nd of the 512 query rows, all 32 heads, all keys"}, "TFLOP/s")
+            w2, {"calls": [0], "rows": lambda n: list(range(n)),
+                 "desc": "configs[1] whole: all 512 query rows, all 32 heads, all keys (under a second of CPU "
+                         "work; the oracle is the plain definition on BLAS)"}, "TFLOP/s")
     del w2
 
     # ---------------------------------------------------------------- decode (configs[2])
@@ -234,8 +235,8 @@ def main():
         }
         if not args.skip_cpu:
             line["decode"]["cpu_baseline"] = cpu_baseline(
-                w3, {"calls": list(range(0, 64, 4)), "rows": lambda n: [0],
-                     "desc": "configs[2], 16 of the 64 calls"}, "GB/s")
+                w3, {"calls": list(range(64)), "rows": lambda n: [0],
+                     "desc": "configs[2] whole: all 64 calls"}, "GB/s")
         del w3
 
     # ---------------------------------------------------------------- long context (configs[4])
@@ -286,6 +287,41 @@ def main():
             "workload": "configs[3]: 8 agents x 6 rounds, 48 appends of 256 tokens interleaved with 6 batched prefills",
             "ms_per_sequence": sec4 * 1e3, "tflops_incl_appends": f4 / sec4 / 1e12, "flops": f4, "reps": reps}
         del w4
+
+    # ------------------------------------------------ decode loop: tails growing one token per step
+    if not args.skip_extras and (not only or "loop" in only):
+        w6 = gen.decode_loop()
+        dw = harness.DeviceWorkload(w6)
+        first_loop = next(i for i, s_ in enumerate(dw.steps) if s_[0] == "attend")
+        n_steps = sum(1 for s_ in dw.steps if s_[0] == "attend")
+        times = []
+        for rep in range(3):
+            cache = harness.make_cache(w6)
+            for s_ in dw.steps[:first_loop]:
+                cache.append_message(s_[1].data_ptr(), s_[2].data_ptr(), s_[3], s_[4])
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for s_ in dw.steps[first_loop:]:
+                if s_[0] == "extend":
+                    cache.append_tokens_batch(s_[3], s_[1].data_ptr(), s_[2].data_ptr())
+                else:
+                    cache.attend(s_[1], s_[3].data_ptr(), s_[4].data_ptr(), 0, 0, s_[2])
+            torch.cuda.synchronize()
+            times.append(time.perf_counter() - t0)
+            cache.close()
+        sec6 = min(times[1:])
+        b6 = 0
+        for i, e in enumerate(w6.events):
+            if e.kind == "attend":
+                lens = w6.message_lengths(upto_event=i)
+                b6 += sum(sum(lens[m] for m, _ in c.sel) + lens[c.self_msg] for c in e.calls) * 4096
+        n_calls6 = len(w6.events[-1].calls)
+        line.setdefault("extras", {})["decode_loop"] = {
+            "workload": "configs[2]-shaped parallel decode as a loop: 64 calls (2048-token system + 8 pool messages each), "
+                        "tails grow from 1 to 64 tokens; a step = pc_append_tokens_batch (one token per call) + pc_attend",
+            "steps": n_steps, "us_per_step": sec6 / n_steps * 1e6, "tokens_per_s": n_calls6 * n_steps / sec6,
+            "gbs_logical": b6 / sec6 / 1e9, "B_logical_total": b6}
+        del w6, dw
 
     # ------------------------------------------------ position updates vs. in-kernel rotation
     if not args.skip_extras and (not only or "reposition" in only):

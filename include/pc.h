@@ -103,6 +103,21 @@ const char *pc_last_error(const pc_cache *c);
 int32_t pc_append_message(pc_cache *c, const void *k, const void *v, int32_t len,
                           int32_t reserve, int32_t *msg_id, void *stream);
 
+/* Growth of existing messages within the room reserved at pc_append_message
+ * (Sec. 2.4: decode tails grow token by token; parallel calls grow theirs in step).
+ * pc_append_tokens: n more tokens for one message, k, v device [n, n_kv_heads, head_dim].
+ * pc_append_tokens_batch: one more token for each of n_msgs distinct messages in one
+ * launch; msg_ids host (copied before return), row j of k, v ([n_msgs, n_kv_heads,
+ * head_dim]) goes to message msg_ids[j].
+ * Keys are turned to base + in-message index like those of pc_append_message.  Stream
+ * ordered: a later pc_attend on the same stream sees the longer messages.
+ * Errors (nothing enqueued): unknown id, an id listed twice in a batch, n < 1, more
+ * tokens than the reserve has room for (PC_ERR_NO_SPACE). */
+int32_t pc_append_tokens(pc_cache *c, int32_t msg_id, const void *k, const void *v, int32_t n,
+                         void *stream);
+int32_t pc_append_tokens_batch(pc_cache *c, const int32_t *msg_ids, int32_t n_msgs, const void *k,
+                               const void *v, void *stream);
+
 /* One parent of a call: message id and the position of its first token
  * (Sec. 2.3 `parents` and `offsets`). */
 typedef struct { int32_t msg_id; int32_t start_pos; } pc_sel;

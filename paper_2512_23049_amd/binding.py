@@ -62,6 +62,10 @@ def lib():
         L.pc_last_error.argtypes = [vp]
         L.pc_append_message.restype = i32
         L.pc_append_message.argtypes = [vp, vp, vp, i32, i32, C.POINTER(i32), vp]
+        L.pc_append_tokens.restype = i32
+        L.pc_append_tokens.argtypes = [vp, i32, vp, vp, i32, vp]
+        L.pc_append_tokens_batch.restype = i32
+        L.pc_append_tokens_batch.argtypes = [vp, C.POINTER(i32), i32, vp, vp, vp]
         L.pc_attend.restype = i32
         L.pc_attend.argtypes = [vp, C.POINTER(pc_call), i32, vp, vp, vp, vp]
         L.pc_build_tables.restype = i32
@@ -175,6 +179,13 @@ class Cache:
         ln, st, rs = C.c_int32(0), C.c_int64(0), C.c_int32(0)
         self._check(lib().pc_message_info(self.h, msg_id, C.byref(ln), C.byref(st), C.byref(rs)))
         return ln.value, st.value, rs.value
+
+    def append_tokens(self, msg_id: int, k_ptr: int, v_ptr: int, n: int, stream: int = 0):
+        self._check(lib().pc_append_tokens(self.h, msg_id, k_ptr, v_ptr, n, stream))
+
+    def append_tokens_batch(self, msg_ids, k_ptr: int, v_ptr: int, stream: int = 0):
+        arr = (C.c_int32 * max(len(msg_ids), 1))(*[int(m) for m in msg_ids])
+        self._check(lib().pc_append_tokens_batch(self.h, arr, len(msg_ids), k_ptr, v_ptr, stream))
 
     def message_base(self, msg_id: int) -> int:
         b = C.c_int32(0)

@@ -18,6 +18,14 @@ struct PcMsgEntry {
     int32_t pad;
 };
 
+// One token appended to an existing message (staged by the host).
+struct PcTokenItem {
+    int32_t msg;              // message that grows
+    int32_t slot;             // physical slot the token goes to
+    int32_t pos;              // base_pos + in-message index: what its key is turned to
+    int32_t new_len;          // the message's length once this token is in
+};
+
 // One call of a batch as staged by the host.
 struct PcCallDesc {
     int32_t sel_off;          // first entry in the packed (msg, start) list

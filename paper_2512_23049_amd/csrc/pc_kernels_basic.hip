@@ -137,6 +137,71 @@ void pc_launch_append(int dtype, const void *k, const void *v, int len, int n_kv
 }
 
 // ----------------------------------------------------------------------------------
+// Tokens appended to existing messages (Sec. 2.4: the tails of parallel decode calls
+// grow one token per step, interleaved).  thread = (token j, KV head h, frequency pair
+// i0 = 2*m): key turned to the item's position, value written into its 8-slot group.
+// ----------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void pc_append_tokens_kernel(
+    const PcTokenItem *__restrict__ items, int n, const T *__restrict__ k, const T *__restrict__ v,
+    int n_kv_heads, int D, int64_t slots, const double *__restrict__ inv_freq,
+    T *__restrict__ k_store, T *__restrict__ v_store, PcMsgEntry *__restrict__ table)
+{
+    const int half = D / 2, per_row = half / 2;
+    const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (tid >= (int64_t)n * n_kv_heads * per_row) return;
+    const int i0 = 2 * (int)(tid % per_row);
+    const int h = (int)((tid / per_row) % n_kv_heads);
+    const int j = (int)(tid / ((int64_t)per_row * n_kv_heads));
+    const PcTokenItem it = items[j];
+    if (h == 0 && i0 == 0) table[it.msg].len = it.new_len;      // every item of a message carries its final length
+    double s0, c0, s1, c1;
+    sincos((double)it.pos * inv_freq[i0], &s0, &c0);
+    sincos((double)it.pos * inv_freq[i0 + 1], &s1, &c1);
+    const float fc0 = (float)c0, fs0 = (float)s0, fc1 = (float)c1, fs1 = (float)s1;
+    const T *ksrc = k + ((int64_t)j * n_kv_heads + h) * D;
+    const T *vsrc = v + ((int64_t)j * n_kv_heads + h) * D;
+    T *kdst = k_store + ((int64_t)h * slots + it.slot) * D;
+    if constexpr (sizeof(T) == 2) {
+        using P = Pair2<__hip_bfloat16>;
+        const uint32_t lo = *reinterpret_cast<const uint32_t *>(ksrc + i0);
+        const uint32_t hi = *reinterpret_cast<const uint32_t *>(ksrc + half + i0);
+        const float a0 = P::lo(lo), a1 = P::hi(lo), b0 = P::lo(hi), b1 = P::hi(hi);
+        *reinterpret_cast<uint32_t *>(kdst + i0) = P::pack(a0 * fc0 - b0 * fs0, a1 * fc1 - b1 * fs1);
+        *reinterpret_cast<uint32_t *>(kdst + half + i0) = P::pack(a0 * fs0 + b0 * fc0, a1 * fs1 + b1 * fc1);
+        // V: [H_kv][slots/8][D][8]; this thread moves dims i0, i0+1 and half+i0, half+i0+1
+        T *vg = v_store + ((int64_t)h * (slots / PC_VGROUP) + it.slot / PC_VGROUP) * D * PC_VGROUP + (it.slot % PC_VGROUP);
+        vg[(int64_t)i0 * PC_VGROUP] = vsrc[i0];
+        vg[(int64_t)(i0 + 1) * PC_VGROUP] = vsrc[i0 + 1];
+        vg[(int64_t)(half + i0) * PC_VGROUP] = vsrc[half + i0];
+        vg[(int64_t)(half + i0 + 1) * PC_VGROUP] = vsrc[half + i0 + 1];
+    } else {
+        const float a0 = ksrc[i0], a1 = ksrc[i0 + 1], b0 = ksrc[half + i0], b1 = ksrc[half + i0 + 1];
+        kdst[i0] = a0 * fc0 - b0 * fs0; kdst[i0 + 1] = a1 * fc1 - b1 * fs1;
+        kdst[half + i0] = a0 * fs0 + b0 * fc0; kdst[half + i0 + 1] = a1 * fs1 + b1 * fc1;
+        T *vdst = v_store + ((int64_t)h * slots + it.slot) * D;
+        vdst[i0] = vsrc[i0]; vdst[i0 + 1] = vsrc[i0 + 1];
+        vdst[half + i0] = vsrc[half + i0]; vdst[half + i0 + 1] = vsrc[half + i0 + 1];
+    }
+}
+
+void pc_launch_append_tokens(int dtype, const PcTokenItem *items, int n, const void *k, const void *v, int n_kv_heads,
+                             int D, int64_t slots, const double *inv_freq, void *k_store, void *v_store,
+                             PcMsgEntry *table, hipStream_t st)
+{
+    const int64_t total = (int64_t)n * n_kv_heads * (D / 4);
+    const unsigned grid = (unsigned)((total + 255) / 256);
+    if (grid == 0) return;
+    if (dtype == 1)
+        pc_append_tokens_kernel<uint16_t><<<grid, 256, 0, st>>>(items, n, (const uint16_t *)k, (const uint16_t *)v, n_kv_heads,
+                                                                D, slots, inv_freq, (uint16_t *)k_store,
+                                                                (uint16_t *)v_store, table);
+    else
+        pc_append_tokens_kernel<float><<<grid, 256, 0, st>>>(items, n, (const float *)k, (const float *)v, n_kv_heads, D,
+                                                             slots, inv_freq, (float *)k_store, (float *)v_store, table);
+}
+
+// ----------------------------------------------------------------------------------
 // In-place position update of one cached message (Sec. 2.4 "Position Updates"): every
 // stored key is turned by `delta` more positions, with a table of the D/2 rotations
 // (cos, sin)(delta * theta_i) built once per block in fp64.  V is not touched.

@@ -41,6 +41,7 @@ struct pc_cache {
     PcMsgEntry *table_dev = nullptr;
     double *inv_freq_dev = nullptr;
     void *ws = nullptr; size_t ws_cap = 0;
+    PcTokenItem *tok_dev = nullptr; size_t tok_cap = 0;   // staged items of pc_append_tokens*
     StageSlot stage[N_STAGE]; int stage_next = 0;
     // profiling
     bool prof = false;
@@ -292,6 +293,7 @@ int32_t pc_cache_destroy(pc_cache *c)
         for (auto e : c->ev_pool) (void)hipEventDestroy(e);
         for (auto &s : c->stage) { if (s.host) (void)hipHostFree(s.host); if (s.ev) (void)hipEventDestroy(s.ev); }
         if (c->ws) (void)hipFree(c->ws);
+        if (c->tok_dev) (void)hipFree(c->tok_dev);
         if (c->inv_freq_dev) (void)hipFree(c->inv_freq_dev);
         if (c->table_dev) (void)hipFree(c->table_dev);
         if (c->owns_storage && c->storage) (void)hipFree(c->storage);
@@ -328,6 +330,75 @@ int32_t pc_append_message(pc_cache *c, const void *k, const void *v, int32_t len
     c->next_slot = (int64_t)align_up((size_t)(start + res), PC_SLOT_ALIGN);
     *msg_id = id;
     return PC_OK;
+}
+
+// shared by pc_append_tokens and pc_append_tokens_batch: token j of k, v goes to message ids[j]
+// (ids sorted by message with a message's tokens in order; validated by the callers)
+static int32_t append_token_items(pc_cache *c, const std::vector<int32_t> &ids, const void *k, const void *v, hipStream_t st)
+{
+    const int n = (int)ids.size();
+    std::vector<PcTokenItem> items((size_t)n);
+    std::vector<int32_t> grown(c->msgs.size(), 0);
+    for (int j = 0; j < n; ++j) grown[(size_t)ids[j]] += 1;
+    for (size_t m = 0; m < grown.size(); ++m)
+        if (grown[m] && c->msgs[m].len + grown[m] > c->msgs[m].reserve)
+            return fail(c, PC_ERR_NO_SPACE, "append_tokens: message %d holds %d of %d reserved tokens, %d more do not fit",
+                        (int)m, c->msgs[m].len, c->msgs[m].reserve, grown[m]);
+    std::vector<int32_t> seen(c->msgs.size(), 0);
+    for (int j = 0; j < n; ++j) {
+        const HostMsg &m = c->msgs[(size_t)ids[j]];
+        const int t = m.len + seen[(size_t)ids[j]]++;
+        items[(size_t)j] = PcTokenItem{ids[j], (int32_t)(m.slot_start + t), m.base_pos + t, m.len + grown[(size_t)ids[j]]};
+    }
+    if (!c->host_only) {
+        if ((size_t)n > c->tok_cap) {
+            PC_HIP(c, hipStreamSynchronize(st));
+            PC_HIP(c, hipDeviceSynchronize());
+            if (c->tok_dev) PC_HIP(c, hipFree(c->tok_dev));
+            c->tok_dev = nullptr; c->tok_cap = 0;
+            const size_t cap = std::max<size_t>(4096, (size_t)n * 2);
+            PC_HIP(c, hipMalloc((void **)&c->tok_dev, cap * sizeof(PcTokenItem)));
+            c->tok_cap = cap;
+        }
+        StageSlot *slot = nullptr;
+        const int32_t rc = stage_acquire(c, sizeof(PcTokenItem) * (size_t)n, &slot);
+        if (rc != PC_OK) return rc;
+        std::memcpy(slot->host, items.data(), sizeof(PcTokenItem) * (size_t)n);
+        PC_HIP(c, hipMemcpyAsync(c->tok_dev, slot->host, sizeof(PcTokenItem) * (size_t)n, hipMemcpyHostToDevice, st));
+        PC_HIP(c, hipEventRecord(slot->ev, st));
+        slot->used = true;
+        ProfScope ps(c, 0, st);
+        pc_launch_append_tokens(c->cfg.dtype, c->tok_dev, n, k, v, c->cfg.n_kv_heads, c->D, c->slots, c->inv_freq_dev,
+                                c->k_store, c->v_store, c->table_dev, st);
+        PC_HIP(c, hipGetLastError());
+    }
+    for (size_t m = 0; m < grown.size(); ++m) c->msgs[m].len += grown[m];
+    return PC_OK;
+}
+
+int32_t pc_append_tokens(pc_cache *c, int32_t msg_id, const void *k, const void *v, int32_t n, void *stream)
+{
+    if (!c) return PC_ERR_INVALID_ARG;
+    if (msg_id < 0 || msg_id >= (int)c->msgs.size()) return fail(c, PC_ERR_BAD_MSG_ID, "append_tokens: unknown message %d", msg_id);
+    if (n < 1) return fail(c, PC_ERR_INVALID_ARG, "append_tokens: n = %d must be >= 1", n);
+    if (!c->host_only && (!k || !v)) return fail(c, PC_ERR_INVALID_ARG, "append_tokens: null k or v");
+    return append_token_items(c, std::vector<int32_t>((size_t)n, msg_id), k, v, (hipStream_t)stream);
+}
+
+int32_t pc_append_tokens_batch(pc_cache *c, const int32_t *msg_ids, int32_t n_msgs, const void *k, const void *v, void *stream)
+{
+    if (!c) return PC_ERR_INVALID_ARG;
+    if (n_msgs < 0 || (n_msgs > 0 && !msg_ids)) return fail(c, PC_ERR_INVALID_ARG, "append_tokens_batch: bad id list");
+    if (n_msgs == 0) return PC_OK;
+    if (!c->host_only && (!k || !v)) return fail(c, PC_ERR_INVALID_ARG, "append_tokens_batch: null k or v");
+    std::vector<char> listed(c->msgs.size(), 0);
+    for (int j = 0; j < n_msgs; ++j) {
+        const int32_t m = msg_ids[j];
+        if (m < 0 || m >= (int)c->msgs.size()) return fail(c, PC_ERR_BAD_MSG_ID, "append_tokens_batch: unknown message %d", m);
+        if (listed[(size_t)m]) return fail(c, PC_ERR_INVALID_ARG, "append_tokens_batch: message %d listed twice", m);
+        listed[(size_t)m] = 1;
+    }
+    return append_token_items(c, std::vector<int32_t>(msg_ids, msg_ids + n_msgs), k, v, (hipStream_t)stream);
 }
 
 int32_t pc_resolve_call(pc_cache *c, const pc_call *call, int32_t *starts_out, int32_t *self_start_out, int64_t *n_kv)

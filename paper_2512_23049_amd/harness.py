@@ -36,6 +36,9 @@ class DeviceWorkload:
             if e.kind == "append":
                 self.steps.append(("append", to_device(e.k, w.dtype, device), to_device(e.v, w.dtype, device),
                                    int(e.k.shape[0]), int(e.reserve)))
+            elif e.kind == "extend":
+                self.steps.append(("extend", to_device(e.k, w.dtype, device), to_device(e.v, w.dtype, device),
+                                   list(e.msgs)))
             else:
                 q = to_device(e.q, w.dtype, device)
                 out = torch.empty_like(q)
@@ -48,6 +51,8 @@ class DeviceWorkload:
         for s in self.steps:
             if s[0] == "append":
                 cache.append_message(s[1].data_ptr(), s[2].data_ptr(), s[3], s[4], stream)
+            elif s[0] == "extend":
+                cache.append_tokens_batch(s[3], s[1].data_ptr(), s[2].data_ptr(), stream)
             else:
                 _, calls, m, q, out, lse = s
                 cache.attend(calls, q.data_ptr(), out.data_ptr(), lse.data_ptr() if want_lse else 0, stream, m)

@@ -17,5 +17,6 @@ from .generators import (  # noqa: F401
     parallel_decode,
     multi_agent_rounds,
     long_context,
+    decode_loop,
     small_random,
 )

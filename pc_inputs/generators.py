@@ -3,8 +3,9 @@
 Every generator returns a :class:`Workload`: model shape, dtype name, RoPE
 base, and an ordered list of events.  An ``append`` event carries one
 message's unrotated K and V (``float32`` arrays whose values are exactly
-representable in the workload dtype); an ``attend`` event carries a batch of
-calls and the packed query rows.  Random numbers come from
+representable in the workload dtype); an ``extend`` event carries one more token
+for each of a list of messages (decode tails growing in step); an ``attend``
+event carries a batch of calls and the packed query rows.  Random numbers come from
 ``numpy.random.default_rng(seed)`` and are drawn in the order the code reads.
 
 The five named workloads mirror the *shapes* of the multi-agent workflows the
@@ -33,9 +34,10 @@ class Call:
 
 @dataclass
 class Event:
-    kind: str                             # "append" | "attend"
-    k: Optional[np.ndarray] = None        # append: [L, H_kv, D] float32
+    kind: str                             # "append" | "extend" | "attend"
+    k: Optional[np.ndarray] = None        # append: [L, H_kv, D] float32; extend: [n_msgs, H_kv, D]
     v: Optional[np.ndarray] = None
+    msgs: Optional[List[int]] = None      # extend: message i of the list gets token row i
     reserve: int = 0                      # append: slots to reserve (0 = len)
     calls: Optional[List[Call]] = None    # attend
     q: Optional[np.ndarray] = None        # attend: [sum n_q, H_q, D] float32
@@ -55,8 +57,18 @@ class Workload:
     def n_messages(self) -> int:
         return sum(1 for e in self.events if e.kind == "append")
 
-    def message_lengths(self) -> List[int]:
-        return [int(e.k.shape[0]) for e in self.events if e.kind == "append"]
+    def message_lengths(self, upto_event: Optional[int] = None) -> List[int]:
+        """Token counts after the first `upto_event` events (all events if None)."""
+        lens: List[int] = []
+        for i, e in enumerate(self.events):
+            if upto_event is not None and i >= upto_event:
+                break
+            if e.kind == "append":
+                lens.append(int(e.k.shape[0]))
+            elif e.kind == "extend":
+                for m in e.msgs:
+                    lens[m] += 1
+        return lens
 
     def message_reserves(self) -> List[int]:
         return [int(max(e.reserve, e.k.shape[0])) for e in self.events if e.kind == "append"]
@@ -81,6 +93,12 @@ def _append(w: Workload, rng, length: int, reserve: int = 0) -> int:
     v = _normal(rng, (length, w.n_kv_heads, w.head_dim), w.dtype)
     w.events.append(Event("append", k=k, v=v, reserve=reserve))
     return w.n_messages - 1
+
+
+def _extend(w: Workload, rng, msgs: List[int]) -> None:
+    k = _normal(rng, (len(msgs), w.n_kv_heads, w.head_dim), w.dtype)
+    v = _normal(rng, (len(msgs), w.n_kv_heads, w.head_dim), w.dtype)
+    w.events.append(Event("extend", k=k, v=v, msgs=list(msgs)))
 
 
 def _attend(w: Workload, rng, calls: List[Call]) -> None:
@@ -222,6 +240,42 @@ def long_context(seed: int = 5, n_msgs: int = 512, len_lo: int = 64, len_hi: int
         else:
             calls.append(Call(sel, new_id, s, n_prefill_q, None))
     _attend(w, rng, calls)
+    return w
+
+
+# --------------------------------------------------------------------------
+# parallel decode loop: the calls of config 3, but the tails start short and every
+# step adds one token to each tail before the calls attend again (the decode phase
+# of a workflow: Sec. 2.4, tails of parallel calls growing in step)
+# --------------------------------------------------------------------------
+def decode_loop(seed: int = 6, n_calls: int = 64, n_steps: int = 63, sys_len: int = 2048, n_pool: int = 512,
+                len_lo: int = 128, len_hi: int = 512, n_sel: int = 8, tail0: int = 1,
+                n_q_heads: int = 32, n_kv_heads: int = 8, head_dim: int = 128,
+                dtype: str = "bf16") -> Workload:
+    rng = np.random.default_rng(seed)
+    w = Workload("decode_loop", n_q_heads, n_kv_heads, head_dim, dtype, 500000.0)
+    _append(w, rng, sys_len)
+    lens = {0: sys_len}
+    pool = []
+    for L in rng.integers(len_lo, len_hi + 1, size=n_pool):
+        m = _append(w, rng, int(L))
+        lens[m] = int(L)
+        pool.append(m)
+    tails = [_append(w, rng, tail0, reserve=tail0 + n_steps) for _ in range(n_calls)]
+    layouts = []
+    for c in range(n_calls):
+        chosen = [pool[int(i)] for i in rng.permutation(n_pool)[:n_sel]]
+        sel = [(0, 0)]
+        s = sys_len
+        for m in chosen:
+            s += int(rng.integers(0, 33))
+            sel.append((m, s))
+            s += lens[m]
+        layouts.append((sel, s))
+    for step in range(n_steps + 1):
+        if step > 0:
+            _extend(w, rng, tails)
+        _attend(w, rng, [Call(sel, tails[c], s, 1, None) for c, (sel, s) in enumerate(layouts)])
     return w
 
 

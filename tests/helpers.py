@@ -10,6 +10,10 @@ def cache_lists(w, upto_event=None):
         if e.kind == "append":
             ks.append(e.k)      # float32 holding exactly representable values; the
             vs.append(e.v)      # oracle widens what it gathers to fp64
+        elif e.kind == "extend":                    # one more token for each listed message
+            for j, m in enumerate(e.msgs):
+                ks[m] = np.concatenate([ks[m], e.k[j:j + 1]], axis=0)
+                vs[m] = np.concatenate([vs[m], e.v[j:j + 1]], axis=0)
     return ks, vs
 
 
