@@ -181,6 +181,18 @@ int32_t pc_build_tables(pc_cache *c, const pc_call *call, int32_t *kv_slot, int3
 int32_t pc_resolve_call(pc_cache *c, const pc_call *call, int32_t *starts_out,
                         int32_t *self_start_out, int64_t *n_kv);
 
+/* Gives a message's reserved slots back (Sec. 2.4: the cache is a map from message id to
+ * physical span; a message no call will select again can make room).  Host bookkeeping
+ * only, nothing is enqueued: work already enqueued that reads the message is not
+ * disturbed by a later pc_append_message on the same stream that reuses the slots, but the
+ * caller must not reuse them from another stream before that work has finished.
+ * The id becomes unknown to every function (PC_ERR_BAD_MSG_ID) and is never given out
+ * again: ids keep counting up, and max_messages bounds the appends of a cache's lifetime.
+ * Allocation rule after frees: pc_append_message takes the first freed span (lowest slot)
+ * that holds the reserve rounded up to PC_SLOT_ALIGN, else the end of the used region;
+ * adjacent freed spans merge; a span freed at the end shrinks the used region. */
+int32_t pc_message_free(pc_cache *c, int32_t msg_id);
+
 /* Message and cache bookkeeping (Sec. 2.4: count of cached tokens, id -> span). */
 int32_t pc_message_info(pc_cache *c, int32_t msg_id, int32_t *len, int64_t *slot_start,
                         int32_t *reserved);

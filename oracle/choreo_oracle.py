@@ -53,6 +53,44 @@ def slot_starts(reserves: Sequence[int], align: int) -> List[int]:
     return starts
 
 
+class SlotModel:
+    """The same layout rule with messages that can be given back (an interface fact of the
+    library's header): a new message takes the lowest freed span that holds its reserve rounded
+    up to `align`, else the end of the used region; adjacent freed spans merge; a span freed at
+    the end of the used region shrinks it.  Plain bookkeeping over a list of (start, size)."""
+
+    def __init__(self, align: int):
+        self.align, self.end, self.free, self.span = align, 0, [], {}
+
+    def append(self, msg_id: int, reserve: int) -> int:
+        need = ((int(reserve) + self.align - 1) // self.align) * self.align
+        for i, (st, sz) in enumerate(self.free):
+            if sz >= need:
+                if sz == need:
+                    del self.free[i]
+                else:
+                    self.free[i] = (st + need, sz - need)
+                self.span[msg_id] = (st, need)
+                return st
+        st = self.end
+        self.end += need
+        self.span[msg_id] = (st, need)
+        return st
+
+    def release(self, msg_id: int) -> None:
+        st, sz = self.span.pop(msg_id)
+        spans = sorted(self.free + [(st, sz)])
+        merged = []
+        for a, n in spans:
+            if merged and merged[-1][0] + merged[-1][1] == a:
+                merged[-1] = (merged[-1][0], merged[-1][1] + n)
+            else:
+                merged.append((a, n))
+        if merged and merged[-1][0] + merged[-1][1] == self.end:
+            self.end = merged.pop()[0]
+        self.free = merged
+
+
 # ---------------------------------------------------------------------------
 # default offsets (Sec. 2.3: an omitted offset is the position right after the
 # end of the preceding parent).  Reading: "preceding" = the previous list entry;

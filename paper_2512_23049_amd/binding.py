@@ -74,6 +74,8 @@ def lib():
         L.pc_resolve_call.argtypes = [vp, C.POINTER(pc_call), C.POINTER(i32), C.POINTER(i32), C.POINTER(i64)]
         L.pc_message_info.restype = i32
         L.pc_message_info.argtypes = [vp, i32, C.POINTER(i32), C.POINTER(i64), C.POINTER(i32)]
+        L.pc_message_free.restype = i32
+        L.pc_message_free.argtypes = [vp, i32]
         L.pc_message_base.restype = i32
         L.pc_message_base.argtypes = [vp, i32, C.POINTER(i32)]
         L.pc_reposition.restype = i32
@@ -186,6 +188,9 @@ class Cache:
     def append_tokens_batch(self, msg_ids, k_ptr: int, v_ptr: int, stream: int = 0):
         arr = (C.c_int32 * max(len(msg_ids), 1))(*[int(m) for m in msg_ids])
         self._check(lib().pc_append_tokens_batch(self.h, arr, len(msg_ids), k_ptr, v_ptr, stream))
+
+    def message_free(self, msg_id: int):
+        self._check(lib().pc_message_free(self.h, msg_id))
 
     def message_base(self, msg_id: int) -> int:
         b = C.c_int32(0)

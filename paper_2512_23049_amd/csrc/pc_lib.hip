@@ -13,7 +13,8 @@
 
 namespace {
 
-struct HostMsg { int64_t slot_start; int32_t len; int32_t reserve; int32_t base_pos; };
+struct HostMsg { int64_t slot_start; int32_t len; int32_t reserve; int32_t base_pos; bool live; };
+struct FreeSpan { int64_t start, size; };            // freed slots, multiples of PC_SLOT_ALIGN
 
 struct StageSlot { void *host = nullptr; size_t cap = 0; hipEvent_t ev = nullptr; bool used = false; };
 
@@ -34,6 +35,7 @@ struct pc_cache {
     size_t esize = 0;
     float scale = 0.f;
     std::vector<HostMsg> msgs;
+    std::vector<FreeSpan> free_spans;                // sorted by start, neighbours merged, none touches next_slot
     int64_t next_slot = 0;
     // device
     void *storage = nullptr; bool owns_storage = false;
@@ -115,6 +117,8 @@ struct Resolved {
     int32_t tiles = 0;            // KV tiles incl. the new message
 };
 
+inline bool known(const pc_cache *c, int32_t m) { return m >= 0 && m < (int32_t)c->msgs.size() && c->msgs[(size_t)m].live; }
+
 int32_t resolve_call(pc_cache *c, const pc_call *call, int idx, Resolved &out)
 {
     if (!call) return fail(c, PC_ERR_INVALID_ARG, "call %d: null", idx);
@@ -122,12 +126,11 @@ int32_t resolve_call(pc_cache *c, const pc_call *call, int idx, Resolved &out)
         return fail(c, PC_ERR_INVALID_ARG, "call %d: bad parent list", idx);
     if (call->n_q < 1) return fail(c, PC_ERR_INVALID_ARG, "call %d: n_q = %d must be >= 1", idx, call->n_q);
     const int64_t maxp = c->cfg.max_position;
-    const int n_msgs = (int)c->msgs.size();
     out.sel.resize(call->n_sel);
     int64_t nxt = 0, n_kv = 0, tiles = 0;
     for (int e = 0; e < call->n_sel; ++e) {
         const int32_t m = call->sel[e].msg_id;
-        if (m < 0 || m >= n_msgs) return fail(c, PC_ERR_BAD_MSG_ID, "call %d: parent %d names unknown message %d", idx, e, m);
+        if (!known(c, m)) return fail(c, PC_ERR_BAD_MSG_ID, "call %d: parent %d names unknown message %d", idx, e, m);
         const int64_t len = c->msgs[m].len;
         const int64_t s = call->sel[e].start_pos == PC_POS_AUTO ? nxt : (int64_t)call->sel[e].start_pos;
         if (s < -maxp || s + len - 1 > maxp)
@@ -139,7 +142,7 @@ int32_t resolve_call(pc_cache *c, const pc_call *call, int idx, Resolved &out)
     out.self_msg = -1; out.self_len = 0;
     int64_t s_self = call->self_start == PC_POS_AUTO ? nxt : (int64_t)call->self_start;
     if (call->self_msg >= 0) {
-        if (call->self_msg >= n_msgs) return fail(c, PC_ERR_BAD_MSG_ID, "call %d: new message id %d unknown", idx, call->self_msg);
+        if (!known(c, call->self_msg)) return fail(c, PC_ERR_BAD_MSG_ID, "call %d: new message id %d unknown", idx, call->self_msg);
         out.self_msg = call->self_msg;
         out.self_len = c->msgs[call->self_msg].len;
         if (call->n_q > out.self_len)
@@ -314,8 +317,13 @@ int32_t pc_append_message(pc_cache *c, const void *k, const void *v, int32_t len
     if ((int64_t)c->msgs.size() >= c->cfg.max_messages)
         return fail(c, PC_ERR_NO_SPACE, "append: message table full (%d)", c->cfg.max_messages);
     const int32_t res = std::max(reserve, len);
-    const int64_t start = c->next_slot;
-    if (start + res > c->slots)
+    // first freed span that is large enough, else the end of the used region
+    const int64_t need = (int64_t)align_up((size_t)res, PC_SLOT_ALIGN);
+    int64_t start = c->next_slot;
+    size_t from_free = c->free_spans.size();
+    for (size_t i = 0; i < c->free_spans.size(); ++i)
+        if (c->free_spans[i].size >= need) { from_free = i; start = c->free_spans[i].start; break; }
+    if (from_free == c->free_spans.size() && start + res > c->slots)
         return fail(c, PC_ERR_NO_SPACE, "append: needs slots [%lld, %lld), capacity %lld", (long long)start,
                     (long long)(start + res), (long long)c->slots);
     const int id = (int)c->msgs.size();
@@ -326,8 +334,14 @@ int32_t pc_append_message(pc_cache *c, const void *k, const void *v, int32_t len
                          c->k_store, c->v_store, c->table_dev, id, st);
         PC_HIP(c, hipGetLastError());
     }
-    c->msgs.push_back({start, len, res, 0});
-    c->next_slot = (int64_t)align_up((size_t)(start + res), PC_SLOT_ALIGN);
+    c->msgs.push_back({start, len, res, 0, true});
+    if (from_free < c->free_spans.size()) {
+        FreeSpan &f = c->free_spans[from_free];
+        f.start += need; f.size -= need;
+        if (f.size == 0) c->free_spans.erase(c->free_spans.begin() + (long)from_free);
+    } else {
+        c->next_slot = start + need;
+    }
     *msg_id = id;
     return PC_OK;
 }
@@ -379,7 +393,7 @@ static int32_t append_token_items(pc_cache *c, const std::vector<int32_t> &ids, 
 int32_t pc_append_tokens(pc_cache *c, int32_t msg_id, const void *k, const void *v, int32_t n, void *stream)
 {
     if (!c) return PC_ERR_INVALID_ARG;
-    if (msg_id < 0 || msg_id >= (int)c->msgs.size()) return fail(c, PC_ERR_BAD_MSG_ID, "append_tokens: unknown message %d", msg_id);
+    if (!known(c, msg_id)) return fail(c, PC_ERR_BAD_MSG_ID, "append_tokens: unknown message %d", msg_id);
     if (n < 1) return fail(c, PC_ERR_INVALID_ARG, "append_tokens: n = %d must be >= 1", n);
     if (!c->host_only && (!k || !v)) return fail(c, PC_ERR_INVALID_ARG, "append_tokens: null k or v");
     return append_token_items(c, std::vector<int32_t>((size_t)n, msg_id), k, v, (hipStream_t)stream);
@@ -394,7 +408,7 @@ int32_t pc_append_tokens_batch(pc_cache *c, const int32_t *msg_ids, int32_t n_ms
     std::vector<char> listed(c->msgs.size(), 0);
     for (int j = 0; j < n_msgs; ++j) {
         const int32_t m = msg_ids[j];
-        if (m < 0 || m >= (int)c->msgs.size()) return fail(c, PC_ERR_BAD_MSG_ID, "append_tokens_batch: unknown message %d", m);
+        if (!known(c, m)) return fail(c, PC_ERR_BAD_MSG_ID, "append_tokens_batch: unknown message %d", m);
         if (listed[(size_t)m]) return fail(c, PC_ERR_INVALID_ARG, "append_tokens_batch: message %d listed twice", m);
         listed[(size_t)m] = 1;
     }
@@ -416,7 +430,7 @@ int32_t pc_resolve_call(pc_cache *c, const pc_call *call, int32_t *starts_out, i
 int32_t pc_message_info(pc_cache *c, int32_t msg_id, int32_t *len, int64_t *slot_start, int32_t *reserved)
 {
     if (!c) return PC_ERR_INVALID_ARG;
-    if (msg_id < 0 || msg_id >= (int)c->msgs.size()) return fail(c, PC_ERR_BAD_MSG_ID, "unknown message %d", msg_id);
+    if (!known(c, msg_id)) return fail(c, PC_ERR_BAD_MSG_ID, "unknown message %d", msg_id);
     if (len) *len = c->msgs[msg_id].len;
     if (slot_start) *slot_start = c->msgs[msg_id].slot_start;
     if (reserved) *reserved = c->msgs[msg_id].reserve;
@@ -426,7 +440,7 @@ int32_t pc_message_info(pc_cache *c, int32_t msg_id, int32_t *len, int64_t *slot
 int32_t pc_message_base(pc_cache *c, int32_t msg_id, int32_t *base_pos)
 {
     if (!c) return PC_ERR_INVALID_ARG;
-    if (msg_id < 0 || msg_id >= (int)c->msgs.size()) return fail(c, PC_ERR_BAD_MSG_ID, "unknown message %d", msg_id);
+    if (!known(c, msg_id)) return fail(c, PC_ERR_BAD_MSG_ID, "unknown message %d", msg_id);
     if (base_pos) *base_pos = c->msgs[msg_id].base_pos;
     return PC_OK;
 }
@@ -434,7 +448,7 @@ int32_t pc_message_base(pc_cache *c, int32_t msg_id, int32_t *base_pos)
 int32_t pc_reposition(pc_cache *c, int32_t msg_id, int32_t new_base, void *stream)
 {
     if (!c) return PC_ERR_INVALID_ARG;
-    if (msg_id < 0 || msg_id >= (int)c->msgs.size()) return fail(c, PC_ERR_BAD_MSG_ID, "reposition: unknown message %d", msg_id);
+    if (!known(c, msg_id)) return fail(c, PC_ERR_BAD_MSG_ID, "reposition: unknown message %d", msg_id);
     if (new_base > c->cfg.max_position || new_base < -c->cfg.max_position)
         return fail(c, PC_ERR_INVALID_ARG, "reposition: position %d outside [-%d, %d]", new_base, c->cfg.max_position,
                     c->cfg.max_position);
@@ -449,6 +463,32 @@ int32_t pc_reposition(pc_cache *c, int32_t msg_id, int32_t new_base, void *strea
         PC_HIP(c, hipGetLastError());
     }
     m.base_pos = new_base;
+    return PC_OK;
+}
+
+int32_t pc_message_free(pc_cache *c, int32_t msg_id)
+{
+    if (!c) return PC_ERR_INVALID_ARG;
+    if (!known(c, msg_id)) return fail(c, PC_ERR_BAD_MSG_ID, "free: unknown message %d", msg_id);
+    HostMsg &m = c->msgs[(size_t)msg_id];
+    m.live = false;
+    FreeSpan f{m.slot_start, (int64_t)align_up((size_t)m.reserve, PC_SLOT_ALIGN)};
+    auto &fs = c->free_spans;
+    size_t i = 0;
+    while (i < fs.size() && fs[i].start < f.start) ++i;
+    fs.insert(fs.begin() + (long)i, f);
+    if (i + 1 < fs.size() && fs[i].start + fs[i].size == fs[i + 1].start) {           // merge with the span behind
+        fs[i].size += fs[i + 1].size;
+        fs.erase(fs.begin() + (long)i + 1);
+    }
+    if (i > 0 && fs[i - 1].start + fs[i - 1].size == fs[i].start) {                   // ... and the one in front
+        fs[i - 1].size += fs[i].size;
+        fs.erase(fs.begin() + (long)i);
+    }
+    if (!fs.empty() && fs.back().start + fs.back().size == c->next_slot) {            // freed at the end: the used region shrinks
+        c->next_slot = fs.back().start;
+        fs.pop_back();
+    }
     return PC_OK;
 }
 

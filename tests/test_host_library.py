@@ -173,3 +173,49 @@ def test_reposition_bookkeeping_on_a_host_only_cache(pc):
     with pytest.raises(pc.PcError) as ei:
         c.reposition(9, 0)
     assert ei.value.code == pc.PC_ERR_BAD_MSG_ID
+
+
+def test_free_and_reuse_follow_the_slot_model(pc):
+    rng = np.random.default_rng(7)
+    c = host_cache(pc, capacity_tokens=1 << 16, max_messages=400)
+    model = orc.SlotModel(pc.PC_SLOT_ALIGN)
+    live = []
+    for step in range(300):
+        if live and rng.random() < 0.4:
+            m = live.pop(int(rng.integers(0, len(live))))
+            c.message_free(m)
+            model.release(m)
+            with pytest.raises(pc.PcError) as ei:
+                c.message_info(m)
+            assert ei.value.code == pc.PC_ERR_BAD_MSG_ID
+        else:
+            L = int(rng.integers(1, 200))
+            r = int(rng.integers(0, 260))
+            m = c.append_message(0, 0, L, r)
+            assert c.message_info(m)[1] == model.append(m, max(L, r))
+            live.append(m)
+        assert c.cache_info()[1] == model.end
+    # a freed id is unknown everywhere, and is not handed out again
+    dead = [m for m in range(c.cache_info()[0]) if m not in live][0]
+    for fn in (lambda: c.message_free(dead), lambda: c.reposition(dead, 0), lambda: c.append_tokens(dead, 0, 0, 1),
+               lambda: c.resolve_call(Call([(dead, 0)], -1, 0, 1, None)),
+               lambda: c.resolve_call(Call([], dead, 0, 1, None))):
+        with pytest.raises(pc.PcError) as ei:
+            fn()
+        assert ei.value.code == pc.PC_ERR_BAD_MSG_ID
+    assert c.append_message(0, 0, 1) == c.cache_info()[0] - 1
+
+
+def test_growing_messages_on_a_host_only_cache(pc):
+    c = host_cache(pc)
+    a = c.append_message(0, 0, 3, 10)
+    b = c.append_message(0, 0, 1, 4)
+    c.append_tokens(a, 0, 0, 7)
+    c.append_tokens_batch([b], 0, 0)
+    assert c.message_info(a)[0] == 10 and c.message_info(b)[0] == 2
+    with pytest.raises(pc.PcError) as ei:
+        c.append_tokens_batch([a, b], 0, 0)                  # a is full: nothing may change
+    assert ei.value.code == pc.PC_ERR_NO_SPACE
+    assert c.message_info(b)[0] == 2
+    starts, s_self, n = c.resolve_call(Call([(a, POS_AUTO)], b, POS_AUTO, 2, None))
+    assert starts == [0] and s_self == 10 and n == 12

@@ -89,6 +89,29 @@ def test_position_updates_compose():
     assert np.abs(n0 - n1).max() < 1e-10
 
 
+def test_slot_model_hand_worked_sequence():
+    # hand-worked with align 32: A(40)->[0,64) B(10)->[64,96) C(100)->[96,224) D(32)->[224,256)
+    m = orc.SlotModel(32)
+    assert [m.append(i, r) for i, r in enumerate([40, 10, 100, 32])] == [0, 64, 96, 224]
+    m.release(1)                                   # free [64,96)
+    assert m.append(4, 33) == 256                  # needs 64: the hole is too small, goes to the end -> [256,320)
+    assert m.append(5, 32) == 64                   # fits the hole exactly
+    m.release(0); m.release(5)                     # [0,64) + [64,96) merge into [0,96)
+    assert m.free == [(0, 96)]
+    assert m.append(6, 70) == 0                    # takes 96 of it
+    m.release(4)                                   # the last span: the used region shrinks to 256
+    assert m.end == 256 and m.free == []
+    m.release(3)                                   # now D is last: shrinks to 224
+    assert m.end == 224
+    m.release(2)                                   # C too: 96
+    assert m.end == 96 and m.free == []
+    assert m.append(7, 1) == 96
+    # without any release the model is the bump rule
+    m2 = orc.SlotModel(32)
+    rs = [3, 64, 65, 1, 200]
+    assert [m2.append(i, r) for i, r in enumerate(rs)] == orc.slot_starts(rs, 32)
+
+
 # ---------------------------------------------------------------- brute force
 @pytest.mark.parametrize("seed", [0, 1, 2])
 def test_brute_force_agrees_on_tiny_inputs(seed):
