@@ -154,7 +154,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--skip-extras", action="store_true")
     ap.add_argument("--skip-cpu", action="store_true")
-    ap.add_argument("--only", default="", help="comma list of sections: decode,long,rounds,loop,reposition")
+    ap.add_argument("--only", default="", help="comma list of sections: decode,long,rounds,baseline,loop,reposition")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="also launch one plain device copy of this many MiB (reference for scaling rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE counters)")
@@ -287,6 +287,46 @@ def main():
             "workload": "configs[3]: 8 agents x 6 rounds, 48 appends of 256 tokens interleaved with 6 batched prefills",
             "ms_per_sequence": sec4 * 1e3, "tflops_incl_appends": f4 / sec4 / 1e12, "flops": f4, "reps": reps}
         del w4
+
+    # ------------------------------------------------ attention work of a prefix-caching baseline
+    if not args.skip_extras and (not only or "baseline" in only):
+        def run_sequence(w, reps):
+            dw_ = harness.DeviceWorkload(w)
+            caches = [harness.make_cache(w) for _ in range(reps + 1)]
+            dw_.run(caches[0], want_lse=False)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for c_ in caches[1:]:
+                dw_.run(c_, want_lse=False)
+            torch.cuda.synchronize()
+            dt = (time.perf_counter() - t0) / reps
+            for c_ in caches:
+                c_.close()
+            fl, toks = 0.0, 0
+            for i, e in enumerate(w.events):
+                if e.kind == "attend":
+                    lens = w.message_lengths(upto_event=i)
+                    for c in e.calls:
+                        n_par = sum(lens[m] for m, _ in c.sel)
+                        L = lens[c.self_msg]
+                        fl += 4.0 * w.head_dim * w.n_q_heads * sum(n_par + L - c.n_q + r + 1 for r in range(c.n_q))
+                elif e.kind == "append":
+                    toks += int(e.k.shape[0])
+            return dt, fl, toks
+        comp = {}
+        for name, (na, nr) in {"8 agents x 6 rounds (configs[3])": (8, 6), "3 agents x 3 rounds (the paper's parallel debate)": (3, 3)}.items():
+            t_c, f_c, k_c = run_sequence(gen.multi_agent_rounds(n_agents=na, n_rounds=nr), 5)
+            t_b, f_b, k_b = run_sequence(gen.prefix_cache_baseline_rounds(n_agents=na, n_rounds=nr), 5)
+            comp[name] = {"choreographed_ms": t_c * 1e3, "baseline_ms": t_b * 1e3, "time_ratio": t_b / t_c,
+                          "choreographed_attention_gflop": f_c / 1e9, "baseline_attention_gflop": f_b / 1e9,
+                          "flop_ratio": f_b / f_c, "choreographed_tokens_encoded": k_c, "baseline_tokens_encoded": k_b}
+        line.setdefault("extras", {})["prefix_cache_baseline"] = {
+            "workload": "attention and cache-append work only, 256-token messages: choreographed rounds (each agent "
+                        "prefills its new message over the cached messages of all earlier rounds) against a prefix-caching "
+                        "baseline (each agent keeps its own prompt as prefix and encodes the other agents' last-round "
+                        "messages again with its new one); the model's other layers, which the baseline also runs again "
+                        "for every re-encoded token, are not part of this path",
+            **comp}
 
     # ------------------------------------------------ decode loop: tails growing one token per step
     if not args.skip_extras and (not only or "loop" in only):

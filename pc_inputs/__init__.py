@@ -18,5 +18,6 @@ from .generators import (  # noqa: F401
     multi_agent_rounds,
     long_context,
     decode_loop,
+    prefix_cache_baseline_rounds,
     small_random,
 )

@@ -208,6 +208,31 @@ def multi_agent_rounds(seed: int = 4, n_agents: int = 8, n_rounds: int = 6, msg_
 
 
 # --------------------------------------------------------------------------
+# The attention work a prefix-caching baseline does for the same rounds (Sec. 3.1 "A
+# Baseline Approach", Sec. 5 "Performance"): an agent's prompt keeps its own earlier
+# prompt as a cached prefix, but the messages the OTHER agents wrote in the last round
+# are new text in it and are encoded again, followed by its own new message.  So in
+# round r agent a appends one chunk of (n_agents - 1) * msg_len re-encoded tokens plus
+# msg_len new ones (round 0: only its own msg_len) and all of them are causal query rows
+# over the agent's private prefix.  Only shapes matter here; values are random.
+# --------------------------------------------------------------------------
+def prefix_cache_baseline_rounds(seed: int = 7, n_agents: int = 8, n_rounds: int = 6, msg_len: int = 256,
+                                 n_q_heads: int = 32, n_kv_heads: int = 8, head_dim: int = 128,
+                                 dtype: str = "bf16") -> Workload:
+    rng = np.random.default_rng(seed)
+    w = Workload("prefix_cache_baseline_rounds", n_q_heads, n_kv_heads, head_dim, dtype, 500000.0)
+    chunks = [[] for _ in range(n_agents)]                 # message ids of each agent's private prompt
+    for r in range(n_rounds):
+        n_new = msg_len if r == 0 else n_agents * msg_len
+        new_ids = [_append(w, rng, n_new) for _ in range(n_agents)]
+        calls = [Call([(m, POS_AUTO) for m in chunks[a]], new_ids[a], POS_AUTO, n_new, None) for a in range(n_agents)]
+        _attend(w, rng, calls)
+        for a in range(n_agents):
+            chunks[a].append(new_ids[a])
+    return w
+
+
+# --------------------------------------------------------------------------
 # config 5: long-context 70B-shaped, 32 decode calls + one causal prefill
 # --------------------------------------------------------------------------
 def long_context(seed: int = 5, n_msgs: int = 512, len_lo: int = 64, len_hi: int = 256,

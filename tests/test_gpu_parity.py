@@ -261,3 +261,9 @@ def test_shift_and_permutation_on_gpu(hip):
     assert np.abs(o[0] - o[1]).max() <= 2e-2 and np.abs(o[0] - o[1]).mean() <= 1e-3
     assert np.abs(o[0] - o[2]).max() <= 2e-2 and np.abs(o[0] - o[2]).mean() <= 1e-3
     cache.close()
+
+
+def test_prefix_cache_baseline_shape_scaled(hip):
+    # the comparator workload of bench.py (long causal new messages over a private prefix), small
+    w = gen.prefix_cache_baseline_rounds(n_agents=3, n_rounds=3, msg_len=40, n_q_heads=8, n_kv_heads=2)
+    run_and_compare(hip, w)
