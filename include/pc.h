@@ -165,6 +165,11 @@ int32_t pc_attend(pc_cache *c, const pc_call *calls, int32_t n_calls,
  * Errors: unknown id, |new_base| > max_position.  new_base equal to the current base
  * launches nothing. */
 int32_t pc_reposition(pc_cache *c, int32_t msg_id, int32_t new_base, void *stream);
+/* The same for n_msgs distinct messages in one launch (msg_ids, new_bases: host lists,
+ * copied before return).  Nothing is enqueued if any entry is in error (also: an id
+ * listed twice). */
+int32_t pc_reposition_batch(pc_cache *c, const int32_t *msg_ids, const int32_t *new_bases,
+                            int32_t n_msgs, void *stream);
 
 /* Parity/debug: the expanded gather table and position map of one call, in list
  * order then the new message: kv_slot[i] = physical slot, kv_pos[i] = logical

@@ -80,6 +80,8 @@ def lib():
         L.pc_message_base.argtypes = [vp, i32, C.POINTER(i32)]
         L.pc_reposition.restype = i32
         L.pc_reposition.argtypes = [vp, i32, i32, vp]
+        L.pc_reposition_batch.restype = i32
+        L.pc_reposition_batch.argtypes = [vp, C.POINTER(i32), C.POINTER(i32), i32, vp]
         L.pc_cache_info.restype = i32
         L.pc_cache_info.argtypes = [vp, C.POINTER(i32), C.POINTER(i64), C.POINTER(i64)]
         L.pc_profile_enable.restype = i32
@@ -199,6 +201,12 @@ class Cache:
 
     def reposition(self, msg_id: int, new_base: int, stream: int = 0):
         self._check(lib().pc_reposition(self.h, msg_id, new_base, stream))
+
+    def reposition_batch(self, msg_ids, new_bases, stream: int = 0):
+        n = len(msg_ids)
+        ids = (C.c_int32 * max(n, 1))(*[int(m) for m in msg_ids])
+        bases = (C.c_int32 * max(n, 1))(*[int(b) for b in new_bases])
+        self._check(lib().pc_reposition_batch(self.h, ids, bases, n, stream))
 
     def cache_info(self):
         n, used, cap = C.c_int32(0), C.c_int64(0), C.c_int64(0)

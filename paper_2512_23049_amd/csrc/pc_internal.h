@@ -26,6 +26,16 @@ struct PcTokenItem {
     int32_t new_len;          // the message's length once this token is in
 };
 
+// One message of a batched position update (staged by the host).
+struct PcMoveItem {
+    int32_t msg;
+    int32_t slot_start;
+    int32_t len;
+    int32_t delta;            // positions the stored keys are turned by
+    int32_t new_base;
+    int32_t pad[3];
+};
+
 // One call of a batch as staged by the host.
 struct PcCallDesc {
     int32_t sel_off;          // first entry in the packed (msg, start) list

@@ -18,6 +18,10 @@ void pc_launch_reposition(int dtype, int len, int n_kv_heads, int D, int64_t slo
                           int new_base, const double *inv_freq, void *k_store, PcMsgEntry *table, int msg_id,
                           hipStream_t st);
 
+// the same for a staged list of messages, one launch (blockIdx.y = message)
+void pc_launch_reposition_batch(int dtype, const PcMoveItem *items, int n_items, int n_kv_heads, int D, int64_t slots,
+                                const double *inv_freq, void *k_store, PcMsgEntry *table, hipStream_t st);
+
 void pc_launch_build_plan(const PcCallDesc *calls, int n_calls, const int2 *sel, const int32_t *q_pos,
                           const PcMsgEntry *table, const double *inv_freq, int half, int total_seg,
                           int total_q, PcSegment *segs, int32_t *seg_kvoff, float2 *rot_seg,

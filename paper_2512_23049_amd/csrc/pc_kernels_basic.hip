@@ -258,6 +258,61 @@ void pc_launch_reposition(int dtype, int len, int n_kv_heads, int D, int64_t slo
                                                           (float *)k_store, table, msg_id);
 }
 
+// Batched form: blockIdx.y names the message, the blocks of a row of the grid walk its
+// (token, KV head, frequency pair) triples with a grid stride.
+template <typename T>
+__global__ __launch_bounds__(256) void pc_reposition_batch_kernel(
+    const PcMoveItem *__restrict__ items, int n_kv_heads, int D, int64_t slots,
+    const double *__restrict__ inv_freq, T *__restrict__ k_store, PcMsgEntry *__restrict__ table)
+{
+    __shared__ float2 s_lut[64];
+    const PcMoveItem it = items[blockIdx.y];
+    const int half = D / 2;
+    if ((int)threadIdx.x < half) {
+        double s, c;
+        sincos((double)it.delta * inv_freq[threadIdx.x], &s, &c);
+        s_lut[threadIdx.x] = make_float2((float)c, (float)s);
+    }
+    __syncthreads();
+    if (blockIdx.x == 0 && threadIdx.x == 0) table[it.msg].base_pos = it.new_base;
+    const int per_row = half / 2;
+    const int64_t total = (int64_t)it.len * n_kv_heads * per_row;
+    for (int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; tid < total; tid += (int64_t)gridDim.x * blockDim.x) {
+        const int i0 = 2 * (int)(tid % per_row);
+        const int h = (int)((tid / per_row) % n_kv_heads);
+        const int t = (int)(tid / ((int64_t)per_row * n_kv_heads));
+        const float2 r0 = s_lut[i0], r1 = s_lut[i0 + 1];
+        T *row = k_store + ((int64_t)h * slots + it.slot_start + t) * D;
+        if constexpr (sizeof(T) == 2) {
+            using P = Pair2<__hip_bfloat16>;
+            const uint32_t lo = *reinterpret_cast<const uint32_t *>(row + i0);
+            const uint32_t hi = *reinterpret_cast<const uint32_t *>(row + half + i0);
+            const float a0 = P::lo(lo), a1 = P::hi(lo), b0 = P::lo(hi), b1 = P::hi(hi);
+            *reinterpret_cast<uint32_t *>(row + i0) = P::pack(a0 * r0.x - b0 * r0.y, a1 * r1.x - b1 * r1.y);
+            *reinterpret_cast<uint32_t *>(row + half + i0) = P::pack(a0 * r0.y + b0 * r0.x, a1 * r1.y + b1 * r1.x);
+        } else {
+            const float a0 = row[i0], a1 = row[i0 + 1], b0 = row[half + i0], b1 = row[half + i0 + 1];
+            row[i0] = a0 * r0.x - b0 * r0.y; row[i0 + 1] = a1 * r1.x - b1 * r1.y;
+            row[half + i0] = a0 * r0.y + b0 * r0.x; row[half + i0 + 1] = a1 * r1.y + b1 * r1.x;
+        }
+    }
+}
+
+void pc_launch_reposition_batch(int dtype, const PcMoveItem *items, int n_items, int n_kv_heads, int D, int64_t slots,
+                                const double *inv_freq, void *k_store, PcMsgEntry *table, hipStream_t st)
+{
+    for (int first = 0; first < n_items; first += 65535) {            // grid.y is limited to 65535
+        const int n = n_items - first < 65535 ? n_items - first : 65535;
+        dim3 grid(8, (unsigned)n);                       // 8 blocks of 256 threads per message
+        if (dtype == 1)
+            pc_reposition_batch_kernel<uint16_t><<<grid, 256, 0, st>>>(items + first, n_kv_heads, D, slots, inv_freq,
+                                                                       (uint16_t *)k_store, table);
+        else
+            pc_reposition_batch_kernel<float><<<grid, 256, 0, st>>>(items + first, n_kv_heads, D, slots, inv_freq,
+                                                                    (float *)k_store, table);
+    }
+}
+
 // ----------------------------------------------------------------------------------
 // K2: plan builder.  Blocks [0, n_calls): per call, look each listed message up in the
 // device message table and scan lengths into the segment list (Sec. 2.4 "Dynamic

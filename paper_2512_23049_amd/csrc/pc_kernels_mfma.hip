@@ -7,9 +7,10 @@
 // MFMA (O^T = V^T . P^T) wants for its B operand.  V is stored key-transposed in groups of
 // 8 slots, so the A operand of the second MFMA is one 16-byte load per lane.
 //
-// Keys are stored turned to their in-message index t; a message placed at start s then
-// needs the query turned by (q_pos - s): <R(p)q, R(s+t)k> = <R(p-s)q, R(t)k>.  The query is
-// turned once by p (table rot_q) and once more per segment by -s (table rot_seg).
+// Keys are stored turned to b + t (in-message index t, base b = 0 unless the message was
+// repositioned); a message placed at start s then needs the query turned by (q_pos - s + b):
+// <R(p)q, R(s+t)k> = <R(p-s+b)q, R(b+t)k>.  The query is turned once by p (table rot_q) and
+// once more per segment by -(s - b) (table rot_seg).
 #include "pc_mfma_common.h"
 
 // ----------------------------------------------------------------------------------------

@@ -17,22 +17,29 @@
 // moved its reference the scores are not shifted at all, so a score costs one v_exp, one add
 // and half a convert.
 //
-// Overlap.  The two waves that share a SIMD run the same work in different rotations: waves
-// 0-3 do scores(i), softmax(i), P.V(i) in iteration i, waves 4-7 do P.V(i-1), scores(i),
-// softmax(i), so that one wave's softmax (vector ALU) runs beside the other's MFMAs.
+// Overlap.  Every wave runs a software pipeline over the tiles in which the vector ALU work of
+// the softmax sits a few instructions behind each MFMA: iteration i issues the eight score
+// MFMAs of tile i+1 beside 12 of tile i's 16 exponentials, then the eight P.V MFMAs of tile i
+// beside the last four exponentials, the column maximum of tile i+1 and the test whether the
+// reference has to move.  A wave that issues about four vector instructions behind each MFMA
+// runs close to the MFMA-only rate; separate MFMA and vector phases, even on the two waves
+// of a SIMD in opposite order, overlap far less.  Rare work (a segment change, a ragged or
+// causal tile, a moving reference) is laid out off the hot path.
 //
 // Staging.  K and V tiles go global -> LDS directly (global_load_lds, 16 bytes per lane, no
-// staging registers) into rings of 5 slots; K(i+4) and V(i+3) are requested at the top of
-// iteration i and only K(i+2), V(i+1) must have landed at its closing barrier, so a request
-// has two to three iterations to complete.  A direct load writes 1 KB of consecutive LDS per
-// wave, so K rows cannot be padded; instead the 16-byte chunks of row r are stored at chunk
-// position (c ^ (r & 15)), which keeps the fragment reads (16 rows x one logical chunk) free
-// of bank conflicts.  Which tile comes next (physical slot, in-message index, segment, ragged
-// length) is read from the per-call tile table the plan builder wrote, with scalar loads
-// issued five tiles ahead.
+// staging registers) into rings of 5 slots; K(i+5) and V(i+4) are requested inside iteration
+// i's two MFMA runs (not all at one point: the requests of eight waves would queue up) and
+// K(i+3), V(i+1) must have landed at its closing barrier, so a request has two to three
+// iterations to complete.  A direct load writes 1 KB of consecutive LDS per wave, so K rows
+// cannot be padded; instead the 16-byte chunks of row r are stored at chunk position
+// (c ^ (r & 15)), which keeps the fragment reads (16 rows x one logical chunk) free of bank
+// conflicts.  Which tile comes next (physical slot, in-message index, segment, ragged length)
+// is read from the per-call tile table the plan builder wrote, with a scalar load requested
+// at the top of an iteration and awaited between its two MFMA runs.
 //
-// Position: keys are stored turned to their in-message index; per segment the queries are
-// turned by (q_pos - segment start) from an fp32 master copy, half in registers and half in
+// Position: keys are stored turned to base + in-message index (base 0 unless the message was
+// repositioned); whenever start - base changes from one segment to the next the queries are
+// turned by (q_pos - start + base) from an fp32 master copy, half in registers and half in
 // LDS (Sec. 2.4 "Position Updates", applied to the query side).  The kernel uses no
 // accumulation registers on purpose: with all 256 registers of a wave in one file the MFMA
 // results are read by the vector ALU without copies.

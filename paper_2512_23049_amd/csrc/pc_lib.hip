@@ -43,7 +43,7 @@ struct pc_cache {
     PcMsgEntry *table_dev = nullptr;
     double *inv_freq_dev = nullptr;
     void *ws = nullptr; size_t ws_cap = 0;
-    PcTokenItem *tok_dev = nullptr; size_t tok_cap = 0;   // staged items of pc_append_tokens*
+    void *tok_dev = nullptr; size_t tok_cap = 0;          // staged items of pc_append_tokens* / pc_reposition_batch (bytes)
     StageSlot stage[N_STAGE]; int stage_next = 0;
     // profiling
     bool prof = false;
@@ -346,6 +346,28 @@ int32_t pc_append_message(pc_cache *c, const void *k, const void *v, int32_t len
     return PC_OK;
 }
 
+// small host-built item lists go through the pinned ring into one device buffer that grows on demand
+static int32_t stage_items(pc_cache *c, const void *items, size_t bytes, hipStream_t st)
+{
+    if (bytes > c->tok_cap) {
+        PC_HIP(c, hipStreamSynchronize(st));
+        PC_HIP(c, hipDeviceSynchronize());
+        if (c->tok_dev) PC_HIP(c, hipFree(c->tok_dev));
+        c->tok_dev = nullptr; c->tok_cap = 0;
+        const size_t cap = std::max<size_t>(1 << 16, bytes * 2);
+        PC_HIP(c, hipMalloc(&c->tok_dev, cap));
+        c->tok_cap = cap;
+    }
+    StageSlot *slot = nullptr;
+    const int32_t rc = stage_acquire(c, bytes, &slot);
+    if (rc != PC_OK) return rc;
+    std::memcpy(slot->host, items, bytes);
+    PC_HIP(c, hipMemcpyAsync(c->tok_dev, slot->host, bytes, hipMemcpyHostToDevice, st));
+    PC_HIP(c, hipEventRecord(slot->ev, st));
+    slot->used = true;
+    return PC_OK;
+}
+
 // shared by pc_append_tokens and pc_append_tokens_batch: token j of k, v goes to message ids[j]
 // (ids sorted by message with a message's tokens in order; validated by the callers)
 static int32_t append_token_items(pc_cache *c, const std::vector<int32_t> &ids, const void *k, const void *v, hipStream_t st)
@@ -365,24 +387,10 @@ static int32_t append_token_items(pc_cache *c, const std::vector<int32_t> &ids, 
         items[(size_t)j] = PcTokenItem{ids[j], (int32_t)(m.slot_start + t), m.base_pos + t, m.len + grown[(size_t)ids[j]]};
     }
     if (!c->host_only) {
-        if ((size_t)n > c->tok_cap) {
-            PC_HIP(c, hipStreamSynchronize(st));
-            PC_HIP(c, hipDeviceSynchronize());
-            if (c->tok_dev) PC_HIP(c, hipFree(c->tok_dev));
-            c->tok_dev = nullptr; c->tok_cap = 0;
-            const size_t cap = std::max<size_t>(4096, (size_t)n * 2);
-            PC_HIP(c, hipMalloc((void **)&c->tok_dev, cap * sizeof(PcTokenItem)));
-            c->tok_cap = cap;
-        }
-        StageSlot *slot = nullptr;
-        const int32_t rc = stage_acquire(c, sizeof(PcTokenItem) * (size_t)n, &slot);
+        const int32_t rc = stage_items(c, items.data(), sizeof(PcTokenItem) * (size_t)n, st);
         if (rc != PC_OK) return rc;
-        std::memcpy(slot->host, items.data(), sizeof(PcTokenItem) * (size_t)n);
-        PC_HIP(c, hipMemcpyAsync(c->tok_dev, slot->host, sizeof(PcTokenItem) * (size_t)n, hipMemcpyHostToDevice, st));
-        PC_HIP(c, hipEventRecord(slot->ev, st));
-        slot->used = true;
         ProfScope ps(c, 0, st);
-        pc_launch_append_tokens(c->cfg.dtype, c->tok_dev, n, k, v, c->cfg.n_kv_heads, c->D, c->slots, c->inv_freq_dev,
+        pc_launch_append_tokens(c->cfg.dtype, (const PcTokenItem *)c->tok_dev, n, k, v, c->cfg.n_kv_heads, c->D, c->slots, c->inv_freq_dev,
                                 c->k_store, c->v_store, c->table_dev, st);
         PC_HIP(c, hipGetLastError());
     }
@@ -463,6 +471,37 @@ int32_t pc_reposition(pc_cache *c, int32_t msg_id, int32_t new_base, void *strea
         PC_HIP(c, hipGetLastError());
     }
     m.base_pos = new_base;
+    return PC_OK;
+}
+
+int32_t pc_reposition_batch(pc_cache *c, const int32_t *msg_ids, const int32_t *new_bases, int32_t n_msgs, void *stream)
+{
+    if (!c) return PC_ERR_INVALID_ARG;
+    if (n_msgs < 0 || (n_msgs > 0 && (!msg_ids || !new_bases))) return fail(c, PC_ERR_INVALID_ARG, "reposition_batch: bad lists");
+    std::vector<PcMoveItem> items;
+    std::vector<char> listed(c->msgs.size(), 0);
+    for (int j = 0; j < n_msgs; ++j) {
+        const int32_t m = msg_ids[j];
+        if (!known(c, m)) return fail(c, PC_ERR_BAD_MSG_ID, "reposition_batch: unknown message %d", m);
+        if (listed[(size_t)m]) return fail(c, PC_ERR_INVALID_ARG, "reposition_batch: message %d listed twice", m);
+        listed[(size_t)m] = 1;
+        if (new_bases[j] > c->cfg.max_position || new_bases[j] < -c->cfg.max_position)
+            return fail(c, PC_ERR_INVALID_ARG, "reposition_batch: position %d outside [-%d, %d]", new_bases[j],
+                        c->cfg.max_position, c->cfg.max_position);
+        const HostMsg &hm = c->msgs[(size_t)m];
+        const int64_t delta = (int64_t)new_bases[j] - hm.base_pos;
+        if (delta != 0) items.push_back(PcMoveItem{m, (int32_t)hm.slot_start, hm.len, (int32_t)delta, new_bases[j], {0, 0, 0}});
+    }
+    if (!items.empty() && !c->host_only) {
+        hipStream_t st = (hipStream_t)stream;
+        const int32_t rc = stage_items(c, items.data(), sizeof(PcMoveItem) * items.size(), st);
+        if (rc != PC_OK) return rc;
+        ProfScope ps(c, 7, st);
+        pc_launch_reposition_batch(c->cfg.dtype, (const PcMoveItem *)c->tok_dev, (int)items.size(), c->cfg.n_kv_heads, c->D,
+                                   c->slots, c->inv_freq_dev, c->k_store, c->table_dev, st);
+        PC_HIP(c, hipGetLastError());
+    }
+    for (const PcMoveItem &it : items) c->msgs[(size_t)it.msg].base_pos = it.new_base;
     return PC_OK;
 }
 

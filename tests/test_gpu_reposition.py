@@ -108,6 +108,40 @@ def test_parents_at_their_assigned_starts(hip):
     compare(w, run_with_moves(hip, w, moves), "parents at their starts")
 
 
+def test_batched_moves(hip):
+    """All messages moved in one launch, twice (the second batch leaves some where they are)."""
+    import torch
+    w = gen.small_random(37, dtype="bf16")
+    rng = np.random.default_rng(37)
+    cache = hip.make_cache(w, max_position=1 << 20)
+    dw = hip.DeviceWorkload(w)
+    res = []
+    for s in dw.steps:
+        if s[0] == "append":
+            cache.append_message(s[1].data_ptr(), s[2].data_ptr(), s[3], s[4])
+            continue
+        n = cache.cache_info()[0]
+        b1 = [int(x) for x in rng.integers(-2000, 2001, size=n)]
+        cache.reposition_batch(list(range(n)), b1)
+        b2 = [b if i % 3 else b + 17 for i, b in enumerate(b1)]
+        cache.reposition_batch(list(range(n)), b2)
+        assert [cache.message_base(m) for m in range(n)] == b2
+        _, calls, mc, q, out, lse = s
+        cache.attend(calls, q.data_ptr(), out.data_ptr(), lse.data_ptr(), 0, mc)
+        res.append((out, lse))
+    torch.cuda.synchronize()
+    from paper_2512_23049_amd.binding import PcError, PC_ERR_BAD_MSG_ID, PC_ERR_INVALID_ARG
+    for ids, bases, code in [([0, 0], [1, 2], PC_ERR_INVALID_ARG), ([0, 999], [1, 2], PC_ERR_BAD_MSG_ID),
+                             ([0], [(1 << 20) + 1], PC_ERR_INVALID_ARG)]:
+        with pytest.raises(PcError) as e:
+            cache.reposition_batch(ids, bases)
+        assert e.value.code == code
+    assert cache.message_base(0) == b2[0]                # a refused batch moves nothing
+    cache.reposition_batch([], [])
+    cache.close()
+    compare(w, res, "batched moves")
+
+
 def test_stored_keys_after_move(hip):
     """Reads the key store back (caller-owned arena) and compares with the oracle's rotation to
     base + t; tolerance: two roundings to bf16 (append, move) of values of magnitude |k|."""
