@@ -416,6 +416,7 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
             sc = MFMA32(fr[ks], qop[ks], sc);
             fr[ks] = kfrag(1, ks);
         }
+        if (d1.fresh()) turn_query(1);                   // (from tile 2 on the queries are turned at the end of an iteration)
         mask_and_shift(sc, d0);
         rebase(sc, col_max(sc));
         // every wave has read tile 0's K before any wave overwrites its slot with tile 5's
@@ -429,7 +430,6 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
             constexpr int u = decltype(uc)::value;
             constexpr int s0 = u, s1 = (u + 1) % RING, s2 = (u + 2) % RING, s4 = (u + 4) % RING;
             i32x4 raw6 = request_desc(min(tile0 + i + 6, last));     // first used in the next iteration's requests
-            if (__builtin_expect(d1.fresh(), 0)) turn_query(s1);
             f32x16 sn = phase_a(s0, sc, [&] { dma_k(d5, s0); });             // K(i+5) takes the slot of K(i)
             // the descriptor is awaited here, where the wait costs nothing: it waits for every LDS
             // read too, and the V fragments requested during phase A arrived while its vector work
@@ -437,6 +437,10 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
             await_desc(raw6);
             const Desc d6 = decode(raw6);
             phase_b(s2, sc, sn, d1, [&] { dma_v(d4, s4); });                 // V(i+4) takes the slot of V(i-1)
+            // the score MFMAs of this iteration have been issued, so the query operands are free:
+            // turn them now if the tile after next starts a new rotation (its table came with K(i+2));
+            // the P.V MFMAs just issued keep the matrix pipe busy meanwhile
+            if (__builtin_expect(d2.fresh(), 0)) turn_query(s2);
             sc = sn;
             // K(i+3), V(i+1) (requested two and three iterations ago) must have landed; the requests
             // of this and the previous iteration (a K and a V each, rotation tables in front of
