@@ -9,7 +9,7 @@
 // occupied part of the cache; the i-th token's key is turned to a position by RoPE).
 // Stored form: the key of in-message token t is turned by t (delta-rotated form), so
 // that placing the message at offset s later only needs the query turned by -s.
-// blockIdx.y == 0: K part, one thread per (token, 2 adjacent frequency pairs... ) see below
+// blockIdx.y == 0: K part, one thread per (token, kv head, 2 adjacent frequency pairs)
 // blockIdx.y == 1: V part, one thread per (group of 8 tokens, kv head, 2 adjacent dims)
 // ----------------------------------------------------------------------------------
 template <typename T> struct Pair2;
@@ -34,25 +34,25 @@ __global__ __launch_bounds__(256) void pc_append_bf16_kernel(
     const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (blockIdx.y == 0) {
         if (tid == 0) { table[msg_id].slot_start = (int32_t)slot_start; table[msg_id].len = len; table[msg_id].base_pos = 0; }
-        // thread = (token t, pair index i0 = 2*j): handles frequency pairs i0 and i0+1
+        // thread = (token t, KV head h, pair index i0 = 2*j): handles frequency pairs i0 and i0+1 of one
+        // head, so that no thread walks the heads one dependent load after the other
         const int per_tok = half / 2;
-        if (tid >= (int64_t)len * per_tok) return;
-        const int t = (int)(tid / per_tok);
+        if (tid >= (int64_t)len * n_kv_heads * per_tok) return;
         const int i0 = 2 * (int)(tid % per_tok);
+        const int h = (int)((tid / per_tok) % n_kv_heads);
+        const int t = (int)(tid / ((int64_t)per_tok * n_kv_heads));
+        const uint16_t *src = k + ((int64_t)t * n_kv_heads + h) * D;
+        const uint32_t lo = *reinterpret_cast<const uint32_t *>(src + i0);
+        const uint32_t hi = *reinterpret_cast<const uint32_t *>(src + half + i0);
         double s0, c0, s1, c1;
         sincos((double)t * inv_freq[i0], &s0, &c0);
         sincos((double)t * inv_freq[i0 + 1], &s1, &c1);
         const float fc0 = (float)c0, fs0 = (float)s0, fc1 = (float)c1, fs1 = (float)s1;
         using P = Pair2<__hip_bfloat16>;
-        for (int h = 0; h < n_kv_heads; ++h) {
-            const uint16_t *src = k + ((int64_t)t * n_kv_heads + h) * D;
-            const uint32_t lo = *reinterpret_cast<const uint32_t *>(src + i0);
-            const uint32_t hi = *reinterpret_cast<const uint32_t *>(src + half + i0);
-            const float a0 = P::lo(lo), a1 = P::hi(lo), b0 = P::lo(hi), b1 = P::hi(hi);
-            uint16_t *dst = k_store + ((int64_t)h * slots + slot_start + t) * D;
-            *reinterpret_cast<uint32_t *>(dst + i0) = P::pack(a0 * fc0 - b0 * fs0, a1 * fc1 - b1 * fs1);
-            *reinterpret_cast<uint32_t *>(dst + half + i0) = P::pack(a0 * fs0 + b0 * fc0, a1 * fs1 + b1 * fc1);
-        }
+        const float a0 = P::lo(lo), a1 = P::hi(lo), b0 = P::lo(hi), b1 = P::hi(hi);
+        uint16_t *dst = k_store + ((int64_t)h * slots + slot_start + t) * D;
+        *reinterpret_cast<uint32_t *>(dst + i0) = P::pack(a0 * fc0 - b0 * fs0, a1 * fc1 - b1 * fs1);
+        *reinterpret_cast<uint32_t *>(dst + half + i0) = P::pack(a0 * fs0 + b0 * fc0, a1 * fs1 + b1 * fc1);
     } else {
         // thread = (token group tg, head h, dim pair d0): 8 tokens x 2 dims, zero padded
         const int dp = D / 2;
@@ -118,7 +118,7 @@ void pc_launch_append(int dtype, const void *k, const void *v, int len, int n_kv
                       void *v_store, PcMsgEntry *table, int msg_id, hipStream_t st)
 {
     if (dtype == 1) {
-        const int64_t nk = (int64_t)len * (D / 4);
+        const int64_t nk = (int64_t)len * n_kv_heads * (D / 4);
         const int64_t nv = (int64_t)((len + PC_VGROUP - 1) / PC_VGROUP) * n_kv_heads * (D / 2);
         const int64_t n = nk > nv ? nk : nv;
         dim3 grid((unsigned)((n + 255) / 256), 2);
