@@ -473,9 +473,10 @@ void pc_launch_expand_tables(const PcSegment *segs, const int32_t *seg_kvoff, in
 //   m = max m_s,  w_s = l_s 2^(m_s - m),  l = sum w_s,  O = sum w_s O_s / l
 // taken in split order (deterministic; no atomics), four splits at a time with the
 // running maximum carried from one group of four to the next.
-// One wave per (row, head), a lane owns two of the 128 dimensions.  The kernel is bound by
-// the latency of its dependent loads, so there are only two levels of them: the row's
-// descriptor, then the sums and outputs of four splits together.
+// Sixteen threads per (row, head), a thread owns eight of the 128 dimensions (one 16-byte
+// load per split).  The kernel is bound by the latency of its dependent loads, so there are
+// only two levels of them: the row's descriptor, then the sums and outputs of four splits
+// together.
 // ----------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void pc_merge_kernel(
     const PcMergeRow *__restrict__ merge_rows, const uint16_t *__restrict__ part_o,
@@ -483,42 +484,54 @@ __global__ __launch_bounds__(256) void pc_merge_kernel(
     int n_pairs)
 {
     constexpr int D = 128;
-    const int pair = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+    const int pair = blockIdx.x * 16 + (threadIdx.x >> 4), sub = threadIdx.x & 15;
     if (pair >= n_pairs) return;
     const int h = pair % n_q_heads;
     const PcMergeRow mr = merge_rows[pair / n_q_heads];
-    float m = -INFINITY, l = 0.f, o0 = 0.f, o1 = 0.f;
+    float m = -INFINITY, l = 0.f, o[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) o[j] = 0.f;
     for (int s0 = 0; s0 < mr.n_splits; s0 += 4) {
         float2 ml[4];
-        uint32_t v[4];
+        uint4 v[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const int s = min(s0 + u, mr.n_splits - 1);
             const int64_t pr = (int64_t)mr.part_row0 + (int64_t)s * mr.n_q;
             ml[u] = *reinterpret_cast<const float2 *>(part_ml + (pr * n_q_heads + h) * 2);
-            v[u] = *reinterpret_cast<const uint32_t *>(part_o + (pr * n_q_heads + h) * D + 2 * lane);
+            v[u] = *reinterpret_cast<const uint4 *>(part_o + (pr * n_q_heads + h) * D + 8 * sub);
         }
         float m_new = m;
 #pragma unroll
         for (int u = 0; u < 4; ++u) m_new = fmaxf(m_new, ml[u].x);          // (a repeated last split changes nothing)
         if (m_new == -INFINITY) continue;
         const float keep = (m > -INFINITY) ? exp2f(m - m_new) : 0.f;
-        l *= keep; o0 *= keep; o1 *= keep;
+        l *= keep;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) o[j] *= keep;
         m = m_new;
 #pragma unroll
         for (int u = 0; u < 4; ++u) {                    // in split order
             if (s0 + u >= mr.n_splits) break;
             const float w = (ml[u].x > -INFINITY) ? ml[u].y * exp2f(ml[u].x - m) : 0.f;
             l += w;
-            o0 += (float)__builtin_bit_cast(_Float16, (uint16_t)(v[u] & 0xFFFF)) * w;
-            o1 += (float)__builtin_bit_cast(_Float16, (uint16_t)(v[u] >> 16)) * w;
+            const uint32_t d[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                o[2 * j] += (float)__builtin_bit_cast(_Float16, (uint16_t)(d[j] & 0xFFFF)) * w;
+                o[2 * j + 1] += (float)__builtin_bit_cast(_Float16, (uint16_t)(d[j] >> 16)) * w;
+            }
         }
     }
     const float inv = (l > 0.f) ? 1.f / l : 0.f;
-    __hip_bfloat16 b0 = __float2bfloat16(o0 * inv), b1 = __float2bfloat16(o1 * inv);
-    const uint32_t packed = (uint32_t)*reinterpret_cast<uint16_t *>(&b0) | ((uint32_t)*reinterpret_cast<uint16_t *>(&b1) << 16);
-    *reinterpret_cast<uint32_t *>(out + ((int64_t)mr.row * n_q_heads + h) * D + 2 * lane) = packed;
-    if (lse && lane == 0)
+    uint32_t packed[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        __hip_bfloat16 b0 = __float2bfloat16(o[2 * j] * inv), b1 = __float2bfloat16(o[2 * j + 1] * inv);
+        packed[j] = (uint32_t)*reinterpret_cast<uint16_t *>(&b0) | ((uint32_t)*reinterpret_cast<uint16_t *>(&b1) << 16);
+    }
+    *reinterpret_cast<uint4 *>(out + ((int64_t)mr.row * n_q_heads + h) * D + 8 * sub) = make_uint4(packed[0], packed[1], packed[2], packed[3]);
+    if (lse && sub == 0)
         lse[(int64_t)mr.row * n_q_heads + h] = (l > 0.f) ? (m + log2f(l)) * 0.6931471805599453f : -INFINITY;
 }
 
@@ -528,7 +541,7 @@ void pc_launch_merge(int dtype, const PcMergeRow *merge_rows, int n_merge_rows, 
 {
     if (n_merge_rows <= 0 || dtype != 1 || D != 128) return;
     const int n_pairs = n_merge_rows * n_q_heads;
-    pc_merge_kernel<<<(n_pairs + 3) / 4, 256, 0, st>>>(merge_rows, part_o, part_ml, (uint16_t *)out, lse, n_q_heads, n_pairs);
+    pc_merge_kernel<<<(n_pairs + 15) / 16, 256, 0, st>>>(merge_rows, part_o, part_ml, (uint16_t *)out, lse, n_q_heads, n_pairs);
 }
 
 // ----------------------------------------------------------------------------------
