@@ -600,10 +600,12 @@ static int32_t plan_and_stage(pc_cache *c, const pc_call *calls, int32_t n_calls
     int64_t part_rows = 0, total_tiles = 0;
     int sel_off = 0, q_off = 0, seg_off = 0;
     // first pass: how many prefill groups without splitting (to decide on KV splits)
-    int64_t pre_groups = 0;
+    int64_t pre_groups = 0, dec_groups = 0;
     if (want_items && bf16)
-        for (auto &r : P.res)
+        for (auto &r : P.res) {
             if (r.n_q * g > 16) pre_groups += (int64_t)(((r.n_q + 31) / 32) * g + P.pre_waves - 1) / P.pre_waves * H_kv;
+            else dec_groups += H_kv;
+        }
     for (int i = 0; i < n_calls; ++i) {
         Resolved &r = P.res[i];
         PcCallDesc &cd = cds[i];
@@ -615,8 +617,11 @@ static int32_t plan_and_stage(pc_cache *c, const pc_call *calls, int32_t n_calls
         if (!want_items || !bf16) continue;
         const int T = r.tiles;
         if (r.n_q * g <= 16) {                       // decode-shaped: all rows x heads of a KV head in one wave
-            const int per = c->decode_tiles_per_split > 0 ? c->decode_tiles_per_split : 48;
-            int ns = std::max(1, std::min(MAX_SPLITS, (T + per - 1) / per));
+            // as few splits as fill the chip (256 workgroups): the kernel is bound by memory, and every
+            // split beyond that only adds partial results to write and merge
+            int ns = c->decode_tiles_per_split > 0 ? (T + c->decode_tiles_per_split - 1) / c->decode_tiles_per_split
+                                                   : (int)std::min<int64_t>((256 + dec_groups - 1) / dec_groups, std::max(1, T / 16));
+            ns = std::max(1, std::min(MAX_SPLITS, ns));
             const int chunk = std::max(1, (T + ns - 1) / ns);
             ns = std::max(1, (T + chunk - 1) / chunk);
             cd.n_splits = ns;
