@@ -103,6 +103,15 @@ const char *pc_last_error(const pc_cache *c);
 int32_t pc_append_message(pc_cache *c, const void *k, const void *v, int32_t len,
                           int32_t reserve, int32_t *msg_id, void *stream);
 
+/* The same for n messages in one launch (Sec. 2.4 "Parallel API Calls": the new messages
+ * of parallel calls).  k, v: host arrays of n device pointers; lens, reserves (may be NULL:
+ * no extra room), msg_ids: host arrays of n entries; all copied / filled before return.
+ * Ids are consecutive in list order.  All or nothing: on any error (a length < 1, a null
+ * pointer, no room for one of them) nothing is appended. */
+int32_t pc_append_messages(pc_cache *c, int32_t n, const void *const *k, const void *const *v,
+                           const int32_t *lens, const int32_t *reserves, int32_t *msg_ids,
+                           void *stream);
+
 /* Growth of existing messages within the room reserved at pc_append_message
  * (Sec. 2.4: decode tails grow token by token; parallel calls grow theirs in step).
  * pc_append_tokens: n more tokens for one message, k, v device [n, n_kv_heads, head_dim].

@@ -62,6 +62,9 @@ def lib():
         L.pc_last_error.argtypes = [vp]
         L.pc_append_message.restype = i32
         L.pc_append_message.argtypes = [vp, vp, vp, i32, i32, C.POINTER(i32), vp]
+        L.pc_append_messages.restype = i32
+        L.pc_append_messages.argtypes = [vp, i32, C.POINTER(vp), C.POINTER(vp), C.POINTER(i32), C.POINTER(i32),
+                                         C.POINTER(i32), vp]
         L.pc_append_tokens.restype = i32
         L.pc_append_tokens.argtypes = [vp, i32, vp, vp, i32, vp]
         L.pc_append_tokens_batch.restype = i32
@@ -183,6 +186,16 @@ class Cache:
         ln, st, rs = C.c_int32(0), C.c_int64(0), C.c_int32(0)
         self._check(lib().pc_message_info(self.h, msg_id, C.byref(ln), C.byref(st), C.byref(rs)))
         return ln.value, st.value, rs.value
+
+    def append_messages(self, k_ptrs, v_ptrs, lengths, reserves=None, stream: int = 0):
+        n = len(lengths)
+        ka = (C.c_void_p * max(n, 1))(*[int(p) if p else None for p in k_ptrs])
+        va = (C.c_void_p * max(n, 1))(*[int(p) if p else None for p in v_ptrs])
+        la = (C.c_int32 * max(n, 1))(*[int(x) for x in lengths])
+        ra = (C.c_int32 * max(n, 1))(*[int(x) for x in (reserves or [0] * n)])
+        ids = (C.c_int32 * max(n, 1))()
+        self._check(lib().pc_append_messages(self.h, n, ka, va, la, ra, ids, stream))
+        return [ids[i] for i in range(n)]
 
     def append_tokens(self, msg_id: int, k_ptr: int, v_ptr: int, n: int, stream: int = 0):
         self._check(lib().pc_append_tokens(self.h, msg_id, k_ptr, v_ptr, n, stream))

@@ -18,6 +18,15 @@ struct PcMsgEntry {
     int32_t pad;
 };
 
+// One message of a batched append (staged by the host).
+struct PcAppendItem {
+    const void *k, *v;        // device, [len, H_kv, D] each
+    int32_t msg;
+    int32_t slot_start;
+    int32_t len;
+    int32_t pad;
+};
+
 // One token appended to an existing message (staged by the host).
 struct PcTokenItem {
     int32_t msg;              // message that grows

@@ -8,6 +8,11 @@ void pc_launch_append(int dtype, const void *k, const void *v, int len, int n_kv
                       int64_t slot_start, int64_t slots, const double *inv_freq, void *k_store,
                       void *v_store, PcMsgEntry *table, int msg_id, hipStream_t st);
 
+// several whole messages in one launch
+void pc_launch_append_batch(int dtype, const PcAppendItem *items, int n_items, int max_len, int n_kv_heads, int D,
+                            int64_t slots, const double *inv_freq, void *k_store, void *v_store, PcMsgEntry *table,
+                            hipStream_t st);
+
 // n tokens (rows of k, v: [n, H_kv, D]) into the slots the items name
 void pc_launch_append_tokens(int dtype, const PcTokenItem *items, int n, const void *k, const void *v, int n_kv_heads,
                              int D, int64_t slots, const double *inv_freq, void *k_store, void *v_store,

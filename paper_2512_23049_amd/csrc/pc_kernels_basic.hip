@@ -4,6 +4,8 @@
 
 #include <hip/hip_bf16.h>
 
+#include <algorithm>
+
 // ----------------------------------------------------------------------------------
 // K1: fused cache append (Sec. 2.4: new messages are appended at the end of the
 // occupied part of the cache; the i-th token's key is turned to a position by RoPE).
@@ -24,16 +26,14 @@ template <> struct Pair2<__hip_bfloat16> {
     }
 };
 
-__global__ __launch_bounds__(256) void pc_append_bf16_kernel(
-    const uint16_t *__restrict__ k, const uint16_t *__restrict__ v, int len, int n_kv_heads, int D,
-    int64_t slot_start, int64_t slots, const double *__restrict__ inv_freq,
-    uint16_t *__restrict__ k_store, uint16_t *__restrict__ v_store,
-    PcMsgEntry *__restrict__ table, int msg_id)
+// what one thread of the K part (part 0) or the V part (part 1) does; tid counts the threads of a part
+__device__ __forceinline__ void append_bf16_thread(
+    int part, int64_t tid, const uint16_t *__restrict__ k, const uint16_t *__restrict__ v, int len, int n_kv_heads,
+    int D, int64_t slot_start, int64_t slots, const double *__restrict__ inv_freq,
+    uint16_t *__restrict__ k_store, uint16_t *__restrict__ v_store)
 {
     const int half = D / 2;
-    const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (blockIdx.y == 0) {
-        if (tid == 0) { table[msg_id].slot_start = (int32_t)slot_start; table[msg_id].len = len; table[msg_id].base_pos = 0; }
+    if (part == 0) {
         // thread = (token t, KV head h, pair index i0 = 2*j): handles frequency pairs i0 and i0+1 of one
         // head, so that no thread walks the heads one dependent load after the other
         const int per_tok = half / 2;
@@ -81,16 +81,13 @@ __global__ __launch_bounds__(256) void pc_append_bf16_kernel(
     }
 }
 
-__global__ __launch_bounds__(256) void pc_append_f32_kernel(
-    const float *__restrict__ k, const float *__restrict__ v, int len, int n_kv_heads, int D,
+__device__ __forceinline__ void append_f32_thread(
+    int part, int64_t tid, const float *__restrict__ k, const float *__restrict__ v, int len, int n_kv_heads, int D,
     int64_t slot_start, int64_t slots, const double *__restrict__ inv_freq,
-    float *__restrict__ k_store, float *__restrict__ v_store,
-    PcMsgEntry *__restrict__ table, int msg_id)
+    float *__restrict__ k_store, float *__restrict__ v_store)
 {
     const int half = D / 2;
-    const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (blockIdx.y == 0) {
-        if (tid == 0) { table[msg_id].slot_start = (int32_t)slot_start; table[msg_id].len = len; table[msg_id].base_pos = 0; }
+    if (part == 0) {
         if (tid >= (int64_t)len * half) return;
         const int t = (int)(tid / half);
         const int i = (int)(tid % half);
@@ -110,6 +107,75 @@ __global__ __launch_bounds__(256) void pc_append_f32_kernel(
         const int h = (int)((tid / D) % n_kv_heads);
         const int t = (int)(tid / ((int64_t)D * n_kv_heads));
         v_store[((int64_t)h * slots + slot_start + t) * D + d] = v[tid];
+    }
+}
+
+__global__ __launch_bounds__(256) void pc_append_bf16_kernel(
+    const uint16_t *__restrict__ k, const uint16_t *__restrict__ v, int len, int n_kv_heads, int D,
+    int64_t slot_start, int64_t slots, const double *__restrict__ inv_freq,
+    uint16_t *__restrict__ k_store, uint16_t *__restrict__ v_store,
+    PcMsgEntry *__restrict__ table, int msg_id)
+{
+    const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (blockIdx.y == 0 && tid == 0) { table[msg_id].slot_start = (int32_t)slot_start; table[msg_id].len = len; table[msg_id].base_pos = 0; }
+    append_bf16_thread((int)blockIdx.y, tid, k, v, len, n_kv_heads, D, slot_start, slots, inv_freq, k_store, v_store);
+}
+
+__global__ __launch_bounds__(256) void pc_append_f32_kernel(
+    const float *__restrict__ k, const float *__restrict__ v, int len, int n_kv_heads, int D,
+    int64_t slot_start, int64_t slots, const double *__restrict__ inv_freq,
+    float *__restrict__ k_store, float *__restrict__ v_store,
+    PcMsgEntry *__restrict__ table, int msg_id)
+{
+    const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (blockIdx.y == 0 && tid == 0) { table[msg_id].slot_start = (int32_t)slot_start; table[msg_id].len = len; table[msg_id].base_pos = 0; }
+    append_f32_thread((int)blockIdx.y, tid, k, v, len, n_kv_heads, D, slot_start, slots, inv_freq, k_store, v_store);
+}
+
+// Several messages in one launch (Sec. 2.4 "Parallel API Calls": the new messages of parallel
+// calls arrive together): blockIdx.z names the message, the blocks of a (part, message) walk
+// its threads with a grid stride.
+template <typename T>
+__global__ __launch_bounds__(256) void pc_append_batch_kernel(
+    const PcAppendItem *__restrict__ items, int n_kv_heads, int D, int64_t slots,
+    const double *__restrict__ inv_freq, T *__restrict__ k_store, T *__restrict__ v_store, PcMsgEntry *__restrict__ table)
+{
+    const PcAppendItem it = items[blockIdx.z];
+    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) {
+        table[it.msg].slot_start = it.slot_start; table[it.msg].len = it.len; table[it.msg].base_pos = 0;
+    }
+    int64_t total;
+    if constexpr (sizeof(T) == 2)
+        total = blockIdx.y == 0 ? (int64_t)it.len * n_kv_heads * (D / 4)
+                                : (int64_t)((it.len + PC_VGROUP - 1) / PC_VGROUP) * n_kv_heads * (D / 2);
+    else
+        total = blockIdx.y == 0 ? (int64_t)it.len * (D / 2) : (int64_t)it.len * n_kv_heads * D;
+    for (int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; tid < total; tid += (int64_t)gridDim.x * blockDim.x) {
+        if constexpr (sizeof(T) == 2)
+            append_bf16_thread((int)blockIdx.y, tid, (const uint16_t *)it.k, (const uint16_t *)it.v, it.len, n_kv_heads, D,
+                               it.slot_start, slots, inv_freq, k_store, v_store);
+        else
+            append_f32_thread((int)blockIdx.y, tid, (const float *)it.k, (const float *)it.v, it.len, n_kv_heads, D,
+                              it.slot_start, slots, inv_freq, k_store, v_store);
+    }
+}
+
+void pc_launch_append_batch(int dtype, const PcAppendItem *items, int n_items, int max_len, int n_kv_heads, int D,
+                            int64_t slots, const double *inv_freq, void *k_store, void *v_store, PcMsgEntry *table,
+                            hipStream_t st)
+{
+    // enough blocks per (part, message) for the longest message at one pass, within reason
+    const int64_t per = (int64_t)max_len * n_kv_heads * (dtype == 1 ? D / 4 : D);
+    const unsigned bx = (unsigned)std::min<int64_t>(std::max<int64_t>((per + 255) / 256, 1), 256);
+    for (int first = 0; first < n_items; first += 65535) {            // grid.z is limited to 65535
+        const int n = n_items - first < 65535 ? n_items - first : 65535;
+        dim3 grid(bx, 2, (unsigned)n);
+        if (dtype == 1)
+            pc_append_batch_kernel<uint16_t><<<grid, 256, 0, st>>>(items + first, n_kv_heads, D, slots, inv_freq,
+                                                                   (uint16_t *)k_store, (uint16_t *)v_store, table);
+        else
+            pc_append_batch_kernel<float><<<grid, 256, 0, st>>>(items + first, n_kv_heads, D, slots, inv_freq,
+                                                                (float *)k_store, (float *)v_store, table);
     }
 }
 

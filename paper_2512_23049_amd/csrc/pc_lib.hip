@@ -307,6 +307,24 @@ int32_t pc_cache_destroy(pc_cache *c)
 
 const char *pc_last_error(const pc_cache *c) { return c ? c->err.c_str() : "null cache"; }
 
+// Takes the slots of one message out of (spans, next): the first freed span that holds the reserve
+// rounded up to the slot alignment, else the end of the used region.  False (nothing changed) if neither has room.
+static bool take_slots(std::vector<FreeSpan> &spans, int64_t &next, int64_t capacity, int32_t res, int64_t &start)
+{
+    const int64_t need = (int64_t)align_up((size_t)res, PC_SLOT_ALIGN);
+    for (size_t i = 0; i < spans.size(); ++i)
+        if (spans[i].size >= need) {
+            start = spans[i].start;
+            spans[i].start += need; spans[i].size -= need;
+            if (spans[i].size == 0) spans.erase(spans.begin() + (long)i);
+            return true;
+        }
+    if (next + res > capacity) return false;
+    start = next;
+    next += need;
+    return true;
+}
+
 int32_t pc_append_message(pc_cache *c, const void *k, const void *v, int32_t len, int32_t reserve,
                           int32_t *msg_id, void *stream)
 {
@@ -317,16 +335,13 @@ int32_t pc_append_message(pc_cache *c, const void *k, const void *v, int32_t len
     if ((int64_t)c->msgs.size() >= c->cfg.max_messages)
         return fail(c, PC_ERR_NO_SPACE, "append: message table full (%d)", c->cfg.max_messages);
     const int32_t res = std::max(reserve, len);
-    // first freed span that is large enough, else the end of the used region
-    const int64_t need = (int64_t)align_up((size_t)res, PC_SLOT_ALIGN);
-    int64_t start = c->next_slot;
-    size_t from_free = c->free_spans.size();
-    for (size_t i = 0; i < c->free_spans.size(); ++i)
-        if (c->free_spans[i].size >= need) { from_free = i; start = c->free_spans[i].start; break; }
-    if (from_free == c->free_spans.size() && start + res > c->slots)
-        return fail(c, PC_ERR_NO_SPACE, "append: needs slots [%lld, %lld), capacity %lld", (long long)start,
-                    (long long)(start + res), (long long)c->slots);
+    int64_t start = 0;
+    if (!take_slots(c->free_spans, c->next_slot, c->slots, res, start))
+        return fail(c, PC_ERR_NO_SPACE, "append: needs slots [%lld, %lld), capacity %lld", (long long)c->next_slot,
+                    (long long)(c->next_slot + res), (long long)c->slots);
     const int id = (int)c->msgs.size();
+    c->msgs.push_back({start, len, res, 0, true});
+    *msg_id = id;
     if (!c->host_only) {
         hipStream_t st = (hipStream_t)stream;
         ProfScope ps(c, 0, st);
@@ -334,15 +349,6 @@ int32_t pc_append_message(pc_cache *c, const void *k, const void *v, int32_t len
                          c->k_store, c->v_store, c->table_dev, id, st);
         PC_HIP(c, hipGetLastError());
     }
-    c->msgs.push_back({start, len, res, 0, true});
-    if (from_free < c->free_spans.size()) {
-        FreeSpan &f = c->free_spans[from_free];
-        f.start += need; f.size -= need;
-        if (f.size == 0) c->free_spans.erase(c->free_spans.begin() + (long)from_free);
-    } else {
-        c->next_slot = start + need;
-    }
-    *msg_id = id;
     return PC_OK;
 }
 
@@ -365,6 +371,49 @@ static int32_t stage_items(pc_cache *c, const void *items, size_t bytes, hipStre
     PC_HIP(c, hipMemcpyAsync(c->tok_dev, slot->host, bytes, hipMemcpyHostToDevice, st));
     PC_HIP(c, hipEventRecord(slot->ev, st));
     slot->used = true;
+    return PC_OK;
+}
+
+int32_t pc_append_messages(pc_cache *c, int32_t n, const void *const *k, const void *const *v, const int32_t *lens,
+                           const int32_t *reserves, int32_t *msg_ids, void *stream)
+{
+    if (!c) return PC_ERR_INVALID_ARG;
+    if (n < 0 || (n > 0 && (!lens || !msg_ids))) return fail(c, PC_ERR_INVALID_ARG, "append_messages: bad lists");
+    if (n == 0) return PC_OK;
+    if (!c->host_only && (!k || !v)) return fail(c, PC_ERR_INVALID_ARG, "append_messages: null k or v list");
+    if ((int64_t)c->msgs.size() + n > c->cfg.max_messages)
+        return fail(c, PC_ERR_NO_SPACE, "append_messages: message table full (%d)", c->cfg.max_messages);
+    // all or nothing: allocate on copies first
+    std::vector<FreeSpan> spans = c->free_spans;
+    int64_t next = c->next_slot;
+    std::vector<PcAppendItem> items((size_t)n);
+    std::vector<HostMsg> fresh((size_t)n);
+    int max_len = 0;
+    for (int j = 0; j < n; ++j) {
+        if (lens[j] < 1) return fail(c, PC_ERR_INVALID_ARG, "append_messages: message %d has len = %d", j, lens[j]);
+        if (!c->host_only && (!k[j] || !v[j])) return fail(c, PC_ERR_INVALID_ARG, "append_messages: message %d has null k or v", j);
+        const int32_t res = std::max(reserves ? reserves[j] : 0, lens[j]);
+        int64_t start = 0;
+        if (!take_slots(spans, next, c->slots, res, start))
+            return fail(c, PC_ERR_NO_SPACE, "append_messages: message %d (%d slots) does not fit, capacity %lld", j, res,
+                        (long long)c->slots);
+        fresh[(size_t)j] = HostMsg{start, lens[j], res, 0, true};
+        items[(size_t)j] = PcAppendItem{c->host_only ? nullptr : k[j], c->host_only ? nullptr : v[j],
+                                        (int32_t)c->msgs.size() + j, (int32_t)start, lens[j], 0};
+        max_len = std::max(max_len, lens[j]);
+    }
+    if (!c->host_only) {
+        hipStream_t st = (hipStream_t)stream;
+        const int32_t rc = stage_items(c, items.data(), sizeof(PcAppendItem) * (size_t)n, st);
+        if (rc != PC_OK) return rc;
+        ProfScope ps(c, 0, st);
+        pc_launch_append_batch(c->cfg.dtype, (const PcAppendItem *)c->tok_dev, n, max_len, c->cfg.n_kv_heads, c->D, c->slots,
+                               c->inv_freq_dev, c->k_store, c->v_store, c->table_dev, st);
+        PC_HIP(c, hipGetLastError());
+    }
+    for (int j = 0; j < n; ++j) { msg_ids[j] = (int32_t)c->msgs.size(); c->msgs.push_back(fresh[(size_t)j]); }
+    c->free_spans.swap(spans);
+    c->next_slot = next;
     return PC_OK;
 }
 

@@ -45,10 +45,22 @@ class DeviceWorkload:
                 lse = torch.empty(q.shape[:2], dtype=torch.float32, device=device)
                 self.steps.append(("attend", e.calls, marshal_calls(e.calls), q, out, lse))
 
-    def run(self, cache: Cache, stream: int = 0, want_lse: bool = True):
-        """One pass over all events; returns the list of (out, lse) of the attend events."""
+    def run(self, cache: Cache, stream: int = 0, want_lse: bool = True, batch_appends: bool = False):
+        """One pass over all events; returns the list of (out, lse) of the attend events.
+        batch_appends: consecutive append events go through one pc_append_messages call."""
         res = []
+        pending = []
+
+        def flush():
+            if pending:
+                cache.append_messages([p[1].data_ptr() for p in pending], [p[2].data_ptr() for p in pending],
+                                      [p[3] for p in pending], [p[4] for p in pending], stream)
+                pending.clear()
         for s in self.steps:
+            if s[0] == "append" and batch_appends:
+                pending.append(s)
+                continue
+            flush()
             if s[0] == "append":
                 cache.append_message(s[1].data_ptr(), s[2].data_ptr(), s[3], s[4], stream)
             elif s[0] == "extend":
@@ -57,6 +69,7 @@ class DeviceWorkload:
                 _, calls, m, q, out, lse = s
                 cache.attend(calls, q.data_ptr(), out.data_ptr(), lse.data_ptr() if want_lse else 0, stream, m)
                 res.append((out, lse))
+        flush()
         return res
 
     def run_attends_only(self, cache: Cache, stream: int = 0, want_lse: bool = False):

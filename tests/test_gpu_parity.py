@@ -28,7 +28,7 @@ def hip():
     return harness
 
 
-def run_and_compare(hip, w, rows_per_call=None, calls_subset=None, events=None, tuning=None):
+def run_and_compare(hip, w, rows_per_call=None, calls_subset=None, events=None, tuning=None, batch_appends=False):
     import torch
     cache = hip.make_cache(w)
     if tuning:
@@ -36,7 +36,7 @@ def run_and_compare(hip, w, rows_per_call=None, calls_subset=None, events=None, 
     dw = hip.DeviceWorkload(w)
     say(f"[run] {w.name} dtype={w.dtype} Hq={w.n_q_heads} Hkv={w.n_kv_heads} D={w.head_dim} "
         f"msgs={w.n_messages} attends={len(attend_events(w))}")
-    res = dw.run(cache)
+    res = dw.run(cache, batch_appends=batch_appends)
     torch.cuda.synchronize()
     tol = TOL[w.dtype]
     worst = 0.0
@@ -203,6 +203,16 @@ def test_config4_scaled(hip):
     w = gen.multi_agent_rounds(n_agents=3, n_rounds=3, msg_len=70)
     tables_check(hip, w)
     run_and_compare(hip, w)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_batched_appends(hip, dtype):
+    # the messages of a round go through one pc_append_messages launch (ragged lengths, several tiles)
+    kw = dict(n_q_heads=4, n_kv_heads=2, head_dim=64) if dtype == "f32" else {}
+    w = gen.multi_agent_rounds(n_agents=3, n_rounds=3, msg_len=70, dtype=dtype, **kw)
+    run_and_compare(hip, w, batch_appends=True)
+    w = gen.small_random(41, dtype=dtype, **kw)
+    run_and_compare(hip, w, batch_appends=True)
 
 
 def test_config5_scaled(hip):

@@ -219,3 +219,28 @@ def test_growing_messages_on_a_host_only_cache(pc):
     assert c.message_info(b)[0] == 2
     starts, s_self, n = c.resolve_call(Call([(a, POS_AUTO)], b, POS_AUTO, 2, None))
     assert starts == [0] and s_self == 10 and n == 12
+
+
+def test_batched_append_is_all_or_nothing_and_follows_the_slot_model(pc):
+    c = host_cache(pc, capacity_tokens=1024, max_messages=10)
+    model = orc.SlotModel(pc.PC_SLOT_ALIGN)
+    ids = c.append_messages([0, 0, 0], [0, 0, 0], [40, 3, 100], [0, 64, 0])
+    assert ids == [0, 1, 2]
+    for m, r in zip(ids, [40, 64, 100]):
+        assert c.message_info(m)[1] == model.append(m, r)
+    c.message_free(1); model.release(1)
+    before = c.cache_info()
+    with pytest.raises(pc.PcError) as ei:                 # the third one does not fit: nothing happens
+        c.append_messages([0, 0, 0], [0, 0, 0], [10, 20, 900])
+    assert ei.value.code == pc.PC_ERR_NO_SPACE
+    with pytest.raises(pc.PcError) as ei:
+        c.append_messages([0, 0], [0, 0], [10, 0])
+    assert ei.value.code == pc.PC_ERR_INVALID_ARG
+    assert c.cache_info() == before
+    ids = c.append_messages([0, 0], [0, 0], [33, 200])    # 33 -> 64 slots: the freed span; 200: the end
+    assert ids == [3, 4]
+    assert [c.message_info(m)[1] for m in ids] == [model.append(3, 33), model.append(4, 200)]
+    with pytest.raises(pc.PcError) as ei:                 # 5 live ids + 6 > max_messages
+        c.append_messages([0] * 6, [0] * 6, [1] * 6)
+    assert ei.value.code == pc.PC_ERR_NO_SPACE
+    assert c.append_messages([], [], []) == []
