@@ -49,10 +49,9 @@ extern "C" {
 #define PC_F32  0
 #define PC_BF16 1
 
-/* "omitted offset": the position right after the end of the preceding list entry
- * (Sec. 2.3: "Any omitted offset defaults to the position immediately after the
- * end of the preceding parent message").  For the first entry it means 0; for the
- * new message it means right after the last list entry (0 if the list is empty). */
+/* An omitted offset (Sec. 2.3, the rule for offsets that are left out): the position
+ * right after the end of the preceding list entry.  For the first entry it means 0; for
+ * the new message it means right after the last list entry (0 if the list is empty). */
 #define PC_POS_AUTO INT32_MIN
 
 /* Every message starts at a slot that is a multiple of this (cache layout rule:

@@ -335,13 +335,13 @@ int32_t pc_append_message(pc_cache *c, const void *k, const void *v, int32_t len
     if ((int64_t)c->msgs.size() >= c->cfg.max_messages)
         return fail(c, PC_ERR_NO_SPACE, "append: message table full (%d)", c->cfg.max_messages);
     const int32_t res = std::max(reserve, len);
-    int64_t start = 0;
-    if (!take_slots(c->free_spans, c->next_slot, c->slots, res, start))
+    // the bookkeeping changes only once the launch has been accepted
+    std::vector<FreeSpan> spans = c->free_spans;
+    int64_t next = c->next_slot, start = 0;
+    if (!take_slots(spans, next, c->slots, res, start))
         return fail(c, PC_ERR_NO_SPACE, "append: needs slots [%lld, %lld), capacity %lld", (long long)c->next_slot,
                     (long long)(c->next_slot + res), (long long)c->slots);
     const int id = (int)c->msgs.size();
-    c->msgs.push_back({start, len, res, 0, true});
-    *msg_id = id;
     if (!c->host_only) {
         hipStream_t st = (hipStream_t)stream;
         ProfScope ps(c, 0, st);
@@ -349,6 +349,10 @@ int32_t pc_append_message(pc_cache *c, const void *k, const void *v, int32_t len
                          c->k_store, c->v_store, c->table_dev, id, st);
         PC_HIP(c, hipGetLastError());
     }
+    c->msgs.push_back({start, len, res, 0, true});
+    c->free_spans.swap(spans);
+    c->next_slot = next;
+    *msg_id = id;
     return PC_OK;
 }
 
