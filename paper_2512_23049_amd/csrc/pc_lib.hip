@@ -692,11 +692,26 @@ static int32_t plan_and_stage(pc_cache *c, const pc_call *calls, int32_t n_calls
             const int chunk = std::max(1, (T + ns - 1) / ns);
             ns = std::max(1, (T + chunk - 1) / chunk);
             cd.n_splits = ns;
-            for (int gidx = 0; gidx < groups; ++gidx)
+            // A group of row units walks the parents' tiles and the tiles of the new message up to the
+            // causal limit of its last row; its splits divide THAT count evenly, so the groups with
+            // early rows do not end up with a nearly empty last split.
+            const int self_tiles = r.self_msg >= 0 ? (r.self_len + PC_TILE - 1) / PC_TILE : 0;
+            const int parent_tiles = T - self_tiles;
+            for (int gidx = 0; gidx < groups; ++gidx) {
+                int Tg = T;
+                if (r.self_msg >= 0) {
+                    const int last_unit = std::min(gidx * P.pre_waves + P.pre_waves - 1, units - 1);
+                    const int lim = (r.self_len - r.n_q) + std::min(32 * (last_unit / g) + 31, r.n_q - 1);   // last own token seen
+                    Tg = parent_tiles + std::min(self_tiles, lim / PC_TILE + 1);
+                }
+                const int chunk_g = std::max(1, (Tg + ns - 1) / ns);
                 for (int s = 0; s < ns; ++s) {
-                    PcItem it{}; it.call = i; it.unit0 = gidx * P.pre_waves; it.tile_begin = s * chunk; it.tile_end = std::min(T, (s + 1) * chunk); it.split = s;
+                    PcItem it{}; it.call = i; it.unit0 = gidx * P.pre_waves; it.split = s;
+                    it.tile_begin = std::min(Tg, s * chunk_g);
+                    it.tile_end = s == ns - 1 ? T : std::min(Tg, (s + 1) * chunk_g);
                     pre.push_back(it);
                 }
+            }
         }
         if (cd.n_splits > 1) { cd.part_off = (int32_t)part_rows; part_rows += (int64_t)cd.n_splits * cd.n_q; }
     }
