@@ -650,6 +650,8 @@ static int32_t plan_and_stage(pc_cache *c, const pc_call *calls, int32_t n_calls
     P.pre_waves = 8;
     std::vector<PcCallDesc> cds((size_t)n_calls);
     std::vector<PcItem> dec, pre;
+    std::vector<uint64_t> sort_keys;
+    std::vector<int2> sorted_sel;
     int64_t part_rows = 0, total_tiles = 0;
     int sel_off = 0, q_off = 0, seg_off = 0;
     // first pass: how many prefill groups without splitting (to decide on KV splits)
@@ -670,6 +672,18 @@ static int32_t plan_and_stage(pc_cache *c, const pc_call *calls, int32_t n_calls
         if (!want_items || !bf16) continue;
         const int T = r.tiles;
         if (r.n_q * g <= 16) {                       // decode-shaped: all rows x heads of a KV head in one wave
+            // Attention does not depend on the order the keys are visited in (each keeps its own
+            // position), so a decode call walks its parents in ascending cache-slot order: calls that
+            // share messages then touch them at about the same time and the later ones hit in L2.
+            if (r.sel.size() > 1) {
+                sort_keys.resize(r.sel.size());
+                for (size_t e = 0; e < r.sel.size(); ++e)
+                    sort_keys[e] = ((uint64_t)(uint32_t)c->msgs[(size_t)r.sel[e].x].slot_start << 32) | (uint32_t)e;
+                std::sort(sort_keys.begin(), sort_keys.end());
+                sorted_sel.resize(r.sel.size());
+                for (size_t e = 0; e < r.sel.size(); ++e) sorted_sel[e] = r.sel[(size_t)(uint32_t)sort_keys[e]];
+                r.sel.swap(sorted_sel);
+            }
             // as few splits as fill the chip (256 workgroups): the kernel is bound by memory, and every
             // split beyond that only adds partial results to write and merge
             int ns = c->decode_tiles_per_split > 0 ? (T + c->decode_tiles_per_split - 1) / c->decode_tiles_per_split
