@@ -650,8 +650,8 @@ static int32_t plan_and_stage(pc_cache *c, const pc_call *calls, int32_t n_calls
     P.pre_waves = 8;
     std::vector<PcCallDesc> cds((size_t)n_calls);
     std::vector<PcItem> dec, pre;
-    std::vector<uint64_t> sort_keys;
-    std::vector<int2> sorted_sel;
+    struct SortKey { uint64_t key; int2 v; };
+    std::vector<SortKey> sort_keys;
     int64_t part_rows = 0, total_tiles = 0;
     int sel_off = 0, q_off = 0, seg_off = 0;
     // first pass: how many prefill groups without splitting (to decide on KV splits)
@@ -675,14 +675,13 @@ static int32_t plan_and_stage(pc_cache *c, const pc_call *calls, int32_t n_calls
             // Attention does not depend on the order the keys are visited in (each keeps its own
             // position), so a decode call walks its parents in ascending cache-slot order: calls that
             // share messages then touch them at about the same time and the later ones hit in L2.
-            if (r.sel.size() > 1) {
+            if (r.sel.size() > 1) {                  // ties (a message listed twice) go by start, so the order is the listing's no more
                 sort_keys.resize(r.sel.size());
                 for (size_t e = 0; e < r.sel.size(); ++e)
-                    sort_keys[e] = ((uint64_t)(uint32_t)c->msgs[(size_t)r.sel[e].x].slot_start << 32) | (uint32_t)e;
-                std::sort(sort_keys.begin(), sort_keys.end());
-                sorted_sel.resize(r.sel.size());
-                for (size_t e = 0; e < r.sel.size(); ++e) sorted_sel[e] = r.sel[(size_t)(uint32_t)sort_keys[e]];
-                r.sel.swap(sorted_sel);
+                    sort_keys[e] = {((uint64_t)(uint32_t)c->msgs[(size_t)r.sel[e].x].slot_start << 32) |
+                                    ((uint32_t)r.sel[e].y ^ 0x80000000u), r.sel[e]};
+                std::sort(sort_keys.begin(), sort_keys.end(), [](const SortKey &a, const SortKey &b) { return a.key < b.key; });
+                for (size_t e = 0; e < r.sel.size(); ++e) r.sel[e] = sort_keys[e].v;
             }
             // as few splits as fill the chip (256 workgroups): the kernel is bound by memory, and every
             // split beyond that only adds partial results to write and merge

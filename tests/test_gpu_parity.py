@@ -329,3 +329,51 @@ def test_large_logits_move_the_softmax_reference(hip, n_q):
         assert d.max() <= 2e-2 and d.mean() <= 1e-3
         assert (e_lse <= 2e-2 + 1e-5 * np.abs(l)).all()
     cache.close()
+
+
+def test_decode_result_does_not_depend_on_parent_order(hip):
+    """Sec. 2.4 "Dynamic Masking" / "Position Updates": what a call sees is a set of messages, each
+    with its own start position; the order they are listed in carries no information once every
+    start is given explicitly.  The decode path walks parents in cache order, so two listings of
+    the same (message, start) pairs must give the same bits, and both must match the oracle."""
+    import torch
+    from oracle import choreo_oracle as orc
+    from pc_inputs import Call
+    from paper_2512_23049_amd.binding import PC_BF16, Cache
+    rng = np.random.default_rng(91)
+    H_q, H_kv, D = 16, 4, 128
+    lens = [70, 33, 1, 128, 257, 64, 5, 96, 40, 31, 200, 17]
+
+    def rnd(*shape):
+        return gen.round_to_bf16(rng.standard_normal(shape).astype(np.float32))
+    ks = [rnd(L, H_kv, D) for L in lens]
+    vs = [rnd(L, H_kv, D) for L in lens]
+    cache = Cache(H_q, H_kv, D, PC_BF16, 10000.0, 4096, 32)
+    keep = []
+    for k, v in zip(ks, vs):
+        kd, vd = hip.to_device(k, "bf16"), hip.to_device(v, "bf16")
+        keep += [kd, vd]
+        cache.append_message(kd.data_ptr(), vd.data_ptr(), k.shape[0], 0)
+    # scattered, partly overlapping, partly negative starts; message 3 is listed twice at two places
+    pairs = [(0, 500), (4, -40), (3, 0), (9, 1200), (1, 77), (3, 640), (10, 900), (6, 3), (2, 1500), (7, 260), (5, 320), (8, 2000)]
+    q = rnd(3, H_q, D)
+    qd = hip.to_device(q, "bf16")
+    q_pos = np.asarray([2100, 2100, 2100], dtype=np.int32)
+    outs = []
+    for order in (np.arange(len(pairs)), rng.permutation(len(pairs)), np.arange(len(pairs))[::-1]):
+        sel = [pairs[i] for i in order]
+        calls = [Call(sel, -1, 0, 1, q_pos[r:r + 1]) for r in range(3)]          # three one-row decode calls
+        out = torch.empty_like(qd)
+        lse = torch.empty((3, H_q), dtype=torch.float32, device="cuda:0")
+        cache.attend(calls, qd.data_ptr(), out.data_ptr(), lse.data_ptr())
+        torch.cuda.synchronize()
+        outs.append((out.cpu(), lse.cpu()))
+        for r in range(3):
+            o, l = orc.attend_call(ks, vs, sel, -1, 0, 1, q_pos[r:r + 1], q[r:r + 1], 10000.0)
+            d = np.abs(out[r:r + 1].float().cpu().numpy() - o)
+            assert d.max() <= 2e-2 and d.mean() <= 1e-3
+            assert np.abs(lse[r:r + 1].cpu().numpy() - l).max() <= 2e-2
+    for o, l in outs[1:]:
+        assert torch.equal(o.view(torch.int16), outs[0][0].view(torch.int16)), "listing order changed the result bits"
+        assert torch.equal(l, outs[0][1])
+    cache.close()
