@@ -398,6 +398,11 @@ __global__ __launch_bounds__(256) void pc_build_plan_kernel(
     __shared__ int s_tiles[256];
     __shared__ int s_carry[2];
     __shared__ int s_rot[257];                           // query rotation (position - stored base) of the chunk's segments
+    // the call's segment list as the tile loop needs it, kept in LDS when it fits (it nearly always
+    // does): the per-tile binary search then costs LDS latencies, not a chain of global loads
+    constexpr int SEG_LDS = 1024;
+    __shared__ int s_seg_tile[SEG_LDS], s_seg_slot[SEG_LDS], s_seg_len[SEG_LDS];
+    __shared__ unsigned char s_seg_same[SEG_LDS];
     if ((int)blockIdx.x < n_calls) {
         const PcCallDesc cd = calls[blockIdx.x];
         if (threadIdx.x == 0) { s_carry[0] = 0; s_carry[1] = 0; s_rot[0] = 0; }
@@ -436,6 +441,7 @@ __global__ __launch_bounds__(256) void pc_build_plan_kernel(
                 sg.pad[0] = sg.pad[1] = 0;
                 segs[cd.seg_off + e] = sg;
                 seg_kvoff[cd.seg_off + e] = c_len + s_len[threadIdx.x] - len;
+                if (e < SEG_LDS) { s_seg_tile[e] = sg.tile_off; s_seg_slot[e] = slot; s_seg_len[e] = len; s_seg_same[e] = (unsigned char)sg.same_rot; }
             }
             __syncthreads();
             if (threadIdx.x == 255) { s_carry[0] = c_len + s_len[255]; s_carry[1] = c_tiles + s_tiles[255]; s_rot[0] = rot; }
@@ -445,19 +451,30 @@ __global__ __launch_bounds__(256) void pc_build_plan_kernel(
         // entries written above by this block are visible after the barrier)
         const int n_tiles = s_carry[1];
         const PcSegment *sg = segs + cd.seg_off;
+        const bool in_lds = cd.n_seg <= SEG_LDS;
         for (int t = threadIdx.x; t < n_tiles; t += 256) {
             int lo = 0, hi = cd.n_seg - 1;
-            while (lo < hi) {
-                const int mid = (lo + hi + 1) >> 1;
-                if (sg[mid].tile_off <= t) lo = mid; else hi = mid - 1;
+            int g_tile, g_slot, g_len, g_same;
+            if (in_lds) {
+                while (lo < hi) {
+                    const int mid = (lo + hi + 1) >> 1;
+                    if (s_seg_tile[mid] <= t) lo = mid; else hi = mid - 1;
+                }
+                g_tile = s_seg_tile[lo]; g_slot = s_seg_slot[lo]; g_len = s_seg_len[lo]; g_same = s_seg_same[lo];
+            } else {
+                while (lo < hi) {
+                    const int mid = (lo + hi + 1) >> 1;
+                    if (sg[mid].tile_off <= t) lo = mid; else hi = mid - 1;
+                }
+                const PcSegment g = sg[lo];
+                g_tile = g.tile_off; g_slot = g.slot_start; g_len = g.len; g_same = g.same_rot;
             }
-            const PcSegment g = sg[lo];
             PcTile tl;
-            tl.key0 = (t - g.tile_off) * PC_TILE;
-            tl.slot0 = g.slot_start + tl.key0;
+            tl.key0 = (t - g_tile) * PC_TILE;
+            tl.slot0 = g_slot + tl.key0;
             tl.seg = lo;
-            const int valid = g.len - tl.key0 < PC_TILE ? g.len - tl.key0 : PC_TILE;
-            tl.valid_flags = valid | ((t == g.tile_off && !g.same_rot) ? PC_TILE_FRESH : 0) |
+            const int valid = g_len - tl.key0 < PC_TILE ? g_len - tl.key0 : PC_TILE;
+            tl.valid_flags = valid | ((t == g_tile && !g_same) ? PC_TILE_FRESH : 0) |
                              ((cd.self_msg >= 0 && lo == cd.n_seg - 1) ? PC_TILE_SELF : 0);
             tiles[cd.tile_off + t] = tl;
         }
