@@ -93,6 +93,8 @@ def lib():
         L.pc_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i64), i32]
         L.pc_set_tuning.restype = i32
         L.pc_set_tuning.argtypes = [vp, i32, i32]
+        L.pc_set_decode_sharing.restype = i32
+        L.pc_set_decode_sharing.argtypes = [vp, i32]
         _lib = L
     return _lib
 
@@ -237,3 +239,7 @@ class Cache:
 
     def set_tuning(self, decode_tiles_per_split: int = 0, prefill_tiles_per_split: int = 0):
         self._check(lib().pc_set_tuning(self.h, decode_tiles_per_split, prefill_tiles_per_split))
+
+    def set_decode_sharing(self, mode: int = 0):
+        """0: shared walk when a group's calls overlap enough; 1: never; 2: whenever the shape allows."""
+        self._check(lib().pc_set_decode_sharing(self.h, mode))

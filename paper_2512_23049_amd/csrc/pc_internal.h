@@ -100,6 +100,42 @@ struct PcMergeRow {
     int32_t n_q;
 };
 
+// ---- shared decode: a group of one-row calls walks the union of its calls' messages once ----
+#define PC_SH_ABSENT INT32_MIN    // rotation-table entry of a (message, row) pair the row's call does not list
+
+// One message of a group's union list, in cache-slot order (staged by the host).
+struct PcShSeg {
+    int32_t slot_start;
+    int32_t len;
+    int32_t tile_off;         // KV tiles of the union before this message
+    int32_t pad;
+    uint32_t vis[8];          // bit n of word b: row 32*b + n of the group lists this message
+};
+
+// One group: consecutive one-row calls (staged by the host).
+struct PcShGroup {
+    int32_t seg_off, n_seg;   // its messages in the PcShSeg array
+    int32_t n_tiles;          // KV tiles of the union
+    int32_t row0;             // packed query row of the group's first call
+    int32_t n_rows;           // calls in the group (<= 32 * 8 / g)
+    int32_t rot_off;          // entry (message s, row r) of the rotation table is rot_off + s * n_rows + r
+    int32_t part_off;         // first partial row when n_splits > 1 (split s is n_rows rows further)
+    int32_t n_splits;
+};
+
+struct PcShItem {
+    int32_t group;
+    int32_t tile_begin, tile_end;     // range of the union's tiles
+    int32_t split;
+};
+
+struct PcShLaunch {
+    const PcShGroup *groups;
+    const PcShSeg   *segs;
+    const PcShItem  *items;
+    const float2    *rot;     // [entries][D/2] (cos, sin)((start - stored base) * theta_i)
+};
+
 // Everything an attention kernel needs, passed by value.
 struct PcLaunch {
     const PcCallDesc *calls;

@@ -44,4 +44,8 @@ void pc_launch_attend_f32(const PcLaunch &L, const int32_t *row_call, int total_
 void pc_launch_decode_bf16(const PcLaunch &L, int n_items, hipStream_t st);
 void pc_launch_prefill_bf16(const PcLaunch &L, int n_items, hipStream_t st);
 
+// shared decode: rotation table of the listed (message, row) pairs, then the attention kernel
+void pc_launch_shared_rot(const int32_t *pos, int64_t n_ent, const double *inv_freq, int half, float2 *rot, hipStream_t st);
+void pc_launch_decode_shared_bf16(const PcLaunch &L, const PcShLaunch &S, int n_items, hipStream_t st);
+
 #endif

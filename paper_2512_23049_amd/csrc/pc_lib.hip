@@ -53,6 +53,7 @@ struct pc_cache {
     int64_t prof_n[PC_N_KERNEL_CLASSES] = {0};
     // tuning
     int decode_tiles_per_split = 0, prefill_tiles_per_split = 0;
+    int decode_sharing = 0;                            // 0 auto, 1 never, 2 whenever possible
     std::string err;
 };
 
@@ -201,12 +202,13 @@ int32_t stage_acquire(pc_cache *c, size_t bytes, StageSlot **out)
 
 // layout of the staged (host -> device) block and of the device-built block
 struct PlanLayout {
-    size_t calls, sel, q_pos, row_call, merge_rows, items_dec, items_pre, h2d_bytes;
-    size_t segs, seg_kvoff, rot_seg, rot_q, tiles, part_o, part_ml, total;
+    size_t calls, sel, q_pos, row_call, merge_rows, items_dec, items_pre, sh_groups, sh_segs, sh_items, sh_pos, h2d_bytes;
+    size_t segs, seg_kvoff, rot_seg, rot_q, tiles, sh_rot, part_o, part_ml, total;
 };
 
 PlanLayout make_layout(int n_calls, int total_sel, int total_q, int total_seg, int n_dec, int n_pre,
-                       int64_t part_rows, int64_t total_tiles, int H_q, int D)
+                       int64_t part_rows, int64_t total_tiles, int H_q, int D,
+                       size_t n_sh_groups = 0, size_t n_sh_segs = 0, size_t n_sh_items = 0, size_t n_sh_pos = 0)
 {
     PlanLayout L{};
     size_t o = 0;
@@ -218,12 +220,17 @@ PlanLayout make_layout(int n_calls, int total_sel, int total_q, int total_seg, i
     L.merge_rows = take(sizeof(PcMergeRow) * (size_t)std::max(total_q, 1));
     L.items_dec = take(sizeof(PcItem) * (size_t)std::max(n_dec, 1));
     L.items_pre = take(sizeof(PcItem) * (size_t)std::max(n_pre, 1));
+    L.sh_groups = take(sizeof(PcShGroup) * std::max<size_t>(n_sh_groups, 1));
+    L.sh_segs = take(sizeof(PcShSeg) * std::max<size_t>(n_sh_segs, 1));
+    L.sh_items = take(sizeof(PcShItem) * std::max<size_t>(n_sh_items, 1));
+    L.sh_pos = take(sizeof(int32_t) * std::max<size_t>(n_sh_pos, 1));
     L.h2d_bytes = o;
     L.segs = take(sizeof(PcSegment) * (size_t)std::max(total_seg, 1));
     L.seg_kvoff = take(sizeof(int32_t) * (size_t)std::max(total_seg, 1));
     L.rot_seg = take(sizeof(float2) * (size_t)std::max(total_seg, 1) * (D / 2));
     L.rot_q = take(sizeof(float2) * (size_t)std::max(total_q, 1) * (D / 2));
     L.tiles = take(sizeof(PcTile) * (size_t)std::max<int64_t>(total_tiles, 1));
+    L.sh_rot = take(sizeof(float2) * std::max<size_t>(n_sh_pos, 1) * (D / 2));
     L.part_o = take(sizeof(uint16_t) * (size_t)std::max<int64_t>(part_rows, 1) * H_q * D);
     L.part_ml = take(sizeof(float) * (size_t)std::max<int64_t>(part_rows, 1) * H_q * 2);
     L.total = o;
@@ -614,6 +621,13 @@ int32_t pc_profile_read(pc_cache *c, double ms_total[PC_N_KERNEL_CLASSES], int64
     return PC_OK;
 }
 
+int32_t pc_set_decode_sharing(pc_cache *c, int32_t mode)
+{
+    if (!c || mode < 0 || mode > 2) return PC_ERR_INVALID_ARG;
+    c->decode_sharing = mode;
+    return PC_OK;
+}
+
 int32_t pc_set_tuning(pc_cache *c, int32_t decode_tiles_per_split, int32_t prefill_tiles_per_split)
 {
     if (!c || decode_tiles_per_split < 0 || prefill_tiles_per_split < 0) return PC_ERR_INVALID_ARG;
@@ -629,8 +643,124 @@ struct Planned {
     PlanLayout lay;
     int n_calls = 0, total_sel = 0, total_q = 0, total_seg = 0, n_dec = 0, n_pre = 0, pre_waves = 4;
     int n_merge_rows = 0;
+    int n_sh_items = 0;
+    size_t n_sh_pos = 0;
     std::vector<Resolved> res;
 };
+
+// a decode call's parents in ascending cache-slot order; ties (a message listed twice) go by start
+static void sort_by_slot(const pc_cache *c, Resolved &r)
+{
+    if (r.sel.size() < 2) return;
+    struct SortKey { uint64_t key; int2 v; };
+    static thread_local std::vector<SortKey> keys;
+    keys.resize(r.sel.size());
+    for (size_t e = 0; e < r.sel.size(); ++e)
+        keys[e] = {((uint64_t)(uint32_t)c->msgs[(size_t)r.sel[e].x].slot_start << 32) | ((uint32_t)r.sel[e].y ^ 0x80000000u), r.sel[e]};
+    std::sort(keys.begin(), keys.end(), [](const SortKey &a, const SortKey &b) { return a.key < b.key; });
+    for (size_t e = 0; e < r.sel.size(); ++e) r.sel[e] = keys[e].v;
+}
+
+// Shared decode (message-major): runs of consecutive one-row calls are cut into groups of up to
+// 32 * 8 / g rows; a group whose calls overlap enough walks the union of their messages once.
+struct SharedPlan {
+    std::vector<char> in_shared;                 // per call
+    std::vector<PcShGroup> groups;
+    std::vector<PcShSeg> segs;
+    std::vector<PcShItem> items;
+    std::vector<int32_t> pos;                    // rotation positions, PC_SH_ABSENT where a row does not list the message
+};
+
+// Calls that read n times the bytes of the union gain from the shared walk once n exceeds
+// what a union tile costs there (a whole workgroup's pass) relative to a streamed tile.
+constexpr double SHARE_MIN = 4.0;
+
+static void plan_shared(const pc_cache *c, std::vector<Resolved> &res, const std::vector<int> &q_off, int g, SharedPlan &sp)
+{
+    const int n_calls = (int)res.size();
+    sp.in_shared.assign((size_t)n_calls, 0);
+    if (c->decode_sharing == 1 || !(g == 1 || g == 2 || g == 4 || g == 8)) return;
+    const int rows_max = 32 * (8 / g);
+    std::vector<int32_t> useg_of_msg(c->msgs.size(), -1);
+    struct USeg { int32_t msg, occ; int64_t slot; int32_t len; };
+    struct Entry { int32_t useg, row, pos; };
+    std::vector<USeg> usegs;
+    std::vector<Entry> entries;
+    std::vector<std::pair<int64_t, int32_t>> extra;       // (msg << 20 | occurrence) -> useg, for repeats within a call
+    std::vector<int32_t> order, new_index;
+    for (int i = 0; i < n_calls;) {
+        if (res[i].n_q != 1) { ++i; continue; }
+        int j = i;
+        while (j < n_calls && res[j].n_q == 1 && j - i < rows_max) ++j;
+        usegs.clear(); entries.clear(); extra.clear();
+        int64_t call_tiles = 0;
+        auto lookup = [&](int32_t m, int32_t occ) -> int32_t {
+            if (occ == 0) {
+                if (useg_of_msg[(size_t)m] < 0) {
+                    useg_of_msg[(size_t)m] = (int32_t)usegs.size();
+                    usegs.push_back({m, 0, c->msgs[(size_t)m].slot_start, c->msgs[(size_t)m].len});
+                }
+                return useg_of_msg[(size_t)m];
+            }
+            const int64_t key = ((int64_t)m << 20) | occ;
+            for (auto &kv : extra) if (kv.first == key) return kv.second;
+            extra.push_back({key, (int32_t)usegs.size()});
+            usegs.push_back({m, occ, c->msgs[(size_t)m].slot_start, c->msgs[(size_t)m].len});
+            return extra.back().second;
+        };
+        for (int r = 0; r < j - i; ++r) {
+            Resolved &rc = res[(size_t)(i + r)];
+            sort_by_slot(c, rc);
+            call_tiles += rc.tiles;
+            int32_t prev = -1, occ = 0, self_occ = 0;
+            for (const int2 &e : rc.sel) {
+                occ = (e.x == prev) ? occ + 1 : 0;
+                prev = e.x;
+                if (e.x == rc.self_msg) ++self_occ;
+                if (c->msgs[(size_t)e.x].len > 0)
+                    entries.push_back({lookup(e.x, occ), r, e.y - c->msgs[(size_t)e.x].base_pos});
+            }
+            if (rc.self_msg >= 0 && rc.self_len > 0)      // the call's own tail: one row, one token from the end -> all of it visible
+                entries.push_back({lookup(rc.self_msg, self_occ), r, rc.self_start - c->msgs[(size_t)rc.self_msg].base_pos});
+        }
+        int64_t union_tiles = 0;
+        for (const USeg &u : usegs) union_tiles += (u.len + PC_TILE - 1) / PC_TILE;
+        const bool take = union_tiles > 0 && union_tiles < INT32_MAX / 2 &&
+                          (c->decode_sharing == 2 || (j - i >= 2 && (double)call_tiles >= SHARE_MIN * (double)union_tiles));
+        if (take) {
+            // union in cache-slot order
+            order.resize(usegs.size()); new_index.resize(usegs.size());
+            for (size_t u = 0; u < usegs.size(); ++u) order[u] = (int32_t)u;
+            std::sort(order.begin(), order.end(), [&](int32_t a, int32_t b) {
+                return usegs[(size_t)a].slot != usegs[(size_t)b].slot ? usegs[(size_t)a].slot < usegs[(size_t)b].slot
+                                                                      : usegs[(size_t)a].occ < usegs[(size_t)b].occ; });
+            PcShGroup gr{};
+            gr.seg_off = (int32_t)sp.segs.size(); gr.n_seg = (int32_t)usegs.size();
+            gr.row0 = q_off[(size_t)i]; gr.n_rows = j - i; gr.rot_off = (int32_t)sp.pos.size();
+            gr.n_splits = 1; gr.part_off = 0;
+            int32_t tile_off = 0;
+            for (size_t k = 0; k < order.size(); ++k) {
+                const USeg &u = usegs[(size_t)order[k]];
+                new_index[(size_t)order[k]] = (int32_t)k;
+                PcShSeg sg{};
+                sg.slot_start = (int32_t)u.slot; sg.len = u.len; sg.tile_off = tile_off;
+                tile_off += (u.len + PC_TILE - 1) / PC_TILE;
+                sp.segs.push_back(sg);
+            }
+            gr.n_tiles = tile_off;
+            sp.pos.resize(sp.pos.size() + usegs.size() * (size_t)gr.n_rows, PC_SH_ABSENT);
+            for (const Entry &en : entries) {
+                const int32_t k = new_index[(size_t)en.useg];
+                sp.segs[(size_t)gr.seg_off + (size_t)k].vis[en.row >> 5] |= 1u << (en.row & 31);
+                sp.pos[(size_t)gr.rot_off + (size_t)k * (size_t)gr.n_rows + (size_t)en.row] = en.pos;
+            }
+            sp.groups.push_back(gr);
+            for (int k = i; k < j; ++k) sp.in_shared[(size_t)k] = 1;
+        }
+        for (const USeg &u : usegs) if (u.occ == 0) useg_of_msg[(size_t)u.msg] = -1;
+        i = j;
+    }
+}
 
 static int32_t plan_and_stage(pc_cache *c, const pc_call *calls, int32_t n_calls, bool want_items,
                               hipStream_t st, Planned &P)
@@ -650,14 +780,22 @@ static int32_t plan_and_stage(pc_cache *c, const pc_call *calls, int32_t n_calls
     P.pre_waves = 8;
     std::vector<PcCallDesc> cds((size_t)n_calls);
     std::vector<PcItem> dec, pre;
-    struct SortKey { uint64_t key; int2 v; };
-    std::vector<SortKey> sort_keys;
     int64_t part_rows = 0, total_tiles = 0;
     int sel_off = 0, q_off = 0, seg_off = 0;
+    // groups of one-row calls that share enough of their messages take the shared walk
+    SharedPlan sp;
+    sp.in_shared.assign((size_t)n_calls, 0);
+    if (want_items && bf16) {
+        std::vector<int> q_offs((size_t)n_calls);
+        for (int i = 0, o = 0; i < n_calls; ++i) { q_offs[(size_t)i] = o; o += P.res[(size_t)i].n_q; }
+        plan_shared(c, P.res, q_offs, g, sp);
+    }
     // first pass: how many prefill groups without splitting (to decide on KV splits)
     int64_t pre_groups = 0, dec_groups = 0;
     if (want_items && bf16)
-        for (auto &r : P.res) {
+        for (int i = 0; i < n_calls; ++i) {
+            const Resolved &r = P.res[(size_t)i];
+            if (sp.in_shared[(size_t)i]) continue;
             if (r.n_q * g > 16) pre_groups += (int64_t)(((r.n_q + 31) / 32) * g + P.pre_waves - 1) / P.pre_waves * H_kv;
             else dec_groups += H_kv;
         }
@@ -669,20 +807,13 @@ static int32_t plan_and_stage(pc_cache *c, const pc_call *calls, int32_t n_calls
         cd.self_len = r.self_len; cd.n_splits = 1; cd.part_off = 0; cd.tile_off = (int32_t)total_tiles;
         total_tiles += r.tiles;
         sel_off += cd.n_sel; q_off += cd.n_q; seg_off += cd.n_seg;
-        if (!want_items || !bf16) continue;
+        if (!want_items || !bf16 || sp.in_shared[(size_t)i]) continue;
         const int T = r.tiles;
         if (r.n_q * g <= 16) {                       // decode-shaped: all rows x heads of a KV head in one wave
             // Attention does not depend on the order the keys are visited in (each keeps its own
             // position), so a decode call walks its parents in ascending cache-slot order: calls that
             // share messages then touch them at about the same time and the later ones hit in L2.
-            if (r.sel.size() > 1) {                  // ties (a message listed twice) go by start, so the order is the listing's no more
-                sort_keys.resize(r.sel.size());
-                for (size_t e = 0; e < r.sel.size(); ++e)
-                    sort_keys[e] = {((uint64_t)(uint32_t)c->msgs[(size_t)r.sel[e].x].slot_start << 32) |
-                                    ((uint32_t)r.sel[e].y ^ 0x80000000u), r.sel[e]};
-                std::sort(sort_keys.begin(), sort_keys.end(), [](const SortKey &a, const SortKey &b) { return a.key < b.key; });
-                for (size_t e = 0; e < r.sel.size(); ++e) r.sel[e] = sort_keys[e].v;
-            }
+            sort_by_slot(c, r);
             // as few splits as fill the chip (256 workgroups): the kernel is bound by memory, and every
             // split beyond that only adds partial results to write and merge
             int ns = c->decode_tiles_per_split > 0 ? (T + c->decode_tiles_per_split - 1) / c->decode_tiles_per_split
@@ -728,10 +859,28 @@ static int32_t plan_and_stage(pc_cache *c, const pc_call *calls, int32_t n_calls
         }
         if (cd.n_splits > 1) { cd.part_off = (int32_t)part_rows; part_rows += (int64_t)cd.n_splits * cd.n_q; }
     }
+    // shared groups: as many splits of the union as fill the chip together
+    for (size_t gi = 0; gi < sp.groups.size(); ++gi) {
+        PcShGroup &gr = sp.groups[gi];
+        const int T = gr.n_tiles;
+        int ns = c->decode_tiles_per_split > 0 ? (T + c->decode_tiles_per_split - 1) / c->decode_tiles_per_split
+                                               : (int)std::min<int64_t>((256 + (int64_t)sp.groups.size() * H_kv - 1) / ((int64_t)sp.groups.size() * H_kv),
+                                                                        std::max(1, T / 8));
+        ns = std::max(1, std::min(MAX_SPLITS, ns));
+        const int chunk = std::max(1, (T + ns - 1) / ns);
+        ns = std::max(1, (T + chunk - 1) / chunk);
+        gr.n_splits = ns;
+        if (ns > 1) { gr.part_off = (int32_t)part_rows; part_rows += (int64_t)ns * gr.n_rows; }
+        for (int sidx = 0; sidx < ns; ++sidx)
+            sp.items.push_back(PcShItem{(int32_t)gi, sidx * chunk, std::min(T, (sidx + 1) * chunk), sidx});
+    }
     if (part_rows > INT32_MAX) return fail(c, PC_ERR_SHAPE, "attend: partial buffer too large");
     P.n_dec = (int)dec.size(); P.n_pre = (int)pre.size();
+    P.n_sh_items = (int)sp.items.size(); P.n_sh_pos = sp.pos.size();
     if (total_tiles > INT32_MAX / 2) return fail(c, PC_ERR_SHAPE, "attend: too many KV tiles");
-    P.lay = make_layout(n_calls, P.total_sel, P.total_q, P.total_seg, P.n_dec, P.n_pre, part_rows, total_tiles, c->cfg.n_q_heads, c->D);
+    if (sp.pos.size() > (size_t)INT32_MAX / 2) return fail(c, PC_ERR_SHAPE, "attend: shared decode table too large");
+    P.lay = make_layout(n_calls, P.total_sel, P.total_q, P.total_seg, P.n_dec, P.n_pre, part_rows, total_tiles, c->cfg.n_q_heads, c->D,
+                        sp.groups.size(), sp.segs.size(), sp.items.size(), sp.pos.size());
     if (c->host_only) return PC_OK;
 
     int32_t rc = ensure_ws(c, P.lay.total, st);
@@ -752,8 +901,17 @@ static int32_t plan_and_stage(pc_cache *c, const pc_call *calls, int32_t n_calls
         if (cds[i].n_splits > 1)
             for (int q = 0; q < r.n_q; ++q) hm[P.n_merge_rows++] = PcMergeRow{cds[i].q_off + q, cds[i].part_off + q, cds[i].n_splits, r.n_q};
     }
+    for (const PcShGroup &gr : sp.groups)
+        if (gr.n_splits > 1)
+            for (int q = 0; q < gr.n_rows; ++q) hm[P.n_merge_rows++] = PcMergeRow{gr.row0 + q, gr.part_off + q, gr.n_splits, gr.n_rows};
     if (!dec.empty()) std::memcpy(h + P.lay.items_dec, dec.data(), sizeof(PcItem) * dec.size());
     if (!pre.empty()) std::memcpy(h + P.lay.items_pre, pre.data(), sizeof(PcItem) * pre.size());
+    if (!sp.items.empty()) {
+        std::memcpy(h + P.lay.sh_groups, sp.groups.data(), sizeof(PcShGroup) * sp.groups.size());
+        std::memcpy(h + P.lay.sh_segs, sp.segs.data(), sizeof(PcShSeg) * sp.segs.size());
+        std::memcpy(h + P.lay.sh_items, sp.items.data(), sizeof(PcShItem) * sp.items.size());
+        std::memcpy(h + P.lay.sh_pos, sp.pos.data(), sizeof(int32_t) * sp.pos.size());
+    }
     PC_HIP(c, hipMemcpyAsync(c->ws, h, P.lay.h2d_bytes, hipMemcpyHostToDevice, st));
     PC_HIP(c, hipEventRecord(slot->ev, st));
     slot->used = true;
@@ -765,6 +923,11 @@ static int32_t plan_and_stage(pc_cache *c, const pc_call *calls, int32_t n_calls
                              P.total_q, (PcSegment *)(w + P.lay.segs), (int32_t *)(w + P.lay.seg_kvoff),
                              (float2 *)(w + P.lay.rot_seg), (float2 *)(w + P.lay.rot_q), (PcTile *)(w + P.lay.tiles), st);
         PC_HIP(c, hipGetLastError());
+        if (P.n_sh_items > 0) {
+            pc_launch_shared_rot((const int32_t *)(w + P.lay.sh_pos), (int64_t)P.n_sh_pos, c->inv_freq_dev, c->half,
+                                 (float2 *)(w + P.lay.sh_rot), st);
+            PC_HIP(c, hipGetLastError());
+        }
     }
     return PC_OK;
 }
@@ -808,6 +971,16 @@ int32_t pc_attend(pc_cache *c, const pc_call *calls, int32_t n_calls, const void
         ProfScope ps(c, 3, st);
         L.items = (const PcItem *)(w + P.lay.items_dec);
         pc_launch_decode_bf16(L, P.n_dec, st);
+        PC_HIP(c, hipGetLastError());
+    }
+    if (P.n_sh_items > 0) {
+        ProfScope ps(c, 3, st);
+        PcShLaunch S{};
+        S.groups = (const PcShGroup *)(w + P.lay.sh_groups);
+        S.segs = (const PcShSeg *)(w + P.lay.sh_segs);
+        S.items = (const PcShItem *)(w + P.lay.sh_items);
+        S.rot = (const float2 *)(w + P.lay.sh_rot);
+        pc_launch_decode_shared_bf16(L, S, P.n_sh_items, st);
         PC_HIP(c, hipGetLastError());
     }
     if (P.n_merge_rows > 0) {

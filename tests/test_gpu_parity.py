@@ -29,11 +29,13 @@ def hip():
 
 
 def run_and_compare(hip, w, rows_per_call=None, calls_subset=None, events=None, tuning=None, batch_appends=False,
-                    lse_rel=0.0):
+                    lse_rel=0.0, sharing=None):
     import torch
     cache = hip.make_cache(w)
     if tuning:
         cache.set_tuning(*tuning)
+    if sharing is not None:
+        cache.set_decode_sharing(sharing)
     dw = hip.DeviceWorkload(w)
     say(f"[run] {w.name} dtype={w.dtype} Hq={w.n_q_heads} Hkv={w.n_kv_heads} D={w.head_dim} "
         f"msgs={w.n_messages} attends={len(attend_events(w))}")
