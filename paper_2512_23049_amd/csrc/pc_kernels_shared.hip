@@ -12,9 +12,10 @@
 //     kernel fills;
 //   * the rows are independent calls, so there is no causal structure: a call's own growing
 //     tail is just one more message that only its row sees.
-// The loop is the plain one (stage a tile through registers into one of two LDS buffers, one
-// barrier per tile, ordinary online softmax): the path is bound by the one pass over the
-// union's bytes, not by the MFMA rate.
+// K and V tiles go global -> LDS directly (16 bytes per lane, no staging registers) into a
+// ring of four slots, requested three tiles ahead; one barrier per tile, ordinary online
+// softmax: the path is bound by the one pass over the union's bytes and by the latency of that
+// pass, not by the MFMA rate.
 //
 // Register/LDS layouts (fragment addressing, key permutation of the score rows, accumulator
 // layout) are those of the prefill kernel, so that split partials and the merge are shared.
@@ -34,6 +35,26 @@ __device__ __forceinline__ float sh_sum_halves(float x)
 {
     auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
     return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+// One 16-byte-per-lane direct load: lane l's 16 bytes land at lds_wave_base + 16*l.  Assembly, so
+// that the compiler keeps no record of the LDS write and does not drain every outstanding request
+// in front of later LDS reads or at barriers; completion is awaited with s_waitcnt vmcnt(n).
+__device__ __forceinline__ void sh_dma16(const void *gbase_uniform, unsigned lane_off, unsigned lds_wave_base)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 ::"s"(lds_wave_base), "v"(lane_off), "s"(gbase_uniform) : "memory", "m0");
+}
+// workgroup barrier without the fence of __syncthreads() (which would wait for every direct load)
+__device__ __forceinline__ void sh_barrier() { asm volatile("s_barrier" ::: "memory"); }
+
+#define SH_RING 4                 // ring slots of 16 KB (K and V tile)
+#define SH_AHEAD (SH_RING - 1)    // tiles in flight beyond the one being computed
+// wait until at most the 2 * (SH_AHEAD - 1) youngest direct loads of this wave are outstanding
+__device__ __forceinline__ void sh_wait_landed()
+{
+    constexpr int n = 2 * (SH_AHEAD - 1);
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (n & 15) | ((n >> 4) << 14));     // vmcnt: bits 3:0 and 15:14
 }
 
 }  // namespace
@@ -56,8 +77,9 @@ __global__ __launch_bounds__(256) void pc_shared_rot_kernel(const int32_t *__res
 
 __global__ __launch_bounds__(512, 1) void pc_decode_shared_bf16_kernel(PcLaunch L, PcShLaunch S)
 {
-    __shared__ __attribute__((aligned(1024))) unsigned char s_k[2][8192];
-    __shared__ __attribute__((aligned(1024))) unsigned char s_v[2][8192];
+    __shared__ __attribute__((aligned(1024))) unsigned char s_k[SH_RING][8192];
+    __shared__ __attribute__((aligned(1024))) unsigned char s_v[SH_RING][8192];
+    __shared__ __attribute__((aligned(16))) float4 s_qm[8][8][64];    // upper half (dims 64..127) of the fp32 query master
 
     const int kh = blockIdx.x % L.n_kv_heads;          // consecutive workgroups (one per XCD) take different KV heads
     const PcShItem item = S.items[blockIdx.x / L.n_kv_heads];
@@ -71,9 +93,10 @@ __global__ __launch_bounds__(512, 1) void pc_decode_shared_bf16_kernel(PcLaunch 
     const bool row_ok = row < gr.n_rows;
     const int Rg = gr.row0 + (row_ok ? row : 0);         // the group's calls are consecutive one-row calls
 
-    // query turned by its own position, scaled by softmax_scale * log2(e), fp32:
-    // x[ks][j] is dim 16*ks + 8*hh + j, y[ks][j] is dim 64 + 16*ks + 8*hh + j
-    float x[4][8], y[4][8];
+    // query turned by its own position, scaled by softmax_scale * log2(e), fp32: x[ks][j] is dim
+    // 16*ks + 8*hh + j (registers); its partner 64 dims up is kept in LDS (s_qm[wave][2*ks + j/4][lane],
+    // read back once per message): the registers are needed for the MFMA fragments
+    float x[4][8];
     {
         const uint16_t *qp = (const uint16_t *)L.q + ((int64_t)Rg * L.n_q_heads + h) * PC_D + 8 * hh;
         const float2 *rq = L.rot_q + (int64_t)Rg * (PC_D / 2) + 8 * hh;
@@ -82,14 +105,17 @@ __global__ __launch_bounds__(512, 1) void pc_decode_shared_bf16_kernel(PcLaunch 
         for (int ks = 0; ks < 4; ++ks) {
             const uint4 lo = ldg16(qp + 16 * ks), hi = ldg16(qp + 16 * ks + 64);
             const uint32_t lw[4] = {lo.x, lo.y, lo.z, lo.w}, hw[4] = {hi.x, hi.y, hi.z, hi.w};
+            float yy[8];
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
                 const float a = ((j & 1) ? bf_hi(lw[j >> 1]) : bf_lo(lw[j >> 1])) * sc;
                 const float b = ((j & 1) ? bf_hi(hw[j >> 1]) : bf_lo(hw[j >> 1])) * sc;
                 const float2 cs = rq[16 * ks + j];
                 x[ks][j] = a * cs.x - b * cs.y;
-                y[ks][j] = a * cs.y + b * cs.x;
+                yy[j] = a * cs.y + b * cs.x;
             }
+            s_qm[wave][2 * ks][lane] = make_float4(yy[0], yy[1], yy[2], yy[3]);
+            s_qm[wave][2 * ks + 1][lane] = make_float4(yy[4], yy[5], yy[6], yy[7]);
         }
     }
 
@@ -110,44 +136,73 @@ __global__ __launch_bounds__(512, 1) void pc_decode_shared_bf16_kernel(PcLaunch 
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[db][r] = 0.f;
 
-    // segment cursor over the group's union list (uniform over the workgroup)
+    // Cursor of the REQUESTS over the group's union list (uniform over the workgroup): tiles are
+    // requested in order, so it only moves forward; the descriptor of the segment after the
+    // current one is loaded when the cursor enters a segment, several tiles before it is needed.
     const PcShSeg *segs = S.segs + gr.seg_off;
-    int e = 0, seg_slot = 0, seg_len = 0, seg_tile0 = 0, seg_tiles_end = 0;
-    bool vis = false;
-    auto seek = [&](int t) {
-        if (seg_tiles_end == 0) {                        // first use: binary search
-            int lo = 0, hi = gr.n_seg - 1;
-            while (lo < hi) {
-                const int mid = (lo + hi + 1) >> 1;
-                if (segs[mid].tile_off <= t) lo = mid; else hi = mid - 1;
-            }
-            e = lo - 1;
+    struct SegD { int slot, len, tile0; unsigned vis; };
+    // (scalar loads: they are counted apart from the direct loads, so waiting for a descriptor does
+    // not drain the ring)
+    typedef int i32x4 __attribute__((ext_vector_type(4)));
+    const int ub_s = __builtin_amdgcn_readfirstlane(ub);
+    auto load_seg = [&](int e) {
+        const int ec = __builtin_amdgcn_readfirstlane(min(e, gr.n_seg - 1));
+        const uintptr_t at = reinterpret_cast<uintptr_t>(segs + ec);
+        const i32x4 w = *reinterpret_cast<const __attribute__((address_space(4))) i32x4 *>(at);
+        SegD d;
+        d.slot = w.x; d.len = w.y; d.tile0 = w.z;
+        d.vis = *reinterpret_cast<const __attribute__((address_space(4))) unsigned *>(at + 16 + 4 * ub_s);
+        return d;
+    };
+    int e = 0;
+    {
+        int lo = 0, hi = gr.n_seg - 1;                   // the segment that owns the first tile
+        while (lo < hi) {
+            const int mid = (lo + hi + 1) >> 1;
+            if (segs[mid].tile_off <= item.tile_begin) lo = mid; else hi = mid - 1;
         }
-        while (t >= seg_tiles_end) {
-            ++e;
-            seg_slot = segs[e].slot_start; seg_len = segs[e].len; seg_tile0 = segs[e].tile_off;
-            seg_tiles_end = seg_tile0 + (seg_len + PC_TILE - 1) / PC_TILE;
-        }
+        e = lo;
+    }
+    SegD sg = load_seg(e), sg_next = load_seg(e + 1);
+    // a tile in flight: where it comes from is only needed for the request; what the compute step
+    // needs travels in these three scalars
+    struct TileD { int seg, valid; unsigned vis; };
+    const unsigned wave_lds = __builtin_amdgcn_readfirstlane(wave) * 1024;
+    const unsigned lds_k = (unsigned)(size_t)&s_k[0][0] + wave_lds, lds_v = (unsigned)(size_t)&s_v[0][0] + wave_lds;
+    auto request = [&](int t, int ring) {                // t in [tile_begin, tile_end)
+        while (t >= sg.tile0 + (sg.len + PC_TILE - 1) / PC_TILE) { ++e; sg = sg_next; sg_next = load_seg(e + 1); }
+        const int key0 = (t - sg.tile0) * PC_TILE;
+        const int64_t slot0 = (int64_t)__builtin_amdgcn_readfirstlane(sg.slot) + key0;
+        sh_dma16(kb + slot0 * 256, k_src_off, lds_k + ring * 8192);
+        sh_dma16(vb + slot0 * 256, v_src_off, lds_v + ring * 8192);
+        TileD d;
+        d.seg = e; d.valid = min(PC_TILE, sg.len - key0); d.vis = sg.vis;
+        return d;
     };
 
     bf16x8 qop[8];
     int cur_seg = -1;
     // turn this lane's row by -(start - base) of the message for its call; rows that do not list the
     // message keep whatever operands they have (their scores are masked)
-    auto turn = [&](int seg) {
+    bool vis = false;
+    auto turn = [&](int seg, unsigned vis_word) {
         cur_seg = seg;
-        vis = row_ok && ((segs[seg].vis[ub] >> n) & 1u);
+        vis = row_ok && ((vis_word >> n) & 1u);
         if (vis) {
             const float4 *rs = reinterpret_cast<const float4 *>(S.rot + ((int64_t)gr.rot_off + (int64_t)seg * gr.n_rows + row) * (PC_D / 2) + 8 * hh);
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks) {
                 uint32_t lo[4], hi[4];
 #pragma unroll
-                for (int j2 = 0; j2 < 4; ++j2) {
-                    const float4 c = rs[(16 * ks + 2 * j2) >> 1];       // (cos, sin) of pairs 2*j2, 2*j2 + 1
-                    const float x0 = x[ks][2 * j2], y0 = y[ks][2 * j2], x1 = x[ks][2 * j2 + 1], y1 = y[ks][2 * j2 + 1];
-                    lo[j2] = pack_bf16(x0 * c.x + y0 * c.y, x1 * c.z + y1 * c.w);
-                    hi[j2] = pack_bf16(y0 * c.x - x0 * c.y, y1 * c.z - x1 * c.w);
+                for (int j4 = 0; j4 < 2; ++j4) {
+                    const float4 c0 = rs[(16 * ks + 4 * j4) >> 1];          // (cos, sin) of pairs 4*j4, 4*j4 + 1
+                    const float4 c1 = rs[((16 * ks + 4 * j4) >> 1) + 1];    // ... 4*j4 + 2, 4*j4 + 3
+                    const float x0 = x[ks][4 * j4], x1 = x[ks][4 * j4 + 1], x2 = x[ks][4 * j4 + 2], x3 = x[ks][4 * j4 + 3];
+                    const float4 yv = s_qm[wave][2 * ks + j4][lane];
+                    lo[2 * j4] = pack_bf16(x0 * c0.x + yv.x * c0.y, x1 * c0.z + yv.y * c0.w);
+                    hi[2 * j4] = pack_bf16(yv.x * c0.x - x0 * c0.y, yv.y * c0.z - x1 * c0.w);
+                    lo[2 * j4 + 1] = pack_bf16(x2 * c1.x + yv.z * c1.y, x3 * c1.z + yv.w * c1.w);
+                    hi[2 * j4 + 1] = pack_bf16(yv.z * c1.x - x2 * c1.y, yv.w * c1.z - x3 * c1.w);
                 }
                 qop[ks] = __builtin_bit_cast(bf16x8, make_uint4(lo[0], lo[1], lo[2], lo[3]));
                 qop[ks + 4] = __builtin_bit_cast(bf16x8, make_uint4(hi[0], hi[1], hi[2], hi[3]));
@@ -159,13 +214,24 @@ __global__ __launch_bounds__(512, 1) void pc_decode_shared_bf16_kernel(PcLaunch 
 
     auto compute = [&](int buf, int valid) {
         const unsigned char *kt = &s_k[buf][0], *vt = &s_v[buf][0];
+        // all eight K fragments are requested up front; each is replaced by a V fragment as soon as its
+        // MFMA has consumed it, so the P.V MFMAs find their operands in registers
+        bf16x8 fr[8];
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks)
+            fr[ks] = *reinterpret_cast<const bf16x8 *>(kt + krow * 256 + (((2 * ks + hh) ^ (krow & 15)) << 4));
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) asm volatile("" : "+v"(fr[ks]));      // (keeps the compiler from moving each read down to its MFMA)
         f32x16 s;
 #pragma unroll
         for (int r = 0; r < 16; ++r) s[r] = 0.f;
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) {
-            const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(kt + krow * 256 + (((2 * ks + hh) ^ (krow & 15)) << 4));
-            s = MFMA32(kf, qop[ks], s);
+            s = MFMA32(fr[ks], qop[ks], s);
+            // V fragment f: d block f & 3, key step f >> 2; group 2*(f >> 2) + hh, dim 32*(f & 3) + n
+            fr[ks] = *reinterpret_cast<const bf16x8 *>(vt + ((2 * (ks >> 2) + hh) * PC_D + 32 * (ks & 3) + n) * 16);
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
         }
         const int lim = vis ? valid : 0;
         float mx = -INFINITY;
@@ -196,47 +262,33 @@ __global__ __launch_bounds__(512, 1) void pc_decode_shared_bf16_kernel(PcLaunch 
         const bf16x8 p0 = __builtin_bit_cast(bf16x8, make_uint4(pk[0], pk[1], pk[2], pk[3]));
         const bf16x8 p1 = __builtin_bit_cast(bf16x8, make_uint4(pk[4], pk[5], pk[6], pk[7]));
 #pragma unroll
-        for (int f = 0; f < 8; ++f) {
-            // V fragment f: d block f & 3, key step f >> 2; group 2*(f >> 2) + hh, dim 32*(f & 3) + n
-            const bf16x8 vf = *reinterpret_cast<const bf16x8 *>(vt + ((2 * (f >> 2) + hh) * PC_D + 32 * (f & 3) + n) * 16);
-            acc[f & 3] = MFMA32(vf, (f >> 2) ? p1 : p0, acc[f & 3]);
-        }
+        for (int f = 0; f < 8; ++f) acc[f & 3] = MFMA32(fr[f], (f >> 2) ? p1 : p0, acc[f & 3]);
     };
 
-    // the walk: tile t is computed from LDS buffer (t - tile_begin) & 1 while tile t + 1 is on its way
-    // from global memory in two registers per thread
+    // The walk.  Ring slot of tile t is (t - t0) mod SH_RING; SH_AHEAD tiles are in flight beyond the
+    // one being computed.  Requests beyond the last tile repeat the last one, so that the number of
+    // requests in flight is the same at every wait.
     const int t0 = item.tile_begin, t1 = item.tile_end;
     if (t0 < t1) {
-        seek(t0);
-        int c_seg = e, c_valid = min(PC_TILE, seg_len - (t0 - seg_tile0) * PC_TILE);
-        {
-            const int64_t slot0 = (int64_t)seg_slot + (int64_t)(t0 - seg_tile0) * PC_TILE;
-            const uint4 a = ldg16(kb + slot0 * 256 + k_src_off), b = ldg16(vb + slot0 * 256 + v_src_off);
-            *reinterpret_cast<uint4 *>(&s_k[0][threadIdx.x * 16]) = a;
-            *reinterpret_cast<uint4 *>(&s_v[0][threadIdx.x * 16]) = b;
-        }
-        __syncthreads();
+        const int last = t1 - 1;
+        TileD d[SH_AHEAD + 1];
+#pragma unroll
+        for (int i = 0; i < SH_AHEAD; ++i) d[i] = request(min(t0 + i, last), i);
+        sh_wait_landed();                                // the first tile has landed
+        sh_barrier();
         for (int t = t0; t < t1; ++t) {
-            const int buf = (t - t0) & 1;
-            const bool more = t + 1 < t1;
-            uint4 nk = make_uint4(0, 0, 0, 0), nv = nk;
-            int n_seg_i = c_seg, n_valid = 0;
-            if (more) {
-                seek(t + 1);
-                n_seg_i = e; n_valid = min(PC_TILE, seg_len - (t + 1 - seg_tile0) * PC_TILE);
-                const int64_t slot0 = (int64_t)seg_slot + (int64_t)(t + 1 - seg_tile0) * PC_TILE;
-                nk = ldg16(kb + slot0 * 256 + k_src_off);
-                nv = ldg16(vb + slot0 * 256 + v_src_off);
-            }
-            if (c_seg != cur_seg) turn(c_seg);
-            compute(buf, c_valid);
-            if (more) {
-                *reinterpret_cast<uint4 *>(&s_k[buf ^ 1][threadIdx.x * 16]) = nk;
-                *reinterpret_cast<uint4 *>(&s_v[buf ^ 1][threadIdx.x * 16]) = nv;
-            }
-            __syncthreads();
-            c_seg = n_seg_i; c_valid = n_valid;
+            const int ring = (t - t0) & (SH_RING - 1);
+            // (the table loads of a turn go first: issued behind the new requests they would have to wait for them)
+            if (d[0].seg != cur_seg) turn(d[0].seg, d[0].vis);
+            // tile t + SH_AHEAD takes the slot of tile t - 1, which every wave left before the last barrier
+            d[SH_AHEAD] = request(min(t + SH_AHEAD, last), (ring + SH_AHEAD) & (SH_RING - 1));
+            compute(ring, d[0].valid);
+            sh_wait_landed();                            // tile t + 1 has landed (the later ones may be in flight)
+            sh_barrier();
+#pragma unroll
+            for (int i = 0; i < SH_AHEAD; ++i) d[i] = d[i + 1];
         }
+        __builtin_amdgcn_s_waitcnt(0x0F70);              // drain the repeated requests
     }
 
     // epilogue: a lane holds, for its row, dims 32*db + 8*(r/4) + 4*hh + (r%4)

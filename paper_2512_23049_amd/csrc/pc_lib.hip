@@ -671,9 +671,10 @@ struct SharedPlan {
     std::vector<int32_t> pos;                    // rotation positions, PC_SH_ABSENT where a row does not list the message
 };
 
-// Calls that read n times the bytes of the union gain from the shared walk once n exceeds
-// what a union tile costs there (a whole workgroup's pass) relative to a streamed tile.
-constexpr double SHARE_MIN = 4.0;
+// Calls that together list n times the tokens of the union gain from the shared walk once n
+// exceeds what a union tile costs there (a workgroup's pass over it for all rows: 8.7 ns per tile
+// and KV head with the chip full) relative to a tile streamed by one call (1.7 to 1.8 ns).
+constexpr double SHARE_MIN = 5.0;
 
 static void plan_shared(const pc_cache *c, std::vector<Resolved> &res, const std::vector<int> &q_off, int g, SharedPlan &sp)
 {
