@@ -65,7 +65,7 @@ def time_steps(fn, steps, warmup, torch):
     return (time.perf_counter() - t0) / steps
 
 
-def bench_attend_workload(name, w, steps, warmup, torch, harness, reappend_self=True, tuning=None):
+def bench_attend_workload(name, w, steps, warmup, torch, harness, reappend_self=True, tuning=None, sharing=None):
     """Loads the cache once, then times steps of (append new messages + attend)."""
     from paper_2512_23049_amd.binding import marshal_calls
     from pc_inputs import Call
@@ -78,6 +78,8 @@ def bench_attend_workload(name, w, steps, warmup, torch, harness, reappend_self=
     cache = harness.make_cache(w, slack_tokens=slack, extra_messages=total_steps * len(new_ids) + 16)
     if tuning:
         cache.set_tuning(*tuning)
+    if sharing is not None:
+        cache.set_decode_sharing(sharing)
     dw = harness.DeviceWorkload(w)
     dw.run(cache)                      # resident state: every message appended once
     torch.cuda.synchronize()
@@ -86,14 +88,20 @@ def bench_attend_workload(name, w, steps, warmup, torch, harness, reappend_self=
     append_steps = [s for s in dw.steps if s[0] == "append"]
     new_kv = {m: (append_steps[m][1], append_steps[m][2], append_steps[m][3], append_steps[m][4]) for m in new_ids}
 
+    # the call list is marshalled once; a step that appends the new messages again only patches their ids in
+    # (building thousands of ctypes entries per step would otherwise be what the step waits for)
+    marsh = marshal_calls(calls)
+    with_self = [(i, c.self_msg) for i, c in enumerate(calls) if c.self_msg >= 0]
+
     def step():
-        remap = {}
         if reappend_self:
+            remap = {}
             for m in new_ids:
                 k, v, L, res = new_kv[m]
                 remap[m] = cache.append_message(k.data_ptr(), v.data_ptr(), L, res)
-            cs = [Call(c.sel, remap.get(c.self_msg, c.self_msg), c.self_start, c.n_q, c.q_pos) for c in calls]
-            cache.attend(cs, q.data_ptr(), out.data_ptr(), 0, 0, marshal_calls(cs))
+            for i, m in with_self:
+                marsh[0][i].self_msg = remap[m]
+            cache.attend(calls, q.data_ptr(), out.data_ptr(), 0, 0, marsh)
         else:
             cache.attend(calls, q.data_ptr(), out.data_ptr(), 0, 0, att[2])
 
@@ -154,7 +162,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--skip-extras", action="store_true")
     ap.add_argument("--skip-cpu", action="store_true")
-    ap.add_argument("--only", default="", help="comma list of sections: decode,long,rounds,baseline,loop,reposition")
+    ap.add_argument("--only", default="", help="comma list of sections: decode,long,longdecode,rounds,baseline,loop,reposition")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="also launch one plain device copy of this many MiB (reference for scaling rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE counters)")
@@ -275,6 +283,24 @@ def main():
             "kernels_us": {k: v["avg_us"] for k, v in kern.items()},
         }
         del w5
+
+    # ------------------------------------------- the decode calls of configs[4] on their own (a decode step)
+    if not args.skip_extras and (not only or "longdecode" in only):
+        w5d = gen.long_context(n_prefill_q=0)
+        steps5 = max(3, min(args.steps, 50))
+        out_ld = {}
+        for name, mode in (("shared_walk", 0), ("per_call_walk", 1)):
+            sec, _, kern, vp = bench_attend_workload("long_context_decode", w5d, steps5, 3, torch, harness,
+                                                     reappend_self=False, sharing=mode)
+            b_dec = sum(v[1] + v[2] for v in vp) * 4096
+            out_ld[name] = {"us_per_step": sec * 1e6, "gbs_logical": b_dec / sec / 1e9,
+                            "kernels_us": {k: v["avg_us"] for k, v in kern.items()}}
+        line.setdefault("extras", {})["long_context_decode_only"] = {
+            "workload": "the 32 one-row calls of configs[4] alone (each ~64k selected tokens of the same 512 messages); "
+                        "step = one pc_attend, host planning included; shared walk (default rule) against "
+                        "pc_set_decode_sharing(1)",
+            "B_logical": b_dec, **out_ld}
+        del w5d
 
     # ---------------------------------------------------------------- multi-agent rounds (configs[3])
     if not args.skip_extras and (not only or "rounds" in only):

@@ -37,6 +37,7 @@ struct pc_cache {
     std::vector<HostMsg> msgs;
     std::vector<FreeSpan> free_spans;                // sorted by start, neighbours merged, none touches next_slot
     int64_t next_slot = 0;
+    bool slots_in_id_order = true;                   // no message was ever placed in a freed span: ids ascend with slots
     // device
     void *storage = nullptr; bool owns_storage = false;
     void *k_store = nullptr, *v_store = nullptr;
@@ -356,6 +357,7 @@ int32_t pc_append_message(pc_cache *c, const void *k, const void *v, int32_t len
                          c->k_store, c->v_store, c->table_dev, id, st);
         PC_HIP(c, hipGetLastError());
     }
+    if (!c->msgs.empty() && start < c->msgs.back().slot_start) c->slots_in_id_order = false;
     c->msgs.push_back({start, len, res, 0, true});
     c->free_spans.swap(spans);
     c->next_slot = next;
@@ -422,7 +424,11 @@ int32_t pc_append_messages(pc_cache *c, int32_t n, const void *const *k, const v
                                c->inv_freq_dev, c->k_store, c->v_store, c->table_dev, st);
         PC_HIP(c, hipGetLastError());
     }
-    for (int j = 0; j < n; ++j) { msg_ids[j] = (int32_t)c->msgs.size(); c->msgs.push_back(fresh[(size_t)j]); }
+    for (int j = 0; j < n; ++j) {
+        msg_ids[j] = (int32_t)c->msgs.size();
+        if (!c->msgs.empty() && fresh[(size_t)j].slot_start < c->msgs.back().slot_start) c->slots_in_id_order = false;
+        c->msgs.push_back(fresh[(size_t)j]);
+    }
     c->free_spans.swap(spans);
     c->next_slot = next;
     return PC_OK;
@@ -652,6 +658,26 @@ struct Planned {
 static void sort_by_slot(const pc_cache *c, Resolved &r)
 {
     if (r.sel.size() < 2) return;
+    // While ids ascend with slots (no freed span was ever refilled) and the list is long, one pass over
+    // a table indexed by message id does it; a message listed twice sends the call to the general sort.
+    if (c->slots_in_id_order && r.sel.size() * 8 > c->msgs.size()) {
+        static thread_local std::vector<int32_t> where;
+        static thread_local std::vector<int2> sorted;
+        where.assign(c->msgs.size(), -1);
+        bool twice = false;
+        for (size_t e = 0; e < r.sel.size() && !twice; ++e) {
+            int32_t &w = where[(size_t)r.sel[e].x];
+            twice = w >= 0;
+            w = (int32_t)e;
+        }
+        if (!twice) {
+            sorted.clear();
+            for (size_t m = 0; m < where.size(); ++m)
+                if (where[m] >= 0) sorted.push_back(r.sel[(size_t)where[m]]);
+            r.sel.assign(sorted.begin(), sorted.end());
+            return;
+        }
+    }
     struct SortKey { uint64_t key; int2 v; };
     static thread_local std::vector<SortKey> keys;
     keys.resize(r.sel.size());
