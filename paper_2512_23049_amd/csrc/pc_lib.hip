@@ -752,7 +752,9 @@ static void plan_shared(const pc_cache *c, std::vector<Resolved> &res, const std
         }
         int64_t union_tiles = 0;
         for (const USeg &u : usegs) union_tiles += (u.len + PC_TILE - 1) / PC_TILE;
+        // (the rotation table has one 512-byte row per (message, row) pair: keep it under 256 MB)
         const bool take = union_tiles > 0 && union_tiles < INT32_MAX / 2 &&
+                          (int64_t)usegs.size() * (j - i) <= ((int64_t)1 << 19) &&
                           (c->decode_sharing == 2 || (j - i >= 2 && (double)call_tiles >= SHARE_MIN * (double)union_tiles));
         if (take) {
             // union in cache-slot order
