@@ -206,6 +206,24 @@ int32_t pc_resolve_call(pc_cache *c, const pc_call *call, int32_t *starts_out,
  * adjacent freed spans merge; a span freed at the end shrinks the used region. */
 int32_t pc_message_free(pc_cache *c, int32_t msg_id);
 
+/* Swap (Sec. 2.2 "Simplifying Assumptions", the note on caches that do not fit GPU memory, and
+ * the note to Sec. 2.4's append-only cache: messages may be moved out to CPU memory for a while).
+ * pc_message_swap_out copies the stored K and V of a live message (its whole reserved span, as
+ * stored: keys turned to their stored base) into `blob`, then gives the slots back exactly as
+ * pc_message_free does.  `blob`: caller-owned, pc_message_swap_bytes(msg) bytes, pinned host or
+ * device memory (any memory hipMemcpyDefault can write); the copy is enqueued on `stream`, so
+ * appends that reuse the slots must go to the same stream or wait for it, and the blob is complete
+ * once the stream has passed this point.  Until it is swapped in again the id is unknown to every
+ * other function (PC_ERR_BAD_MSG_ID), but it is kept: pc_message_swap_in(msg, blob) takes slots by
+ * the allocation rule above (PC_ERR_NO_SPACE if there is no room; nothing changed then), copies the
+ * blob back on `stream` and the message is what it was: same id, length, reserve and stored base,
+ * bit-identical K and V, possibly at other slots.  The blob's layout is private to the library
+ * and tied to the cache's configuration.  pc_message_swap_bytes returns the blob size for a live
+ * or swapped-out message, or a negative error code. */
+int64_t pc_message_swap_bytes(pc_cache *c, int32_t msg_id);
+int32_t pc_message_swap_out(pc_cache *c, int32_t msg_id, void *blob, void *stream);
+int32_t pc_message_swap_in(pc_cache *c, int32_t msg_id, const void *blob, void *stream);
+
 /* Message and cache bookkeeping (Sec. 2.4: count of cached tokens, id -> span). */
 int32_t pc_message_info(pc_cache *c, int32_t msg_id, int32_t *len, int64_t *slot_start,
                         int32_t *reserved);

@@ -93,6 +93,12 @@ def lib():
         L.pc_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i64), i32]
         L.pc_set_tuning.restype = i32
         L.pc_set_tuning.argtypes = [vp, i32, i32]
+        L.pc_message_swap_bytes.restype = i64
+        L.pc_message_swap_bytes.argtypes = [vp, i32]
+        L.pc_message_swap_out.restype = i32
+        L.pc_message_swap_out.argtypes = [vp, i32, vp, vp]
+        L.pc_message_swap_in.restype = i32
+        L.pc_message_swap_in.argtypes = [vp, i32, vp, vp]
         L.pc_set_decode_sharing.restype = i32
         L.pc_set_decode_sharing.argtypes = [vp, i32]
         _lib = L
@@ -239,6 +245,18 @@ class Cache:
 
     def set_tuning(self, decode_tiles_per_split: int = 0, prefill_tiles_per_split: int = 0):
         self._check(lib().pc_set_tuning(self.h, decode_tiles_per_split, prefill_tiles_per_split))
+
+    def message_swap_bytes(self, msg: int) -> int:
+        n = lib().pc_message_swap_bytes(self.h, msg)
+        if n < 0:
+            self._check(int(n))
+        return int(n)
+
+    def message_swap_out(self, msg: int, blob_ptr: int, stream: int = 0):
+        self._check(lib().pc_message_swap_out(self.h, msg, blob_ptr or None, stream or None))
+
+    def message_swap_in(self, msg: int, blob_ptr: int, stream: int = 0):
+        self._check(lib().pc_message_swap_in(self.h, msg, blob_ptr or None, stream or None))
 
     def set_decode_sharing(self, mode: int = 0):
         """0: shared walk when a group's calls overlap enough; 1: never; 2: whenever the shape allows."""

@@ -13,7 +13,7 @@
 
 namespace {
 
-struct HostMsg { int64_t slot_start; int32_t len; int32_t reserve; int32_t base_pos; bool live; };
+struct HostMsg { int64_t slot_start; int32_t len; int32_t reserve; int32_t base_pos; bool live; bool swapped = false; };
 struct FreeSpan { int64_t start, size; };            // freed slots, multiples of PC_SLOT_ALIGN
 
 struct StageSlot { void *host = nullptr; size_t cap = 0; hipEvent_t ev = nullptr; bool used = false; };
@@ -571,13 +571,9 @@ int32_t pc_reposition_batch(pc_cache *c, const int32_t *msg_ids, const int32_t *
     return PC_OK;
 }
 
-int32_t pc_message_free(pc_cache *c, int32_t msg_id)
+// gives a span of slots back: sorted insert, merge with its neighbours, shrink the used region
+static void release_span(pc_cache *c, FreeSpan f)
 {
-    if (!c) return PC_ERR_INVALID_ARG;
-    if (!known(c, msg_id)) return fail(c, PC_ERR_BAD_MSG_ID, "free: unknown message %d", msg_id);
-    HostMsg &m = c->msgs[(size_t)msg_id];
-    m.live = false;
-    FreeSpan f{m.slot_start, (int64_t)align_up((size_t)m.reserve, PC_SLOT_ALIGN)};
     auto &fs = c->free_spans;
     size_t i = 0;
     while (i < fs.size() && fs[i].start < f.start) ++i;
@@ -594,6 +590,93 @@ int32_t pc_message_free(pc_cache *c, int32_t msg_id)
         c->next_slot = fs.back().start;
         fs.pop_back();
     }
+}
+
+int32_t pc_message_free(pc_cache *c, int32_t msg_id)
+{
+    if (!c) return PC_ERR_INVALID_ARG;
+    if (!known(c, msg_id)) return fail(c, PC_ERR_BAD_MSG_ID, "free: unknown message %d", msg_id);
+    HostMsg &m = c->msgs[(size_t)msg_id];
+    m.live = false;
+    release_span(c, FreeSpan{m.slot_start, (int64_t)align_up((size_t)m.reserve, PC_SLOT_ALIGN)});
+    return PC_OK;
+}
+
+// ---- swap: a message's stored K and V leave the cache as one blob and come back later -----------
+static inline bool swapped_out(const pc_cache *c, int32_t m) { return m >= 0 && m < (int32_t)c->msgs.size() && c->msgs[(size_t)m].swapped; }
+
+int64_t pc_message_swap_bytes(pc_cache *c, int32_t msg_id)
+{
+    if (!c) return PC_ERR_INVALID_ARG;
+    if (!known(c, msg_id) && !swapped_out(c, msg_id)) return fail(c, PC_ERR_BAD_MSG_ID, "swap_bytes: unknown message %d", msg_id);
+    const int64_t span = (int64_t)align_up((size_t)c->msgs[(size_t)msg_id].reserve, PC_SLOT_ALIGN);
+    return 2 * span * c->cfg.n_kv_heads * c->D * (int64_t)c->esize;
+}
+
+// the span [slot_start, slot_start + span) of every KV head, K heads first then V heads; both stores keep a
+// head's slots contiguous (V in groups of 8 slots, and spans are multiples of 32), so each is one strided copy
+static int32_t copy_span(pc_cache *c, int64_t slot_start, int64_t span, void *blob, bool out, hipStream_t st)
+{
+    const size_t row = (size_t)span * (size_t)c->D * c->esize;                 // one head's share of the span
+    const size_t pitch = (size_t)c->slots * (size_t)c->D * c->esize;           // one head's share of the store
+    const size_t at = (size_t)slot_start * (size_t)c->D * c->esize;
+    char *bk = (char *)blob, *bv = bk + row * (size_t)c->cfg.n_kv_heads;
+    char *sk = (char *)c->k_store + at, *sv = (char *)c->v_store + at;
+    if (out) {
+        PC_HIP(c, hipMemcpy2DAsync(bk, row, sk, pitch, row, (size_t)c->cfg.n_kv_heads, hipMemcpyDefault, st));
+        PC_HIP(c, hipMemcpy2DAsync(bv, row, sv, pitch, row, (size_t)c->cfg.n_kv_heads, hipMemcpyDefault, st));
+    } else {
+        PC_HIP(c, hipMemcpy2DAsync(sk, pitch, bk, row, row, (size_t)c->cfg.n_kv_heads, hipMemcpyDefault, st));
+        PC_HIP(c, hipMemcpy2DAsync(sv, pitch, bv, row, row, (size_t)c->cfg.n_kv_heads, hipMemcpyDefault, st));
+    }
+    return PC_OK;
+}
+
+int32_t pc_message_swap_out(pc_cache *c, int32_t msg_id, void *blob, void *stream)
+{
+    if (!c) return PC_ERR_INVALID_ARG;
+    if (!known(c, msg_id)) return fail(c, PC_ERR_BAD_MSG_ID, "swap_out: unknown message %d", msg_id);
+    if (!c->host_only && !blob) return fail(c, PC_ERR_INVALID_ARG, "swap_out: null blob");
+    HostMsg &m = c->msgs[(size_t)msg_id];
+    const int64_t span = (int64_t)align_up((size_t)m.reserve, PC_SLOT_ALIGN);
+    if (!c->host_only) {
+        const int32_t rc = copy_span(c, m.slot_start, span, blob, true, (hipStream_t)stream);
+        if (rc != PC_OK) return rc;
+    }
+    m.live = false; m.swapped = true;
+    release_span(c, FreeSpan{m.slot_start, span});
+    return PC_OK;
+}
+
+int32_t pc_message_swap_in(pc_cache *c, int32_t msg_id, const void *blob, void *stream)
+{
+    if (!c) return PC_ERR_INVALID_ARG;
+    if (!swapped_out(c, msg_id)) return fail(c, PC_ERR_BAD_MSG_ID, "swap_in: message %d is not swapped out", msg_id);
+    if (!c->host_only && !blob) return fail(c, PC_ERR_INVALID_ARG, "swap_in: null blob");
+    HostMsg &m = c->msgs[(size_t)msg_id];
+    std::vector<FreeSpan> spans = c->free_spans;
+    int64_t next = c->next_slot, start = 0;
+    if (!take_slots(spans, next, c->slots, m.reserve, start))
+        return fail(c, PC_ERR_NO_SPACE, "swap_in: message %d (%d slots) does not fit, capacity %lld", msg_id, m.reserve, (long long)c->slots);
+    if (!c->host_only) {
+        hipStream_t st = (hipStream_t)stream;
+        const int64_t span = (int64_t)align_up((size_t)m.reserve, PC_SLOT_ALIGN);
+        int32_t rc = copy_span(c, start, span, const_cast<void *>(blob), false, st);
+        if (rc != PC_OK) return rc;
+        // the device table learns where the message lives now
+        StageSlot *slot = nullptr;
+        rc = stage_acquire(c, sizeof(PcMsgEntry), &slot);
+        if (rc != PC_OK) return rc;
+        const PcMsgEntry en{(int32_t)start, m.len, m.base_pos, 0};
+        std::memcpy(slot->host, &en, sizeof en);
+        PC_HIP(c, hipMemcpyAsync(c->table_dev + msg_id, slot->host, sizeof en, hipMemcpyHostToDevice, st));
+        PC_HIP(c, hipEventRecord(slot->ev, st));
+        slot->used = true;
+    }
+    m.slot_start = start; m.live = true; m.swapped = false;
+    c->slots_in_id_order = false;                       // an old id may now sit behind newer ones
+    c->free_spans.swap(spans);
+    c->next_slot = next;
     return PC_OK;
 }
 

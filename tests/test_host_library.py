@@ -244,3 +244,54 @@ def test_batched_append_is_all_or_nothing_and_follows_the_slot_model(pc):
         c.append_messages([0] * 6, [0] * 6, [1] * 6)
     assert ei.value.code == pc.PC_ERR_NO_SPACE
     assert c.append_messages([], [], []) == []
+
+
+def test_swap_bookkeeping_on_a_host_only_cache(pc):
+    # swap-out frees the span exactly as a free does, swap-in takes slots by the allocation rule and the
+    # message is what it was (id, length, reserve, stored base); in between the id is unknown elsewhere
+    c = host_cache(pc, capacity_tokens=1024, max_messages=64)
+    model = orc.SlotModel(pc.PC_SLOT_ALIGN)
+    ids = []
+    for L, r in ((40, 0), (10, 70), (33, 0), (5, 0)):
+        m = c.append_message(0, 0, L, r)
+        assert c.message_info(m)[1] == model.append(m, max(L, r))
+        ids.append(m)
+    a, b, cc, d = ids
+    c.reposition(b, 123)
+    per_slot = 2 * 2 * 64 * 4                                  # K and V, 2 KV heads, D 64, fp32 (host_cache's shape)
+    assert c.message_swap_bytes(b) == 96 * per_slot            # reserve 70 -> 96 slots
+    c.message_swap_out(b, 0)
+    model.release(b)
+    assert c.message_swap_bytes(b) == 96 * per_slot
+    for fn in (lambda: c.message_info(b), lambda: c.message_swap_out(b, 0), lambda: c.message_free(b),
+               lambda: c.reposition(b, 0), lambda: c.append_tokens(b, 0, 0, 1),
+               lambda: c.resolve_call(Call([(b, 0)], -1, 0, 1, None))):
+        with pytest.raises(pc.PcError) as ei:
+            fn()
+        assert ei.value.code == pc.PC_ERR_BAD_MSG_ID
+    with pytest.raises(pc.PcError) as ei:
+        c.message_swap_in(a, 0)                                # a live message cannot be swapped in
+    assert ei.value.code == pc.PC_ERR_BAD_MSG_ID
+    e = c.append_message(0, 0, 20)                             # takes the head of b's old span
+    assert c.message_info(e)[1] == model.append(e, 20)
+    c.message_swap_in(b, 0)                                    # 96 slots: what is left of the hole is too small
+    assert c.message_info(b)[1] == model.append(b, 70)
+    assert c.message_info(b)[0] == 10 and c.message_base(b) == 123
+    assert c.cache_info()[1] == model.end
+    c.append_tokens(b, 0, 0, 60)                               # the reserve came back with it
+    assert c.message_info(b)[0] == 70
+    # no room: nothing changes and the message stays swapped out
+    c.message_swap_out(cc, 0)
+    model.release(cc)
+    big = c.append_message(0, 0, 1024 - model.end)             # fills the cache to the end
+    model.append(big, 1024 - (model.end))
+    f2 = c.append_message(0, 0, 70)                            # and of the hole (cc's span merged with b's leftover: 128) 32 stay
+    assert c.message_info(f2)[1] == model.append(f2, 70)
+    with pytest.raises(pc.PcError) as ei:
+        c.message_swap_in(cc, 0)
+    assert ei.value.code == pc.PC_ERR_NO_SPACE
+    assert c.message_swap_bytes(cc) == 64 * per_slot
+    c.message_free(f2)
+    model.release(f2)
+    c.message_swap_in(cc, 0)
+    assert c.message_info(cc)[1] == model.append(cc, 33)
