@@ -27,7 +27,8 @@ are listed in the repository's design notes; each is marked "reading" below.
 Every function here is pinned by tests that do not call it to produce their
 own expectation: brute force with complex arithmetic, reduction to a library
 causal attention, shift / permutation invariance, closed forms, hand-written
-tables.  Agreement with the authors' implementation on real model activations
+tables; the gradient (attend_call_backward) by central differences of the forward
+oracle and by closed forms.  Agreement with the authors' implementation on real model activations
 is "parity unpinned": that code and its weights are not available.
 """
 from __future__ import annotations
@@ -307,3 +308,74 @@ def merge_partials(outs: Sequence[np.ndarray], lses: Sequence[np.ndarray]):
         l = safe + np.log(den)
     ok = den > 0
     return np.where(ok[..., None], o, 0.0), np.where(ok, l, -np.inf)
+
+
+# ---------------------------------------------------------------------------
+# gradient of one call (Sec. 2.4: during fine-tuning a position update is applied
+# non-destructively so that gradients flow through it to the cached keys; the
+# gradient with respect to the UNROTATED keys, the values and the queries is what a
+# training graph needs).  The chain rule of attend_call written out step by step on
+# the same dense matrices: for the scalar  sum(out * d_out),
+#   dV_c = P^T dO,  dP = dO V_c^T,  dS = P * (dP - rowsum(dO * O)),
+#   dQr = scale dS Kr,  dKr = scale dS^T Qr,
+# a rotation's transpose is the rotation by the opposite angle, and a token gathered
+# several times (by several list entries, or by parent and new message both) collects
+# the sum of its copies' gradients.
+# ---------------------------------------------------------------------------
+def attend_call_backward(msgs_k: Sequence[np.ndarray], msgs_v: Sequence[np.ndarray],
+                         sel: Sequence[Tuple[int, int]], self_msg: int, self_start: int,
+                         n_q: int, q_pos: Optional[np.ndarray], q: np.ndarray, d_out: np.ndarray,
+                         theta: float, scale: Optional[float] = None):
+    """Returns (d_q [n_q, H_q, D], d_k, d_v) with d_k[m], d_v[m]: [L_m, H_kv, D] for every
+    message (zeros where the call does not read it), all fp64."""
+    lengths = [int(k.shape[0]) for k in msgs_k]
+    sel_r, s_self = resolve_positions(sel, lengths, self_start)
+    self_len = lengths[self_msg] if self_msg >= 0 else 0
+    starts = slot_starts(lengths, 1)
+    kv_slot, kv_pos, n_parent = assemble(sel_r, self_msg, s_self, lengths, starts)
+    H_kv, D = msgs_k[0].shape[1], msgs_k[0].shape[2]
+    H_q = q.shape[1]
+    g = H_q // H_kv
+    if scale is None:
+        scale = 1.0 / np.sqrt(D)
+    d_k = [np.zeros((L, H_kv, D)) for L in lengths]
+    d_v = [np.zeros((L, H_kv, D)) for L in lengths]
+    d_q = np.zeros((n_q, H_q, D))
+    N = kv_slot.shape[0]
+    if N == 0:
+        return d_q, d_k, d_v
+    entries = list(sel_r) + ([(self_msg, s_self)] if self_msg >= 0 else [])
+    Kc = np.concatenate([np.asarray(msgs_k[m], dtype=np.float64) for m, _ in entries], axis=0)
+    Vc = np.concatenate([np.asarray(msgs_v[m], dtype=np.float64) for m, _ in entries], axis=0)
+    Kr = rope(Kc, kv_pos, theta)
+    p_rows = query_positions(n_q, self_len if self_msg >= 0 else n_q, s_self, q_pos)
+    Qr = rope(np.asarray(q, dtype=np.float64), p_rows, theta)
+    vis = visibility(n_q, n_parent, self_len)
+    dO = np.asarray(d_out, dtype=np.float64)
+    dQr = np.zeros_like(Qr)
+    dKr = np.zeros_like(Kr)
+    dVc = np.zeros_like(Vc)
+    for h in range(H_q):
+        kh = h // g
+        S = np.where(vis, scale * (Qr[:, h, :] @ Kr[:, kh, :].T), -np.inf)
+        mx = S.max(axis=1, keepdims=True)
+        ok = np.isfinite(mx[:, 0])
+        P = np.exp(S - np.where(np.isfinite(mx), mx, 0.0))
+        den = P.sum(axis=1, keepdims=True)
+        with np.errstate(divide="ignore", invalid="ignore"):
+            P = np.where(ok[:, None], P / den, 0.0)          # a row that sees nothing contributes nothing
+        O = P @ Vc[:, kh, :]
+        dVc[:, kh, :] += P.T @ dO[:, h, :]
+        dP = dO[:, h, :] @ Vc[:, kh, :].T
+        dS = P * (dP - (dO[:, h, :] * O).sum(axis=1, keepdims=True))
+        dQr[:, h, :] = scale * (dS @ Kr[:, kh, :])
+        dKr[:, kh, :] += scale * (dS.T @ Qr[:, h, :])
+    d_q = rope(dQr, -np.asarray(p_rows), theta)
+    dKc = rope(dKr, -np.asarray(kv_pos), theta)
+    at = 0
+    for m, _ in entries:
+        L = lengths[m]
+        d_k[m] += dKc[at:at + L]
+        d_v[m] += dVc[at:at + L]
+        at += L
+    return d_q, d_k, d_v

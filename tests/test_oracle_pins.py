@@ -415,3 +415,77 @@ def test_batched_attend_packs_calls_in_order():
         assert np.allclose(l[at:at + c.n_q], np.asarray(lb).reshape(c.n_q, 4), atol=1e-11)
         at += c.n_q
     assert at == o.shape[0]
+
+
+# ---------------------------------------------------------------------------
+# gradient oracle: pinned by numerical differentiation of the FORWARD oracle (which has its
+# own pins above) and by closed forms; nothing here calls attend_call_backward to make its
+# own expectation
+# ---------------------------------------------------------------------------
+def _grad_case(seed=5):
+    rng = np.random.default_rng(seed)
+    H_q, H_kv, D = 4, 2, 16
+    lens = [5, 3, 7, 4]
+    ks = [rng.standard_normal((L, H_kv, D)) for L in lens]
+    vs = [rng.standard_normal((L, H_kv, D)) for L in lens]
+    sel = [(2, 11), (0, -3), (2, 40)]                      # message 2 twice, a negative start
+    self_msg, self_start, n_q = 3, 20, 3                   # rows = the last 3 of 4 own tokens (causal part)
+    q = rng.standard_normal((n_q, H_q, D))
+    d_out = rng.standard_normal((n_q, H_q, D))
+    return ks, vs, sel, self_msg, self_start, n_q, q, d_out
+
+
+def test_gradient_oracle_matches_central_differences_of_the_forward_oracle():
+    ks, vs, sel, self_msg, self_start, n_q, q, d_out = _grad_case()
+    theta = 10000.0
+
+    def loss(ks_, vs_, q_):
+        o, _ = orc.attend_call(ks_, vs_, sel, self_msg, self_start, n_q, None, q_, theta)
+        return float((o * d_out).sum())
+    d_q, d_k, d_v = orc.attend_call_backward(ks, vs, sel, self_msg, self_start, n_q, None, q, d_out, theta)
+    rng = np.random.default_rng(1)
+    eps = 1e-6
+
+    def check(arr_list, which, grads, n=12):
+        for _ in range(n):
+            m = int(rng.integers(0, len(arr_list)))
+            idx = tuple(int(rng.integers(0, s)) for s in arr_list[m].shape)
+            keep = arr_list[m][idx]
+            arr_list[m][idx] = keep + eps
+            up = loss(ks, vs, q)
+            arr_list[m][idx] = keep - eps
+            dn = loss(ks, vs, q)
+            arr_list[m][idx] = keep
+            num = (up - dn) / (2 * eps)
+            assert abs(num - grads[m][idx]) <= 1e-7 + 1e-6 * abs(num), (which, m, idx, num, grads[m][idx])
+    check(ks, "K", d_k)
+    check(vs, "V", d_v)
+    check([q], "q", [d_q])
+    assert np.abs(d_k[1]).max() == 0 and np.abs(d_v[1]).max() == 0          # message 1 is not read
+
+
+def test_gradient_oracle_closed_forms():
+    rng = np.random.default_rng(9)
+    H_q, H_kv, D = 2, 1, 8
+    # one visible key: the output IS its value row, whatever q and k are
+    ks, vs = [rng.standard_normal((1, H_kv, D))], [rng.standard_normal((1, H_kv, D))]
+    q, d_out = rng.standard_normal((2, H_q, D)), rng.standard_normal((2, H_q, D))
+    d_q, d_k, d_v = orc.attend_call_backward(ks, vs, [(0, 7)], -1, 0, 2, np.asarray([3, 9]), q, d_out, 1e4)
+    assert np.abs(d_q).max() < 1e-12 and np.abs(d_k[0]).max() < 1e-12
+    assert np.allclose(d_v[0][0, 0], d_out.sum(axis=(0, 1)), atol=1e-12)
+    # all positions zero and q = 0: uniform weights 1/N, so dV rows are dO/N and dK = scale * dS^T q = 0;
+    # dq = scale * sum_j dS_j k_j with dS_j = (dO.v_j - mean_j dO.v_j) / N
+    N = 5
+    ks, vs = [rng.standard_normal((N, H_kv, D))], [rng.standard_normal((N, H_kv, D))]
+    q0 = np.zeros((1, H_q, D))
+    d_out = rng.standard_normal((1, H_q, D))
+    d_q, d_k, d_v = orc.attend_call_backward(ks, vs, [(0, 0)], -1, 0, 1, np.asarray([0]), q0, d_out, 1e4)
+    assert np.allclose(d_v[0][:, 0], np.tile(d_out[0].sum(axis=0) / N, (N, 1)), atol=1e-12)
+    assert np.abs(d_k[0]).max() < 1e-12
+    for h in range(H_q):
+        dp = vs[0][:, 0] @ d_out[0, h]
+        ds = (dp - dp.mean()) / N
+        # position 0 for every key would need starts that put all N tokens at 0: they sit at 0..N-1 instead,
+        # so compare through the rotation: dq (at position 0) = scale * sum_j ds_j R(j) k_j
+        want = sum(ds[j] * orc.rope(ks[0][j:j + 1, 0], np.asarray([j]), 1e4)[0] for j in range(N)) / np.sqrt(D)
+        assert np.allclose(d_q[0, h], want, atol=1e-12)
