@@ -99,6 +99,10 @@ def lib():
         L.pc_message_swap_out.argtypes = [vp, i32, vp, vp]
         L.pc_message_swap_in.restype = i32
         L.pc_message_swap_in.argtypes = [vp, i32, vp, vp]
+        L.pc_attend_backward.restype = i32
+        L.pc_attend_backward.argtypes = [vp, C.POINTER(pc_call), i32, vp, vp, vp, vp, vp, vp, vp]
+        L.pc_grad_keys_finalize.restype = i32
+        L.pc_grad_keys_finalize.argtypes = [vp, vp, vp]
         L.pc_set_decode_sharing.restype = i32
         L.pc_set_decode_sharing.argtypes = [vp, i32]
         _lib = L
@@ -257,6 +261,15 @@ class Cache:
 
     def message_swap_in(self, msg: int, blob_ptr: int, stream: int = 0):
         self._check(lib().pc_message_swap_in(self.h, msg, blob_ptr or None, stream or None))
+
+    def attend_backward(self, calls, q_ptr: int, lse_ptr: int, d_out_ptr: int, d_q_ptr: int, d_k_ptr: int, d_v_ptr: int,
+                        stream: int = 0):
+        arr, keep = marshal_calls(calls)
+        self._check(lib().pc_attend_backward(self.h, arr, len(calls), q_ptr or None, lse_ptr or None, d_out_ptr or None,
+                                             d_q_ptr or None, d_k_ptr or None, d_v_ptr or None, stream or None))
+
+    def grad_keys_finalize(self, d_k_ptr: int, stream: int = 0):
+        self._check(lib().pc_grad_keys_finalize(self.h, d_k_ptr or None, stream or None))
 
     def set_decode_sharing(self, mode: int = 0):
         """0: shared walk when a group's calls overlap enough; 1: never; 2: whenever the shape allows."""

@@ -40,6 +40,12 @@ void pc_launch_merge(int dtype, const PcMergeRow *merge_rows, int n_merge_rows, 
 
 void pc_launch_attend_f32(const PcLaunch &L, const int32_t *row_call, int total_q, int D, hipStream_t st);
 
+// gradient of the fp32 attention; d_k collects the gradient w.r.t. the stored keys until the finalize pass
+void pc_launch_attend_bwd_f32(const PcLaunch &L, const int32_t *row_call, int total_q, int D, const float *lse,
+                              const float *d_out, float scale, float *d_q, float *d_k, float *d_v, hipStream_t st);
+void pc_launch_grad_keys_finalize(const PcMsgEntry *msgs, int n_msgs, int n_kv_heads, int D, const double *inv_freq,
+                                  float *d_k, hipStream_t st);
+
 // bf16 MFMA kernels (D = 128)
 void pc_launch_decode_bf16(const PcLaunch &L, int n_items, hipStream_t st);
 void pc_launch_prefill_bf16(const PcLaunch &L, int n_items, hipStream_t st);

@@ -719,3 +719,174 @@ void pc_launch_attend_f32(const PcLaunch &L, const int32_t *row_call, int total_
     if (D == 64) pc_attend_f32_kernel<64><<<grid, 64, 0, st>>>(L, row_call);
     else pc_attend_f32_kernel<128><<<grid, 64, 0, st>>>(L, row_call);
 }
+
+// ----------------------------------------------------------------------------------
+// Gradient of the fp32 attention (Sec. 2.4: in fine-tuning a position update is applied
+// non-destructively, so gradients flow through it to the cached keys).  One wave per
+// (query row, head), keys lane-strided as in the forward kernel.  With p_j = exp(s_j - LSE)
+// from the forward's LSE and dp_j = dO . v_j:
+//   Delta = sum_j p_j dp_j,   ds_j = p_j (dp_j - Delta),
+//   dV_j += p_j dO,   dK~_j += scale ds_j qe,   dqe += scale ds_j K~_j
+// where K~ is the stored key (turned to base + t) and qe the query turned for the segment;
+// dqe is turned back per segment and once more by the row's own position at the end.
+// d_k collects the gradient with respect to the STORED keys (pc_grad_keys_finalize turns
+// it into the gradient with respect to the keys as they were appended); contributions of
+// different rows and heads meet in d_k, d_v through float atomics.
+// A plain kernel: this path is not a hot one.
+// ----------------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(64) void pc_attend_bwd_f32_kernel(PcLaunch L, const int32_t *__restrict__ row_call,
+                                                               const float *__restrict__ lse, const float *__restrict__ d_out,
+                                                               float scale, float *__restrict__ d_q,
+                                                               float *__restrict__ d_k, float *__restrict__ d_v)
+{
+    constexpr int HALF = D / 2;
+    __shared__ float s_qhat[D], s_qe[D], s_do[D], s_dqhat[D];
+    __shared__ float s_red[64 * (D + 1)];
+    const int R = blockIdx.x, h = blockIdx.y, lane = threadIdx.x;
+    const PcCallDesc cd = L.calls[row_call[R]];
+    const int r = R - cd.q_off;
+    const int g = L.n_q_heads / L.n_kv_heads;
+    const int kh = h / g;
+    const int64_t rh = (int64_t)R * L.n_q_heads + h;
+    const float *q = (const float *)L.q + rh * D;
+    for (int i = lane; i < HALF; i += 64) {
+        const float2 cs = L.rot_q[(int64_t)R * HALF + i];
+        const float a = q[i], b = q[i + HALF];
+        s_qhat[i] = a * cs.x - b * cs.y;
+        s_qhat[i + HALF] = a * cs.y + b * cs.x;
+    }
+    for (int d = lane; d < D; d += 64) { s_do[d] = d_out[rh * D + d]; s_dqhat[d] = 0.f; }
+    const float row_lse = lse[rh];
+    float *dq = d_q + rh * D;
+    if (!(row_lse > -INFINITY)) {                          // the row saw nothing: no gradient anywhere
+        for (int d = lane; d < D; d += 64) dq[d] = 0.f;
+        return;
+    }
+    __syncthreads();
+    const float *kbase = (const float *)L.k_store + (int64_t)kh * L.slots * D;
+    const float *vbase = (const float *)L.v_store + (int64_t)kh * L.slots * D;
+    auto visible = [&](const PcSegment &sg, int e) {
+        int n_vis = sg.len;
+        if (cd.self_msg >= 0 && e == cd.n_seg - 1) {
+            const int lim = cd.self_len - cd.n_q + r + 1;
+            n_vis = lim < n_vis ? lim : n_vis;
+        }
+        return n_vis;
+    };
+    auto turn = [&](int e) {                               // s_qe = query turned by -(start - base) of segment e
+        __syncthreads();
+        for (int i = lane; i < HALF; i += 64) {
+            const float2 cs = L.rot_seg[(int64_t)(cd.seg_off + e) * HALF + i];
+            const float a = s_qhat[i], b = s_qhat[i + HALF];
+            s_qe[i] = a * cs.x + b * cs.y;
+            s_qe[i + HALF] = -a * cs.y + b * cs.x;
+        }
+        __syncthreads();
+    };
+    // pass 1: Delta
+    float delta = 0.f;
+    for (int e = 0; e < cd.n_seg; ++e) {
+        const PcSegment sg = L.segs[cd.seg_off + e];
+        const int n_vis = visible(sg, e);
+        if (n_vis <= 0) continue;
+        turn(e);
+        for (int t = lane; t < n_vis; t += 64) {
+            const float *kr = kbase + (int64_t)(sg.slot_start + t) * D;
+            const float *vr = vbase + (int64_t)(sg.slot_start + t) * D;
+            float s = 0.f, dp = 0.f;
+#pragma unroll 8
+            for (int d = 0; d < D; ++d) { s = fmaf(s_qe[d], kr[d], s); dp = fmaf(s_do[d], vr[d], dp); }
+            delta += expf(s * scale - row_lse) * dp;
+        }
+    }
+    for (int off = 32; off > 0; off >>= 1) delta += __shfl_xor(delta, off);
+    // pass 2: the gradients
+    for (int e = 0; e < cd.n_seg; ++e) {
+        const PcSegment sg = L.segs[cd.seg_off + e];
+        const int n_vis = visible(sg, e);
+        if (n_vis <= 0) continue;
+        turn(e);
+        float dqe[D];
+#pragma unroll
+        for (int d = 0; d < D; ++d) dqe[d] = 0.f;
+        for (int t = lane; t < n_vis; t += 64) {
+            const int64_t slot = sg.slot_start + t;
+            const float *kr = kbase + slot * D;
+            const float *vr = vbase + slot * D;
+            float s = 0.f, dp = 0.f;
+#pragma unroll 8
+            for (int d = 0; d < D; ++d) { s = fmaf(s_qe[d], kr[d], s); dp = fmaf(s_do[d], vr[d], dp); }
+            const float p = expf(s * scale - row_lse);
+            const float ds = p * (dp - delta) * scale;
+            float *gk = d_k + (slot * L.n_kv_heads + kh) * D;
+            float *gv = d_v + (slot * L.n_kv_heads + kh) * D;
+#pragma unroll 8
+            for (int d = 0; d < D; ++d) {
+                dqe[d] = fmaf(ds, kr[d], dqe[d]);
+                atomicAdd(gk + d, ds * s_qe[d]);
+                atomicAdd(gv + d, p * s_do[d]);
+            }
+        }
+        // sum the lanes' dqe, turn it back by +(start - base), add to the gradient of the position-turned query
+        __syncthreads();
+#pragma unroll
+        for (int d = 0; d < D; ++d) s_red[lane * (D + 1) + d] = dqe[d];
+        __syncthreads();
+        for (int i = lane; i < HALF; i += 64) {
+            float a = 0.f, b = 0.f;
+            for (int j = 0; j < 64; ++j) { a += s_red[j * (D + 1) + i]; b += s_red[j * (D + 1) + i + HALF]; }
+            const float2 cs = L.rot_seg[(int64_t)(cd.seg_off + e) * HALF + i];
+            s_dqhat[i] += a * cs.x - b * cs.y;
+            s_dqhat[i + HALF] += a * cs.y + b * cs.x;
+        }
+    }
+    __syncthreads();
+    for (int i = lane; i < HALF; i += 64) {                // back through the row's own position
+        const float2 cs = L.rot_q[(int64_t)R * HALF + i];
+        const float a = s_dqhat[i], b = s_dqhat[i + HALF];
+        dq[i] = a * cs.x + b * cs.y;
+        dq[i + HALF] = -a * cs.y + b * cs.x;
+    }
+}
+
+void pc_launch_attend_bwd_f32(const PcLaunch &L, const int32_t *row_call, int total_q, int D, const float *lse,
+                              const float *d_out, float scale, float *d_q, float *d_k, float *d_v, hipStream_t st)
+{
+    if (total_q <= 0) return;
+    dim3 grid(total_q, L.n_q_heads);
+    if (D == 64) pc_attend_bwd_f32_kernel<64><<<grid, 64, 0, st>>>(L, row_call, lse, d_out, scale, d_q, d_k, d_v);
+    else pc_attend_bwd_f32_kernel<128><<<grid, 64, 0, st>>>(L, row_call, lse, d_out, scale, d_q, d_k, d_v);
+}
+
+// d_k holds the gradient with respect to the stored keys K~_t = R(base + t) k_t; the gradient with
+// respect to k_t is R(base + t)^T of it (Sec. 2.4 "Position Updates", transposed).  One thread per
+// (token, KV head, rotation pair) of every listed message (blockIdx.y).
+__global__ __launch_bounds__(256) void pc_grad_keys_finalize_kernel(const PcMsgEntry *__restrict__ msgs, int n_kv_heads, int D,
+                                                                    const double *__restrict__ inv_freq, float *__restrict__ d_k)
+{
+    const PcMsgEntry m = msgs[blockIdx.y];
+    const int half = D / 2;
+    const int64_t n = (int64_t)m.len * n_kv_heads * half;
+    for (int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x; idx < n; idx += (int64_t)gridDim.x * 256) {
+        const int i = (int)(idx % half);
+        const int kh = (int)((idx / half) % n_kv_heads);
+        const int t = (int)(idx / ((int64_t)half * n_kv_heads));
+        double sn, cs;
+        sincos((double)(m.base_pos + t) * inv_freq[i], &sn, &cs);
+        float *row = d_k + ((int64_t)(m.slot_start + t) * n_kv_heads + kh) * D;
+        const float a = row[i], b = row[i + half];
+        row[i] = a * (float)cs + b * (float)sn;
+        row[i + half] = -a * (float)sn + b * (float)cs;
+    }
+}
+
+void pc_launch_grad_keys_finalize(const PcMsgEntry *msgs, int n_msgs, int n_kv_heads, int D, const double *inv_freq,
+                                  float *d_k, hipStream_t st)
+{
+    for (int first = 0; first < n_msgs; first += 65535) {              // grid.y is limited to 65535
+        const int n = n_msgs - first < 65535 ? n_msgs - first : 65535;
+        dim3 grid(16, (unsigned)n);
+        pc_grad_keys_finalize_kernel<<<grid, 256, 0, st>>>(msgs + first, n_kv_heads, D, inv_freq, d_k);
+    }
+}

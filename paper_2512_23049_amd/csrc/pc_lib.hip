@@ -1104,6 +1104,54 @@ int32_t pc_attend(pc_cache *c, const pc_call *calls, int32_t n_calls, const void
     return PC_OK;
 }
 
+int32_t pc_attend_backward(pc_cache *c, const pc_call *calls, int32_t n_calls, const void *q, const float *lse,
+                           const void *d_out, void *d_q, float *d_k, float *d_v, void *stream)
+{
+    if (!c) return PC_ERR_INVALID_ARG;
+    if (c->cfg.dtype != PC_F32) return fail(c, PC_ERR_INVALID_ARG, "attend_backward: needs a PC_F32 cache");
+    if (n_calls < 0 || (n_calls > 0 && !calls)) return fail(c, PC_ERR_INVALID_ARG, "attend_backward: bad call list");
+    if (n_calls == 0) return PC_OK;
+    if (!c->host_only && (!q || !lse || !d_out || !d_q || !d_k || !d_v))
+        return fail(c, PC_ERR_INVALID_ARG, "attend_backward: null argument");
+    hipStream_t st = (hipStream_t)stream;
+    Planned P;
+    const int32_t rc = plan_and_stage(c, calls, n_calls, false, st, P);
+    if (rc != PC_OK || c->host_only) return rc;
+    char *w = (char *)c->ws;
+    PcLaunch L{};
+    L.calls = (const PcCallDesc *)(w + P.lay.calls);
+    L.segs = (const PcSegment *)(w + P.lay.segs);
+    L.rot_seg = (const float2 *)(w + P.lay.rot_seg);
+    L.rot_q = (const float2 *)(w + P.lay.rot_q);
+    L.k_store = c->k_store; L.v_store = c->v_store; L.q = q;
+    L.slots = c->slots; L.n_q_heads = c->cfg.n_q_heads; L.n_kv_heads = c->cfg.n_kv_heads;
+    L.scale_log2 = c->scale * 1.4426950408889634f;
+    ProfScope ps(c, 5, st);
+    pc_launch_attend_bwd_f32(L, (const int32_t *)(w + P.lay.row_call), P.total_q, c->D, lse, (const float *)d_out, c->scale,
+                             (float *)d_q, d_k, d_v, st);
+    PC_HIP(c, hipGetLastError());
+    return PC_OK;
+}
+
+int32_t pc_grad_keys_finalize(pc_cache *c, float *d_k, void *stream)
+{
+    if (!c) return PC_ERR_INVALID_ARG;
+    if (c->cfg.dtype != PC_F32) return fail(c, PC_ERR_INVALID_ARG, "grad_keys_finalize: needs a PC_F32 cache");
+    if (c->host_only) return PC_OK;
+    if (!d_k) return fail(c, PC_ERR_INVALID_ARG, "grad_keys_finalize: null d_k");
+    std::vector<PcMsgEntry> live;
+    for (const HostMsg &m : c->msgs)
+        if (m.live && m.len > 0) live.push_back(PcMsgEntry{(int32_t)m.slot_start, m.len, m.base_pos, 0});
+    if (live.empty()) return PC_OK;
+    hipStream_t st = (hipStream_t)stream;
+    const int32_t rc = stage_items(c, live.data(), sizeof(PcMsgEntry) * live.size(), st);
+    if (rc != PC_OK) return rc;
+    ProfScope ps(c, 5, st);
+    pc_launch_grad_keys_finalize((const PcMsgEntry *)c->tok_dev, (int)live.size(), c->cfg.n_kv_heads, c->D, c->inv_freq_dev, d_k, st);
+    PC_HIP(c, hipGetLastError());
+    return PC_OK;
+}
+
 int32_t pc_build_tables(pc_cache *c, const pc_call *call, int32_t *kv_slot, int32_t *kv_pos, int64_t cap,
                         int64_t *n_kv, void *stream)
 {

@@ -295,3 +295,20 @@ def test_swap_bookkeeping_on_a_host_only_cache(pc):
     model.release(f2)
     c.message_swap_in(cc, 0)
     assert c.message_info(cc)[1] == model.append(cc, 33)
+
+
+def test_gradient_entry_points_need_an_fp32_cache(pc):
+    c = host_cache(pc)                                         # bf16
+    a = c.append_message(0, 0, 5)
+    with pytest.raises(pc.PcError) as ei:
+        c.attend_backward([Call([(a, 0)], -1, 0, 1, None)], 0, 0, 0, 0, 0, 0)
+    assert ei.value.code == pc.PC_ERR_INVALID_ARG
+    with pytest.raises(pc.PcError) as ei:
+        c.grad_keys_finalize(0)
+    assert ei.value.code == pc.PC_ERR_INVALID_ARG
+    f = host_cache(pc, dtype=pc.PC_F32, head_dim=64)
+    a = f.append_message(0, 0, 5)
+    f.attend_backward([Call([(a, 0)], -1, 0, 1, None)], 0, 0, 0, 0, 0, 0)       # host-only: validation and planning
+    with pytest.raises(pc.PcError) as ei:
+        f.attend_backward([Call([(a + 1, 0)], -1, 0, 1, None)], 0, 0, 0, 0, 0, 0)
+    assert ei.value.code == pc.PC_ERR_BAD_MSG_ID
