@@ -62,6 +62,17 @@ extern "C" {
 /* pc_config.flags */
 #define PC_FLAG_HOST_ONLY 1u  /* no device memory, no launches: validation, allocation
                                  and position resolution only (k/v/q/out are ignored) */
+#define PC_FLAG_GROW_EXTENTS 2u /* a message whose reserve is used up grows into a further extent
+                                 (Sec. 2.4: the message table maps an id to where its tokens
+                                 live; here to one or more spans) instead of PC_ERR_NO_SPACE:
+                                 pc_append_tokens* then takes slots for it by the allocation
+                                 rule, room for the tokens the call still brings and at least
+                                 the message's first reserve.  Every extent uses one row of the
+                                 message table (max_messages bounds messages plus further
+                                 extents), so message ids stay ascending but need not be
+                                 consecutive.  To every call the message is one sequence of
+                                 tokens; the query rows of a call must lie in the last extent
+                                 of its new message (PC_ERR_SHAPE otherwise). */
 
 typedef struct pc_cache pc_cache;
 
@@ -227,6 +238,11 @@ int32_t pc_message_swap_in(pc_cache *c, int32_t msg_id, const void *blob, void *
 /* Message and cache bookkeeping (Sec. 2.4: count of cached tokens, id -> span). */
 int32_t pc_message_info(pc_cache *c, int32_t msg_id, int32_t *len, int64_t *slot_start,
                         int32_t *reserved);
+/* The extents of a message in token order: *n_extents (always written), and for the first
+ * min(cap, *n_extents) of them the first slot and the tokens held.  pc_message_info reports
+ * the first extent's slot_start and the totals over all extents. */
+int32_t pc_message_extents(pc_cache *c, int32_t msg_id, int32_t *n_extents, int64_t *slot_starts,
+                           int32_t *lens, int32_t cap);
 /* *base_pos: the position the message's stored keys are currently turned to (see
  * pc_reposition). */
 int32_t pc_message_base(pc_cache *c, int32_t msg_id, int32_t *base_pos);

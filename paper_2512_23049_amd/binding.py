@@ -20,6 +20,7 @@ PC_F32, PC_BF16 = 0, 1
 PC_POS_AUTO = -(2 ** 31)
 PC_SLOT_ALIGN = 32
 PC_FLAG_HOST_ONLY = 1
+PC_FLAG_GROW_EXTENTS = 2
 PC_N_KERNEL_CLASSES = 8
 KERNEL_CLASSES = ("append", "plan", "prefill", "decode", "merge", "attend_f32", "expand", "reposition")
 
@@ -77,6 +78,8 @@ def lib():
         L.pc_resolve_call.argtypes = [vp, C.POINTER(pc_call), C.POINTER(i32), C.POINTER(i32), C.POINTER(i64)]
         L.pc_message_info.restype = i32
         L.pc_message_info.argtypes = [vp, i32, C.POINTER(i32), C.POINTER(i64), C.POINTER(i32)]
+        L.pc_message_extents.restype = i32
+        L.pc_message_extents.argtypes = [vp, i32, C.POINTER(i32), C.POINTER(i64), C.POINTER(i32), i32]
         L.pc_message_free.restype = i32
         L.pc_message_free.argtypes = [vp, i32]
         L.pc_message_base.restype = i32
@@ -270,6 +273,13 @@ class Cache:
 
     def grad_keys_finalize(self, d_k_ptr: int, stream: int = 0):
         self._check(lib().pc_grad_keys_finalize(self.h, d_k_ptr or None, stream or None))
+
+    def message_extents(self, msg: int, cap: int = 64):
+        """[(slot_start, len), ...] of the message's extents in token order."""
+        n = C.c_int32(0)
+        starts, lens = (C.c_int64 * cap)(), (C.c_int32 * cap)()
+        self._check(lib().pc_message_extents(self.h, msg, C.byref(n), starts, lens, cap))
+        return [(int(starts[i]), int(lens[i])) for i in range(min(cap, n.value))]
 
     def set_decode_sharing(self, mode: int = 0):
         """0: shared walk when a group's calls overlap enough; 1: never; 2: whenever the shape allows."""

@@ -13,7 +13,11 @@
 
 namespace {
 
-struct HostMsg { int64_t slot_start; int32_t len; int32_t reserve; int32_t base_pos; bool live; bool swapped = false; };
+// One extent of a message.  A message is a chain of extents: the record under the message's id, then the
+// records it grew into once its reserve was used up (PC_FLAG_GROW_EXTENTS); those sit in the same table under
+// ids no caller is given.  base_pos of an extent = base of the message + tokens in the extents before it.
+struct HostMsg { int64_t slot_start; int32_t len; int32_t reserve; int32_t base_pos; bool live; bool swapped = false;
+                 int32_t next = -1; bool is_ext = false; };
 struct FreeSpan { int64_t start, size; };            // freed slots, multiples of PC_SLOT_ALIGN
 
 struct StageSlot { void *host = nullptr; size_t cap = 0; hipEvent_t ev = nullptr; bool used = false; };
@@ -30,6 +34,7 @@ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 struct pc_cache {
     pc_config cfg;
     bool host_only = false;
+    bool grow_extents = false;
     int D = 0, half = 0, g = 0;
     int64_t slots = 0;
     size_t esize = 0;
@@ -112,14 +117,30 @@ void prof_collect(pc_cache *c)
 
 // ---- validated, resolved form of one call -------------------------------------------
 struct Resolved {
-    std::vector<int2> sel;        // (msg, resolved start)
-    int32_t self_msg = -1, self_start = 0, self_len = 0, n_q = 0;
+    std::vector<int2> sel;        // (extent record, resolved start), the caller's entries expanded
+    std::vector<int32_t> entry_start;   // resolved start of each entry of the caller's list
+    int32_t self_msg = -1, self_start = 0, self_len = 0, n_q = 0;   // the new message's LAST extent
+    int32_t msg_start = 0;        // resolved start of the new message's first token
     std::vector<int32_t> q_pos;
     int64_t n_kv = 0;
     int32_t tiles = 0;            // KV tiles incl. the new message
 };
 
-inline bool known(const pc_cache *c, int32_t m) { return m >= 0 && m < (int32_t)c->msgs.size() && c->msgs[(size_t)m].live; }
+inline bool known(const pc_cache *c, int32_t m)
+{
+    return m >= 0 && m < (int32_t)c->msgs.size() && c->msgs[(size_t)m].live && !c->msgs[(size_t)m].is_ext;
+}
+inline int32_t chain_len(const pc_cache *c, int32_t m)
+{
+    int32_t n = 0;
+    for (int32_t r = m; r >= 0; r = c->msgs[(size_t)r].next) n += c->msgs[(size_t)r].len;
+    return n;
+}
+inline int32_t chain_last(const pc_cache *c, int32_t m)
+{
+    while (c->msgs[(size_t)m].next >= 0) m = c->msgs[(size_t)m].next;
+    return m;
+}
 
 int32_t resolve_call(pc_cache *c, const pc_call *call, int idx, Resolved &out)
 {
@@ -128,39 +149,64 @@ int32_t resolve_call(pc_cache *c, const pc_call *call, int idx, Resolved &out)
         return fail(c, PC_ERR_INVALID_ARG, "call %d: bad parent list", idx);
     if (call->n_q < 1) return fail(c, PC_ERR_INVALID_ARG, "call %d: n_q = %d must be >= 1", idx, call->n_q);
     const int64_t maxp = c->cfg.max_position;
-    out.sel.resize(call->n_sel);
+    // a listed message becomes one (extent record, start) pair per extent that holds tokens
+    out.sel.clear();
+    out.sel.reserve((size_t)call->n_sel);
+    out.entry_start.resize((size_t)call->n_sel);
     int64_t nxt = 0, n_kv = 0, tiles = 0;
     for (int e = 0; e < call->n_sel; ++e) {
         const int32_t m = call->sel[e].msg_id;
         if (!known(c, m)) return fail(c, PC_ERR_BAD_MSG_ID, "call %d: parent %d names unknown message %d", idx, e, m);
-        const int64_t len = c->msgs[m].len;
+        const int64_t len = chain_len(c, m);
         const int64_t s = call->sel[e].start_pos == PC_POS_AUTO ? nxt : (int64_t)call->sel[e].start_pos;
         if (s < -maxp || s + len - 1 > maxp)
             return fail(c, PC_ERR_INVALID_ARG, "call %d: parent %d spans positions [%lld, %lld], limit is +-%lld", idx, e,
                         (long long)s, (long long)(s + len - 1), (long long)maxp);
-        out.sel[e] = make_int2(m, (int)s);
-        nxt = s + len; n_kv += len; tiles += (len + PC_TILE - 1) / PC_TILE;
+        out.entry_start[(size_t)e] = (int32_t)s;
+        int64_t at = s;
+        for (int32_t r = m; r >= 0; r = c->msgs[(size_t)r].next) {
+            const int32_t rl = c->msgs[(size_t)r].len;
+            if (rl > 0 || r == m) out.sel.push_back(make_int2(r, (int)at));
+            at += rl; tiles += (rl + PC_TILE - 1) / PC_TILE;
+        }
+        nxt = s + len; n_kv += len;
     }
     out.self_msg = -1; out.self_len = 0;
     int64_t s_self = call->self_start == PC_POS_AUTO ? nxt : (int64_t)call->self_start;
+    int64_t self_total = 0;
     if (call->self_msg >= 0) {
         if (!known(c, call->self_msg)) return fail(c, PC_ERR_BAD_MSG_ID, "call %d: new message id %d unknown", idx, call->self_msg);
-        out.self_msg = call->self_msg;
-        out.self_len = c->msgs[call->self_msg].len;
-        if (call->n_q > out.self_len)
-            return fail(c, PC_ERR_SHAPE, "call %d: n_q = %d exceeds the new message's %d tokens", idx, call->n_q, out.self_len);
-        if (s_self < -maxp || s_self + out.self_len - 1 > maxp)
+        self_total = chain_len(c, call->self_msg);
+        if (call->n_q > self_total)
+            return fail(c, PC_ERR_SHAPE, "call %d: n_q = %d exceeds the new message's %lld tokens", idx, call->n_q, (long long)self_total);
+        if (s_self < -maxp || s_self + self_total - 1 > maxp)
             return fail(c, PC_ERR_INVALID_ARG, "call %d: new message spans positions beyond +-%lld", idx, (long long)maxp);
-        n_kv += out.self_len; tiles += (out.self_len + PC_TILE - 1) / PC_TILE;
+        // The causal part lives in the message's last extent; the extents before it are seen whole by
+        // every query row, like parents.
+        const int32_t last = chain_last(c, call->self_msg);
+        if (call->n_q > c->msgs[(size_t)last].len)
+            return fail(c, PC_ERR_SHAPE, "call %d: the %d query rows must lie in the new message's last extent (%d tokens)", idx,
+                        call->n_q, c->msgs[(size_t)last].len);
+        int64_t at = s_self;
+        for (int32_t r = call->self_msg; r != last; r = c->msgs[(size_t)r].next) {
+            const int32_t rl = c->msgs[(size_t)r].len;
+            if (rl > 0) out.sel.push_back(make_int2(r, (int)at));
+            at += rl; tiles += (rl + PC_TILE - 1) / PC_TILE;
+        }
+        out.self_msg = last;
+        out.self_len = c->msgs[(size_t)last].len;
+        out.self_start = (int32_t)at;
+        n_kv += self_total; tiles += (out.self_len + PC_TILE - 1) / PC_TILE;
     } else if (call->self_msg != -1) {
         return fail(c, PC_ERR_BAD_MSG_ID, "call %d: self_msg must be -1 or a message id", idx);
     } else if (s_self < -maxp || s_self + call->n_q - 1 > maxp) {
         return fail(c, PC_ERR_INVALID_ARG, "call %d: query positions beyond +-%lld", idx, (long long)maxp);
     }
-    out.self_start = (int32_t)s_self;
+    out.msg_start = (int32_t)s_self;
+    if (out.self_msg < 0) out.self_start = (int32_t)s_self;
     out.n_q = call->n_q;
     out.q_pos.resize(call->n_q);
-    const int64_t tok0 = out.self_msg >= 0 ? out.self_len - call->n_q : 0;
+    const int64_t tok0 = out.self_msg >= 0 ? self_total - call->n_q : 0;
     for (int r = 0; r < call->n_q; ++r) {
         const int64_t p = call->q_pos ? (int64_t)call->q_pos[r] : s_self + tok0 + r;
         if (p < -maxp || p > maxp) return fail(c, PC_ERR_INVALID_ARG, "call %d: query position %lld beyond +-%lld", idx, (long long)p, (long long)maxp);
@@ -263,6 +309,7 @@ int32_t pc_cache_create(const pc_config *cfg, pc_cache **out)
     c->cfg = *cfg;
     if (c->cfg.max_position <= 0) c->cfg.max_position = 1 << 24;
     c->host_only = (cfg->flags & PC_FLAG_HOST_ONLY) != 0;
+    c->grow_extents = (cfg->flags & PC_FLAG_GROW_EXTENTS) != 0;
     c->D = cfg->head_dim; c->half = c->D / 2; c->g = cfg->n_q_heads / cfg->n_kv_heads;
     c->slots = (int64_t)align_up((size_t)cfg->capacity_tokens, PC_SLOT_ALIGN);
     if (c->slots > INT32_MAX) { delete c; return PC_ERR_SHAPE; }
@@ -440,19 +487,64 @@ static int32_t append_token_items(pc_cache *c, const std::vector<int32_t> &ids, 
 {
     const int n = (int)ids.size();
     std::vector<PcTokenItem> items((size_t)n);
-    std::vector<int32_t> grown(c->msgs.size(), 0);
-    for (int j = 0; j < n; ++j) grown[(size_t)ids[j]] += 1;
-    for (size_t m = 0; m < grown.size(); ++m)
-        if (grown[m] && c->msgs[m].len + grown[m] > c->msgs[m].reserve)
-            return fail(c, PC_ERR_NO_SPACE, "append_tokens: message %d holds %d of %d reserved tokens, %d more do not fit",
-                        (int)m, c->msgs[m].len, c->msgs[m].reserve, grown[m]);
-    std::vector<int32_t> seen(c->msgs.size(), 0);
+    std::vector<int32_t> left(c->msgs.size(), 0);            // tokens of this call still to place, per message
+    for (int j = 0; j < n; ++j) left[(size_t)ids[j]] += 1;
+    // the extent each message is writing into, as it will be (nothing is committed before the launch is accepted)
+    struct Cur { int32_t rec, len, reserve, base; int64_t slot; };
+    std::vector<int32_t> cur_of(c->msgs.size(), -1);
+    std::vector<Cur> cur;
+    std::vector<HostMsg> fresh;                              // new extent records: ids msgs.size(), msgs.size() + 1, ...
+    std::vector<std::pair<int32_t, int32_t>> links;          // (record, its new next)
+    std::vector<FreeSpan> spans = c->free_spans;
+    int64_t next = c->next_slot;
+    const int32_t first_new = (int32_t)c->msgs.size();
     for (int j = 0; j < n; ++j) {
-        const HostMsg &m = c->msgs[(size_t)ids[j]];
-        const int t = m.len + seen[(size_t)ids[j]]++;
-        items[(size_t)j] = PcTokenItem{ids[j], (int32_t)(m.slot_start + t), m.base_pos + t, m.len + grown[(size_t)ids[j]]};
+        const int32_t m = ids[j];
+        if (cur_of[(size_t)m] < 0) {
+            const int32_t last = chain_last(c, m);
+            const HostMsg &hm = c->msgs[(size_t)last];
+            cur_of[(size_t)m] = (int32_t)cur.size();
+            cur.push_back(Cur{last, hm.len, hm.reserve, hm.base_pos, hm.slot_start});
+        }
+        Cur &cu = cur[(size_t)cur_of[(size_t)m]];
+        if (cu.len == cu.reserve) {
+            if (!c->grow_extents)
+                return fail(c, PC_ERR_NO_SPACE, "append_tokens: message %d holds %d of %d reserved tokens, %d more do not fit",
+                            (int)m, chain_len(c, m), chain_len(c, m), left[(size_t)m]);
+            // a further extent: room for what this call still brings, at least the message's first reserve
+            if ((int64_t)c->msgs.size() + (int64_t)fresh.size() >= c->cfg.max_messages)
+                return fail(c, PC_ERR_NO_SPACE, "append_tokens: message table full (%d)", c->cfg.max_messages);
+            const int32_t res = std::max(left[(size_t)m], std::max<int32_t>(PC_SLOT_ALIGN, c->msgs[(size_t)m].reserve));
+            int64_t start = 0;
+            if (!take_slots(spans, next, c->slots, res, start))
+                return fail(c, PC_ERR_NO_SPACE, "append_tokens: no room for a further extent of %d slots for message %d", res, (int)m);
+            const int32_t id = first_new + (int32_t)fresh.size();
+            HostMsg rec{start, 0, res, cu.base + cu.len, true};
+            rec.is_ext = true;
+            fresh.push_back(rec);
+            links.push_back({cu.rec, id});
+            cu = Cur{id, 0, res, rec.base_pos, start};
+        }
+        items[(size_t)j] = PcTokenItem{cu.rec, (int32_t)(cu.slot + cu.len), cu.base + cu.len, 0};
+        cu.len += 1;
+        left[(size_t)m] -= 1;
     }
+    // every item carries the final length of the extent it goes to
+    std::vector<int32_t> final_len(c->msgs.size() + fresh.size(), 0);
+    for (size_t r = 0; r < c->msgs.size(); ++r) final_len[r] = c->msgs[r].len;
+    for (int j = 0; j < n; ++j) final_len[(size_t)items[(size_t)j].msg] += 1;
+    for (int j = 0; j < n; ++j) items[(size_t)j].new_len = final_len[(size_t)items[(size_t)j].msg];
     if (!c->host_only) {
+        if (!fresh.empty()) {                                // the device table learns the new extents (length 0 until the kernel sets it)
+            StageSlot *slot = nullptr;
+            const int32_t rc = stage_acquire(c, sizeof(PcMsgEntry) * fresh.size(), &slot);
+            if (rc != PC_OK) return rc;
+            PcMsgEntry *en = (PcMsgEntry *)slot->host;
+            for (size_t r = 0; r < fresh.size(); ++r) en[r] = PcMsgEntry{(int32_t)fresh[r].slot_start, 0, fresh[r].base_pos, 0};
+            PC_HIP(c, hipMemcpyAsync(c->table_dev + first_new, slot->host, sizeof(PcMsgEntry) * fresh.size(), hipMemcpyHostToDevice, st));
+            PC_HIP(c, hipEventRecord(slot->ev, st));
+            slot->used = true;
+        }
         const int32_t rc = stage_items(c, items.data(), sizeof(PcTokenItem) * (size_t)n, st);
         if (rc != PC_OK) return rc;
         ProfScope ps(c, 0, st);
@@ -460,7 +552,14 @@ static int32_t append_token_items(pc_cache *c, const std::vector<int32_t> &ids, 
                                 c->k_store, c->v_store, c->table_dev, st);
         PC_HIP(c, hipGetLastError());
     }
-    for (size_t m = 0; m < grown.size(); ++m) c->msgs[m].len += grown[m];
+    for (const HostMsg &rec : fresh) {
+        if (!c->msgs.empty() && rec.slot_start < c->msgs.back().slot_start) c->slots_in_id_order = false;
+        c->msgs.push_back(rec);
+    }
+    for (const auto &lk : links) c->msgs[(size_t)lk.first].next = lk.second;
+    for (size_t r = 0; r < c->msgs.size(); ++r) c->msgs[r].len = final_len[r];
+    c->free_spans.swap(spans);
+    c->next_slot = next;
     return PC_OK;
 }
 
@@ -495,8 +594,8 @@ int32_t pc_resolve_call(pc_cache *c, const pc_call *call, int32_t *starts_out, i
     Resolved r;
     const int32_t rc = resolve_call(c, call, 0, r);
     if (rc != PC_OK) return rc;
-    if (starts_out) for (size_t e = 0; e < r.sel.size(); ++e) starts_out[e] = r.sel[e].y;
-    if (self_start_out) *self_start_out = r.self_start;
+    if (starts_out) for (size_t e = 0; e < r.entry_start.size(); ++e) starts_out[e] = r.entry_start[e];
+    if (self_start_out) *self_start_out = r.msg_start;
     if (n_kv) *n_kv = r.n_kv;
     return PC_OK;
 }
@@ -505,9 +604,27 @@ int32_t pc_message_info(pc_cache *c, int32_t msg_id, int32_t *len, int64_t *slot
 {
     if (!c) return PC_ERR_INVALID_ARG;
     if (!known(c, msg_id)) return fail(c, PC_ERR_BAD_MSG_ID, "unknown message %d", msg_id);
-    if (len) *len = c->msgs[msg_id].len;
+    if (len) *len = chain_len(c, msg_id);
     if (slot_start) *slot_start = c->msgs[msg_id].slot_start;
-    if (reserved) *reserved = c->msgs[msg_id].reserve;
+    if (reserved) {
+        int32_t r = 0;
+        for (int32_t e = msg_id; e >= 0; e = c->msgs[(size_t)e].next) r += c->msgs[(size_t)e].reserve;
+        *reserved = r;
+    }
+    return PC_OK;
+}
+
+int32_t pc_message_extents(pc_cache *c, int32_t msg_id, int32_t *n_extents, int64_t *slot_starts, int32_t *lens, int32_t cap)
+{
+    if (!c) return PC_ERR_INVALID_ARG;
+    if (!known(c, msg_id)) return fail(c, PC_ERR_BAD_MSG_ID, "unknown message %d", msg_id);
+    int32_t n = 0;
+    for (int32_t e = msg_id; e >= 0; e = c->msgs[(size_t)e].next, ++n)
+        if (n < cap) {
+            if (slot_starts) slot_starts[n] = c->msgs[(size_t)e].slot_start;
+            if (lens) lens[n] = c->msgs[(size_t)e].len;
+        }
+    if (n_extents) *n_extents = n;
     return PC_OK;
 }
 
@@ -519,6 +636,8 @@ int32_t pc_message_base(pc_cache *c, int32_t msg_id, int32_t *base_pos)
     return PC_OK;
 }
 
+int32_t pc_reposition_batch(pc_cache *c, const int32_t *msg_ids, const int32_t *new_bases, int32_t n_msgs, void *stream);
+
 int32_t pc_reposition(pc_cache *c, int32_t msg_id, int32_t new_base, void *stream)
 {
     if (!c) return PC_ERR_INVALID_ARG;
@@ -526,6 +645,7 @@ int32_t pc_reposition(pc_cache *c, int32_t msg_id, int32_t new_base, void *strea
     if (new_base > c->cfg.max_position || new_base < -c->cfg.max_position)
         return fail(c, PC_ERR_INVALID_ARG, "reposition: position %d outside [-%d, %d]", new_base, c->cfg.max_position,
                     c->cfg.max_position);
+    if (c->msgs[(size_t)msg_id].next >= 0) return pc_reposition_batch(c, &msg_id, &new_base, 1, stream);   // every extent moves
     HostMsg &m = c->msgs[(size_t)msg_id];
     const int64_t delta = (int64_t)new_base - m.base_pos;
     if (delta == 0) return PC_OK;
@@ -554,9 +674,12 @@ int32_t pc_reposition_batch(pc_cache *c, const int32_t *msg_ids, const int32_t *
         if (new_bases[j] > c->cfg.max_position || new_bases[j] < -c->cfg.max_position)
             return fail(c, PC_ERR_INVALID_ARG, "reposition_batch: position %d outside [-%d, %d]", new_bases[j],
                         c->cfg.max_position, c->cfg.max_position);
-        const HostMsg &hm = c->msgs[(size_t)m];
-        const int64_t delta = (int64_t)new_bases[j] - hm.base_pos;
-        if (delta != 0) items.push_back(PcMoveItem{m, (int32_t)hm.slot_start, hm.len, (int32_t)delta, new_bases[j], {0, 0, 0}});
+        const int64_t delta = (int64_t)new_bases[j] - c->msgs[(size_t)m].base_pos;
+        if (delta != 0)
+            for (int32_t r = m; r >= 0; r = c->msgs[(size_t)r].next) {          // every extent turns by the same angle
+                const HostMsg &hm = c->msgs[(size_t)r];
+                items.push_back(PcMoveItem{r, (int32_t)hm.slot_start, hm.len, (int32_t)delta, (int32_t)(hm.base_pos + delta), {0, 0, 0}});
+            }
     }
     if (!items.empty() && !c->host_only) {
         hipStream_t st = (hipStream_t)stream;
@@ -596,9 +719,11 @@ int32_t pc_message_free(pc_cache *c, int32_t msg_id)
 {
     if (!c) return PC_ERR_INVALID_ARG;
     if (!known(c, msg_id)) return fail(c, PC_ERR_BAD_MSG_ID, "free: unknown message %d", msg_id);
-    HostMsg &m = c->msgs[(size_t)msg_id];
-    m.live = false;
-    release_span(c, FreeSpan{m.slot_start, (int64_t)align_up((size_t)m.reserve, PC_SLOT_ALIGN)});
+    for (int32_t r = msg_id; r >= 0; r = c->msgs[(size_t)r].next) {
+        HostMsg &m = c->msgs[(size_t)r];
+        m.live = false;
+        release_span(c, FreeSpan{m.slot_start, (int64_t)align_up((size_t)m.reserve, PC_SLOT_ALIGN)});
+    }
     return PC_OK;
 }
 
@@ -608,8 +733,10 @@ static inline bool swapped_out(const pc_cache *c, int32_t m) { return m >= 0 && 
 int64_t pc_message_swap_bytes(pc_cache *c, int32_t msg_id)
 {
     if (!c) return PC_ERR_INVALID_ARG;
-    if (!known(c, msg_id) && !swapped_out(c, msg_id)) return fail(c, PC_ERR_BAD_MSG_ID, "swap_bytes: unknown message %d", msg_id);
-    const int64_t span = (int64_t)align_up((size_t)c->msgs[(size_t)msg_id].reserve, PC_SLOT_ALIGN);
+    if ((!known(c, msg_id) && !swapped_out(c, msg_id)) || c->msgs[(size_t)msg_id].is_ext)
+        return fail(c, PC_ERR_BAD_MSG_ID, "swap_bytes: unknown message %d", msg_id);
+    int64_t span = 0;                                    // every extent's reserved span, one after the other
+    for (int32_t r = msg_id; r >= 0; r = c->msgs[(size_t)r].next) span += (int64_t)align_up((size_t)c->msgs[(size_t)r].reserve, PC_SLOT_ALIGN);
     return 2 * span * c->cfg.n_kv_heads * c->D * (int64_t)c->esize;
 }
 
@@ -637,43 +764,67 @@ int32_t pc_message_swap_out(pc_cache *c, int32_t msg_id, void *blob, void *strea
     if (!c) return PC_ERR_INVALID_ARG;
     if (!known(c, msg_id)) return fail(c, PC_ERR_BAD_MSG_ID, "swap_out: unknown message %d", msg_id);
     if (!c->host_only && !blob) return fail(c, PC_ERR_INVALID_ARG, "swap_out: null blob");
-    HostMsg &m = c->msgs[(size_t)msg_id];
-    const int64_t span = (int64_t)align_up((size_t)m.reserve, PC_SLOT_ALIGN);
+    const size_t per_slot = 2 * (size_t)c->cfg.n_kv_heads * (size_t)c->D * c->esize;
     if (!c->host_only) {
-        const int32_t rc = copy_span(c, m.slot_start, span, blob, true, (hipStream_t)stream);
-        if (rc != PC_OK) return rc;
+        char *at = (char *)blob;
+        for (int32_t r = msg_id; r >= 0; r = c->msgs[(size_t)r].next) {
+            const HostMsg &m = c->msgs[(size_t)r];
+            const int64_t span = (int64_t)align_up((size_t)m.reserve, PC_SLOT_ALIGN);
+            const int32_t rc = copy_span(c, m.slot_start, span, at, true, (hipStream_t)stream);
+            if (rc != PC_OK) return rc;
+            at += (size_t)span * per_slot;
+        }
     }
-    m.live = false; m.swapped = true;
-    release_span(c, FreeSpan{m.slot_start, span});
+    for (int32_t r = msg_id; r >= 0; r = c->msgs[(size_t)r].next) {
+        HostMsg &m = c->msgs[(size_t)r];
+        m.live = false; m.swapped = true;
+        release_span(c, FreeSpan{m.slot_start, (int64_t)align_up((size_t)m.reserve, PC_SLOT_ALIGN)});
+    }
     return PC_OK;
 }
 
 int32_t pc_message_swap_in(pc_cache *c, int32_t msg_id, const void *blob, void *stream)
 {
     if (!c) return PC_ERR_INVALID_ARG;
-    if (!swapped_out(c, msg_id)) return fail(c, PC_ERR_BAD_MSG_ID, "swap_in: message %d is not swapped out", msg_id);
+    if (!swapped_out(c, msg_id) || c->msgs[(size_t)msg_id].is_ext)
+        return fail(c, PC_ERR_BAD_MSG_ID, "swap_in: message %d is not swapped out", msg_id);
     if (!c->host_only && !blob) return fail(c, PC_ERR_INVALID_ARG, "swap_in: null blob");
-    HostMsg &m = c->msgs[(size_t)msg_id];
+    // slots for every extent first: all or nothing
     std::vector<FreeSpan> spans = c->free_spans;
-    int64_t next = c->next_slot, start = 0;
-    if (!take_slots(spans, next, c->slots, m.reserve, start))
-        return fail(c, PC_ERR_NO_SPACE, "swap_in: message %d (%d slots) does not fit, capacity %lld", msg_id, m.reserve, (long long)c->slots);
+    int64_t next = c->next_slot;
+    std::vector<std::pair<int32_t, int64_t>> placed;      // (record, new slot_start)
+    for (int32_t r = msg_id; r >= 0; r = c->msgs[(size_t)r].next) {
+        int64_t start = 0;
+        if (!take_slots(spans, next, c->slots, c->msgs[(size_t)r].reserve, start))
+            return fail(c, PC_ERR_NO_SPACE, "swap_in: message %d does not fit (an extent of %d slots), capacity %lld", msg_id,
+                        c->msgs[(size_t)r].reserve, (long long)c->slots);
+        placed.push_back({r, start});
+    }
     if (!c->host_only) {
         hipStream_t st = (hipStream_t)stream;
-        const int64_t span = (int64_t)align_up((size_t)m.reserve, PC_SLOT_ALIGN);
-        int32_t rc = copy_span(c, start, span, const_cast<void *>(blob), false, st);
-        if (rc != PC_OK) return rc;
-        // the device table learns where the message lives now
-        StageSlot *slot = nullptr;
-        rc = stage_acquire(c, sizeof(PcMsgEntry), &slot);
-        if (rc != PC_OK) return rc;
-        const PcMsgEntry en{(int32_t)start, m.len, m.base_pos, 0};
-        std::memcpy(slot->host, &en, sizeof en);
-        PC_HIP(c, hipMemcpyAsync(c->table_dev + msg_id, slot->host, sizeof en, hipMemcpyHostToDevice, st));
-        PC_HIP(c, hipEventRecord(slot->ev, st));
-        slot->used = true;
+        const size_t per_slot = 2 * (size_t)c->cfg.n_kv_heads * (size_t)c->D * c->esize;
+        const char *at = (const char *)blob;
+        for (const auto &pl : placed) {
+            const HostMsg &m = c->msgs[(size_t)pl.first];
+            const int64_t span = (int64_t)align_up((size_t)m.reserve, PC_SLOT_ALIGN);
+            int32_t rc = copy_span(c, pl.second, span, const_cast<char *>(at), false, st);
+            if (rc != PC_OK) return rc;
+            at += (size_t)span * per_slot;
+            // the device table learns where the extent lives now
+            StageSlot *slot = nullptr;
+            rc = stage_acquire(c, sizeof(PcMsgEntry), &slot);
+            if (rc != PC_OK) return rc;
+            const PcMsgEntry en{(int32_t)pl.second, m.len, m.base_pos, 0};
+            std::memcpy(slot->host, &en, sizeof en);
+            PC_HIP(c, hipMemcpyAsync(c->table_dev + pl.first, slot->host, sizeof en, hipMemcpyHostToDevice, st));
+            PC_HIP(c, hipEventRecord(slot->ev, st));
+            slot->used = true;
+        }
     }
-    m.slot_start = start; m.live = true; m.swapped = false;
+    for (const auto &pl : placed) {
+        HostMsg &m = c->msgs[(size_t)pl.first];
+        m.slot_start = pl.second; m.live = true; m.swapped = false;
+    }
     c->slots_in_id_order = false;                       // an old id may now sit behind newer ones
     c->free_spans.swap(spans);
     c->next_slot = next;

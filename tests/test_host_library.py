@@ -312,3 +312,57 @@ def test_gradient_entry_points_need_an_fp32_cache(pc):
     with pytest.raises(pc.PcError) as ei:
         f.attend_backward([Call([(a + 1, 0)], -1, 0, 1, None)], 0, 0, 0, 0, 0, 0)
     assert ei.value.code == pc.PC_ERR_BAD_MSG_ID
+
+
+def test_messages_grow_into_further_extents(pc):
+    # with PC_FLAG_GROW_EXTENTS a full message takes another span; to callers it stays one sequence of tokens
+    c = host_cache(pc, capacity_tokens=1024, max_messages=16, flags=pc.PC_FLAG_HOST_ONLY | pc.PC_FLAG_GROW_EXTENTS)
+    a = c.append_message(0, 0, 3, 5)            # [0, 32): 3 of 5
+    b = c.append_message(0, 0, 40)              # [32, 96): full
+    c.append_tokens(a, 0, 0, 2)                 # fills a's reserve
+    assert c.message_extents(a) == [(0, 5)]
+    c.append_tokens(a, 0, 0, 40)                # one further extent: room for the 40, [96, 160)
+    assert c.message_extents(a) == [(0, 5), (96, 40)]
+    assert c.message_info(a) == (45, 0, 45)
+    c.append_tokens_batch([a, b], 0, 0)         # a: third extent (first reserve 5 -> 32 slots) at [160, 192); b: second at [192, 256)
+    assert c.message_extents(a) == [(0, 5), (96, 40), (160, 1)]
+    assert c.message_extents(b) == [(32, 40), (192, 1)]
+    assert c.cache_info()[1] == 256
+    d = c.append_message(0, 0, 7)               # ids keep ascending past the hidden extent rows
+    assert d == 5 and c.message_info(d)[1] == 256
+    # one sequence of tokens to a call: lengths, default offsets, position limits
+    starts, s_self, n = c.resolve_call(Call([(a, POS_AUTO), (b, POS_AUTO)], d, POS_AUTO, 7, None))
+    assert starts == [0, 46] and s_self == 87 and n == 46 + 41 + 7
+    # the query rows must lie in the last extent of the new message
+    starts, s_self, n = c.resolve_call(Call([(b, 0)], a, 100, 1, None))
+    assert s_self == 100 and n == 41 + 46
+    with pytest.raises(pc.PcError) as ei:
+        c.resolve_call(Call([], a, 0, 2, None))
+    assert ei.value.code == pc.PC_ERR_SHAPE
+    # hidden extent rows are not messages
+    for hidden in (2, 3, 4):
+        with pytest.raises(pc.PcError) as ei:
+            c.message_info(hidden)
+        assert ei.value.code == pc.PC_ERR_BAD_MSG_ID
+    c.reposition(a, 1000)
+    assert c.message_base(a) == 1000
+    # swap and free cover every extent
+    per_slot = 2 * 2 * 128 * 2
+    assert c.message_swap_bytes(a) == (32 + 64 + 32) * per_slot
+    c.message_swap_out(a, 0)
+    e = c.append_message(0, 0, 30)              # first hole: a's first span
+    assert c.message_info(e)[1] == 0
+    c.message_swap_in(a, 0)                     # hole [96, 192): 5 -> [96, 128), 40 -> [128, 192); 1 -> the end, [288, 320)
+    assert c.message_extents(a) == [(96, 5), (128, 40), (288, 1)]
+    assert c.message_info(a)[0] == 46 and c.message_base(a) == 1000
+    c.message_free(b)
+    with pytest.raises(pc.PcError):
+        c.message_info(b)
+    f = c.append_message(0, 0, 60)              # b's first span [32, 96) is free again
+    assert c.message_info(f)[1] == 32
+    # without the flag a full message is full
+    p = host_cache(pc)
+    m = p.append_message(0, 0, 2)
+    with pytest.raises(pc.PcError) as ei:
+        p.append_tokens(m, 0, 0, 1)
+    assert ei.value.code == pc.PC_ERR_NO_SPACE
