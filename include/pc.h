@@ -131,7 +131,9 @@ int32_t pc_append_messages(pc_cache *c, int32_t n, const void *const *k, const v
  * Keys are turned to base + in-message index like those of pc_append_message.  Stream
  * ordered: a later pc_attend on the same stream sees the longer messages.
  * Errors (nothing enqueued): unknown id, an id listed twice in a batch, n < 1, more
- * tokens than the reserve has room for (PC_ERR_NO_SPACE). */
+ * tokens than the reserve has room for (PC_ERR_NO_SPACE; with PC_FLAG_GROW_EXTENTS the
+ * message takes a further extent instead, and PC_ERR_NO_SPACE means the cache or the
+ * message table has no room for it). */
 int32_t pc_append_tokens(pc_cache *c, int32_t msg_id, const void *k, const void *v, int32_t n,
                          void *stream);
 int32_t pc_append_tokens_batch(pc_cache *c, const int32_t *msg_ids, int32_t n_msgs, const void *k,
