@@ -1033,9 +1033,7 @@ static int32_t plan_and_stage(pc_cache *c, const pc_call *calls, int32_t n_calls
     for (int i = 0; i < n_calls; ++i) {
         const int32_t rc = resolve_call(c, &calls[i], i, P.res[i]);
         if (rc != PC_OK) return rc;
-        P.total_sel += (int)P.res[i].sel.size();
         P.total_q += P.res[i].n_q;
-        P.total_seg += (int)P.res[i].sel.size() + (P.res[i].self_msg >= 0 ? 1 : 0);
     }
     const int g = c->g, H_kv = c->cfg.n_kv_heads;
     const bool bf16 = c->cfg.dtype == PC_BF16;
@@ -1065,12 +1063,16 @@ static int32_t plan_and_stage(pc_cache *c, const pc_call *calls, int32_t n_calls
     for (int i = 0; i < n_calls; ++i) {
         Resolved &r = P.res[i];
         PcCallDesc &cd = cds[i];
-        cd.sel_off = sel_off; cd.n_sel = (int)r.sel.size(); cd.self_msg = r.self_msg; cd.self_start = r.self_start;
-        cd.n_q = r.n_q; cd.q_off = q_off; cd.seg_off = seg_off; cd.n_seg = cd.n_sel + (r.self_msg >= 0 ? 1 : 0);
-        cd.self_len = r.self_len; cd.n_splits = 1; cd.part_off = 0; cd.tile_off = (int32_t)total_tiles;
-        total_tiles += r.tiles;
+        // a call served by the shared walk needs no segments, tiles or rotation rows of its own: the plan
+        // builder sees it as a call that lists nothing
+        const bool own_plan = !sp.in_shared[(size_t)i];
+        cd.sel_off = sel_off; cd.n_sel = own_plan ? (int)r.sel.size() : 0;
+        cd.self_msg = own_plan ? r.self_msg : -1; cd.self_start = r.self_start;
+        cd.n_q = r.n_q; cd.q_off = q_off; cd.seg_off = seg_off; cd.n_seg = cd.n_sel + (cd.self_msg >= 0 ? 1 : 0);
+        cd.self_len = own_plan ? r.self_len : 0; cd.n_splits = 1; cd.part_off = 0; cd.tile_off = (int32_t)total_tiles;
+        if (own_plan) total_tiles += r.tiles;
         sel_off += cd.n_sel; q_off += cd.n_q; seg_off += cd.n_seg;
-        if (!want_items || !bf16 || sp.in_shared[(size_t)i]) continue;
+        if (!want_items || !bf16 || !own_plan) continue;
         const int T = r.tiles;
         if (r.n_q * g <= 16) {                       // decode-shaped: all rows x heads of a KV head in one wave
             // Attention does not depend on the order the keys are visited in (each keeps its own
@@ -1138,6 +1140,7 @@ static int32_t plan_and_stage(pc_cache *c, const pc_call *calls, int32_t n_calls
             sp.items.push_back(PcShItem{(int32_t)gi, sidx * chunk, std::min(T, (sidx + 1) * chunk), sidx});
     }
     if (part_rows > INT32_MAX) return fail(c, PC_ERR_SHAPE, "attend: partial buffer too large");
+    P.total_sel = sel_off; P.total_seg = seg_off;
     P.n_dec = (int)dec.size(); P.n_pre = (int)pre.size();
     P.n_sh_items = (int)sp.items.size(); P.n_sh_pos = sp.pos.size();
     if (total_tiles > INT32_MAX / 2) return fail(c, PC_ERR_SHAPE, "attend: too many KV tiles");
@@ -1158,7 +1161,7 @@ static int32_t plan_and_stage(pc_cache *c, const pc_call *calls, int32_t n_calls
     PcMergeRow *hm = (PcMergeRow *)(h + P.lay.merge_rows);
     for (int i = 0; i < n_calls; ++i) {
         const Resolved &r = P.res[i];
-        if (!r.sel.empty()) std::memcpy(hs + cds[i].sel_off, r.sel.data(), sizeof(int2) * r.sel.size());
+        if (cds[i].n_sel > 0) std::memcpy(hs + cds[i].sel_off, r.sel.data(), sizeof(int2) * (size_t)cds[i].n_sel);
         std::memcpy(hq + cds[i].q_off, r.q_pos.data(), sizeof(int32_t) * r.q_pos.size());
         for (int q = 0; q < r.n_q; ++q) hr[cds[i].q_off + q] = i;
         if (cds[i].n_splits > 1)
