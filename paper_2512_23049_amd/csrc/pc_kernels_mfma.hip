@@ -22,6 +22,19 @@
 // with one workgroup per CU (what an unconstrained register allocation gives) it reached
 // only four fifths of the bandwidth it reaches with two.
 // ----------------------------------------------------------------------------------------
+// maximum over the lane pairs (l, l ^ 16) and (l, l ^ 32) without a trip through LDS: the swap
+// instructions exchange 16- resp. 32-lane rows between their two operands
+__device__ __forceinline__ float max_lanes_xor16(float x)
+{
+    auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float max_lanes_xor32(float x)
+{
+    auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+
 struct DecTile {
     uint4 k[2][4];      // [16-key half][d step of 32]
     uint4 v[8];         // [16-d block]
@@ -80,8 +93,9 @@ __global__ __launch_bounds__(256, 2) void pc_decode_bf16_kernel(PcLaunch L)
                 const float x = (j & 1) ? bf_hi(lw[j >> 1]) : bf_lo(lw[j >> 1]);
                 const float y = (j & 1) ? bf_hi(hw[j >> 1]) : bf_lo(hw[j >> 1]);
                 const float2 cs = rq[32 * ks + j];
-                qh[ks][j] = col_ok ? x * cs.x - y * cs.y : 0.f;
-                qh[ks + 2][j] = col_ok ? x * cs.y + y * cs.x : 0.f;
+                // (the softmax scale, times log2 e, rides on the query: scores come out of the MFMA ready for exp2)
+                qh[ks][j] = col_ok ? (x * cs.x - y * cs.y) * L.scale_log2 : 0.f;
+                qh[ks + 2][j] = col_ok ? (x * cs.y + y * cs.x) * L.scale_log2 : 0.f;
             }
         }
     }
@@ -159,28 +173,29 @@ __global__ __launch_bounds__(256, 2) void pc_decode_bf16_kernel(PcLaunch L)
         // lane holds keys 8a + 0..7 of column n
         const int lim = (T.seg == self_seg) ? min(T.valid, self_lim - T.key0 + 1) : T.valid;
         float sc[8];
-        float mx = -INFINITY;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const float v = s[j >> 2][j & 3] * L.scale_log2;
-            sc[j] = (8 * a + j < lim) ? v : -INFINITY;
-            mx = fmaxf(mx, sc[j]);
+        for (int j = 0; j < 8; ++j) sc[j] = s[j >> 2][j & 3];
+        if (T.valid < PC_TILE || T.seg == self_seg) {      // ragged or causal tile (uniform over the wave): mask
+#pragma unroll
+            for (int j = 0; j < 8; ++j) sc[j] = (8 * a + j < lim) ? sc[j] : -INFINITY;
         }
-        mx = fmaxf(mx, __shfl_xor(mx, 16));
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        float mx = fmaxf(fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3])), fmaxf(fmaxf(sc[4], sc[5]), fmaxf(sc[6], sc[7])));
+        mx = max_lanes_xor16(mx);
+        mx = max_lanes_xor32(mx);
         const float m_new = fmaxf(m_run, mx);
         const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
-        const float alpha = exp2f(m_run - m_safe);
+        const float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);
         float p[8], ps = 0.f;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) { p[j] = exp2f(sc[j] - m_safe); ps += p[j]; }
+        for (int j = 0; j < 8; ++j) { p[j] = __builtin_amdgcn_exp2f(sc[j] - m_safe); ps += p[j]; }
         l_run = l_run * alpha + ps;
         m_run = m_new;
+        const bool rescale = __builtin_amdgcn_ballot_w64(alpha != 1.f) != 0;   // rare once the running maxima have settled
         const bf16x8 pop = __builtin_bit_cast(bf16x8, make_uint4(pack_bf16(p[0], p[1]), pack_bf16(p[2], p[3]),
                                                                  pack_bf16(p[4], p[5]), pack_bf16(p[6], p[7])));
 #pragma unroll
         for (int db = 0; db < 8; ++db) {
-            acc[db] *= alpha;
+            if (rescale) acc[db] *= alpha;
             acc[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, T.v[db]), pop, acc[db], 0, 0, 0);
         }
     };
