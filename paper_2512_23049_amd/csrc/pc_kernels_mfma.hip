@@ -41,6 +41,7 @@ struct DecTile {
     int seg;            // segment index within the call
     int key0;           // first in-message token of the tile
     int valid;          // tokens of the tile that exist (1..32)
+    bool fresh;         // first tile of a segment whose query rotation differs from the one before
 };
 
 __device__ __forceinline__ void dec_load(DecTile &T, const uint16_t *__restrict__ kb, const uint16_t *__restrict__ vb,
@@ -79,6 +80,23 @@ __global__ __launch_bounds__(256, 2) void pc_decode_bf16_kernel(PcLaunch L)
     const int self_seg = cd.self_msg >= 0 ? cd.n_seg - 1 : -1;
     const int self_lim = cd.self_len - cd.n_q + qr;      // last own token this column sees
 
+    // this wave's contiguous run of tiles
+    const int n_tiles = item.tile_end - item.tile_begin;
+    const int per_wave = (n_tiles + 3) >> 2;
+    int tile = item.tile_begin + wave * per_wave;
+    const int tile_stop = min(item.tile_end, tile + per_wave);
+    // Where a tile lives comes from the call's tile table (written by the plan builder), read with a
+    // scalar load one tile ahead of the loads it steers; the first one is requested here, in front of
+    // the query, so that the wave's first K/V loads do not wait behind a search through the segments.
+    typedef int i32x4 __attribute__((ext_vector_type(4)));
+    const PcTile *tile_tab = L.tiles + cd.tile_off;
+    auto describe = [&](int t) {
+        const int tc = __builtin_amdgcn_readfirstlane(max(0, min(t, item.tile_end - 1)));
+        if (item.tile_end <= 0) return (i32x4){0, 0, 0, 0};                   // a call that sees nothing has no table
+        return *reinterpret_cast<const __attribute__((address_space(4))) i32x4 *>(reinterpret_cast<uintptr_t>(tile_tab + tc));
+    };
+    i32x4 next_desc = describe(tile);                    // {slot0, key0, seg, valid | flags}
+
     // query turned by its own position, kept in fp32: element (ks, j) is dim 32*ks + 8*a + j
     float qh[4][8];
     {
@@ -103,50 +121,23 @@ __global__ __launch_bounds__(256, 2) void pc_decode_bf16_kernel(PcLaunch L)
     const uint16_t *kb = (const uint16_t *)L.k_store + (int64_t)kh * L.slots * PC_D;
     const uint16_t *vb = (const uint16_t *)L.v_store + (int64_t)kh * L.slots * PC_D;
 
-    // this wave's contiguous run of tiles
-    const int n_tiles = item.tile_end - item.tile_begin;
-    const int per_wave = (n_tiles + 3) >> 2;
-    int tile = item.tile_begin + wave * per_wave;
-    const int tile_stop = min(item.tile_end, tile + per_wave);
-
     float m_run = -INFINITY, l_run = 0.f;
     f32x4 acc[8];
 #pragma unroll
     for (int db = 0; db < 8; ++db) acc[db] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-    // segment cursor
-    int e = 0;
-    PcSegment sg = {0, 0, 0, 0};
-    int seg_tiles_end = 0;
-    auto seek = [&](int t) {           // make (e, sg) the segment that owns tile t
-        while (t >= seg_tiles_end) {
-            // binary search on first use, then linear steps
-            if (seg_tiles_end == 0) {
-                int lo = 0, hi = cd.n_seg - 1;
-                while (lo < hi) {
-                    const int mid = (lo + hi + 1) >> 1;
-                    if (L.segs[cd.seg_off + mid].tile_off <= t) lo = mid; else hi = mid - 1;
-                }
-                e = lo;
-            } else {
-                ++e;
-            }
-            sg = L.segs[cd.seg_off + e];
-            seg_tiles_end = sg.tile_off + (sg.len + PC_TILE - 1) / PC_TILE;
-        }
-    };
-    auto fetch = [&](DecTile &T, int t) {
-        seek(t);
-        const int key0 = (t - sg.tile_off) * PC_TILE;
-        T.seg = e; T.key0 = key0; T.valid = min(PC_TILE, sg.len - key0);
-        dec_load(T, kb, vb, sg.slot_start + key0, T.valid, lane);
+    auto fetch = [&](DecTile &T, int t) {                // t is the tile next_desc describes
+        const i32x4 d = next_desc;
+        next_desc = describe(t + 1);
+        T.seg = d.z; T.key0 = d.y; T.valid = d.w & 0xFF; T.fresh = (d.w & PC_TILE_FRESH) != 0;
+        dec_load(T, kb, vb, d.x, T.valid, lane);
     };
 
     int cur_seg = -1;
     bf16x8 qop[4];
     auto compute = [&](const DecTile &T) {
-        if (T.seg != cur_seg) {                          // turn the query by -segment start
-            cur_seg = T.seg;
+        if (T.fresh || cur_seg < 0) {                    // turn the query by -(segment start - stored base): a new
+            cur_seg = T.seg;                             // rotation starts here, or the wave starts inside a segment
             const float2 *rs = L.rot_seg + (int64_t)(cd.seg_off + cur_seg) * (PC_D / 2) + 8 * a;
 #pragma unroll
             for (int ks = 0; ks < 2; ++ks) {
