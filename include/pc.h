@@ -289,7 +289,7 @@ int32_t pc_grad_keys_finalize(pc_cache *c, float *d_k, void *stream);
  * query heads per KV head, for g in {1, 2, 4, 8}) can be served as a group that reads the
  * union of their messages once per KV head instead of once per call; results are the same
  * up to rounding.  mode 0 (default): a group takes the shared walk when its calls together
- * list at least five times the tokens of the union; 1: never; 2: always when the shape
+ * list at least six times the tokens of the union; 1: never; 2: always when the shape
  * allows it.  Applies to PC_BF16 caches; other calls are unaffected. */
 int32_t pc_set_decode_sharing(pc_cache *c, int32_t mode);
 

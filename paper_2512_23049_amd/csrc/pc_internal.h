@@ -127,6 +127,8 @@ struct PcShItem {
     int32_t group;
     int32_t tile_begin, tile_end;     // range of the union's tiles
     int32_t split;
+    int32_t seg_begin;                // message of the union that owns tile_begin
+    int32_t pad[3];
 };
 
 struct PcShLaunch {

@@ -154,15 +154,7 @@ __global__ __launch_bounds__(512, 1) void pc_decode_shared_bf16_kernel(PcLaunch 
         d.vis = *reinterpret_cast<const __attribute__((address_space(4))) unsigned *>(at + 16 + 4 * ub_s);
         return d;
     };
-    int e = 0;
-    {
-        int lo = 0, hi = gr.n_seg - 1;                   // the segment that owns the first tile
-        while (lo < hi) {
-            const int mid = (lo + hi + 1) >> 1;
-            if (segs[mid].tile_off <= item.tile_begin) lo = mid; else hi = mid - 1;
-        }
-        e = lo;
-    }
+    int e = item.seg_begin;                              // the message that owns the first tile (found by the host)
     SegD sg = load_seg(e), sg_next = load_seg(e + 1);
     // a tile in flight: where it comes from is only needed for the request; what the compute step
     // needs travels in these three scalars

@@ -933,8 +933,8 @@ struct SharedPlan {
 
 // Calls that together list n times the tokens of the union gain from the shared walk once n
 // exceeds what a union tile costs there (a workgroup's pass over it for all rows: 8.7 ns per tile
-// and KV head with the chip full) relative to a tile streamed by one call (1.7 to 1.8 ns).
-constexpr double SHARE_MIN = 5.0;
+// and KV head with the chip full) relative to a tile streamed by one call (1.5 to 1.7 ns).
+constexpr double SHARE_MIN = 6.0;
 
 static void plan_shared(const pc_cache *c, std::vector<Resolved> &res, const std::vector<int> &q_off, int g, SharedPlan &sp)
 {
@@ -1136,8 +1136,12 @@ static int32_t plan_and_stage(pc_cache *c, const pc_call *calls, int32_t n_calls
         ns = std::max(1, (T + chunk - 1) / chunk);
         gr.n_splits = ns;
         if (ns > 1) { gr.part_off = (int32_t)part_rows; part_rows += (int64_t)ns * gr.n_rows; }
-        for (int sidx = 0; sidx < ns; ++sidx)
-            sp.items.push_back(PcShItem{(int32_t)gi, sidx * chunk, std::min(T, (sidx + 1) * chunk), sidx});
+        int seg = 0;                                     // the message that owns a split's first tile (splits ascend)
+        for (int sidx = 0; sidx < ns; ++sidx) {
+            const int t0 = sidx * chunk;
+            while (seg + 1 < gr.n_seg && sp.segs[(size_t)gr.seg_off + (size_t)seg + 1].tile_off <= t0) ++seg;
+            sp.items.push_back(PcShItem{(int32_t)gi, t0, std::min(T, (sidx + 1) * chunk), sidx, seg, {0, 0, 0}});
+        }
     }
     if (part_rows > INT32_MAX) return fail(c, PC_ERR_SHAPE, "attend: partial buffer too large");
     P.total_sel = sel_off; P.total_seg = seg_off;
