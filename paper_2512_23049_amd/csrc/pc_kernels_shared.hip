@@ -50,6 +50,7 @@ __device__ __forceinline__ void sh_barrier() { asm volatile("s_barrier" ::: "mem
 
 #define SH_RING 4                 // ring slots of 16 KB (K and V tile)
 #define SH_AHEAD (SH_RING - 1)    // tiles in flight beyond the one being computed
+#define SH_LAZY 8.0f               // log2 of how far a tile's maximum may exceed the softmax reference before it moves
 // wait until at most the 2 * (SH_AHEAD - 1) youngest direct loads of this wave are outstanding
 __device__ __forceinline__ void sh_wait_landed()
 {
@@ -128,6 +129,10 @@ __global__ __launch_bounds__(512, 1) void pc_decode_shared_bf16_kernel(PcLaunch 
     // K row read by this lane for MFMA row n: rows are permuted so that score registers 0..7 / 8..15
     // of a lane are keys 8*hh + 0..7 / 16 + 8*hh + 0..7 (the layout the second MFMA's B operand wants)
     const int krow = 16 * (n >> 4) + 8 * ((n >> 2) & 1) + 4 * ((n >> 3) & 1) + (n & 3);
+
+    unsigned k_off[8];                                   // byte offset of K fragment ks within a tile, for this lane
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) k_off[ks] = (unsigned)(krow * 256 + (((2 * ks + hh) ^ (krow & 15)) << 4));
 
     float m_run = -INFINITY, l_run = 0.f;
     f32x16 acc[4];
@@ -210,8 +215,7 @@ __global__ __launch_bounds__(512, 1) void pc_decode_shared_bf16_kernel(PcLaunch 
         // MFMA has consumed it, so the P.V MFMAs find their operands in registers
         bf16x8 fr[8];
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks)
-            fr[ks] = *reinterpret_cast<const bf16x8 *>(kt + krow * 256 + (((2 * ks + hh) ^ (krow & 15)) << 4));
+        for (int ks = 0; ks < 8; ++ks) fr[ks] = *reinterpret_cast<const bf16x8 *>(kt + k_off[ks]);
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) asm volatile("" : "+v"(fr[ks]));      // (keeps the compiler from moving each read down to its MFMA)
         f32x16 s;
@@ -225,29 +229,35 @@ __global__ __launch_bounds__(512, 1) void pc_decode_shared_bf16_kernel(PcLaunch 
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
         }
-        const int lim = vis ? valid : 0;
-        float mx = -INFINITY;
+        if (valid < PC_TILE) {                           // ragged last tile of a message (uniform): keys past its end
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int key = 16 * (r >> 3) + 8 * hh + (r & 7);
-            s[r] = (key < lim) ? s[r] : -INFINITY;
-            mx = fmaxf(mx, s[r]);
+            for (int r = 0; r < 16; ++r) {
+                const int key = 16 * (r >> 3) + 8 * hh + (r & 7);
+                s[r] = (key < valid) ? s[r] : -INFINITY;
+            }
         }
+        float mx = fmaxf(s[0], s[1]);
+#pragma unroll
+        for (int r = 2; r < 16; r += 2) mx = fmaxf(mx, fmaxf(s[r], s[r + 1]));
         mx = sh_max_halves(mx);
-        const float m_new = fmaxf(m_run, mx);
-        const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
-        const float alpha = sh_exp2(m_run - m_safe);     // 0 while nothing has been seen
+        mx = vis ? mx : -INFINITY;                       // a row that does not list the message: nothing moves, and ...
+        // The reference moves (and the accumulators are rescaled) only when a tile's maximum exceeds it by more than
+        // 2^SH_LAZY, or when the row sees its first keys: probabilities stay below 2^SH_LAZY, far inside fp32 and bf16.
+        const bool move = mx > m_run + SH_LAZY;
+        const float m_new = move ? mx : m_run;
+        const float alpha = move ? sh_exp2(m_run - m_new) : 1.f;           // 0 when nothing had been seen
+        const float m_use = vis ? m_new : INFINITY;      // ... all its probabilities are exp2(-inf) = 0
         float ps = 0.f;
         uint32_t pk[8];
 #pragma unroll
         for (int r = 0; r < 16; r += 2) {
-            const float p0 = sh_exp2(s[r] - m_safe), p1 = sh_exp2(s[r + 1] - m_safe);
+            const float p0 = sh_exp2(s[r] - m_use), p1 = sh_exp2(s[r + 1] - m_use);
             ps += p0 + p1;
             pk[r >> 1] = pack_bf16(p0, p1);
         }
         l_run = l_run * alpha + ps;
         m_run = m_new;
-        if (__builtin_amdgcn_ballot_w64(alpha != 1.f) != 0) {
+        if (__builtin_amdgcn_ballot_w64(move) != 0) {
 #pragma unroll
             for (int db = 0; db < 4; ++db) acc[db] *= alpha;
         }

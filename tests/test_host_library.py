@@ -366,3 +366,63 @@ def test_messages_grow_into_further_extents(pc):
     with pytest.raises(pc.PcError) as ei:
         p.append_tokens(m, 0, 0, 1)
     assert ei.value.code == pc.PC_ERR_NO_SPACE
+
+
+def test_random_walk_of_the_allocator_with_extents_swaps_and_frees(pc):
+    # appends, growth into further extents, swaps out and in, and frees in random order: every span the library
+    # hands out is where the slot model puts it (an extent is a message of its own to the model), and the
+    # library's view of each message (length, extents) matches a plain record kept here
+    rng = np.random.default_rng(23)
+    c = host_cache(pc, capacity_tokens=1 << 15, max_messages=4096, flags=pc.PC_FLAG_HOST_ONLY | pc.PC_FLAG_GROW_EXTENTS)
+    model = orc.SlotModel(pc.PC_SLOT_ALIGN)
+    msgs, swapped = {}, {}                       # id -> list of [model key, slot, len, reserve]
+    key = [0]
+
+    def place(res):
+        key[0] += 1
+        return [key[0], model.append(key[0], res), 0, res]
+
+    for step in range(600):
+        u = rng.random()
+        if u < 0.25 or not msgs:
+            L, r = int(rng.integers(1, 90)), int(rng.integers(0, 120))
+            ext = place(max(L, r)); ext[2] = L
+            m = c.append_message(0, 0, L, r)
+            msgs[m] = [ext]
+        elif u < 0.65:
+            m = list(msgs)[int(rng.integers(0, len(msgs)))]
+            n = int(rng.integers(1, 70))
+            first_res = msgs[m][0][3]
+            left = n
+            while left:
+                ext = msgs[m][-1]
+                if ext[2] == ext[3]:
+                    ext = place(max(left, max(pc.PC_SLOT_ALIGN, first_res)))
+                    msgs[m].append(ext)
+                take = min(left, ext[3] - ext[2])
+                ext[2] += take
+                left -= take
+            c.append_tokens(m, 0, 0, n)
+        elif u < 0.8:
+            m = list(msgs)[int(rng.integers(0, len(msgs)))]
+            c.message_swap_out(m, 0)
+            for ext in msgs[m]:
+                model.release(ext[0])
+            swapped[m] = msgs.pop(m)
+        elif u < 0.9 and swapped:
+            m = list(swapped)[int(rng.integers(0, len(swapped)))]
+            exts = swapped.pop(m)
+            for ext in exts:
+                key[0] += 1
+                ext[0], ext[1] = key[0], model.append(key[0], ext[3])
+            c.message_swap_in(m, 0)
+            msgs[m] = exts
+        else:
+            m = list(msgs)[int(rng.integers(0, len(msgs)))]
+            c.message_free(m)
+            for ext in msgs.pop(m):
+                model.release(ext[0])
+        assert c.cache_info()[1] == model.end
+        for m, exts in msgs.items():
+            assert c.message_extents(m, 256) == [(e[1], e[2]) for e in exts], (step, m)
+            assert c.message_info(m)[0] == sum(e[2] for e in exts)
