@@ -4,8 +4,8 @@
 // is loaded once per KV head for all of them).
 //
 // The query rows of the group (one per call) times the g query heads of a KV head are the
-// columns of 32x32x16 MFMAs, as in the prefill kernel: a workgroup is 8 waves, a wave owns 32
-// rows of one head.  What differs from prefill:
+// columns of 32x32x16 MFMAs, as in the prefill kernel: a workgroup is 8 waves, a wave owns 32 / g
+// rows times the g heads.  What differs from prefill:
 //   * a row sees a message only if its call lists it: one bit per (message, row);
 //   * each call places a message at its own start, so the queries are turned per (message, row)
 //     from a table of (cos, sin)((start - stored base) theta_i) the host lists and a small
@@ -88,9 +88,13 @@ __global__ __launch_bounds__(512, 1) void pc_decode_shared_bf16_kernel(PcLaunch 
     const int g = L.n_q_heads / L.n_kv_heads;            // 1, 2, 4 or 8: a workgroup covers 8 / g blocks of 32 rows
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int n = lane & 31, hh = lane >> 5;
-    const int ub = wave / g, uj = wave - ub * g;
-    const int h = kh * g + uj;
-    const int row = 32 * ub + n;
+    // A wave's 32 columns are 32 / g rows (calls) times the g heads of the KV head, head fastest: the lanes of
+    // a wave then need the rotation rows of only 32 / g calls (for g = 8 an eighth of the table traffic of a
+    // wave that held 32 rows of one head).  The workgroup covers 8 * 32 / g rows either way.
+    const int rpw = 32 / g;
+    const int row = rpw * wave + n / g;
+    const int h = kh * g + n % g;
+    const int ub = (rpw * wave) >> 5;                   // the 32-row block of the visibility masks this wave's rows lie in
     const bool row_ok = row < gr.n_rows;
     const int Rg = gr.row0 + (row_ok ? row : 0);         // the group's calls are consecutive one-row calls
 
@@ -184,7 +188,7 @@ __global__ __launch_bounds__(512, 1) void pc_decode_shared_bf16_kernel(PcLaunch 
     bool vis = false;
     auto turn = [&](int seg, unsigned vis_word) {
         cur_seg = seg;
-        vis = row_ok && ((vis_word >> n) & 1u);
+        vis = row_ok && ((vis_word >> (row & 31)) & 1u);
         if (vis) {
             const float4 *rs = reinterpret_cast<const float4 *>(S.rot + ((int64_t)gr.rot_off + (int64_t)seg * gr.n_rows + row) * (PC_D / 2) + 8 * hh);
 #pragma unroll
