@@ -267,21 +267,22 @@ int32_t pc_set_tuning(pc_cache *c, int32_t decode_tiles_per_split, int32_t prefi
 
 /* Gradient of pc_attend for fine-tuning (Sec. 2.4: while fine-tuning, a position update is
  * applied to the keys without destroying them, so that gradients flow back through it to the
- * cached keys).  PC_F32 caches only.  For the scalar sum(out * d_out) of a pc_attend with the
- * same cache state, calls and q:
+ * cached keys).  For the scalar sum(out * d_out) of a pc_attend with the same cache state,
+ * calls and q (q and d_out in the cache dtype, like out; gradients are fp32 for both dtypes):
  *   d_q   [sum n_q][n_q_heads][head_dim] fp32, device: written, the gradient w.r.t. q;
  *   d_k, d_v [capacity slots][n_kv_heads][head_dim] fp32, device, indexed by physical slot
- *         (a message's rows start at its slot_start, see pc_message_info): ADDED to, so that
- *         the gradients of several calls and batches collect in one buffer the caller zeroed.
- * lse: the [sum n_q][n_q_heads] fp32 log-sum-exp pc_attend wrote for these calls; d_out as out.
+ *         (a message's rows start at its slot_start, see pc_message_info / pc_message_extents):
+ *         ADDED to, so that the gradients of several calls and batches collect in one buffer
+ *         the caller zeroed.
+ * lse: the [sum n_q][n_q_heads] fp32 log-sum-exp pc_attend wrote for these calls.
  * d_v is the gradient w.r.t. the appended V.  d_k collects the gradient w.r.t. the keys AS
- * STORED (turned to their stored base); once every backward call has been enqueued,
- * pc_grad_keys_finalize(d_k) turns the rows of every live message into the gradient w.r.t.
- * the K that was appended.  No message may be repositioned, freed or swapped between the first
- * backward call into a buffer and its finalize.  A functional path (one wave per row and head,
- * float atomics): not tuned. */
+ * STORED (turned to their stored base; in a PC_BF16 cache also rounded once more); once every
+ * backward call has been enqueued, pc_grad_keys_finalize(d_k) turns the rows of every live
+ * message into the gradient w.r.t. the K that was appended.  No message may be repositioned,
+ * freed or swapped between the first backward call into a buffer and its finalize.  A
+ * functional path (fp32 arithmetic, one wave per row and head, float atomics): not tuned. */
 int32_t pc_attend_backward(pc_cache *c, const pc_call *calls, int32_t n_calls, const void *q, const float *lse,
-                           const void *d_out, void *d_q, float *d_k, float *d_v, void *stream);
+                           const void *d_out, float *d_q, float *d_k, float *d_v, void *stream);
 int32_t pc_grad_keys_finalize(pc_cache *c, float *d_k, void *stream);
 
 /* Shared decode (Sec. 2.4 "Parallel decoding": parallel calls read the same cached

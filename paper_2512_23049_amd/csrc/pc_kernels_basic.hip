@@ -721,7 +721,7 @@ void pc_launch_attend_f32(const PcLaunch &L, const int32_t *row_call, int total_
 }
 
 // ----------------------------------------------------------------------------------
-// Gradient of the fp32 attention (Sec. 2.4: in fine-tuning a position update is applied
+// Gradient of the attention, for both cache dtypes, in fp32 arithmetic (Sec. 2.4: in fine-tuning a position update is applied
 // non-destructively, so gradients flow through it to the cached keys).  One wave per
 // (query row, head), keys lane-strided as in the forward kernel.  With p_j = exp(s_j - LSE)
 // from the forward's LSE and dp_j = dO . v_j:
@@ -734,11 +734,22 @@ void pc_launch_attend_f32(const PcLaunch &L, const int32_t *row_call, int total_
 // different rows and heads meet in d_k, d_v through float atomics.
 // A plain kernel: this path is not a hot one.
 // ----------------------------------------------------------------------------------
-template <int D>
-__global__ __launch_bounds__(64) void pc_attend_bwd_f32_kernel(PcLaunch L, const int32_t *__restrict__ row_call,
-                                                               const float *__restrict__ lse, const float *__restrict__ d_out,
-                                                               float scale, float *__restrict__ d_q,
-                                                               float *__restrict__ d_k, float *__restrict__ d_v)
+// element access for the two cache dtypes: fp32 as it is, bf16 widened; V of a bf16 cache is stored
+// key-transposed in groups of 8 slots
+template <typename T> __device__ __forceinline__ float bwd_ld(const T *p);
+template <> __device__ __forceinline__ float bwd_ld<float>(const float *p) { return *p; }
+template <> __device__ __forceinline__ float bwd_ld<uint16_t>(const uint16_t *p) { return __uint_as_float((uint32_t)*p << 16); }
+template <typename T> __device__ __forceinline__ float bwd_v(const T *vbase, int64_t slot, int d, int D)
+{
+    if constexpr (sizeof(T) == 2) return bwd_ld(vbase + ((slot / PC_VGROUP) * D + d) * PC_VGROUP + (slot % PC_VGROUP));
+    else return vbase[slot * D + d];
+}
+
+template <int D, typename T>
+__global__ __launch_bounds__(64) void pc_attend_bwd_kernel(PcLaunch L, const int32_t *__restrict__ row_call,
+                                                           const float *__restrict__ lse, const T *__restrict__ d_out,
+                                                           float scale, float *__restrict__ d_q,
+                                                           float *__restrict__ d_k, float *__restrict__ d_v)
 {
     constexpr int HALF = D / 2;
     __shared__ float s_qhat[D], s_qe[D], s_do[D], s_dqhat[D];
@@ -749,14 +760,14 @@ __global__ __launch_bounds__(64) void pc_attend_bwd_f32_kernel(PcLaunch L, const
     const int g = L.n_q_heads / L.n_kv_heads;
     const int kh = h / g;
     const int64_t rh = (int64_t)R * L.n_q_heads + h;
-    const float *q = (const float *)L.q + rh * D;
+    const T *q = (const T *)L.q + rh * D;
     for (int i = lane; i < HALF; i += 64) {
         const float2 cs = L.rot_q[(int64_t)R * HALF + i];
-        const float a = q[i], b = q[i + HALF];
+        const float a = bwd_ld(q + i), b = bwd_ld(q + i + HALF);
         s_qhat[i] = a * cs.x - b * cs.y;
         s_qhat[i + HALF] = a * cs.y + b * cs.x;
     }
-    for (int d = lane; d < D; d += 64) { s_do[d] = d_out[rh * D + d]; s_dqhat[d] = 0.f; }
+    for (int d = lane; d < D; d += 64) { s_do[d] = bwd_ld(d_out + rh * D + d); s_dqhat[d] = 0.f; }
     const float row_lse = lse[rh];
     float *dq = d_q + rh * D;
     if (!(row_lse > -INFINITY)) {                          // the row saw nothing: no gradient anywhere
@@ -764,8 +775,8 @@ __global__ __launch_bounds__(64) void pc_attend_bwd_f32_kernel(PcLaunch L, const
         return;
     }
     __syncthreads();
-    const float *kbase = (const float *)L.k_store + (int64_t)kh * L.slots * D;
-    const float *vbase = (const float *)L.v_store + (int64_t)kh * L.slots * D;
+    const T *kbase = (const T *)L.k_store + (int64_t)kh * L.slots * D;
+    const T *vbase = (const T *)L.v_store + (int64_t)kh * L.slots * D;
     auto visible = [&](const PcSegment &sg, int e) {
         int n_vis = sg.len;
         if (cd.self_msg >= 0 && e == cd.n_seg - 1) {
@@ -792,11 +803,11 @@ __global__ __launch_bounds__(64) void pc_attend_bwd_f32_kernel(PcLaunch L, const
         if (n_vis <= 0) continue;
         turn(e);
         for (int t = lane; t < n_vis; t += 64) {
-            const float *kr = kbase + (int64_t)(sg.slot_start + t) * D;
-            const float *vr = vbase + (int64_t)(sg.slot_start + t) * D;
+            const int64_t slot = sg.slot_start + t;
+            const T *kr = kbase + slot * D;
             float s = 0.f, dp = 0.f;
 #pragma unroll 8
-            for (int d = 0; d < D; ++d) { s = fmaf(s_qe[d], kr[d], s); dp = fmaf(s_do[d], vr[d], dp); }
+            for (int d = 0; d < D; ++d) { s = fmaf(s_qe[d], bwd_ld(kr + d), s); dp = fmaf(s_do[d], bwd_v(vbase, slot, d, D), dp); }
             delta += expf(s * scale - row_lse) * dp;
         }
     }
@@ -812,18 +823,17 @@ __global__ __launch_bounds__(64) void pc_attend_bwd_f32_kernel(PcLaunch L, const
         for (int d = 0; d < D; ++d) dqe[d] = 0.f;
         for (int t = lane; t < n_vis; t += 64) {
             const int64_t slot = sg.slot_start + t;
-            const float *kr = kbase + slot * D;
-            const float *vr = vbase + slot * D;
+            const T *kr = kbase + slot * D;
             float s = 0.f, dp = 0.f;
 #pragma unroll 8
-            for (int d = 0; d < D; ++d) { s = fmaf(s_qe[d], kr[d], s); dp = fmaf(s_do[d], vr[d], dp); }
+            for (int d = 0; d < D; ++d) { s = fmaf(s_qe[d], bwd_ld(kr + d), s); dp = fmaf(s_do[d], bwd_v(vbase, slot, d, D), dp); }
             const float p = expf(s * scale - row_lse);
             const float ds = p * (dp - delta) * scale;
             float *gk = d_k + (slot * L.n_kv_heads + kh) * D;
             float *gv = d_v + (slot * L.n_kv_heads + kh) * D;
 #pragma unroll 8
             for (int d = 0; d < D; ++d) {
-                dqe[d] = fmaf(ds, kr[d], dqe[d]);
+                dqe[d] = fmaf(ds, bwd_ld(kr + d), dqe[d]);
                 atomicAdd(gk + d, ds * s_qe[d]);
                 atomicAdd(gv + d, p * s_do[d]);
             }
@@ -850,13 +860,20 @@ __global__ __launch_bounds__(64) void pc_attend_bwd_f32_kernel(PcLaunch L, const
     }
 }
 
-void pc_launch_attend_bwd_f32(const PcLaunch &L, const int32_t *row_call, int total_q, int D, const float *lse,
-                              const float *d_out, float scale, float *d_q, float *d_k, float *d_v, hipStream_t st)
+void pc_launch_attend_bwd(int dtype, const PcLaunch &L, const int32_t *row_call, int total_q, int D, const float *lse,
+                          const void *d_out, float scale, float *d_q, float *d_k, float *d_v, hipStream_t st)
 {
     if (total_q <= 0) return;
     dim3 grid(total_q, L.n_q_heads);
-    if (D == 64) pc_attend_bwd_f32_kernel<64><<<grid, 64, 0, st>>>(L, row_call, lse, d_out, scale, d_q, d_k, d_v);
-    else pc_attend_bwd_f32_kernel<128><<<grid, 64, 0, st>>>(L, row_call, lse, d_out, scale, d_q, d_k, d_v);
+    if (dtype == 1) {
+        const uint16_t *go = (const uint16_t *)d_out;
+        if (D == 64) pc_attend_bwd_kernel<64, uint16_t><<<grid, 64, 0, st>>>(L, row_call, lse, go, scale, d_q, d_k, d_v);
+        else pc_attend_bwd_kernel<128, uint16_t><<<grid, 64, 0, st>>>(L, row_call, lse, go, scale, d_q, d_k, d_v);
+    } else {
+        const float *go = (const float *)d_out;
+        if (D == 64) pc_attend_bwd_kernel<64, float><<<grid, 64, 0, st>>>(L, row_call, lse, go, scale, d_q, d_k, d_v);
+        else pc_attend_bwd_kernel<128, float><<<grid, 64, 0, st>>>(L, row_call, lse, go, scale, d_q, d_k, d_v);
+    }
 }
 
 // d_k holds the gradient with respect to the stored keys K~_t = R(base + t) k_t; the gradient with

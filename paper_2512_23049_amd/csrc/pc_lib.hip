@@ -1263,10 +1263,9 @@ int32_t pc_attend(pc_cache *c, const pc_call *calls, int32_t n_calls, const void
 }
 
 int32_t pc_attend_backward(pc_cache *c, const pc_call *calls, int32_t n_calls, const void *q, const float *lse,
-                           const void *d_out, void *d_q, float *d_k, float *d_v, void *stream)
+                           const void *d_out, float *d_q, float *d_k, float *d_v, void *stream)
 {
     if (!c) return PC_ERR_INVALID_ARG;
-    if (c->cfg.dtype != PC_F32) return fail(c, PC_ERR_INVALID_ARG, "attend_backward: needs a PC_F32 cache");
     if (n_calls < 0 || (n_calls > 0 && !calls)) return fail(c, PC_ERR_INVALID_ARG, "attend_backward: bad call list");
     if (n_calls == 0) return PC_OK;
     if (!c->host_only && (!q || !lse || !d_out || !d_q || !d_k || !d_v))
@@ -1285,8 +1284,8 @@ int32_t pc_attend_backward(pc_cache *c, const pc_call *calls, int32_t n_calls, c
     L.slots = c->slots; L.n_q_heads = c->cfg.n_q_heads; L.n_kv_heads = c->cfg.n_kv_heads;
     L.scale_log2 = c->scale * 1.4426950408889634f;
     ProfScope ps(c, 5, st);
-    pc_launch_attend_bwd_f32(L, (const int32_t *)(w + P.lay.row_call), P.total_q, c->D, lse, (const float *)d_out, c->scale,
-                             (float *)d_q, d_k, d_v, st);
+    pc_launch_attend_bwd(c->cfg.dtype, L, (const int32_t *)(w + P.lay.row_call), P.total_q, c->D, lse, d_out, c->scale,
+                         (float *)d_q, d_k, d_v, st);
     PC_HIP(c, hipGetLastError());
     return PC_OK;
 }
@@ -1294,7 +1293,6 @@ int32_t pc_attend_backward(pc_cache *c, const pc_call *calls, int32_t n_calls, c
 int32_t pc_grad_keys_finalize(pc_cache *c, float *d_k, void *stream)
 {
     if (!c) return PC_ERR_INVALID_ARG;
-    if (c->cfg.dtype != PC_F32) return fail(c, PC_ERR_INVALID_ARG, "grad_keys_finalize: needs a PC_F32 cache");
     if (c->host_only) return PC_OK;
     if (!d_k) return fail(c, PC_ERR_INVALID_ARG, "grad_keys_finalize: null d_k");
     std::vector<PcMsgEntry> live;
