@@ -162,7 +162,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--skip-extras", action="store_true")
     ap.add_argument("--skip-cpu", action="store_true")
-    ap.add_argument("--only", default="", help="comma list of sections: decode,long,longdecode,rounds,baseline,loop,reposition")
+    ap.add_argument("--only", default="", help="comma list of sections: decode,long,longdecode,rounds,baseline,loop,reposition,backward")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="also launch one plain device copy of this many MiB (reference for scaling rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE counters)")
@@ -460,6 +460,38 @@ def main():
         }
         cache.close()
         del w5
+
+    # ------------------------------------------------ gradient path (functional, untuned): a small shape
+    if not args.skip_extras and (not only or "backward" in only):
+        wb = gen.single_prefill(n_msgs=24, len_lo=40, len_hi=300, n_sel=6, n_new=200)
+        cache = harness.make_cache(wb)
+        dw = harness.DeviceWorkload(wb)
+        dw.run(cache)
+        torch.cuda.synchronize()
+        att = [s_ for s_ in dw.steps if s_[0] == "attend"][-1]
+        _, calls, mc, q, out, lse = att
+        slots = cache.cache_info()[2]
+        d_out = torch.randn(tuple(q.shape), device="cuda:0").to(q.dtype)
+        d_q = torch.empty(tuple(q.shape), dtype=torch.float32, device="cuda:0")
+        d_k = torch.zeros((slots, wb.n_kv_heads, wb.head_dim), dtype=torch.float32, device="cuda:0")
+        d_v = torch.zeros_like(d_k)
+        cache.attend(calls, q.data_ptr(), out.data_ptr(), lse.data_ptr(), 0, mc)
+
+        def bwd():
+            cache.attend_backward(calls, q.data_ptr(), lse.data_ptr(), d_out.data_ptr(), d_q.data_ptr(), d_k.data_ptr(),
+                                  d_v.data_ptr())
+            cache.grad_keys_finalize(d_k.data_ptr())
+        t_b = time_steps(bwd, max(3, min(args.steps, 20)), 2, torch)
+        pairs_b = sum(v[3] for v in visible_pairs(wb, wb.events[-1]))
+        line.setdefault("extras", {})["backward"] = {
+            "workload": "scaled single prefill (200 causal rows over 6 parents of 40-300 tokens + the new message, 32/8 heads, "
+                        "bf16 cache): pc_attend_backward + pc_grad_keys_finalize; a functional path (fp32 arithmetic, one wave "
+                        "per row and head, float atomics), not tuned",
+            "ms_per_call": t_b * 1e3,
+            "gflops": 2.5 * 4.0 * wb.head_dim * wb.n_q_heads * pairs_b / t_b / 1e9,
+        }
+        cache.close()
+        del wb
 
     line["context"] = ("paper reports whole-workflow ratios only: 2.0-6.2x faster time-to-first-token and up to 2.2x "
                        "end-to-end vs prefix caching (Llama-3.1-8B; one A100-80GB is the only GPU the paper names); "
