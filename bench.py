@@ -485,8 +485,8 @@ def main():
         pairs_b = sum(v[3] for v in visible_pairs(wb, wb.events[-1]))
         line.setdefault("extras", {})["backward"] = {
             "workload": "scaled single prefill (200 causal rows over 6 parents of 40-300 tokens + the new message, 32/8 heads, "
-                        "bf16 cache): pc_attend_backward + pc_grad_keys_finalize; a functional path (fp32 arithmetic, one wave "
-                        "per row and head, float atomics), not tuned",
+                        "bf16 cache): pc_attend_backward + pc_grad_keys_finalize; a functional path (plain fp32 vector "
+                        "kernels, no matrix cores), not tuned",
             "ms_per_call": t_b * 1e3,
             "gflops": 2.5 * 4.0 * wb.head_dim * wb.n_q_heads * pairs_b / t_b / 1e9,
         }

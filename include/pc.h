@@ -280,7 +280,7 @@ int32_t pc_set_tuning(pc_cache *c, int32_t decode_tiles_per_split, int32_t prefi
  * backward call has been enqueued, pc_grad_keys_finalize(d_k) turns the rows of every live
  * message into the gradient w.r.t. the K that was appended.  No message may be repositioned,
  * freed or swapped between the first backward call into a buffer and its finalize.  A
- * functional path (fp32 arithmetic, one wave per row and head, float atomics): not tuned. */
+ * functional path (plain fp32 vector kernels, no matrix cores): not tuned. */
 int32_t pc_attend_backward(pc_cache *c, const pc_call *calls, int32_t n_calls, const void *q, const float *lse,
                            const void *d_out, float *d_q, float *d_k, float *d_v, void *stream);
 int32_t pc_grad_keys_finalize(pc_cache *c, float *d_k, void *stream);

@@ -42,8 +42,9 @@ void pc_launch_attend_f32(const PcLaunch &L, const int32_t *row_call, int total_
 
 // gradient of the attention (dtype of q, d_out and the cache: 0 fp32, 1 bf16; gradients fp32); d_k collects the
 // gradient w.r.t. the stored keys until the finalize pass
-void pc_launch_attend_bwd(int dtype, const PcLaunch &L, const int32_t *row_call, int total_q, int D, const float *lse,
-                          const void *d_out, float scale, float *d_q, float *d_k, float *d_v, hipStream_t st);
+void pc_launch_attend_bwd(int dtype, const PcLaunch &L, const int32_t *row_call, int n_calls, int total_q, int total_seg,
+                          int max_seg_len, int D, const float *lse, const void *d_out, float scale, float *delta,
+                          float *d_q, float *d_k, float *d_v, hipStream_t st);
 void pc_launch_grad_keys_finalize(const PcMsgEntry *msgs, int n_msgs, int n_kv_heads, int D, const double *inv_freq,
                                   float *d_k, hipStream_t st);
 

@@ -730,9 +730,9 @@ void pc_launch_attend_f32(const PcLaunch &L, const int32_t *row_call, int total_
 // where K~ is the stored key (turned to base + t) and qe the query turned for the segment;
 // dqe is turned back per segment and once more by the row's own position at the end.
 // d_k collects the gradient with respect to the STORED keys (pc_grad_keys_finalize turns
-// it into the gradient with respect to the keys as they were appended); contributions of
-// different rows and heads meet in d_k, d_v through float atomics.
-// A plain kernel: this path is not a hot one.
+// it into the gradient with respect to the keys as they were appended).  Two kernels: this one, row-major,
+// gives Delta and the gradient of the query; the key-major one below gives those of the keys and values.
+// Plain fp32 vector code: this path is not a hot one.
 // ----------------------------------------------------------------------------------
 // element access for the two cache dtypes: fp32 as it is, bf16 widened; V of a bf16 cache is stored
 // key-transposed in groups of 8 slots
@@ -749,7 +749,7 @@ template <int D, typename T>
 __global__ __launch_bounds__(64) void pc_attend_bwd_kernel(PcLaunch L, const int32_t *__restrict__ row_call,
                                                            const float *__restrict__ lse, const T *__restrict__ d_out,
                                                            float scale, float *__restrict__ d_q,
-                                                           float *__restrict__ d_k, float *__restrict__ d_v)
+                                                           float *__restrict__ delta_out)
 {
     constexpr int HALF = D / 2;
     __shared__ float s_qhat[D], s_qe[D], s_do[D], s_dqhat[D];
@@ -772,6 +772,7 @@ __global__ __launch_bounds__(64) void pc_attend_bwd_kernel(PcLaunch L, const int
     float *dq = d_q + rh * D;
     if (!(row_lse > -INFINITY)) {                          // the row saw nothing: no gradient anywhere
         for (int d = lane; d < D; d += 64) dq[d] = 0.f;
+        if (lane == 0) delta_out[rh] = 0.f;
         return;
     }
     __syncthreads();
@@ -812,7 +813,8 @@ __global__ __launch_bounds__(64) void pc_attend_bwd_kernel(PcLaunch L, const int
         }
     }
     for (int off = 32; off > 0; off >>= 1) delta += __shfl_xor(delta, off);
-    // pass 2: the gradients
+    if (lane == 0) delta_out[rh] = delta;                  // the key-major kernel needs it too
+    // pass 2: the gradient of the query
     for (int e = 0; e < cd.n_seg; ++e) {
         const PcSegment sg = L.segs[cd.seg_off + e];
         const int n_vis = visible(sg, e);
@@ -829,14 +831,8 @@ __global__ __launch_bounds__(64) void pc_attend_bwd_kernel(PcLaunch L, const int
             for (int d = 0; d < D; ++d) { s = fmaf(s_qe[d], bwd_ld(kr + d), s); dp = fmaf(s_do[d], bwd_v(vbase, slot, d, D), dp); }
             const float p = expf(s * scale - row_lse);
             const float ds = p * (dp - delta) * scale;
-            float *gk = d_k + (slot * L.n_kv_heads + kh) * D;
-            float *gv = d_v + (slot * L.n_kv_heads + kh) * D;
 #pragma unroll 8
-            for (int d = 0; d < D; ++d) {
-                dqe[d] = fmaf(ds, bwd_ld(kr + d), dqe[d]);
-                atomicAdd(gk + d, ds * s_qe[d]);
-                atomicAdd(gv + d, p * s_do[d]);
-            }
+            for (int d = 0; d < D; ++d) dqe[d] = fmaf(ds, bwd_ld(kr + d), dqe[d]);
         }
         // sum the lanes' dqe, turn it back by +(start - base), add to the gradient of the position-turned query
         __syncthreads();
@@ -860,19 +856,110 @@ __global__ __launch_bounds__(64) void pc_attend_bwd_kernel(PcLaunch L, const int
     }
 }
 
-void pc_launch_attend_bwd(int dtype, const PcLaunch &L, const int32_t *row_call, int total_q, int D, const float *lse,
-                          const void *d_out, float scale, float *d_q, float *d_k, float *d_v, hipStream_t st)
+// Key-major half of the gradient: a block owns 16 tokens of one gathered segment (one placement of a message
+// in one call) and one KV head, four lanes per token with D/4 dims each, and walks the call's query rows and
+// the g heads of the group: the sums over rows and heads stay in registers, and a token's gradient meets
+// those of its other placements (other calls, repeated listings) in d_k, d_v through one float atomic per
+// element at the end.
+template <int D, typename T>
+__global__ __launch_bounds__(64) void pc_attend_bwd_kv_kernel(PcLaunch L, int n_calls, const float *__restrict__ lse,
+                                                              const T *__restrict__ d_out, const float *__restrict__ delta,
+                                                              float scale, float *__restrict__ d_k, float *__restrict__ d_v)
+{
+    constexpr int HALF = D / 2, Q = D / 4;
+    __shared__ float s_qe[D], s_do[D];
+    const int seg = blockIdx.x, chunk = blockIdx.y, kh = blockIdx.z, tid = threadIdx.x;   // (segments on x: no 65535 limit)
+    // the call that owns this segment (segments are laid out call by call)
+    int lo = 0, hi = n_calls - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (L.calls[mid].seg_off <= seg) lo = mid; else hi = mid - 1;
+    }
+    const PcCallDesc cd = L.calls[lo];
+    const int e = seg - cd.seg_off;
+    if (e >= cd.n_seg) return;                             // (a call without segments in front of this index)
+    const PcSegment sg = L.segs[seg];
+    const int t = chunk * 16 + (tid >> 2), part = tid & 3;
+    if (chunk * 16 >= sg.len) return;
+    const bool t_ok = t < sg.len;
+    const bool is_self = cd.self_msg >= 0 && e == cd.n_seg - 1;
+    const int g = L.n_q_heads / L.n_kv_heads;
+    const int64_t slot = sg.slot_start + (t_ok ? t : 0);
+    const T *kbase = (const T *)L.k_store + (int64_t)kh * L.slots * D;
+    const T *vbase = (const T *)L.v_store + (int64_t)kh * L.slots * D;
+    float kq[Q], vq[Q], dk[Q], dv[Q];
+#pragma unroll
+    for (int d = 0; d < Q; ++d) {
+        kq[d] = bwd_ld(kbase + slot * D + part * Q + d);
+        vq[d] = bwd_v(vbase, slot, part * Q + d, D);
+        dk[d] = 0.f; dv[d] = 0.f;
+    }
+    // rows that can see this block's tokens at all: in the new message a row sees tokens up to its own
+    const int r_first = is_self ? max(0, chunk * 16 - (cd.self_len - cd.n_q)) : 0;
+    for (int r = r_first; r < cd.n_q; ++r) {
+        const int R = cd.q_off + r;
+        const int n_vis = is_self ? min(sg.len, cd.self_len - cd.n_q + r + 1) : sg.len;
+        for (int j = 0; j < g; ++j) {
+            const int h = kh * g + j;
+            const int64_t rh = (int64_t)R * L.n_q_heads + h;
+            __syncthreads();
+            if (tid < HALF) {                              // the query of (row, head) turned for this segment
+                const T *q = (const T *)L.q + rh * D;
+                const float2 cq = L.rot_q[(int64_t)R * HALF + tid];
+                const float a = bwd_ld(q + tid), b = bwd_ld(q + tid + HALF);
+                const float qa = a * cq.x - b * cq.y, qb = a * cq.y + b * cq.x;
+                const float2 cs = L.rot_seg[(int64_t)seg * HALF + tid];
+                s_qe[tid] = qa * cs.x + qb * cs.y;
+                s_qe[tid + HALF] = -qa * cs.y + qb * cs.x;
+            }
+            for (int d = tid; d < D; d += 64) s_do[d] = bwd_ld(d_out + rh * D + d);
+            __syncthreads();
+            const float row_lse = lse[rh];
+            if (!(row_lse > -INFINITY)) continue;          // (uniform over the block)
+            float sp = 0.f, dpp = 0.f;
+#pragma unroll
+            for (int d = 0; d < Q; ++d) { sp = fmaf(s_qe[part * Q + d], kq[d], sp); dpp = fmaf(s_do[part * Q + d], vq[d], dpp); }
+            sp += __shfl_xor(sp, 1); sp += __shfl_xor(sp, 2);
+            dpp += __shfl_xor(dpp, 1); dpp += __shfl_xor(dpp, 2);
+            const float p = (t < n_vis) ? expf(sp * scale - row_lse) : 0.f;
+            const float ds = p * (dpp - delta[rh]) * scale;
+#pragma unroll
+            for (int d = 0; d < Q; ++d) { dk[d] = fmaf(ds, s_qe[part * Q + d], dk[d]); dv[d] = fmaf(p, s_do[part * Q + d], dv[d]); }
+        }
+    }
+    if (!t_ok) return;
+    float *gk = d_k + (slot * L.n_kv_heads + kh) * D + part * Q;
+    float *gv = d_v + (slot * L.n_kv_heads + kh) * D + part * Q;
+#pragma unroll
+    for (int d = 0; d < Q; ++d) { atomicAdd(gk + d, dk[d]); atomicAdd(gv + d, dv[d]); }
+}
+
+void pc_launch_attend_bwd(int dtype, const PcLaunch &L, const int32_t *row_call, int n_calls, int total_q, int total_seg,
+                          int max_seg_len, int D, const float *lse, const void *d_out, float scale, float *delta,
+                          float *d_q, float *d_k, float *d_v, hipStream_t st)
 {
     if (total_q <= 0) return;
     dim3 grid(total_q, L.n_q_heads);
+    dim3 grid_kv((unsigned)total_seg, (unsigned)((max_seg_len + 15) / 16), (unsigned)L.n_kv_heads);
+    const bool kv = total_seg > 0 && max_seg_len > 0;
     if (dtype == 1) {
         const uint16_t *go = (const uint16_t *)d_out;
-        if (D == 64) pc_attend_bwd_kernel<64, uint16_t><<<grid, 64, 0, st>>>(L, row_call, lse, go, scale, d_q, d_k, d_v);
-        else pc_attend_bwd_kernel<128, uint16_t><<<grid, 64, 0, st>>>(L, row_call, lse, go, scale, d_q, d_k, d_v);
+        if (D == 64) {
+            pc_attend_bwd_kernel<64, uint16_t><<<grid, 64, 0, st>>>(L, row_call, lse, go, scale, d_q, delta);
+            if (kv) pc_attend_bwd_kv_kernel<64, uint16_t><<<grid_kv, 64, 0, st>>>(L, n_calls, lse, go, delta, scale, d_k, d_v);
+        } else {
+            pc_attend_bwd_kernel<128, uint16_t><<<grid, 64, 0, st>>>(L, row_call, lse, go, scale, d_q, delta);
+            if (kv) pc_attend_bwd_kv_kernel<128, uint16_t><<<grid_kv, 64, 0, st>>>(L, n_calls, lse, go, delta, scale, d_k, d_v);
+        }
     } else {
         const float *go = (const float *)d_out;
-        if (D == 64) pc_attend_bwd_kernel<64, float><<<grid, 64, 0, st>>>(L, row_call, lse, go, scale, d_q, d_k, d_v);
-        else pc_attend_bwd_kernel<128, float><<<grid, 64, 0, st>>>(L, row_call, lse, go, scale, d_q, d_k, d_v);
+        if (D == 64) {
+            pc_attend_bwd_kernel<64, float><<<grid, 64, 0, st>>>(L, row_call, lse, go, scale, d_q, delta);
+            if (kv) pc_attend_bwd_kv_kernel<64, float><<<grid_kv, 64, 0, st>>>(L, n_calls, lse, go, delta, scale, d_k, d_v);
+        } else {
+            pc_attend_bwd_kernel<128, float><<<grid, 64, 0, st>>>(L, row_call, lse, go, scale, d_q, delta);
+            if (kv) pc_attend_bwd_kv_kernel<128, float><<<grid_kv, 64, 0, st>>>(L, n_calls, lse, go, delta, scale, d_k, d_v);
+        }
     }
 }
 

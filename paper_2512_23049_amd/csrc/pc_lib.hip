@@ -250,7 +250,7 @@ int32_t stage_acquire(pc_cache *c, size_t bytes, StageSlot **out)
 // layout of the staged (host -> device) block and of the device-built block
 struct PlanLayout {
     size_t calls, sel, q_pos, row_call, merge_rows, items_dec, items_pre, sh_groups, sh_segs, sh_items, sh_pos, h2d_bytes;
-    size_t segs, seg_kvoff, rot_seg, rot_q, tiles, sh_rot, part_o, part_ml, total;
+    size_t segs, seg_kvoff, rot_seg, rot_q, tiles, sh_rot, part_o, part_ml, row_scalar, total;
 };
 
 PlanLayout make_layout(int n_calls, int total_sel, int total_q, int total_seg, int n_dec, int n_pre,
@@ -280,6 +280,7 @@ PlanLayout make_layout(int n_calls, int total_sel, int total_q, int total_seg, i
     L.sh_rot = take(sizeof(float2) * std::max<size_t>(n_sh_pos, 1) * (D / 2));
     L.part_o = take(sizeof(uint16_t) * (size_t)std::max<int64_t>(part_rows, 1) * H_q * D);
     L.part_ml = take(sizeof(float) * (size_t)std::max<int64_t>(part_rows, 1) * H_q * 2);
+    L.row_scalar = take(sizeof(float) * (size_t)std::max(total_q, 1) * H_q);      // one float per (row, head): the gradient path's Delta
     L.total = o;
     return L;
 }
@@ -1284,8 +1285,15 @@ int32_t pc_attend_backward(pc_cache *c, const pc_call *calls, int32_t n_calls, c
     L.slots = c->slots; L.n_q_heads = c->cfg.n_q_heads; L.n_kv_heads = c->cfg.n_kv_heads;
     L.scale_log2 = c->scale * 1.4426950408889634f;
     ProfScope ps(c, 5, st);
-    pc_launch_attend_bwd(c->cfg.dtype, L, (const int32_t *)(w + P.lay.row_call), P.total_q, c->D, lse, d_out, c->scale,
-                         (float *)d_q, d_k, d_v, st);
+    int max_seg_len = 0;
+    for (const Resolved &r : P.res) {
+        for (const int2 &e : r.sel) max_seg_len = std::max(max_seg_len, c->msgs[(size_t)e.x].len);
+        max_seg_len = std::max(max_seg_len, r.self_len);
+    }
+    if ((max_seg_len + 15) / 16 > 65535) return fail(c, PC_ERR_SHAPE, "attend_backward: a message of %d tokens is too long", max_seg_len);
+    L.calls = (const PcCallDesc *)(w + P.lay.calls);
+    pc_launch_attend_bwd(c->cfg.dtype, L, (const int32_t *)(w + P.lay.row_call), n_calls, P.total_q, P.total_seg, max_seg_len, c->D,
+                         lse, d_out, c->scale, (float *)(w + P.lay.row_scalar), d_q, d_k, d_v, st);
     PC_HIP(c, hipGetLastError());
     return PC_OK;
 }

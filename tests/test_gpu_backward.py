@@ -125,3 +125,64 @@ def test_backward_small_random_bf16(hip, seed, hq, hkv):
 
 def test_backward_bf16_scaled_prefill_shape(hip):
     run_backward_case(hip, gen.single_prefill(n_msgs=10, len_lo=20, len_hi=90, n_sel=5, n_new=48))
+
+
+def test_backward_through_a_message_of_several_extents(hip):
+    """The gradient of a message that lives in several spans (PC_FLAG_GROW_EXTENTS) and was moved: its rows of
+    d_k, d_v are those of its extents, in token order."""
+    import torch
+    from oracle import choreo_oracle as orc
+    from paper_2512_23049_amd.binding import PC_F32, PC_FLAG_GROW_EXTENTS, Cache
+    rng = np.random.default_rng(7)
+    H_q, H_kv, D = 4, 2, 64
+    cache = Cache(H_q, H_kv, D, PC_F32, 10000.0, 2048, 32, flags=PC_FLAG_GROW_EXTENTS)
+    keep = []
+
+    def dev(x):
+        t = hip.to_device(x, "f32"); keep.append(t); return t
+    lens = [3 + 45, 20, 12]
+    ks = [rng.standard_normal((L, H_kv, D)).astype(np.float32) for L in lens]
+    vs = [rng.standard_normal((L, H_kv, D)).astype(np.float32) for L in lens]
+    a = cache.append_message(dev(ks[0][:3]).data_ptr(), dev(vs[0][:3]).data_ptr(), 3, 0)
+    b = cache.append_message(dev(ks[1]).data_ptr(), dev(vs[1]).data_ptr(), 20, 0)
+    cache.append_tokens(a, dev(ks[0][3:]).data_ptr(), dev(vs[0][3:]).data_ptr(), 45)       # a second extent behind b
+    new = cache.append_message(dev(ks[2]).data_ptr(), dev(vs[2]).data_ptr(), 12, 0)
+    assert len(cache.message_extents(a)) == 2
+    cache.reposition(a, 200)
+    ids = {a: 0, b: 1, new: 2}
+    assert sorted(ids) == [a, b, new]
+    calls = [Call([(b, 0), (a, 30)], new, 100, 12, None), Call([(a, 200)], -1, 0, 2, np.asarray([260, 300], dtype=np.int32))]
+    n_rows = 14
+    q = rng.standard_normal((n_rows, H_q, D)).astype(np.float32)
+    d_out = rng.standard_normal((n_rows, H_q, D)).astype(np.float32)
+    qd, dod = dev(q), dev(d_out)
+    out = torch.empty_like(qd); lse = torch.empty((n_rows, H_q), dtype=torch.float32, device="cuda:0")
+    cache.attend(calls, qd.data_ptr(), out.data_ptr(), lse.data_ptr())
+    slots = cache.cache_info()[2]
+    d_q = torch.empty_like(qd)
+    d_k = torch.zeros((slots, H_kv, D), dtype=torch.float32, device="cuda:0"); d_v = torch.zeros_like(d_k)
+    cache.attend_backward(calls, qd.data_ptr(), lse.data_ptr(), dod.data_ptr(), d_q.data_ptr(), d_k.data_ptr(), d_v.data_ptr())
+    cache.grad_keys_finalize(d_k.data_ptr())
+    torch.cuda.synchronize()
+    # the oracle numbers messages 0, 1, 2 in the order a, b, new
+    kl, vl = [None] * 3, [None] * 3
+    for m, i in ids.items():
+        kl[i], vl[i] = ks[i], vs[i]
+    remap = lambda sel: [(ids[m], s) for m, s in sel]
+    want_k = [np.zeros(k.shape) for k in kl]; want_v = [np.zeros(v.shape) for v in vl]
+    want_q = np.zeros((n_rows, H_q, D)); at = 0
+    for c in calls:
+        gq, gk, gv = orc.attend_call_backward(kl, vl, remap(c.sel), ids.get(c.self_msg, -1), c.self_start, c.n_q, c.q_pos,
+                                              q[at:at + c.n_q], d_out[at:at + c.n_q], 10000.0)
+        want_q[at:at + c.n_q] = gq
+        for i in range(3):
+            want_k[i] += gk[i]; want_v[i] += gv[i]
+        at += c.n_q
+    gk_d, gv_d = d_k.cpu().numpy(), d_v.cpu().numpy()
+    worst = np.abs(d_q.cpu().numpy() - want_q).max()
+    for m, i in ids.items():
+        rows = np.concatenate([np.arange(s, s + l) for s, l in cache.message_extents(m)])
+        worst = max(worst, np.abs(gk_d[rows] - want_k[i]).max(), np.abs(gv_d[rows] - want_v[i]).max())
+    say(f"  gradient through extents: worst abs error {worst:.3e}")
+    assert worst <= 2e-4
+    cache.close()
