@@ -35,6 +35,9 @@ struct PcTokenItem {
     int32_t new_len;          // the message's length once this token is in
 };
 
+#define PC_TOKEN_PACK 128     // token items that travel in a kernel's arguments (2 KB)
+struct PcTokenPack { PcTokenItem it[PC_TOKEN_PACK]; };
+
 // One message of a batched position update (staged by the host).
 struct PcMoveItem {
     int32_t msg;

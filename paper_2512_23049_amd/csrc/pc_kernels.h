@@ -18,6 +18,11 @@ void pc_launch_append_tokens(int dtype, const PcTokenItem *items, int n, const v
                              int D, int64_t slots, const double *inv_freq, void *k_store, void *v_store,
                              PcMsgEntry *table, hipStream_t st);
 
+// the same for at most PC_TOKEN_PACK items, passed in the kernel's arguments (no staging copy)
+void pc_launch_append_tokens_packed(int dtype, const PcTokenPack &pack, int n, const void *k, const void *v, int n_kv_heads,
+                                    int D, int64_t slots, const double *inv_freq, void *k_store, void *v_store,
+                                    PcMsgEntry *table, hipStream_t st);
+
 // turn the stored keys of one message by delta positions, in place
 void pc_launch_reposition(int dtype, int len, int n_kv_heads, int D, int64_t slot_start, int64_t slots, int delta,
                           int new_base, const double *inv_freq, void *k_store, PcMsgEntry *table, int msg_id,

@@ -208,18 +208,12 @@ void pc_launch_append(int dtype, const void *k, const void *v, int len, int n_kv
 // i0 = 2*m): key turned to the item's position, value written into its 8-slot group.
 // ----------------------------------------------------------------------------------
 template <typename T>
-__global__ __launch_bounds__(256) void pc_append_tokens_kernel(
-    const PcTokenItem *__restrict__ items, int n, const T *__restrict__ k, const T *__restrict__ v,
-    int n_kv_heads, int D, int64_t slots, const double *__restrict__ inv_freq,
-    T *__restrict__ k_store, T *__restrict__ v_store, PcMsgEntry *__restrict__ table)
+__device__ __forceinline__ void append_token_thread(const PcTokenItem it, int j, int h, int i0, const T *__restrict__ k,
+                                                    const T *__restrict__ v, int n_kv_heads, int D, int64_t slots,
+                                                    const double *__restrict__ inv_freq, T *__restrict__ k_store,
+                                                    T *__restrict__ v_store, PcMsgEntry *__restrict__ table)
 {
-    const int half = D / 2, per_row = half / 2;
-    const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (tid >= (int64_t)n * n_kv_heads * per_row) return;
-    const int i0 = 2 * (int)(tid % per_row);
-    const int h = (int)((tid / per_row) % n_kv_heads);
-    const int j = (int)(tid / ((int64_t)per_row * n_kv_heads));
-    const PcTokenItem it = items[j];
+    const int half = D / 2;
     if (h == 0 && i0 == 0) table[it.msg].len = it.new_len;      // every item of a message carries its final length
     double s0, c0, s1, c1;
     sincos((double)it.pos * inv_freq[i0], &s0, &c0);
@@ -249,6 +243,52 @@ __global__ __launch_bounds__(256) void pc_append_tokens_kernel(
         vdst[i0] = vsrc[i0]; vdst[i0 + 1] = vsrc[i0 + 1];
         vdst[half + i0] = vsrc[half + i0]; vdst[half + i0 + 1] = vsrc[half + i0 + 1];
     }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void pc_append_tokens_kernel(
+    const PcTokenItem *__restrict__ items, int n, const T *__restrict__ k, const T *__restrict__ v,
+    int n_kv_heads, int D, int64_t slots, const double *__restrict__ inv_freq,
+    T *__restrict__ k_store, T *__restrict__ v_store, PcMsgEntry *__restrict__ table)
+{
+    const int per_row = D / 4;
+    const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (tid >= (int64_t)n * n_kv_heads * per_row) return;
+    const int j = (int)(tid / ((int64_t)per_row * n_kv_heads));
+    append_token_thread<T>(items[j], j, (int)((tid / per_row) % n_kv_heads), 2 * (int)(tid % per_row), k, v, n_kv_heads, D, slots,
+                           inv_freq, k_store, v_store, table);
+}
+
+// The same with the items passed by value (a decode step's one token per call: up to PC_TOKEN_PACK items fit the
+// kernel's arguments, which saves staging them through pinned memory and a copy).
+template <typename T>
+__global__ __launch_bounds__(256) void pc_append_tokens_packed_kernel(
+    const PcTokenPack pack, int n, const T *__restrict__ k, const T *__restrict__ v,
+    int n_kv_heads, int D, int64_t slots, const double *__restrict__ inv_freq,
+    T *__restrict__ k_store, T *__restrict__ v_store, PcMsgEntry *__restrict__ table)
+{
+    const int per_row = D / 4;
+    const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (tid >= (int64_t)n * n_kv_heads * per_row) return;
+    const int j = (int)(tid / ((int64_t)per_row * n_kv_heads));
+    append_token_thread<T>(pack.it[j], j, (int)((tid / per_row) % n_kv_heads), 2 * (int)(tid % per_row), k, v, n_kv_heads, D, slots,
+                           inv_freq, k_store, v_store, table);
+}
+
+void pc_launch_append_tokens_packed(int dtype, const PcTokenPack &pack, int n, const void *k, const void *v, int n_kv_heads,
+                                    int D, int64_t slots, const double *inv_freq, void *k_store, void *v_store,
+                                    PcMsgEntry *table, hipStream_t st)
+{
+    const int64_t total = (int64_t)n * n_kv_heads * (D / 4);
+    const unsigned grid = (unsigned)((total + 255) / 256);
+    if (grid == 0) return;
+    if (dtype == 1)
+        pc_append_tokens_packed_kernel<uint16_t><<<grid, 256, 0, st>>>(pack, n, (const uint16_t *)k, (const uint16_t *)v, n_kv_heads,
+                                                                       D, slots, inv_freq, (uint16_t *)k_store,
+                                                                       (uint16_t *)v_store, table);
+    else
+        pc_append_tokens_packed_kernel<float><<<grid, 256, 0, st>>>(pack, n, (const float *)k, (const float *)v, n_kv_heads, D,
+                                                                    slots, inv_freq, (float *)k_store, (float *)v_store, table);
 }
 
 void pc_launch_append_tokens(int dtype, const PcTokenItem *items, int n, const void *k, const void *v, int n_kv_heads,

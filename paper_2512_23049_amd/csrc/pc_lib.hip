@@ -546,12 +546,21 @@ static int32_t append_token_items(pc_cache *c, const std::vector<int32_t> &ids, 
             PC_HIP(c, hipEventRecord(slot->ev, st));
             slot->used = true;
         }
-        const int32_t rc = stage_items(c, items.data(), sizeof(PcTokenItem) * (size_t)n, st);
-        if (rc != PC_OK) return rc;
-        ProfScope ps(c, 0, st);
-        pc_launch_append_tokens(c->cfg.dtype, (const PcTokenItem *)c->tok_dev, n, k, v, c->cfg.n_kv_heads, c->D, c->slots, c->inv_freq_dev,
-                                c->k_store, c->v_store, c->table_dev, st);
-        PC_HIP(c, hipGetLastError());
+        if (n <= PC_TOKEN_PACK) {                            // a decode step's handful of tokens rides in the kernel arguments
+            PcTokenPack pack;
+            std::memcpy(pack.it, items.data(), sizeof(PcTokenItem) * (size_t)n);
+            ProfScope ps(c, 0, st);
+            pc_launch_append_tokens_packed(c->cfg.dtype, pack, n, k, v, c->cfg.n_kv_heads, c->D, c->slots, c->inv_freq_dev,
+                                           c->k_store, c->v_store, c->table_dev, st);
+            PC_HIP(c, hipGetLastError());
+        } else {
+            const int32_t rc = stage_items(c, items.data(), sizeof(PcTokenItem) * (size_t)n, st);
+            if (rc != PC_OK) return rc;
+            ProfScope ps(c, 0, st);
+            pc_launch_append_tokens(c->cfg.dtype, (const PcTokenItem *)c->tok_dev, n, k, v, c->cfg.n_kv_heads, c->D, c->slots, c->inv_freq_dev,
+                                    c->k_store, c->v_store, c->table_dev, st);
+            PC_HIP(c, hipGetLastError());
+        }
     }
     for (const HostMsg &rec : fresh) {
         if (!c->msgs.empty() && rec.slot_start < c->msgs.back().slot_start) c->slots_in_id_order = false;
