@@ -379,3 +379,54 @@ def test_decode_result_does_not_depend_on_parent_order(hip):
         assert torch.equal(o.view(torch.int16), outs[0][0].view(torch.int16)), "listing order changed the result bits"
         assert torch.equal(l, outs[0][1])
     cache.close()
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_positions_far_from_zero(hip, dtype):
+    """Sec. 2.4 "Position Updates": only position differences matter, however large the positions.  The same calls
+    placed around +-10^7 (angles of millions of radians at the highest frequency: the rotation tables are built in
+    fp64 from integer positions) against the oracle; prefill, decode per call and decode through the shared walk."""
+    import torch
+    from oracle import choreo_oracle as orc
+    from pc_inputs import Call
+    from paper_2512_23049_amd.binding import PC_BF16, PC_F32, Cache
+    rng = np.random.default_rng(55)
+    H_q, H_kv, D = (8, 2, 128) if dtype == "bf16" else (4, 2, 64)
+    tol = TOL[dtype]
+    lens = [70, 33, 128, 40, 9]
+
+    def rnd(*shape):
+        x = rng.standard_normal(shape).astype(np.float32)
+        return gen.round_to_bf16(x) if dtype == "bf16" else x
+    ks = [rnd(L, H_kv, D) for L in lens]
+    vs = [rnd(L, H_kv, D) for L in lens]
+    cache = Cache(H_q, H_kv, D, PC_BF16 if dtype == "bf16" else PC_F32, 500000.0, 2048, 16)
+    keep = []
+    for k, v in zip(ks, vs):
+        kd, vd = hip.to_device(k, dtype), hip.to_device(v, dtype)
+        keep += [kd, vd]
+        cache.append_message(kd.data_ptr(), vd.data_ptr(), k.shape[0], 0)
+    far = 10_000_000
+    for sign in (1, -1):
+        base = sign * far
+        calls = [Call([(0, base), (2, base + 70), (1, base + 150)], 3, base + 200, 40, None),              # prefill
+                 Call([(2, base - 300), (0, base - 100)], 4, base, 1, None),                                # decode
+                 Call([(0, base - 100), (2, base - 300), (1, base - 400)], -1, 0, 1, np.asarray([base + 5], dtype=np.int32))]
+        n_rows = sum(c.n_q for c in calls)
+        q = rnd(n_rows, H_q, D)
+        qd = hip.to_device(q, dtype)
+        for mode in ((1, 2) if dtype == "bf16" else (1,)):
+            cache.set_decode_sharing(mode)
+            out = torch.empty_like(qd)
+            lse = torch.empty((n_rows, H_q), dtype=torch.float32, device="cuda:0")
+            cache.attend(calls, qd.data_ptr(), out.data_ptr(), lse.data_ptr())
+            torch.cuda.synchronize()
+            at = 0
+            for c in calls:
+                o, l = orc.attend_call(ks, vs, c.sel, c.self_msg, c.self_start, c.n_q, c.q_pos, q[at:at + c.n_q], 500000.0)
+                d = np.abs(out[at:at + c.n_q].float().cpu().numpy() - o)
+                say(f"  {dtype} base {base} mode {mode}: max_abs={d.max():.3e} mean_abs={d.mean():.3e}")
+                assert d.max() <= tol["max_abs"] and d.mean() <= tol["mean_abs"]
+                assert np.abs(lse[at:at + c.n_q].cpu().numpy() - l).max() <= tol["lse"]
+                at += c.n_q
+    cache.close()
