@@ -220,9 +220,11 @@ int32_t resolve_call(pc_cache *c, const pc_call *call, int idx, Resolved &out)
 int32_t ensure_ws(pc_cache *c, size_t bytes, hipStream_t st)
 {
     if (bytes <= c->ws_cap) return PC_OK;
-    PC_HIP(c, hipStreamSynchronize(st));
-    PC_HIP(c, hipDeviceSynchronize());
-    if (c->ws) PC_HIP(c, hipFree(c->ws));
+    if (c->ws) {                                         // work in flight may still use the old one
+        PC_HIP(c, hipStreamSynchronize(st));
+        PC_HIP(c, hipDeviceSynchronize());
+        PC_HIP(c, hipFree(c->ws));
+    }
     c->ws = nullptr; c->ws_cap = 0;
     const size_t cap = align_up(bytes + bytes / 4, 1 << 20);
     PC_HIP(c, hipMalloc(&c->ws, cap));
@@ -339,6 +341,16 @@ int32_t pc_cache_create(const pc_config *cfg, pc_cache **out)
     for (int i = 0; i < c->half; ++i) f[i] = std::pow((double)cfg->rope_theta, -2.0 * i / c->D);
     if (hipMalloc((void **)&c->inv_freq_dev, sizeof(double) * f.size()) != hipSuccess) return bail(PC_ERR_HIP);
     if (hipMemcpy(c->inv_freq_dev, f.data(), sizeof(double) * f.size(), hipMemcpyHostToDevice) != hipSuccess) return bail(PC_ERR_HIP);
+    // first buffers of a modest size, so that ordinary calls do not allocate on their way (they grow on demand)
+    if (hipMalloc(&c->ws, (size_t)32 << 20) != hipSuccess) return bail(PC_ERR_HIP);
+    c->ws_cap = (size_t)32 << 20;
+    if (hipMalloc(&c->tok_dev, (size_t)1 << 16) != hipSuccess) return bail(PC_ERR_HIP);
+    c->tok_cap = (size_t)1 << 16;
+    for (int i = 0; i < N_STAGE; ++i) {
+        if (hipHostMalloc(&c->stage[i].host, (size_t)1 << 20, hipHostMallocDefault) != hipSuccess) return bail(PC_ERR_HIP);
+        c->stage[i].cap = (size_t)1 << 20;
+        if (hipEventCreateWithFlags(&c->stage[i].ev, hipEventDisableTiming) != hipSuccess) return bail(PC_ERR_HIP);
+    }
     if (hipDeviceSynchronize() != hipSuccess) return bail(PC_ERR_HIP);
     return PC_OK;
 }
@@ -417,9 +429,11 @@ int32_t pc_append_message(pc_cache *c, const void *k, const void *v, int32_t len
 static int32_t stage_items(pc_cache *c, const void *items, size_t bytes, hipStream_t st)
 {
     if (bytes > c->tok_cap) {
-        PC_HIP(c, hipStreamSynchronize(st));
-        PC_HIP(c, hipDeviceSynchronize());
-        if (c->tok_dev) PC_HIP(c, hipFree(c->tok_dev));
+        if (c->tok_dev) {                                // work in flight may still use the old one
+            PC_HIP(c, hipStreamSynchronize(st));
+            PC_HIP(c, hipDeviceSynchronize());
+            PC_HIP(c, hipFree(c->tok_dev));
+        }
         c->tok_dev = nullptr; c->tok_cap = 0;
         const size_t cap = std::max<size_t>(1 << 16, bytes * 2);
         PC_HIP(c, hipMalloc(&c->tok_dev, cap));
