@@ -1,0 +1,139 @@
+// Host side of the library: the attention entry points (forward, gradient, expanded tables).
+#include "pc_host.h"
+
+extern "C" {
+
+int32_t pc_attend(pc_cache *c, const pc_call *calls, int32_t n_calls, const void *q, void *out, float *lse, void *stream)
+{
+    if (!c) return PC_ERR_INVALID_ARG;
+    if (n_calls < 0 || (n_calls > 0 && !calls)) return pc_fail(c, PC_ERR_INVALID_ARG, "attend: bad call list");
+    if (n_calls == 0) return PC_OK;
+    if (!c->host_only && (!q || !out)) return pc_fail(c, PC_ERR_INVALID_ARG, "attend: null q or out");
+    hipStream_t st = (hipStream_t)stream;
+    Planned P;
+    const int32_t rc = pc_plan_and_stage(c, calls, n_calls, true, st, P);
+    if (rc != PC_OK || c->host_only) return rc;
+
+    char *w = (char *)c->ws;
+    PcLaunch L{};
+    L.calls = (const PcCallDesc *)(w + P.lay.calls);
+    L.segs = (const PcSegment *)(w + P.lay.segs);
+    L.rot_seg = (const float2 *)(w + P.lay.rot_seg);
+    L.rot_q = (const float2 *)(w + P.lay.rot_q);
+    L.tiles = (const PcTile *)(w + P.lay.tiles);
+    L.k_store = c->k_store; L.v_store = c->v_store; L.q = q; L.out = out; L.lse = lse;
+    L.part_o = (uint16_t *)(w + P.lay.part_o); L.part_ml = (float *)(w + P.lay.part_ml);
+    L.slots = c->slots; L.n_q_heads = c->cfg.n_q_heads; L.n_kv_heads = c->cfg.n_kv_heads;
+    L.scale_log2 = c->scale * 1.4426950408889634f;
+    const int32_t *row_call = (const int32_t *)(w + P.lay.row_call);
+    if (c->cfg.dtype == PC_F32) {
+        ProfScope ps(c, 5, st);
+        pc_launch_attend_f32(L, row_call, P.total_q, c->D, st);
+        PC_HIP(c, hipGetLastError());
+        return PC_OK;
+    }
+    if (P.n_pre > 0) {
+        ProfScope ps(c, 2, st);
+        L.items = (const PcItem *)(w + P.lay.items_pre);
+        pc_launch_prefill_bf16(L, P.n_pre, st);
+        PC_HIP(c, hipGetLastError());
+    }
+    if (P.n_dec > 0) {
+        ProfScope ps(c, 3, st);
+        L.items = (const PcItem *)(w + P.lay.items_dec);
+        pc_launch_decode_bf16(L, P.n_dec, st);
+        PC_HIP(c, hipGetLastError());
+    }
+    if (P.n_sh_items > 0) {
+        ProfScope ps(c, 3, st);
+        PcShLaunch S{};
+        S.groups = (const PcShGroup *)(w + P.lay.sh_groups);
+        S.segs = (const PcShSeg *)(w + P.lay.sh_segs);
+        S.items = (const PcShItem *)(w + P.lay.sh_items);
+        S.rot = (const float2 *)(w + P.lay.sh_rot);
+        pc_launch_decode_shared_bf16(L, S, P.n_sh_items, st);
+        PC_HIP(c, hipGetLastError());
+    }
+    if (P.n_merge_rows > 0) {
+        ProfScope ps(c, 4, st);
+        pc_launch_merge(c->cfg.dtype, (const PcMergeRow *)(w + P.lay.merge_rows), P.n_merge_rows, L.part_o, L.part_ml, out, lse,
+                        c->cfg.n_q_heads, c->D, st);
+        PC_HIP(c, hipGetLastError());
+    }
+    return PC_OK;
+}
+
+int32_t pc_attend_backward(pc_cache *c, const pc_call *calls, int32_t n_calls, const void *q, const float *lse,
+                           const void *d_out, float *d_q, float *d_k, float *d_v, void *stream)
+{
+    if (!c) return PC_ERR_INVALID_ARG;
+    if (n_calls < 0 || (n_calls > 0 && !calls)) return pc_fail(c, PC_ERR_INVALID_ARG, "attend_backward: bad call list");
+    if (n_calls == 0) return PC_OK;
+    if (!c->host_only && (!q || !lse || !d_out || !d_q || !d_k || !d_v))
+        return pc_fail(c, PC_ERR_INVALID_ARG, "attend_backward: null argument");
+    hipStream_t st = (hipStream_t)stream;
+    Planned P;
+    const int32_t rc = pc_plan_and_stage(c, calls, n_calls, false, st, P);
+    if (rc != PC_OK || c->host_only) return rc;
+    char *w = (char *)c->ws;
+    PcLaunch L{};
+    L.calls = (const PcCallDesc *)(w + P.lay.calls);
+    L.segs = (const PcSegment *)(w + P.lay.segs);
+    L.rot_seg = (const float2 *)(w + P.lay.rot_seg);
+    L.rot_q = (const float2 *)(w + P.lay.rot_q);
+    L.k_store = c->k_store; L.v_store = c->v_store; L.q = q;
+    L.slots = c->slots; L.n_q_heads = c->cfg.n_q_heads; L.n_kv_heads = c->cfg.n_kv_heads;
+    L.scale_log2 = c->scale * 1.4426950408889634f;
+    ProfScope ps(c, 5, st);
+    int max_seg_len = 0;
+    for (const Resolved &r : P.res) {
+        for (const int2 &e : r.sel) max_seg_len = std::max(max_seg_len, c->msgs[(size_t)e.x].len);
+        max_seg_len = std::max(max_seg_len, r.self_len);
+    }
+    if ((max_seg_len + 15) / 16 > 65535) return pc_fail(c, PC_ERR_SHAPE, "attend_backward: a message of %d tokens is too long", max_seg_len);
+    L.calls = (const PcCallDesc *)(w + P.lay.calls);
+    pc_launch_attend_bwd(c->cfg.dtype, L, (const int32_t *)(w + P.lay.row_call), n_calls, P.total_q, P.total_seg, max_seg_len, c->D,
+                         lse, d_out, c->scale, (float *)(w + P.lay.row_scalar), d_q, d_k, d_v, st);
+    PC_HIP(c, hipGetLastError());
+    return PC_OK;
+}
+
+int32_t pc_grad_keys_finalize(pc_cache *c, float *d_k, void *stream)
+{
+    if (!c) return PC_ERR_INVALID_ARG;
+    if (c->host_only) return PC_OK;
+    if (!d_k) return pc_fail(c, PC_ERR_INVALID_ARG, "grad_keys_finalize: null d_k");
+    std::vector<PcMsgEntry> live;
+    for (const HostMsg &m : c->msgs)
+        if (m.live && m.len > 0) live.push_back(PcMsgEntry{(int32_t)m.slot_start, m.len, m.base_pos, 0});
+    if (live.empty()) return PC_OK;
+    hipStream_t st = (hipStream_t)stream;
+    const int32_t rc = pc_stage_items(c, live.data(), sizeof(PcMsgEntry) * live.size(), st);
+    if (rc != PC_OK) return rc;
+    ProfScope ps(c, 5, st);
+    pc_launch_grad_keys_finalize((const PcMsgEntry *)c->tok_dev, (int)live.size(), c->cfg.n_kv_heads, c->D, c->inv_freq_dev, d_k, st);
+    PC_HIP(c, hipGetLastError());
+    return PC_OK;
+}
+
+int32_t pc_build_tables(pc_cache *c, const pc_call *call, int32_t *kv_slot, int32_t *kv_pos, int64_t cap,
+                        int64_t *n_kv, void *stream)
+{
+    if (!c) return PC_ERR_INVALID_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    Planned P;
+    const int32_t rc = pc_plan_and_stage(c, call, 1, false, st, P);
+    if (rc != PC_OK) return rc;
+    const int64_t n = P.res[0].n_kv;
+    if (n_kv) *n_kv = n;
+    if (c->host_only || cap < n || n == 0) return PC_OK;
+    if (!kv_slot || !kv_pos) return pc_fail(c, PC_ERR_INVALID_ARG, "build_tables: null output with cap > 0");
+    ProfScope ps(c, 6, st);
+    char *w = (char *)c->ws;
+    pc_launch_expand_tables((const PcSegment *)(w + P.lay.segs), (const int32_t *)(w + P.lay.seg_kvoff), P.total_seg, n,
+                            kv_slot, kv_pos, st);
+    PC_HIP(c, hipGetLastError());
+    return PC_OK;
+}
+
+}  // extern "C"
