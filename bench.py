@@ -215,6 +215,31 @@ def main():
                          "work; the oracle is the plain definition on BLAS)"}, "TFLOP/s")
     del w2
 
+    # ------------------------------------ what this chip sustains for the two resources (probe kernels of the library)
+    achievable = None
+    if not args.skip_extras:
+        from paper_2512_23049_amd import probe_hbm_read, probe_mfma_bf16
+        sink = torch.zeros(4, dtype=torch.float32, device="cuda:0")
+        g = torch.Generator(device="cpu").manual_seed(7)
+        ops_rand = torch.randn(8192, generator=g).to(torch.bfloat16).to("cuda:0")
+        ops_zero = torch.zeros(8192, dtype=torch.bfloat16, device="cuda:0")
+        big = torch.ones(1 << 29, dtype=torch.float32, device="cuda:0")        # 2 GiB, several times the last-level cache
+        st = torch.cuda.current_stream().cuda_stream
+        achievable = {
+            "mfma_bf16_random_operands_tflops": probe_mfma_bf16(ops_rand.data_ptr(), ops_rand.numel() * 2, sink.data_ptr(),
+                                                                iters=16384, reps=5, stream=st),
+            "mfma_bf16_zero_operands_tflops": probe_mfma_bf16(ops_zero.data_ptr(), ops_zero.numel() * 2, sink.data_ptr(),
+                                                              iters=16384, reps=5, stream=st),
+            "hbm_stream_read_gbs": probe_hbm_read(big.data_ptr(), big.numel() * 4, sink.data_ptr(), reps=10, stream=st),
+            "how": "pc_probe_mfma_bf16 (bare 32x32x16 bf16 MFMA loop, 2 waves per SIMD on every CU; N(0,1) operands, "
+                   "then all-zero operands) and pc_probe_hbm_read (2 GiB streaming read)",
+        }
+        del big, ops_rand, ops_zero
+        line["achievable"] = achievable
+        if line["roofline"]["achieved"]:
+            line["roofline"]["frac_of_achievable"] = (line["roofline"]["achieved"]
+                                                      / achievable["mfma_bf16_random_operands_tflops"])
+
     # ---------------------------------------------------------------- decode (configs[2])
     if not args.skip_extras and (not only or "decode" in only):
         w3 = gen.parallel_decode()
@@ -247,6 +272,9 @@ def main():
                          "hbm_measured_frac": (traffic_dec / (k_dec * 1e-6) / 1e9 / HBM_PEAK_GBS) if (k_dec and traffic_dec) else None},
             "kernels_us": {k: v["avg_us"] for k, v in kern.items()},
         }
+        if achievable and line["decode"]["roofline"]["hbm_measured_gbs"]:
+            line["decode"]["roofline"]["hbm_measured_frac_of_achievable"] = (
+                line["decode"]["roofline"]["hbm_measured_gbs"] / achievable["hbm_stream_read_gbs"])
         if not args.skip_cpu:
             line["decode"]["cpu_baseline"] = cpu_baseline(
                 w3, {"calls": list(range(64)), "rows": lambda n: [0],

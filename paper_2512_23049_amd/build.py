@@ -7,7 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpc.so")
 SOURCES = ["pc_lib.hip", "pc_plan.hip", "pc_attend.hip", "pc_kernels_basic.hip", "pc_kernels_backward.hip", "pc_kernels_mfma.hip", "pc_kernels_prefill.hip",
-           "pc_kernels_shared.hip"]
+           "pc_kernels_shared.hip", "pc_probe.hip"]
 # the prefill kernel never produces NaNs in its max reductions: let the compiler drop the
 # canonicalising v_max x, x in front of every fmax
 FILE_FLAGS = {"pc_kernels_prefill.hip": ["-fno-honor-nans"]}

@@ -1,0 +1,40 @@
+"""GPU test of the achievable-peak probes the benchmark reports beside the datasheet peaks: both run
+to completion, report rates inside what the hardware can do, and all-zero operands are not slower than
+random ones (the clock the chip holds under matrix load depends on the operand bits)."""
+import sys
+
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+
+def say(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+def test_probes_report_plausible_rates():
+    import torch
+    import paper_2512_23049_amd as pc
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    st = torch.cuda.current_stream().cuda_stream
+    sink = torch.zeros(4, dtype=torch.float32, device="cuda:0")
+    g = torch.Generator(device="cpu").manual_seed(11)
+    rnd = torch.randn(8192, generator=g).to(torch.bfloat16).to("cuda:0")
+    zer = torch.zeros(8192, dtype=torch.bfloat16, device="cuda:0")
+    say("probe: mfma, random operands")
+    t_rnd = pc.probe_mfma_bf16(rnd.data_ptr(), rnd.numel() * 2, sink.data_ptr(), iters=4096, reps=3, stream=st)
+    say("probe: mfma, zero operands")
+    t_zer = pc.probe_mfma_bf16(zer.data_ptr(), zer.numel() * 2, sink.data_ptr(), iters=4096, reps=3, stream=st)
+    say("probe: mfma one wave per SIMD")
+    t_one = pc.probe_mfma_bf16(zer.data_ptr(), zer.numel() * 2, sink.data_ptr(), iters=4096, waves_per_simd=1, reps=3,
+                               stream=st)
+    buf = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")           # 1 GiB
+    say("probe: hbm read")
+    bw = pc.probe_hbm_read(buf.data_ptr(), buf.numel() * 4, sink.data_ptr(), reps=5, stream=st)
+    say("rates", t_rnd, t_zer, t_one, bw)
+    assert 300.0 < t_rnd <= 2600.0          # the datasheet peak is 2500 TFLOP/s (boost clocks leave a little headroom)
+    assert 300.0 < t_zer <= 2600.0 and 300.0 < t_one <= 2600.0
+    assert t_zer >= 0.95 * t_rnd
+    assert 1000.0 < bw <= 8200.0            # the datasheet peak is 8000 GB/s
+    assert float(sink.sum()) == 0.0         # the sink stays untouched

@@ -306,3 +306,18 @@ def test_gradient_entry_points_validate_like_attend(pc):
         with pytest.raises(pc.PcError) as ei:
             f.attend_backward([Call([(a + 1, 0)], -1, 0, 1, None)], 0, 0, 0, 0, 0, 0)
         assert ei.value.code == pc.PC_ERR_BAD_MSG_ID
+
+
+def test_probe_entries_reject_bad_arguments_before_touching_the_device(pc):
+    lib = pc.lib()
+    out = ctypes.c_double(0.0)
+    one = ctypes.c_void_p(4096)            # never dereferenced: every call below fails its argument checks
+    assert lib.pc_probe_mfma_bf16(None, 8192, 16, 2, 1, one, ctypes.byref(out), None) == pc.PC_ERR_INVALID_ARG
+    assert lib.pc_probe_mfma_bf16(one, 8191, 16, 2, 1, one, ctypes.byref(out), None) == pc.PC_ERR_SHAPE
+    assert lib.pc_probe_mfma_bf16(one, 8192, 0, 2, 1, one, ctypes.byref(out), None) == pc.PC_ERR_INVALID_ARG
+    assert lib.pc_probe_mfma_bf16(one, 8192, 16, 3, 1, one, ctypes.byref(out), None) == pc.PC_ERR_INVALID_ARG
+    assert lib.pc_probe_hbm_read(None, 1 << 20, 1, one, ctypes.byref(out), None) == pc.PC_ERR_INVALID_ARG
+    assert lib.pc_probe_hbm_read(one, 24, 1, one, ctypes.byref(out), None) == pc.PC_ERR_SHAPE
+    assert lib.pc_probe_hbm_read(ctypes.c_void_p(4100), 1 << 20, 1, one, ctypes.byref(out), None) == pc.PC_ERR_SHAPE
+    assert lib.pc_probe_hbm_read(one, 1 << 20, 0, one, ctypes.byref(out), None) == pc.PC_ERR_INVALID_ARG
+    assert out.value == 0.0
