@@ -430,3 +430,45 @@ def test_positions_far_from_zero(hip, dtype):
                 assert np.abs(lse[at:at + c.n_q].cpu().numpy() - l).max() <= tol["lse"]
                 at += c.n_q
     cache.close()
+
+
+@pytest.mark.parametrize("sharing", [None, 2])
+def test_calls_with_more_than_a_thousand_parents(hip, sharing):
+    """Calls that list more messages than the plan builder keeps on chip (it then searches the segment
+    list in device memory), most of them shorter than a tile: prefill and decode, repeats included."""
+    from pc_inputs import Call, Event, Workload, POS_AUTO
+    rng = np.random.default_rng(77)
+    w = Workload("many_parents", 8, 2, 128, "bf16", 10000.0)
+    n_msgs = 1400
+    lens = rng.integers(1, 4, size=n_msgs)
+    lens[::97] = 40                                        # a few that span two tiles
+    for L in lens:
+        k = gen.round_to_bf16(rng.standard_normal((int(L), 2, 128), dtype=np.float32))
+        v = gen.round_to_bf16(rng.standard_normal((int(L), 2, 128), dtype=np.float32))
+        w.events.append(Event("append", k=k, v=v))
+    tails = []
+    for _ in range(5):
+        k = gen.round_to_bf16(rng.standard_normal((48, 2, 128), dtype=np.float32))
+        v = gen.round_to_bf16(rng.standard_normal((48, 2, 128), dtype=np.float32))
+        w.events.append(Event("append", k=k, v=v))
+        tails.append(w.n_messages - 1)
+
+    def parents(n, repeat=0):
+        order = rng.permutation(n_msgs)[:n]
+        if repeat:
+            order = np.concatenate([order, order[:repeat]])
+        pos, sel = 0, []
+        for m in order:
+            sel.append((int(m), pos))
+            pos += int(lens[m]) + int(rng.integers(0, 3))
+        return sel, pos
+    calls = []
+    sel, end = parents(1100, repeat=30)
+    calls.append(Call(sel, tails[0], end + 5, 48, None))                      # prefill, 1131 segments
+    for t in tails[1:]:
+        sel, end = parents(1300)
+        calls.append(Call(sel, t, end, 1, None))                              # decode, 1301 segments each
+    q = gen.round_to_bf16(rng.standard_normal((sum(c.n_q for c in calls), 8, 128), dtype=np.float32))
+    w.events.append(Event("attend", calls=calls, q=q))
+    tables_check(hip, w, max_calls=2)
+    run_and_compare(hip, w, sharing=sharing)
