@@ -270,58 +270,60 @@ int32_t pc_append_messages(pc_cache *c, int32_t n, const void *const *k, const v
 }
 
 // shared by pc_append_tokens and pc_append_tokens_batch: token j of k, v goes to message ids[j]
-// (ids sorted by message with a message's tokens in order; validated by the callers)
+// (the tokens of one message are consecutive and in order, no message has two runs; validated by
+// the callers).  Host work is proportional to the tokens, not to the messages the cache holds.
 static int32_t append_token_items(pc_cache *c, const std::vector<int32_t> &ids, const void *k, const void *v, hipStream_t st)
 {
     const int n = (int)ids.size();
     std::vector<PcTokenItem> items((size_t)n);
-    std::vector<int32_t> left(c->msgs.size(), 0);            // tokens of this call still to place, per message
-    for (int j = 0; j < n; ++j) left[(size_t)ids[j]] += 1;
-    // the extent each message is writing into, as it will be (nothing is committed before the launch is accepted)
-    struct Cur { int32_t rec, len, reserve, base; int64_t slot; };
-    std::vector<int32_t> cur_of(c->msgs.size(), -1);
-    std::vector<Cur> cur;
     std::vector<HostMsg> fresh;                              // new extent records: ids msgs.size(), msgs.size() + 1, ...
     std::vector<std::pair<int32_t, int32_t>> links;          // (record, its new next)
-    std::vector<FreeSpan> spans = c->free_spans;
+    std::vector<std::pair<int32_t, int32_t>> grown;          // (record, its length after this call)
+    std::vector<FreeSpan> spans = c->free_spans;             // nothing is committed before the launch is accepted
     int64_t next = c->next_slot;
     const int32_t first_new = (int32_t)c->msgs.size();
-    for (int j = 0; j < n; ++j) {
-        const int32_t m = ids[j];
-        if (cur_of[(size_t)m] < 0) {
-            const int32_t last = chain_last(c, m);
-            const HostMsg &hm = c->msgs[(size_t)last];
-            cur_of[(size_t)m] = (int32_t)cur.size();
-            cur.push_back(Cur{last, hm.len, hm.reserve, hm.base_pos, hm.slot_start});
+    for (int j = 0; j < n;) {
+        const int32_t m = ids[(size_t)j];
+        int run_end = j;
+        while (run_end < n && ids[(size_t)run_end] == m) ++run_end;
+        // the extent the message is writing into, as it will be
+        const int32_t last = chain_last(c, m);
+        const HostMsg &hm = c->msgs[(size_t)last];
+        int32_t rec = last, len = hm.len, reserve = hm.reserve, base = hm.base_pos;
+        int64_t slot = hm.slot_start;
+        int first_item = j;                                  // first token of this call in the current extent
+        // every item carries the final length of the extent it goes to
+        auto close_extent = [&](int upto) {
+            if (upto == first_item) return;
+            for (int t = first_item; t < upto; ++t) items[(size_t)t].new_len = len;
+            grown.push_back({rec, len});
+        };
+        for (; j < run_end; ++j) {
+            if (len == reserve) {
+                if (!c->grow_extents)
+                    return pc_fail(c, PC_ERR_NO_SPACE, "append_tokens: message %d holds %d of %d reserved tokens, %d more do not fit",
+                                (int)m, chain_len(c, m), chain_len(c, m), run_end - j);
+                // a further extent: room for what this call still brings, at least the message's first reserve
+                if ((int64_t)c->msgs.size() + (int64_t)fresh.size() >= c->cfg.max_messages)
+                    return pc_fail(c, PC_ERR_NO_SPACE, "append_tokens: message table full (%d)", c->cfg.max_messages);
+                const int32_t res = std::max(run_end - j, std::max<int32_t>(PC_SLOT_ALIGN, c->msgs[(size_t)m].reserve));
+                int64_t start = 0;
+                if (!take_slots(spans, next, c->slots, res, start))
+                    return pc_fail(c, PC_ERR_NO_SPACE, "append_tokens: no room for a further extent of %d slots for message %d", res, (int)m);
+                close_extent(j);
+                const int32_t id = first_new + (int32_t)fresh.size();
+                HostMsg ext{start, 0, res, base + len, true};
+                ext.is_ext = true;
+                fresh.push_back(ext);
+                links.push_back({rec, id});
+                rec = id; len = 0; reserve = res; base = ext.base_pos; slot = start;
+                first_item = j;
+            }
+            items[(size_t)j] = PcTokenItem{rec, (int32_t)(slot + len), base + len, 0};
+            len += 1;
         }
-        Cur &cu = cur[(size_t)cur_of[(size_t)m]];
-        if (cu.len == cu.reserve) {
-            if (!c->grow_extents)
-                return pc_fail(c, PC_ERR_NO_SPACE, "append_tokens: message %d holds %d of %d reserved tokens, %d more do not fit",
-                            (int)m, chain_len(c, m), chain_len(c, m), left[(size_t)m]);
-            // a further extent: room for what this call still brings, at least the message's first reserve
-            if ((int64_t)c->msgs.size() + (int64_t)fresh.size() >= c->cfg.max_messages)
-                return pc_fail(c, PC_ERR_NO_SPACE, "append_tokens: message table full (%d)", c->cfg.max_messages);
-            const int32_t res = std::max(left[(size_t)m], std::max<int32_t>(PC_SLOT_ALIGN, c->msgs[(size_t)m].reserve));
-            int64_t start = 0;
-            if (!take_slots(spans, next, c->slots, res, start))
-                return pc_fail(c, PC_ERR_NO_SPACE, "append_tokens: no room for a further extent of %d slots for message %d", res, (int)m);
-            const int32_t id = first_new + (int32_t)fresh.size();
-            HostMsg rec{start, 0, res, cu.base + cu.len, true};
-            rec.is_ext = true;
-            fresh.push_back(rec);
-            links.push_back({cu.rec, id});
-            cu = Cur{id, 0, res, rec.base_pos, start};
-        }
-        items[(size_t)j] = PcTokenItem{cu.rec, (int32_t)(cu.slot + cu.len), cu.base + cu.len, 0};
-        cu.len += 1;
-        left[(size_t)m] -= 1;
+        close_extent(run_end);
     }
-    // every item carries the final length of the extent it goes to
-    std::vector<int32_t> final_len(c->msgs.size() + fresh.size(), 0);
-    for (size_t r = 0; r < c->msgs.size(); ++r) final_len[r] = c->msgs[r].len;
-    for (int j = 0; j < n; ++j) final_len[(size_t)items[(size_t)j].msg] += 1;
-    for (int j = 0; j < n; ++j) items[(size_t)j].new_len = final_len[(size_t)items[(size_t)j].msg];
     if (!c->host_only) {
         if (!fresh.empty()) {                                // the device table learns the new extents (length 0 until the kernel sets it)
             StageSlot *slot = nullptr;
@@ -354,7 +356,7 @@ static int32_t append_token_items(pc_cache *c, const std::vector<int32_t> &ids, 
         c->msgs.push_back(rec);
     }
     for (const auto &lk : links) c->msgs[(size_t)lk.first].next = lk.second;
-    for (size_t r = 0; r < c->msgs.size(); ++r) c->msgs[r].len = final_len[r];
+    for (const auto &g : grown) c->msgs[(size_t)g.first].len = g.second;
     c->free_spans.swap(spans);
     c->next_slot = next;
     return PC_OK;
@@ -375,13 +377,12 @@ int32_t pc_append_tokens_batch(pc_cache *c, const int32_t *msg_ids, int32_t n_ms
     if (n_msgs < 0 || (n_msgs > 0 && !msg_ids)) return pc_fail(c, PC_ERR_INVALID_ARG, "append_tokens_batch: bad id list");
     if (n_msgs == 0) return PC_OK;
     if (!c->host_only && (!k || !v)) return pc_fail(c, PC_ERR_INVALID_ARG, "append_tokens_batch: null k or v");
-    std::vector<char> listed(c->msgs.size(), 0);
-    for (int j = 0; j < n_msgs; ++j) {
-        const int32_t m = msg_ids[j];
-        if (!known(c, m)) return pc_fail(c, PC_ERR_BAD_MSG_ID, "append_tokens_batch: unknown message %d", m);
-        if (listed[(size_t)m]) return pc_fail(c, PC_ERR_INVALID_ARG, "append_tokens_batch: message %d listed twice", m);
-        listed[(size_t)m] = 1;
-    }
+    for (int j = 0; j < n_msgs; ++j)
+        if (!known(c, msg_ids[j])) return pc_fail(c, PC_ERR_BAD_MSG_ID, "append_tokens_batch: unknown message %d", msg_ids[j]);
+    std::vector<int32_t> sorted(msg_ids, msg_ids + n_msgs);
+    std::sort(sorted.begin(), sorted.end());
+    const auto twice = std::adjacent_find(sorted.begin(), sorted.end());
+    if (twice != sorted.end()) return pc_fail(c, PC_ERR_INVALID_ARG, "append_tokens_batch: message %d listed twice", *twice);
     return append_token_items(c, std::vector<int32_t>(msg_ids, msg_ids + n_msgs), k, v, (hipStream_t)stream);
 }
 
