@@ -300,7 +300,7 @@ int32_t pc_set_decode_sharing(pc_cache *c, int32_t mode);
  * They take no cache and allocate no device memory: the caller passes the buffers.
  *  pc_probe_mfma_bf16: the rate of 32x32x16 bf16 matrix instructions with nothing else in the
  *    loop, on every compute unit with `waves_per_simd` (1 or 2) waves per SIMD, each wave running
- *    iters * 16 of them.  operands (device, operand_bytes >= 8192, 16-byte aligned) supplies the
+ *    iters * 16 of them (iters <= 65536, reps <= 100).  operands (device, operand_bytes >= 8192, 16-byte aligned) supplies the
  *    bf16 operand fragments; the clock the chip holds depends on how many operand bits toggle,
  *    so all-zero operands give the datasheet rate and random ones the rate real data can reach.
  *  pc_probe_hbm_read: the rate of a streaming read of `bytes` (multiple of 16, device, 16-byte

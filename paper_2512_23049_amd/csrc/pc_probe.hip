@@ -93,7 +93,7 @@ int32_t pc_probe_mfma_bf16(const void *operands, int64_t operand_bytes, int32_t 
                            int32_t reps, float *sink, double *tflops, void *stream) {
     if (!operands || !sink || !tflops) return PC_ERR_INVALID_ARG;
     if (operand_bytes < (int64_t)PROBE_CHAINS * 64 * 32) return PC_ERR_SHAPE;
-    if (iters < 1 || iters > (1 << 20) || reps < 1 || reps > 1000) return PC_ERR_INVALID_ARG;
+    if (iters < 1 || iters > (1 << 16) || reps < 1 || reps > 100) return PC_ERR_INVALID_ARG;   // at most ~2 s of GPU time
     if (waves_per_simd < 1 || waves_per_simd > 2) return PC_ERR_INVALID_ARG;
     int cus = 0;
     if (int32_t rc = compute_units(&cus)) return rc;
@@ -119,7 +119,7 @@ int32_t pc_probe_hbm_read(const void *src, int64_t bytes, int32_t reps, float *s
                           void *stream) {
     if (!src || !sink || !gb_per_s) return PC_ERR_INVALID_ARG;
     if (bytes < 16 || (bytes & 15) || ((uintptr_t)src & 15)) return PC_ERR_SHAPE;
-    if (reps < 1 || reps > 1000) return PC_ERR_INVALID_ARG;
+    if (reps < 1 || reps > 100) return PC_ERR_INVALID_ARG;
     int cus = 0;
     if (int32_t rc = compute_units(&cus)) return rc;
     hipStream_t st = (hipStream_t)stream;
