@@ -176,14 +176,19 @@ __global__ __launch_bounds__(256, 2) void pc_decode_bf16_kernel(PcLaunch L)
         const float m_new = fmaxf(m_run, mx);
         const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
         const float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);
-        float p[8], ps = 0.f;
+        // the row sum is taken over the probabilities as the second MFMA sees them (rounded to bf16): the
+        // rounding then cancels between numerator and denominator (a row with a single key returns its V exactly)
+        uint32_t pk[4];
+        float ps = 0.f;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) { p[j] = __builtin_amdgcn_exp2f(sc[j] - m_safe); ps += p[j]; }
+        for (int j = 0; j < 4; ++j) {
+            pk[j] = pack_bf16(__builtin_amdgcn_exp2f(sc[2 * j] - m_safe), __builtin_amdgcn_exp2f(sc[2 * j + 1] - m_safe));
+            ps += bf_lo(pk[j]) + bf_hi(pk[j]);
+        }
         l_run = l_run * alpha + ps;
         m_run = m_new;
         const bool rescale = __builtin_amdgcn_ballot_w64(alpha != 1.f) != 0;   // rare once the running maxima have settled
-        const bf16x8 pop = __builtin_bit_cast(bf16x8, make_uint4(pack_bf16(p[0], p[1]), pack_bf16(p[2], p[3]),
-                                                                 pack_bf16(p[4], p[5]), pack_bf16(p[6], p[7])));
+        const bf16x8 pop = __builtin_bit_cast(bf16x8, make_uint4(pk[0], pk[1], pk[2], pk[3]));
 #pragma unroll
         for (int db = 0; db < 8; ++db) {
             if (rescale) acc[db] *= alpha;

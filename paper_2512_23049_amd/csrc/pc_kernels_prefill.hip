@@ -468,12 +468,19 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
             const unsigned char *vl = v_rd + ((T - 1) % RING) * TILE_BYTES;
 #pragma unroll
             for (int f = 0; f < 8; ++f) fr[f] = *reinterpret_cast<const bf16x8 *>(vl + (((f >> 2) * 2) * PC_D + 32 * (f & 3)) * 16);
-            float e[16], ps = 0.f;
+            // outside the pipelined loop the row sum can afford to take the probabilities as the MFMA sees them
+            // (rounded to bf16): for calls of a single tile the rounding then cancels between numerator and
+            // denominator (a row with one visible key returns its V exactly)
+            uint32_t pl[8];
+            float ps = 0.f;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) { e[r] = fast_exp2(sc[r]); ps += e[r]; }
+            for (int r = 0; r < 8; ++r) {
+                pl[r] = pack_bf16(fast_exp2(sc[2 * r]), fast_exp2(sc[2 * r + 1]));
+                ps += bf_lo(pl[r]) + bf_hi(pl[r]);
+            }
             l_run += ps;
-            const bf16x8 p0 = __builtin_bit_cast(bf16x8, make_uint4(pack_bf16(e[0], e[1]), pack_bf16(e[2], e[3]), pack_bf16(e[4], e[5]), pack_bf16(e[6], e[7])));
-            const bf16x8 p1 = __builtin_bit_cast(bf16x8, make_uint4(pack_bf16(e[8], e[9]), pack_bf16(e[10], e[11]), pack_bf16(e[12], e[13]), pack_bf16(e[14], e[15])));
+            const bf16x8 p0 = __builtin_bit_cast(bf16x8, make_uint4(pl[0], pl[1], pl[2], pl[3]));
+            const bf16x8 p1 = __builtin_bit_cast(bf16x8, make_uint4(pl[4], pl[5], pl[6], pl[7]));
 #pragma unroll
             for (int f = 0; f < 8; ++f) acc[f & 3] = MFMA32(fr[f], (f >> 2) ? p1 : p0, acc[f & 3]);
         }

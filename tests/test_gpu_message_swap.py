@@ -76,8 +76,18 @@ def test_swapped_message_comes_back_bit_identical(hip, dtype, where):
     cache.message_swap_in(b, blob.data_ptr())
     assert cache.message_info(b)[1] != slot_before and cache.message_info(b)[0] == 61 and cache.message_base(b) == 300
     out1, lse1 = attend()
-    assert torch.equal(out0.view(torch.uint8), out1.view(torch.uint8)), "the message changed on its way out and back"
-    assert torch.equal(lse0, lse1)
+    # The prefill call walks its parents in list order: the same arithmetic, bit for bit.  The one-row call
+    # of a bf16 cache walks them in cache-slot order, which the move changed: the same terms summed in another
+    # order (fp32 rounding in the sums; the bf16 output may differ in its last bit).
+    n0 = calls[0].n_q
+    assert torch.equal(out0[:n0].view(torch.uint8), out1[:n0].view(torch.uint8)), "the message changed on its way out and back"
+    assert torch.equal(lse0[:n0], lse1[:n0])
+    if dtype == "f32":
+        assert torch.equal(out0[n0:].view(torch.uint8), out1[n0:].view(torch.uint8)) and torch.equal(lse0[n0:], lse1[n0:])
+    else:
+        o0, o1 = out0[n0:].float(), out1[n0:].float()
+        assert ((o0 - o1).abs() <= 2.0 ** -7 * o0.abs()).all()
+        assert ((lse0[n0:] - lse1[n0:]).abs() <= 1e-6 * lse0[n0:].abs() + 1e-6).all()
     # and the results are the oracle's (message b's keys carry one more rounding in bf16: twice the bars)
     off = 0
     for cl in calls:
