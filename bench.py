@@ -162,7 +162,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--skip-extras", action="store_true")
     ap.add_argument("--skip-cpu", action="store_true")
-    ap.add_argument("--only", default="", help="comma list of sections: decode,long,longdecode,rounds,baseline,loop,reposition,backward")
+    ap.add_argument("--only", default="", help="comma list of sections: achievable,decode,long,longdecode,rounds,baseline,loop,reposition,backward")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="also launch one plain device copy of this many MiB (reference for scaling rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE counters)")
@@ -217,7 +217,7 @@ def main():
 
     # ------------------------------------ what this chip sustains for the two resources (probe kernels of the library)
     achievable = None
-    if not args.skip_extras:
+    if not args.skip_extras and (not only or "achievable" in only):
         from paper_2512_23049_amd import probe_hbm_read, probe_mfma_bf16
         sink = torch.zeros(4, dtype=torch.float32, device="cuda:0")
         g = torch.Generator(device="cpu").manual_seed(7)
