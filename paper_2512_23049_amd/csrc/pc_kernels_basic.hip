@@ -364,8 +364,9 @@ void pc_launch_reposition(int dtype, int len, int n_kv_heads, int D, int64_t slo
                                                           (float *)k_store, table, msg_id);
 }
 
-// Batched form: blockIdx.y names the message, the blocks of a row of the grid walk its
-// (token, KV head, frequency pair) triples with a grid stride.
+// Batched form: blockIdx.y names the message, the blocks of a row of the grid walk its key rows
+// with a grid stride.  A thread takes 16 bytes from each half of a key row per step (8 frequency
+// pairs in bf16, 4 in fp32): the kernel is one read and one write of K and lives on wide accesses.
 template <typename T>
 __global__ __launch_bounds__(256) void pc_reposition_batch_kernel(
     const PcMoveItem *__restrict__ items, int n_kv_heads, int D, int64_t slots,
@@ -374,6 +375,10 @@ __global__ __launch_bounds__(256) void pc_reposition_batch_kernel(
     __shared__ float2 s_lut[64];
     const PcMoveItem it = items[blockIdx.y];
     const int half = D / 2;
+    constexpr int PER = 16 / (int)sizeof(T);             // frequency pairs per thread and step
+    const int per_row = half / PER;
+    const int64_t total = (int64_t)it.len * n_kv_heads * per_row;
+    if ((int64_t)blockIdx.x * blockDim.x >= total) return;            // a short message needs fewer blocks than the grid has
     if ((int)threadIdx.x < half) {
         double s, c;
         sincos((double)it.delta * inv_freq[threadIdx.x], &s, &c);
@@ -381,26 +386,34 @@ __global__ __launch_bounds__(256) void pc_reposition_batch_kernel(
     }
     __syncthreads();
     if (blockIdx.x == 0 && threadIdx.x == 0) table[it.msg].base_pos = it.new_base;
-    const int per_row = half / 2;
-    const int64_t total = (int64_t)it.len * n_kv_heads * per_row;
     for (int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; tid < total; tid += (int64_t)gridDim.x * blockDim.x) {
-        const int i0 = 2 * (int)(tid % per_row);
+        const int i0 = PER * (int)(tid % per_row);
         const int h = (int)((tid / per_row) % n_kv_heads);
         const int t = (int)(tid / ((int64_t)per_row * n_kv_heads));
-        const float2 r0 = s_lut[i0], r1 = s_lut[i0 + 1];
         T *row = k_store + ((int64_t)h * slots + it.slot_start + t) * D;
+        uint4 lo = *reinterpret_cast<const uint4 *>(row + i0);
+        uint4 hi = *reinterpret_cast<const uint4 *>(row + half + i0);
+        uint32_t *lw = reinterpret_cast<uint32_t *>(&lo), *hw = reinterpret_cast<uint32_t *>(&hi);
         if constexpr (sizeof(T) == 2) {
             using P = Pair2<__hip_bfloat16>;
-            const uint32_t lo = *reinterpret_cast<const uint32_t *>(row + i0);
-            const uint32_t hi = *reinterpret_cast<const uint32_t *>(row + half + i0);
-            const float a0 = P::lo(lo), a1 = P::hi(lo), b0 = P::lo(hi), b1 = P::hi(hi);
-            *reinterpret_cast<uint32_t *>(row + i0) = P::pack(a0 * r0.x - b0 * r0.y, a1 * r1.x - b1 * r1.y);
-            *reinterpret_cast<uint32_t *>(row + half + i0) = P::pack(a0 * r0.y + b0 * r0.x, a1 * r1.y + b1 * r1.x);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const float2 r0 = s_lut[i0 + 2 * u], r1 = s_lut[i0 + 2 * u + 1];
+                const float a0 = P::lo(lw[u]), a1 = P::hi(lw[u]), b0 = P::lo(hw[u]), b1 = P::hi(hw[u]);
+                lw[u] = P::pack(a0 * r0.x - b0 * r0.y, a1 * r1.x - b1 * r1.y);
+                hw[u] = P::pack(a0 * r0.y + b0 * r0.x, a1 * r1.y + b1 * r1.x);
+            }
         } else {
-            const float a0 = row[i0], a1 = row[i0 + 1], b0 = row[half + i0], b1 = row[half + i0 + 1];
-            row[i0] = a0 * r0.x - b0 * r0.y; row[i0 + 1] = a1 * r1.x - b1 * r1.y;
-            row[half + i0] = a0 * r0.y + b0 * r0.x; row[half + i0 + 1] = a1 * r1.y + b1 * r1.x;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const float2 r = s_lut[i0 + u];
+                const float a = __uint_as_float(lw[u]), b_ = __uint_as_float(hw[u]);
+                lw[u] = __float_as_uint(a * r.x - b_ * r.y);
+                hw[u] = __float_as_uint(a * r.y + b_ * r.x);
+            }
         }
+        *reinterpret_cast<uint4 *>(row + i0) = lo;
+        *reinterpret_cast<uint4 *>(row + half + i0) = hi;
     }
 }
 
@@ -409,7 +422,7 @@ void pc_launch_reposition_batch(int dtype, const PcMoveItem *items, int n_items,
 {
     for (int first = 0; first < n_items; first += 65535) {            // grid.y is limited to 65535
         const int n = n_items - first < 65535 ? n_items - first : 65535;
-        dim3 grid(8, (unsigned)n);                       // 8 blocks of 256 threads per message
+        dim3 grid(64, (unsigned)n);                      // up to 64 blocks of 256 threads per message
         if (dtype == 1)
             pc_reposition_batch_kernel<uint16_t><<<grid, 256, 0, st>>>(items + first, n_kv_heads, D, slots, inv_freq,
                                                                        (uint16_t *)k_store, table);
