@@ -346,14 +346,49 @@ def main():
         sec4 = (time.perf_counter() - t0) / reps
         for c in caches:
             c.close()
-        f4 = 0.0
-        for e in w4.events:
-            if e.kind == "attend":
-                f4 += 4.0 * w4.head_dim * w4.n_q_heads * sum(v[3] for v in visible_pairs(w4, e))
+        f_round = [4.0 * w4.head_dim * w4.n_q_heads * sum(v[3] for v in visible_pairs(w4, e))
+                   for e in w4.events if e.kind == "attend"]
+        f4 = sum(f_round)
+        # one more sequence with the library's kernel events on, read round by round: kernel time per class
+        # (append GB/s on 2 * 4096 B per token, prefill TFLOP/s on the kernel's own time) and wall time per round
+        c = harness.make_cache(w4)
+        dw.run(c, want_lse=False, batch_appends=True)
+        c.close()
+        c = harness.make_cache(w4)
+        c.profile_enable(True)
+        c.profile_read(reset=True)
+        per_round, pending, tok_round = [], [], 0
+        torch.cuda.synchronize()
+        t_r = time.perf_counter()
+        for s_ in dw.steps:
+            if s_[0] == "append":
+                pending.append(s_)
+                tok_round += s_[3]
+                continue
+            c.append_messages([p_[1].data_ptr() for p_ in pending], [p_[2].data_ptr() for p_ in pending],
+                              [p_[3] for p_ in pending], [p_[4] for p_ in pending])
+            pending = []
+            _, calls_, m_, q_, out_, lse_ = s_
+            c.attend(calls_, q_.data_ptr(), out_.data_ptr(), 0, 0, m_)
+            pr = c.profile_read(reset=True)                     # waits for the round's work
+            now = time.perf_counter()
+            k_app = pr["append"][0] * 1e-3
+            k_pre = pr["prefill"][0] * 1e-3
+            r = len(per_round)
+            per_round.append({"wall_ms": (now - t_r) * 1e3, "append_kernel_us": k_app * 1e6,
+                              "append_gbs": (2 * 4096 * tok_round / k_app / 1e9) if k_app > 0 else None,
+                              "prefill_kernel_us": k_pre * 1e6,
+                              "prefill_tflops_kernel": (f_round[r] / k_pre / 1e12) if k_pre > 0 else None,
+                              "other_kernels_us": sum(v[0] for k_, v in pr.items() if k_ not in ("append", "prefill")) * 1e3})
+            tok_round = 0
+            t_r = now
+        c.profile_enable(False)
+        c.close()
         line.setdefault("extras", {})["multi_agent_rounds"] = {
             "workload": "configs[3]: 8 agents x 6 rounds; per round one pc_append_messages of the 8 new 256-token messages "
                         "and one pc_attend of the 8 prefill calls",
-            "ms_per_sequence": sec4 * 1e3, "tflops_incl_appends": f4 / sec4 / 1e12, "flops": f4, "reps": reps}
+            "ms_per_sequence": sec4 * 1e3, "tflops_incl_appends": f4 / sec4 / 1e12, "flops": f4, "reps": reps,
+            "per_round_with_kernel_events": per_round}
         del w4
 
     # ------------------------------------------------ attention work of a prefix-caching baseline

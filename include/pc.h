@@ -104,8 +104,9 @@ const char *pc_last_error(const pc_cache *c);
 /* Append one message (Sec. 2.3: prefill/decode "append a newly encoded message to
  * the global KV cache and return a unique new identifier"; Sec. 2.4: new messages go
  * at the end of the occupied part of the cache).
- *   k, v     device, [len, n_kv_heads, head_dim] contiguous, cache dtype; k is the
- *            UNROTATED key (no positional rotation applied by the caller).
+ *   k, v     device, [len, n_kv_heads, head_dim] contiguous, cache dtype, 16-byte aligned
+ *            (PC_ERR_INVALID_ARG otherwise); k is the UNROTATED key (no positional rotation
+ *            applied by the caller).
  *   reserve  slots to reserve for the message (0 or < len means len).
  *   msg_id   receives the new id.
  * The fused append kernel stores K turned to its in-message index (delta-rotated

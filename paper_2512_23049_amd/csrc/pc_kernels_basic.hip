@@ -11,8 +11,11 @@
 // occupied part of the cache; the i-th token's key is turned to a position by RoPE).
 // Stored form: the key of in-message token t is turned by t (delta-rotated form), so
 // that placing the message at offset s later only needs the query turned by -s.
-// blockIdx.y == 0: K part, one thread per (token, kv head, 2 adjacent frequency pairs)
-// blockIdx.y == 1: V part, one thread per (group of 8 tokens, kv head, 2 adjacent dims)
+// bf16 caches: blockIdx.y == 0 is the K part (a block takes APP_TB consecutive tokens: its threads
+// first share out the (token, frequency) rotations, one fp64 sincos each, into LDS, then each moves
+// 16 bytes of the lower and of the upper half of a (token, KV head) row), blockIdx.y == 1 the V part
+// (a thread transposes 8 tokens x 2 dims of one KV head).  k and v must be 16-byte aligned.
+// fp32 caches (small reference configurations): one thread per (token, frequency pair) and per element.
 // ----------------------------------------------------------------------------------
 template <typename T> struct Pair2;
 template <> struct Pair2<__hip_bfloat16> {
@@ -26,59 +29,77 @@ template <> struct Pair2<__hip_bfloat16> {
     }
 };
 
-// what one thread of the K part (part 0) or the V part (part 1) does; tid counts the threads of a part
-__device__ __forceinline__ void append_bf16_thread(
-    int part, int64_t tid, const uint16_t *__restrict__ k, const uint16_t *__restrict__ v, int len, int n_kv_heads,
-    int D, int64_t slot_start, int64_t slots, const double *__restrict__ inv_freq,
-    uint16_t *__restrict__ k_store, uint16_t *__restrict__ v_store)
+#define APP_TB 4               // tokens per block step of the K part: 4 x 64 rotations = one sincos per thread
+
+// K part: tokens [t0, t0 + APP_TB) of one message.  s_cs: APP_TB * 64 rotations.
+__device__ __forceinline__ void append_bf16_k_block(
+    const uint16_t *__restrict__ k, int len, int t0, int n_kv_heads, int D, int64_t slot_start, int64_t slots,
+    const double *__restrict__ inv_freq, uint16_t *__restrict__ k_store, float2 *s_cs)
 {
     const int half = D / 2;
-    if (part == 0) {
-        // thread = (token t, KV head h, pair index i0 = 2*j): handles frequency pairs i0 and i0+1 of one
-        // head, so that no thread walks the heads one dependent load after the other
-        const int per_tok = half / 2;
-        if (tid >= (int64_t)len * n_kv_heads * per_tok) return;
-        const int i0 = 2 * (int)(tid % per_tok);
-        const int h = (int)((tid / per_tok) % n_kv_heads);
-        const int t = (int)(tid / ((int64_t)per_tok * n_kv_heads));
-        const uint16_t *src = k + ((int64_t)t * n_kv_heads + h) * D;
-        const uint32_t lo = *reinterpret_cast<const uint32_t *>(src + i0);
-        const uint32_t hi = *reinterpret_cast<const uint32_t *>(src + half + i0);
-        double s0, c0, s1, c1;
-        sincos((double)t * inv_freq[i0], &s0, &c0);
-        sincos((double)t * inv_freq[i0 + 1], &s1, &c1);
-        const float fc0 = (float)c0, fs0 = (float)s0, fc1 = (float)c1, fs1 = (float)s1;
-        using P = Pair2<__hip_bfloat16>;
-        const float a0 = P::lo(lo), a1 = P::hi(lo), b0 = P::lo(hi), b1 = P::hi(hi);
-        uint16_t *dst = k_store + ((int64_t)h * slots + slot_start + t) * D;
-        *reinterpret_cast<uint32_t *>(dst + i0) = P::pack(a0 * fc0 - b0 * fs0, a1 * fc1 - b1 * fs1);
-        *reinterpret_cast<uint32_t *>(dst + half + i0) = P::pack(a0 * fs0 + b0 * fc0, a1 * fs1 + b1 * fc1);
-    } else {
-        // thread = (token group tg, head h, dim pair d0): 8 tokens x 2 dims, zero padded
-        const int dp = D / 2;
-        const int n_groups = (len + PC_VGROUP - 1) / PC_VGROUP;
-        if (tid >= (int64_t)n_groups * n_kv_heads * dp) return;
-        const int d0 = 2 * (int)(tid % dp);
-        const int h = (int)((tid / dp) % n_kv_heads);
-        const int tg = (int)(tid / ((int64_t)dp * n_kv_heads));
-        uint16_t a[PC_VGROUP], b[PC_VGROUP];
-#pragma unroll
-        for (int j = 0; j < PC_VGROUP; ++j) {
-            const int t = tg * PC_VGROUP + j;
-            uint32_t u = 0;
-            if (t < len) u = *reinterpret_cast<const uint32_t *>(v + ((int64_t)t * n_kv_heads + h) * D + d0);
-            a[j] = (uint16_t)(u & 0xFFFFu);
-            b[j] = (uint16_t)(u >> 16);
-        }
-        uint16_t *dst = v_store + (((int64_t)h * (slots / PC_VGROUP) + slot_start / PC_VGROUP + tg) * D + d0) * PC_VGROUP;
-        uint4 wa, wb;
-        wa.x = a[0] | ((uint32_t)a[1] << 16); wa.y = a[2] | ((uint32_t)a[3] << 16);
-        wa.z = a[4] | ((uint32_t)a[5] << 16); wa.w = a[6] | ((uint32_t)a[7] << 16);
-        wb.x = b[0] | ((uint32_t)b[1] << 16); wb.y = b[2] | ((uint32_t)b[3] << 16);
-        wb.z = b[4] | ((uint32_t)b[5] << 16); wb.w = b[6] | ((uint32_t)b[7] << 16);
-        *reinterpret_cast<uint4 *>(dst) = wa;
-        *reinterpret_cast<uint4 *>(dst + PC_VGROUP) = wb;
+    const int nt = min(APP_TB, len - t0);
+    for (int e = threadIdx.x; e < nt * half; e += blockDim.x) {
+        const int tt = e / half, i = e - tt * half;
+        double s, c;
+        sincos((double)(t0 + tt) * inv_freq[i], &s, &c);
+        s_cs[tt * 64 + i] = make_float2((float)c, (float)s);
     }
+    __syncthreads();
+    const int chunks = half / 8;                         // 16-byte chunks in half a row
+    const int tasks = nt * n_kv_heads * chunks;
+    using P = Pair2<__hip_bfloat16>;
+    for (int e = threadIdx.x; e < tasks; e += blockDim.x) {
+        const int c8 = e % chunks;
+        const int h = (e / chunks) % n_kv_heads;
+        const int tt = e / (chunks * n_kv_heads);
+        const int t = t0 + tt;
+        const uint16_t *src = k + ((int64_t)t * n_kv_heads + h) * D + 8 * c8;
+        uint4 lo = *reinterpret_cast<const uint4 *>(src);
+        uint4 hi = *reinterpret_cast<const uint4 *>(src + half);
+        uint32_t *lw = reinterpret_cast<uint32_t *>(&lo), *hw = reinterpret_cast<uint32_t *>(&hi);
+        const float2 *cs = s_cs + tt * 64 + 8 * c8;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const float fc0 = cs[2 * u].x, fs0 = cs[2 * u].y, fc1 = cs[2 * u + 1].x, fs1 = cs[2 * u + 1].y;
+            const float a0 = P::lo(lw[u]), a1 = P::hi(lw[u]), b0 = P::lo(hw[u]), b1 = P::hi(hw[u]);
+            lw[u] = P::pack(a0 * fc0 - b0 * fs0, a1 * fc1 - b1 * fs1);
+            hw[u] = P::pack(a0 * fs0 + b0 * fc0, a1 * fs1 + b1 * fc1);
+        }
+        uint16_t *dst = k_store + ((int64_t)h * slots + slot_start + t) * D + 8 * c8;
+        *reinterpret_cast<uint4 *>(dst) = lo;
+        *reinterpret_cast<uint4 *>(dst + half) = hi;
+    }
+    __syncthreads();                                     // s_cs is rewritten by the block's next step
+}
+
+// V part: thread tid = (token group tg, KV head h, dim pair d0): 8 tokens x 2 dims, zero padded behind
+// the message's last token, written key-transposed ([H_kv][slots/8][D][8]) as two 16-byte stores.
+__device__ __forceinline__ void append_bf16_v_thread(
+    int64_t tid, const uint16_t *__restrict__ v, int len, int n_kv_heads, int D, int64_t slot_start, int64_t slots,
+    uint16_t *__restrict__ v_store)
+{
+    const int dp = D / 2;
+    const int n_groups = (len + PC_VGROUP - 1) / PC_VGROUP;
+    if (tid >= (int64_t)n_groups * n_kv_heads * dp) return;
+    const int d0 = 2 * (int)(tid % dp);
+    const int h = (int)((tid / dp) % n_kv_heads);
+    const int tg = (int)(tid / ((int64_t)dp * n_kv_heads));
+    uint32_t in[PC_VGROUP];
+#pragma unroll
+    for (int j = 0; j < PC_VGROUP; ++j) {
+        const int t = tg * PC_VGROUP + j;
+        in[j] = (t < len) ? *reinterpret_cast<const uint32_t *>(v + ((int64_t)t * n_kv_heads + h) * D + d0) : 0u;
+    }
+    uint4 ev, od;
+    uint32_t *ew = reinterpret_cast<uint32_t *>(&ev), *ow = reinterpret_cast<uint32_t *>(&od);
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {                        // tokens 2w and 2w + 1 of the group
+        ew[w] = (in[2 * w] & 0xFFFFu) | (in[2 * w + 1] << 16);
+        ow[w] = (in[2 * w] >> 16) | (in[2 * w + 1] & 0xFFFF0000u);
+    }
+    uint16_t *dst = v_store + (((int64_t)h * (slots / PC_VGROUP) + slot_start / PC_VGROUP + tg) * D + d0) * PC_VGROUP;
+    *reinterpret_cast<uint4 *>(dst) = ev;
+    *reinterpret_cast<uint4 *>(dst + PC_VGROUP) = od;
 }
 
 __device__ __forceinline__ void append_f32_thread(
@@ -116,9 +137,14 @@ __global__ __launch_bounds__(256) void pc_append_bf16_kernel(
     uint16_t *__restrict__ k_store, uint16_t *__restrict__ v_store,
     PcMsgEntry *__restrict__ table, int msg_id)
 {
-    const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (blockIdx.y == 0 && tid == 0) { table[msg_id].slot_start = (int32_t)slot_start; table[msg_id].len = len; table[msg_id].base_pos = 0; }
-    append_bf16_thread((int)blockIdx.y, tid, k, v, len, n_kv_heads, D, slot_start, slots, inv_freq, k_store, v_store);
+    __shared__ float2 s_cs[APP_TB * 64];
+    if (blockIdx.y == 0) {
+        if (blockIdx.x == 0 && threadIdx.x == 0) { table[msg_id].slot_start = (int32_t)slot_start; table[msg_id].len = len; table[msg_id].base_pos = 0; }
+        const int t0 = (int)blockIdx.x * APP_TB;
+        if (t0 < len) append_bf16_k_block(k, len, t0, n_kv_heads, D, slot_start, slots, inv_freq, k_store, s_cs);
+    } else {
+        append_bf16_v_thread((int64_t)blockIdx.x * blockDim.x + threadIdx.x, v, len, n_kv_heads, D, slot_start, slots, v_store);
+    }
 }
 
 __global__ __launch_bounds__(256) void pc_append_f32_kernel(
@@ -144,17 +170,19 @@ __global__ __launch_bounds__(256) void pc_append_batch_kernel(
     if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) {
         table[it.msg].slot_start = it.slot_start; table[it.msg].len = it.len; table[it.msg].base_pos = 0;
     }
-    int64_t total;
-    if constexpr (sizeof(T) == 2)
-        total = blockIdx.y == 0 ? (int64_t)it.len * n_kv_heads * (D / 4)
-                                : (int64_t)((it.len + PC_VGROUP - 1) / PC_VGROUP) * n_kv_heads * (D / 2);
-    else
-        total = blockIdx.y == 0 ? (int64_t)it.len * (D / 2) : (int64_t)it.len * n_kv_heads * D;
-    for (int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; tid < total; tid += (int64_t)gridDim.x * blockDim.x) {
-        if constexpr (sizeof(T) == 2)
-            append_bf16_thread((int)blockIdx.y, tid, (const uint16_t *)it.k, (const uint16_t *)it.v, it.len, n_kv_heads, D,
-                               it.slot_start, slots, inv_freq, k_store, v_store);
-        else
+    if constexpr (sizeof(T) == 2) {
+        __shared__ float2 s_cs[APP_TB * 64];
+        if (blockIdx.y == 0) {
+            for (int t0 = (int)blockIdx.x * APP_TB; t0 < it.len; t0 += (int)gridDim.x * APP_TB)
+                append_bf16_k_block((const uint16_t *)it.k, it.len, t0, n_kv_heads, D, it.slot_start, slots, inv_freq, k_store, s_cs);
+        } else {
+            const int64_t total = (int64_t)((it.len + PC_VGROUP - 1) / PC_VGROUP) * n_kv_heads * (D / 2);
+            for (int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; tid < total; tid += (int64_t)gridDim.x * blockDim.x)
+                append_bf16_v_thread(tid, (const uint16_t *)it.v, it.len, n_kv_heads, D, it.slot_start, slots, v_store);
+        }
+    } else {
+        const int64_t total = blockIdx.y == 0 ? (int64_t)it.len * (D / 2) : (int64_t)it.len * n_kv_heads * D;
+        for (int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; tid < total; tid += (int64_t)gridDim.x * blockDim.x)
             append_f32_thread((int)blockIdx.y, tid, (const float *)it.k, (const float *)it.v, it.len, n_kv_heads, D,
                               it.slot_start, slots, inv_freq, k_store, v_store);
     }
@@ -165,8 +193,9 @@ void pc_launch_append_batch(int dtype, const PcAppendItem *items, int n_items, i
                             hipStream_t st)
 {
     // enough blocks per (part, message) for the longest message at one pass, within reason
-    const int64_t per = (int64_t)max_len * n_kv_heads * (dtype == 1 ? D / 4 : D);
-    const unsigned bx = (unsigned)std::min<int64_t>(std::max<int64_t>((per + 255) / 256, 1), 256);
+    // (bf16: the K part takes APP_TB tokens per block step, which is more blocks than the V part needs)
+    const int64_t per = dtype == 1 ? ((int64_t)max_len + APP_TB - 1) / APP_TB : ((int64_t)max_len * n_kv_heads * D + 255) / 256;
+    const unsigned bx = (unsigned)std::min<int64_t>(std::max<int64_t>(per, 1), 256);
     for (int first = 0; first < n_items; first += 65535) {            // grid.z is limited to 65535
         const int n = n_items - first < 65535 ? n_items - first : 65535;
         dim3 grid(bx, 2, (unsigned)n);
@@ -184,10 +213,9 @@ void pc_launch_append(int dtype, const void *k, const void *v, int len, int n_kv
                       void *v_store, PcMsgEntry *table, int msg_id, hipStream_t st)
 {
     if (dtype == 1) {
-        const int64_t nk = (int64_t)len * n_kv_heads * (D / 4);
-        const int64_t nv = (int64_t)((len + PC_VGROUP - 1) / PC_VGROUP) * n_kv_heads * (D / 2);
-        const int64_t n = nk > nv ? nk : nv;
-        dim3 grid((unsigned)((n + 255) / 256), 2);
+        const int64_t bk = ((int64_t)len + APP_TB - 1) / APP_TB;
+        const int64_t bv = ((int64_t)((len + PC_VGROUP - 1) / PC_VGROUP) * n_kv_heads * (D / 2) + 255) / 256;
+        dim3 grid((unsigned)(bk > bv ? bk : bv), 2);
         pc_append_bf16_kernel<<<grid, 256, 0, st>>>((const uint16_t *)k, (const uint16_t *)v, len, n_kv_heads, D,
                                                     slot_start, slots, inv_freq, (uint16_t *)k_store,
                                                     (uint16_t *)v_store, table, msg_id);

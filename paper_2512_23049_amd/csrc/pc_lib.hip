@@ -172,6 +172,7 @@ int32_t pc_append_message(pc_cache *c, const void *k, const void *v, int32_t len
     if (!c) return PC_ERR_INVALID_ARG;
     if (len < 1) return pc_fail(c, PC_ERR_INVALID_ARG, "append: len = %d must be >= 1", len);
     if (!c->host_only && (!k || !v)) return pc_fail(c, PC_ERR_INVALID_ARG, "append: null k or v");
+    if (!c->host_only && (((uintptr_t)k | (uintptr_t)v) & 15)) return pc_fail(c, PC_ERR_INVALID_ARG, "append: k and v must be 16-byte aligned");
     if (!msg_id) return pc_fail(c, PC_ERR_INVALID_ARG, "append: null msg_id");
     if ((int64_t)c->msgs.size() >= c->cfg.max_messages)
         return pc_fail(c, PC_ERR_NO_SPACE, "append: message table full (%d)", c->cfg.max_messages);
@@ -240,6 +241,8 @@ int32_t pc_append_messages(pc_cache *c, int32_t n, const void *const *k, const v
     for (int j = 0; j < n; ++j) {
         if (lens[j] < 1) return pc_fail(c, PC_ERR_INVALID_ARG, "append_messages: message %d has len = %d", j, lens[j]);
         if (!c->host_only && (!k[j] || !v[j])) return pc_fail(c, PC_ERR_INVALID_ARG, "append_messages: message %d has null k or v", j);
+        if (!c->host_only && (((uintptr_t)k[j] | (uintptr_t)v[j]) & 15))
+            return pc_fail(c, PC_ERR_INVALID_ARG, "append_messages: k and v of message %d must be 16-byte aligned", j);
         const int32_t res = std::max(reserves ? reserves[j] : 0, lens[j]);
         int64_t start = 0;
         if (!take_slots(spans, next, c->slots, res, start))
