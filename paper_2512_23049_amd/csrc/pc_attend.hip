@@ -56,7 +56,9 @@ int32_t pc_attend(pc_cache *c, const pc_call *calls, int32_t n_calls, const void
     }
     if (P.n_merge_rows > 0) {
         ProfScope ps(c, 4, st);
-        pc_launch_merge(c->cfg.dtype, (const PcMergeRow *)(w + P.lay.merge_rows), P.n_merge_rows, L.part_o, L.part_ml, out, lse,
+        const PcMergeRow *rows = (const PcMergeRow *)(w + P.lay.merge_rows);
+        pc_launch_merge(c->cfg.dtype, rows, P.n_merge_few, 1, L.part_o, L.part_ml, out, lse, c->cfg.n_q_heads, c->D, st);
+        pc_launch_merge(c->cfg.dtype, rows + P.n_merge_few, P.n_merge_rows - P.n_merge_few, 4, L.part_o, L.part_ml, out, lse,
                         c->cfg.n_q_heads, c->D, st);
         PC_HIP(c, hipGetLastError());
     }

@@ -129,7 +129,7 @@ struct PlanLayout {
 struct Planned {
     PlanLayout lay;
     int n_calls = 0, total_sel = 0, total_q = 0, total_seg = 0, n_dec = 0, n_pre = 0, pre_waves = 4;
-    int n_merge_rows = 0;
+    int n_merge_rows = 0, n_merge_few = 0;               // rows to merge; the first n_merge_few have few splits
     int n_sh_items = 0;
     size_t n_sh_pos = 0;
     std::vector<Resolved> res;

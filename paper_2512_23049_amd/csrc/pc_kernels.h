@@ -40,7 +40,8 @@ void pc_launch_build_plan(const PcCallDesc *calls, int n_calls, const int2 *sel,
 void pc_launch_expand_tables(const PcSegment *segs, const int32_t *seg_kvoff, int n_seg, int64_t n_kv,
                              int32_t *kv_slot, int32_t *kv_pos, hipStream_t st);
 
-void pc_launch_merge(int dtype, const PcMergeRow *merge_rows, int n_merge_rows, const uint16_t *part_o,
+// split_lanes: 1, or 4 for rows with many splits (their splits are shared out over four lanes)
+void pc_launch_merge(int dtype, const PcMergeRow *merge_rows, int n_merge_rows, int split_lanes, const uint16_t *part_o,
                      const float *part_ml, void *out, float *lse, int n_q_heads, int D, hipStream_t st);
 
 void pc_launch_attend_f32(const PcLaunch &L, const int32_t *row_call, int total_q, int D, hipStream_t st);

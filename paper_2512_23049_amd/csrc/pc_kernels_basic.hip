@@ -635,39 +635,48 @@ void pc_launch_expand_tables(const PcSegment *segs, const int32_t *seg_kvoff, in
 // K5: merge of KV splits.  Each split s of a row holds its own normalised output O_s
 // (fp16), a running maximum m_s (scaled log2 domain) and a sum l_s; the result is
 //   m = max m_s,  w_s = l_s 2^(m_s - m),  l = sum w_s,  O = sum w_s O_s / l
-// taken in split order (deterministic; no atomics), four splits at a time with the
-// running maximum carried from one group of four to the next.
-// Sixteen threads per (row, head), a thread owns eight of the 128 dimensions (one 16-byte
-// load per split).  The kernel is bound by the latency of its dependent loads, so there are
-// only two levels of them: the row's descriptor, then the sums and outputs of four splits
-// together.
+// in a fixed order (deterministic; no atomics).
+// SL * 16 threads per (row, head): a thread = (one of SL equal parts of the splits, eight of the 128
+// dimensions).  It folds its part in split order, four splits per round of loads (one 16-byte load
+// per split); for SL = 4 (rows with many splits, a wave per (row, head)) the four parts are then
+// combined pairwise across lanes.  The kernel is bound by the latency of its dependent loads, so
+// there are few levels of them: the row's descriptor, then the sums and outputs of up to four
+// splits together.
 // ----------------------------------------------------------------------------------
+template <int SL>
 __global__ __launch_bounds__(256) void pc_merge_kernel(
     const PcMergeRow *__restrict__ merge_rows, const uint16_t *__restrict__ part_o,
     const float *__restrict__ part_ml, uint16_t *__restrict__ out, float *__restrict__ lse, int n_q_heads,
     int n_pairs)
 {
     constexpr int D = 128;
-    const int pair = blockIdx.x * 16 + (threadIdx.x >> 4), sub = threadIdx.x & 15;
-    if (pair >= n_pairs) return;
+    constexpr int TPP = 16 * SL;                         // threads per (row, head)
+    const int pair = blockIdx.x * (256 / TPP) + (int)threadIdx.x / TPP;
+    if (pair >= n_pairs) return;                         // (SL = 4: whole waves)
+    const int sub = threadIdx.x & 15, sg = ((int)threadIdx.x % TPP) >> 4;
     const int h = pair % n_q_heads;
     const PcMergeRow mr = merge_rows[pair / n_q_heads];
+    const int part = (mr.n_splits + SL - 1) / SL;
+    const int s_begin = sg * part, s_end = min(s_begin + part, mr.n_splits);
     float m = -INFINITY, l = 0.f, o[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) o[j] = 0.f;
-    for (int s0 = 0; s0 < mr.n_splits; s0 += 4) {
+    for (int s0 = s_begin; s0 < s_end; s0 += 4) {
         float2 ml[4];
         uint4 v[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            const int s = min(s0 + u, mr.n_splits - 1);
-            const int64_t pr = (int64_t)mr.part_row0 + (int64_t)s * mr.n_q;
-            ml[u] = *reinterpret_cast<const float2 *>(part_ml + (pr * n_q_heads + h) * 2);
-            v[u] = *reinterpret_cast<const uint4 *>(part_o + (pr * n_q_heads + h) * D + 8 * sub);
+            ml[u] = make_float2(-INFINITY, 0.f);
+            v[u] = make_uint4(0, 0, 0, 0);
+            if (s0 + u < s_end) {
+                const int64_t pr = (int64_t)mr.part_row0 + (int64_t)(s0 + u) * mr.n_q;
+                ml[u] = *reinterpret_cast<const float2 *>(part_ml + (pr * n_q_heads + h) * 2);
+                v[u] = *reinterpret_cast<const uint4 *>(part_o + (pr * n_q_heads + h) * D + 8 * sub);
+            }
         }
         float m_new = m;
 #pragma unroll
-        for (int u = 0; u < 4; ++u) m_new = fmaxf(m_new, ml[u].x);          // (a repeated last split changes nothing)
+        for (int u = 0; u < 4; ++u) m_new = fmaxf(m_new, ml[u].x);
         if (m_new == -INFINITY) continue;
         const float keep = (m > -INFINITY) ? exp2f(m - m_new) : 0.f;
         l *= keep;
@@ -676,7 +685,6 @@ __global__ __launch_bounds__(256) void pc_merge_kernel(
         m = m_new;
 #pragma unroll
         for (int u = 0; u < 4; ++u) {                    // in split order
-            if (s0 + u >= mr.n_splits) break;
             const float w = (ml[u].x > -INFINITY) ? ml[u].y * exp2f(ml[u].x - m) : 0.f;
             l += w;
             const uint32_t d[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
@@ -687,6 +695,19 @@ __global__ __launch_bounds__(256) void pc_merge_kernel(
             }
         }
     }
+    // parts 0+1 and 2+3, then the two halves; only the lanes of part 0 keep the result
+#pragma unroll
+    for (int mask = 16; mask < TPP; mask <<= 1) {
+        const float m_o = __shfl_xor(m, mask), l_o = __shfl_xor(l, mask);
+        const float m_c = fmaxf(m, m_o);
+        const float w_own = (m > -INFINITY) ? exp2f(m - m_c) : 0.f;
+        const float w_oth = (m_o > -INFINITY) ? exp2f(m_o - m_c) : 0.f;
+        l = l * w_own + l_o * w_oth;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) o[j] = o[j] * w_own + __shfl_xor(o[j], mask) * w_oth;
+        m = m_c;
+    }
+    if (sg != 0) return;
     const float inv = (l > 0.f) ? 1.f / l : 0.f;
     uint32_t packed[4];
 #pragma unroll
@@ -700,12 +721,15 @@ __global__ __launch_bounds__(256) void pc_merge_kernel(
 }
 
 // only bf16 caches with D = 128 split their work (the fp32 kernel never does)
-void pc_launch_merge(int dtype, const PcMergeRow *merge_rows, int n_merge_rows, const uint16_t *part_o,
+void pc_launch_merge(int dtype, const PcMergeRow *merge_rows, int n_merge_rows, int split_lanes, const uint16_t *part_o,
                      const float *part_ml, void *out, float *lse, int n_q_heads, int D, hipStream_t st)
 {
     if (n_merge_rows <= 0 || dtype != 1 || D != 128) return;
     const int n_pairs = n_merge_rows * n_q_heads;
-    pc_merge_kernel<<<(n_pairs + 15) / 16, 256, 0, st>>>(merge_rows, part_o, part_ml, (uint16_t *)out, lse, n_q_heads, n_pairs);
+    if (split_lanes == 4)
+        pc_merge_kernel<4><<<(n_pairs + 3) / 4, 256, 0, st>>>(merge_rows, part_o, part_ml, (uint16_t *)out, lse, n_q_heads, n_pairs);
+    else
+        pc_merge_kernel<1><<<(n_pairs + 15) / 16, 256, 0, st>>>(merge_rows, part_o, part_ml, (uint16_t *)out, lse, n_q_heads, n_pairs);
 }
 
 // ----------------------------------------------------------------------------------

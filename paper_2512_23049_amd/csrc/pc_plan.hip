@@ -156,6 +156,8 @@ struct SharedPlan {
 // exceeds what a union tile costs there (a workgroup's pass over it for all rows: 8.7 ns per tile
 // and KV head with the chip full) relative to a tile streamed by one call (1.5 to 1.7 ns).
 constexpr double SHARE_MIN = 6.0;
+// rows with more splits than this are merged by four lanes per 8 dimensions
+constexpr int MERGE_MANY_SPLITS = 8;
 
 static void plan_shared(const pc_cache *c, std::vector<Resolved> &res, const std::vector<int> &q_off, int g, SharedPlan &sp)
 {
@@ -389,12 +391,19 @@ int32_t pc_plan_and_stage(pc_cache *c, const pc_call *calls, int32_t n_calls, bo
         if (cds[i].n_sel > 0) std::memcpy(hs + cds[i].sel_off, r.sel.data(), sizeof(int2) * (size_t)cds[i].n_sel);
         std::memcpy(hq + cds[i].q_off, r.q_pos.data(), sizeof(int32_t) * r.q_pos.size());
         for (int q = 0; q < r.n_q; ++q) hr[cds[i].q_off + q] = i;
-        if (cds[i].n_splits > 1)
-            for (int q = 0; q < r.n_q; ++q) hm[P.n_merge_rows++] = PcMergeRow{cds[i].q_off + q, cds[i].part_off + q, cds[i].n_splits, r.n_q};
     }
-    for (const PcShGroup &gr : sp.groups)
-        if (gr.n_splits > 1)
-            for (int q = 0; q < gr.n_rows; ++q) hm[P.n_merge_rows++] = PcMergeRow{gr.row0 + q, gr.part_off + q, gr.n_splits, gr.n_rows};
+    // rows to merge: those with few splits first, then those with many (they get four lanes per 8 dimensions)
+    for (int pass = 0; pass < 2; ++pass) {
+        auto wanted = [&](int n_splits) { return n_splits > 1 && (n_splits > MERGE_MANY_SPLITS) == (pass == 1); };
+        for (int i = 0; i < n_calls; ++i)
+            if (wanted(cds[i].n_splits))
+                for (int q = 0; q < P.res[i].n_q; ++q)
+                    hm[P.n_merge_rows++] = PcMergeRow{cds[i].q_off + q, cds[i].part_off + q, cds[i].n_splits, P.res[i].n_q};
+        for (const PcShGroup &gr : sp.groups)
+            if (wanted(gr.n_splits))
+                for (int q = 0; q < gr.n_rows; ++q) hm[P.n_merge_rows++] = PcMergeRow{gr.row0 + q, gr.part_off + q, gr.n_splits, gr.n_rows};
+        if (pass == 0) P.n_merge_few = P.n_merge_rows;
+    }
     if (!dec.empty()) std::memcpy(h + P.lay.items_dec, dec.data(), sizeof(PcItem) * dec.size());
     if (!pre.empty()) std::memcpy(h + P.lay.items_pre, pre.data(), sizeof(PcItem) * pre.size());
     if (!sp.items.empty()) {
