@@ -160,7 +160,7 @@ def test_edge_cases_bf16(hip):
 
 def test_empty_batch_and_errors(hip):
     import torch
-    from paper_2512_23049_amd import PcError, PC_ERR_BAD_MSG_ID, PC_ERR_SHAPE, PC_ERR_NO_SPACE
+    from paper_2512_23049_amd import PcError, PC_ERR_BAD_MSG_ID, PC_ERR_INVALID_ARG, PC_ERR_SHAPE, PC_ERR_NO_SPACE
     from pc_inputs import Call
     w = gen.small_random(5, dtype="bf16", n_q_heads=8, n_kv_heads=2, head_dim=128, n_msgs=3, n_calls=1)
     cache = hip.make_cache(w)
@@ -184,6 +184,10 @@ def test_empty_batch_and_errors(hip):
         big = torch.zeros((10 ** 6, 2, 128), dtype=torch.bfloat16, device="cuda:0")
         cache.append_message(big.data_ptr(), big.data_ptr(), 10 ** 6)
     assert ei.value.code == PC_ERR_NO_SPACE
+    with pytest.raises(PcError) as ei:                               # K, V of an append must be 16-byte aligned
+        small = torch.zeros((2 * 2 * 128 + 8,), dtype=torch.bfloat16, device="cuda:0")
+        cache.append_message(small.data_ptr() + 2, small.data_ptr(), 2)
+    assert ei.value.code == PC_ERR_INVALID_ARG
     torch.cuda.synchronize()
     assert (out == 1).all()                                          # failed calls enqueue nothing
     cache.close()
