@@ -77,9 +77,9 @@ extern "C" {
 typedef struct pc_cache pc_cache;
 
 typedef struct {
-    int32_t  n_q_heads;        /* H_q  (multiple of n_kv_heads)                          */
+    int32_t  n_q_heads;        /* H_q  (multiple of n_kv_heads; PC_BF16: at most 16 per KV head) */
     int32_t  n_kv_heads;       /* H_kv                                                  */
-    int32_t  head_dim;         /* D: 64 or 128                                          */
+    int32_t  head_dim;         /* D: 64 or 128 (PC_BF16: 128); other shapes: PC_ERR_SHAPE */
     int32_t  dtype;            /* PC_F32 | PC_BF16: type of k, v, q, out and of storage */
     float    rope_theta;       /* RoPE base, e.g. 1e4 or 5e5                            */
     float    softmax_scale;    /* 0 -> 1/sqrt(D)                                        */
