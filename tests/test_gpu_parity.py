@@ -29,7 +29,10 @@ def hip():
 
 
 def run_and_compare(hip, w, rows_per_call=None, calls_subset=None, events=None, tuning=None, batch_appends=False,
-                    lse_rel=0.0, sharing=None):
+                    lse_rel=0.0, sharing=None, few_key_calls=False):
+    """few_key_calls: the batch is full of calls whose rows see a handful of keys, so that outputs are of order
+    one.  The bf16 result itself is then rounded by about 1.4e-3 of its size on average (a quarter ulp), which
+    the fixed mean bar cannot absorb: the mean bar of a call grows by 2^-9 times the mean size of its exact output."""
     import torch
     cache = hip.make_cache(w)
     if tuning:
@@ -54,7 +57,8 @@ def run_and_compare(hip, w, rows_per_call=None, calls_subset=None, events=None, 
             say(f"  event {k} call {ci}: rows={len(rows)} max_abs={d.max() if d.size else 0:.3e} "
                 f"mean_abs={d.mean() if d.size else 0:.3e}")
             assert d.size == 0 or d.max() <= tol["max_abs"]
-            assert d.size == 0 or d.mean() <= tol["mean_abs"]
+            mean_bar = tol["mean_abs"] + (2.0 ** -9 * float(np.abs(o).mean()) if (few_key_calls and d.size) else 0.0)
+            assert d.size == 0 or d.mean() <= mean_bar
             fin = np.isfinite(l)
             assert np.array_equal(np.isfinite(lse[rows]), fin)
             assert np.array_equal(np.isneginf(lse[rows]), np.isneginf(l))
@@ -476,3 +480,16 @@ def test_calls_with_more_than_a_thousand_parents(hip, sharing):
     w.events.append(Event("attend", calls=calls, q=q))
     tables_check(hip, w, max_calls=2)
     run_and_compare(hip, w, sharing=sharing)
+
+
+@pytest.mark.parametrize("sharing", [None, 2])
+def test_batch_of_fifteen_hundred_one_row_calls(hip, sharing):
+    """A large parallel step: 1500 one-row calls in one pc_attend (per-call walk, and groups on the shared walk)."""
+    w = gen.small_random(88, dtype="bf16", n_q_heads=8, n_kv_heads=2, head_dim=128, n_msgs=40, n_calls=1500, max_q=1)
+    run_and_compare(hip, w, sharing=sharing, few_key_calls=True)
+
+
+def test_batch_of_many_small_prefill_calls(hip):
+    """400 calls of up to 12 rows each in one pc_attend."""
+    w = gen.small_random(89, dtype="bf16", n_q_heads=8, n_kv_heads=2, head_dim=128, n_msgs=40, n_calls=400, max_q=12)
+    run_and_compare(hip, w, few_key_calls=True)
