@@ -155,38 +155,18 @@ def cpu_baseline(w, sample, unit, cores_hint=None):
             "seconds": dt}
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--skip-extras", action="store_true")
-    ap.add_argument("--skip-cpu", action="store_true")
-    ap.add_argument("--only", default="", help="comma list of sections: achievable,decode,long,longdecode,rounds,baseline,loop,reposition,backward")
-    ap.add_argument("--copy-probe-mib", type=int, default=0,
-                    help="also launch one plain device copy of this many MiB (reference for scaling rocprofv3 "
-                         "FETCH_SIZE / WRITE_SIZE counters)")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
-              file=sys.stderr)
-        sys.exit(2)
+class Ctx:
+    """What the sections share: the command line, the modules that need the GPU, the JSON line being built."""
 
-    import torch
-    import pc_inputs as gen
-    from paper_2512_23049_amd import harness
-    assert torch.cuda.is_available(), "bench.py needs the MI355X"
-    only = set(x for x in args.only.split(",") if x)
-    bytes_per_token = None
-    if args.copy_probe_mib > 0:
-        src = torch.ones(args.copy_probe_mib << 18, dtype=torch.float32, device="cuda:0")
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
+    def __init__(self, args, torch, gen, harness):
+        self.args, self.torch, self.gen, self.harness = args, torch, gen, harness
+        self.line = {}
+        self.achievable = None           # filled by section_achievable, read by section_decode
 
-    # ---------------------------------------------------------------- headline: prefill
+
+def section_headline(cx):
+    """configs[1], the workload the metric is quoted on: fills the contract's fields of the JSON line."""
+    args, torch, gen, harness = cx.args, cx.torch, cx.gen, cx.harness
     w2 = gen.single_prefill()
     sec, sec_prof, kern, vp = bench_attend_workload("single_prefill", w2, args.steps, args.warmup, torch, harness)
     pairs = sum(v[3] for v in vp)
@@ -214,348 +194,412 @@ def main():
                  "desc": "configs[1] whole: all 512 query rows, all 32 heads, all keys (under a second of CPU "
                          "work; the oracle is the plain definition on BLAS)"}, "TFLOP/s")
     del w2
+    cx.line = line
 
-    # ------------------------------------ what this chip sustains for the two resources (probe kernels of the library)
-    achievable = None
-    if not args.skip_extras and (not only or "achievable" in only):
-        from paper_2512_23049_amd import probe_hbm_read, probe_mfma_bf16
-        sink = torch.zeros(4, dtype=torch.float32, device="cuda:0")
-        g = torch.Generator(device="cpu").manual_seed(7)
-        ops_rand = torch.randn(8192, generator=g).to(torch.bfloat16).to("cuda:0")
-        ops_zero = torch.zeros(8192, dtype=torch.bfloat16, device="cuda:0")
-        big = torch.ones(1 << 29, dtype=torch.float32, device="cuda:0")        # 2 GiB, several times the last-level cache
-        st = torch.cuda.current_stream().cuda_stream
-        achievable = {
-            "mfma_bf16_random_operands_tflops": probe_mfma_bf16(ops_rand.data_ptr(), ops_rand.numel() * 2, sink.data_ptr(),
-                                                                iters=16384, reps=5, stream=st),
-            "mfma_bf16_zero_operands_tflops": probe_mfma_bf16(ops_zero.data_ptr(), ops_zero.numel() * 2, sink.data_ptr(),
-                                                              iters=16384, reps=5, stream=st),
-            "hbm_stream_read_gbs": probe_hbm_read(big.data_ptr(), big.numel() * 4, sink.data_ptr(), reps=10, stream=st),
-            "how": "pc_probe_mfma_bf16 (bare 32x32x16 bf16 MFMA loop, 2 waves per SIMD on every CU; N(0,1) operands, "
-                   "then all-zero operands) and pc_probe_hbm_read (2 GiB streaming read)",
-        }
-        del big, ops_rand, ops_zero
-        line["achievable"] = achievable
-        if line["roofline"]["achieved"]:
-            line["roofline"]["frac_of_achievable"] = (line["roofline"]["achieved"]
-                                                      / achievable["mfma_bf16_random_operands_tflops"])
 
-    # ---------------------------------------------------------------- decode (configs[2])
-    if not args.skip_extras and (not only or "decode" in only):
-        w3 = gen.parallel_decode()
-        sec, sec_prof, kern, vp = bench_attend_workload("parallel_decode", w3, args.steps, args.warmup, torch, harness,
-                                                        reappend_self=False)
-        bytes_per_token = 2 * w3.n_kv_heads * w3.head_dim * 2
-        b_logical = sum(v[1] + v[2] for v in vp) * bytes_per_token
-        ev = w3.events[-1]
-        lens = w3.message_lengths()
-        uniq = set()
-        for c in ev.calls:
-            uniq.update(m for m, _ in c.sel)
-            uniq.add(c.self_msg)
-        b_unique = sum(lens[m] for m in uniq) * bytes_per_token
-        k_dec = kern.get("decode", {}).get("avg_us")
-        traffic_dec = measured_traffic("pc_decode_bf16_kernel", "parallel_decode")
-        line["decode"] = {
-            "workload": "configs[2] parallel decode: 64 calls x (2048-token system + 8 pool messages + 64-token tail), "
-                        "one query token per call; step = pc_attend",
-            "value": b_logical / sec / 1e9, "unit": "GB/s (logical bytes: 4096 B per call-selected token)",
-            "ms_per_step": sec * 1e3, "B_logical": b_logical, "B_unique": b_unique,
-            "roofline": {"bound": "hbm", "kernel": "pc_decode_bf16_kernel",
-                         "achieved": (b_logical / (k_dec * 1e-6) / 1e9) if k_dec else None, "peak": HBM_PEAK_GBS,
-                         "unit": "GB/s", "frac": (b_logical / (k_dec * 1e-6) / 1e9 / HBM_PEAK_GBS) if k_dec else None,
-                         "traffic": traffic_dec, "avg_kernel_us": k_dec,
-                         # calls share messages (B_unique < B_logical), so the logical rate is an EFFECTIVE one and
-                         # may exceed the HBM peak; the HBM claim rests on the bytes rocprofv3 counted per launch
-                         "effective": True,
-                         "hbm_measured_gbs": (traffic_dec / (k_dec * 1e-6) / 1e9) if (k_dec and traffic_dec) else None,
-                         "hbm_measured_frac": (traffic_dec / (k_dec * 1e-6) / 1e9 / HBM_PEAK_GBS) if (k_dec and traffic_dec) else None},
-            "kernels_us": {k: v["avg_us"] for k, v in kern.items()},
-        }
-        if achievable and line["decode"]["roofline"]["hbm_measured_gbs"]:
-            line["decode"]["roofline"]["hbm_measured_frac_of_achievable"] = (
-                line["decode"]["roofline"]["hbm_measured_gbs"] / achievable["hbm_stream_read_gbs"])
-        if not args.skip_cpu:
-            line["decode"]["cpu_baseline"] = cpu_baseline(
-                w3, {"calls": list(range(64)), "rows": lambda n: [0],
-                     "desc": "configs[2] whole: all 64 calls"}, "GB/s")
-        del w3
+def section_achievable(cx):
+    """What this chip sustains for the two resources the kernels are priced against (probe kernels of the library)."""
+    args, torch, gen, harness, line = cx.args, cx.torch, cx.gen, cx.harness, cx.line
+    from paper_2512_23049_amd import probe_hbm_read, probe_mfma_bf16
+    sink = torch.zeros(4, dtype=torch.float32, device="cuda:0")
+    g = torch.Generator(device="cpu").manual_seed(7)
+    ops_rand = torch.randn(8192, generator=g).to(torch.bfloat16).to("cuda:0")
+    ops_zero = torch.zeros(8192, dtype=torch.bfloat16, device="cuda:0")
+    big = torch.ones(1 << 29, dtype=torch.float32, device="cuda:0")        # 2 GiB, several times the last-level cache
+    st = torch.cuda.current_stream().cuda_stream
+    achievable = {
+        "mfma_bf16_random_operands_tflops": probe_mfma_bf16(ops_rand.data_ptr(), ops_rand.numel() * 2, sink.data_ptr(),
+                                                            iters=16384, reps=5, stream=st),
+        "mfma_bf16_zero_operands_tflops": probe_mfma_bf16(ops_zero.data_ptr(), ops_zero.numel() * 2, sink.data_ptr(),
+                                                          iters=16384, reps=5, stream=st),
+        "hbm_stream_read_gbs": probe_hbm_read(big.data_ptr(), big.numel() * 4, sink.data_ptr(), reps=10, stream=st),
+        "how": "pc_probe_mfma_bf16 (bare 32x32x16 bf16 MFMA loop, 2 waves per SIMD on every CU; N(0,1) operands, "
+               "then all-zero operands) and pc_probe_hbm_read (2 GiB streaming read)",
+    }
+    del big, ops_rand, ops_zero
+    line["achievable"] = achievable
+    if line["roofline"]["achieved"]:
+        line["roofline"]["frac_of_achievable"] = (line["roofline"]["achieved"]
+                                                  / achievable["mfma_bf16_random_operands_tflops"])
+    cx.achievable = achievable
 
-    # ---------------------------------------------------------------- long context (configs[4])
-    if not args.skip_extras and (not only or "long" in only):
-        w5 = gen.long_context()
-        steps5 = max(3, min(args.steps, 20))
-        sec, sec_prof, kern, vp = bench_attend_workload("long_context", w5, steps5, 2, torch, harness)
-        pre = [v for v in vp if v[0] > 1]
-        dec = [v for v in vp if v[0] == 1]
-        f_pre = 4.0 * w5.head_dim * w5.n_q_heads * sum(v[3] for v in pre)
-        b_dec = sum(v[1] + v[2] for v in dec) * 4096
-        k_pre = kern.get("prefill", {}).get("avg_us")
-        k_dec = kern.get("decode", {}).get("avg_us")
-        traffic_dec5 = measured_traffic("pc_decode_shared_bf16_kernel", "long_context")
-        line.setdefault("extras", {})["long_context"] = {
-            "workload": "configs[4]: 32 decode calls + one 2048-row causal prefill over ~64k selected tokens each, "
-                        "64 q heads / 8 kv heads; step = append new messages + one pc_attend",
-            "ms_per_step": sec * 1e3, "steps": steps5,
-            "prefill_tflops_kernel": (f_pre / (k_pre * 1e-6) / 1e12) if k_pre else None,
-            "prefill_frac_mfma_peak": (f_pre / (k_pre * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS) if k_pre else None,
-            # the 32 decode calls list mostly the same messages: they are served by the shared walk, which reads the
-            # union of their messages once (decode_B_unique), so the logical rate is an EFFECTIVE one, far above the
-            # HBM peak; the bytes rocprofv3 counted per launch are in profiles/attention_kernels_hbm_traffic.txt
-            "decode_walk": "shared (pc_decode_shared_bf16_kernel)",
-            "decode_gbs_logical_kernel": (b_dec / (k_dec * 1e-6) / 1e9) if k_dec else None,
-            "decode_frac_hbm_peak_logical": (b_dec / (k_dec * 1e-6) / 1e9 / HBM_PEAK_GBS) if k_dec else None,
-            "decode_effective": True,
-            "decode_hbm_measured_gbs": (traffic_dec5 / (k_dec * 1e-6) / 1e9) if (k_dec and traffic_dec5) else None,
-            "prefill_flops": f_pre, "decode_B_logical": b_dec,
-            "kernels_us": {k: v["avg_us"] for k, v in kern.items()},
-        }
-        del w5
 
-    # ------------------------------------------- the decode calls of configs[4] on their own (a decode step)
-    if not args.skip_extras and (not only or "longdecode" in only):
-        w5d = gen.long_context(n_prefill_q=0)
-        steps5 = max(3, min(args.steps, 50))
-        out_ld = {}
-        for name, mode in (("shared_walk", 0), ("per_call_walk", 1)):
-            sec, _, kern, vp = bench_attend_workload("long_context_decode", w5d, steps5, 3, torch, harness,
-                                                     reappend_self=False, sharing=mode)
-            b_dec = sum(v[1] + v[2] for v in vp) * 4096
-            out_ld[name] = {"us_per_step": sec * 1e6, "gbs_logical": b_dec / sec / 1e9,
-                            "kernels_us": {k: v["avg_us"] for k, v in kern.items()}}
-        line.setdefault("extras", {})["long_context_decode_only"] = {
-            "workload": "the 32 one-row calls of configs[4] alone (each ~64k selected tokens of the same 512 messages); "
-                        "step = one pc_attend, host planning included; shared walk (default rule) against "
-                        "pc_set_decode_sharing(1)",
-            "B_logical": b_dec, **out_ld}
-        del w5d
+def section_decode(cx):
+    """configs[2]: the parallel decode step, HBM roofline on logical and on measured bytes."""
+    args, torch, gen, harness, line = cx.args, cx.torch, cx.gen, cx.harness, cx.line
+    achievable = cx.achievable
+    w3 = gen.parallel_decode()
+    sec, sec_prof, kern, vp = bench_attend_workload("parallel_decode", w3, args.steps, args.warmup, torch, harness,
+                                                    reappend_self=False)
+    bytes_per_token = 2 * w3.n_kv_heads * w3.head_dim * 2
+    b_logical = sum(v[1] + v[2] for v in vp) * bytes_per_token
+    ev = w3.events[-1]
+    lens = w3.message_lengths()
+    uniq = set()
+    for c in ev.calls:
+        uniq.update(m for m, _ in c.sel)
+        uniq.add(c.self_msg)
+    b_unique = sum(lens[m] for m in uniq) * bytes_per_token
+    k_dec = kern.get("decode", {}).get("avg_us")
+    traffic_dec = measured_traffic("pc_decode_bf16_kernel", "parallel_decode")
+    line["decode"] = {
+        "workload": "configs[2] parallel decode: 64 calls x (2048-token system + 8 pool messages + 64-token tail), "
+                    "one query token per call; step = pc_attend",
+        "value": b_logical / sec / 1e9, "unit": "GB/s (logical bytes: 4096 B per call-selected token)",
+        "ms_per_step": sec * 1e3, "B_logical": b_logical, "B_unique": b_unique,
+        "roofline": {"bound": "hbm", "kernel": "pc_decode_bf16_kernel",
+                     "achieved": (b_logical / (k_dec * 1e-6) / 1e9) if k_dec else None, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": (b_logical / (k_dec * 1e-6) / 1e9 / HBM_PEAK_GBS) if k_dec else None,
+                     "traffic": traffic_dec, "avg_kernel_us": k_dec,
+                     # calls share messages (B_unique < B_logical), so the logical rate is an EFFECTIVE one and
+                     # may exceed the HBM peak; the HBM claim rests on the bytes rocprofv3 counted per launch
+                     "effective": True,
+                     "hbm_measured_gbs": (traffic_dec / (k_dec * 1e-6) / 1e9) if (k_dec and traffic_dec) else None,
+                     "hbm_measured_frac": (traffic_dec / (k_dec * 1e-6) / 1e9 / HBM_PEAK_GBS) if (k_dec and traffic_dec) else None},
+        "kernels_us": {k: v["avg_us"] for k, v in kern.items()},
+    }
+    if achievable and line["decode"]["roofline"]["hbm_measured_gbs"]:
+        line["decode"]["roofline"]["hbm_measured_frac_of_achievable"] = (
+            line["decode"]["roofline"]["hbm_measured_gbs"] / achievable["hbm_stream_read_gbs"])
+    if not args.skip_cpu:
+        line["decode"]["cpu_baseline"] = cpu_baseline(
+            w3, {"calls": list(range(64)), "rows": lambda n: [0],
+                 "desc": "configs[2] whole: all 64 calls"}, "GB/s")
+    del w3
 
-    # ---------------------------------------------------------------- multi-agent rounds (configs[3])
-    if not args.skip_extras and (not only or "rounds" in only):
-        w4 = gen.multi_agent_rounds()
-        dw = harness.DeviceWorkload(w4)
-        reps = max(3, min(args.steps, 20))
-        caches = [harness.make_cache(w4) for _ in range(reps + 2)]
-        for c in caches[:2]:
-            dw.run(c, want_lse=False, batch_appends=True)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for c in caches[2:]:
-            dw.run(c, want_lse=False, batch_appends=True)
-        torch.cuda.synchronize()
-        sec4 = (time.perf_counter() - t0) / reps
-        for c in caches:
-            c.close()
-        f_round = [4.0 * w4.head_dim * w4.n_q_heads * sum(v[3] for v in visible_pairs(w4, e))
-                   for e in w4.events if e.kind == "attend"]
-        f4 = sum(f_round)
-        # one more sequence with the library's kernel events on, read round by round: kernel time per class
-        # (append GB/s on 2 * 4096 B per token, prefill TFLOP/s on the kernel's own time) and wall time per round
-        c = harness.make_cache(w4)
+
+def section_long_context(cx):
+    """configs[4]: 32 decode calls and one 2048-row prefill in one batch."""
+    args, torch, gen, harness, line = cx.args, cx.torch, cx.gen, cx.harness, cx.line
+    w5 = gen.long_context()
+    steps5 = max(3, min(args.steps, 20))
+    sec, sec_prof, kern, vp = bench_attend_workload("long_context", w5, steps5, 2, torch, harness)
+    pre = [v for v in vp if v[0] > 1]
+    dec = [v for v in vp if v[0] == 1]
+    f_pre = 4.0 * w5.head_dim * w5.n_q_heads * sum(v[3] for v in pre)
+    b_dec = sum(v[1] + v[2] for v in dec) * 4096
+    k_pre = kern.get("prefill", {}).get("avg_us")
+    k_dec = kern.get("decode", {}).get("avg_us")
+    traffic_dec5 = measured_traffic("pc_decode_shared_bf16_kernel", "long_context")
+    line.setdefault("extras", {})["long_context"] = {
+        "workload": "configs[4]: 32 decode calls + one 2048-row causal prefill over ~64k selected tokens each, "
+                    "64 q heads / 8 kv heads; step = append new messages + one pc_attend",
+        "ms_per_step": sec * 1e3, "steps": steps5,
+        "prefill_tflops_kernel": (f_pre / (k_pre * 1e-6) / 1e12) if k_pre else None,
+        "prefill_frac_mfma_peak": (f_pre / (k_pre * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS) if k_pre else None,
+        # the 32 decode calls list mostly the same messages: they are served by the shared walk, which reads the
+        # union of their messages once (decode_B_unique), so the logical rate is an EFFECTIVE one, far above the
+        # HBM peak; the bytes rocprofv3 counted per launch are in profiles/attention_kernels_hbm_traffic.txt
+        "decode_walk": "shared (pc_decode_shared_bf16_kernel)",
+        "decode_gbs_logical_kernel": (b_dec / (k_dec * 1e-6) / 1e9) if k_dec else None,
+        "decode_frac_hbm_peak_logical": (b_dec / (k_dec * 1e-6) / 1e9 / HBM_PEAK_GBS) if k_dec else None,
+        "decode_effective": True,
+        "decode_hbm_measured_gbs": (traffic_dec5 / (k_dec * 1e-6) / 1e9) if (k_dec and traffic_dec5) else None,
+        "prefill_flops": f_pre, "decode_B_logical": b_dec,
+        "kernels_us": {k: v["avg_us"] for k, v in kern.items()},
+    }
+    del w5
+
+
+def section_long_context_decode(cx):
+    """The decode calls of configs[4] as a step of their own: shared walk against per-call walk."""
+    args, torch, gen, harness, line = cx.args, cx.torch, cx.gen, cx.harness, cx.line
+    w5d = gen.long_context(n_prefill_q=0)
+    steps5 = max(3, min(args.steps, 50))
+    out_ld = {}
+    for name, mode in (("shared_walk", 0), ("per_call_walk", 1)):
+        sec, _, kern, vp = bench_attend_workload("long_context_decode", w5d, steps5, 3, torch, harness,
+                                                 reappend_self=False, sharing=mode)
+        b_dec = sum(v[1] + v[2] for v in vp) * 4096
+        out_ld[name] = {"us_per_step": sec * 1e6, "gbs_logical": b_dec / sec / 1e9,
+                        "kernels_us": {k: v["avg_us"] for k, v in kern.items()}}
+    line.setdefault("extras", {})["long_context_decode_only"] = {
+        "workload": "the 32 one-row calls of configs[4] alone (each ~64k selected tokens of the same 512 messages); "
+                    "step = one pc_attend, host planning included; shared walk (default rule) against "
+                    "pc_set_decode_sharing(1)",
+        "B_logical": b_dec, **out_ld}
+    del w5d
+
+
+def section_rounds(cx):
+    """configs[3]: multi-agent rounds, appends and prefills interleaved; whole sequences and a per-round breakdown."""
+    args, torch, gen, harness, line = cx.args, cx.torch, cx.gen, cx.harness, cx.line
+    w4 = gen.multi_agent_rounds()
+    dw = harness.DeviceWorkload(w4)
+    reps = max(3, min(args.steps, 20))
+    caches = [harness.make_cache(w4) for _ in range(reps + 2)]
+    for c in caches[:2]:
         dw.run(c, want_lse=False, batch_appends=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for c in caches[2:]:
+        dw.run(c, want_lse=False, batch_appends=True)
+    torch.cuda.synchronize()
+    sec4 = (time.perf_counter() - t0) / reps
+    for c in caches:
         c.close()
-        c = harness.make_cache(w4)
-        c.profile_enable(True)
-        c.profile_read(reset=True)
-        per_round, pending, tok_round = [], [], 0
+    f_round = [4.0 * w4.head_dim * w4.n_q_heads * sum(v[3] for v in visible_pairs(w4, e))
+               for e in w4.events if e.kind == "attend"]
+    f4 = sum(f_round)
+    # one more sequence with the library's kernel events on, read round by round: kernel time per class
+    # (append GB/s on 2 * 4096 B per token, prefill TFLOP/s on the kernel's own time) and wall time per round
+    c = harness.make_cache(w4)
+    dw.run(c, want_lse=False, batch_appends=True)
+    c.close()
+    c = harness.make_cache(w4)
+    c.profile_enable(True)
+    c.profile_read(reset=True)
+    per_round, pending, tok_round = [], [], 0
+    torch.cuda.synchronize()
+    t_r = time.perf_counter()
+    for s_ in dw.steps:
+        if s_[0] == "append":
+            pending.append(s_)
+            tok_round += s_[3]
+            continue
+        c.append_messages([p_[1].data_ptr() for p_ in pending], [p_[2].data_ptr() for p_ in pending],
+                          [p_[3] for p_ in pending], [p_[4] for p_ in pending])
+        pending = []
+        _, calls_, m_, q_, out_, lse_ = s_
+        c.attend(calls_, q_.data_ptr(), out_.data_ptr(), 0, 0, m_)
+        pr = c.profile_read(reset=True)                     # waits for the round's work
+        now = time.perf_counter()
+        k_app = pr["append"][0] * 1e-3
+        k_pre = pr["prefill"][0] * 1e-3
+        r = len(per_round)
+        per_round.append({"wall_ms": (now - t_r) * 1e3, "append_kernel_us": k_app * 1e6,
+                          "append_gbs": (2 * 4096 * tok_round / k_app / 1e9) if k_app > 0 else None,
+                          "prefill_kernel_us": k_pre * 1e6,
+                          "prefill_tflops_kernel": (f_round[r] / k_pre / 1e12) if k_pre > 0 else None,
+                          "other_kernels_us": sum(v[0] for k_, v in pr.items() if k_ not in ("append", "prefill")) * 1e3})
+        tok_round = 0
+        t_r = now
+    c.profile_enable(False)
+    c.close()
+    line.setdefault("extras", {})["multi_agent_rounds"] = {
+        "workload": "configs[3]: 8 agents x 6 rounds; per round one pc_append_messages of the 8 new 256-token messages "
+                    "and one pc_attend of the 8 prefill calls",
+        "ms_per_sequence": sec4 * 1e3, "tflops_incl_appends": f4 / sec4 / 1e12, "flops": f4, "reps": reps,
+        "per_round_with_kernel_events": per_round}
+    del w4
+
+
+def section_baseline(cx):
+    """The attention and append work a prefix-caching baseline would do for the same rounds."""
+    args, torch, gen, harness, line = cx.args, cx.torch, cx.gen, cx.harness, cx.line
+    def run_sequence(w, reps):
+        dw_ = harness.DeviceWorkload(w)
+        caches = [harness.make_cache(w) for _ in range(reps + 1)]
+        dw_.run(caches[0], want_lse=False)
         torch.cuda.synchronize()
-        t_r = time.perf_counter()
-        for s_ in dw.steps:
-            if s_[0] == "append":
-                pending.append(s_)
-                tok_round += s_[3]
-                continue
-            c.append_messages([p_[1].data_ptr() for p_ in pending], [p_[2].data_ptr() for p_ in pending],
-                              [p_[3] for p_ in pending], [p_[4] for p_ in pending])
-            pending = []
-            _, calls_, m_, q_, out_, lse_ = s_
-            c.attend(calls_, q_.data_ptr(), out_.data_ptr(), 0, 0, m_)
-            pr = c.profile_read(reset=True)                     # waits for the round's work
-            now = time.perf_counter()
-            k_app = pr["append"][0] * 1e-3
-            k_pre = pr["prefill"][0] * 1e-3
-            r = len(per_round)
-            per_round.append({"wall_ms": (now - t_r) * 1e3, "append_kernel_us": k_app * 1e6,
-                              "append_gbs": (2 * 4096 * tok_round / k_app / 1e9) if k_app > 0 else None,
-                              "prefill_kernel_us": k_pre * 1e6,
-                              "prefill_tflops_kernel": (f_round[r] / k_pre / 1e12) if k_pre > 0 else None,
-                              "other_kernels_us": sum(v[0] for k_, v in pr.items() if k_ not in ("append", "prefill")) * 1e3})
-            tok_round = 0
-            t_r = now
-        c.profile_enable(False)
-        c.close()
-        line.setdefault("extras", {})["multi_agent_rounds"] = {
-            "workload": "configs[3]: 8 agents x 6 rounds; per round one pc_append_messages of the 8 new 256-token messages "
-                        "and one pc_attend of the 8 prefill calls",
-            "ms_per_sequence": sec4 * 1e3, "tflops_incl_appends": f4 / sec4 / 1e12, "flops": f4, "reps": reps,
-            "per_round_with_kernel_events": per_round}
-        del w4
-
-    # ------------------------------------------------ attention work of a prefix-caching baseline
-    if not args.skip_extras and (not only or "baseline" in only):
-        def run_sequence(w, reps):
-            dw_ = harness.DeviceWorkload(w)
-            caches = [harness.make_cache(w) for _ in range(reps + 1)]
-            dw_.run(caches[0], want_lse=False)
-            torch.cuda.synchronize()
-            t0 = time.perf_counter()
-            for c_ in caches[1:]:
-                dw_.run(c_, want_lse=False)
-            torch.cuda.synchronize()
-            dt = (time.perf_counter() - t0) / reps
-            for c_ in caches:
-                c_.close()
-            fl, toks = 0.0, 0
-            for i, e in enumerate(w.events):
-                if e.kind == "attend":
-                    lens = w.message_lengths(upto_event=i)
-                    for c in e.calls:
-                        n_par = sum(lens[m] for m, _ in c.sel)
-                        L = lens[c.self_msg]
-                        fl += 4.0 * w.head_dim * w.n_q_heads * sum(n_par + L - c.n_q + r + 1 for r in range(c.n_q))
-                elif e.kind == "append":
-                    toks += int(e.k.shape[0])
-            return dt, fl, toks
-        comp = {}
-        for name, (na, nr) in {"8 agents x 6 rounds (configs[3])": (8, 6), "3 agents x 3 rounds (the paper's parallel debate)": (3, 3)}.items():
-            t_c, f_c, k_c = run_sequence(gen.multi_agent_rounds(n_agents=na, n_rounds=nr), 5)
-            t_b, f_b, k_b = run_sequence(gen.prefix_cache_baseline_rounds(n_agents=na, n_rounds=nr), 5)
-            comp[name] = {"choreographed_ms": t_c * 1e3, "baseline_ms": t_b * 1e3, "time_ratio": t_b / t_c,
-                          "choreographed_attention_gflop": f_c / 1e9, "baseline_attention_gflop": f_b / 1e9,
-                          "flop_ratio": f_b / f_c, "choreographed_tokens_encoded": k_c, "baseline_tokens_encoded": k_b}
-        line.setdefault("extras", {})["prefix_cache_baseline"] = {
-            "workload": "attention and cache-append work only, 256-token messages: choreographed rounds (each agent "
-                        "prefills its new message over the cached messages of all earlier rounds) against a prefix-caching "
-                        "baseline (each agent keeps its own prompt as prefix and encodes the other agents' last-round "
-                        "messages again with its new one); the model's other layers, which the baseline also runs again "
-                        "for every re-encoded token, are not part of this path",
-            **comp}
-
-    # ------------------------------------------------ decode loop: tails growing one token per step
-    if not args.skip_extras and (not only or "loop" in only):
-        w6 = gen.decode_loop()
-        dw = harness.DeviceWorkload(w6)
-        first_loop = next(i for i, s_ in enumerate(dw.steps) if s_[0] == "attend")
-        n_steps = sum(1 for s_ in dw.steps if s_[0] == "attend")
-        times = []
-        for rep in range(3):
-            cache = harness.make_cache(w6)
-            for s_ in dw.steps[:first_loop]:
-                cache.append_message(s_[1].data_ptr(), s_[2].data_ptr(), s_[3], s_[4])
-            torch.cuda.synchronize()
-            t0 = time.perf_counter()
-            for s_ in dw.steps[first_loop:]:
-                if s_[0] == "extend":
-                    cache.append_tokens_batch(s_[3], s_[1].data_ptr(), s_[2].data_ptr())
-                else:
-                    cache.attend(s_[1], s_[3].data_ptr(), s_[4].data_ptr(), 0, 0, s_[2])
-            torch.cuda.synchronize()
-            times.append(time.perf_counter() - t0)
-            cache.close()
-        sec6 = min(times[1:])
-        b6 = 0
-        for i, e in enumerate(w6.events):
+        t0 = time.perf_counter()
+        for c_ in caches[1:]:
+            dw_.run(c_, want_lse=False)
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / reps
+        for c_ in caches:
+            c_.close()
+        fl, toks = 0.0, 0
+        for i, e in enumerate(w.events):
             if e.kind == "attend":
-                lens = w6.message_lengths(upto_event=i)
-                b6 += sum(sum(lens[m] for m, _ in c.sel) + lens[c.self_msg] for c in e.calls) * 4096
-        n_calls6 = len(w6.events[-1].calls)
-        line.setdefault("extras", {})["decode_loop"] = {
-            "workload": "configs[2]-shaped parallel decode as a loop: 64 calls (2048-token system + 8 pool messages each), "
-                        "tails grow from 1 to 64 tokens; a step = pc_append_tokens_batch (one token per call) + pc_attend",
-            "steps": n_steps, "us_per_step": sec6 / n_steps * 1e6, "tokens_per_s": n_calls6 * n_steps / sec6,
-            "gbs_logical": b6 / sec6 / 1e9, "B_logical_total": b6}
-        del w6, dw
+                lens = w.message_lengths(upto_event=i)
+                for c in e.calls:
+                    n_par = sum(lens[m] for m, _ in c.sel)
+                    L = lens[c.self_msg]
+                    fl += 4.0 * w.head_dim * w.n_q_heads * sum(n_par + L - c.n_q + r + 1 for r in range(c.n_q))
+            elif e.kind == "append":
+                toks += int(e.k.shape[0])
+        return dt, fl, toks
+    comp = {}
+    for name, (na, nr) in {"8 agents x 6 rounds (configs[3])": (8, 6), "3 agents x 3 rounds (the paper's parallel debate)": (3, 3)}.items():
+        t_c, f_c, k_c = run_sequence(gen.multi_agent_rounds(n_agents=na, n_rounds=nr), 5)
+        t_b, f_b, k_b = run_sequence(gen.prefix_cache_baseline_rounds(n_agents=na, n_rounds=nr), 5)
+        comp[name] = {"choreographed_ms": t_c * 1e3, "baseline_ms": t_b * 1e3, "time_ratio": t_b / t_c,
+                      "choreographed_attention_gflop": f_c / 1e9, "baseline_attention_gflop": f_b / 1e9,
+                      "flop_ratio": f_b / f_c, "choreographed_tokens_encoded": k_c, "baseline_tokens_encoded": k_b}
+    line.setdefault("extras", {})["prefix_cache_baseline"] = {
+        "workload": "attention and cache-append work only, 256-token messages: choreographed rounds (each agent "
+                    "prefills its new message over the cached messages of all earlier rounds) against a prefix-caching "
+                    "baseline (each agent keeps its own prompt as prefix and encodes the other agents' last-round "
+                    "messages again with its new one); the model's other layers, which the baseline also runs again "
+                    "for every re-encoded token, are not part of this path",
+        **comp}
 
-    # ------------------------------------------------ position updates vs. in-kernel rotation
-    if not args.skip_extras and (not only or "reposition" in only):
-        from paper_2512_23049_amd.binding import marshal_calls
-        w5 = gen.long_context(n_decode=0)
-        cache = harness.make_cache(w5)
-        dw = harness.DeviceWorkload(w5)
-        dw.run(cache)
-        torch.cuda.synchronize()
-        att = [s_ for s_ in dw.steps if s_[0] == "attend"][-1]
-        _, calls, mc, q, out, lse = att
-        call = calls[0]
-        lens = w5.message_lengths()
-        starts, s_self, _ = cache.resolve_call(call)
-        reps = max(3, min(args.steps, 10))
 
-        def attend_only():
-            cache.attend(calls, q.data_ptr(), out.data_ptr(), 0, 0, mc)
-        t_before = time_steps(attend_only, reps, 2, torch)
-        cache.profile_enable(True)
-        cache.profile_read(reset=True)
-        moved = [(m, st_) for (m, _), st_ in zip(call.sel, starts)] + [(call.self_msg, s_self)]
-        t0 = time.perf_counter()
-        for m, st_ in moved:
-            cache.reposition(m, st_)
-        torch.cuda.synchronize()
-        t_move = time.perf_counter() - t0
-        prof = cache.profile_read(reset=True)
-        t_after = time_steps(attend_only, reps, 2, torch)
-        # the same moves as one launch: back to base 0, then to the starts again
-        ids = [m for m, _ in moved]
-        cache.reposition_batch(ids, [0] * len(ids))
+def section_decode_loop(cx):
+    """Decode loop: tails growing one token per step (append + attend per step)."""
+    args, torch, gen, harness, line = cx.args, cx.torch, cx.gen, cx.harness, cx.line
+    w6 = gen.decode_loop()
+    dw = harness.DeviceWorkload(w6)
+    first_loop = next(i for i, s_ in enumerate(dw.steps) if s_[0] == "attend")
+    n_steps = sum(1 for s_ in dw.steps if s_[0] == "attend")
+    times = []
+    for rep in range(3):
+        cache = harness.make_cache(w6)
+        for s_ in dw.steps[:first_loop]:
+            cache.append_message(s_[1].data_ptr(), s_[2].data_ptr(), s_[3], s_[4])
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        cache.reposition_batch(ids, [st_ for _, st_ in moved])
+        for s_ in dw.steps[first_loop:]:
+            if s_[0] == "extend":
+                cache.append_tokens_batch(s_[3], s_[1].data_ptr(), s_[2].data_ptr())
+            else:
+                cache.attend(s_[1], s_[3].data_ptr(), s_[4].data_ptr(), 0, 0, s_[2])
         torch.cuda.synchronize()
-        t_batch = time.perf_counter() - t0
-        prof_b = cache.profile_read(reset=True)
-        cache.profile_enable(False)
-        pairs5 = sum(v[3] for v in visible_pairs(w5, w5.events[-1]))
-        f5 = 4.0 * w5.head_dim * w5.n_q_heads * pairs5
-        k_bytes = sum(lens[m] for m, _ in moved) * w5.n_kv_heads * w5.head_dim * 2
-        k_batch_us = (prof_b["reposition"][0] / prof_b["reposition"][1] * 1e3) if prof_b["reposition"][1] else None
-        line.setdefault("extras", {})["reposition"] = {
-            "workload": "configs[4] prefill call alone (2048 rows over ~64k tokens in ~410 messages of 64-256 tokens): "
-                        "pc_attend with every parent at base 0 (queries turned per parent), then every parent moved to "
-                        "the start the call gives it (one pc_reposition each, and again as one pc_reposition_batch), "
-                        "then the same pc_attend (one turn in all)",
-            "attend_ms_before": t_before * 1e3, "attend_ms_after": t_after * 1e3,
-            "tflops_before": f5 / t_before / 1e12, "tflops_after": f5 / t_after / 1e12,
-            "messages_moved": len(moved), "one_by_one_ms_host_clock": t_move * 1e3,
-            "one_by_one_kernel_us_avg": (prof["reposition"][0] / prof["reposition"][1] * 1e3) if prof["reposition"][1] else None,
-            "batched_ms_host_clock": t_batch * 1e3, "batched_kernel_us": k_batch_us,
-            "batched_gbs": (2 * k_bytes / (k_batch_us * 1e-6) / 1e9) if k_batch_us else None,
-            "bytes_read_plus_written": 2 * k_bytes,
-        }
+        times.append(time.perf_counter() - t0)
         cache.close()
-        del w5
+    sec6 = min(times[1:])
+    b6 = 0
+    for i, e in enumerate(w6.events):
+        if e.kind == "attend":
+            lens = w6.message_lengths(upto_event=i)
+            b6 += sum(sum(lens[m] for m, _ in c.sel) + lens[c.self_msg] for c in e.calls) * 4096
+    n_calls6 = len(w6.events[-1].calls)
+    line.setdefault("extras", {})["decode_loop"] = {
+        "workload": "configs[2]-shaped parallel decode as a loop: 64 calls (2048-token system + 8 pool messages each), "
+                    "tails grow from 1 to 64 tokens; a step = pc_append_tokens_batch (one token per call) + pc_attend",
+        "steps": n_steps, "us_per_step": sec6 / n_steps * 1e6, "tokens_per_s": n_calls6 * n_steps / sec6,
+        "gbs_logical": b6 / sec6 / 1e9, "B_logical_total": b6}
+    del w6, dw
 
-    # ------------------------------------------------ gradient path (functional, untuned): a small shape
-    if not args.skip_extras and (not only or "backward" in only):
-        wb = gen.single_prefill(n_msgs=24, len_lo=40, len_hi=300, n_sel=6, n_new=200)
-        cache = harness.make_cache(wb)
-        dw = harness.DeviceWorkload(wb)
-        dw.run(cache)
+
+def section_reposition(cx):
+    """Position updates in place against in-kernel rotation on configs[4]'s prefill call."""
+    args, torch, gen, harness, line = cx.args, cx.torch, cx.gen, cx.harness, cx.line
+    from paper_2512_23049_amd.binding import marshal_calls
+    w5 = gen.long_context(n_decode=0)
+    cache = harness.make_cache(w5)
+    dw = harness.DeviceWorkload(w5)
+    dw.run(cache)
+    torch.cuda.synchronize()
+    att = [s_ for s_ in dw.steps if s_[0] == "attend"][-1]
+    _, calls, mc, q, out, lse = att
+    call = calls[0]
+    lens = w5.message_lengths()
+    starts, s_self, _ = cache.resolve_call(call)
+    reps = max(3, min(args.steps, 10))
+
+    def attend_only():
+        cache.attend(calls, q.data_ptr(), out.data_ptr(), 0, 0, mc)
+    t_before = time_steps(attend_only, reps, 2, torch)
+    cache.profile_enable(True)
+    cache.profile_read(reset=True)
+    moved = [(m, st_) for (m, _), st_ in zip(call.sel, starts)] + [(call.self_msg, s_self)]
+    t0 = time.perf_counter()
+    for m, st_ in moved:
+        cache.reposition(m, st_)
+    torch.cuda.synchronize()
+    t_move = time.perf_counter() - t0
+    prof = cache.profile_read(reset=True)
+    t_after = time_steps(attend_only, reps, 2, torch)
+    # the same moves as one launch: back to base 0, then to the starts again
+    ids = [m for m, _ in moved]
+    cache.reposition_batch(ids, [0] * len(ids))
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    cache.reposition_batch(ids, [st_ for _, st_ in moved])
+    torch.cuda.synchronize()
+    t_batch = time.perf_counter() - t0
+    prof_b = cache.profile_read(reset=True)
+    cache.profile_enable(False)
+    pairs5 = sum(v[3] for v in visible_pairs(w5, w5.events[-1]))
+    f5 = 4.0 * w5.head_dim * w5.n_q_heads * pairs5
+    k_bytes = sum(lens[m] for m, _ in moved) * w5.n_kv_heads * w5.head_dim * 2
+    k_batch_us = (prof_b["reposition"][0] / prof_b["reposition"][1] * 1e3) if prof_b["reposition"][1] else None
+    line.setdefault("extras", {})["reposition"] = {
+        "workload": "configs[4] prefill call alone (2048 rows over ~64k tokens in ~410 messages of 64-256 tokens): "
+                    "pc_attend with every parent at base 0 (queries turned per parent), then every parent moved to "
+                    "the start the call gives it (one pc_reposition each, and again as one pc_reposition_batch), "
+                    "then the same pc_attend (one turn in all)",
+        "attend_ms_before": t_before * 1e3, "attend_ms_after": t_after * 1e3,
+        "tflops_before": f5 / t_before / 1e12, "tflops_after": f5 / t_after / 1e12,
+        "messages_moved": len(moved), "one_by_one_ms_host_clock": t_move * 1e3,
+        "one_by_one_kernel_us_avg": (prof["reposition"][0] / prof["reposition"][1] * 1e3) if prof["reposition"][1] else None,
+        "batched_ms_host_clock": t_batch * 1e3, "batched_kernel_us": k_batch_us,
+        "batched_gbs": (2 * k_bytes / (k_batch_us * 1e-6) / 1e9) if k_batch_us else None,
+        "bytes_read_plus_written": 2 * k_bytes,
+    }
+    cache.close()
+    del w5
+
+
+def section_backward(cx):
+    """Gradient path (functional, untuned) on a small shape."""
+    args, torch, gen, harness, line = cx.args, cx.torch, cx.gen, cx.harness, cx.line
+    wb = gen.single_prefill(n_msgs=24, len_lo=40, len_hi=300, n_sel=6, n_new=200)
+    cache = harness.make_cache(wb)
+    dw = harness.DeviceWorkload(wb)
+    dw.run(cache)
+    torch.cuda.synchronize()
+    att = [s_ for s_ in dw.steps if s_[0] == "attend"][-1]
+    _, calls, mc, q, out, lse = att
+    slots = cache.cache_info()[2]
+    d_out = torch.randn(tuple(q.shape), device="cuda:0").to(q.dtype)
+    d_q = torch.empty(tuple(q.shape), dtype=torch.float32, device="cuda:0")
+    d_k = torch.zeros((slots, wb.n_kv_heads, wb.head_dim), dtype=torch.float32, device="cuda:0")
+    d_v = torch.zeros_like(d_k)
+    cache.attend(calls, q.data_ptr(), out.data_ptr(), lse.data_ptr(), 0, mc)
+
+    def bwd():
+        cache.attend_backward(calls, q.data_ptr(), lse.data_ptr(), d_out.data_ptr(), d_q.data_ptr(), d_k.data_ptr(),
+                              d_v.data_ptr())
+        cache.grad_keys_finalize(d_k.data_ptr())
+    t_b = time_steps(bwd, max(3, min(args.steps, 20)), 2, torch)
+    pairs_b = sum(v[3] for v in visible_pairs(wb, wb.events[-1]))
+    line.setdefault("extras", {})["backward"] = {
+        "workload": "scaled single prefill (200 causal rows over 6 parents of 40-300 tokens + the new message, 32/8 heads, "
+                    "bf16 cache): pc_attend_backward + pc_grad_keys_finalize; a functional path (plain fp32 vector "
+                    "kernels, no matrix cores), not tuned",
+        "ms_per_call": t_b * 1e3,
+        "gflops": 2.5 * 4.0 * wb.head_dim * wb.n_q_heads * pairs_b / t_b / 1e9,
+    }
+    cache.close()
+    del wb
+
+
+# sections after the headline, in the order they run; --only names them
+SECTIONS = [("achievable", section_achievable), ("decode", section_decode), ("long", section_long_context),
+            ("longdecode", section_long_context_decode), ("rounds", section_rounds), ("baseline", section_baseline),
+            ("loop", section_decode_loop), ("reposition", section_reposition), ("backward", section_backward)]
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--skip-extras", action="store_true")
+    ap.add_argument("--skip-cpu", action="store_true")
+    ap.add_argument("--only", default="", help="comma list of sections: achievable,decode,long,longdecode,rounds,baseline,loop,reposition,backward")
+    ap.add_argument("--copy-probe-mib", type=int, default=0,
+                    help="also launch one plain device copy of this many MiB (reference for scaling rocprofv3 "
+                         "FETCH_SIZE / WRITE_SIZE counters)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import pc_inputs as gen
+    from paper_2512_23049_amd import harness
+    assert torch.cuda.is_available(), "bench.py needs the MI355X"
+    only = set(x for x in args.only.split(",") if x)
+    if args.copy_probe_mib > 0:
+        src = torch.ones(args.copy_probe_mib << 18, dtype=torch.float32, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
         torch.cuda.synchronize()
-        att = [s_ for s_ in dw.steps if s_[0] == "attend"][-1]
-        _, calls, mc, q, out, lse = att
-        slots = cache.cache_info()[2]
-        d_out = torch.randn(tuple(q.shape), device="cuda:0").to(q.dtype)
-        d_q = torch.empty(tuple(q.shape), dtype=torch.float32, device="cuda:0")
-        d_k = torch.zeros((slots, wb.n_kv_heads, wb.head_dim), dtype=torch.float32, device="cuda:0")
-        d_v = torch.zeros_like(d_k)
-        cache.attend(calls, q.data_ptr(), out.data_ptr(), lse.data_ptr(), 0, mc)
+        del src, dst
 
-        def bwd():
-            cache.attend_backward(calls, q.data_ptr(), lse.data_ptr(), d_out.data_ptr(), d_q.data_ptr(), d_k.data_ptr(),
-                                  d_v.data_ptr())
-            cache.grad_keys_finalize(d_k.data_ptr())
-        t_b = time_steps(bwd, max(3, min(args.steps, 20)), 2, torch)
-        pairs_b = sum(v[3] for v in visible_pairs(wb, wb.events[-1]))
-        line.setdefault("extras", {})["backward"] = {
-            "workload": "scaled single prefill (200 causal rows over 6 parents of 40-300 tokens + the new message, 32/8 heads, "
-                        "bf16 cache): pc_attend_backward + pc_grad_keys_finalize; a functional path (plain fp32 vector "
-                        "kernels, no matrix cores), not tuned",
-            "ms_per_call": t_b * 1e3,
-            "gflops": 2.5 * 4.0 * wb.head_dim * wb.n_q_heads * pairs_b / t_b / 1e9,
-        }
-        cache.close()
-        del wb
-
+    cx = Ctx(args, torch, gen, harness)
+    section_headline(cx)
+    if not args.skip_extras:
+        for name, section in SECTIONS:
+            if not only or name in only:
+                section(cx)
+    line = cx.line
     line["context"] = ("paper reports whole-workflow ratios only: 2.0-6.2x faster time-to-first-token and up to 2.2x "
                        "end-to-end vs prefix caching (Llama-3.1-8B; one A100-80GB is the only GPU the paper names); "
                        "no kernel-level figure exists to compare with")
