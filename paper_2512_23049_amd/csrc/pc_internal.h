@@ -92,7 +92,9 @@ struct PcItem {
     int32_t tile_begin;       // KV tile range [begin, end) within the call
     int32_t tile_end;
     int32_t split;            // split index within the call
-    int32_t pad[3];
+    int32_t tile_tab0;        // the call's first entry in the tile table (a copy of its PcCallDesc::tile_off, so that
+                              // the first tile descriptors can be requested without waiting for the call descriptor)
+    int32_t pad[2];
 };
 
 // One output row whose KV splits the merge kernel combines (staged by the host).

@@ -101,10 +101,7 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
     const int ub = unit_ok ? unit / g : 0;               // 32-row block
     const int uj = unit_ok ? unit - ub * g : 0;          // head within the group
     const int h = kh * g + uj;
-    const int self_seg = cd.self_msg >= 0 ? cd.n_seg - 1 : -1;
     const int tok0 = cd.self_len - cd.n_q;               // own token index of query row 0
-    const int last_unit = min(item.unit0 + 7, n_units - 1);
-    const int wg_lim = tok0 + min(32 * (last_unit / g) + 31, cd.n_q - 1);   // last own token any row here sees
     const int row = 32 * ub + n;
     const bool row_ok = unit_ok && row < cd.n_q;
     const int Rg = cd.q_off + (row_ok ? row : 0);
@@ -140,12 +137,9 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
     const unsigned char *kb = (const unsigned char *)L.k_store + (int64_t)kh * L.slots * PC_D * 2;
     const unsigned char *vb = (const unsigned char *)L.v_store + (int64_t)kh * L.slots * PC_D * 2;
 
-    // tiles this workgroup walks: its split's range, cut at the causal limit of its last row
-    int tile_end = item.tile_end;
-    if (self_seg >= 0) {
-        const int self_tile_off = L.segs[cd.seg_off + self_seg].tile_off;
-        tile_end = min(tile_end, self_tile_off + (wg_lim + PC_TILE) / PC_TILE);
-    }
+    // tiles this workgroup walks: its split's range (the host has cut it at the causal limit of the
+    // workgroup's last row, so nothing has to be looked up for it)
+    const int tile_end = item.tile_end;
     const int tile0 = item.tile_begin;
     const int T = tile_end - tile0;
 
@@ -173,7 +167,7 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
         __device__ bool is_self() const { return (__builtin_amdgcn_readfirstlane(flags) & PC_TILE_SELF) != 0; }
         __device__ int key() const { return __builtin_amdgcn_readfirstlane(key0); }
     };
-    const PcTile *tile_tab = L.tiles + cd.tile_off;
+    const PcTile *tile_tab = L.tiles + item.tile_tab0;   // (from the work item: no need to wait for the call descriptor)
     typedef int i32x4 __attribute__((ext_vector_type(4)));
     auto decode = [&](const i32x4 &v) {
         Desc d;

@@ -312,6 +312,7 @@ int32_t pc_plan_and_stage(pc_cache *c, const pc_call *calls, int32_t n_calls, bo
             cd.n_splits = ns;
             for (int s = 0; s < ns; ++s) {
                 PcItem it{}; it.call = i; it.unit0 = 0; it.tile_begin = s * chunk; it.tile_end = std::min(T, (s + 1) * chunk); it.split = s;
+                it.tile_tab0 = cd.tile_off;
                 dec.push_back(it);
             }
         } else {
@@ -325,8 +326,9 @@ int32_t pc_plan_and_stage(pc_cache *c, const pc_call *calls, int32_t n_calls, bo
             ns = std::max(1, (T + chunk - 1) / chunk);
             cd.n_splits = ns;
             // A group of row units walks the parents' tiles and the tiles of the new message up to the
-            // causal limit of its last row; its splits divide THAT count evenly, so the groups with
-            // early rows do not end up with a nearly empty last split.
+            // causal limit of its last row (the kernel relies on tile_end being cut there); its splits
+            // divide THAT count evenly, so the groups with early rows do not end up with a nearly empty
+            // last split.
             const int self_tiles = r.self_msg >= 0 ? (r.self_len + PC_TILE - 1) / PC_TILE : 0;
             const int parent_tiles = T - self_tiles;
             for (int gidx = 0; gidx < groups; ++gidx) {
@@ -338,9 +340,9 @@ int32_t pc_plan_and_stage(pc_cache *c, const pc_call *calls, int32_t n_calls, bo
                 }
                 const int chunk_g = std::max(1, (Tg + ns - 1) / ns);
                 for (int s = 0; s < ns; ++s) {
-                    PcItem it{}; it.call = i; it.unit0 = gidx * P.pre_waves; it.split = s;
+                    PcItem it{}; it.call = i; it.unit0 = gidx * P.pre_waves; it.split = s; it.tile_tab0 = cd.tile_off;
                     it.tile_begin = std::min(Tg, s * chunk_g);
-                    it.tile_end = s == ns - 1 ? T : std::min(Tg, (s + 1) * chunk_g);
+                    it.tile_end = s == ns - 1 ? Tg : std::min(Tg, (s + 1) * chunk_g);
                     pre.push_back(it);
                 }
             }
