@@ -89,7 +89,7 @@ __global__ __launch_bounds__(256, 2) void pc_decode_bf16_kernel(PcLaunch L)
     // scalar load one tile ahead of the loads it steers; the first one is requested here, in front of
     // the query, so that the wave's first K/V loads do not wait behind a search through the segments.
     typedef int i32x4 __attribute__((ext_vector_type(4)));
-    const PcTile *tile_tab = L.tiles + cd.tile_off;
+    const PcTile *tile_tab = L.tiles + item.tile_tab0;   // (from the work item: requested beside the call descriptor, not behind it)
     auto describe = [&](int t) {
         const int tc = __builtin_amdgcn_readfirstlane(max(0, min(t, item.tile_end - 1)));
         if (item.tile_end <= 0) return (i32x4){0, 0, 0, 0};                   // a call that sees nothing has no table
