@@ -282,7 +282,9 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
         if (__builtin_expect(need_mask != 0, 0)) {
             const bool need = (need_mask >> lane) & 1;
             const float shift = need ? mx : 0.f;
-            const float alpha = fast_exp2(-shift);       // > 1 only while nothing has been accumulated
+            // The reference moves down only at a row's first scores, when nothing has been accumulated yet:
+            // the factor is then irrelevant, and 2^-shift could overflow (0 * inf); it is taken as 1.
+            const float alpha = fast_exp2(-__builtin_fmaxf(shift, 0.f));
             l_run *= alpha;
 #pragma unroll
             for (int db = 0; db < 4; ++db) acc[db] *= alpha;

@@ -26,6 +26,7 @@
 namespace {
 
 __device__ __forceinline__ float sh_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ __forceinline__ float sh_max3(float a, float b, float c) { return __builtin_fmaxf(__builtin_fmaxf(a, b), c); }
 __device__ __forceinline__ float sh_max_halves(float x)
 {
     auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
@@ -138,7 +139,12 @@ __global__ __launch_bounds__(512, 1) void pc_decode_shared_bf16_kernel(PcLaunch 
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) k_off[ks] = (unsigned)(krow * 256 + (((2 * ks + hh) ^ (krow & 15)) << 4));
 
-    float m_run = -INFINITY, l_run = 0.f;
+    // Softmax state of this lane's column, as in the prefill kernel: probabilities are 2^(score - m_ref)
+    // with a reference that starts at 0 and moves only when it has to (a tile's maximum more than
+    // 2^SH_LAZY above it, or a row's first scores more than 2^SH_LAZY below it).  While no lane of the
+    // wave has moved its reference the scores are not shifted at all.
+    float m_ref = 0.f, thr_lo = -SH_LAZY, l_run = 0.f;
+    bool shifted = false;                                // some lane of this wave has m_ref != 0
     f32x16 acc[4];
 #pragma unroll
     for (int db = 0; db < 4; ++db)
@@ -240,31 +246,51 @@ __global__ __launch_bounds__(512, 1) void pc_decode_shared_bf16_kernel(PcLaunch 
                 s[r] = (key < valid) ? s[r] : -INFINITY;
             }
         }
-        float mx = fmaxf(s[0], s[1]);
+        if (__builtin_expect(shifted, 0)) {
 #pragma unroll
-        for (int r = 2; r < 16; r += 2) mx = fmaxf(mx, fmaxf(s[r], s[r + 1]));
+            for (int r = 0; r < 16; ++r) s[r] -= m_ref;
+        }
+        float mx = sh_max3(sh_max3(s[0], s[1], s[2]), s[3], s[4]);
+        mx = sh_max3(sh_max3(mx, s[5], s[6]), s[7], s[8]);
+        mx = sh_max3(sh_max3(mx, s[9], s[10]), s[11], s[12]);
+        mx = sh_max3(sh_max3(mx, s[13], s[14]), s[15], s[15]);
         mx = sh_max_halves(mx);
         mx = vis ? mx : -INFINITY;                       // a row that does not list the message: nothing moves, and ...
-        // The reference moves (and the accumulators are rescaled) only when a tile's maximum exceeds it by more than
-        // 2^SH_LAZY, or when the row sees its first keys: probabilities stay below 2^SH_LAZY, far inside fp32 and bf16.
-        const bool move = mx > m_run + SH_LAZY;
-        const float m_new = move ? mx : m_run;
-        const float alpha = move ? sh_exp2(m_run - m_new) : 1.f;           // 0 when nothing had been seen
-        const float m_use = vis ? m_new : INFINITY;      // ... all its probabilities are exp2(-inf) = 0
+        {
+            const uint64_t above = __builtin_amdgcn_ballot_w64(mx > SH_LAZY);
+            const uint64_t below = __builtin_amdgcn_ballot_w64(mx < thr_lo);
+            const bool seen = mx > -INFINITY;
+            const uint64_t need_mask = above | (below & __builtin_amdgcn_ballot_w64(seen));
+            thr_lo = seen ? -INFINITY : thr_lo;
+            if (__builtin_expect(need_mask != 0, 0)) {
+                const bool need = (need_mask >> lane) & 1;
+                const float shift = need ? mx : 0.f;
+                // (moving down happens only at a row's first scores, with nothing accumulated: the factor is
+                // irrelevant then, and 2^-shift could overflow into 0 * inf; it is taken as 1)
+                const float alpha = sh_exp2(-fmaxf(shift, 0.f));
+                l_run *= alpha;
+#pragma unroll
+                for (int db = 0; db < 4; ++db) acc[db] *= alpha;
+                m_ref += shift;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) s[r] -= shift;
+                shifted = __builtin_amdgcn_ballot_w64(m_ref != 0.f) != 0;
+            }
+        }
         float ps = 0.f;
         uint32_t pk[8];
 #pragma unroll
         for (int r = 0; r < 16; r += 2) {
-            const float p0 = sh_exp2(s[r] - m_use), p1 = sh_exp2(s[r + 1] - m_use);
+            const float p0 = sh_exp2(s[r]), p1 = sh_exp2(s[r + 1]);
             ps += p0 + p1;
             pk[r >> 1] = pack_bf16(p0, p1);
         }
-        l_run = l_run * alpha + ps;
-        m_run = m_new;
-        if (__builtin_amdgcn_ballot_w64(move) != 0) {
+        if (!vis) {                                      // ... its probabilities are dropped
+            ps = 0.f;
 #pragma unroll
-            for (int db = 0; db < 4; ++db) acc[db] *= alpha;
+            for (int j = 0; j < 8; ++j) pk[j] = 0u;
         }
+        l_run += ps;
         const bf16x8 p0 = __builtin_bit_cast(bf16x8, make_uint4(pk[0], pk[1], pk[2], pk[3]));
         const bf16x8 p1 = __builtin_bit_cast(bf16x8, make_uint4(pk[4], pk[5], pk[6], pk[7]));
 #pragma unroll
@@ -314,7 +340,7 @@ __global__ __launch_bounds__(512, 1) void pc_decode_shared_bf16_kernel(PcLaunch 
                 *reinterpret_cast<uint2 *>(o + d) = w;
             }
         if (L.lse && hh == 0)
-            L.lse[(int64_t)Rg * L.n_q_heads + h] = (l > 0.f) ? (m_run + log2f(l)) * 0.6931471805599453f : -INFINITY;
+            L.lse[(int64_t)Rg * L.n_q_heads + h] = (l > 0.f) ? (m_ref + log2f(l)) * 0.6931471805599453f : -INFINITY;
     } else {
         const int64_t pr = (int64_t)gr.part_off + (int64_t)item.split * gr.n_rows + row;
         uint16_t *o = L.part_o + (pr * L.n_q_heads + h) * PC_D;
@@ -329,7 +355,7 @@ __global__ __launch_bounds__(512, 1) void pc_decode_shared_bf16_kernel(PcLaunch 
                 *reinterpret_cast<uint2 *>(o + d) = w;
             }
         if (hh == 0) {
-            L.part_ml[(pr * L.n_q_heads + h) * 2] = (l > 0.f) ? m_run : -INFINITY;
+            L.part_ml[(pr * L.n_q_heads + h) * 2] = (l > 0.f) ? m_ref : -INFINITY;
             L.part_ml[(pr * L.n_q_heads + h) * 2 + 1] = l;
         }
     }

@@ -325,15 +325,19 @@ def test_large_logits_move_the_softmax_reference(hip, n_q):
     qd = hip.to_device(q, "bf16")
     out = torch.empty_like(qd)
     lse = torch.empty((n_q, H_q), dtype=torch.float32, device="cuda:0")
-    for tuning in ((0, 0), (7, 7)):                       # default splits, and splits of seven tiles
+    variants = [((0, 0), 0), ((7, 7), 0)]                 # default splits, and splits of seven tiles
+    if n_q == 1:
+        variants += [((0, 0), 2), ((7, 0), 2)]            # ... and the one-row call on the shared decode walk
+    for tuning, sharing in variants:
         cache.set_tuning(*tuning)
+        cache.set_decode_sharing(sharing)
         cache.attend([call], qd.data_ptr(), out.data_ptr(), lse.data_ptr())
         torch.cuda.synchronize()
         o, l = orc.attend_call(ks, vs, call.sel, -1, 0, n_q, call.q_pos, q, 10000.0, scale=scale)
         got = out.float().cpu().numpy()
         d = np.abs(got - o)
         e_lse = np.abs(lse.cpu().numpy() - l)
-        say(f"  n_q={n_q} tuning={tuning}: max_abs={d.max():.3e} mean_abs={d.mean():.3e} "
+        say(f"  n_q={n_q} tuning={tuning} sharing={sharing}: max_abs={d.max():.3e} mean_abs={d.mean():.3e} "
             f"lse range [{l.min():.1f}, {l.max():.1f}] max lse err {e_lse.max():.3e}")
         assert np.isfinite(got).all()
         assert d.max() <= 2e-2 and d.mean() <= 1e-3
@@ -493,3 +497,49 @@ def test_batch_of_many_small_prefill_calls(hip):
     """400 calls of up to 12 rows each in one pc_attend."""
     w = gen.small_random(89, dtype="bf16", n_q_heads=8, n_kv_heads=2, head_dim=128, n_msgs=40, n_calls=400, max_q=12)
     run_and_compare(hip, w, few_key_calls=True)
+
+
+@pytest.mark.parametrize("n_q,sharing", [(40, 0), (1, 1), (1, 2)])
+def test_first_key_far_below_every_other(hip, n_q, sharing):
+    """A call whose first visible key scores thousands of log2 units below the rest, for every row: its weight
+    is zero, and the softmax reference, which starts at 0, has to move down by more than fp32's exponent range
+    at that first tile without disturbing what follows (prefill, per-call decode and shared decode)."""
+    import torch
+    from oracle import choreo_oracle as orc
+    from pc_inputs import Call
+    from paper_2512_23049_amd.binding import PC_BF16, Cache
+    rng = np.random.default_rng(5)
+    H_q, H_kv, D = 8, 2, 128
+    u = np.where(np.arange(D) % 3 == 0, -1.0, 1.0).astype(np.float32)
+
+    def rnd(*shape):
+        return gen.round_to_bf16(rng.standard_normal(shape).astype(np.float32))
+    k_far = gen.round_to_bf16(np.broadcast_to(-64.0 * u, (1, H_kv, D)).copy())
+    ks = [k_far] + [rnd(1, H_kv, D) for _ in range(70)]   # one-token messages: each sits exactly at the queries' position
+    vs = [rnd(1, H_kv, D) for _ in range(71)]
+    q = gen.round_to_bf16(rnd(n_q, H_q, D) + 3.0 * u[None, None, :])
+    # (scores exact on the GPU, as in the test above: no rotation, and softmax_scale * log2(e) = 2^-3 folds
+    # into the bf16 queries without rounding; the bf16 bars are for scores that carry no rounding of their own)
+    scale = 2.0 ** -3 / 1.4426950408889634
+    cache = Cache(H_q, H_kv, D, PC_BF16, 10000.0, 4096, 80, softmax_scale=scale)
+    cache.set_decode_sharing(sharing)
+    keep = [(hip.to_device(k, "bf16"), hip.to_device(v, "bf16")) for k, v in zip(ks, vs)]
+    ids = [cache.append_message(kd.data_ptr(), vd.data_ptr(), k.shape[0]) for (kd, vd), k in zip(keep, ks)]
+    pos = 300
+    # every key at the queries' own position: no rotation, so the far key stays far for every row
+    call = Call([(m, pos) for m in ids], -1, 0, n_q, np.full(n_q, pos, dtype=np.int32))
+    qd = hip.to_device(q, "bf16")
+    out = torch.empty_like(qd)
+    lse = torch.empty((n_q, H_q), dtype=torch.float32, device="cuda:0")
+    for tuning in ((0, 0), (9, 9)):
+        cache.set_tuning(*tuning)
+        cache.attend([call], qd.data_ptr(), out.data_ptr(), lse.data_ptr())
+        torch.cuda.synchronize()
+        o, l = orc.attend_call(ks, vs, call.sel, -1, 0, n_q, call.q_pos, q, 10000.0, scale=scale)
+        got = out.float().cpu().numpy()
+        d = np.abs(got - o)
+        say(f"  n_q={n_q} sharing={sharing} tuning={tuning}: max_abs={d.max():.3e} mean_abs={d.mean():.3e}")
+        assert np.isfinite(got).all() and np.isfinite(lse.cpu().numpy()).all()
+        assert d.max() <= 2e-2 and d.mean() <= 1e-3
+        assert (np.abs(lse.cpu().numpy() - l) <= 2e-2 + 1e-3 * np.abs(l)).all()
+    cache.close()
