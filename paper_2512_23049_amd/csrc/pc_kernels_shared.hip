@@ -13,9 +13,9 @@
 //   * the rows are independent calls, so there is no causal structure: a call's own growing
 //     tail is just one more message that only its row sees.
 // K and V tiles go global -> LDS directly (16 bytes per lane, no staging registers) into a
-// ring of four slots, requested three tiles ahead; one barrier per tile, ordinary online
-// softmax: the path is bound by the one pass over the union's bytes and by the latency of that
-// pass, not by the MFMA rate.
+// ring of four slots, requested three tiles ahead; one barrier per tile; the softmax keeps the
+// prefill kernel's lazily moved reference.  The tile step is not software-pipelined: score MFMAs,
+// softmax and P.V MFMAs of a wave follow each other.
 //
 // Register/LDS layouts (fragment addressing, key permutation of the score rows, accumulator
 // layout) are those of the prefill kernel, so that split partials and the merge are shared.
