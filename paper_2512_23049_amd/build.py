@@ -28,13 +28,19 @@ def build(verbose: bool = False, extra=()):
             print(" ".join(cmd), flush=True)
         procs.append((cmd, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
         objs.append(o)
-    for cmd, p in procs:
+    failed = None
+    for cmd, p in procs:                                  # every compiler runs to its end before anything is reported
         out, _ = p.communicate()
         lines = [l for l in out.splitlines() if "packed-fp32-ops" not in l or "error" in l]
-        if p.returncode != 0:
-            raise RuntimeError("hipcc failed: " + " ".join(cmd) + "\n" + out)
+        if p.returncode != 0 and failed is None:
+            failed = "hipcc failed: " + " ".join(cmd) + "\n" + out
         if verbose and lines:
             print("\n".join(lines))
+    for f in os.listdir(CSRC):                            # what an interrupted or failed compile leaves behind
+        if f.endswith(".o.tmp"):
+            os.remove(os.path.join(CSRC, f))
+    if failed:
+        raise RuntimeError(failed)
     cmd = [hipcc, "-shared", "-fPIC", "--offload-arch=gfx950", *objs, "-o", LIB]
     r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     if r.returncode != 0:
