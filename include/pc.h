@@ -67,7 +67,8 @@ extern "C" {
                                  live; here to one or more spans) instead of PC_ERR_NO_SPACE:
                                  pc_append_tokens* then takes slots for it by the allocation
                                  rule, room for the tokens the call still brings and at least
-                                 the message's first reserve.  Every extent uses one row of the
+                                 the message's first reserve and PC_SLOT_ALIGN tokens.  Every
+                                 extent uses one row of the
                                  message table (max_messages bounds messages plus further
                                  extents), so message ids stay ascending but need not be
                                  consecutive.  To every call the message is one sequence of

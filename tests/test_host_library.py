@@ -321,3 +321,102 @@ def test_probe_entries_reject_bad_arguments_before_touching_the_device(pc):
     assert lib.pc_probe_hbm_read(ctypes.c_void_p(4100), 1 << 20, 1, one, ctypes.byref(out), None) == pc.PC_ERR_SHAPE
     assert lib.pc_probe_hbm_read(one, 1 << 20, 0, one, ctypes.byref(out), None) == pc.PC_ERR_INVALID_ARG
     assert out.value == 0.0
+
+
+def test_random_walk_over_growing_freed_swapped_and_moved_messages(pc):
+    """Messages that grow into further extents (PC_FLAG_GROW_EXTENTS), are freed, swapped out and in and moved,
+    in random order on a host-only cache, against a model written from the header's rules: every extent is a span
+    of the slot model under a row of its own; a further extent holds what the call still brings for the message
+    and at least the message's first reserve (and a tile); a free or a swap-out gives every span back; a swap-in
+    takes a span per extent in token order; a position update moves every extent's stored base."""
+    rng = np.random.default_rng(123)
+    flags = pc.PC_FLAG_HOST_ONLY | pc.PC_FLAG_GROW_EXTENTS
+    c = host_cache(pc, capacity_tokens=1 << 17, max_messages=4000, flags=flags)
+    model = orc.SlotModel(pc.PC_SLOT_ALIGN)
+    ext, base, out = {}, {}, {}          # message -> [[row, len, reserve], ...];  stored base;  swapped-out messages
+    rows = [0]                           # next row of the message table
+
+    def new_row():
+        rows[0] += 1
+        return rows[0] - 1
+
+    def grow(m, n, pending):
+        """n tokens for message m; pending collects the extents to allocate, in the order the tokens come."""
+        e = ext[m]
+        for left in range(n, 0, -1):
+            if e[-1][1] == e[-1][2]:
+                res = max(left, pc.PC_SLOT_ALIGN, e[0][2])
+                e.append([None, 0, res])
+                pending.append((m, len(e) - 1))
+            e[-1][1] += 1
+
+    def commit(pending):
+        for m, i in pending:
+            row = new_row()
+            ext[m][i][0] = row
+            model.append(row, ext[m][i][2])
+
+    for step in range(1500):
+        live = sorted(ext)
+        op = rng.random()
+        if op < 0.25 or not live:
+            L, r = int(rng.integers(1, 120)), int(rng.integers(0, 150))
+            m = c.append_message(0, 0, L, r)
+            row = new_row()
+            assert m == row
+            model.append(row, max(L, r))
+            ext[m], base[m] = [[row, L, max(L, r)]], 0
+        elif op < 0.50:
+            m = live[int(rng.integers(0, len(live)))]
+            n = int(rng.integers(1, 90))
+            c.append_tokens(m, 0, 0, n)
+            pending = []
+            grow(m, n, pending)
+            commit(pending)
+        elif op < 0.65:
+            k = int(rng.integers(1, min(6, len(live)) + 1))
+            ms = [live[i] for i in rng.permutation(len(live))[:k]]
+            c.append_tokens_batch(ms, 0, 0)
+            pending = []
+            for m in ms:
+                grow(m, 1, pending)
+            commit(pending)
+        elif op < 0.75:
+            m = live[int(rng.integers(0, len(live)))]
+            c.message_free(m)
+            for row, _, _ in ext.pop(m):
+                model.release(row)
+            base.pop(m)
+        elif op < 0.85:
+            m = live[int(rng.integers(0, len(live)))]
+            c.message_swap_out(m, 0)
+            for row, _, _ in ext[m]:
+                model.release(row)
+            out[m] = (ext.pop(m), base.pop(m))
+        elif op < 0.93 and out:
+            m = sorted(out)[int(rng.integers(0, len(out)))]
+            c.message_swap_in(m, 0)
+            e, b = out.pop(m)
+            for rec in e:
+                model.append(rec[0], rec[2])
+            ext[m], base[m] = e, b
+        else:
+            m = live[int(rng.integers(0, len(live)))]
+            nb = int(rng.integers(-5000, 5000))
+            c.reposition(m, nb)
+            base[m] = nb
+        # the library and the model agree on everything a caller can see
+        assert c.cache_info()[1] == model.end, step
+        for m in (sorted(ext)[-3:] + sorted(ext)[:2]):
+            e = ext[m]
+            assert c.message_extents(m) == [(model.span[row][0], ln) for row, ln, _ in e], (step, m)
+            assert c.message_info(m) == (sum(ln for _, ln, _ in e), model.span[e[0][0]][0], sum(r for _, _, r in e)), (step, m)
+            assert c.message_base(m) == base[m]
+        for m in list(out)[:2]:
+            with pytest.raises(pc.PcError) as ei:
+                c.message_info(m)
+            assert ei.value.code == pc.PC_ERR_BAD_MSG_ID
+    # at the end: every live message, in full
+    for m, e in ext.items():
+        assert c.message_extents(m, cap=256) == [(model.span[row][0], ln) for row, ln, _ in e]
+    assert len(ext) > 20 and max(len(e) for e in ext.values()) >= 3
