@@ -420,3 +420,16 @@ def test_random_walk_over_growing_freed_swapped_and_moved_messages(pc):
     for m, e in ext.items():
         assert c.message_extents(m, cap=256) == [(model.span[row][0], ln) for row, ln, _ in e]
     assert len(ext) > 20 and max(len(e) for e in ext.values()) >= 3
+    # to a call a message of several extents is one sequence of tokens: omitted offsets and the gathered
+    # length follow the oracle's rule on the messages' total lengths
+    live = sorted(ext)
+    lengths = {m: sum(ln for _, ln, _ in e) for m, e in ext.items()}
+    for _ in range(40):
+        sel = [(live[int(rng.integers(0, len(live)))], POS_AUTO if rng.random() < 0.5 else int(rng.integers(-900, 900)))
+               for _ in range(int(rng.integers(0, 6)))]
+        m_self = live[int(rng.integers(0, len(live)))]
+        s_self = POS_AUTO if rng.random() < 0.5 else int(rng.integers(-900, 900))
+        want_sel, want_self = orc.resolve_positions(sel, lengths, s_self)
+        starts, got_self, n_kv = c.resolve_call(Call(sel, m_self, s_self, 1, None))
+        assert starts == [s for _, s in want_sel] and got_self == want_self
+        assert n_kv == sum(lengths[m] for m, _ in sel) + lengths[m_self]
