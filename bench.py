@@ -200,7 +200,7 @@ def section_headline(cx):
 def section_achievable(cx):
     """What this chip sustains for the two resources the kernels are priced against (probe kernels of the library)."""
     args, torch, gen, harness, line = cx.args, cx.torch, cx.gen, cx.harness, cx.line
-    from paper_2512_23049_amd import probe_hbm_read, probe_mfma_bf16
+    from paper_2512_23049_amd.probe import probe_hbm_read, probe_mfma_bf16
     sink = torch.zeros(4, dtype=torch.float32, device="cuda:0")
     g = torch.Generator(device="cpu").manual_seed(7)
     ops_rand = torch.randn(8192, generator=g).to(torch.bfloat16).to("cuda:0")

@@ -296,23 +296,6 @@ int32_t pc_grad_keys_finalize(pc_cache *c, float *d_k, void *stream);
  * allows it.  Applies to PC_BF16 caches; other calls are unaffected. */
 int32_t pc_set_decode_sharing(pc_cache *c, int32_t mode);
 
-/* Achievable-peak probes for benchmarks (measurement aids: they name no passage of the paper and
- * no attention call uses them).  Both enqueue one untimed and `reps` timed launches on `stream`,
- * bracket the timed ones with events, WAIT for them and write the sustained rate to a host double.
- * They take no cache and allocate no device memory: the caller passes the buffers.
- *  pc_probe_mfma_bf16: the rate of 32x32x16 bf16 matrix instructions with nothing else in the
- *    loop, on every compute unit with `waves_per_simd` (1 or 2) waves per SIMD, each wave running
- *    iters * 16 of them (iters <= 65536, reps <= 100).  operands (device, operand_bytes >= 8192, 16-byte aligned) supplies the
- *    bf16 operand fragments; the clock the chip holds depends on how many operand bits toggle,
- *    so all-zero operands give the datasheet rate and random ones the rate real data can reach.
- *  pc_probe_hbm_read: the rate of a streaming read of `bytes` (multiple of 16, device, 16-byte
- *    aligned) with 16-byte loads; use a buffer several times the last-level cache.
- * sink: one device float the kernels may write (their way of keeping the work observable). */
-int32_t pc_probe_mfma_bf16(const void *operands, int64_t operand_bytes, int32_t iters, int32_t waves_per_simd,
-                           int32_t reps, float *sink, double *tflops, void *stream);
-int32_t pc_probe_hbm_read(const void *src, int64_t bytes, int32_t reps, float *sink, double *gb_per_s,
-                          void *stream);
-
 #ifdef __cplusplus
 }
 #endif

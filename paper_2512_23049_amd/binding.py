@@ -108,10 +108,6 @@ def lib():
         L.pc_grad_keys_finalize.argtypes = [vp, vp, vp]
         L.pc_set_decode_sharing.restype = i32
         L.pc_set_decode_sharing.argtypes = [vp, i32]
-        L.pc_probe_mfma_bf16.restype = i32
-        L.pc_probe_mfma_bf16.argtypes = [vp, i64, i32, i32, i32, vp, C.POINTER(C.c_double), vp]
-        L.pc_probe_hbm_read.restype = i32
-        L.pc_probe_hbm_read.argtypes = [vp, i64, i32, vp, C.POINTER(C.c_double), vp]
         _lib = L
     return _lib
 
@@ -120,26 +116,6 @@ class PcError(RuntimeError):
     def __init__(self, code: int, msg: str):
         super().__init__(f"pc error {code}: {msg}")
         self.code = code
-
-
-def probe_mfma_bf16(operands_ptr: int, operand_bytes: int, sink_ptr: int, iters: int = 4096, waves_per_simd: int = 2,
-                    reps: int = 3, stream: int = 0) -> float:
-    """Sustained TFLOP/s of bare 32x32x16 bf16 matrix instructions on the operands given (device)."""
-    out = C.c_double(0.0)
-    rc = lib().pc_probe_mfma_bf16(operands_ptr or None, operand_bytes, iters, waves_per_simd, reps, sink_ptr or None,
-                                  C.byref(out), stream or None)
-    if rc != PC_OK:
-        raise PcError(rc, "pc_probe_mfma_bf16 failed")
-    return out.value
-
-
-def probe_hbm_read(src_ptr: int, nbytes: int, sink_ptr: int, reps: int = 5, stream: int = 0) -> float:
-    """Sustained GB/s of a streaming read of the device buffer given."""
-    out = C.c_double(0.0)
-    rc = lib().pc_probe_hbm_read(src_ptr or None, nbytes, reps, sink_ptr or None, C.byref(out), stream or None)
-    if rc != PC_OK:
-        raise PcError(rc, "pc_probe_hbm_read failed")
-    return out.value
 
 
 def marshal_calls(calls: Sequence):

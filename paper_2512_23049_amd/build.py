@@ -1,4 +1,5 @@
-"""Builds libpc.so (the C-ABI library) in-tree with hipcc for gfx950."""
+"""Builds libpc.so (the C-ABI library) and libpc_probe.so (the benchmark's achievable-peak probes) in-tree with
+hipcc for gfx950."""
 import os
 import subprocess
 import sys
@@ -6,8 +7,10 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpc.so")
+PROBE_LIB = os.path.join(HERE, "libpc_probe.so")
+PROBE_SOURCES = ["pc_probe.hip"]
 SOURCES = ["pc_lib.hip", "pc_plan.hip", "pc_attend.hip", "pc_kernels_basic.hip", "pc_kernels_backward.hip", "pc_kernels_mfma.hip", "pc_kernels_prefill.hip",
-           "pc_kernels_shared.hip", "pc_probe.hip"]
+           "pc_kernels_shared.hip"]
 # the prefill kernel never produces NaNs in its max reductions: let the compiler drop the
 # canonicalising v_max x, x in front of every fmax
 FILE_FLAGS = {"pc_kernels_prefill.hip": ["-fno-honor-nans"]}
@@ -21,7 +24,7 @@ def build(verbose: bool = False, extra=()):
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     objs = []
     procs = []
-    for s in SOURCES:
+    for s in SOURCES + PROBE_SOURCES:
         o = os.path.join(CSRC, s.replace(".hip", ".o"))
         cmd = [hipcc, *FLAGS, *FILE_FLAGS.get(s, []), *extra, "-c", os.path.join(CSRC, s), "-o", o]
         if verbose:
@@ -41,10 +44,12 @@ def build(verbose: bool = False, extra=()):
             os.remove(os.path.join(CSRC, f))
     if failed:
         raise RuntimeError(failed)
-    cmd = [hipcc, "-shared", "-fPIC", "--offload-arch=gfx950", *objs, "-o", LIB]
-    r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
-    if r.returncode != 0:
-        raise RuntimeError("link failed:\n" + r.stdout)
+    n = len(SOURCES)
+    for out_lib, its in ((LIB, objs[:n]), (PROBE_LIB, objs[n:])):
+        cmd = [hipcc, "-shared", "-fPIC", "--offload-arch=gfx950", *its, "-o", out_lib]
+        r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+        if r.returncode != 0:
+            raise RuntimeError("link failed:\n" + r.stdout)
     return LIB
 
 

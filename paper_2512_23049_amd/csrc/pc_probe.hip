@@ -5,7 +5,7 @@
 
 #include <cstdint>
 
-#include "../../include/pc.h"
+#include "../../include/pc_probe.h"
 
 namespace {
 
@@ -15,30 +15,38 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int PROBE_CHAINS = 4;          // independent accumulators per wave: no MFMA waits for another
 constexpr int PROBE_UNROLL = 4;          // MFMAs per chain per loop trip
+constexpr int PROBE_SETS = 8;            // operand fragment sets a wave cycles through
 
 // Every wave runs iters * 16 MFMAs (32x32x16 bf16) on operand fragments read once from
-// `operands` (chain c, lane l: 32 bytes at ((c * 64 + l) * 32), A then B).  The power a matrix
-// core draws, and with it the clock the chip holds, depends on how many operand bits toggle,
-// so the caller chooses the data: all-zero operands give the datasheet rate, random ones the
-// rate real data can reach.
+// `operands` (set s, lane l: 32 bytes at ((s * 64 + l) * 32), A then B).  Consecutive MFMAs take
+// different A and B fragments (MFMA i of a loop trip: A set i mod 8, B set 3 i mod 8, so the 16 MFMAs
+// of a trip see 16 different (A, B) pairs) and the accumulators change all the time: the matrix
+// core's inputs toggle from one instruction to the next as they do in an attention loop.  The
+// power a matrix core draws, and with it the clock the chip holds, depends on how many operand
+// bits toggle, so the caller chooses the data: all-zero operands give the datasheet rate, random
+// ones the rate real data can reach.
 __global__ __launch_bounds__(256) void pc_probe_mfma_kernel(const uint4 *__restrict__ operands,
                                                             int iters, float *sink) {
     const int lane = threadIdx.x & 63;
-    bf16x8 a[PROBE_CHAINS], b[PROBE_CHAINS];
+    bf16x8 a[PROBE_SETS], b[PROBE_SETS];
     f32x16 acc[PROBE_CHAINS];
 #pragma unroll
-    for (int c = 0; c < PROBE_CHAINS; ++c) {
-        a[c] = __builtin_bit_cast(bf16x8, operands[(c * 64 + lane) * 2]);
-        b[c] = __builtin_bit_cast(bf16x8, operands[(c * 64 + lane) * 2 + 1]);
+    for (int s = 0; s < PROBE_SETS; ++s) {
+        a[s] = __builtin_bit_cast(bf16x8, operands[(s * 64 + lane) * 2]);
+        b[s] = __builtin_bit_cast(bf16x8, operands[(s * 64 + lane) * 2 + 1]);
+    }
+#pragma unroll
+    for (int c = 0; c < PROBE_CHAINS; ++c)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[c][r] = 0.f;
-    }
     for (int it = 0; it < iters; ++it) {
 #pragma unroll
         for (int u = 0; u < PROBE_UNROLL; ++u)
 #pragma unroll
-            for (int c = 0; c < PROBE_CHAINS; ++c)
-                acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[c], b[c], acc[c], 0, 0, 0);
+            for (int c = 0; c < PROBE_CHAINS; ++c) {
+                const int i = u * PROBE_CHAINS + c;
+                acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i % PROBE_SETS], b[(3 * i) % PROBE_SETS], acc[c], 0, 0, 0);
+            }
     }
     float s = 0.f;
 #pragma unroll
@@ -80,9 +88,9 @@ struct EventPair {
 
 int32_t compute_units(int *cus) {
     int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess) return PC_ERR_HIP;
-    if (hipDeviceGetAttribute(cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return PC_ERR_HIP;
-    return *cus > 0 ? PC_OK : PC_ERR_HIP;
+    if (hipGetDevice(&dev) != hipSuccess) return PC_PROBE_ERR_HIP;
+    if (hipDeviceGetAttribute(cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return PC_PROBE_ERR_HIP;
+    return *cus > 0 ? PC_PROBE_OK : PC_PROBE_ERR_HIP;
 }
 
 }  // namespace
@@ -91,52 +99,52 @@ extern "C" {
 
 int32_t pc_probe_mfma_bf16(const void *operands, int64_t operand_bytes, int32_t iters, int32_t waves_per_simd,
                            int32_t reps, float *sink, double *tflops, void *stream) {
-    if (!operands || !sink || !tflops) return PC_ERR_INVALID_ARG;
-    if (operand_bytes < (int64_t)PROBE_CHAINS * 64 * 32) return PC_ERR_SHAPE;
-    if (iters < 1 || iters > (1 << 16) || reps < 1 || reps > 100) return PC_ERR_INVALID_ARG;   // at most ~2 s of GPU time
-    if (waves_per_simd < 1 || waves_per_simd > 2) return PC_ERR_INVALID_ARG;
+    if (!operands || !sink || !tflops) return PC_PROBE_ERR_INVALID_ARG;
+    if (operand_bytes < (int64_t)PROBE_SETS * 64 * 32) return PC_PROBE_ERR_SHAPE;
+    if (iters < 1 || iters > (1 << 16) || reps < 1 || reps > 100) return PC_PROBE_ERR_INVALID_ARG;   // at most ~2 s of GPU time
+    if (waves_per_simd < 1 || waves_per_simd > 2) return PC_PROBE_ERR_INVALID_ARG;
     int cus = 0;
     if (int32_t rc = compute_units(&cus)) return rc;
     hipStream_t st = (hipStream_t)stream;
     EventPair ev;
-    if (ev.create() != hipSuccess) return PC_ERR_HIP;
+    if (ev.create() != hipSuccess) return PC_PROBE_ERR_HIP;
     const int grid = cus * waves_per_simd;              // a workgroup is four waves, one per SIMD
     const uint4 *ops = (const uint4 *)operands;
     pc_probe_mfma_kernel<<<grid, 256, 0, st>>>(ops, iters, sink);          // untimed first launch
-    if (hipEventRecord(ev.t0, st) != hipSuccess) return PC_ERR_HIP;
+    if (hipEventRecord(ev.t0, st) != hipSuccess) return PC_PROBE_ERR_HIP;
     for (int r = 0; r < reps; ++r) pc_probe_mfma_kernel<<<grid, 256, 0, st>>>(ops, iters, sink);
-    if (hipEventRecord(ev.t1, st) != hipSuccess) return PC_ERR_HIP;
-    if (hipEventSynchronize(ev.t1) != hipSuccess) return PC_ERR_HIP;
-    if (hipGetLastError() != hipSuccess) return PC_ERR_HIP;
+    if (hipEventRecord(ev.t1, st) != hipSuccess) return PC_PROBE_ERR_HIP;
+    if (hipEventSynchronize(ev.t1) != hipSuccess) return PC_PROBE_ERR_HIP;
+    if (hipGetLastError() != hipSuccess) return PC_PROBE_ERR_HIP;
     float ms = 0.f;
-    if (hipEventElapsedTime(&ms, ev.t0, ev.t1) != hipSuccess || ms <= 0.f) return PC_ERR_HIP;
+    if (hipEventElapsedTime(&ms, ev.t0, ev.t1) != hipSuccess || ms <= 0.f) return PC_PROBE_ERR_HIP;
     const double flop = (double)grid * 4 * (double)iters * PROBE_CHAINS * PROBE_UNROLL * (2.0 * 32 * 32 * 16);
     *tflops = flop * reps / (ms * 1e-3) / 1e12;
-    return PC_OK;
+    return PC_PROBE_OK;
 }
 
 int32_t pc_probe_hbm_read(const void *src, int64_t bytes, int32_t reps, float *sink, double *gb_per_s,
                           void *stream) {
-    if (!src || !sink || !gb_per_s) return PC_ERR_INVALID_ARG;
-    if (bytes < 16 || (bytes & 15) || ((uintptr_t)src & 15)) return PC_ERR_SHAPE;
-    if (reps < 1 || reps > 100) return PC_ERR_INVALID_ARG;
+    if (!src || !sink || !gb_per_s) return PC_PROBE_ERR_INVALID_ARG;
+    if (bytes < 16 || (bytes & 15) || ((uintptr_t)src & 15)) return PC_PROBE_ERR_SHAPE;
+    if (reps < 1 || reps > 100) return PC_PROBE_ERR_INVALID_ARG;
     int cus = 0;
     if (int32_t rc = compute_units(&cus)) return rc;
     hipStream_t st = (hipStream_t)stream;
     EventPair ev;
-    if (ev.create() != hipSuccess) return PC_ERR_HIP;
+    if (ev.create() != hipSuccess) return PC_PROBE_ERR_HIP;
     const int grid = cus * 8;
     const u32x4 *p = (const u32x4 *)src;
     pc_probe_read_kernel<<<grid, 256, 0, st>>>(p, bytes / 16, sink);       // untimed first launch
-    if (hipEventRecord(ev.t0, st) != hipSuccess) return PC_ERR_HIP;
+    if (hipEventRecord(ev.t0, st) != hipSuccess) return PC_PROBE_ERR_HIP;
     for (int r = 0; r < reps; ++r) pc_probe_read_kernel<<<grid, 256, 0, st>>>(p, bytes / 16, sink);
-    if (hipEventRecord(ev.t1, st) != hipSuccess) return PC_ERR_HIP;
-    if (hipEventSynchronize(ev.t1) != hipSuccess) return PC_ERR_HIP;
-    if (hipGetLastError() != hipSuccess) return PC_ERR_HIP;
+    if (hipEventRecord(ev.t1, st) != hipSuccess) return PC_PROBE_ERR_HIP;
+    if (hipEventSynchronize(ev.t1) != hipSuccess) return PC_PROBE_ERR_HIP;
+    if (hipGetLastError() != hipSuccess) return PC_PROBE_ERR_HIP;
     float ms = 0.f;
-    if (hipEventElapsedTime(&ms, ev.t0, ev.t1) != hipSuccess || ms <= 0.f) return PC_ERR_HIP;
+    if (hipEventElapsedTime(&ms, ev.t0, ev.t1) != hipSuccess || ms <= 0.f) return PC_PROBE_ERR_HIP;
     *gb_per_s = (double)bytes * reps / (ms * 1e-3) / 1e9;
-    return PC_OK;
+    return PC_PROBE_OK;
 }
 
 }  // extern "C"

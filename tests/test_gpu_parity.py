@@ -232,55 +232,43 @@ def test_config5_scaled(hip):
     run_and_compare(hip, w)
 
 
-# ------------------------------- full sizes, launch configuration of the benchmark, sampled
-def _sample_rows(n_q):
-    if n_q <= 8:
-        return list(range(n_q))
-    return sorted({0, 1, 31, 32, 33, n_q // 2, n_q - 2, n_q - 1} & set(range(n_q)))
-
-
-def test_config2_full_sampled(hip):
-    w = gen.single_prefill()
-    tables_check(hip, w)
-    run_and_compare(hip, w, rows_per_call=_sample_rows)
-
-
-def test_config3_full_sampled(hip):
-    w = gen.parallel_decode()
-    tables_check(hip, w, max_calls=8)
-    run_and_compare(hip, w, calls_subset=[0, 1, 31, 63])
-
-
-def test_config4_full_sampled(hip):
-    w = gen.multi_agent_rounds()
-    run_and_compare(hip, w, rows_per_call=lambda n: [0, 100, n - 1], calls_subset=[0, 5], events=[0, 1, 5])
-
-
-def test_config5_full_sampled(hip):
-    w = gen.long_context()
-    tables_check(hip, w, max_calls=2)
-    run_and_compare(hip, w, rows_per_call=lambda n: [0] if n == 1 else [0, 777, n - 1], calls_subset=[0, 17, 32])
+# (full sizes, in the launch configuration of the benchmark: tests/test_gpu_full_configs.py)
 
 
 # --------------------------------------------------- properties that hold at any size
 def test_shift_and_permutation_on_gpu(hip):
+    """Sec. 2.4 "Position Updates": only position differences matter; "Dynamic Masking": what a call sees is a set.
+    The same call as listed, with every position moved by 4096, and with its parent list reversed: each of the
+    three against the oracle's result for ITS OWN listing, and the oracle's three results against each other
+    (they agree to fp64 rounding, so the GPU's three agree to the bf16 bars by the triangle inequality as well)."""
     import torch
+    from oracle import choreo_oracle as orc
     from pc_inputs import Call
+    from tests.helpers import cache_lists
     w = gen.single_prefill(n_msgs=12, len_lo=20, len_hi=90, n_sel=5, n_new=48)
     ev = w.events[-1]
     c0 = ev.calls[0]
     shifted = Call([(m, s + 4096) for m, s in c0.sel], c0.self_msg, c0.self_start + 4096, c0.n_q, None)
     perm = Call(list(reversed(c0.sel)), c0.self_msg, c0.self_start, c0.n_q, None)
+    q0 = ev.q
     ev.calls = [c0, shifted, perm]
-    ev.q = np.concatenate([ev.q, ev.q, ev.q], axis=0)
+    ev.q = np.concatenate([q0, q0, q0], axis=0)
     cache = hip.make_cache(w)
     dw = hip.DeviceWorkload(w)
     (out, lse), = dw.run(cache)
     torch.cuda.synchronize()
     o = out.float().cpu().numpy().reshape(3, c0.n_q, w.n_q_heads, w.head_dim)
-    # same stored keys, same arithmetic up to the rounding of the turned queries
-    assert np.abs(o[0] - o[1]).max() <= 2e-2 and np.abs(o[0] - o[1]).mean() <= 1e-3
-    assert np.abs(o[0] - o[2]).max() <= 2e-2 and np.abs(o[0] - o[2]).mean() <= 1e-3
+    l = lse.cpu().numpy().reshape(3, c0.n_q, w.n_q_heads)
+    ks, vs = cache_lists(w, upto_event=len(w.events) - 1)
+    refs = []
+    for i, c in enumerate(ev.calls):
+        ro, rl = orc.attend_call(ks, vs, c.sel, c.self_msg, c.self_start, c.n_q, c.q_pos, q0, w.rope_theta)
+        refs.append(ro)
+        d = np.abs(o[i] - ro)
+        say(f"  listing {i}: max_abs={d.max():.3e} mean_abs={d.mean():.3e}")
+        assert d.max() <= 2e-2 and d.mean() <= 1e-3
+        assert np.abs(l[i] - rl).max() <= 2e-2
+    assert np.abs(refs[0] - refs[1]).max() <= 1e-9 and np.abs(refs[0] - refs[2]).max() <= 1e-9
     cache.close()
 
 

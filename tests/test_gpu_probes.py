@@ -15,7 +15,7 @@ def say(*a):
 
 def test_probes_report_plausible_rates():
     import torch
-    import paper_2512_23049_amd as pc
+    from paper_2512_23049_amd import probe as pc
     assert torch.cuda.is_available(), "these tests need the MI355X"
     st = torch.cuda.current_stream().cuda_stream
     sink = torch.zeros(4, dtype=torch.float32, device="cuda:0")

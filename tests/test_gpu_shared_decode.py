@@ -129,14 +129,4 @@ def test_shared_walk_hand_made_cases(hip):
     cache.close()
 
 
-def test_full_size_long_context_decode_shared_sampled(hip):
-    # configs[4] at full size: the 32 decode calls take the shared walk by the default rule
-    w = gen.long_context()
-    run_and_compare(hip, w, rows_per_call=lambda n: [0] if n == 1 else [0, n - 1], calls_subset=[0, 9, 31, 32])
-
-
-def test_full_size_parallel_decode_forced_shared_sampled(hip):
-    # configs[2] at full size through the shared walk (the default rule keeps the per-call walk there): 64 calls =
-    # one group of two 32-row blocks at g = 4, the 2048-token system message seen by every row, pool messages by few
-    w = gen.parallel_decode()
-    run_and_compare(hip, w, calls_subset=[0, 1, 31, 32, 63], sharing=ALWAYS)
+# (configs[2] and configs[4] at full size through this walk: tests/test_gpu_full_configs.py)

@@ -309,17 +309,24 @@ def test_gradient_entry_points_validate_like_attend(pc):
 
 
 def test_probe_entries_reject_bad_arguments_before_touching_the_device(pc):
-    lib = pc.lib()
+    from paper_2512_23049_amd import probe
+    hdr = open(os.path.join(ROOT, "include", "pc_probe.h")).read()
+    names = set(re.findall(r"\b(pc_probe_[a-z0-9_]+)\s*\(", hdr))
+    assert names == {"pc_probe_mfma_bf16", "pc_probe_hbm_read"}
+    lib = probe.lib()
+    for n in names:
+        assert hasattr(lib, n), n
     out = ctypes.c_double(0.0)
     one = ctypes.c_void_p(4096)            # never dereferenced: every call below fails its argument checks
-    assert lib.pc_probe_mfma_bf16(None, 8192, 16, 2, 1, one, ctypes.byref(out), None) == pc.PC_ERR_INVALID_ARG
-    assert lib.pc_probe_mfma_bf16(one, 8191, 16, 2, 1, one, ctypes.byref(out), None) == pc.PC_ERR_SHAPE
-    assert lib.pc_probe_mfma_bf16(one, 8192, 0, 2, 1, one, ctypes.byref(out), None) == pc.PC_ERR_INVALID_ARG
-    assert lib.pc_probe_mfma_bf16(one, 8192, 16, 3, 1, one, ctypes.byref(out), None) == pc.PC_ERR_INVALID_ARG
-    assert lib.pc_probe_hbm_read(None, 1 << 20, 1, one, ctypes.byref(out), None) == pc.PC_ERR_INVALID_ARG
-    assert lib.pc_probe_hbm_read(one, 24, 1, one, ctypes.byref(out), None) == pc.PC_ERR_SHAPE
-    assert lib.pc_probe_hbm_read(ctypes.c_void_p(4100), 1 << 20, 1, one, ctypes.byref(out), None) == pc.PC_ERR_SHAPE
-    assert lib.pc_probe_hbm_read(one, 1 << 20, 0, one, ctypes.byref(out), None) == pc.PC_ERR_INVALID_ARG
+    INVALID, SHAPE = -1, -4
+    assert lib.pc_probe_mfma_bf16(None, 16384, 16, 2, 1, one, ctypes.byref(out), None) == INVALID
+    assert lib.pc_probe_mfma_bf16(one, 16383, 16, 2, 1, one, ctypes.byref(out), None) == SHAPE
+    assert lib.pc_probe_mfma_bf16(one, 16384, 0, 2, 1, one, ctypes.byref(out), None) == INVALID
+    assert lib.pc_probe_mfma_bf16(one, 16384, 16, 3, 1, one, ctypes.byref(out), None) == INVALID
+    assert lib.pc_probe_hbm_read(None, 1 << 20, 1, one, ctypes.byref(out), None) == INVALID
+    assert lib.pc_probe_hbm_read(one, 24, 1, one, ctypes.byref(out), None) == SHAPE
+    assert lib.pc_probe_hbm_read(ctypes.c_void_p(4100), 1 << 20, 1, one, ctypes.byref(out), None) == SHAPE
+    assert lib.pc_probe_hbm_read(one, 1 << 20, 0, one, ctypes.byref(out), None) == INVALID
     assert out.value == 0.0
 
 
