@@ -175,6 +175,20 @@ typedef struct {
 int32_t pc_attend(pc_cache *c, const pc_call *calls, int32_t n_calls,
                   const void *q, void *out, float *lse, void *stream);
 
+/* pc_attend for callers that cannot allocate device memory: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments, same kernels, same results (bit for bit) as pc_attend; the
+ * per-call workspace (staged descriptors, the device-built plan, split partials) lives in a fixed array of
+ * PC_STATIC_WS_BYTES (32 MiB) that the library holds on every GPU it runs on until the process ends, and the
+ * function calls no hipMalloc, hipFree or other allocating routine.  A batch whose workspace exceeds that size, or
+ * whose staged descriptors exceed one slot of the cache's pinned staging ring (1 MiB), is rejected with
+ * PC_ERR_NO_SPACE before anything is enqueued (pc_last_error names both sizes).  Kernel timing (pc_profile_enable)
+ * does not cover it.  Every cache on a GPU shares that GPU's array, which keeps the last call's contents (nothing
+ * in it has to start at zero: every call writes what it reads): calls on one GPU that overlap in time - two
+ * streams, or two caches - race; order them on one stream or with events. */
+#define PC_STATIC_WS_BYTES ((size_t)32 << 20)
+int32_t pc_attend_static(pc_cache *c, const pc_call *calls, int32_t n_calls,
+                         const void *q, void *out, float *lse, void *stream);
+
 /* In-place position update of a cached message (Sec. 2.4 "Position Updates": the
  * paper's mechanism, a rotation of the cached keys through a table of the D/2
  * rotations for the move).  The stored key of token t, so far turned to position

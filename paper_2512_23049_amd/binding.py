@@ -72,6 +72,8 @@ def lib():
         L.pc_append_tokens_batch.argtypes = [vp, C.POINTER(i32), i32, vp, vp, vp]
         L.pc_attend.restype = i32
         L.pc_attend.argtypes = [vp, C.POINTER(pc_call), i32, vp, vp, vp, vp]
+        L.pc_attend_static.restype = i32
+        L.pc_attend_static.argtypes = [vp, C.POINTER(pc_call), i32, vp, vp, vp, vp]
         L.pc_build_tables.restype = i32
         L.pc_build_tables.argtypes = [vp, C.POINTER(pc_call), vp, vp, i64, C.POINTER(i64), vp]
         L.pc_resolve_call.restype = i32
@@ -182,6 +184,11 @@ class Cache:
         arr, keep = marshalled if marshalled is not None else marshal_calls(calls)
         self._check(lib().pc_attend(self.h, arr, len(calls), q_ptr or None, out_ptr or None,
                                     lse_ptr or None, stream or None))
+
+    def attend_static(self, calls, q_ptr: int, out_ptr: int, lse_ptr: int = 0, stream: int = 0, marshalled=None):
+        arr, keep = marshalled if marshalled is not None else marshal_calls(calls)
+        self._check(lib().pc_attend_static(self.h, arr, len(calls), q_ptr or None, out_ptr or None,
+                                           lse_ptr or None, stream or None))
 
     def build_tables(self, call, kv_slot_ptr: int, kv_pos_ptr: int, cap: int, stream: int = 0) -> int:
         arr, keep = marshal_calls([call])

@@ -1,20 +1,41 @@
 // Host side of the library: the attention entry points (forward, gradient, expanded tables).
 #include "pc_host.h"
 
-extern "C" {
+// ---------------------------------------------------------------------------------------------------------
+// The library's fixed scratch memory: the per-call workspace (staged descriptors, the device-built plan, split
+// partials) of pc_attend_static, for callers that must not allocate.  Every device the library runs on holds its
+// own copy of the array, at its own address, until the process ends.  In host code the array's NAME is only a
+// handle: the address kernels and copies can use comes from hipGetSymbolAddress, looked up once per device with
+// that device current, and only that pointer is ever passed on.
+// ---------------------------------------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char scratch[PC_STATIC_WS_BYTES];
 
-int32_t pc_attend(pc_cache *c, const pc_call *calls, int32_t n_calls, const void *q, void *out, float *lse, void *stream)
+int32_t pc_static_scratch(void **ptr, size_t *bytes)
 {
-    if (!c) return PC_ERR_INVALID_ARG;
-    if (n_calls < 0 || (n_calls > 0 && !calls)) return pc_fail(c, PC_ERR_INVALID_ARG, "attend: bad call list");
-    if (n_calls == 0) return PC_OK;
-    if (!c->host_only && (!q || !out)) return pc_fail(c, PC_ERR_INVALID_ARG, "attend: null q or out");
-    hipStream_t st = (hipStream_t)stream;
+    constexpr int MAX_DEV = 64;
+    static void *per_device[MAX_DEV] = {nullptr};
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEV) return PC_ERR_HIP;
+    if (!per_device[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return PC_ERR_HIP;
+        per_device[dev] = p;
+    }
+    *ptr = per_device[dev];
+    *bytes = PC_STATIC_WS_BYTES;
+    return PC_OK;
+}
+
+// fixed_ws: nullptr = the cache's own workspace (grows on demand), else a buffer of fixed_cap bytes the call must fit into
+static int32_t attend_impl(pc_cache *c, const pc_call *calls, int32_t n_calls, const void *q, void *out, float *lse,
+                           hipStream_t st, void *fixed_ws, size_t fixed_cap)
+{
     Planned P;
+    P.fixed_ws = fixed_ws; P.fixed_cap = fixed_cap;
     const int32_t rc = pc_plan_and_stage(c, calls, n_calls, true, st, P);
     if (rc != PC_OK || c->host_only) return rc;
 
-    char *w = (char *)c->ws;
+    char *w = (char *)P.ws;
     PcLaunch L{};
     L.calls = (const PcCallDesc *)(w + P.lay.calls);
     L.segs = (const PcSegment *)(w + P.lay.segs);
@@ -65,6 +86,32 @@ int32_t pc_attend(pc_cache *c, const pc_call *calls, int32_t n_calls, const void
     return PC_OK;
 }
 
+extern "C" {
+
+int32_t pc_attend(pc_cache *c, const pc_call *calls, int32_t n_calls, const void *q, void *out, float *lse, void *stream)
+{
+    if (!c) return PC_ERR_INVALID_ARG;
+    if (n_calls < 0 || (n_calls > 0 && !calls)) return pc_fail(c, PC_ERR_INVALID_ARG, "attend: bad call list");
+    if (n_calls == 0) return PC_OK;
+    if (!c->host_only && (!q || !out)) return pc_fail(c, PC_ERR_INVALID_ARG, "attend: null q or out");
+    return attend_impl(c, calls, n_calls, q, out, lse, (hipStream_t)stream, nullptr, 0);
+}
+
+int32_t pc_attend_static(pc_cache *c, const pc_call *calls, int32_t n_calls, const void *q, void *out, float *lse, void *stream)
+{
+    if (!c) return PC_ERR_INVALID_ARG;
+    if (n_calls < 0 || (n_calls > 0 && !calls)) return pc_fail(c, PC_ERR_INVALID_ARG, "attend_static: bad call list");
+    if (n_calls == 0) return PC_OK;
+    if (c->host_only) return attend_impl(c, calls, n_calls, q, out, lse, nullptr, nullptr, 0);
+    if (!q || !out) return pc_fail(c, PC_ERR_INVALID_ARG, "attend_static: null q or out");
+    if (!c->static_ws) return pc_fail(c, PC_ERR_HIP, "attend_static: the fixed scratch array was not found on this device");
+    const bool prof = c->prof;                           // kernel timing takes events from a pool that may have to grow
+    c->prof = false;
+    const int32_t rc = attend_impl(c, calls, n_calls, q, out, lse, (hipStream_t)stream, c->static_ws, PC_STATIC_WS_BYTES);
+    c->prof = prof;
+    return rc;
+}
+
 int32_t pc_attend_backward(pc_cache *c, const pc_call *calls, int32_t n_calls, const void *q, const float *lse,
                            const void *d_out, float *d_q, float *d_k, float *d_v, void *stream)
 {
@@ -77,7 +124,7 @@ int32_t pc_attend_backward(pc_cache *c, const pc_call *calls, int32_t n_calls, c
     Planned P;
     const int32_t rc = pc_plan_and_stage(c, calls, n_calls, false, st, P);
     if (rc != PC_OK || c->host_only) return rc;
-    char *w = (char *)c->ws;
+    char *w = (char *)P.ws;
     PcLaunch L{};
     L.calls = (const PcCallDesc *)(w + P.lay.calls);
     L.segs = (const PcSegment *)(w + P.lay.segs);
@@ -131,7 +178,7 @@ int32_t pc_build_tables(pc_cache *c, const pc_call *call, int32_t *kv_slot, int3
     if (c->host_only || cap < n || n == 0) return PC_OK;
     if (!kv_slot || !kv_pos) return pc_fail(c, PC_ERR_INVALID_ARG, "build_tables: null output with cap > 0");
     ProfScope ps(c, 6, st);
-    char *w = (char *)c->ws;
+    char *w = (char *)P.ws;
     pc_launch_expand_tables((const PcSegment *)(w + P.lay.segs), (const int32_t *)(w + P.lay.seg_kvoff), P.total_seg, n,
                             kv_slot, kv_pos, st);
     PC_HIP(c, hipGetLastError());

@@ -61,6 +61,7 @@ struct pc_cache {
     // tuning
     int decode_tiles_per_split = 0, prefill_tiles_per_split = 0;
     int decode_sharing = 0;                            // 0 auto, 1 never, 2 whenever possible
+    void *static_ws = nullptr;                         // this device's copy of the library's fixed scratch array
     std::string err;
 };
 
@@ -133,12 +134,19 @@ struct Planned {
     int n_sh_items = 0;
     size_t n_sh_pos = 0;
     std::vector<Resolved> res;
+    // Where the call's workspace lives.  On entry: fixed_ws != nullptr names a buffer of fixed_cap bytes the plan
+    // must fit into (nothing is allocated then: a plan or staging block that does not fit is an error); nullptr
+    // means the cache's own workspace, which grows on demand.  On return ws is the buffer the plan was staged to.
+    void *fixed_ws = nullptr; size_t fixed_cap = 0;
+    void *ws = nullptr;
 };
 
 // pc_lib.hip
 int32_t pc_ensure_ws(pc_cache *c, size_t bytes, hipStream_t st);
 int32_t pc_stage_acquire(pc_cache *c, size_t bytes, StageSlot **out);
 extern "C" int32_t pc_stage_items(pc_cache *c, const void *items, size_t bytes, hipStream_t st);
+// pc_attend.hip: the address, on the current device, of the library's fixed scratch array (looked up once per device)
+int32_t pc_static_scratch(void **ptr, size_t *bytes);
 // pc_plan.hip
 int32_t pc_resolve(pc_cache *c, const pc_call *call, int idx, Resolved &out);
 int32_t pc_plan_and_stage(pc_cache *c, const pc_call *calls, int32_t n_calls, bool want_items, hipStream_t st, Planned &P);

@@ -124,6 +124,10 @@ int32_t pc_cache_create(const pc_config *cfg, pc_cache **out)
         c->stage[i].cap = (size_t)1 << 20;
         if (hipEventCreateWithFlags(&c->stage[i].ev, hipEventDisableTiming) != hipSuccess) return bail(PC_ERR_HIP);
     }
+    {   // this device's address of the library's fixed scratch array (pc_attend_static works in it)
+        size_t n = 0;
+        if (pc_static_scratch(&c->static_ws, &n) != PC_OK) return bail(PC_ERR_HIP);
+    }
     if (hipDeviceSynchronize() != hipSuccess) return bail(PC_ERR_HIP);
     return PC_OK;
 }

@@ -378,8 +378,20 @@ int32_t pc_plan_and_stage(pc_cache *c, const pc_call *calls, int32_t n_calls, bo
                         sp.groups.size(), sp.segs.size(), sp.items.size(), sp.pos.size());
     if (c->host_only) return PC_OK;
 
-    int32_t rc = pc_ensure_ws(c, P.lay.total, st);
-    if (rc != PC_OK) return rc;
+    int32_t rc = PC_OK;
+    if (P.fixed_ws) {                                    // nothing may be allocated: the plan fits or the call fails
+        if (P.lay.total > P.fixed_cap)
+            return pc_fail(c, PC_ERR_NO_SPACE, "attend: this batch needs %zu bytes of workspace, the fixed one holds %zu",
+                           P.lay.total, P.fixed_cap);
+        if (P.lay.h2d_bytes > c->stage[c->stage_next].cap)
+            return pc_fail(c, PC_ERR_NO_SPACE, "attend: this batch stages %zu bytes of descriptors, the pinned ring slot holds %zu",
+                           P.lay.h2d_bytes, c->stage[c->stage_next].cap);
+        P.ws = P.fixed_ws;
+    } else {
+        rc = pc_ensure_ws(c, P.lay.total, st);
+        if (rc != PC_OK) return rc;
+        P.ws = c->ws;
+    }
     StageSlot *slot = nullptr;
     rc = pc_stage_acquire(c, P.lay.h2d_bytes, &slot);
     if (rc != PC_OK) return rc;
@@ -414,12 +426,12 @@ int32_t pc_plan_and_stage(pc_cache *c, const pc_call *calls, int32_t n_calls, bo
         std::memcpy(h + P.lay.sh_items, sp.items.data(), sizeof(PcShItem) * sp.items.size());
         std::memcpy(h + P.lay.sh_pos, sp.pos.data(), sizeof(int32_t) * sp.pos.size());
     }
-    PC_HIP(c, hipMemcpyAsync(c->ws, h, P.lay.h2d_bytes, hipMemcpyHostToDevice, st));
+    PC_HIP(c, hipMemcpyAsync(P.ws, h, P.lay.h2d_bytes, hipMemcpyHostToDevice, st));
     PC_HIP(c, hipEventRecord(slot->ev, st));
     slot->used = true;
     {
         ProfScope ps(c, 1, st);
-        char *w = (char *)c->ws;
+        char *w = (char *)P.ws;
         pc_launch_build_plan((const PcCallDesc *)(w + P.lay.calls), n_calls, (const int2 *)(w + P.lay.sel),
                              (const int32_t *)(w + P.lay.q_pos), c->table_dev, c->inv_freq_dev, c->half, P.total_seg,
                              P.total_q, (PcSegment *)(w + P.lay.segs), (int32_t *)(w + P.lay.seg_kvoff),
