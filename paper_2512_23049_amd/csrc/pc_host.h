@@ -43,6 +43,7 @@ struct pc_cache {
     std::vector<HostMsg> msgs;
     std::vector<FreeSpan> free_spans;                // sorted by start, neighbours merged, none touches next_slot
     int64_t next_slot = 0;
+    int64_t dirty_end = 0;                           // slots below this may hold what a freed or swapped-out message left
     bool slots_in_id_order = true;                   // no message was ever placed in a freed span: ids ascend with slots
     // device
     void *storage = nullptr; bool owns_storage = false;

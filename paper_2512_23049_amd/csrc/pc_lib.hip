@@ -170,6 +170,16 @@ static bool take_slots(std::vector<FreeSpan> &spans, int64_t &next, int64_t capa
     return true;
 }
 
+// A span taken where a freed or swapped-out message may have lived: its V rows are cleared before the new owner's
+// append kernel runs (the attention kernels multiply what lies behind a message's last token, inside its last
+// tile, by exact zeros, which needs finite values there).
+static void clear_if_reused(pc_cache *c, int64_t start, int32_t res, hipStream_t st)
+{
+    if (c->host_only || start >= c->dirty_end) return;
+    const int64_t need = (int64_t)align_up((size_t)res, PC_SLOT_ALIGN);
+    pc_launch_zero_v_span(c->cfg.dtype, c->v_store, c->slots, c->cfg.n_kv_heads, c->D, start, std::min(need, c->dirty_end - start), st);
+}
+
 int32_t pc_append_message(pc_cache *c, const void *k, const void *v, int32_t len, int32_t reserve,
                           int32_t *msg_id, void *stream)
 {
@@ -190,6 +200,7 @@ int32_t pc_append_message(pc_cache *c, const void *k, const void *v, int32_t len
     const int id = (int)c->msgs.size();
     if (!c->host_only) {
         hipStream_t st = (hipStream_t)stream;
+        clear_if_reused(c, start, res, st);
         ProfScope ps(c, 0, st);
         pc_launch_append(c->cfg.dtype, k, v, len, c->cfg.n_kv_heads, c->D, start, c->slots, c->inv_freq_dev,
                          c->k_store, c->v_store, c->table_dev, id, st);
@@ -261,6 +272,7 @@ int32_t pc_append_messages(pc_cache *c, int32_t n, const void *const *k, const v
         hipStream_t st = (hipStream_t)stream;
         const int32_t rc = pc_stage_items(c, items.data(), sizeof(PcAppendItem) * (size_t)n, st);
         if (rc != PC_OK) return rc;
+        for (int j = 0; j < n; ++j) clear_if_reused(c, fresh[(size_t)j].slot_start, fresh[(size_t)j].reserve, st);
         ProfScope ps(c, 0, st);
         pc_launch_append_batch(c->cfg.dtype, (const PcAppendItem *)c->tok_dev, n, max_len, c->cfg.n_kv_heads, c->D, c->slots,
                                c->inv_freq_dev, c->k_store, c->v_store, c->table_dev, st);
@@ -332,6 +344,7 @@ static int32_t append_token_items(pc_cache *c, const std::vector<int32_t> &ids, 
         close_extent(run_end);
     }
     if (!c->host_only) {
+        for (const HostMsg &rec : fresh) clear_if_reused(c, rec.slot_start, rec.reserve, st);
         if (!fresh.empty()) {                                // the device table learns the new extents (length 0 until the kernel sets it)
             StageSlot *slot = nullptr;
             const int32_t rc = pc_stage_acquire(c, sizeof(PcMsgEntry) * fresh.size(), &slot);
@@ -490,6 +503,7 @@ int32_t pc_reposition_batch(pc_cache *c, const int32_t *msg_ids, const int32_t *
 // gives a span of slots back: sorted insert, merge with its neighbours, shrink the used region
 static void release_span(pc_cache *c, FreeSpan f)
 {
+    c->dirty_end = std::max(c->dirty_end, f.start + f.size);
     auto &fs = c->free_spans;
     size_t i = 0;
     while (i < fs.size() && fs[i].start < f.start) ++i;
