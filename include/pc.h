@@ -271,8 +271,8 @@ int32_t pc_cache_info(pc_cache *c, int32_t *n_messages, int64_t *slots_used,
  * bracketed by events on the caller's stream.  pc_profile_read waits for the stream
  * work recorded so far, then returns per-kernel-class totals since the last reset.
  * Classes: 0 append, 1 plan builder, 2 prefill attention, 3 decode attention,
- * 4 split merge, 5 fp32 attention, 6 table expansion, 7 reposition. */
-#define PC_N_KERNEL_CLASSES 8
+ * 4 split merge, 5 fp32 attention, 6 table expansion, 7 reposition, 8 key gather. */
+#define PC_N_KERNEL_CLASSES 9
 int32_t pc_profile_enable(pc_cache *c, int32_t on);
 int32_t pc_profile_read(pc_cache *c, double ms_total[PC_N_KERNEL_CLASSES],
                         int64_t launches[PC_N_KERNEL_CLASSES], int32_t reset);
@@ -280,6 +280,15 @@ int32_t pc_profile_read(pc_cache *c, double ms_total[PC_N_KERNEL_CLASSES],
 /* Tuning knobs (0 keeps the default): KV tiles (of 32 keys) per split for decode
  * and for prefill work items. */
 int32_t pc_set_tuning(pc_cache *c, int32_t decode_tiles_per_split, int32_t prefill_tiles_per_split);
+
+/* Key gather (Sec. 2.4 "Position Updates", applied to a copy).  A prefill call with many query rows can have
+ * its keys copied once, each message turned to the position the call gives it, into the call's workspace; the
+ * attention kernel then reads keys from the copy and turns the queries by their own position only, instead of
+ * once more per listed message.  The cache itself is not changed, results are the same up to one more rounding
+ * of the copied keys to bf16.  mode 0 (default): calls for which the copy costs less than the turns it saves
+ * (rows x query heads above about 5300 x the call's KV tiles per listed message); 1: never; 2: every prefill call.
+ * PC_BF16 caches only; pc_attend_static never gathers (the copy may not fit its fixed workspace). */
+int32_t pc_set_key_gather(pc_cache *c, int32_t mode);
 
 /* Gradient of pc_attend for fine-tuning (Sec. 2.4: while fine-tuning, a position update is
  * applied to the keys without destroying them, so that gradients flow back through it to the

@@ -21,8 +21,8 @@ PC_POS_AUTO = -(2 ** 31)
 PC_SLOT_ALIGN = 32
 PC_FLAG_HOST_ONLY = 1
 PC_FLAG_GROW_EXTENTS = 2
-PC_N_KERNEL_CLASSES = 8
-KERNEL_CLASSES = ("append", "plan", "prefill", "decode", "merge", "attend_f32", "expand", "reposition")
+PC_N_KERNEL_CLASSES = 9
+KERNEL_CLASSES = ("append", "plan", "prefill", "decode", "merge", "attend_f32", "expand", "reposition", "gather")
 
 
 class pc_config(C.Structure):
@@ -110,6 +110,8 @@ def lib():
         L.pc_grad_keys_finalize.argtypes = [vp, vp, vp]
         L.pc_set_decode_sharing.restype = i32
         L.pc_set_decode_sharing.argtypes = [vp, i32]
+        L.pc_set_key_gather.restype = i32
+        L.pc_set_key_gather.argtypes = [vp, i32]
         _lib = L
     return _lib
 
@@ -287,6 +289,10 @@ class Cache:
         starts, lens = (C.c_int64 * cap)(), (C.c_int32 * cap)()
         self._check(lib().pc_message_extents(self.h, msg, C.byref(n), starts, lens, cap))
         return [(int(starts[i]), int(lens[i])) for i in range(min(cap, n.value))]
+
+    def set_key_gather(self, mode: int = 0):
+        """0: prefill calls with enough rows read keys from a copy turned to their positions; 1: never; 2: always."""
+        self._check(lib().pc_set_key_gather(self.h, mode))
 
     def set_decode_sharing(self, mode: int = 0):
         """0: shared walk when a group's calls overlap enough; 1: never; 2: whenever the shape allows."""

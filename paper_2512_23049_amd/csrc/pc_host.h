@@ -62,6 +62,7 @@ struct pc_cache {
     // tuning
     int decode_tiles_per_split = 0, prefill_tiles_per_split = 0;
     int decode_sharing = 0;                            // 0 auto, 1 never, 2 whenever possible
+    int key_gather = 0;                                // 0 auto, 1 never, 2 every prefill call
     void *static_ws = nullptr;                         // this device's copy of the library's fixed scratch array
     std::string err;
 };
@@ -121,8 +122,8 @@ inline int32_t chain_last(const pc_cache *c, int32_t m)
 
 // layout of the staged (host -> device) block and of the device-built block
 struct PlanLayout {
-    size_t calls, sel, q_pos, row_call, merge_rows, items_dec, items_pre, sh_groups, sh_segs, sh_items, sh_pos, h2d_bytes;
-    size_t segs, seg_kvoff, rot_seg, rot_q, tiles, sh_rot, part_o, part_ml, row_scalar, total;
+    size_t calls, sel, q_pos, row_call, merge_rows, items_dec, items_pre, sh_groups, sh_segs, sh_items, sh_pos, kg_items, h2d_bytes;
+    size_t segs, seg_kvoff, rot_seg, rot_q, tiles, sh_rot, part_o, part_ml, row_scalar, k_gather, total;
 };
 
 // -------------------------------------------------------------------------------------
@@ -134,6 +135,7 @@ struct Planned {
     int n_merge_rows = 0, n_merge_few = 0;               // rows to merge; the first n_merge_few have few splits
     int n_sh_items = 0;
     size_t n_sh_pos = 0;
+    int n_kg_items = 0; int64_t kg_tiles = 0;            // calls whose keys are gathered, and their tiles in all
     std::vector<Resolved> res;
     // Where the call's workspace lives.  On entry: fixed_ws != nullptr names a buffer of fixed_cap bytes the plan
     // must fit into (nothing is allocated then: a plan or staging block that does not fit is an error); nullptr

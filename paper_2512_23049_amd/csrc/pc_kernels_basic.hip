@@ -563,10 +563,11 @@ __global__ __launch_bounds__(256) void pc_build_plan_kernel(
     }
     // rotation tables: entity = segment (position from the staged lists) or query row
     const int64_t tid = (int64_t)(blockIdx.x - n_calls) * 256 + threadIdx.x;
-    const int64_t n_ent = (int64_t)total_seg + total_q;
+    const int64_t n_ent = (int64_t)total_seg + total_q + 1;          // the last one: the rotation by zero, row total_seg of rot_seg
     if (tid >= n_ent * half) return;
     const int ent = (int)(tid / half);
     const int i = (int)(tid % half);
+    if (ent == total_seg + total_q) { rot_seg[(int64_t)total_seg * half + i] = make_float2(1.f, 0.f); return; }
     int pos;
     if (ent < total_seg) {
         // find the call that owns this segment (calls are few; segments are laid out call by call)
@@ -596,7 +597,7 @@ void pc_launch_build_plan(const PcCallDesc *calls, int n_calls, const int2 *sel,
                           int total_q, PcSegment *segs, int32_t *seg_kvoff, float2 *rot_seg,
                           float2 *rot_q, PcTile *tiles, hipStream_t st)
 {
-    const int64_t n_rot = ((int64_t)total_seg + total_q) * half;
+    const int64_t n_rot = ((int64_t)total_seg + total_q + 1) * half;
     const unsigned grid = (unsigned)(n_calls + (n_rot + 255) / 256);
     pc_build_plan_kernel<<<grid, 256, 0, st>>>(calls, n_calls, sel, q_pos, table, inv_freq, half, total_seg,
                                                total_q, segs, seg_kvoff, rot_seg, rot_q, tiles);
@@ -850,4 +851,53 @@ void pc_launch_zero_v_span(int dtype, void *v_store, int64_t slots, int n_kv_hea
     const int64_t n16 = n_slots * per_slot16;
     dim3 grid((unsigned)std::min<int64_t>((n16 + 255) / 256, 1024), (unsigned)n_kv_heads);
     pc_zero_v_span_kernel<<<grid, 256, 0, st>>>((uint4 *)v_store, slots * per_slot16, slot_start * per_slot16, n16);
+}
+
+// ----------------------------------------------------------------------------------------
+// K2g: key gather.  For a call with many query rows it is cheaper to turn the KEYS to the
+// positions the call gives them once than to turn the queries of every (32-row block, head) at
+// every segment: the call's key tiles are copied, in the order of its tile table, into a buffer
+// of their own, key t of a segment turned from its stored position base + t to start + t (Sec. 2.4
+// "Position Updates": the rotation by start - base, here into a copy, so that the cache keeps its
+// position-independent form and other calls may place the same message elsewhere).  The prefill
+// kernel then reads K from the copy with queries turned by their own position only; V stays where
+// it is.  Rows past a message's end are written as zeros.
+// One block per (tile, KV head): thread = (key row, 8 low dims and their partners 64 up).
+// ----------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void pc_gather_keys_kernel(PcLaunch L, const PcGatherItem *__restrict__ items, int n_items)
+{
+    const int G = blockIdx.x, kh = blockIdx.y;
+    int j = 0;
+    while (j + 1 < n_items && items[j + 1].kg_tile0 <= G) ++j;           // few calls gather: a short scan
+    const PcGatherItem it = items[j];
+    const PcCallDesc cd = L.calls[it.call];
+    const PcTile tl = L.tiles[cd.tile_off + (G - it.kg_tile0)];
+    const int valid = tl.valid_flags & 0xFF;
+    const int r = threadIdx.x >> 3, c = threadIdx.x & 7;
+    const uint16_t *src = (const uint16_t *)L.k_store + ((int64_t)kh * L.slots + tl.slot0 + r) * 128 + 8 * c;
+    uint16_t *dst = (uint16_t *)L.k_gather + ((int64_t)kh * L.kg_slots + (int64_t)G * PC_TILE + r) * 128 + 8 * c;
+    uint4 lo = make_uint4(0, 0, 0, 0), hi = lo;
+    if (r < valid) {
+        lo = *reinterpret_cast<const uint4 *>(src);
+        hi = *reinterpret_cast<const uint4 *>(src + 64);
+        const float4 *rot = reinterpret_cast<const float4 *>(L.rot_seg + (int64_t)(cd.seg_off + tl.seg) * 64 + 8 * c);
+        uint32_t *lw = reinterpret_cast<uint32_t *>(&lo), *hw = reinterpret_cast<uint32_t *>(&hi);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const float4 cs = rot[u];                    // (cos, sin) of pairs 2u and 2u + 1
+            using P = Pair2<__hip_bfloat16>;
+            const float x0 = P::lo(lw[u]), x1 = P::hi(lw[u]), y0 = P::lo(hw[u]), y1 = P::hi(hw[u]);
+            lw[u] = P::pack(x0 * cs.x - y0 * cs.y, x1 * cs.z - y1 * cs.w);
+            hw[u] = P::pack(x0 * cs.y + y0 * cs.x, x1 * cs.w + y1 * cs.z);
+        }
+    }
+    *reinterpret_cast<uint4 *>(dst) = lo;
+    *reinterpret_cast<uint4 *>(dst + 64) = hi;
+}
+
+void pc_launch_gather_keys(const PcLaunch &L, const PcGatherItem *items, int n_items, int64_t n_tiles, hipStream_t st)
+{
+    if (n_items <= 0 || n_tiles <= 0) return;
+    dim3 grid((unsigned)n_tiles, (unsigned)L.n_kv_heads);
+    pc_gather_keys_kernel<<<grid, 256, 0, st>>>(L, items, n_items);
 }

@@ -134,8 +134,15 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
         }
     };
 
-    const unsigned char *kb = (const unsigned char *)L.k_store + (int64_t)kh * L.slots * PC_D * 2;
+    // A call whose keys were gathered (copied tile by tile, each message turned to the position the call gives it)
+    // reads K from the copy, tile t of the call at slot 32 t, and never turns its queries after the first tile,
+    // which uses the table's last row, the rotation by zero.  V comes from the cache either way.
+    const int kg = __builtin_amdgcn_readfirstlane(cd.kg_tile0);
+    const bool gathered = kg >= 0;
+    const unsigned char *kb = gathered ? (const unsigned char *)L.k_gather + ((int64_t)kh * L.kg_slots + (int64_t)kg * PC_TILE) * PC_D * 2
+                                       : (const unsigned char *)L.k_store + (int64_t)kh * L.slots * PC_D * 2;
     const unsigned char *vb = (const unsigned char *)L.v_store + (int64_t)kh * L.slots * PC_D * 2;
+    const int flag_keep = gathered ? ~PC_TILE_FRESH : ~0, seg_keep = gathered ? 0 : ~0;
 
     // tiles this workgroup walks: its split's range (the host has cut it at the causal limit of the
     // workgroup's last row, so nothing has to be looked up for it)
@@ -171,7 +178,7 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
     typedef int i32x4 __attribute__((ext_vector_type(4)));
     auto decode = [&](const i32x4 &v) {
         Desc d;
-        d.slot0 = v.x; d.key0 = v.y; d.seg = v.z; d.flags = v.w;
+        d.slot0 = v.x; d.key0 = v.y; d.seg = v.z & seg_keep; d.flags = v.w & flag_keep;
         return d;
     };
     auto describe = [&](int t) {
@@ -196,11 +203,13 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
     const unsigned wave_lds = __builtin_amdgcn_readfirstlane(wave) * 1024;
     const unsigned lds_k = (unsigned)(size_t)&s_k[0][0] + wave_lds, lds_v = (unsigned)(size_t)&s_v[0][0] + wave_lds;
     const unsigned lds_rot = (unsigned)(size_t)&s_rot[0][0];
-    const unsigned char *rot_base = (const unsigned char *)(L.rot_seg + (int64_t)cd.seg_off * (PC_D / 2));
-    auto dma_k = [&](const Desc &d, int slot) {         // the rotation table first: it must be the oldest request
+    const unsigned char *rot_base = (const unsigned char *)(L.rot_seg + (int64_t)(gathered ? L.ident_row : cd.seg_off) * (PC_D / 2));
+    // t: the tile's index in the call's tile table
+    auto dma_k = [&](const Desc &d, int slot, int t) {  // the rotation table first: it must be the oldest request
         if (d.fresh() && threadIdx.x < 32)
             dma16(rot_base + (int64_t)__builtin_amdgcn_readfirstlane(d.seg) * (PC_D / 2) * sizeof(float2), threadIdx.x * 16, lds_rot + slot * (unsigned)sizeof(s_rot[0]));
-        dma16(kb + (int64_t)__builtin_amdgcn_readfirstlane(d.slot0) * 256, k_src_off, lds_k + slot * TILE_BYTES);
+        const int ks0 = gathered ? (__builtin_amdgcn_readfirstlane(t) << 5) : __builtin_amdgcn_readfirstlane(d.slot0);
+        dma16(kb + (int64_t)ks0 * 256, k_src_off, lds_k + slot * TILE_BYTES);
     };
     auto dma_v = [&](const Desc &d, int slot) {
         dma16(vb + (int64_t)__builtin_amdgcn_readfirstlane(d.slot0) * 256, v_src_off, lds_v + slot * TILE_BYTES);
@@ -390,11 +399,11 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
         Desc d3 = describe(min(tile0 + 3, last));
         Desc d4 = describe(min(tile0 + 4, last));
         Desc d5 = describe(min(tile0 + 5, last));
-        dma_k(d0, 0); dma_v(d0, 0);
-        dma_k(d1, 1); dma_v(d1, 1);
-        dma_k(d2, 2); dma_v(d2, 2);
-        dma_k(d3, 3); dma_v(d3, 3);
-        dma_k(d4, 4);
+        dma_k(d0, 0, tile0); dma_v(d0, 0);
+        dma_k(d1, 1, min(tile0 + 1, last)); dma_v(d1, 1);
+        dma_k(d2, 2, min(tile0 + 2, last)); dma_v(d2, 2);
+        dma_k(d3, 3, min(tile0 + 3, last)); dma_v(d3, 3);
+        dma_k(d4, 4, min(tile0 + 4, last));
         load_query();
         __builtin_amdgcn_s_waitcnt(0x0F70);              // vmcnt(0)
         __syncthreads();
@@ -426,7 +435,7 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
             constexpr int u = decltype(uc)::value;
             constexpr int s0 = u, s1 = (u + 1) % RING, s2 = (u + 2) % RING, s4 = (u + 4) % RING;
             i32x4 raw6 = request_desc(min(tile0 + i + 6, last));     // first used in the next iteration's requests
-            f32x16 sn = phase_a(s0, sc, [&] { dma_k(d5, s0); });             // K(i+5) takes the slot of K(i)
+            f32x16 sn = phase_a(s0, sc, [&] { dma_k(d5, s0, min(tile0 + i + 5, last)); });             // K(i+5) takes the slot of K(i)
             // the descriptor is awaited here, where the wait costs nothing: it waits for every LDS
             // read too, and the V fragments requested during phase A arrived while its vector work
             // finished

@@ -675,6 +675,13 @@ int32_t pc_set_decode_sharing(pc_cache *c, int32_t mode)
     return PC_OK;
 }
 
+int32_t pc_set_key_gather(pc_cache *c, int32_t mode)
+{
+    if (!c || mode < 0 || mode > 2) return PC_ERR_INVALID_ARG;
+    c->key_gather = mode;
+    return PC_OK;
+}
+
 int32_t pc_set_tuning(pc_cache *c, int32_t decode_tiles_per_split, int32_t prefill_tiles_per_split)
 {
     if (!c || decode_tiles_per_split < 0 || prefill_tiles_per_split < 0) return PC_ERR_INVALID_ARG;

@@ -23,6 +23,7 @@ pytestmark = pytest.mark.gpu
 
 MAX_ABS, MEAN_ABS, LSE_ABS = 2e-2, 1e-3, 2e-2
 PER_CALL, SHARED = 1, 2
+NO_GATHER, GATHER = 1, 2
 
 
 def say(*a):
@@ -38,12 +39,14 @@ def hip():
     return harness
 
 
-def gpu_results(hip, w, sharing=None):
+def gpu_results(hip, w, sharing=None, gather=None):
     """One pass of the workload through the library; [(out, lse)] per attend event as numpy arrays."""
     import torch
     cache = hip.make_cache(w)
     if sharing is not None:
         cache.set_decode_sharing(sharing)
+    if gather is not None:
+        cache.set_key_gather(gather)
     res = hip.DeviceWorkload(w).run(cache)
     torch.cuda.synchronize()
     got = [(o.float().cpu().numpy(), l.cpu().numpy()) for o, l in res]
@@ -76,11 +79,12 @@ def check(tag, out, lse, rows, o, l):
 def test_configs1_single_prefill_every_row(hip):
     w = gen.single_prefill()
     tables_check(hip, w)
-    (out, lse), = gpu_results(hip, w)
     ei, _ = attend_events(w)[-1]
     rows, o, l = oracle_call(w, ei, 0)
     assert len(rows) == 512
-    check("configs[1] call 0", out, lse, rows, o, l)
+    for name, gather in (("default", None), ("gathered keys", GATHER)):
+        (out, lse), = gpu_results(hip, w, gather=gather)
+        check(f"configs[1] call 0 {name}", out, lse, rows, o, l)
 
 
 # ------------------------------------------------------------------ configs[2]: all 64 calls, both walks
@@ -103,14 +107,15 @@ def test_configs3_multi_agent_rounds_every_row_of_every_round(hip):
     w = gen.multi_agent_rounds()
     tables_check(hip, w)
     got = gpu_results(hip, w)
+    got_g = gpu_results(hip, w, gather=GATHER)
     evs = attend_events(w)
     assert len(evs) == 6 and all(len(e.calls) == 8 for _, e in evs)
     for k, (ei, ev) in enumerate(evs):
-        out, lse = got[k]
         for ci in range(len(ev.calls)):
             rows, o, l = oracle_call(w, ei, ci)
             assert len(rows) == 256
-            check(f"configs[3] round {k} call {ci}", out, lse, rows, o, l)
+            check(f"configs[3] round {k} call {ci}", got[k][0], got[k][1], rows, o, l)
+            check(f"configs[3] round {k} call {ci} gathered keys", got_g[k][0], got_g[k][1], rows, o, l)
 
 
 # ------------------------------------------------------------------ configs[4]: 32 decode calls + the prefill call
@@ -119,7 +124,9 @@ def long_context_runs(hip):
     w = gen.long_context()
     ei, ev = attend_events(w)[-1]
     assert [c.n_q for c in ev.calls] == [1] * 32 + [2048]
-    runs = {"default (shared walk)": gpu_results(hip, w)[0], "per-call walk": gpu_results(hip, w, sharing=PER_CALL)[0]}
+    # default: the decode calls take the shared walk, the prefill call reads gathered keys
+    runs = {"default (shared walk, gathered keys)": gpu_results(hip, w)[0],
+            "per-call walk, queries turned per message": gpu_results(hip, w, sharing=PER_CALL, gather=NO_GATHER)[0]}
     return w, ei, ev, runs
 
 

@@ -29,7 +29,7 @@ def hip():
 
 
 def run_and_compare(hip, w, rows_per_call=None, calls_subset=None, events=None, tuning=None, batch_appends=False,
-                    lse_rel=0.0, sharing=None, few_key_calls=False):
+                    lse_rel=0.0, sharing=None, few_key_calls=False, gather=None):
     """few_key_calls: the batch is full of calls whose rows see a handful of keys, so that outputs are of order
     one.  The bf16 result itself is then rounded by about 1.4e-3 of its size on average (a quarter ulp), which
     the fixed mean bar cannot absorb: the mean bar of a call grows by 2^-9 times the mean size of its exact output."""
@@ -39,6 +39,8 @@ def run_and_compare(hip, w, rows_per_call=None, calls_subset=None, events=None, 
         cache.set_tuning(*tuning)
     if sharing is not None:
         cache.set_decode_sharing(sharing)
+    if gather is not None:
+        cache.set_key_gather(gather)
     dw = hip.DeviceWorkload(w)
     say(f"[run] {w.name} dtype={w.dtype} Hq={w.n_q_heads} Hkv={w.n_kv_heads} D={w.head_dim} "
         f"msgs={w.n_messages} attends={len(attend_events(w))}")
@@ -133,6 +135,29 @@ def test_small_random_bf16_split_settings(hip, tuning):
     # KV splits of 1 tile, a few tiles, and no splitting must all agree with the oracle
     w = gen.small_random(211, dtype="bf16", n_q_heads=8, n_kv_heads=2, head_dim=128, len_hi=200, max_q=90)
     run_and_compare(hip, w, tuning=tuning)
+    run_and_compare(hip, w, tuning=tuning, gather=GATHER_ALWAYS)
+
+
+# Key gather (Sec. 2.4 "Position Updates", applied to a copy of the call's keys): prefill calls read keys that a
+# pass before the attention kernel turned to the positions the call gives them.  By default only calls with many
+# rows take it; here every prefill call of the small and ragged workloads does (mode 2), and none (mode 1).
+GATHER_NEVER, GATHER_ALWAYS = 1, 2
+
+
+@pytest.mark.parametrize("seed,hq,hkv", [(201, 8, 2), (202, 16, 2), (203, 4, 4), (204, 6, 3), (205, 32, 2)])
+def test_small_random_bf16_with_gathered_keys(hip, seed, hq, hkv):
+    w = gen.small_random(seed, dtype="bf16", n_q_heads=hq, n_kv_heads=hkv, head_dim=128)
+    run_and_compare(hip, w, gather=GATHER_ALWAYS)
+    run_and_compare(hip, w, gather=GATHER_NEVER)
+
+
+def test_scaled_configs_with_gathered_keys(hip):
+    run_and_compare(hip, gen.single_prefill(n_msgs=24, len_lo=40, len_hi=300, n_sel=6, n_new=200), gather=GATHER_ALWAYS)
+    run_and_compare(hip, gen.multi_agent_rounds(n_agents=3, n_rounds=3, msg_len=70), gather=GATHER_ALWAYS, batch_appends=True)
+    run_and_compare(hip, gen.long_context(n_msgs=40, len_lo=30, len_hi=120, target_tokens=2500, n_decode=5, n_prefill_q=150),
+                    gather=GATHER_ALWAYS)
+    run_and_compare(hip, gen.prefix_cache_baseline_rounds(n_agents=3, n_rounds=3, msg_len=40, n_q_heads=8, n_kv_heads=2),
+                    gather=GATHER_ALWAYS)
 
 
 def test_edge_cases_bf16(hip):
@@ -160,6 +185,7 @@ def test_edge_cases_bf16(hip):
     w.events.append(Event("attend", calls=calls, q=q))
     tables_check(hip, w)
     run_and_compare(hip, w)
+    run_and_compare(hip, w, gather=GATHER_ALWAYS)
 
 
 def test_empty_batch_and_errors(hip):
@@ -472,6 +498,8 @@ def test_calls_with_more_than_a_thousand_parents(hip, sharing):
     w.events.append(Event("attend", calls=calls, q=q))
     tables_check(hip, w, max_calls=2)
     run_and_compare(hip, w, sharing=sharing)
+    if sharing is None:
+        run_and_compare(hip, w, gather=GATHER_ALWAYS)
 
 
 @pytest.mark.parametrize("sharing", [None, 2])
