@@ -23,8 +23,8 @@ void pc_launch_append_tokens_packed(int dtype, const PcTokenPack &pack, int n, c
                                     int D, int64_t slots, const double *inv_freq, void *k_store, void *v_store,
                                     PcMsgEntry *table, hipStream_t st);
 
-// zero the V rows of n_slots slots from slot_start on (both multiples of the tile), every KV head
-void pc_launch_zero_v_span(int dtype, void *v_store, int64_t slots, int n_kv_heads, int D, int64_t slot_start, int64_t n_slots,
+// zero the rows of n_slots slots from slot_start on (both multiples of the tile) of the K or the V store, every KV head
+void pc_launch_zero_span(int dtype, void *store, int64_t slots, int n_kv_heads, int D, int64_t slot_start, int64_t n_slots,
                            hipStream_t st);
 
 // turn the stored keys of one message by delta positions, in place

@@ -827,30 +827,30 @@ void pc_launch_attend_f32(const PcLaunch &L, const int32_t *row_call, int total_
 }
 
 // ----------------------------------------------------------------------------------------
-// Zero the V rows of a span of slots that is taken again after a free.  The attention kernels
-// read whole 32-key tiles: behind a message's last token the K side is masked after the score
-// MFMA, the V side meets probabilities that are exactly zero, which only works if what lies
-// there is finite.  A span never used before is zero from the cache's creation; one that held
-// another message is cleared here, before the new message's append kernel, on the same stream.
-// Both V layouts keep a head's slots contiguous (bf16: groups of 8 slots, and spans are multiples
-// of 32), so a span is one run of bytes per KV head.
+// Zero the K or V rows of a span of slots that is taken again after a free.  The attention kernels
+// read whole 32-key tiles: behind a message's last token the scores are masked (the prefill kernel
+// adds -inf to them) and the V side meets probabilities that are exactly zero, both of which only
+// work if what lies there is finite.  A span never used before is zero from the cache's creation;
+// one that held another message is cleared here, before the new message's append kernel, on the
+// same stream.  The K store and both V layouts keep a head's slots contiguous (bf16 V: groups of 8
+// slots, and spans are multiples of 32), so a span is one run of bytes per KV head.
 // ----------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void pc_zero_v_span_kernel(uint4 *__restrict__ v_store, int64_t head_stride16, int64_t start16,
+__global__ __launch_bounds__(256) void pc_zero_span_kernel(uint4 *__restrict__ store, int64_t head_stride16, int64_t start16,
                                                              int64_t n16)
 {
-    uint4 *p = v_store + (int64_t)blockIdx.y * head_stride16 + start16;
+    uint4 *p = store + (int64_t)blockIdx.y * head_stride16 + start16;
     const uint4 z = make_uint4(0, 0, 0, 0);
     for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (int64_t)gridDim.x * 256) p[i] = z;
 }
 
-void pc_launch_zero_v_span(int dtype, void *v_store, int64_t slots, int n_kv_heads, int D, int64_t slot_start, int64_t n_slots,
+void pc_launch_zero_span(int dtype, void *store, int64_t slots, int n_kv_heads, int D, int64_t slot_start, int64_t n_slots,
                            hipStream_t st)
 {
     if (n_slots <= 0) return;
     const int64_t per_slot16 = (int64_t)D * (dtype == 1 ? 2 : 4) / 16;        // 16-byte pieces per slot and head
     const int64_t n16 = n_slots * per_slot16;
     dim3 grid((unsigned)std::min<int64_t>((n16 + 255) / 256, 1024), (unsigned)n_kv_heads);
-    pc_zero_v_span_kernel<<<grid, 256, 0, st>>>((uint4 *)v_store, slots * per_slot16, slot_start * per_slot16, n16);
+    pc_zero_span_kernel<<<grid, 256, 0, st>>>((uint4 *)store, slots * per_slot16, slot_start * per_slot16, n16);
 }
 
 // ----------------------------------------------------------------------------------------

@@ -88,7 +88,14 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
     __shared__ __attribute__((aligned(1024))) unsigned char s_v[RING][TILE_BYTES];
     __shared__ __attribute__((aligned(1024))) float2 s_rot[RING][PC_D / 2];
     __shared__ __attribute__((aligned(16))) float4 s_qm[8][8][64];    // upper half (dims 64..127) of the fp32 query master
+    // what a lane adds to its 16 scores of a tile of which it may see the first `lim` keys only (0 <= lim <= 32):
+    // 0 for a visible key, -inf for the others; row [lim][lane >> 5], register r = key 16 (r / 8) + 8 (lane >> 5) + r % 8
+    __shared__ __attribute__((aligned(16))) float s_bias[PC_TILE + 1][2][16];
 
+    for (int idx = threadIdx.x; idx < (PC_TILE + 1) * 32; idx += 512) {           // (visible after the barrier in front of the first tile)
+        const int lim = idx >> 5, half = (idx >> 4) & 1, r = idx & 15;
+        s_bias[lim][half][r] = (16 * (r >> 3) + 8 * half + (r & 7) < lim) ? 0.f : -INFINITY;
+    }
     const int kh = blockIdx.x % L.n_kv_heads;          // consecutive workgroups (one per XCD) take different KV heads
     const PcItem item = L.items[blockIdx.x / L.n_kv_heads];
     const PcCallDesc cd = L.calls[item.call];
@@ -157,6 +164,7 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
     // scores at all (`shifted` is false) and a score costs one v_exp, one add and half a convert.
     float m_ref = 0.f, thr_lo = -LAZY_LOG2, l_run = 0.f;
     bool shifted = false;                                // some lane of this wave has m_ref != 0
+    bool all_seen = false;                               // every lane of this wave has met a visible key (thr_lo is -inf everywhere)
     f32x16 acc[4];
 #pragma unroll
     for (int db = 0; db < 4; ++db)
@@ -268,11 +276,15 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
     auto mask_and_shift = [&](f32x16 &s, const Desc &d) __attribute__((always_inline)) {
         const bool is_self = d.is_self();
         if (__builtin_expect(d.valid() < PC_TILE || (is_self && d.key() + PC_TILE - 1 > blk_lim_lo), 0)) {
-            const int lim = is_self ? min(d.valid(), self_lim - d.key() + 1) : d.valid();
+            // (added, not selected: sixteen additions and four LDS reads instead of sixteen compares and selects;
+            // the scores of keys that do not exist are finite, because the slots behind a message's end hold zeros
+            // or what an earlier, finite message left there)
+            const int lim = is_self ? max(0, min(d.valid(), self_lim - d.key() + 1)) : d.valid();
+            const float4 *b = reinterpret_cast<const float4 *>(&s_bias[lim][hh][0]);
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int key = 16 * (r >> 3) + 8 * hh + (r & 7);
-                s[r] = (key < lim) ? s[r] : -INFINITY;
+            for (int q4 = 0; q4 < 4; ++q4) {
+                const float4 bv = b[q4];
+                s[4 * q4] += bv.x; s[4 * q4 + 1] += bv.y; s[4 * q4 + 2] += bv.z; s[4 * q4 + 3] += bv.w;
             }
         }
         if (__builtin_expect(shifted, 0)) {
@@ -284,10 +296,14 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
     // The test is three compares whose lane masks are combined on the scalar side.
     auto rebase = [&](f32x16 &s, float mx) __attribute__((always_inline)) {
         const uint64_t above = __builtin_amdgcn_ballot_w64(mx > LAZY_LOG2);
-        const uint64_t below = __builtin_amdgcn_ballot_w64(mx < thr_lo);
-        const bool seen = mx > -INFINITY;
-        const uint64_t need_mask = above | (below & __builtin_amdgcn_ballot_w64(seen));
-        thr_lo = seen ? -INFINITY : thr_lo;
+        uint64_t need_mask = above;
+        if (__builtin_expect(!all_seen, 0)) {            // until every row of the wave has met a visible key
+            const uint64_t below = __builtin_amdgcn_ballot_w64(mx < thr_lo);
+            const bool seen = mx > -INFINITY;
+            need_mask |= below & __builtin_amdgcn_ballot_w64(seen);
+            thr_lo = seen ? -INFINITY : thr_lo;
+            all_seen = __builtin_amdgcn_ballot_w64(thr_lo == -INFINITY) == ~0ull;
+        }
         if (__builtin_expect(need_mask != 0, 0)) {
             const bool need = (need_mask >> lane) & 1;
             const float shift = need ? mx : 0.f;

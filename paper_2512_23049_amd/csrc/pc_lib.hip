@@ -170,14 +170,16 @@ static bool take_slots(std::vector<FreeSpan> &spans, int64_t &next, int64_t capa
     return true;
 }
 
-// A span taken where a freed or swapped-out message may have lived: its V rows are cleared before the new owner's
-// append kernel runs (the attention kernels multiply what lies behind a message's last token, inside its last
-// tile, by exact zeros, which needs finite values there).
+// A span taken where a freed or swapped-out message may have lived: its K and V rows are cleared before the new
+// owner's append kernel runs (the attention kernels mask what lies behind a message's last token, inside its last
+// tile, by adding -inf to its scores and multiply its V rows by exact zeros, both of which need finite values there).
 static void clear_if_reused(pc_cache *c, int64_t start, int32_t res, hipStream_t st)
 {
     if (c->host_only || start >= c->dirty_end) return;
     const int64_t need = (int64_t)align_up((size_t)res, PC_SLOT_ALIGN);
-    pc_launch_zero_v_span(c->cfg.dtype, c->v_store, c->slots, c->cfg.n_kv_heads, c->D, start, std::min(need, c->dirty_end - start), st);
+    const int64_t n = std::min(need, c->dirty_end - start);
+    pc_launch_zero_span(c->cfg.dtype, c->k_store, c->slots, c->cfg.n_kv_heads, c->D, start, n, st);
+    pc_launch_zero_span(c->cfg.dtype, c->v_store, c->slots, c->cfg.n_kv_heads, c->D, start, n, st);
 }
 
 int32_t pc_append_message(pc_cache *c, const void *k, const void *v, int32_t len, int32_t reserve,
