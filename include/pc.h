@@ -281,12 +281,12 @@ int32_t pc_profile_read(pc_cache *c, double ms_total[PC_N_KERNEL_CLASSES],
  * and for prefill work items. */
 int32_t pc_set_tuning(pc_cache *c, int32_t decode_tiles_per_split, int32_t prefill_tiles_per_split);
 
-/* Key gather (Sec. 2.4 "Position Updates", applied to a copy).  A prefill call with many query rows can have
- * its keys copied once, each message turned to the position the call gives it, into the call's workspace; the
- * attention kernel then reads keys from the copy and turns the queries by their own position only, instead of
- * once more per listed message.  The cache itself is not changed, results are the same up to one more rounding
- * of the copied keys to bf16.  mode 0 (default): calls for which the copy costs less than the turns it saves
- * (rows x query heads above about 5300 x the call's KV tiles per listed message); 1: never; 2: every prefill call.
+/* Gather pass (Sec. 2.4 "Position Updates", applied to a copy).  A prefill call with many query rows can have the
+ * keys and values it lists copied once into the call's workspace: tokens in list order without gaps between
+ * messages, every key turned to the position the call gives it.  The attention kernel then reads plain tiles of the
+ * copy and turns the queries by their own position only, instead of once more per listed message.  The cache itself
+ * is not changed; results are the same up to one more rounding of the copied keys to bf16.  mode 0 (default): calls
+ * with rows x query heads >= 32768 (below that the copy costs more than it saves); 1: never; 2: every prefill call.
  * PC_BF16 caches only; pc_attend_static never gathers (the copy may not fit its fixed workspace). */
 int32_t pc_set_key_gather(pc_cache *c, int32_t mode);
 

@@ -46,7 +46,7 @@ static int32_t attend_impl(pc_cache *c, const pc_call *calls, int32_t n_calls, c
     L.part_o = (uint16_t *)(w + P.lay.part_o); L.part_ml = (float *)(w + P.lay.part_ml);
     L.slots = c->slots; L.n_q_heads = c->cfg.n_q_heads; L.n_kv_heads = c->cfg.n_kv_heads;
     L.scale_log2 = c->scale * 1.4426950408889634f;
-    L.k_gather = w + P.lay.k_gather; L.kg_slots = P.kg_tiles * PC_TILE; L.ident_row = P.total_seg;
+    L.k_gather = w + P.lay.k_gather; L.v_gather = w + P.lay.v_gather; L.kg_slots = P.kg_tiles * PC_TILE;
     const int32_t *row_call = (const int32_t *)(w + P.lay.row_call);
     if (c->cfg.dtype == PC_F32) {
         ProfScope ps(c, 5, st);
@@ -56,13 +56,19 @@ static int32_t attend_impl(pc_cache *c, const pc_call *calls, int32_t n_calls, c
     }
     if (P.n_kg_items > 0) {
         ProfScope ps(c, 8, st);
-        pc_launch_gather_keys(L, (const PcGatherItem *)(w + P.lay.kg_items), P.n_kg_items, P.kg_tiles, st);
+        pc_launch_gather(L, (const PcGatherItem *)(w + P.lay.kg_items), P.n_kg_items, P.kg_tiles, (const int32_t *)(w + P.lay.seg_kvoff), st);
+        PC_HIP(c, hipGetLastError());
+    }
+    if (P.n_pre_pk > 0) {
+        ProfScope ps(c, 2, st);
+        L.items = (const PcItem *)(w + P.lay.items_pk);
+        pc_launch_prefill_bf16(L, P.n_pre_pk, true, st);
         PC_HIP(c, hipGetLastError());
     }
     if (P.n_pre > 0) {
         ProfScope ps(c, 2, st);
         L.items = (const PcItem *)(w + P.lay.items_pre);
-        pc_launch_prefill_bf16(L, P.n_pre, st);
+        pc_launch_prefill_bf16(L, P.n_pre, false, st);
         PC_HIP(c, hipGetLastError());
     }
     if (P.n_dec > 0) {

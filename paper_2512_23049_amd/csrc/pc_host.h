@@ -62,7 +62,7 @@ struct pc_cache {
     // tuning
     int decode_tiles_per_split = 0, prefill_tiles_per_split = 0;
     int decode_sharing = 0;                            // 0 auto, 1 never, 2 whenever possible
-    int key_gather = 0;                                // 0 auto, 1 never, 2 every prefill call
+    int key_gather = 0;                                // gather pass for prefill calls: 0 by size, 1 never, 2 always
     void *static_ws = nullptr;                         // this device's copy of the library's fixed scratch array
     std::string err;
 };
@@ -122,8 +122,8 @@ inline int32_t chain_last(const pc_cache *c, int32_t m)
 
 // layout of the staged (host -> device) block and of the device-built block
 struct PlanLayout {
-    size_t calls, sel, q_pos, row_call, merge_rows, items_dec, items_pre, sh_groups, sh_segs, sh_items, sh_pos, kg_items, h2d_bytes;
-    size_t segs, seg_kvoff, rot_seg, rot_q, tiles, sh_rot, part_o, part_ml, row_scalar, k_gather, total;
+    size_t calls, sel, q_pos, row_call, merge_rows, items_dec, items_pre, items_pk, sh_groups, sh_segs, sh_items, sh_pos, kg_items, h2d_bytes;
+    size_t segs, seg_kvoff, rot_seg, rot_q, tiles, sh_rot, part_o, part_ml, row_scalar, k_gather, v_gather, total;
 };
 
 // -------------------------------------------------------------------------------------
@@ -131,7 +131,7 @@ struct PlanLayout {
 // -------------------------------------------------------------------------------------
 struct Planned {
     PlanLayout lay;
-    int n_calls = 0, total_sel = 0, total_q = 0, total_seg = 0, n_dec = 0, n_pre = 0, pre_waves = 4;
+    int n_calls = 0, total_sel = 0, total_q = 0, total_seg = 0, n_dec = 0, n_pre = 0, n_pre_pk = 0, pre_waves = 4;
     int n_merge_rows = 0, n_merge_few = 0;               // rows to merge; the first n_merge_few have few splits
     int n_sh_items = 0;
     size_t n_sh_pos = 0;

@@ -62,18 +62,19 @@ struct PcCallDesc {
     int32_t n_splits;         // KV splits of this call's work items
     int32_t part_off;         // first partial row (units of rows) when n_splits > 1
     int32_t tile_off;         // first entry of this call in the tile table
-    int32_t kg_tile0;         // -1, or the call's first tile in the gathered-keys buffer: its keys were copied there
-                              // tile by tile, each turned to the position the call gives it (the queries then need
-                              // no turn per segment)
-    int32_t pad[3];
+    int32_t kg_tile0;         // -1, or the call's first tile in the gather buffers: its keys (turned to the positions
+                              // the call gives them) and values were copied there token after token, the parents'
+                              // part padded to whole tiles, then the new message
+    int32_t n_par;            // tokens of the parents' part (all segments but the new message)
+    int32_t pad[2];
 };
 
 // One call whose keys the gather pass copies (staged by the host).
 struct PcGatherItem {
     int32_t call;
     int32_t kg_tile0;         // its first tile in the gathered-keys buffer
-    int32_t n_tiles;
-    int32_t pad;
+    int32_t n_tiles;          // tiles of its copy: ceil(n_par / 32) + ceil(self_len / 32)
+    int32_t n_par;            // tokens of the parents' part
 };
 
 // A gathered segment = one whole message placed at pos_start (built on device).
@@ -159,7 +160,7 @@ struct PcShLaunch {
 struct PcLaunch {
     const PcCallDesc *calls;
     const PcSegment  *segs;
-    const float2     *rot_seg;    // [total_seg + 1][D/2] (cos, sin)((pos_start - stored base) * theta_i); last row: no rotation
+    const float2     *rot_seg;    // [total_seg][D/2] (cos, sin)((pos_start - stored base) * theta_i)
     const float2     *rot_q;      // [total_q][D/2]   (cos, sin)(q_pos * theta_i)
     const PcItem     *items;
     const PcTile     *tiles;      // [total tiles] per-call tile tables
@@ -170,10 +171,9 @@ struct PcLaunch {
     float            *lse;        // [total_q][H_q] or null
     uint16_t         *part_o;     // [part rows][H_q][D]   partial outputs, each normalised by its own sum, fp16
     float            *part_ml;    // [part rows][H_q][2]   running max (scaled log2 domain), sum
-    void             *k_gather;   // [H_kv][kg_slots][D]  keys of the calls that gather, turned to their positions
+    void             *k_gather;   // [H_kv][kg_slots][D]       keys of the calls that gather, turned to their positions
+    void             *v_gather;   // [H_kv][kg_slots/8][D][8]  their values, in the cache's group-of-8 layout
     int64_t           kg_slots;   // slots of that buffer per KV head (32 per gathered tile)
-    int32_t           ident_row;  // row of rot_seg that holds the rotation by zero
-    int32_t           pad0;
     int64_t           slots;      // capacity in slots (stride between KV heads)
     int32_t           n_q_heads, n_kv_heads;
     float             scale_log2; // softmax scale * log2(e)

@@ -58,12 +58,14 @@ void pc_launch_attend_bwd(int dtype, const PcLaunch &L, const int32_t *row_call,
 void pc_launch_grad_keys_finalize(const PcMsgEntry *msgs, int n_msgs, int n_kv_heads, int D, const double *inv_freq,
                                   float *d_k, hipStream_t st);
 
-// keys of the listed calls, tile by tile, each turned to the position its call gives it, into L.k_gather
-void pc_launch_gather_keys(const PcLaunch &L, const PcGatherItem *items, int n_items, int64_t n_tiles, hipStream_t st);
+// keys (turned to the positions their call gives them) and values of the listed calls, token after token, into
+// L.k_gather / L.v_gather
+void pc_launch_gather(const PcLaunch &L, const PcGatherItem *items, int n_items, int64_t n_tiles, const int32_t *seg_kvoff,
+                      hipStream_t st);
 
 // bf16 MFMA kernels (D = 128)
 void pc_launch_decode_bf16(const PcLaunch &L, int n_items, hipStream_t st);
-void pc_launch_prefill_bf16(const PcLaunch &L, int n_items, hipStream_t st);
+void pc_launch_prefill_bf16(const PcLaunch &L, int n_items, bool packed, hipStream_t st);   // packed: the items of calls that gathered
 
 // shared decode: rotation table of the listed (message, row) pairs, then the attention kernel
 void pc_launch_shared_rot(const int32_t *pos, int64_t n_ent, const double *inv_freq, int half, float2 *rot, hipStream_t st);

@@ -563,11 +563,10 @@ __global__ __launch_bounds__(256) void pc_build_plan_kernel(
     }
     // rotation tables: entity = segment (position from the staged lists) or query row
     const int64_t tid = (int64_t)(blockIdx.x - n_calls) * 256 + threadIdx.x;
-    const int64_t n_ent = (int64_t)total_seg + total_q + 1;          // the last one: the rotation by zero, row total_seg of rot_seg
+    const int64_t n_ent = (int64_t)total_seg + total_q;
     if (tid >= n_ent * half) return;
     const int ent = (int)(tid / half);
     const int i = (int)(tid % half);
-    if (ent == total_seg + total_q) { rot_seg[(int64_t)total_seg * half + i] = make_float2(1.f, 0.f); return; }
     int pos;
     if (ent < total_seg) {
         // find the call that owns this segment (calls are few; segments are laid out call by call)
@@ -597,7 +596,7 @@ void pc_launch_build_plan(const PcCallDesc *calls, int n_calls, const int2 *sel,
                           int total_q, PcSegment *segs, int32_t *seg_kvoff, float2 *rot_seg,
                           float2 *rot_q, PcTile *tiles, hipStream_t st)
 {
-    const int64_t n_rot = ((int64_t)total_seg + total_q + 1) * half;
+    const int64_t n_rot = ((int64_t)total_seg + total_q) * half;
     const unsigned grid = (unsigned)(n_calls + (n_rot + 255) / 256);
     pc_build_plan_kernel<<<grid, 256, 0, st>>>(calls, n_calls, sel, q_pos, table, inv_freq, half, total_seg,
                                                total_q, segs, seg_kvoff, rot_seg, rot_q, tiles);
@@ -854,50 +853,102 @@ void pc_launch_zero_span(int dtype, void *store, int64_t slots, int n_kv_heads, 
 }
 
 // ----------------------------------------------------------------------------------------
-// K2g: key gather.  For a call with many query rows it is cheaper to turn the KEYS to the
-// positions the call gives them once than to turn the queries of every (32-row block, head) at
-// every segment: the call's key tiles are copied, in the order of its tile table, into a buffer
-// of their own, key t of a segment turned from its stored position base + t to start + t (Sec. 2.4
+// K2g: gather.  A call with many query rows reads its keys and values from a copy of its own:
+// the tokens of its parents in list order, one after the other (no padding between messages),
+// padded IN FRONT to whole 32-key tiles, then the tokens of its new message.  A key is copied
+// turned from its stored position base + t to the position start + t the call gives it (Sec. 2.4
 // "Position Updates": the rotation by start - base, here into a copy, so that the cache keeps its
-// position-independent form and other calls may place the same message elsewhere).  The prefill
-// kernel then reads K from the copy with queries turned by their own position only; V stays where
-// it is.  Rows past a message's end are written as zeros.
-// One block per (tile, KV head): thread = (key row, 8 low dims and their partners 64 up).
+// position-independent form and other calls may place the same message elsewhere); values are
+// copied into the cache's own group-of-8 layout.  The attention kernel then walks plain tiles:
+// nothing to look up per tile, no turn of the queries per message, one ragged tile per part
+// instead of one per message.  Padding rows are written as zeros.
+// One block per (tile of the copy, KV head).  The first 32 threads find where the tile's tokens
+// live (a search in the call's segment offsets); then thread = (key row, 8 low dims and their
+// partners 64 up) for K, and thread = (group of 8 tokens, dim) twice for V: eight 2-byte reads
+// (the 2 KB of a source group are shared by the threads of a block through L1), one 16-byte write.
 // ----------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void pc_gather_keys_kernel(PcLaunch L, const PcGatherItem *__restrict__ items, int n_items)
+__global__ __launch_bounds__(256) void pc_gather_kernel(PcLaunch L, const PcGatherItem *__restrict__ items, int n_items,
+                                                        const int32_t *__restrict__ seg_kvoff)
 {
+    __shared__ int s_slot[PC_TILE], s_seg[PC_TILE];
     const int G = blockIdx.x, kh = blockIdx.y;
     int j = 0;
     while (j + 1 < n_items && items[j + 1].kg_tile0 <= G) ++j;           // few calls gather: a short scan
     const PcGatherItem it = items[j];
     const PcCallDesc cd = L.calls[it.call];
-    const PcTile tl = L.tiles[cd.tile_off + (G - it.kg_tile0)];
-    const int valid = tl.valid_flags & 0xFF;
-    const int r = threadIdx.x >> 3, c = threadIdx.x & 7;
-    const uint16_t *src = (const uint16_t *)L.k_store + ((int64_t)kh * L.slots + tl.slot0 + r) * 128 + 8 * c;
-    uint16_t *dst = (uint16_t *)L.k_gather + ((int64_t)kh * L.kg_slots + (int64_t)G * PC_TILE + r) * 128 + 8 * c;
-    uint4 lo = make_uint4(0, 0, 0, 0), hi = lo;
-    if (r < valid) {
-        lo = *reinterpret_cast<const uint4 *>(src);
-        hi = *reinterpret_cast<const uint4 *>(src + 64);
-        const float4 *rot = reinterpret_cast<const float4 *>(L.rot_seg + (int64_t)(cd.seg_off + tl.seg) * 64 + 8 * c);
-        uint32_t *lw = reinterpret_cast<uint32_t *>(&lo), *hw = reinterpret_cast<uint32_t *>(&hi);
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const float4 cs = rot[u];                    // (cos, sin) of pairs 2u and 2u + 1
-            using P = Pair2<__hip_bfloat16>;
-            const float x0 = P::lo(lw[u]), x1 = P::hi(lw[u]), y0 = P::lo(hw[u]), y1 = P::hi(hw[u]);
-            lw[u] = P::pack(x0 * cs.x - y0 * cs.y, x1 * cs.z - y1 * cs.w);
-            hw[u] = P::pack(x0 * cs.y + y0 * cs.x, x1 * cs.w + y1 * cs.z);
+    const int t = G - it.kg_tile0;
+    const int p_tiles = (it.n_par + PC_TILE - 1) / PC_TILE;
+    if (threadIdx.x < PC_TILE) {
+        const int r = threadIdx.x;
+        int slot = -1, seg = 0;
+        if (t < p_tiles) {
+            const int i = PC_TILE * t + r - (p_tiles * PC_TILE - it.n_par);   // token of the parents' part (the padding comes first)
+            if (i >= 0) {
+                const int32_t *off = seg_kvoff + cd.seg_off;
+                int lo = 0, hi = cd.n_sel - 1;
+                while (lo < hi) {                          // last parent whose first token is <= i (empty ones share their successor's offset)
+                    const int mid = (lo + hi + 1) >> 1;
+                    if (off[mid] <= i) lo = mid; else hi = mid - 1;
+                }
+                seg = lo;
+                slot = L.segs[cd.seg_off + lo].slot_start + (i - off[lo]);
+            }
+        } else {
+            const int i = PC_TILE * (t - p_tiles) + r;     // token of the new message
+            if (i < cd.self_len) { seg = cd.n_seg - 1; slot = L.segs[cd.seg_off + seg].slot_start + i; }
         }
+        s_slot[r] = slot; s_seg[r] = seg;
     }
-    *reinterpret_cast<uint4 *>(dst) = lo;
-    *reinterpret_cast<uint4 *>(dst + 64) = hi;
+    __syncthreads();
+    {
+        const int r = threadIdx.x >> 3, c = threadIdx.x & 7;
+        const int slot = s_slot[r];
+        uint16_t *dst = (uint16_t *)L.k_gather + ((int64_t)kh * L.kg_slots + (int64_t)G * PC_TILE + r) * 128 + 8 * c;
+        uint4 lo = make_uint4(0, 0, 0, 0), hi = lo;
+        if (slot >= 0) {
+            const uint16_t *src = (const uint16_t *)L.k_store + ((int64_t)kh * L.slots + slot) * 128 + 8 * c;
+            lo = *reinterpret_cast<const uint4 *>(src);
+            hi = *reinterpret_cast<const uint4 *>(src + 64);
+            const float4 *rot = reinterpret_cast<const float4 *>(L.rot_seg + (int64_t)(cd.seg_off + s_seg[r]) * 64 + 8 * c);
+            uint32_t *lw = reinterpret_cast<uint32_t *>(&lo), *hw = reinterpret_cast<uint32_t *>(&hi);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const float4 cs = rot[u];                    // (cos, sin) of pairs 2u and 2u + 1
+                using P = Pair2<__hip_bfloat16>;
+                const float x0 = P::lo(lw[u]), x1 = P::hi(lw[u]), y0 = P::lo(hw[u]), y1 = P::hi(hw[u]);
+                lw[u] = P::pack(x0 * cs.x - y0 * cs.y, x1 * cs.z - y1 * cs.w);
+                hw[u] = P::pack(x0 * cs.y + y0 * cs.x, x1 * cs.w + y1 * cs.z);
+            }
+        }
+        *reinterpret_cast<uint4 *>(dst) = lo;
+        *reinterpret_cast<uint4 *>(dst + 64) = hi;
+    }
+    const uint16_t *vsrc = (const uint16_t *)L.v_store;
+    uint16_t *vdst = (uint16_t *)L.v_gather;
+#pragma unroll
+    for (int rep = 0; rep < 2; ++rep) {
+        const int idx = threadIdx.x + 256 * rep;
+        const int q = idx >> 7, d = idx & 127;
+        uint32_t w[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int k = 0; k < PC_VGROUP; ++k) {
+            const int slot = s_slot[PC_VGROUP * q + k];
+            uint32_t v = 0;
+            if (slot >= 0) {
+                const int64_t at = (int64_t)kh * L.slots + slot;
+                v = vsrc[((at >> 3) * 128 + d) * PC_VGROUP + (at & 7)];
+            }
+            w[k >> 1] |= v << (16 * (k & 1));
+        }
+        const int64_t grp = (((int64_t)kh * L.kg_slots + (int64_t)G * PC_TILE) >> 3) + q;
+        *reinterpret_cast<uint4 *>(vdst + (grp * 128 + d) * PC_VGROUP) = make_uint4(w[0], w[1], w[2], w[3]);
+    }
 }
 
-void pc_launch_gather_keys(const PcLaunch &L, const PcGatherItem *items, int n_items, int64_t n_tiles, hipStream_t st)
+void pc_launch_gather(const PcLaunch &L, const PcGatherItem *items, int n_items, int64_t n_tiles, const int32_t *seg_kvoff,
+                      hipStream_t st)
 {
     if (n_items <= 0 || n_tiles <= 0) return;
     dim3 grid((unsigned)n_tiles, (unsigned)L.n_kv_heads);
-    pc_gather_keys_kernel<<<grid, 256, 0, st>>>(L, items, n_items);
+    pc_gather_kernel<<<grid, 256, 0, st>>>(L, items, n_items, seg_kvoff);
 }

@@ -82,6 +82,12 @@ __device__ __forceinline__ void ring_barrier() { asm volatile("s_barrier" ::: "m
 
 template <int I> using IC = std::integral_constant<int, I>;
 
+// PACKED: the call's keys and values were copied by the gather pass into a buffer of their own, token after token in
+// the order the call lists them (keys already turned to the positions the call gives them), the parents' part padded
+// to whole tiles, then the new message.  Tile t of the call then sits at slot 32 t of that copy, only the last tile
+// of each part can be ragged, the queries are turned once by their own position, and nothing has to be looked up per
+// tile: no tile table, no rotation tables, no fp32 copy of the queries.
+template <bool PACKED>
 __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
 {
     __shared__ __attribute__((aligned(1024))) unsigned char s_k[RING][TILE_BYTES];
@@ -119,6 +125,29 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
     // (ks, j) is dim 16*ks + 8*hh + j.  Lower half in registers, upper half in LDS (read back
     // once per segment).  Filled while the first tiles are on their way.
     float qm[4][8];
+    bf16x8 qop[8];
+    // PACKED: the same values go straight into the bf16 MFMA operands (qop[ks]: dims 16 ks + 8 hh + j, qop[ks + 4]: 64 up)
+    auto load_query_direct = [&]() __attribute__((always_inline)) {
+        const uint16_t *qp = (const uint16_t *)L.q + ((int64_t)Rg * L.n_q_heads + h) * PC_D + 8 * hh;
+        const float2 *rq = L.rot_q + (int64_t)Rg * (PC_D / 2) + 8 * hh;
+        const float sc = row_ok ? L.scale_log2 : 0.f;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            uint4 lo = ldg16(qp + 16 * ks), hi = ldg16(qp + 16 * ks + 64);
+            const uint32_t lw[4] = {lo.x, lo.y, lo.z, lo.w}, hw[4] = {hi.x, hi.y, hi.z, hi.w};
+            float xx[8], yy[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const float x = ((j & 1) ? bf_hi(lw[j >> 1]) : bf_lo(lw[j >> 1])) * sc;
+                const float y = ((j & 1) ? bf_hi(hw[j >> 1]) : bf_lo(hw[j >> 1])) * sc;
+                const float2 cs = rq[16 * ks + j];
+                xx[j] = x * cs.x - y * cs.y;
+                yy[j] = x * cs.y + y * cs.x;
+            }
+            qop[ks] = __builtin_bit_cast(bf16x8, make_uint4(pack_bf16(xx[0], xx[1]), pack_bf16(xx[2], xx[3]), pack_bf16(xx[4], xx[5]), pack_bf16(xx[6], xx[7])));
+            qop[ks + 4] = __builtin_bit_cast(bf16x8, make_uint4(pack_bf16(yy[0], yy[1]), pack_bf16(yy[2], yy[3]), pack_bf16(yy[4], yy[5]), pack_bf16(yy[6], yy[7])));
+        }
+    };
     auto load_query = [&]() __attribute__((always_inline)) {
         const uint16_t *qp = (const uint16_t *)L.q + ((int64_t)Rg * L.n_q_heads + h) * PC_D + 8 * hh;
         const float2 *rq = L.rot_q + (int64_t)Rg * (PC_D / 2) + 8 * hh;
@@ -141,15 +170,15 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
         }
     };
 
-    // A call whose keys were gathered (copied tile by tile, each message turned to the position the call gives it)
-    // reads K from the copy, tile t of the call at slot 32 t, and never turns its queries after the first tile,
-    // which uses the table's last row, the rotation by zero.  V comes from the cache either way.
-    const int kg = __builtin_amdgcn_readfirstlane(cd.kg_tile0);
-    const bool gathered = kg >= 0;
-    const unsigned char *kb = gathered ? (const unsigned char *)L.k_gather + ((int64_t)kh * L.kg_slots + (int64_t)kg * PC_TILE) * PC_D * 2
-                                       : (const unsigned char *)L.k_store + (int64_t)kh * L.slots * PC_D * 2;
-    const unsigned char *vb = (const unsigned char *)L.v_store + (int64_t)kh * L.slots * PC_D * 2;
-    const int flag_keep = gathered ? ~PC_TILE_FRESH : ~0, seg_keep = gathered ? 0 : ~0;
+    const unsigned char *kb, *vb;
+    if constexpr (PACKED) {
+        const int64_t at = ((int64_t)kh * L.kg_slots + (int64_t)cd.kg_tile0 * PC_TILE) * PC_D * 2;
+        kb = (const unsigned char *)L.k_gather + at;
+        vb = (const unsigned char *)L.v_gather + at;
+    } else {
+        kb = (const unsigned char *)L.k_store + (int64_t)kh * L.slots * PC_D * 2;
+        vb = (const unsigned char *)L.v_store + (int64_t)kh * L.slots * PC_D * 2;
+    }
 
     // tiles this workgroup walks: its split's range (the host has cut it at the causal limit of the
     // workgroup's last row, so nothing has to be looked up for it)
@@ -186,10 +215,22 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
     typedef int i32x4 __attribute__((ext_vector_type(4)));
     auto decode = [&](const i32x4 &v) {
         Desc d;
-        d.slot0 = v.x; d.key0 = v.y; d.seg = v.z & seg_keep; d.flags = v.w & flag_keep;
+        d.slot0 = v.x; d.key0 = v.y; d.seg = v.z; d.flags = v.w;
         return d;
     };
+    // PACKED: what the table would say follows from the tile's number
+    // (the parents' part is padded IN FRONT to whole tiles: only the call's very first tile has keys that do not
+    // exist, its first `front_pad` ones, and that tile is always met outside the pipelined loop)
+    const int p_tiles = (cd.n_par + PC_TILE - 1) / PC_TILE;          // tiles of the parents' part
+    const int front_pad = p_tiles * PC_TILE - cd.n_par;
+    auto packed_desc = [&](int t) {
+        const bool own = t >= p_tiles;
+        const int key0 = own ? (t - p_tiles) * PC_TILE : 0;
+        const int valid = own ? min(cd.self_len - key0, PC_TILE) : PC_TILE;
+        return (i32x4){t * PC_TILE, key0, 0, valid | (own ? PC_TILE_SELF : 0)};
+    };
     auto describe = [&](int t) {
+        if constexpr (PACKED) return decode(packed_desc(t));
         const i32x4 v = *reinterpret_cast<const __attribute__((address_space(4))) i32x4 *>(reinterpret_cast<uintptr_t>(tile_tab + t));
         return decode(v);
     };
@@ -198,11 +239,12 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
     // compiler's wait counting, which stays correct for its own LDS reads (an extra outstanding
     // scalar load only makes those waits stricter); await_desc waits for everything.
     auto request_desc = [&](int t) {
+        if constexpr (PACKED) return packed_desc(t);
         i32x4 v;
         asm volatile("s_load_dwordx4 %0, %1, 0x0" : "=&s"(v) : "s"(tile_tab + t));
         return v;
     };
-    auto await_desc = [&](i32x4 &v) { asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(v)); };
+    auto await_desc = [&](i32x4 &v) { if constexpr (!PACKED) asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(v)); };
 
     // direct global -> LDS requests.  A tile is 512 16-byte chunks, one per thread.  Chunk
     // position p of a K tile holds logical chunk (p & 15) ^ ((p >> 4) & 15) of row p >> 4.
@@ -211,19 +253,18 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
     const unsigned wave_lds = __builtin_amdgcn_readfirstlane(wave) * 1024;
     const unsigned lds_k = (unsigned)(size_t)&s_k[0][0] + wave_lds, lds_v = (unsigned)(size_t)&s_v[0][0] + wave_lds;
     const unsigned lds_rot = (unsigned)(size_t)&s_rot[0][0];
-    const unsigned char *rot_base = (const unsigned char *)(L.rot_seg + (int64_t)(gathered ? L.ident_row : cd.seg_off) * (PC_D / 2));
-    // t: the tile's index in the call's tile table
-    auto dma_k = [&](const Desc &d, int slot, int t) {  // the rotation table first: it must be the oldest request
-        if (d.fresh() && threadIdx.x < 32)
-            dma16(rot_base + (int64_t)__builtin_amdgcn_readfirstlane(d.seg) * (PC_D / 2) * sizeof(float2), threadIdx.x * 16, lds_rot + slot * (unsigned)sizeof(s_rot[0]));
-        const int ks0 = gathered ? (__builtin_amdgcn_readfirstlane(t) << 5) : __builtin_amdgcn_readfirstlane(d.slot0);
-        dma16(kb + (int64_t)ks0 * 256, k_src_off, lds_k + slot * TILE_BYTES);
+    const unsigned char *rot_base = (const unsigned char *)(L.rot_seg + (int64_t)cd.seg_off * (PC_D / 2));
+    auto dma_k = [&](const Desc &d, int slot) {         // the rotation table first: it must be the oldest request
+        if constexpr (!PACKED) {
+            if (d.fresh() && threadIdx.x < 32)
+                dma16(rot_base + (int64_t)__builtin_amdgcn_readfirstlane(d.seg) * (PC_D / 2) * sizeof(float2), threadIdx.x * 16, lds_rot + slot * (unsigned)sizeof(s_rot[0]));
+        }
+        dma16(kb + (int64_t)__builtin_amdgcn_readfirstlane(d.slot0) * 256, k_src_off, lds_k + slot * TILE_BYTES);
     };
     auto dma_v = [&](const Desc &d, int slot) {
         dma16(vb + (int64_t)__builtin_amdgcn_readfirstlane(d.slot0) * 256, v_src_off, lds_v + slot * TILE_BYTES);
     };
 
-    bf16x8 qop[8];
     // K row read by this lane for MFMA row (lane & 31): rows are permuted so that the score
     // registers 0..7 / 8..15 of a lane are keys 8*hh + 0..7 / 16 + 8*hh + 0..7
     const int krow = 16 * (n >> 4) + 8 * ((n >> 2) & 1) + 4 * ((n >> 3) & 1) + (n & 3);
@@ -374,8 +415,16 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
     // step's probabilities are first needed by the fifth MFMA), the others the column maximum of
     // the next tile's scores sn and the test whether the reference has to move.  It moves after
     // the MFMAs: the accumulators they update are relative to the old reference.
-    auto phase_b = [&](int k_slot, const f32x16 &s, f32x16 &sn, const Desc &dn, auto between) __attribute__((always_inline)) {
-        mask_and_shift(sn, dn);
+    auto phase_b = [&](auto plain_c, int k_slot, const f32x16 &s, f32x16 &sn, const Desc &dn, auto between) __attribute__((always_inline)) {
+        constexpr bool PLAIN = decltype(plain_c)::value;
+        if constexpr (PLAIN) {                           // nothing to mask; a moved reference still has to be subtracted
+            if (__builtin_expect(shifted, 0)) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) sn[r] -= m_ref;
+            }
+        } else {
+            mask_and_shift(sn, dn);
+        }
         const bf16x8 p0 = __builtin_bit_cast(bf16x8, make_uint4(pk[0], pk[1], pk[2], pk[3]));
         float mx = 0.f;
 #pragma unroll
@@ -403,24 +452,29 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
             __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
         }
-        rebase(sn, max_across_halves(mx));
+        mx = max_across_halves(mx);
+        if constexpr (PLAIN) {                           // every row has met a key: one test
+            if (__builtin_expect(__builtin_amdgcn_ballot_w64(mx > LAZY_LOG2) != 0, 0)) rebase(sn, mx);
+        } else {
+            rebase(sn, mx);
+        }
     };
 
     if (T > 0) {
         const int last = tile_end - 1;
         Desc d0 = describe(tile0);
-        d0.flags |= PC_TILE_FRESH;                                 // a split may start in the middle of a segment
+        if constexpr (!PACKED) d0.flags |= PC_TILE_FRESH;          // a split may start in the middle of a segment
         Desc d1 = describe(min(tile0 + 1, last));
         Desc d2 = describe(min(tile0 + 2, last));
         Desc d3 = describe(min(tile0 + 3, last));
         Desc d4 = describe(min(tile0 + 4, last));
         Desc d5 = describe(min(tile0 + 5, last));
-        dma_k(d0, 0, tile0); dma_v(d0, 0);
-        dma_k(d1, 1, min(tile0 + 1, last)); dma_v(d1, 1);
-        dma_k(d2, 2, min(tile0 + 2, last)); dma_v(d2, 2);
-        dma_k(d3, 3, min(tile0 + 3, last)); dma_v(d3, 3);
-        dma_k(d4, 4, min(tile0 + 4, last));
-        load_query();
+        dma_k(d0, 0); dma_v(d0, 0);
+        dma_k(d1, 1); dma_v(d1, 1);
+        dma_k(d2, 2); dma_v(d2, 2);
+        dma_k(d3, 3); dma_v(d3, 3);
+        dma_k(d4, 4);
+        if constexpr (PACKED) load_query_direct(); else load_query();
         __builtin_amdgcn_s_waitcnt(0x0F70);              // vmcnt(0)
         __syncthreads();
 
@@ -428,7 +482,7 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
         // of tile 1 in fr
 #pragma unroll
         for (int f = 0; f < 8; ++f) fr[f] = kfrag(0, f);
-        turn_query(0);
+        if constexpr (!PACKED) turn_query(0);
         f32x16 sc;                                       // scores of the current tile, part 1 done
 #pragma unroll
         for (int r = 0; r < 16; ++r) sc[r] = 0.f;
@@ -437,7 +491,13 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
             sc = MFMA32(fr[ks], qop[ks], sc);
             fr[ks] = kfrag(1, ks);
         }
-        if (d1.fresh()) turn_query(1);                   // (from tile 2 on the queries are turned at the end of an iteration)
+        if constexpr (!PACKED) { if (d1.fresh()) turn_query(1); }   // (from tile 2 on the queries are turned at the end of an iteration)
+        if constexpr (PACKED) {
+            if (tile0 == 0 && front_pad > 0) {           // the padding in front of the parents' part
+#pragma unroll
+                for (int r = 0; r < 16; ++r) sc[r] = (16 * (r >> 3) + 8 * hh + (r & 7) >= front_pad) ? sc[r] : -INFINITY;
+            }
+        }
         mask_and_shift(sc, d0);
         rebase(sc, col_max(sc));
         // every wave has read tile 0's K before any wave overwrites its slot with tile 5's
@@ -447,21 +507,24 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
         // Iteration i (tiles i and i+1); u = i mod RING is a compile-time constant so that ring
         // slots are immediates.  On entry: sc = scores of tile i (part 1 done), fr = K fragments
         // of tile i+1, d1..d5 = descriptors of tiles i+1..i+5.  K(i+2) and V(i) are in LDS.
-        auto iteration = [&](auto uc, int i) {
+        // PLAIN (PACKED calls only): the form of the iteration for the tiles nothing special happens around: tile i+1 is
+        // a whole tile every row of the wave sees all of (nothing to mask) and every row of the wave has met a key; it
+        // tests one thing, whether some score exceeds the reference by more than 2^8.
+        auto iteration = [&](auto uc, auto plain_c, int i) {
             constexpr int u = decltype(uc)::value;
             constexpr int s0 = u, s1 = (u + 1) % RING, s2 = (u + 2) % RING, s4 = (u + 4) % RING;
             i32x4 raw6 = request_desc(min(tile0 + i + 6, last));     // first used in the next iteration's requests
-            f32x16 sn = phase_a(s0, sc, [&] { dma_k(d5, s0, min(tile0 + i + 5, last)); });             // K(i+5) takes the slot of K(i)
+            f32x16 sn = phase_a(s0, sc, [&] { dma_k(d5, s0); });             // K(i+5) takes the slot of K(i)
             // the descriptor is awaited here, where the wait costs nothing: it waits for every LDS
             // read too, and the V fragments requested during phase A arrived while its vector work
             // finished
             await_desc(raw6);
             const Desc d6 = decode(raw6);
-            phase_b(s2, sc, sn, d1, [&] { dma_v(d4, s4); });                 // V(i+4) takes the slot of V(i-1)
+            phase_b(plain_c, s2, sc, sn, d1, [&] { dma_v(d4, s4); });        // V(i+4) takes the slot of V(i-1)
             // the score MFMAs of this iteration have been issued, so the query operands are free:
             // turn them now if the tile after next starts a new rotation (its table came with K(i+2));
             // the P.V MFMAs just issued keep the matrix pipe busy meanwhile
-            if (__builtin_expect(d2.fresh(), 0)) turn_query(s2);
+            if constexpr (!PACKED) { if (__builtin_expect(d2.fresh(), 0)) turn_query(s2); }
             sc = sn;
             // K(i+3), V(i+1) (requested two and three iterations ago) must have landed; the requests
             // of this and the previous iteration (a K and a V each, rotation tables in front of
@@ -472,16 +535,82 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
             d1 = d2; d2 = d3; d3 = d4; d4 = d5; d5 = d6;
         };
         const int n_it = T - 1;
-        for (int i = 0; i < n_it; i += RING) {
-            iteration(IC<0>{}, i);
-            if (i + 1 >= n_it) break;
-            iteration(IC<1>{}, i + 1);
-            if (i + 2 >= n_it) break;
-            iteration(IC<2>{}, i + 2);
-            if (i + 3 >= n_it) break;
-            iteration(IC<3>{}, i + 3);
-            if (i + 4 >= n_it) break;
-            iteration(IC<4>{}, i + 4);
+        if constexpr (PACKED) {
+            auto dsc = [&](int t) { return decode(packed_desc(min(t, last))); };
+            // The plain form of the iteration, software-pipelined, ring slots as immediates: for tiles of which every
+            // row of the wave sees every key (the parents' part; the tiles of the new message below the wave's first
+            // row), once every row has met a key.
+            auto plain_iteration = [&](auto uc, int i) {
+                constexpr int u = decltype(uc)::value;
+                constexpr int s0 = u, s2 = (u + 2) % RING, s4 = (u + 4) % RING;
+                f32x16 sn = phase_a(s0, sc, [&] { dma_k(dsc(tile0 + i + 5), s0); });
+                phase_b(IC<1>{}, s2, sc, sn, d1, [&] { dma_v(dsc(tile0 + i + 4), s4); });
+                sc = sn;
+                __builtin_amdgcn_s_waitcnt(0x0F74);      // vmcnt(4), as in the general form below
+                ring_barrier();
+            };
+            // the first tile not of that kind for this wave: behind the parents' part and the tiles of the new message
+            // that lie wholly below the wave's first row
+            const int whole_own = cd.self_len > 0 ? max(0, (blk_lim_lo + 1) / PC_TILE) : 0;
+            const int n_plain = max(0, min(n_it, p_tiles + whole_own - tile0 - 1));
+            auto ok = [&](int i) { return i < n_plain && all_seen; };
+            int i = 0;
+            for (;; i += RING) {
+                if (!ok(i)) break;
+                plain_iteration(IC<0>{}, i);
+                if (!ok(i + 1)) { i += 1; break; }
+                plain_iteration(IC<1>{}, i + 1);
+                if (!ok(i + 2)) { i += 2; break; }
+                plain_iteration(IC<2>{}, i + 2);
+                if (!ok(i + 3)) { i += 3; break; }
+                plain_iteration(IC<3>{}, i + 3);
+                if (!ok(i + 4)) { i += 4; break; }
+                plain_iteration(IC<4>{}, i + 4);
+            }
+            // The general form for what is left (the tiles on and beyond the causal diagonal, or everything once a
+            // reference has moved): the same steps one after the other, ring slots computed, nothing overlapped.  It
+            // serves a few tiles per workgroup.
+            int u = i % RING;
+            for (; i < n_it; ++i) {
+                const int s0 = u, s2 = u + 2 >= RING ? u + 2 - RING : u + 2, s4 = u + 4 >= RING ? u + 4 - RING : u + 4;
+                dma_k(dsc(tile0 + i + 5), s0);           // K(i+5) takes the slot of K(i)
+                f32x16 sn;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) sn[r] = 0.f;
+#pragma unroll
+                for (int ks = 0; ks < 8; ++ks) sn = MFMA32(fr[ks], qop[ks], sn);       // scores of tile i+1
+#pragma unroll
+                for (int f = 0; f < 8; ++f) fr[f] = vfrag(s0, f);
+                dma_v(dsc(tile0 + i + 4), s4);           // V(i+4) takes the slot of V(i-1)
+                ps = 0.f;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) expo(sc, r);
+                l_run += ps;
+                const bf16x8 p0 = __builtin_bit_cast(bf16x8, make_uint4(pk[0], pk[1], pk[2], pk[3]));
+                const bf16x8 p1 = __builtin_bit_cast(bf16x8, make_uint4(pk[4], pk[5], pk[6], pk[7]));
+#pragma unroll
+                for (int f = 0; f < 8; ++f) acc[f & 3] = MFMA32(fr[f], (f >> 2) ? p1 : p0, acc[f & 3]);
+#pragma unroll
+                for (int ks = 0; ks < 8; ++ks) fr[ks] = kfrag(s2, ks);
+                mask_and_shift(sn, dsc(tile0 + i + 1));
+                rebase(sn, col_max(sn));
+                sc = sn;
+                __builtin_amdgcn_s_waitcnt(0x0F74);      // vmcnt(4)
+                ring_barrier();
+                u = u + 1 == RING ? 0 : u + 1;
+            }
+        } else {
+            for (int i = 0; i < n_it; i += RING) {
+                iteration(IC<0>{}, IC<0>{}, i);
+                if (i + 1 >= n_it) break;
+                iteration(IC<1>{}, IC<0>{}, i + 1);
+                if (i + 2 >= n_it) break;
+                iteration(IC<2>{}, IC<0>{}, i + 2);
+                if (i + 3 >= n_it) break;
+                iteration(IC<3>{}, IC<0>{}, i + 3);
+                if (i + 4 >= n_it) break;
+                iteration(IC<4>{}, IC<0>{}, i + 4);
+            }
         }
         __builtin_amdgcn_s_waitcnt(0x0F70);              // drain outstanding direct loads
         // the last tile: softmax part 2 and P.V with nothing to overlap with
@@ -546,9 +675,10 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
     }
 }
 
-void pc_launch_prefill_bf16(const PcLaunch &L, int n_items, hipStream_t st)
+void pc_launch_prefill_bf16(const PcLaunch &L, int n_items, bool packed, hipStream_t st)
 {
     if (n_items <= 0) return;
     dim3 grid((unsigned)n_items * L.n_kv_heads);
-    pc_prefill_bf16_kernel<<<grid, 512, 0, st>>>(L);
+    if (packed) pc_prefill_bf16_kernel<true><<<grid, 512, 0, st>>>(L);
+    else pc_prefill_bf16_kernel<false><<<grid, 512, 0, st>>>(L);
 }

@@ -77,7 +77,7 @@ int32_t pc_resolve(pc_cache *c, const pc_call *call, int idx, Resolved &out)
     return PC_OK;
 }
 
-PlanLayout make_layout(int n_calls, int total_sel, int total_q, int total_seg, int n_dec, int n_pre,
+PlanLayout make_layout(int n_calls, int total_sel, int total_q, int total_seg, int n_dec, int n_pre, int n_pre_pk,
                        int64_t part_rows, int64_t total_tiles, int H_q, int D,
                        size_t n_sh_groups = 0, size_t n_sh_segs = 0, size_t n_sh_items = 0, size_t n_sh_pos = 0,
                        size_t n_kg_items = 0, int64_t kg_tiles = 0, int H_kv = 1)
@@ -92,6 +92,7 @@ PlanLayout make_layout(int n_calls, int total_sel, int total_q, int total_seg, i
     L.merge_rows = take(sizeof(PcMergeRow) * (size_t)std::max(total_q, 1));
     L.items_dec = take(sizeof(PcItem) * (size_t)std::max(n_dec, 1));
     L.items_pre = take(sizeof(PcItem) * (size_t)std::max(n_pre, 1));
+    L.items_pk = take(sizeof(PcItem) * (size_t)std::max(n_pre_pk, 1));
     L.sh_groups = take(sizeof(PcShGroup) * std::max<size_t>(n_sh_groups, 1));
     L.sh_segs = take(sizeof(PcShSeg) * std::max<size_t>(n_sh_segs, 1));
     L.sh_items = take(sizeof(PcShItem) * std::max<size_t>(n_sh_items, 1));
@@ -100,14 +101,15 @@ PlanLayout make_layout(int n_calls, int total_sel, int total_q, int total_seg, i
     L.h2d_bytes = o;
     L.segs = take(sizeof(PcSegment) * (size_t)std::max(total_seg, 1));
     L.seg_kvoff = take(sizeof(int32_t) * (size_t)std::max(total_seg, 1));
-    L.rot_seg = take(sizeof(float2) * ((size_t)std::max(total_seg, 1) + 1) * (D / 2));       // one more row: the rotation by zero
+    L.rot_seg = take(sizeof(float2) * (size_t)std::max(total_seg, 1) * (D / 2));
     L.rot_q = take(sizeof(float2) * (size_t)std::max(total_q, 1) * (D / 2));
     L.tiles = take(sizeof(PcTile) * (size_t)std::max<int64_t>(total_tiles, 1));
     L.sh_rot = take(sizeof(float2) * std::max<size_t>(n_sh_pos, 1) * (D / 2));
     L.part_o = take(sizeof(uint16_t) * (size_t)std::max<int64_t>(part_rows, 1) * H_q * D);
     L.part_ml = take(sizeof(float) * (size_t)std::max<int64_t>(part_rows, 1) * H_q * 2);
     L.row_scalar = take(sizeof(float) * (size_t)std::max(total_q, 1) * H_q);      // one float per (row, head): the gradient path's Delta
-    L.k_gather = take((size_t)std::max<int64_t>(kg_tiles, 0) * PC_TILE * (size_t)H_kv * (size_t)D * 2);   // bf16 keys of the calls that gather
+    L.k_gather = take((size_t)std::max<int64_t>(kg_tiles, 0) * PC_TILE * (size_t)H_kv * (size_t)D * 2);   // bf16 keys ...
+    L.v_gather = take((size_t)std::max<int64_t>(kg_tiles, 0) * PC_TILE * (size_t)H_kv * (size_t)D * 2);   // ... and values of the calls that gather
     L.total = o;
     return L;
 }
@@ -266,7 +268,7 @@ int32_t pc_plan_and_stage(pc_cache *c, const pc_call *calls, int32_t n_calls, bo
     // work-group shape of the prefill kernel: 8 row units (32 rows x 1 q head each) per group
     P.pre_waves = 8;
     std::vector<PcCallDesc> cds((size_t)n_calls);
-    std::vector<PcItem> dec, pre;
+    std::vector<PcItem> dec, pre, pre_pk;
     std::vector<PcGatherItem> kg;
     int64_t kg_tiles = 0;
     int64_t part_rows = 0, total_tiles = 0;
@@ -298,7 +300,7 @@ int32_t pc_plan_and_stage(pc_cache *c, const pc_call *calls, int32_t n_calls, bo
         cd.self_msg = own_plan ? r.self_msg : -1; cd.self_start = r.self_start;
         cd.n_q = r.n_q; cd.q_off = q_off; cd.seg_off = seg_off; cd.n_seg = cd.n_sel + (cd.self_msg >= 0 ? 1 : 0);
         cd.self_len = own_plan ? r.self_len : 0; cd.n_splits = 1; cd.part_off = 0; cd.tile_off = (int32_t)total_tiles;
-        cd.kg_tile0 = -1; cd.pad[0] = cd.pad[1] = cd.pad[2] = 0;
+        cd.kg_tile0 = -1; cd.n_par = 0; cd.pad[0] = cd.pad[1] = 0;
         if (own_plan) total_tiles += r.tiles;
         sel_off += cd.n_sel; q_off += cd.n_q; seg_off += cd.n_seg;
         if (!want_items || !bf16 || !own_plan) continue;
@@ -322,46 +324,40 @@ int32_t pc_plan_and_stage(pc_cache *c, const pc_call *calls, int32_t n_calls, bo
                 dec.push_back(it);
             }
         } else {
-            // Key gather: with many query rows it is cheaper to turn the call's keys to their positions once, into a
-            // copy, than to turn the queries of every (32-row block, head) at every new message.  Per gathered token the
-            // copy moves 4096 bytes (K of all KV heads read and written: about 0.9 ns); per token and 32-key tile the
-            // turns cost rows x heads x 0.34 ps / (tiles per message) of the attention's own time.  The copy pays when
-            // rows x heads exceeds about 2650 x tiles per turn; taken from twice that on.  (Not with a fixed
-            // workspace the copy may not fit into.)
-            {
-                int64_t n_turns = 0;                      // segments whose start - stored base differs from the one before
-                int32_t prev = 0;
-                for (size_t e = 0; e < r.sel.size(); ++e) {
-                    const int32_t rot = r.sel[e].y - c->msgs[(size_t)r.sel[e].x].base_pos;
-                    n_turns += (e == 0 || rot != prev);
-                    prev = rot;
-                }
-                if (r.self_msg >= 0) n_turns += (r.sel.empty() || r.self_start - c->msgs[(size_t)r.self_msg].base_pos != prev);
-                const bool pays = (int64_t)r.n_q * c->cfg.n_q_heads * n_turns >= (int64_t)5300 * T;
-                if (T > 0 && !P.fixed_ws && (c->key_gather == 2 || (c->key_gather == 0 && pays)) &&
-                    kg_tiles + T < (int64_t)1 << 24) {
-                    cd.kg_tile0 = (int32_t)kg_tiles;
-                    kg.push_back(PcGatherItem{i, (int32_t)kg_tiles, T, 0});
-                    kg_tiles += T;
-                }
+            // Gather: a call with many query rows reads its keys and values from a packed copy (the gather pass: keys
+            // turned to the call's positions, no padding between messages), which moves 8192 bytes per listed token once
+            // (about 1.8 ns) and saves the turns of the queries at every message, the ragged tile at every message's end
+            // and the per-tile lookups: 15 to 25 % of the attention's own time, which is rows x heads x 0.47 ps per token.
+            // The copy pays from rows x query heads of about 20 thousand on; taken from 32768 on.  (Not with a fixed
+            // workspace, which the copy may not fit into.)
+            const int self_tiles = r.self_msg >= 0 ? (r.self_len + PC_TILE - 1) / PC_TILE : 0;
+            int64_t n_par = 0;
+            for (const int2 &e : r.sel) n_par += c->msgs[(size_t)e.x].len;
+            const int p_tiles = (int)((n_par + PC_TILE - 1) / PC_TILE);
+            const bool packed = T > 0 && !P.fixed_ws && kg_tiles + p_tiles + self_tiles < ((int64_t)1 << 24) &&
+                                (c->key_gather == 2 || (c->key_gather == 0 && (int64_t)r.n_q * c->cfg.n_q_heads >= 32768));
+            if (packed) {
+                cd.kg_tile0 = (int32_t)kg_tiles; cd.n_par = (int32_t)n_par;
+                kg.push_back(PcGatherItem{i, (int32_t)kg_tiles, p_tiles + self_tiles, (int32_t)n_par});
+                kg_tiles += p_tiles + self_tiles;
             }
+            const int Tc = packed ? p_tiles + self_tiles : T;        // tiles the attention kernel walks for this call
             const int units = ((r.n_q + 31) / 32) * g;
             const int groups = (units + P.pre_waves - 1) / P.pre_waves;
             int ns = 1;
-            if (c->prefill_tiles_per_split > 0) ns = (T + c->prefill_tiles_per_split - 1) / c->prefill_tiles_per_split;
-            else if (pre_groups < 256) ns = (int)std::min<int64_t>((256 + pre_groups - 1) / pre_groups, std::max(1, T / 16));
+            if (c->prefill_tiles_per_split > 0) ns = (Tc + c->prefill_tiles_per_split - 1) / c->prefill_tiles_per_split;
+            else if (pre_groups < 256) ns = (int)std::min<int64_t>((256 + pre_groups - 1) / pre_groups, std::max(1, Tc / 16));
             ns = std::max(1, std::min(MAX_SPLITS, ns));
-            const int chunk = std::max(1, (T + ns - 1) / ns);
-            ns = std::max(1, (T + chunk - 1) / chunk);
+            const int chunk = std::max(1, (Tc + ns - 1) / ns);
+            ns = std::max(1, (Tc + chunk - 1) / chunk);
             cd.n_splits = ns;
             // A group of row units walks the parents' tiles and the tiles of the new message up to the
             // causal limit of its last row (the kernel relies on tile_end being cut there); its splits
             // divide THAT count evenly, so the groups with early rows do not end up with a nearly empty
             // last split.
-            const int self_tiles = r.self_msg >= 0 ? (r.self_len + PC_TILE - 1) / PC_TILE : 0;
-            const int parent_tiles = T - self_tiles;
+            const int parent_tiles = Tc - self_tiles;
             for (int gidx = 0; gidx < groups; ++gidx) {
-                int Tg = T;
+                int Tg = Tc;
                 if (r.self_msg >= 0) {
                     const int last_unit = std::min(gidx * P.pre_waves + P.pre_waves - 1, units - 1);
                     const int lim = (r.self_len - r.n_q) + std::min(32 * (last_unit / g) + 31, r.n_q - 1);   // last own token seen
@@ -372,7 +368,7 @@ int32_t pc_plan_and_stage(pc_cache *c, const pc_call *calls, int32_t n_calls, bo
                     PcItem it{}; it.call = i; it.unit0 = gidx * P.pre_waves; it.split = s; it.tile_tab0 = cd.tile_off;
                     it.tile_begin = std::min(Tg, s * chunk_g);
                     it.tile_end = s == ns - 1 ? Tg : std::min(Tg, (s + 1) * chunk_g);
-                    pre.push_back(it);
+                    (packed ? pre_pk : pre).push_back(it);
                 }
             }
         }
@@ -399,12 +395,12 @@ int32_t pc_plan_and_stage(pc_cache *c, const pc_call *calls, int32_t n_calls, bo
     }
     if (part_rows > INT32_MAX) return pc_fail(c, PC_ERR_SHAPE, "attend: partial buffer too large");
     P.total_sel = sel_off; P.total_seg = seg_off;
-    P.n_dec = (int)dec.size(); P.n_pre = (int)pre.size();
+    P.n_dec = (int)dec.size(); P.n_pre = (int)pre.size(); P.n_pre_pk = (int)pre_pk.size();
     P.n_sh_items = (int)sp.items.size(); P.n_sh_pos = sp.pos.size();
     P.n_kg_items = (int)kg.size(); P.kg_tiles = kg_tiles;
     if (total_tiles > INT32_MAX / 2) return pc_fail(c, PC_ERR_SHAPE, "attend: too many KV tiles");
     if (sp.pos.size() > (size_t)INT32_MAX / 2) return pc_fail(c, PC_ERR_SHAPE, "attend: shared decode table too large");
-    P.lay = make_layout(n_calls, P.total_sel, P.total_q, P.total_seg, P.n_dec, P.n_pre, part_rows, total_tiles, c->cfg.n_q_heads, c->D,
+    P.lay = make_layout(n_calls, P.total_sel, P.total_q, P.total_seg, P.n_dec, P.n_pre, P.n_pre_pk, part_rows, total_tiles, c->cfg.n_q_heads, c->D,
                         sp.groups.size(), sp.segs.size(), sp.items.size(), sp.pos.size(), kg.size(), kg_tiles, H_kv);
     if (c->host_only) return PC_OK;
 
@@ -450,6 +446,7 @@ int32_t pc_plan_and_stage(pc_cache *c, const pc_call *calls, int32_t n_calls, bo
     }
     if (!dec.empty()) std::memcpy(h + P.lay.items_dec, dec.data(), sizeof(PcItem) * dec.size());
     if (!pre.empty()) std::memcpy(h + P.lay.items_pre, pre.data(), sizeof(PcItem) * pre.size());
+    if (!pre_pk.empty()) std::memcpy(h + P.lay.items_pk, pre_pk.data(), sizeof(PcItem) * pre_pk.size());
     if (!kg.empty()) std::memcpy(h + P.lay.kg_items, kg.data(), sizeof(PcGatherItem) * kg.size());
     if (!sp.items.empty()) {
         std::memcpy(h + P.lay.sh_groups, sp.groups.data(), sizeof(PcShGroup) * sp.groups.size());
