@@ -54,6 +54,36 @@ static int32_t attend_impl(pc_cache *c, const pc_call *calls, int32_t n_calls, c
         PC_HIP(c, hipGetLastError());
         return PC_OK;
     }
+    // A mixed batch (Sec. 2.4 "Parallel API Calls": prefill and decode calls in one batch): the one-row calls run on a
+    // second stream beside the prefill calls, forked behind the plan builder and joined in front of the split merge.
+    // A prefill workgroup fills a compute unit, so the two do not share units; the decode work fills the units the
+    // prefill's uneven tail (causal rows) leaves idle instead of waiting behind it.  With kernel timing on, everything
+    // stays on the caller's stream: the events around a kernel would otherwise time its neighbours as well.
+    const bool has_pre = P.n_pre > 0 || P.n_pre_pk > 0, has_dec = P.n_dec > 0 || P.n_sh_items > 0;
+    const bool fork = has_pre && has_dec && !c->prof && c->side;
+    hipStream_t st_dec = st;
+    if (fork) {
+        PC_HIP(c, hipEventRecord(c->ev_fork, st));
+        PC_HIP(c, hipStreamWaitEvent(c->side, c->ev_fork, 0));
+        st_dec = c->side;
+    }
+    if (P.n_dec > 0) {
+        ProfScope ps(c, 3, st_dec);
+        L.items = (const PcItem *)(w + P.lay.items_dec);
+        pc_launch_decode_bf16(L, P.n_dec, st_dec);
+        PC_HIP(c, hipGetLastError());
+    }
+    if (P.n_sh_items > 0) {
+        ProfScope ps(c, 3, st_dec);
+        PcShLaunch S{};
+        S.groups = (const PcShGroup *)(w + P.lay.sh_groups);
+        S.segs = (const PcShSeg *)(w + P.lay.sh_segs);
+        S.items = (const PcShItem *)(w + P.lay.sh_items);
+        S.rot = (const float2 *)(w + P.lay.sh_rot);
+        pc_launch_decode_shared_bf16(L, S, P.n_sh_items, st_dec);
+        PC_HIP(c, hipGetLastError());
+    }
+    if (fork) PC_HIP(c, hipEventRecord(c->ev_join, c->side));
     if (P.n_kg_items > 0) {
         ProfScope ps(c, 8, st);
         pc_launch_gather(L, (const PcGatherItem *)(w + P.lay.kg_items), P.n_kg_items, P.kg_tiles, (const int32_t *)(w + P.lay.seg_kvoff), st);
@@ -71,22 +101,7 @@ static int32_t attend_impl(pc_cache *c, const pc_call *calls, int32_t n_calls, c
         pc_launch_prefill_bf16(L, P.n_pre, false, st);
         PC_HIP(c, hipGetLastError());
     }
-    if (P.n_dec > 0) {
-        ProfScope ps(c, 3, st);
-        L.items = (const PcItem *)(w + P.lay.items_dec);
-        pc_launch_decode_bf16(L, P.n_dec, st);
-        PC_HIP(c, hipGetLastError());
-    }
-    if (P.n_sh_items > 0) {
-        ProfScope ps(c, 3, st);
-        PcShLaunch S{};
-        S.groups = (const PcShGroup *)(w + P.lay.sh_groups);
-        S.segs = (const PcShSeg *)(w + P.lay.sh_segs);
-        S.items = (const PcShItem *)(w + P.lay.sh_items);
-        S.rot = (const float2 *)(w + P.lay.sh_rot);
-        pc_launch_decode_shared_bf16(L, S, P.n_sh_items, st);
-        PC_HIP(c, hipGetLastError());
-    }
+    if (fork) PC_HIP(c, hipStreamWaitEvent(st, c->ev_join, 0));
     if (P.n_merge_rows > 0) {
         ProfScope ps(c, 4, st);
         const PcMergeRow *rows = (const PcMergeRow *)(w + P.lay.merge_rows);

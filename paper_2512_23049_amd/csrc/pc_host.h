@@ -64,6 +64,9 @@ struct pc_cache {
     int decode_sharing = 0;                            // 0 auto, 1 never, 2 whenever possible
     int key_gather = 0;                                // gather pass for prefill calls: 0 by size, 1 never, 2 always
     void *static_ws = nullptr;                         // this device's copy of the library's fixed scratch array
+    // a mixed batch runs its one-row calls beside its prefill calls: a second stream (default priority) forked from
+    // and joined to the caller's with these two events
+    hipStream_t side = nullptr; hipEvent_t ev_fork = nullptr, ev_join = nullptr;
     std::string err;
 };
 

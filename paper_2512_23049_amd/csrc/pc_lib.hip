@@ -124,6 +124,9 @@ int32_t pc_cache_create(const pc_config *cfg, pc_cache **out)
         c->stage[i].cap = (size_t)1 << 20;
         if (hipEventCreateWithFlags(&c->stage[i].ev, hipEventDisableTiming) != hipSuccess) return bail(PC_ERR_HIP);
     }
+    if (hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking) != hipSuccess) return bail(PC_ERR_HIP);
+    if (hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming) != hipSuccess) return bail(PC_ERR_HIP);
+    if (hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming) != hipSuccess) return bail(PC_ERR_HIP);
     {   // this device's address of the library's fixed scratch array (pc_attend_static works in it)
         size_t n = 0;
         if (pc_static_scratch(&c->static_ws, &n) != PC_OK) return bail(PC_ERR_HIP);
@@ -140,6 +143,9 @@ int32_t pc_cache_destroy(pc_cache *c)
         pc_prof_collect(c);
         for (auto e : c->ev_pool) (void)hipEventDestroy(e);
         for (auto &s : c->stage) { if (s.host) (void)hipHostFree(s.host); if (s.ev) (void)hipEventDestroy(s.ev); }
+        if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);
+        if (c->ev_join) (void)hipEventDestroy(c->ev_join);
+        if (c->side) (void)hipStreamDestroy(c->side);
         if (c->ws) (void)hipFree(c->ws);
         if (c->tok_dev) (void)hipFree(c->tok_dev);
         if (c->inv_freq_dev) (void)hipFree(c->inv_freq_dev);
