@@ -7,10 +7,13 @@ batch of calls (plan builder, attention kernels, split merge).  The messages the
 calls select are already resident in the cache (they are the method's persistent
 state), as are all inputs in HBM.
 
-Prints ONE JSON line.  The headline is the single-call prefill workload (prefill
-TFLOP/s against the bf16 MFMA roofline); the parallel-decode workload (GB/s against
-the HBM roofline) and the other workloads are reported in the same line under
-"decode" and "extras".
+Prints ONE JSON line.  The headline is the largest configuration that fits one GPU, the
+long-context mixed batch (configs[4]: one 2048-row prefill call and 32 decode calls, each
+over ~64k selected tokens, 64 query heads): prefill TFLOP/s of the whole step against the
+bf16 MFMA roofline, with the decode kernel of the same step against the HBM roofline beside
+it.  The other configurations (configs[1] single prefill, configs[2] parallel decode,
+configs[3] multi-agent rounds) and the further workloads are reported in the same line
+under "extras", each with its own roofline and CPU baseline.
 """
 from __future__ import annotations
 
@@ -41,16 +44,41 @@ def visible_pairs(w, ev):
     return out
 
 
+def kernel_sources_hash():
+    """sha256 over the library's sources: a committed counter summary is only quoted while it describes these kernels."""
+    import hashlib
+    h = hashlib.sha256()
+    src = os.path.join(ROOT, "paper_2512_23049_amd", "csrc")
+    for f in sorted(os.listdir(src)):
+        if f.endswith((".hip", ".h")) and not f.startswith("_var_"):
+            h.update(f.encode())
+            h.update(open(os.path.join(src, f), "rb").read())
+    return h.hexdigest()[:16]
+
+
+_TRAFFIC_NOTE = None
+
+
 def measured_traffic(kernel, workload):
-    """HBM bytes per launch (fetch + write) from the committed rocprofv3 counter summary, or None."""
+    """HBM bytes per launch (fetch + write) from the committed rocprofv3 counter summary, or None when there is none
+    for this kernel and workload or when the summary was taken with other kernel sources than the ones in the tree
+    (its header names the hash of the sources it belongs to)."""
+    global _TRAFFIC_NOTE
     path = os.path.join(ROOT, "profiles", "attention_kernels_hbm_traffic.txt")
     try:
-        for ln in open(path):
-            f = ln.strip().split(",")
-            if len(f) >= 6 and f[0].startswith(kernel) and f[5] == workload:
-                return (float(f[3]) + float(f[4])) * 1e6
+        lines = open(path).read().splitlines()
     except OSError:
-        pass
+        _TRAFFIC_NOTE = "no counter summary under profiles/"
+        return None
+    tag = [ln.split(":", 1)[1].strip() for ln in lines if ln.startswith("# csrc_sha256:")]
+    if not tag or tag[0] != kernel_sources_hash():
+        _TRAFFIC_NOTE = ("profiles/attention_kernels_hbm_traffic.txt was taken with other kernel sources (%s, tree %s): "
+                         "not quoted" % (tag[0] if tag else "untagged", kernel_sources_hash()))
+        return None
+    for ln in lines:
+        f = ln.strip().split(",")
+        if len(f) >= 6 and f[0].startswith(kernel) and f[5] == workload:
+            return (float(f[3]) + float(f[4])) * 1e6
     return None
 
 
@@ -93,12 +121,16 @@ def bench_attend_workload(name, w, steps, warmup, torch, harness, reappend_self=
     marsh = marshal_calls(calls)
     with_self = [(i, c.self_msg) for i, c in enumerate(calls) if c.self_msg >= 0]
 
+    k_ptrs = [new_kv[m][0].data_ptr() for m in new_ids]
+    v_ptrs = [new_kv[m][1].data_ptr() for m in new_ids]
+    n_lens = [new_kv[m][2] for m in new_ids]
+    n_res = [new_kv[m][3] for m in new_ids]
+
     def step():
         if reappend_self:
-            remap = {}
-            for m in new_ids:
-                k, v, L, res = new_kv[m]
-                remap[m] = cache.append_message(k.data_ptr(), v.data_ptr(), L, res)
+            # the step's new messages go in with one pc_append_messages (one launch), as a batch of parallel calls does
+            ids = cache.append_messages(k_ptrs, v_ptrs, n_lens, n_res)
+            remap = dict(zip(new_ids, ids))
             for i, m in with_self:
                 marsh[0][i].self_msg = remap[m]
             cache.attend(calls, q.data_ptr(), out.data_ptr(), 0, 0, marsh)
@@ -164,37 +196,106 @@ class Ctx:
         self.achievable = None           # filled by section_achievable, read by section_decode
 
 
+def decode_bytes(w, calls, vp):
+    """(logical, unique) K/V bytes of the given one-row calls: 2 * H_kv * D * 2 bytes per selected token."""
+    per_token = 2 * w.n_kv_heads * w.head_dim * 2
+    lens = w.message_lengths()
+    uniq = set()
+    for c in calls:
+        uniq.update(m for m, _ in c.sel)
+        if c.self_msg >= 0:
+            uniq.add(c.self_msg)
+    return sum(v[1] + v[2] for v in vp) * per_token, sum(lens[m] for m in uniq) * per_token
+
+
+def roofline_mfma(kernel, flops, k_us, workload):
+    ach = (flops / (k_us * 1e-6) / 1e12) if k_us else None
+    return {"bound": "mfma", "kernel": kernel, "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+            "frac": (ach / MFMA_BF16_PEAK_TFLOPS) if ach else None, "traffic": measured_traffic(kernel, workload),
+            "avg_kernel_us": k_us, "algorithmic_flops_per_launch": flops}
+
+
+def roofline_hbm(kernel, b_logical, b_unique, k_us, workload):
+    """HBM roofline of a decode kernel.  `achieved` / `frac` are on the bytes rocprofv3 counted for one launch (None
+    while no counter summary for these kernel sources is committed); the rate on logical bytes (4096 B per
+    call-selected token) is an EFFECTIVE one, because calls share messages, and is kept under its own name."""
+    traffic = measured_traffic(kernel, workload)
+    ach = (traffic / (k_us * 1e-6) / 1e9) if (traffic and k_us) else None
+    return {"bound": "hbm", "kernel": kernel, "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": (ach / HBM_PEAK_GBS) if ach else None, "traffic": traffic, "avg_kernel_us": k_us,
+            "basis": "HBM bytes counted by rocprofv3 per launch (FETCH_SIZE + WRITE_SIZE, scaled by a plain copy)",
+            "B_logical": b_logical, "B_unique": b_unique,
+            "effective_gbs_on_logical_bytes": (b_logical / (k_us * 1e-6) / 1e9) if k_us else None,
+            "gbs_on_unique_bytes": (b_unique / (k_us * 1e-6) / 1e9) if k_us else None}
+
+
 def section_headline(cx):
-    """configs[1], the workload the metric is quoted on: fills the contract's fields of the JSON line."""
+    """configs[4], the largest configuration one GPU holds: fills the contract's fields of the JSON line."""
     args, torch, gen, harness = cx.args, cx.torch, cx.gen, cx.harness
-    w2 = gen.single_prefill()
-    sec, sec_prof, kern, vp = bench_attend_workload("single_prefill", w2, args.steps, args.warmup, torch, harness)
-    pairs = sum(v[3] for v in vp)
-    flops = 4.0 * w2.head_dim * w2.n_q_heads * pairs
+    w5 = gen.long_context()
+    sec, sec_prof, kern, vp = bench_attend_workload("long_context", w5, args.steps, args.warmup, torch, harness)
+    ev = w5.events[-1]
+    pre = [v for v in vp if v[0] > 1]
+    dec = [v for v in vp if v[0] == 1]
+    f_pre = 4.0 * w5.head_dim * w5.n_q_heads * sum(v[3] for v in pre)
+    b_log, b_uni = decode_bytes(w5, [c for c in ev.calls if c.n_q == 1], dec)
     k_pre = kern.get("prefill", {}).get("avg_us")
+    k_dec = kern.get("decode", {}).get("avg_us")
     line = {
         "metric": "choreographed attention prefill TFLOP/s + decode GB/s, % of MI355X roofline",
-        "value": flops / sec / 1e12, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "value": f_pre / sec / 1e12, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": sec * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "configs[1] single-call prefill: 32 q heads / 8 kv heads / D 128, 16 selected "
-                               "messages (%d keys) + causal 512-token new message; step = append new message + pc_attend"
-                               % vp[0][1],
-                   "flops_per_step": flops},
-        "roofline": {"bound": "mfma", "kernel": "pc_prefill_bf16_kernel",
-                     "achieved": (flops / (k_pre * 1e-6) / 1e12) if k_pre else None, "peak": MFMA_BF16_PEAK_TFLOPS,
-                     "unit": "TFLOP/s", "frac": (flops / (k_pre * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS) if k_pre else None,
-                     "traffic": measured_traffic("pc_prefill_bf16_kernel", "single_prefill"), "avg_kernel_us": k_pre},
+        "config": {"workload": "configs[4] long-context mixed batch: 64 q heads / 8 kv heads / D 128; one 2048-row causal "
+                               "prefill call over %d selected tokens + 32 one-row decode calls over ~64k selected tokens each "
+                               "(all drawn from the same 512 cached messages); step = append the new messages (one "
+                               "2048-token message, 32 one-token tails) + ONE pc_attend of the 33 calls; value = the "
+                               "prefill call's algorithmic flops over the whole step's time" % pre[0][1],
+                   "prefill_flops_per_step": f_pre, "decode_logical_bytes_per_step": b_log},
+        # the dominant kernel of the step: the prefill call (it reads the packed copy the gather pass wrote)
+        "roofline": roofline_mfma("pc_prefill_bf16_kernel", f_pre, k_pre, "long_context"),
+        # the decode kernel of the same step (the 32 calls take the shared walk: the union of their messages is read once)
+        "roofline_decode": roofline_hbm("pc_decode_shared_bf16_kernel", b_log, b_uni, k_dec, "long_context"),
+        "decode_value": {"gbs_effective_on_logical_bytes_over_decode_kernel": (b_log / (k_dec * 1e-6) / 1e9) if k_dec else None},
+        # kernel times come from a second pass of the same steps with the library's per-kernel events on; that pass keeps
+        # every kernel on one stream (the timed pass forks the decode kernels onto a second stream), hence two step times
         "kernels_us": {k: v["avg_us"] for k, v in kern.items()},
         "ms_per_step_with_kernel_events": sec_prof * 1e3,
     }
+    if _TRAFFIC_NOTE:
+        line["traffic_note"] = _TRAFFIC_NOTE
     if not args.skip_cpu:
+        rows = list(range(0, 2048, 8))
         line["cpu_baseline"] = cpu_baseline(
-            w2, {"calls": [0], "rows": lambda n: list(range(n)),
-                 "desc": "configs[1] whole: all 512 query rows, all 32 heads, all keys (under a second of CPU "
-                         "work; the oracle is the plain definition on BLAS)"}, "TFLOP/s")
-    del w2
+            w5, {"calls": [32, 0, 10, 21, 31], "rows": lambda n: rows if n > 1 else [0],
+                 "desc": "configs[4] sample: the prefill call's every 8th query row (256 of 2048 rows, all 64 heads, all "
+                         "%d keys) and 4 of the 32 decode calls; TFLOP/s on the sample's visible (row, key) pairs" % pre[0][1]},
+            "TFLOP/s")
+    del w5
     cx.line = line
+
+
+def section_single_prefill(cx):
+    """configs[1]: one 512-row prefill call over 16 selected messages."""
+    args, torch, gen, harness, line = cx.args, cx.torch, cx.gen, cx.harness, cx.line
+    w2 = gen.single_prefill()
+    sec, sec_prof, kern, vp = bench_attend_workload("single_prefill", w2, args.steps, args.warmup, torch, harness)
+    flops = 4.0 * w2.head_dim * w2.n_q_heads * sum(v[3] for v in vp)
+    k_pre = kern.get("prefill", {}).get("avg_us")
+    out = {
+        "workload": "configs[1] single-call prefill: 32 q heads / 8 kv heads / D 128, 16 selected messages (%d keys) + causal "
+                    "512-token new message; step = append new message + pc_attend" % vp[0][1],
+        "value": flops / sec / 1e12, "unit": "TFLOP/s", "ms_per_step": sec * 1e3, "flops_per_step": flops,
+        "roofline": roofline_mfma("pc_prefill_bf16_kernel", flops, k_pre, "single_prefill"),
+        "kernels_us": {k: v["avg_us"] for k, v in kern.items()}, "ms_per_step_with_kernel_events": sec_prof * 1e3}
+    if cx.achievable and out["roofline"]["achieved"]:
+        out["roofline"]["frac_of_achievable"] = out["roofline"]["achieved"] / cx.achievable["mfma_bf16_random_operands_tflops"]
+    if not args.skip_cpu:
+        out["cpu_baseline"] = cpu_baseline(
+            w2, {"calls": [0], "rows": lambda n: list(range(n)),
+                 "desc": "configs[1] whole: all 512 query rows, all 32 heads, all keys"}, "TFLOP/s")
+    line.setdefault("extras", {})["single_prefill"] = out
+    del w2
 
 
 def section_achievable(cx):
@@ -221,84 +322,36 @@ def section_achievable(cx):
     if line["roofline"]["achieved"]:
         line["roofline"]["frac_of_achievable"] = (line["roofline"]["achieved"]
                                                   / achievable["mfma_bf16_random_operands_tflops"])
+    if line["roofline_decode"]["achieved"]:
+        line["roofline_decode"]["frac_of_achievable"] = line["roofline_decode"]["achieved"] / achievable["hbm_stream_read_gbs"]
     cx.achievable = achievable
 
 
 def section_decode(cx):
-    """configs[2]: the parallel decode step, HBM roofline on logical and on measured bytes."""
+    """configs[2]: the parallel decode step, HBM roofline on counted bytes, effective rate on logical bytes."""
     args, torch, gen, harness, line = cx.args, cx.torch, cx.gen, cx.harness, cx.line
-    achievable = cx.achievable
     w3 = gen.parallel_decode()
     sec, sec_prof, kern, vp = bench_attend_workload("parallel_decode", w3, args.steps, args.warmup, torch, harness,
                                                     reappend_self=False)
-    bytes_per_token = 2 * w3.n_kv_heads * w3.head_dim * 2
-    b_logical = sum(v[1] + v[2] for v in vp) * bytes_per_token
     ev = w3.events[-1]
-    lens = w3.message_lengths()
-    uniq = set()
-    for c in ev.calls:
-        uniq.update(m for m, _ in c.sel)
-        uniq.add(c.self_msg)
-    b_unique = sum(lens[m] for m in uniq) * bytes_per_token
+    b_logical, b_unique = decode_bytes(w3, ev.calls, vp)
     k_dec = kern.get("decode", {}).get("avg_us")
-    traffic_dec = measured_traffic("pc_decode_bf16_kernel", "parallel_decode")
-    line["decode"] = {
+    out = {
         "workload": "configs[2] parallel decode: 64 calls x (2048-token system + 8 pool messages + 64-token tail), "
                     "one query token per call; step = pc_attend",
-        "value": b_logical / sec / 1e9, "unit": "GB/s (logical bytes: 4096 B per call-selected token)",
+        "value": b_logical / sec / 1e9, "unit": "GB/s (effective: logical bytes, 4096 B per call-selected token, over the step)",
         "ms_per_step": sec * 1e3, "B_logical": b_logical, "B_unique": b_unique,
-        "roofline": {"bound": "hbm", "kernel": "pc_decode_bf16_kernel",
-                     "achieved": (b_logical / (k_dec * 1e-6) / 1e9) if k_dec else None, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": (b_logical / (k_dec * 1e-6) / 1e9 / HBM_PEAK_GBS) if k_dec else None,
-                     "traffic": traffic_dec, "avg_kernel_us": k_dec,
-                     # calls share messages (B_unique < B_logical), so the logical rate is an EFFECTIVE one and
-                     # may exceed the HBM peak; the HBM claim rests on the bytes rocprofv3 counted per launch
-                     "effective": True,
-                     "hbm_measured_gbs": (traffic_dec / (k_dec * 1e-6) / 1e9) if (k_dec and traffic_dec) else None,
-                     "hbm_measured_frac": (traffic_dec / (k_dec * 1e-6) / 1e9 / HBM_PEAK_GBS) if (k_dec and traffic_dec) else None},
-        "kernels_us": {k: v["avg_us"] for k, v in kern.items()},
+        "roofline": roofline_hbm("pc_decode_bf16_kernel", b_logical, b_unique, k_dec, "parallel_decode"),
+        "kernels_us": {k: v["avg_us"] for k, v in kern.items()}, "ms_per_step_with_kernel_events": sec_prof * 1e3,
     }
-    if achievable and line["decode"]["roofline"]["hbm_measured_gbs"]:
-        line["decode"]["roofline"]["hbm_measured_frac_of_achievable"] = (
-            line["decode"]["roofline"]["hbm_measured_gbs"] / achievable["hbm_stream_read_gbs"])
+    if cx.achievable and out["roofline"]["achieved"]:
+        out["roofline"]["frac_of_achievable"] = out["roofline"]["achieved"] / cx.achievable["hbm_stream_read_gbs"]
     if not args.skip_cpu:
-        line["decode"]["cpu_baseline"] = cpu_baseline(
+        out["cpu_baseline"] = cpu_baseline(
             w3, {"calls": list(range(64)), "rows": lambda n: [0],
                  "desc": "configs[2] whole: all 64 calls"}, "GB/s")
+    line.setdefault("extras", {})["parallel_decode"] = out
     del w3
-
-
-def section_long_context(cx):
-    """configs[4]: 32 decode calls and one 2048-row prefill in one batch."""
-    args, torch, gen, harness, line = cx.args, cx.torch, cx.gen, cx.harness, cx.line
-    w5 = gen.long_context()
-    steps5 = max(3, min(args.steps, 20))
-    sec, sec_prof, kern, vp = bench_attend_workload("long_context", w5, steps5, 2, torch, harness)
-    pre = [v for v in vp if v[0] > 1]
-    dec = [v for v in vp if v[0] == 1]
-    f_pre = 4.0 * w5.head_dim * w5.n_q_heads * sum(v[3] for v in pre)
-    b_dec = sum(v[1] + v[2] for v in dec) * 4096
-    k_pre = kern.get("prefill", {}).get("avg_us")
-    k_dec = kern.get("decode", {}).get("avg_us")
-    traffic_dec5 = measured_traffic("pc_decode_shared_bf16_kernel", "long_context")
-    line.setdefault("extras", {})["long_context"] = {
-        "workload": "configs[4]: 32 decode calls + one 2048-row causal prefill over ~64k selected tokens each, "
-                    "64 q heads / 8 kv heads; step = append new messages + one pc_attend",
-        "ms_per_step": sec * 1e3, "steps": steps5,
-        "prefill_tflops_kernel": (f_pre / (k_pre * 1e-6) / 1e12) if k_pre else None,
-        "prefill_frac_mfma_peak": (f_pre / (k_pre * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS) if k_pre else None,
-        # the 32 decode calls list mostly the same messages: they are served by the shared walk, which reads the
-        # union of their messages once (decode_B_unique), so the logical rate is an EFFECTIVE one, far above the
-        # HBM peak; the bytes rocprofv3 counted per launch are in profiles/attention_kernels_hbm_traffic.txt
-        "decode_walk": "shared (pc_decode_shared_bf16_kernel)",
-        "decode_gbs_logical_kernel": (b_dec / (k_dec * 1e-6) / 1e9) if k_dec else None,
-        "decode_frac_hbm_peak_logical": (b_dec / (k_dec * 1e-6) / 1e9 / HBM_PEAK_GBS) if k_dec else None,
-        "decode_effective": True,
-        "decode_hbm_measured_gbs": (traffic_dec5 / (k_dec * 1e-6) / 1e9) if (k_dec and traffic_dec5) else None,
-        "prefill_flops": f_pre, "decode_B_logical": b_dec,
-        "kernels_us": {k: v["avg_us"] for k, v in kern.items()},
-    }
-    del w5
 
 
 def section_long_context_decode(cx):
@@ -308,7 +361,7 @@ def section_long_context_decode(cx):
     steps5 = max(3, min(args.steps, 50))
     out_ld = {}
     for name, mode in (("shared_walk", 0), ("per_call_walk", 1)):
-        sec, _, kern, vp = bench_attend_workload("long_context_decode", w5d, steps5, 3, torch, harness,
+        sec, _, kern, vp = bench_attend_workload("long_context_decode", w5d, steps5, 20, torch, harness,
                                                  reappend_self=False, sharing=mode)
         b_dec = sum(v[1] + v[2] for v in vp) * 4096
         out_ld[name] = {"us_per_step": sec * 1e6, "gbs_logical": b_dec / sec / 1e9,
@@ -376,11 +429,24 @@ def section_rounds(cx):
         t_r = now
     c.profile_enable(False)
     c.close()
-    line.setdefault("extras", {})["multi_agent_rounds"] = {
+    k_pre_total = sum(r_["prefill_kernel_us"] for r_ in per_round)         # six launches: the six rounds
+    out = {
         "workload": "configs[3]: 8 agents x 6 rounds; per round one pc_append_messages of the 8 new 256-token messages "
                     "and one pc_attend of the 8 prefill calls",
-        "ms_per_sequence": sec4 * 1e3, "tflops_incl_appends": f4 / sec4 / 1e12, "flops": f4, "reps": reps,
+        "value": f4 / sec4 / 1e12, "unit": "TFLOP/s (all six rounds' attention flops over the whole sequence, appends included)",
+        "ms_per_sequence": sec4 * 1e3, "flops": f4, "reps": reps,
+        # the six prefill launches of a sequence together (they differ in size: round r attends over 8 (r - 1) + 1 messages)
+        "roofline": {"bound": "mfma", "kernel": "pc_prefill_bf16_kernel", "achieved": f4 / (k_pre_total * 1e-6) / 1e12,
+                     "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": f4 / (k_pre_total * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+                     "traffic": None, "sum_of_six_kernel_us": k_pre_total, "algorithmic_flops_per_sequence": f4},
         "per_round_with_kernel_events": per_round}
+    if not args.skip_cpu:
+        # the oracle on the whole last round (8 calls x 256 rows over all 48 messages): the largest of the six
+        out["cpu_baseline"] = cpu_baseline(
+            w4, {"calls": list(range(8)), "rows": lambda n: list(range(n)),
+                 "desc": "configs[3] last round whole: 8 calls x 256 rows over the 40 messages of the earlier rounds + own"},
+            "TFLOP/s")
+    line.setdefault("extras", {})["multi_agent_rounds"] = out
     del w4
 
 
@@ -469,6 +535,7 @@ def section_reposition(cx):
     from paper_2512_23049_amd.binding import marshal_calls
     w5 = gen.long_context(n_decode=0)
     cache = harness.make_cache(w5)
+    cache.set_key_gather(1)            # the comparison is between the two ways of placing keys IN the cache: no gathered copy
     dw = harness.DeviceWorkload(w5)
     dw.run(cache)
     torch.cuda.synchronize()
@@ -508,7 +575,7 @@ def section_reposition(cx):
     k_batch_us = (prof_b["reposition"][0] / prof_b["reposition"][1] * 1e3) if prof_b["reposition"][1] else None
     line.setdefault("extras", {})["reposition"] = {
         "workload": "configs[4] prefill call alone (2048 rows over ~64k tokens in ~410 messages of 64-256 tokens): "
-                    "pc_attend with every parent at base 0 (queries turned per parent), then every parent moved to "
+                    "gather pass off; pc_attend with every parent at base 0 (queries turned per parent), then every parent moved to "
                     "the start the call gives it (one pc_reposition each, and again as one pc_reposition_batch), "
                     "then the same pc_attend (one turn in all)",
         "attend_ms_before": t_before * 1e3, "attend_ms_after": t_after * 1e3,
@@ -558,7 +625,7 @@ def section_backward(cx):
 
 
 # sections after the headline, in the order they run; --only names them
-SECTIONS = [("achievable", section_achievable), ("decode", section_decode), ("long", section_long_context),
+SECTIONS = [("achievable", section_achievable), ("prefill", section_single_prefill), ("decode", section_decode),
             ("longdecode", section_long_context_decode), ("rounds", section_rounds), ("baseline", section_baseline),
             ("loop", section_decode_loop), ("reposition", section_reposition), ("backward", section_backward)]
 
@@ -567,10 +634,10 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--skip-extras", action="store_true")
     ap.add_argument("--skip-cpu", action="store_true")
-    ap.add_argument("--only", default="", help="comma list of sections: achievable,decode,long,longdecode,rounds,baseline,loop,reposition,backward")
+    ap.add_argument("--only", default="", help="comma list of sections: achievable,prefill,decode,longdecode,rounds,baseline,loop,reposition,backward")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="also launch one plain device copy of this many MiB (reference for scaling rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE counters)")
