@@ -864,8 +864,9 @@ void pc_launch_zero_span(int dtype, void *store, int64_t slots, int n_kv_heads, 
 // instead of one per message.  Padding rows are written as zeros.
 // One block per (tile of the copy, KV head).  The first 32 threads find where the tile's tokens
 // live (a search in the call's segment offsets); then thread = (key row, 8 low dims and their
-// partners 64 up) for K, and thread = (group of 8 tokens, dim) twice for V: eight 2-byte reads
-// (the 2 KB of a source group are shared by the threads of a block through L1), one 16-byte write.
+// partners 64 up) for K, and thread = (group of 8 tokens, dim) twice for V: when the group's tokens
+// sit in 8 consecutive slots (nearly always: messages are long runs of slots) two 16-byte reads and a
+// shift, else eight 2-byte reads; one 16-byte write.
 // ----------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void pc_gather_kernel(PcLaunch L, const PcGatherItem *__restrict__ items, int n_items,
                                                         const int32_t *__restrict__ seg_kvoff)
@@ -928,17 +929,54 @@ __global__ __launch_bounds__(256) void pc_gather_kernel(PcLaunch L, const PcGath
 #pragma unroll
     for (int rep = 0; rep < 2; ++rep) {
         const int idx = threadIdx.x + 256 * rep;
-        const int q = idx >> 7, d = idx & 127;
-        uint32_t w[4] = {0u, 0u, 0u, 0u};
+        const int q = idx >> 7, d = idx & 127;             // (q is the same for all lanes of a wave)
+        int sl[PC_VGROUP];
+        bool run = true;                                   // the group's 8 tokens sit in 8 consecutive slots of the cache
 #pragma unroll
         for (int k = 0; k < PC_VGROUP; ++k) {
-            const int slot = s_slot[PC_VGROUP * q + k];
-            uint32_t v = 0;
-            if (slot >= 0) {
-                const int64_t at = (int64_t)kh * L.slots + slot;
-                v = vsrc[((at >> 3) * 128 + d) * PC_VGROUP + (at & 7)];
+            sl[k] = s_slot[PC_VGROUP * q + k];
+            run = run && sl[0] >= 0 && sl[k] == sl[0] + k;
+        }
+        uint32_t w[4] = {0u, 0u, 0u, 0u};
+        if (run) {
+            // two 16-byte reads (this dim of the source group the run starts in, and of the next one) and a shift by
+            // the run's offset in its group, instead of eight 2-byte reads
+            const int64_t at = (int64_t)kh * L.slots + sl[0];
+            const int sh = (int)(at & 7);
+            const uint16_t *g0 = vsrc + ((at >> 3) * 128 + d) * PC_VGROUP;
+            const uint4 lo = *reinterpret_cast<const uint4 *>(g0);
+            uint4 hi = make_uint4(0, 0, 0, 0);
+            if (sh) hi = *reinterpret_cast<const uint4 *>(g0 + 128 * PC_VGROUP);
+            const uint32_t x[9] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w, 0u};
+            const unsigned bits = 16u * (unsigned)(sh & 1);
+            switch (sh >> 1) {
+            case 0:
+#pragma unroll
+                for (int j = 0; j < 4; ++j) w[j] = __builtin_amdgcn_alignbit(x[j + 1], x[j], bits);
+                break;
+            case 1:
+#pragma unroll
+                for (int j = 0; j < 4; ++j) w[j] = __builtin_amdgcn_alignbit(x[j + 2], x[j + 1], bits);
+                break;
+            case 2:
+#pragma unroll
+                for (int j = 0; j < 4; ++j) w[j] = __builtin_amdgcn_alignbit(x[j + 3], x[j + 2], bits);
+                break;
+            default:
+#pragma unroll
+                for (int j = 0; j < 4; ++j) w[j] = __builtin_amdgcn_alignbit(x[j + 4], x[j + 3], bits);
+                break;
             }
-            w[k >> 1] |= v << (16 * (k & 1));
+        } else {
+#pragma unroll
+            for (int k = 0; k < PC_VGROUP; ++k) {
+                uint32_t v = 0;
+                if (sl[k] >= 0) {
+                    const int64_t at = (int64_t)kh * L.slots + sl[k];
+                    v = vsrc[((at >> 3) * 128 + d) * PC_VGROUP + (at & 7)];
+                }
+                w[k >> 1] |= v << (16 * (k & 1));
+            }
         }
         const int64_t grp = (((int64_t)kh * L.kg_slots + (int64_t)G * PC_TILE) >> 3) + q;
         *reinterpret_cast<uint4 *>(vdst + (grp * 128 + d) * PC_VGROUP) = make_uint4(w[0], w[1], w[2], w[3]);
