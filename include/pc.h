@@ -175,6 +175,16 @@ typedef struct {
 int32_t pc_attend(pc_cache *c, const pc_call *calls, int32_t n_calls,
                   const void *q, void *out, float *lse, void *stream);
 
+/* One decode step of parallel calls in one call (Sec. 2.4 "Parallel API Calls" and the interleaved decoding of
+ * parallel calls): pc_append_tokens_batch(msg_ids, n_msgs, k, v) followed by pc_attend(calls, ...), with the same
+ * arguments, results and errors as the two.  What the fused form saves: the tokens are written by the plan builder's
+ * own launch and their item list rides in the same staging copy as the call list (one launch and one copy fewer per
+ * step).  The append keeps a launch of its own when a grown message is listed as a PARENT by one of the calls or
+ * needs a further extent.  If the append is refused nothing is enqueued; if the call list is refused the tokens
+ * stay appended, as with the two separate calls. */
+int32_t pc_decode_step(pc_cache *c, const int32_t *msg_ids, int32_t n_msgs, const void *k, const void *v,
+                       const pc_call *calls, int32_t n_calls, const void *q, void *out, float *lse, void *stream);
+
 /* pc_attend for callers that cannot allocate device memory: code under HIP graph capture, tight serving loops,
  * harnesses that forbid hipMalloc.  Same arguments, same kernels, same results (bit for bit) as pc_attend; the
  * per-call workspace (staged descriptors, the device-built plan, split partials) lives in a fixed array of

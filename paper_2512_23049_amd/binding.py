@@ -72,6 +72,8 @@ def lib():
         L.pc_append_tokens_batch.argtypes = [vp, C.POINTER(i32), i32, vp, vp, vp]
         L.pc_attend.restype = i32
         L.pc_attend.argtypes = [vp, C.POINTER(pc_call), i32, vp, vp, vp, vp]
+        L.pc_decode_step.restype = i32
+        L.pc_decode_step.argtypes = [vp, C.POINTER(i32), i32, vp, vp, C.POINTER(pc_call), i32, vp, vp, vp, vp]
         L.pc_attend_static.restype = i32
         L.pc_attend_static.argtypes = [vp, C.POINTER(pc_call), i32, vp, vp, vp, vp]
         L.pc_build_tables.restype = i32
@@ -186,6 +188,14 @@ class Cache:
         arr, keep = marshalled if marshalled is not None else marshal_calls(calls)
         self._check(lib().pc_attend(self.h, arr, len(calls), q_ptr or None, out_ptr or None,
                                     lse_ptr or None, stream or None))
+
+    def decode_step(self, msg_ids, k_ptr: int, v_ptr: int, calls, q_ptr: int, out_ptr: int, lse_ptr: int = 0,
+                    stream: int = 0, marshalled=None):
+        """One token for each of msg_ids, then the batch of calls, in one library call."""
+        ids = (C.c_int32 * max(len(msg_ids), 1))(*[int(m) for m in msg_ids])
+        arr, keep = marshalled if marshalled is not None else marshal_calls(calls)
+        self._check(lib().pc_decode_step(self.h, ids, len(msg_ids), k_ptr or None, v_ptr or None, arr, len(calls),
+                                         q_ptr or None, out_ptr or None, lse_ptr or None, stream or None))
 
     def attend_static(self, calls, q_ptr: int, out_ptr: int, lse_ptr: int = 0, stream: int = 0, marshalled=None):
         arr, keep = marshalled if marshalled is not None else marshal_calls(calls)

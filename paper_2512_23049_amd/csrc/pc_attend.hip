@@ -28,9 +28,10 @@ int32_t pc_static_scratch(void **ptr, size_t *bytes)
 
 // fixed_ws: nullptr = the cache's own workspace (grows on demand), else a buffer of fixed_cap bytes the call must fit into
 static int32_t attend_impl(pc_cache *c, const pc_call *calls, int32_t n_calls, const void *q, void *out, float *lse,
-                           hipStream_t st, void *fixed_ws, size_t fixed_cap)
+                           hipStream_t st, void *fixed_ws, size_t fixed_cap, Planned *with_tokens = nullptr)
 {
-    Planned P;
+    Planned own;
+    Planned &P = with_tokens ? *with_tokens : own;       // (a decode step hands in the tokens the plan builder's launch appends)
     P.fixed_ws = fixed_ws; P.fixed_cap = fixed_cap;
     const int32_t rc = pc_plan_and_stage(c, calls, n_calls, true, st, P);
     if (rc != PC_OK || c->host_only) return rc;
@@ -122,6 +123,57 @@ int32_t pc_attend(pc_cache *c, const pc_call *calls, int32_t n_calls, const void
     if (n_calls == 0) return PC_OK;
     if (!c->host_only && (!q || !out)) return pc_fail(c, PC_ERR_INVALID_ARG, "attend: null q or out");
     return attend_impl(c, calls, n_calls, q, out, lse, (hipStream_t)stream, nullptr, 0);
+}
+
+int32_t pc_decode_step(pc_cache *c, const int32_t *msg_ids, int32_t n_msgs, const void *k, const void *v,
+                       const pc_call *calls, int32_t n_calls, const void *q, void *out, float *lse, void *stream)
+{
+    if (!c) return PC_ERR_INVALID_ARG;
+    if (n_calls < 0 || (n_calls > 0 && !calls)) return pc_fail(c, PC_ERR_INVALID_ARG, "decode_step: bad call list");
+    if (!c->host_only && n_calls > 0 && (!q || !out)) return pc_fail(c, PC_ERR_INVALID_ARG, "decode_step: null q or out");
+    int32_t rc = pc_check_token_batch(c, msg_ids, n_msgs, k, v);
+    if (rc != PC_OK) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    const std::vector<int32_t> ids(msg_ids, msg_ids + std::max(n_msgs, 0));
+    // The tokens can be written by the plan builder's own launch (one launch and one staging copy for the whole step) when
+    // nothing the plan builder reads from the device table changes under it: the new message's length travels with the
+    // call (host side), so what remains is a grown message that some call lists as a PARENT (its length is read from the
+    // table) and a message that needs a further extent (a new table row).  Then the append gets a launch of its own.
+    bool fuse = !c->host_only && n_msgs > 0 && n_calls > 0;
+    if (fuse) {
+        std::vector<char> grows(c->msgs.size(), 0);
+        for (int32_t m : ids) grows[(size_t)m] = 1;
+        for (int i = 0; i < n_calls && fuse; ++i)
+            for (int e = 0; e < calls[i].n_sel && calls[i].sel && fuse; ++e) {
+                const int32_t m = calls[i].sel[e].msg_id;
+                if (m >= 0 && m < (int32_t)grows.size() && grows[(size_t)m]) fuse = false;
+            }
+    }
+    Planned P;
+    if (n_msgs > 0) {
+        rc = pc_append_token_items(c, ids, k, v, st, fuse ? &P.tok_items : nullptr);
+        if (rc != PC_OK) return rc;
+        P.tok_k = k; P.tok_v = v;
+    }
+    auto append_alone = [&]() -> int32_t {               // the tokens are in the host's books: they must reach the cache
+        if (P.tok_items.empty() || P.tok_done) return PC_OK;
+        const int32_t r2 = pc_stage_items(c, P.tok_items.data(), sizeof(PcTokenItem) * P.tok_items.size(), st);
+        if (r2 != PC_OK) return r2;
+        pc_launch_append_tokens(c->cfg.dtype, (const PcTokenItem *)c->tok_dev, (int)P.tok_items.size(), k, v, c->cfg.n_kv_heads, c->D,
+                                c->slots, c->inv_freq_dev, c->k_store, c->v_store, c->table_dev, st);
+        PC_HIP(c, hipGetLastError());
+        P.tok_done = true;
+        return PC_OK;
+    };
+    if (n_calls == 0) return append_alone();
+    rc = attend_impl(c, calls, n_calls, q, out, lse, st, nullptr, 0, &P);
+    if (rc != PC_OK) {                                   // a refused call list: the tokens stay appended, as with the two separate calls
+        const std::string why = c->err;
+        const int32_t r2 = append_alone();
+        c->err = why;
+        return r2 != PC_OK && rc == PC_OK ? r2 : rc;
+    }
+    return PC_OK;
 }
 
 int32_t pc_attend_static(pc_cache *c, const pc_call *calls, int32_t n_calls, const void *q, void *out, float *lse, void *stream)

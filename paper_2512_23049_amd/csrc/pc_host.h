@@ -125,7 +125,7 @@ inline int32_t chain_last(const pc_cache *c, int32_t m)
 
 // layout of the staged (host -> device) block and of the device-built block
 struct PlanLayout {
-    size_t calls, sel, q_pos, row_call, merge_rows, items_dec, items_pre, items_pk, sh_groups, sh_segs, sh_items, sh_pos, kg_items, h2d_bytes;
+    size_t calls, sel, q_pos, row_call, merge_rows, items_dec, items_pre, items_pk, sh_groups, sh_segs, sh_items, sh_pos, kg_items, tok_items, h2d_bytes;
     size_t segs, seg_kvoff, rot_seg, rot_q, tiles, sh_rot, part_o, part_ml, row_scalar, k_gather, v_gather, total;
 };
 
@@ -145,9 +145,15 @@ struct Planned {
     // means the cache's own workspace, which grows on demand.  On return ws is the buffer the plan was staged to.
     void *fixed_ws = nullptr; size_t fixed_cap = 0;
     void *ws = nullptr;
+    // pc_decode_step: tokens the plan builder's launch writes into the cache beside its own work (device k, v rows in
+    // item order); tok_done: that launch was enqueued
+    std::vector<PcTokenItem> tok_items; const void *tok_k = nullptr, *tok_v = nullptr; bool tok_done = false;
 };
 
 // pc_lib.hip
+extern "C" int32_t pc_check_token_batch(pc_cache *c, const int32_t *msg_ids, int32_t n_msgs, const void *k, const void *v);
+extern "C" int32_t pc_append_token_items(pc_cache *c, const std::vector<int32_t> &ids, const void *k, const void *v, hipStream_t st,
+                                         std::vector<PcTokenItem> *defer);
 int32_t pc_ensure_ws(pc_cache *c, size_t bytes, hipStream_t st);
 int32_t pc_stage_acquire(pc_cache *c, size_t bytes, StageSlot **out);
 extern "C" int32_t pc_stage_items(pc_cache *c, const void *items, size_t bytes, hipStream_t st);

@@ -36,10 +36,17 @@ void pc_launch_reposition(int dtype, int len, int n_kv_heads, int D, int64_t slo
 void pc_launch_reposition_batch(int dtype, const PcMoveItem *items, int n_items, int n_kv_heads, int D, int64_t slots,
                                 const double *inv_freq, void *k_store, PcMsgEntry *table, hipStream_t st);
 
+// tok (may be empty): tokens the same launch appends to existing messages (a decode step: one launch for both)
+struct PcTokenWork {
+    const PcTokenItem *items = nullptr; int n = 0;
+    const void *k = nullptr, *v = nullptr;        // [n, H_kv, D] rows in item order
+    void *k_store = nullptr, *v_store = nullptr;
+    int64_t slots = 0; int n_kv_heads = 0, D = 0, dtype = 0;
+};
 void pc_launch_build_plan(const PcCallDesc *calls, int n_calls, const int2 *sel, const int32_t *q_pos,
-                          const PcMsgEntry *table, const double *inv_freq, int half, int total_seg,
+                          PcMsgEntry *table, const double *inv_freq, int half, int total_seg,
                           int total_q, PcSegment *segs, int32_t *seg_kvoff, float2 *rot_seg,
-                          float2 *rot_q, PcTile *tiles, hipStream_t st);
+                          float2 *rot_q, PcTile *tiles, const PcTokenWork &tok, hipStream_t st);
 
 void pc_launch_expand_tables(const PcSegment *segs, const int32_t *seg_kvoff, int n_seg, int64_t n_kv,
                              int32_t *kv_slot, int32_t *kv_pos, hipStream_t st);

@@ -468,13 +468,29 @@ void pc_launch_reposition_batch(int dtype, const PcMoveItem *items, int n_items,
 // every segment start and every query row, in fp64 rounded to fp32 (Sec. 2.4
 // "Position Updates": a lookup table of rotations).
 // ----------------------------------------------------------------------------------
+// Blocks [tok_block0, ...) (a decode step only): the step's new tokens go into the cache in the same launch; the plan
+// blocks never read what they write (the grown messages' new lengths travel with the calls from the host).
 __global__ __launch_bounds__(256) void pc_build_plan_kernel(
     const PcCallDesc *__restrict__ calls, int n_calls, const int2 *__restrict__ sel,
-    const int32_t *__restrict__ q_pos, const PcMsgEntry *__restrict__ table,
+    const int32_t *__restrict__ q_pos, PcMsgEntry *__restrict__ table,
     const double *__restrict__ inv_freq, int half, int total_seg, int total_q,
     PcSegment *__restrict__ segs, int32_t *__restrict__ seg_kvoff,
-    float2 *__restrict__ rot_seg, float2 *__restrict__ rot_q, PcTile *__restrict__ tiles)
+    float2 *__restrict__ rot_seg, float2 *__restrict__ rot_q, PcTile *__restrict__ tiles, PcTokenWork tok, int tok_block0)
 {
+    if ((int)blockIdx.x >= tok_block0) {
+        const int per_row = tok.D / 4;
+        const int64_t tid = (int64_t)((int)blockIdx.x - tok_block0) * 256 + threadIdx.x;
+        if (tid >= (int64_t)tok.n * tok.n_kv_heads * per_row) return;
+        const int j = (int)(tid / ((int64_t)per_row * tok.n_kv_heads));
+        const int hh = (int)((tid / per_row) % tok.n_kv_heads), i0 = 2 * (int)(tid % per_row);
+        if (tok.dtype == 1)
+            append_token_thread<uint16_t>(tok.items[j], j, hh, i0, (const uint16_t *)tok.k, (const uint16_t *)tok.v, tok.n_kv_heads, tok.D,
+                                          tok.slots, inv_freq, (uint16_t *)tok.k_store, (uint16_t *)tok.v_store, table);
+        else
+            append_token_thread<float>(tok.items[j], j, hh, i0, (const float *)tok.k, (const float *)tok.v, tok.n_kv_heads, tok.D,
+                                       tok.slots, inv_freq, (float *)tok.k_store, (float *)tok.v_store, table);
+        return;
+    }
     __shared__ int s_len[256];
     __shared__ int s_tiles[256];
     __shared__ int s_carry[2];
@@ -496,7 +512,8 @@ __global__ __launch_bounds__(256) void pc_build_plan_kernel(
                 if (e < cd.n_sel) { const int2 s = sel[cd.sel_off + e]; m = s.x; p = s.y; }
                 else { m = cd.self_msg; p = cd.self_start; }
                 const PcMsgEntry me = table[m];
-                len = me.len; slot = me.slot_start; pos = p; rot = p - me.base_pos;
+                // (the new message's length comes from the host: a decode step appends its token beside this kernel)
+                len = e < cd.n_sel ? me.len : cd.self_len; slot = me.slot_start; pos = p; rot = p - me.base_pos;
             }
             s_rot[threadIdx.x + 1] = rot;                // s_rot[0]: last segment of the chunk before
             const int tiles = (len + PC_TILE - 1) / PC_TILE;
@@ -592,14 +609,16 @@ __global__ __launch_bounds__(256) void pc_build_plan_kernel(
 }
 
 void pc_launch_build_plan(const PcCallDesc *calls, int n_calls, const int2 *sel, const int32_t *q_pos,
-                          const PcMsgEntry *table, const double *inv_freq, int half, int total_seg,
+                          PcMsgEntry *table, const double *inv_freq, int half, int total_seg,
                           int total_q, PcSegment *segs, int32_t *seg_kvoff, float2 *rot_seg,
-                          float2 *rot_q, PcTile *tiles, hipStream_t st)
+                          float2 *rot_q, PcTile *tiles, const PcTokenWork &tok, hipStream_t st)
 {
     const int64_t n_rot = ((int64_t)total_seg + total_q) * half;
-    const unsigned grid = (unsigned)(n_calls + (n_rot + 255) / 256);
+    const unsigned plan_blocks = (unsigned)(n_calls + (n_rot + 255) / 256);
+    const int64_t tok_threads = (int64_t)tok.n * tok.n_kv_heads * (tok.D / 4);
+    const unsigned grid = plan_blocks + (unsigned)((tok_threads + 255) / 256);
     pc_build_plan_kernel<<<grid, 256, 0, st>>>(calls, n_calls, sel, q_pos, table, inv_freq, half, total_seg,
-                                               total_q, segs, seg_kvoff, rot_seg, rot_q, tiles);
+                                               total_q, segs, seg_kvoff, rot_seg, rot_q, tiles, tok, (int)plan_blocks);
 }
 
 // ----------------------------------------------------------------------------------

@@ -299,8 +299,13 @@ int32_t pc_append_messages(pc_cache *c, int32_t n, const void *const *k, const v
 // shared by pc_append_tokens and pc_append_tokens_batch: token j of k, v goes to message ids[j]
 // (the tokens of one message are consecutive and in order, no message has two runs; validated by
 // the callers).  Host work is proportional to the tokens, not to the messages the cache holds.
-static int32_t append_token_items(pc_cache *c, const std::vector<int32_t> &ids, const void *k, const void *v, hipStream_t st)
+// defer: if given and the tokens need no new table row (no further extent), nothing is launched: the items are handed
+// back for the caller to write them with a kernel of its own (the decode step's plan builder); the host bookkeeping is
+// done either way.  An empty *defer on return means the append was enqueued here.
+int32_t pc_append_token_items(pc_cache *c, const std::vector<int32_t> &ids, const void *k, const void *v, hipStream_t st,
+                              std::vector<PcTokenItem> *defer)
 {
+    if (defer) defer->clear();
     const int n = (int)ids.size();
     std::vector<PcTokenItem> items((size_t)n);
     std::vector<HostMsg> fresh;                              // new extent records: ids msgs.size(), msgs.size() + 1, ...
@@ -351,7 +356,9 @@ static int32_t append_token_items(pc_cache *c, const std::vector<int32_t> &ids, 
         }
         close_extent(run_end);
     }
-    if (!c->host_only) {
+    if (!c->host_only && defer && fresh.empty()) {
+        defer->swap(items);
+    } else if (!c->host_only) {
         for (const HostMsg &rec : fresh) clear_if_reused(c, rec.slot_start, rec.reserve, st);
         if (!fresh.empty()) {                                // the device table learns the new extents (length 0 until the kernel sets it)
             StageSlot *slot = nullptr;
@@ -396,12 +403,11 @@ int32_t pc_append_tokens(pc_cache *c, int32_t msg_id, const void *k, const void 
     if (!known(c, msg_id)) return pc_fail(c, PC_ERR_BAD_MSG_ID, "append_tokens: unknown message %d", msg_id);
     if (n < 1) return pc_fail(c, PC_ERR_INVALID_ARG, "append_tokens: n = %d must be >= 1", n);
     if (!c->host_only && (!k || !v)) return pc_fail(c, PC_ERR_INVALID_ARG, "append_tokens: null k or v");
-    return append_token_items(c, std::vector<int32_t>((size_t)n, msg_id), k, v, (hipStream_t)stream);
+    return pc_append_token_items(c, std::vector<int32_t>((size_t)n, msg_id), k, v, (hipStream_t)stream, nullptr);
 }
 
-int32_t pc_append_tokens_batch(pc_cache *c, const int32_t *msg_ids, int32_t n_msgs, const void *k, const void *v, void *stream)
+int32_t pc_check_token_batch(pc_cache *c, const int32_t *msg_ids, int32_t n_msgs, const void *k, const void *v)
 {
-    if (!c) return PC_ERR_INVALID_ARG;
     if (n_msgs < 0 || (n_msgs > 0 && !msg_ids)) return pc_fail(c, PC_ERR_INVALID_ARG, "append_tokens_batch: bad id list");
     if (n_msgs == 0) return PC_OK;
     if (!c->host_only && (!k || !v)) return pc_fail(c, PC_ERR_INVALID_ARG, "append_tokens_batch: null k or v");
@@ -411,7 +417,15 @@ int32_t pc_append_tokens_batch(pc_cache *c, const int32_t *msg_ids, int32_t n_ms
     std::sort(sorted.begin(), sorted.end());
     const auto twice = std::adjacent_find(sorted.begin(), sorted.end());
     if (twice != sorted.end()) return pc_fail(c, PC_ERR_INVALID_ARG, "append_tokens_batch: message %d listed twice", *twice);
-    return append_token_items(c, std::vector<int32_t>(msg_ids, msg_ids + n_msgs), k, v, (hipStream_t)stream);
+    return PC_OK;
+}
+
+int32_t pc_append_tokens_batch(pc_cache *c, const int32_t *msg_ids, int32_t n_msgs, const void *k, const void *v, void *stream)
+{
+    if (!c) return PC_ERR_INVALID_ARG;
+    const int32_t rc = pc_check_token_batch(c, msg_ids, n_msgs, k, v);
+    if (rc != PC_OK || n_msgs == 0) return rc;
+    return pc_append_token_items(c, std::vector<int32_t>(msg_ids, msg_ids + n_msgs), k, v, (hipStream_t)stream, nullptr);
 }
 
 int32_t pc_message_info(pc_cache *c, int32_t msg_id, int32_t *len, int64_t *slot_start, int32_t *reserved)

@@ -80,7 +80,7 @@ int32_t pc_resolve(pc_cache *c, const pc_call *call, int idx, Resolved &out)
 PlanLayout make_layout(int n_calls, int total_sel, int total_q, int total_seg, int n_dec, int n_pre, int n_pre_pk,
                        int64_t part_rows, int64_t total_tiles, int H_q, int D,
                        size_t n_sh_groups = 0, size_t n_sh_segs = 0, size_t n_sh_items = 0, size_t n_sh_pos = 0,
-                       size_t n_kg_items = 0, int64_t kg_tiles = 0, int H_kv = 1)
+                       size_t n_kg_items = 0, int64_t kg_tiles = 0, int H_kv = 1, size_t n_tok = 0)
 {
     PlanLayout L{};
     size_t o = 0;
@@ -98,6 +98,7 @@ PlanLayout make_layout(int n_calls, int total_sel, int total_q, int total_seg, i
     L.sh_items = take(sizeof(PcShItem) * std::max<size_t>(n_sh_items, 1));
     L.sh_pos = take(sizeof(int32_t) * std::max<size_t>(n_sh_pos, 1));
     L.kg_items = take(sizeof(PcGatherItem) * std::max<size_t>(n_kg_items, 1));
+    L.tok_items = take(sizeof(PcTokenItem) * std::max<size_t>(n_tok, 1));
     L.h2d_bytes = o;
     L.segs = take(sizeof(PcSegment) * (size_t)std::max(total_seg, 1));
     L.seg_kvoff = take(sizeof(int32_t) * (size_t)std::max(total_seg, 1));
@@ -401,7 +402,7 @@ int32_t pc_plan_and_stage(pc_cache *c, const pc_call *calls, int32_t n_calls, bo
     if (total_tiles > INT32_MAX / 2) return pc_fail(c, PC_ERR_SHAPE, "attend: too many KV tiles");
     if (sp.pos.size() > (size_t)INT32_MAX / 2) return pc_fail(c, PC_ERR_SHAPE, "attend: shared decode table too large");
     P.lay = make_layout(n_calls, P.total_sel, P.total_q, P.total_seg, P.n_dec, P.n_pre, P.n_pre_pk, part_rows, total_tiles, c->cfg.n_q_heads, c->D,
-                        sp.groups.size(), sp.segs.size(), sp.items.size(), sp.pos.size(), kg.size(), kg_tiles, H_kv);
+                        sp.groups.size(), sp.segs.size(), sp.items.size(), sp.pos.size(), kg.size(), kg_tiles, H_kv, P.tok_items.size());
     if (c->host_only) return PC_OK;
 
     int32_t rc = PC_OK;
@@ -448,6 +449,7 @@ int32_t pc_plan_and_stage(pc_cache *c, const pc_call *calls, int32_t n_calls, bo
     if (!pre.empty()) std::memcpy(h + P.lay.items_pre, pre.data(), sizeof(PcItem) * pre.size());
     if (!pre_pk.empty()) std::memcpy(h + P.lay.items_pk, pre_pk.data(), sizeof(PcItem) * pre_pk.size());
     if (!kg.empty()) std::memcpy(h + P.lay.kg_items, kg.data(), sizeof(PcGatherItem) * kg.size());
+    if (!P.tok_items.empty()) std::memcpy(h + P.lay.tok_items, P.tok_items.data(), sizeof(PcTokenItem) * P.tok_items.size());
     if (!sp.items.empty()) {
         std::memcpy(h + P.lay.sh_groups, sp.groups.data(), sizeof(PcShGroup) * sp.groups.size());
         std::memcpy(h + P.lay.sh_segs, sp.segs.data(), sizeof(PcShSeg) * sp.segs.size());
@@ -460,11 +462,18 @@ int32_t pc_plan_and_stage(pc_cache *c, const pc_call *calls, int32_t n_calls, bo
     {
         ProfScope ps(c, 1, st);
         char *w = (char *)P.ws;
+        PcTokenWork tok;
+        if (!P.tok_items.empty()) {
+            tok.items = (const PcTokenItem *)(w + P.lay.tok_items); tok.n = (int)P.tok_items.size();
+            tok.k = P.tok_k; tok.v = P.tok_v; tok.k_store = c->k_store; tok.v_store = c->v_store;
+            tok.slots = c->slots; tok.n_kv_heads = c->cfg.n_kv_heads; tok.D = c->D; tok.dtype = c->cfg.dtype;
+        }
         pc_launch_build_plan((const PcCallDesc *)(w + P.lay.calls), n_calls, (const int2 *)(w + P.lay.sel),
                              (const int32_t *)(w + P.lay.q_pos), c->table_dev, c->inv_freq_dev, c->half, P.total_seg,
                              P.total_q, (PcSegment *)(w + P.lay.segs), (int32_t *)(w + P.lay.seg_kvoff),
-                             (float2 *)(w + P.lay.rot_seg), (float2 *)(w + P.lay.rot_q), (PcTile *)(w + P.lay.tiles), st);
+                             (float2 *)(w + P.lay.rot_seg), (float2 *)(w + P.lay.rot_q), (PcTile *)(w + P.lay.tiles), tok, st);
         PC_HIP(c, hipGetLastError());
+        P.tok_done = !P.tok_items.empty();
         if (P.n_sh_items > 0) {
             pc_launch_shared_rot((const int32_t *)(w + P.lay.sh_pos), (int64_t)P.n_sh_pos, c->inv_freq_dev, c->half,
                                  (float2 *)(w + P.lay.sh_rot), st);

@@ -45,11 +45,14 @@ class DeviceWorkload:
                 lse = torch.empty(q.shape[:2], dtype=torch.float32, device=device)
                 self.steps.append(("attend", e.calls, marshal_calls(e.calls), q, out, lse))
 
-    def run(self, cache: Cache, stream: int = 0, want_lse: bool = True, batch_appends: bool = False):
+    def run(self, cache: Cache, stream: int = 0, want_lse: bool = True, batch_appends: bool = False,
+            fused_steps: bool = False):
         """One pass over all events; returns the list of (out, lse) of the attend events.
-        batch_appends: consecutive append events go through one pc_append_messages call."""
+        batch_appends: consecutive append events go through one pc_append_messages call.
+        fused_steps: an extend event followed by an attend event goes through one pc_decode_step call."""
         res = []
         pending = []
+        held = None                                       # an extend step waiting for its attend
 
         def flush():
             if pending:
@@ -57,6 +60,9 @@ class DeviceWorkload:
                                       [p[3] for p in pending], [p[4] for p in pending], stream)
                 pending.clear()
         for s in self.steps:
+            if s[0] == "append" and held is not None:
+                cache.append_tokens_batch(held[3], held[1].data_ptr(), held[2].data_ptr(), stream)
+                held = None
             if s[0] == "append" and batch_appends:
                 pending.append(s)
                 continue
@@ -64,12 +70,25 @@ class DeviceWorkload:
             if s[0] == "append":
                 cache.append_message(s[1].data_ptr(), s[2].data_ptr(), s[3], s[4], stream)
             elif s[0] == "extend":
-                cache.append_tokens_batch(s[3], s[1].data_ptr(), s[2].data_ptr(), stream)
+                if held is not None:
+                    cache.append_tokens_batch(held[3], held[1].data_ptr(), held[2].data_ptr(), stream)
+                    held = None
+                if fused_steps:
+                    held = s
+                else:
+                    cache.append_tokens_batch(s[3], s[1].data_ptr(), s[2].data_ptr(), stream)
             else:
                 _, calls, m, q, out, lse = s
-                cache.attend(calls, q.data_ptr(), out.data_ptr(), lse.data_ptr() if want_lse else 0, stream, m)
+                if held is not None:
+                    cache.decode_step(held[3], held[1].data_ptr(), held[2].data_ptr(), calls, q.data_ptr(), out.data_ptr(),
+                                      lse.data_ptr() if want_lse else 0, stream, m)
+                    held = None
+                else:
+                    cache.attend(calls, q.data_ptr(), out.data_ptr(), lse.data_ptr() if want_lse else 0, stream, m)
                 res.append((out, lse))
         flush()
+        if held is not None:
+            cache.append_tokens_batch(held[3], held[1].data_ptr(), held[2].data_ptr(), stream)
         return res
 
     def run_attends_only(self, cache: Cache, stream: int = 0, want_lse: bool = False):

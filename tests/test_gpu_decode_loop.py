@@ -29,11 +29,14 @@ def hip():
     return harness
 
 
-def run_and_compare(hip, w):
+def run_and_compare(hip, w, fused_steps=False, sharing=None, flags=0):
     import torch
-    cache = hip.make_cache(w)
+    cache = hip.make_cache(w, slack_tokens=2048 if flags else 0, extra_messages=64 if flags else 0,
+                           **({"flags": flags} if flags else {}))
+    if sharing is not None:
+        cache.set_decode_sharing(sharing)
     dw = hip.DeviceWorkload(w)
-    res = dw.run(cache)
+    res = dw.run(cache, fused_steps=fused_steps)
     torch.cuda.synchronize()
     tol = TOL[w.dtype]
     for k, (ei, ev) in enumerate(attend_events(w)):
@@ -65,6 +68,72 @@ def test_tail_crossing_tile_and_group_boundaries(hip):
     w = gen.decode_loop(seed=62, n_calls=3, n_steps=7, sys_len=40, n_pool=4, len_lo=10, len_hi=40, n_sel=2,
                         tail0=29, n_q_heads=8, n_kv_heads=2)
     run_and_compare(hip, w)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_decode_steps_in_one_call(hip, dtype):
+    """pc_decode_step (token append and attention of a parallel decode step in one call, the append running beside
+    the plan builder) against the oracle at every step: plain tails, tails crossing tile and group boundaries, the
+    shared walk, and tails that grow into further extents (which makes the step fall back to one after the other)."""
+    from paper_2512_23049_amd import PC_FLAG_GROW_EXTENTS
+    kw = dict(n_q_heads=4, n_kv_heads=2, head_dim=64) if dtype == "f32" else dict(n_q_heads=8, n_kv_heads=2)
+    w = gen.decode_loop(seed=61, n_calls=6, n_steps=5, sys_len=70, n_pool=10, len_lo=5, len_hi=90, n_sel=3,
+                        tail0=3, dtype=dtype, **kw)
+    run_and_compare(hip, w, fused_steps=True)
+    w = gen.decode_loop(seed=62, n_calls=3, n_steps=7, sys_len=40, n_pool=4, len_lo=10, len_hi=40, n_sel=2,
+                        tail0=29, dtype=dtype, **kw)
+    run_and_compare(hip, w, fused_steps=True)
+    if dtype == "bf16":
+        run_and_compare(hip, w, fused_steps=True, sharing=2)
+    # reserves of one tile: the tails (29 tokens at first) outgrow them in the fourth step
+    w = gen.decode_loop(seed=65, n_calls=4, n_steps=9, sys_len=40, n_pool=4, len_lo=10, len_hi=40, n_sel=2,
+                        tail0=29, dtype=dtype, **kw)
+    for e in w.events:
+        if e.kind == "append" and e.reserve > e.k.shape[0]:
+            e.reserve = 32
+    run_and_compare(hip, w, fused_steps=True, flags=PC_FLAG_GROW_EXTENTS)
+
+
+def test_decode_step_with_a_grown_message_listed_as_a_parent(hip):
+    """A step in which one call lists another call's growing tail as a parent: the parent's length is read from the
+    device table, so the append has to come first; the result must see the new token."""
+    import torch
+    from oracle import choreo_oracle as orc
+    from paper_2512_23049_amd.binding import PC_BF16, Cache
+    rng = np.random.default_rng(66)
+    H_q, H_kv, D = 8, 2, 128
+
+    def rnd(*shape):
+        return gen.round_to_bf16(rng.standard_normal(shape).astype(np.float32))
+    cache = Cache(H_q, H_kv, D, PC_BF16, 10000.0, 1024, 16)
+    ks = [rnd(40, H_kv, D), rnd(5, H_kv, D), rnd(9, H_kv, D)]
+    vs = [rnd(40, H_kv, D), rnd(5, H_kv, D), rnd(9, H_kv, D)]
+    keep = []
+    for k, v in zip(ks, vs):
+        kd, vd = hip.to_device(k, "bf16"), hip.to_device(v, "bf16")
+        keep += [kd, vd]
+        cache.append_message(kd.data_ptr(), vd.data_ptr(), k.shape[0], 64)
+    for step in range(3):
+        k1, v1 = rnd(2, H_kv, D), rnd(2, H_kv, D)
+        kd, vd = hip.to_device(k1, "bf16"), hip.to_device(v1, "bf16")
+        keep += [kd, vd]
+        calls = [Call([(0, 0), (2, 60)], 1, 100, 1, None),          # lists message 2, which grows in this very step
+                 Call([(0, 0)], 2, 50, 1, None)]
+        q = rnd(2, H_q, D)
+        qd = hip.to_device(q, "bf16")
+        out = torch.empty_like(qd)
+        lse = torch.empty((2, H_q), dtype=torch.float32, device="cuda:0")
+        cache.decode_step([1, 2], kd.data_ptr(), vd.data_ptr(), calls, qd.data_ptr(), out.data_ptr(), lse.data_ptr())
+        torch.cuda.synchronize()
+        ks[1] = np.concatenate([ks[1], k1[0:1]]); vs[1] = np.concatenate([vs[1], v1[0:1]])
+        ks[2] = np.concatenate([ks[2], k1[1:2]]); vs[2] = np.concatenate([vs[2], v1[1:2]])
+        for r, c in enumerate(calls):
+            o, l = orc.attend_call(ks, vs, c.sel, c.self_msg, c.self_start, 1, None, q[r:r + 1], 10000.0)
+            d = np.abs(out[r:r + 1].float().cpu().numpy() - o)
+            say(f"  step {step} call {r}: max_abs={d.max():.3e}")
+            assert d.max() <= 2e-2 and d.mean() <= 1e-3
+            assert np.abs(lse[r:r + 1].cpu().numpy() - l).max() <= 2e-2
+    cache.close()
 
 
 def test_chunked_prefill_with_append_tokens(hip):
