@@ -648,6 +648,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--skip-extras", action="store_true")
     ap.add_argument("--skip-cpu", action="store_true")
+    ap.add_argument("--no-headline", action="store_true",
+                    help="run only the sections --only names (profiling runs: one workload per process); the JSON line "
+                         "then holds those sections alone")
     ap.add_argument("--only", default="", help="comma list of sections: achievable,prefill,decode,longdecode,rounds,baseline,loop,reposition,backward")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="also launch one plain device copy of this many MiB (reference for scaling rocprofv3 "
@@ -672,7 +675,10 @@ def main():
         del src, dst
 
     cx = Ctx(args, torch, gen, harness)
-    section_headline(cx)
+    if args.no_headline:
+        cx.line = {"note": "sections only (--no-headline)", "roofline": {"achieved": None}, "roofline_decode": {"achieved": None}}
+    else:
+        section_headline(cx)
     if not args.skip_extras:
         for name, section in SECTIONS:
             if not only or name in only:
