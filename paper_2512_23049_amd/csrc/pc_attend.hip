@@ -42,6 +42,7 @@ static int32_t attend_impl(pc_cache *c, const pc_call *calls, int32_t n_calls, c
     L.segs = (const PcSegment *)(w + P.lay.segs);
     L.rot_seg = (const float2 *)(w + P.lay.rot_seg);
     L.rot_q = (const float2 *)(w + P.lay.rot_q);
+    L.rot_qw = (const float2 *)(w + P.lay.rot_qw);
     L.tiles = (const PcTile *)(w + P.lay.tiles);
     L.k_store = c->k_store; L.v_store = c->v_store; L.q = q; L.out = out; L.lse = lse;
     L.part_o = (uint16_t *)(w + P.lay.part_o); L.part_ml = (float *)(w + P.lay.part_ml);
@@ -209,6 +210,7 @@ int32_t pc_attend_backward(pc_cache *c, const pc_call *calls, int32_t n_calls, c
     L.segs = (const PcSegment *)(w + P.lay.segs);
     L.rot_seg = (const float2 *)(w + P.lay.rot_seg);
     L.rot_q = (const float2 *)(w + P.lay.rot_q);
+    L.rot_qw = (const float2 *)(w + P.lay.rot_qw);
     L.k_store = c->k_store; L.v_store = c->v_store; L.q = q;
     L.slots = c->slots; L.n_q_heads = c->cfg.n_q_heads; L.n_kv_heads = c->cfg.n_kv_heads;
     L.scale_log2 = c->scale * 1.4426950408889634f;

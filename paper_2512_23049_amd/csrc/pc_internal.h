@@ -162,6 +162,9 @@ struct PcLaunch {
     const PcSegment  *segs;
     const float2     *rot_seg;    // [total_seg][D/2] (cos, sin)((pos_start - stored base) * theta_i)
     const float2     *rot_q;      // [total_q][D/2]   (cos, sin)(q_pos * theta_i)
+    const float2     *rot_qw;     // the same values laid out for the bf16 prefill kernel's lanes (D = 128 only, else null):
+                                  // pair 16 ks + 8 hh + 2 jq + e of row R at float2 index
+                                  // ((R / 32 * 1024 + ks * 256 + jq * 64 + hh * 32 + R % 32) * 2 + e
     const PcItem     *items;
     const PcTile     *tiles;      // [total tiles] per-call tile tables
     const void       *k_store;    // [H_kv][slots][D]            K turned to its in-message index

@@ -46,7 +46,7 @@ struct PcTokenWork {
 void pc_launch_build_plan(const PcCallDesc *calls, int n_calls, const int2 *sel, const int32_t *q_pos,
                           PcMsgEntry *table, const double *inv_freq, int half, int total_seg,
                           int total_q, PcSegment *segs, int32_t *seg_kvoff, float2 *rot_seg,
-                          float2 *rot_q, PcTile *tiles, const PcTokenWork &tok, hipStream_t st);
+                          float2 *rot_q, float2 *rot_qw, PcTile *tiles, const PcTokenWork &tok, hipStream_t st);
 
 void pc_launch_expand_tables(const PcSegment *segs, const int32_t *seg_kvoff, int n_seg, int64_t n_kv,
                              int32_t *kv_slot, int32_t *kv_pos, hipStream_t st);

@@ -475,7 +475,7 @@ __global__ __launch_bounds__(256) void pc_build_plan_kernel(
     const int32_t *__restrict__ q_pos, PcMsgEntry *__restrict__ table,
     const double *__restrict__ inv_freq, int half, int total_seg, int total_q,
     PcSegment *__restrict__ segs, int32_t *__restrict__ seg_kvoff,
-    float2 *__restrict__ rot_seg, float2 *__restrict__ rot_q, PcTile *__restrict__ tiles, PcTokenWork tok, int tok_block0)
+    float2 *__restrict__ rot_seg, float2 *__restrict__ rot_q, float2 *__restrict__ rot_qw, PcTile *__restrict__ tiles, PcTokenWork tok, int tok_block0)
 {
     if ((int)blockIdx.x >= tok_block0) {
         const int per_row = tok.D / 4;
@@ -605,20 +605,25 @@ __global__ __launch_bounds__(256) void pc_build_plan_kernel(
     sincos((double)pos * inv_freq[i], &s, &c);
     const float2 r = make_float2((float)c, (float)s);
     if (ent < total_seg) rot_seg[(int64_t)ent * half + i] = r;
-    else rot_q[(int64_t)(ent - total_seg) * half + i] = r;
+    else {
+        const int R = ent - total_seg;
+        rot_q[(int64_t)R * half + i] = r;
+        // the copy the bf16 prefill kernel reads: 16 bytes per lane, the lanes of consecutive rows side by side
+        if (rot_qw) rot_qw[((int64_t)(R >> 5) * 1024 + (i >> 4) * 256 + ((i >> 1) & 3) * 64 + ((i >> 3) & 1) * 32 + (R & 31)) * 2 + (i & 1)] = r;
+    }
 }
 
 void pc_launch_build_plan(const PcCallDesc *calls, int n_calls, const int2 *sel, const int32_t *q_pos,
                           PcMsgEntry *table, const double *inv_freq, int half, int total_seg,
                           int total_q, PcSegment *segs, int32_t *seg_kvoff, float2 *rot_seg,
-                          float2 *rot_q, PcTile *tiles, const PcTokenWork &tok, hipStream_t st)
+                          float2 *rot_q, float2 *rot_qw, PcTile *tiles, const PcTokenWork &tok, hipStream_t st)
 {
     const int64_t n_rot = ((int64_t)total_seg + total_q) * half;
     const unsigned plan_blocks = (unsigned)(n_calls + (n_rot + 255) / 256);
     const int64_t tok_threads = (int64_t)tok.n * tok.n_kv_heads * (tok.D / 4);
     const unsigned grid = plan_blocks + (unsigned)((tok_threads + 255) / 256);
     pc_build_plan_kernel<<<grid, 256, 0, st>>>(calls, n_calls, sel, q_pos, table, inv_freq, half, total_seg,
-                                               total_q, segs, seg_kvoff, rot_seg, rot_q, tiles, tok, (int)plan_blocks);
+                                               total_q, segs, seg_kvoff, rot_seg, rot_q, rot_qw, tiles, tok, (int)plan_blocks);
 }
 
 // ----------------------------------------------------------------------------------

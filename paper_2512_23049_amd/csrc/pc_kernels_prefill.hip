@@ -148,22 +148,52 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
             qop[ks + 4] = __builtin_bit_cast(bf16x8, make_uint4(pack_bf16(yy[0], yy[1]), pack_bf16(yy[2], yy[3]), pack_bf16(yy[4], yy[5]), pack_bf16(yy[6], yy[7])));
         }
     };
-    auto load_query = [&]() __attribute__((always_inline)) {
-        const uint16_t *qp = (const uint16_t *)L.q + ((int64_t)Rg * L.n_q_heads + h) * PC_D + 8 * hh;
-        const float2 *rq = L.rot_q + (int64_t)Rg * (PC_D / 2) + 8 * hh;
+    // In-place walk: the wave's 32 query rows of its head (256 bytes each) arrive by direct loads in the wave's part of
+    // s_qm, which is free until the master copy is written: instruction i brings rows 4 i .. 4 i + 3, sixteen lanes to a
+    // row, whole cache lines (a lane fetching its own row's pieces touches 32 lines per instruction instead of 8).
+    // Chunk c of row r lands at position c ^ (r & 15) of the row, so that the 16 lanes that later read one chunk
+    // index of 16 different rows hit different banks.  The rotation rows come from the copy of the table that is laid
+    // out for this access (rot_qw: 16 bytes per lane, lanes of consecutive rows side by side).
+    float4 rqw[4][4];
+    const unsigned lds_q = (unsigned)(size_t)&s_qm[0][0][0] + __builtin_amdgcn_readfirstlane(wave) * 8192u;
+    auto request_query = [&]() __attribute__((always_inline)) {
+        const int ub_u = __builtin_amdgcn_readfirstlane(ub), h_u = __builtin_amdgcn_readfirstlane(h);
+        const unsigned char *qb = (const unsigned char *)L.q + ((int64_t)(cd.q_off + 32 * ub_u) * L.n_q_heads + h_u) * (PC_D * 2);
+        const int r4 = lane >> 4, c = lane & 15;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int r = 4 * i + r4;
+            const int src = (unit_ok && 32 * ub_u + r < cd.n_q) ? r : 0;          // rows past the call's end: any valid row
+            dma16(qb, (unsigned)(src * L.n_q_heads * (PC_D * 2) + ((c ^ (r & 15)) << 4)), lds_q + i * 1024);
+        }
+        const float4 *rw = reinterpret_cast<const float4 *>(L.rot_qw) + ((int64_t)(Rg >> 5) * 32 + hh) * 32 + (Rg & 31);
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+            for (int jq = 0; jq < 4; ++jq) rqw[ks][jq] = rw[(ks * 4 + jq) * 64];
+    };
+    // ... once they have landed (the caller has waited): into the fp32 master, turned by the row's own position and scaled
+    auto finish_query = [&]() __attribute__((always_inline)) {
         const float sc = row_ok ? L.scale_log2 : 0.f;
+        const unsigned char *ql = reinterpret_cast<const unsigned char *>(&s_qm[wave][0][0]) + n * 256;
+        uint4 lo[4], hi[4];
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
-            uint4 lo = ldg16(qp + 16 * ks), hi = ldg16(qp + 16 * ks + 64);
-            const uint32_t lw[4] = {lo.x, lo.y, lo.z, lo.w}, hw[4] = {hi.x, hi.y, hi.z, hi.w};
+            lo[ks] = *reinterpret_cast<const uint4 *>(ql + (((2 * ks + hh) ^ (n & 15)) << 4));
+            hi[ks] = *reinterpret_cast<const uint4 *>(ql + (((2 * ks + hh + 8) ^ (n & 15)) << 4));
+        }
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            const uint32_t lw[4] = {lo[ks].x, lo[ks].y, lo[ks].z, lo[ks].w}, hw[4] = {hi[ks].x, hi[ks].y, hi[ks].z, hi[ks].w};
             float yy[8];
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
                 const float x = ((j & 1) ? bf_hi(lw[j >> 1]) : bf_lo(lw[j >> 1])) * sc;
                 const float y = ((j & 1) ? bf_hi(hw[j >> 1]) : bf_lo(hw[j >> 1])) * sc;
-                const float2 cs = rq[16 * ks + j];
-                qm[ks][j] = x * cs.x - y * cs.y;
-                yy[j] = x * cs.y + y * cs.x;
+                const float4 t = rqw[ks][j >> 1];
+                const float cs_x = (j & 1) ? t.z : t.x, cs_y = (j & 1) ? t.w : t.y;
+                qm[ks][j] = x * cs_x - y * cs_y;
+                yy[j] = x * cs_y + y * cs_x;
             }
             s_qm[wave][2 * ks][lane] = make_float4(yy[0], yy[1], yy[2], yy[3]);
             s_qm[wave][2 * ks + 1][lane] = make_float4(yy[4], yy[5], yy[6], yy[7]);
@@ -470,12 +500,14 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
         Desc d4 = describe(min(tile0 + 4, last));
         Desc d5 = describe(min(tile0 + 5, last));
         dma_k(d0, 0); dma_v(d0, 0);
+        if constexpr (!PACKED) request_query();          // right behind the first tile: requests come back in order
         dma_k(d1, 1); dma_v(d1, 1);
         dma_k(d2, 2); dma_v(d2, 2);
         dma_k(d3, 3); dma_v(d3, 3);
         dma_k(d4, 4);
-        if constexpr (PACKED) load_query_direct(); else load_query();
-        __builtin_amdgcn_s_waitcnt(0x0F70);              // vmcnt(0)
+        if constexpr (PACKED) load_query_direct();
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        if constexpr (!PACKED) finish_query();
         __syncthreads();
 
         // tile 0: scores and softmax part 1, nothing to overlap with yet; leaves the K fragments
@@ -636,42 +668,42 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
         }
     }
 
-    // epilogue: a lane holds, for its row, dims 32*db + 8*(r/4) + 4*hh + (r%4)
+    // epilogue: a lane holds, for its row, dims 32*db + 8*(r/4) + 4*hh + (r%4).  The 2-byte results (bf16 outputs, or
+    // fp16 partials of a split) are turned round in the wave's part of s_qm so that a row's 256 bytes leave as whole cache
+    // lines: 16 lanes per row, 4 rows per store (written straight from the accumulators a store would touch 32 lines
+    // with 16 bytes each).  Chunk c (16 bytes) of row r sits at position c ^ (r & 15).
     const float l = sum_across_halves(l_run);
-    if (!row_ok) return;
-    if (cd.n_splits == 1) {
-        const float inv = l > 0.f ? 1.f / l : 0.f;
-        uint16_t *o = (uint16_t *)L.out + ((int64_t)Rg * L.n_q_heads + h) * PC_D;
+    const float inv = l > 0.f ? 1.f / l : 0.f;
+    const bool whole = cd.n_splits == 1;
+    {
+        unsigned char *stg = reinterpret_cast<unsigned char *>(&s_qm[wave][0][0]);
 #pragma unroll
         for (int db = 0; db < 4; ++db)
 #pragma unroll
             for (int q4 = 0; q4 < 4; ++q4) {
-                const int d = 32 * db + 8 * q4 + 4 * hh;
+                const float a0 = acc[db][4 * q4] * inv, a1 = acc[db][4 * q4 + 1] * inv, a2 = acc[db][4 * q4 + 2] * inv, a3 = acc[db][4 * q4 + 3] * inv;
                 uint2 w;
-                w.x = pack_bf16(acc[db][4 * q4] * inv, acc[db][4 * q4 + 1] * inv);
-                w.y = pack_bf16(acc[db][4 * q4 + 2] * inv, acc[db][4 * q4 + 3] * inv);
-                *reinterpret_cast<uint2 *>(o + d) = w;
+                w.x = whole ? pack_bf16(a0, a1) : pack_f16(a0, a1);
+                w.y = whole ? pack_bf16(a2, a3) : pack_f16(a2, a3);
+                *reinterpret_cast<uint2 *>(stg + n * 256 + (((4 * db + q4) ^ (n & 15)) << 4) + 8 * hh) = w;
             }
-        if (L.lse && hh == 0)
-            L.lse[(int64_t)Rg * L.n_q_heads + h] = (l > 0.f) ? (m_ref + log2f(l)) * 0.6931471805599453f : -INFINITY;
+        const int64_t row0 = whole ? (int64_t)cd.q_off : (int64_t)cd.part_off + (int64_t)item.split * cd.n_q;
+        unsigned char *dst = reinterpret_cast<unsigned char *>(whole ? (uint16_t *)L.out : L.part_o) + ((row0 * L.n_q_heads + h) * PC_D) * 2;
+        const int r4 = lane >> 4, c = lane & 15;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int r = 4 * i + r4, rw = 32 * ub + r;
+            const uint4 v = *reinterpret_cast<const uint4 *>(stg + r * 256 + ((c ^ (r & 15)) << 4));
+            if (unit_ok && rw < cd.n_q) *reinterpret_cast<uint4 *>(dst + (int64_t)rw * L.n_q_heads * (PC_D * 2) + 16 * c) = v;
+        }
+    }
+    if (!row_ok || hh != 0) return;
+    if (whole) {
+        if (L.lse) L.lse[(int64_t)Rg * L.n_q_heads + h] = (l > 0.f) ? (m_ref + log2f(l)) * 0.6931471805599453f : -INFINITY;
     } else {
         const int64_t pr = (int64_t)cd.part_off + (int64_t)item.split * cd.n_q + row;
-        uint16_t *o = L.part_o + (pr * L.n_q_heads + h) * PC_D;
-        const float inv = l > 0.f ? 1.f / l : 0.f;
-#pragma unroll
-        for (int db = 0; db < 4; ++db)
-#pragma unroll
-            for (int q4 = 0; q4 < 4; ++q4) {
-                const int d = 32 * db + 8 * q4 + 4 * hh;
-                uint2 w;
-                w.x = pack_f16(acc[db][4 * q4] * inv, acc[db][4 * q4 + 1] * inv);
-                w.y = pack_f16(acc[db][4 * q4 + 2] * inv, acc[db][4 * q4 + 3] * inv);
-                *reinterpret_cast<uint2 *>(o + d) = w;
-            }
-        if (hh == 0) {
-            L.part_ml[(pr * L.n_q_heads + h) * 2] = (l > 0.f) ? m_ref : -INFINITY;
-            L.part_ml[(pr * L.n_q_heads + h) * 2 + 1] = l;
-        }
+        L.part_ml[(pr * L.n_q_heads + h) * 2] = (l > 0.f) ? m_ref : -INFINITY;
+        L.part_ml[(pr * L.n_q_heads + h) * 2 + 1] = l;
     }
 }
 

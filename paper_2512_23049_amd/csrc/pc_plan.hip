@@ -104,6 +104,7 @@ PlanLayout make_layout(int n_calls, int total_sel, int total_q, int total_seg, i
     L.seg_kvoff = take(sizeof(int32_t) * (size_t)std::max(total_seg, 1));
     L.rot_seg = take(sizeof(float2) * (size_t)std::max(total_seg, 1) * (D / 2));
     L.rot_q = take(sizeof(float2) * (size_t)std::max(total_q, 1) * (D / 2));
+    L.rot_qw = take(D == 128 ? sizeof(float2) * (size_t)((std::max(total_q, 1) + 31) / 32) * 32 * (D / 2) : 0);   // whole blocks of 32 rows
     L.tiles = take(sizeof(PcTile) * (size_t)std::max<int64_t>(total_tiles, 1));
     L.sh_rot = take(sizeof(float2) * std::max<size_t>(n_sh_pos, 1) * (D / 2));
     L.part_o = take(sizeof(uint16_t) * (size_t)std::max<int64_t>(part_rows, 1) * H_q * D);
@@ -471,7 +472,8 @@ int32_t pc_plan_and_stage(pc_cache *c, const pc_call *calls, int32_t n_calls, bo
         pc_launch_build_plan((const PcCallDesc *)(w + P.lay.calls), n_calls, (const int2 *)(w + P.lay.sel),
                              (const int32_t *)(w + P.lay.q_pos), c->table_dev, c->inv_freq_dev, c->half, P.total_seg,
                              P.total_q, (PcSegment *)(w + P.lay.segs), (int32_t *)(w + P.lay.seg_kvoff),
-                             (float2 *)(w + P.lay.rot_seg), (float2 *)(w + P.lay.rot_q), (PcTile *)(w + P.lay.tiles), tok, st);
+                             (float2 *)(w + P.lay.rot_seg), (float2 *)(w + P.lay.rot_q),
+                             c->cfg.head_dim == 128 ? (float2 *)(w + P.lay.rot_qw) : nullptr, (PcTile *)(w + P.lay.tiles), tok, st);
         PC_HIP(c, hipGetLastError());
         P.tok_done = !P.tok_items.empty();
         if (P.n_sh_items > 0) {
