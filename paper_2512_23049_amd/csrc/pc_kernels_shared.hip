@@ -13,9 +13,11 @@
 //   * the rows are independent calls, so there is no causal structure: a call's own growing
 //     tail is just one more message that only its row sees.
 // K and V tiles go global -> LDS directly (16 bytes per lane, no staging registers) into a
-// ring of four slots, requested three tiles ahead; one barrier per tile; the softmax keeps the
-// prefill kernel's lazily moved reference.  The tile step is not software-pipelined: score MFMAs,
-// softmax and P.V MFMAs of a wave follow each other.
+// ring of four slots, requested three tiles ahead (the two requests of a tile are issued between the
+// score MFMAs, where they queue behind nothing); one barrier per tile; the softmax keeps the prefill
+// kernel's lazily moved reference, and a row that does not list the message subtracts +inf instead of
+// its reference, which takes its probabilities to zero without a select per score.  The tile step is
+// not software-pipelined: score MFMAs, softmax and P.V MFMAs of a wave follow each other.
 //
 // Register/LDS layouts (fragment addressing, key permutation of the score rows, accumulator
 // layout) are those of the prefill kernel, so that split partials and the merge are shared.
@@ -176,16 +178,17 @@ __global__ __launch_bounds__(512, 1) void pc_decode_shared_bf16_kernel(PcLaunch 
     struct TileD { int seg, valid; unsigned vis; };
     const unsigned wave_lds = __builtin_amdgcn_readfirstlane(wave) * 1024;
     const unsigned lds_k = (unsigned)(size_t)&s_k[0][0] + wave_lds, lds_v = (unsigned)(size_t)&s_v[0][0] + wave_lds;
-    auto request = [&](int t, int ring) {                // t in [tile_begin, tile_end)
+    int64_t req_slot0 = 0;
+    auto request = [&](int t) {                          // t in [tile_begin, tile_end): where the tile lives; the loads are issued apart
         while (t >= sg.tile0 + (sg.len + PC_TILE - 1) / PC_TILE) { ++e; sg = sg_next; sg_next = load_seg(e + 1); }
         const int key0 = (t - sg.tile0) * PC_TILE;
-        const int64_t slot0 = (int64_t)__builtin_amdgcn_readfirstlane(sg.slot) + key0;
-        sh_dma16(kb + slot0 * 256, k_src_off, lds_k + ring * 8192);
-        sh_dma16(vb + slot0 * 256, v_src_off, lds_v + ring * 8192);
+        req_slot0 = (int64_t)__builtin_amdgcn_readfirstlane(sg.slot) + key0;
         TileD d;
         d.seg = e; d.valid = min(PC_TILE, sg.len - key0); d.vis = sg.vis;
         return d;
     };
+    auto issue_k = [&](int ring) { sh_dma16(kb + req_slot0 * 256, k_src_off, lds_k + ring * 8192); };
+    auto issue_v = [&](int ring) { sh_dma16(vb + req_slot0 * 256, v_src_off, lds_v + ring * 8192); };
 
     bf16x8 qop[8];
     int cur_seg = -1;
@@ -219,7 +222,7 @@ __global__ __launch_bounds__(512, 1) void pc_decode_shared_bf16_kernel(PcLaunch 
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) qop[ks] = __builtin_bit_cast(bf16x8, make_uint4(0, 0, 0, 0));
 
-    auto compute = [&](int buf, int valid) {
+    auto compute = [&](int buf, int valid, int req_ring) {
         const unsigned char *kt = &s_k[buf][0], *vt = &s_v[buf][0];
         // all eight K fragments are requested up front; each is replaced by a V fragment as soon as its
         // MFMA has consumed it, so the P.V MFMAs find their operands in registers
@@ -234,6 +237,8 @@ __global__ __launch_bounds__(512, 1) void pc_decode_shared_bf16_kernel(PcLaunch 
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) {
             s = MFMA32(fr[ks], qop[ks], s);
+            if (ks == 1) issue_k(req_ring);
+            if (ks == 5) issue_v(req_ring);
             // V fragment f: d block f & 3, key step f >> 2; group 2*(f >> 2) + hh, dim 32*(f & 3) + n
             fr[ks] = *reinterpret_cast<const bf16x8 *>(vt + ((2 * (ks >> 2) + hh) * PC_D + 32 * (ks & 3) + n) * 16);
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
@@ -246,16 +251,16 @@ __global__ __launch_bounds__(512, 1) void pc_decode_shared_bf16_kernel(PcLaunch 
                 s[r] = (key < valid) ? s[r] : -INFINITY;
             }
         }
-        if (__builtin_expect(shifted, 0)) {
+        {                                                // a row that does not list the message: every score to -inf
+            const float m_eff = vis ? m_ref : INFINITY;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) s[r] -= m_ref;
+            for (int r = 0; r < 16; ++r) s[r] -= m_eff;
         }
         float mx = sh_max3(sh_max3(s[0], s[1], s[2]), s[3], s[4]);
         mx = sh_max3(sh_max3(mx, s[5], s[6]), s[7], s[8]);
         mx = sh_max3(sh_max3(mx, s[9], s[10]), s[11], s[12]);
         mx = sh_max3(sh_max3(mx, s[13], s[14]), s[15], s[15]);
         mx = sh_max_halves(mx);
-        mx = vis ? mx : -INFINITY;                       // a row that does not list the message: nothing moves, and ...
         {
             const uint64_t above = __builtin_amdgcn_ballot_w64(mx > SH_LAZY);
             const uint64_t below = __builtin_amdgcn_ballot_w64(mx < thr_lo);
@@ -285,11 +290,6 @@ __global__ __launch_bounds__(512, 1) void pc_decode_shared_bf16_kernel(PcLaunch 
             ps += p0 + p1;
             pk[r >> 1] = pack_bf16(p0, p1);
         }
-        if (!vis) {                                      // ... its probabilities are dropped
-            ps = 0.f;
-#pragma unroll
-            for (int j = 0; j < 8; ++j) pk[j] = 0u;
-        }
         l_run += ps;
         const bf16x8 p0 = __builtin_bit_cast(bf16x8, make_uint4(pk[0], pk[1], pk[2], pk[3]));
         const bf16x8 p1 = __builtin_bit_cast(bf16x8, make_uint4(pk[4], pk[5], pk[6], pk[7]));
@@ -305,7 +305,7 @@ __global__ __launch_bounds__(512, 1) void pc_decode_shared_bf16_kernel(PcLaunch 
         const int last = t1 - 1;
         TileD d[SH_AHEAD + 1];
 #pragma unroll
-        for (int i = 0; i < SH_AHEAD; ++i) d[i] = request(min(t0 + i, last), i);
+        for (int i = 0; i < SH_AHEAD; ++i) { d[i] = request(min(t0 + i, last)); issue_k(i); issue_v(i); }
         sh_wait_landed();                                // the first tile has landed
         sh_barrier();
         for (int t = t0; t < t1; ++t) {
@@ -313,8 +313,8 @@ __global__ __launch_bounds__(512, 1) void pc_decode_shared_bf16_kernel(PcLaunch 
             // (the table loads of a turn go first: issued behind the new requests they would have to wait for them)
             if (d[0].seg != cur_seg) turn(d[0].seg, d[0].vis);
             // tile t + SH_AHEAD takes the slot of tile t - 1, which every wave left before the last barrier
-            d[SH_AHEAD] = request(min(t + SH_AHEAD, last), (ring + SH_AHEAD) & (SH_RING - 1));
-            compute(ring, d[0].valid);
+            d[SH_AHEAD] = request(min(t + SH_AHEAD, last));
+            compute(ring, d[0].valid, (ring + SH_AHEAD) & (SH_RING - 1));
             sh_wait_landed();                            // tile t + 1 has landed (the later ones may be in flight)
             sh_barrier();
 #pragma unroll
