@@ -57,10 +57,11 @@ static int32_t attend_impl(pc_cache *c, const pc_call *calls, int32_t n_calls, c
         return PC_OK;
     }
     // A mixed batch (Sec. 2.4 "Parallel API Calls": prefill and decode calls in one batch): the one-row calls run on a
-    // second stream beside the prefill calls, forked behind the plan builder and joined in front of the split merge.
-    // A prefill workgroup fills a compute unit, so the two do not share units; the decode work fills the units the
-    // prefill's uneven tail (causal rows) leaves idle instead of waiting behind it.  With kernel timing on, everything
-    // stays on the caller's stream: the events around a kernel would otherwise time its neighbours as well.
+    // second stream beside the prefill calls' kernels, forked behind the plan builder and joined in front of the split
+    // merge.  They start together with the gather pass (both stream from HBM) and end under the first prefill
+    // workgroups; a prefill workgroup fills a compute unit, so the two kinds do not share units and the prefill takes
+    // a unit over when its decode workgroup ends.  With kernel timing on, everything stays on the caller's stream: the
+    // events around a kernel would otherwise time its neighbours as well.
     const bool has_pre = P.n_pre > 0 || P.n_pre_pk > 0, has_dec = P.n_dec > 0 || P.n_sh_items > 0;
     const bool fork = has_pre && has_dec && !c->prof && c->side;
     hipStream_t st_dec = st;

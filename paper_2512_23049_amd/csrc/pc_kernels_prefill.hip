@@ -43,6 +43,15 @@
 // LDS (Sec. 2.4 "Position Updates", applied to the query side).  The kernel uses no
 // accumulation registers on purpose: with all 256 registers of a wave in one file the MFMA
 // results are read by the vector ALU without copies.
+//
+// Two walks, one template.  In place (the text above): tiles wherever the messages lie in the cache.  Packed: calls
+// with many rows read a copy of their keys and values that the gather pass wrote token after token, keys already
+// turned to the call's positions; then nothing is looked up per tile, and the loop splits into a plain pipelined loop
+// for the tiles every row of the wave sees whole and a simple loop for the few on the causal diagonal.
+//
+// Queries and results move as whole cache lines: the 32 query rows of a wave come in by direct loads into LDS (16
+// lanes per 256-byte row), the results leave through LDS the same way.  A lane that fetches or stores its own row's
+// pieces touches 32 lines per instruction with 16 or 32 bytes used of each, which cost a launch several microseconds.
 #include "pc_mfma_common.h"
 
 #include <type_traits>
