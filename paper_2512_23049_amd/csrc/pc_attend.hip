@@ -49,6 +49,7 @@ static int32_t attend_impl(pc_cache *c, const pc_call *calls, int32_t n_calls, c
     L.slots = c->slots; L.n_q_heads = c->cfg.n_q_heads; L.n_kv_heads = c->cfg.n_kv_heads;
     L.scale_log2 = c->scale * 1.4426950408889634f;
     L.k_gather = w + P.lay.k_gather; L.v_gather = w + P.lay.v_gather; L.kg_slots = P.kg_tiles * PC_TILE;
+    L.kg_norm = (float *)(w + P.lay.kg_norm);
     const int32_t *row_call = (const int32_t *)(w + P.lay.row_call);
     if (c->cfg.dtype == PC_F32) {
         ProfScope ps(c, 5, st);

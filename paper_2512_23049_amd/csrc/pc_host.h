@@ -126,7 +126,7 @@ inline int32_t chain_last(const pc_cache *c, int32_t m)
 // layout of the staged (host -> device) block and of the device-built block
 struct PlanLayout {
     size_t calls, sel, q_pos, row_call, merge_rows, items_dec, items_pre, items_pk, sh_groups, sh_segs, sh_items, sh_pos, kg_items, tok_items, h2d_bytes;
-    size_t segs, seg_kvoff, rot_seg, rot_q, rot_qw, tiles, sh_rot, part_o, part_ml, row_scalar, k_gather, v_gather, total;
+    size_t segs, seg_kvoff, rot_seg, rot_q, rot_qw, tiles, sh_rot, part_o, part_ml, row_scalar, k_gather, v_gather, kg_norm, total;
 };
 
 // -------------------------------------------------------------------------------------

@@ -177,6 +177,7 @@ struct PcLaunch {
     void             *k_gather;   // [H_kv][kg_slots][D]       keys of the calls that gather, turned to their positions
     void             *v_gather;   // [H_kv][kg_slots/8][D][8]  their values, in the cache's group-of-8 layout
     int64_t           kg_slots;   // slots of that buffer per KV head (32 per gathered tile)
+    float            *kg_norm;    // [H_kv][kg_slots/32]       per tile of that buffer: the largest squared norm of its keys (as stored, bf16)
     int64_t           slots;      // capacity in slots (stride between KV heads)
     int32_t           n_q_heads, n_kv_heads;
     float             scale_log2; // softmax scale * log2(e)

@@ -885,7 +885,9 @@ void pc_launch_zero_span(int dtype, void *store, int64_t slots, int n_kv_heads, 
 // position-independent form and other calls may place the same message elsewhere); values are
 // copied into the cache's own group-of-8 layout.  The attention kernel then walks plain tiles:
 // nothing to look up per tile, no turn of the queries per message, one ragged tile per part
-// instead of one per message.  Padding rows are written as zeros.
+// instead of one per message.  Padding rows are written as zeros.  The pass also leaves, per tile of the
+// copy and KV head, the largest squared norm of the tile's keys (kg_norm), from which the attention kernel
+// bounds the scores of the call before computing any.
 // One block per (tile of the copy, KV head).  The first 32 threads find where the tile's tokens
 // live (a search in the call's segment offsets); then thread = (key row, 8 low dims and their
 // partners 64 up) for K, and thread = (group of 8 tokens, dim) twice for V: when the group's tokens
@@ -896,6 +898,7 @@ __global__ __launch_bounds__(256) void pc_gather_kernel(PcLaunch L, const PcGath
                                                         const int32_t *__restrict__ seg_kvoff)
 {
     __shared__ int s_slot[PC_TILE], s_seg[PC_TILE];
+    __shared__ float s_norm[4];
     const int G = blockIdx.x, kh = blockIdx.y;
     int j = 0;
     while (j + 1 < n_items && items[j + 1].kg_tile0 <= G) ++j;           // few calls gather: a short scan
@@ -947,7 +950,25 @@ __global__ __launch_bounds__(256) void pc_gather_kernel(PcLaunch L, const PcGath
         }
         *reinterpret_cast<uint4 *>(dst) = lo;
         *reinterpret_cast<uint4 *>(dst + 64) = hi;
+        // The largest squared norm of the tile's keys, as stored: with the norm of its queries the attention kernel
+        // bounds every score of the tile before computing any (|q.k| <= |q| |k|).  Eight lanes hold a row.
+        float ss = 0.f;
+        {
+            using P = Pair2<__hip_bfloat16>;
+            const uint32_t *lw = reinterpret_cast<const uint32_t *>(&lo), *hw = reinterpret_cast<const uint32_t *>(&hi);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const float a = P::lo(lw[u]), b = P::hi(lw[u]), e = P::lo(hw[u]), f = P::hi(hw[u]);
+                ss += a * a + b * b + e * e + f * f;
+            }
+        }
+        ss += __shfl_xor(ss, 1); ss += __shfl_xor(ss, 2); ss += __shfl_xor(ss, 4);
+        ss = fmaxf(ss, __shfl_xor(ss, 8)); ss = fmaxf(ss, __shfl_xor(ss, 16)); ss = fmaxf(ss, __shfl_xor(ss, 32));
+        if ((threadIdx.x & 63) == 0) s_norm[threadIdx.x >> 6] = ss;
     }
+    __syncthreads();
+    if (threadIdx.x == 0)
+        L.kg_norm[(int64_t)kh * (L.kg_slots / PC_TILE) + G] = fmaxf(fmaxf(s_norm[0], s_norm[1]), fmaxf(s_norm[2], s_norm[3]));
     const uint16_t *vsrc = (const uint16_t *)L.v_store;
     uint16_t *vdst = (uint16_t *)L.v_gather;
 #pragma unroll

@@ -13,9 +13,12 @@
 // loop keeps it to the essentials: the softmax scale (times log2 e) is folded into the turned
 // queries; probabilities are 2^(score - m_ref) with a reference m_ref that starts at 0 and only
 // moves (and the accumulators are only rescaled) when a tile's maximum exceeds it by more than
-// 2^8 or the first scores of a row lie more than 2^8 below it.  While no lane of a wave has
+// 64 (a probability above 2^64: fp32 sums over 2^17 keys and bf16 probabilities hold that with room
+// to spare) or the first scores of a row lie more than 64 below it.  While no lane of a wave has
 // moved its reference the scores are not shifted at all, so a score costs one v_exp, one add
-// and half a convert.
+// and half a convert.  The packed walk goes one step further: the gather pass leaves the largest
+// key norm of every tile, and when |q| |k| cannot reach 64 for any row of the wave and any key of
+// the call, its loop does not look for the maximum at all (a quarter of its vector instructions).
 //
 // Overlap.  Every wave runs a software pipeline over the tiles in which the vector ALU work of
 // the softmax sits a few instructions behind each MFMA: iteration i issues the eight score
@@ -58,12 +61,22 @@
 
 #define TILE_BYTES 8192
 #define RING 5
-#define LAZY_LOG2 8.0f
+#define LAZY_LOG2 64.0f
 #define MFMA32(a, b, c) __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0)
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 __device__ __forceinline__ float max3(float a, float b, float c) { return __builtin_fmaxf(__builtin_fmaxf(a, b), c); }
+// The same on the bit patterns, as signed integers: equal to the float maximum whenever some input is positive (among
+// positive floats the patterns order like the values, and any positive pattern beats any negative one), which is all
+// a test against a positive threshold needs; integer maxima are not preceded by the quieting v_max(x, x) that the
+// compiler puts in front of a float maximum of MFMA results.
+__device__ __forceinline__ int imax3(int a, int b, int c) { return max(max(a, b), c); }
+__device__ __forceinline__ int imax_across_halves(int x)
+{
+    auto r = __builtin_amdgcn_permlane32_swap((unsigned)x, (unsigned)x, false, false);
+    return max((int)r[0], (int)r[1]);
+}
 __device__ __forceinline__ float max_across_halves(float x)
 {
     // lanes l and l^32 hold the two halves of one column
@@ -106,6 +119,7 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
     // what a lane adds to its 16 scores of a tile of which it may see the first `lim` keys only (0 <= lim <= 32):
     // 0 for a visible key, -inf for the others; row [lim][lane >> 5], register r = key 16 (r / 8) + 8 (lane >> 5) + r % 8
     __shared__ __attribute__((aligned(16))) float s_bias[PC_TILE + 1][2][16];
+    __shared__ float s_red[8];
 
     for (int idx = threadIdx.x; idx < (PC_TILE + 1) * 32; idx += 512) {           // (visible after the barrier in front of the first tile)
         const int lim = idx >> 5, half = (idx >> 4) & 1, r = idx & 15;
@@ -116,6 +130,7 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
     const PcCallDesc cd = L.calls[item.call];
     const int g = L.n_q_heads / L.n_kv_heads;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wave_s = __builtin_amdgcn_readfirstlane(wave);       // (in a scalar register)
     const int n = lane & 31, hh = lane >> 5;
     const int n_units = ((cd.n_q + 31) >> 5) * g;
     const int unit = item.unit0 + wave;
@@ -136,7 +151,9 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
     float qm[4][8];
     bf16x8 qop[8];
     // PACKED: the same values go straight into the bf16 MFMA operands (qop[ks]: dims 16 ks + 8 hh + j, qop[ks + 4]: 64 up)
+    float qn2 = 0.f;                                     // PACKED: the largest squared norm of the wave's query rows (scaled, turned)
     auto load_query_direct = [&]() __attribute__((always_inline)) {
+        float ss = 0.f;
         const uint16_t *qp = (const uint16_t *)L.q + ((int64_t)Rg * L.n_q_heads + h) * PC_D + 8 * hh;
         const float2 *rq = L.rot_q + (int64_t)Rg * (PC_D / 2) + 8 * hh;
         const float sc = row_ok ? L.scale_log2 : 0.f;
@@ -152,10 +169,15 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
                 const float2 cs = rq[16 * ks + j];
                 xx[j] = x * cs.x - y * cs.y;
                 yy[j] = x * cs.y + y * cs.x;
+                ss += xx[j] * xx[j] + yy[j] * yy[j];
             }
             qop[ks] = __builtin_bit_cast(bf16x8, make_uint4(pack_bf16(xx[0], xx[1]), pack_bf16(xx[2], xx[3]), pack_bf16(xx[4], xx[5]), pack_bf16(xx[6], xx[7])));
             qop[ks + 4] = __builtin_bit_cast(bf16x8, make_uint4(pack_bf16(yy[0], yy[1]), pack_bf16(yy[2], yy[3]), pack_bf16(yy[4], yy[5]), pack_bf16(yy[6], yy[7])));
         }
+        ss = sum_across_halves(ss);                      // the row's squared norm, then the largest of the wave's 32 rows
+#pragma unroll
+        for (int o = 1; o < 32; o <<= 1) ss = __builtin_fmaxf(ss, __shfl_xor(ss, o));
+        qn2 = __uint_as_float(__builtin_amdgcn_readfirstlane(__float_as_uint(ss)));
     };
     // In-place walk: the wave's 32 query rows of its head (256 bytes each) arrive by direct loads in the wave's part of
     // s_qm, which is free until the master copy is written: instruction i brings rows 4 i .. 4 i + 3, sixteen lanes to a
@@ -227,7 +249,7 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
 
     // softmax state of this lane's column.  Probabilities are 2^(score - m_ref) with scores in
     // the log2 domain.  m_ref starts at 0 and moves only when it has to: when a tile's maximum
-    // exceeds it by more than 2^8, or when the first scores seen lie more than 2^8 below it.  For
+    // exceeds it by more than LAZY_LOG2, or when the first scores seen lie more than that below it.  For
     // ordinary attention logits it never moves, and then no lane of the wave needs to shift its
     // scores at all (`shifted` is false) and a score costs one v_exp, one add and half a convert.
     float m_ref = 0.f, thr_lo = -LAZY_LOG2, l_run = 0.f;
@@ -414,7 +436,7 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
     float ev[16];
     auto expo = [&](const f32x16 &s, int r) __attribute__((always_inline)) {
         ev[r] = fast_exp2(s[r]);
-        ps += ev[r];
+        ps = r == 0 ? ev[0] : ps + ev[r];                // (r == 0 opens a tile's sum)
         if (r & 1) {
             pk[r >> 1] = pack_bf16(ev[r - 1], ev[r]);
             asm volatile("" : "+v"(pk[r >> 1]), "+v"(ps));    // keeps the vector work from sinking below its MFMA
@@ -455,8 +477,12 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
     // the next tile's scores sn and the test whether the reference has to move.  It moves after
     // the MFMAs: the accumulators they update are relative to the old reference.
     auto phase_b = [&](auto plain_c, int k_slot, const f32x16 &s, f32x16 &sn, const Desc &dn, auto between) __attribute__((always_inline)) {
-        constexpr bool PLAIN = decltype(plain_c)::value;
-        if constexpr (PLAIN) {                           // nothing to mask; a moved reference still has to be subtracted
+        // plain_c: 0 the general form; 1 nothing to mask (PACKED, plain loop); 2 nor can a score exceed the reference by
+        // more than 2^LAZY_LOG2, by the norms of the wave's queries and the call's keys, and no reference has moved
+        constexpr int FORM = decltype(plain_c)::value;
+        constexpr bool PLAIN = FORM != 0, BOUNDED = FORM == 2;
+        if constexpr (BOUNDED) {
+        } else if constexpr (PLAIN) {                    // nothing to mask; a moved reference still has to be subtracted
             if (__builtin_expect(shifted, 0)) {
 #pragma unroll
                 for (int r = 0; r < 16; ++r) sn[r] -= m_ref;
@@ -465,15 +491,17 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
             mask_and_shift(sn, dn);
         }
         const bf16x8 p0 = __builtin_bit_cast(bf16x8, make_uint4(pk[0], pk[1], pk[2], pk[3]));
-        float mx = 0.f;
+        int mxi = 0;
+        auto fi = [](float x) { return __float_as_int(x); };
 #pragma unroll
         for (int f = 0; f < 4; ++f) {
             acc[f] = MFMA32(fr[f], p0, acc[f]);
             fr[f] = kfrag(k_slot, f);
             if (f == 1) between();
             if (f < 2) { expo(s, 12 + 2 * f); expo(s, 13 + 2 * f); }
-            else if (f == 2) mx = max3(max3(sn[0], sn[1], sn[2]), sn[3], sn[4]);     // three-input maxima: 8 for 16 scores
-            else mx = max3(max3(mx, sn[5], sn[6]), sn[7], sn[8]);
+            else if constexpr (BOUNDED) {}
+            else if (f == 2) mxi = imax3(imax3(fi(sn[0]), fi(sn[1]), fi(sn[2])), fi(sn[3]), fi(sn[4]));     // three-input maxima: 8 for 16 scores
+            else mxi = imax3(imax3(mxi, fi(sn[5]), fi(sn[6])), fi(sn[7]), fi(sn[8]));
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
             if (f < 2) __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);
@@ -485,17 +513,24 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
         for (int f = 4; f < 8; ++f) {
             acc[f & 3] = MFMA32(fr[f], p1, acc[f & 3]);
             fr[f] = kfrag(k_slot, f);
-            if (f == 4) mx = max3(max3(mx, sn[9], sn[10]), sn[11], sn[12]);
-            if (f == 5) mx = max3(max3(mx, sn[13], sn[14]), sn[15], sn[15]);
+            if constexpr (!BOUNDED) {
+                if (f == 4) mxi = imax3(imax3(mxi, fi(sn[9]), fi(sn[10])), fi(sn[11]), fi(sn[12]));
+                if (f == 5) mxi = imax3(imax3(mxi, fi(sn[13]), fi(sn[14])), fi(sn[15]), fi(sn[15]));
+            }
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
             __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
         }
-        mx = max_across_halves(mx);
-        if constexpr (PLAIN) {                           // every row has met a key: one test
-            if (__builtin_expect(__builtin_amdgcn_ballot_w64(mx > LAZY_LOG2) != 0, 0)) rebase(sn, mx);
-        } else {
-            rebase(sn, mx);
+        // The column maximum is taken on the bit patterns (see imax3): once every row of the wave has met a key, all that
+        // is asked of it is whether it exceeds the threshold, and in the lanes where it does the pattern's maximum is
+        // the float maximum (the other lanes' references stay where they are).  Until then the rare path takes the float
+        // maximum again, for the test against the lower threshold.
+        if constexpr (!BOUNDED) {
+            mxi = imax_across_halves(mxi);
+            const bool above = __builtin_amdgcn_ballot_w64(mxi > fi(LAZY_LOG2)) != 0;
+            bool early = false;
+            if constexpr (!PLAIN) early = !all_seen;
+            if (__builtin_expect(above || early, 0)) rebase(sn, early ? col_max(sn) : __int_as_float(mxi));
         }
     };
 
@@ -508,6 +543,13 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
         Desc d3 = describe(min(tile0 + 3, last));
         Desc d4 = describe(min(tile0 + 4, last));
         Desc d5 = describe(min(tile0 + 5, last));
+        // PACKED: the largest squared key norm of the call (the gather pass left one per tile)
+        float kn2 = 0.f;
+        if constexpr (PACKED) {
+            const float *kn = L.kg_norm + (int64_t)kh * (L.kg_slots / PC_TILE) + cd.kg_tile0;
+            const int n_all = p_tiles + (cd.self_len + PC_TILE - 1) / PC_TILE;
+            for (int t = threadIdx.x; t < n_all; t += 512) kn2 = __builtin_fmaxf(kn2, kn[t]);
+        }
         dma_k(d0, 0); dma_v(d0, 0);
         if constexpr (!PACKED) request_query();          // right behind the first tile: requests come back in order
         dma_k(d1, 1); dma_v(d1, 1);
@@ -517,7 +559,21 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
         if constexpr (PACKED) load_query_direct();
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         if constexpr (!PACKED) finish_query();
+        if constexpr (PACKED) {
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) kn2 = __builtin_fmaxf(kn2, __shfl_xor(kn2, o));
+            if (lane == 0) s_red[wave] = kn2;
+        }
         __syncthreads();
+        // |q.k| <= |q| |k|: when that bound (with room for the operands' rounding) stays below the threshold at which the
+        // softmax reference would move, no score of the plain loop can cross it and the loop need not look
+        bool bounded = false;
+        if constexpr (PACKED) {
+            kn2 = s_red[0];
+#pragma unroll
+            for (int w8 = 1; w8 < 8; ++w8) kn2 = __builtin_fmaxf(kn2, s_red[w8]);
+            bounded = qn2 * kn2 * 1.05f <= LAZY_LOG2 * LAZY_LOG2;
+        }
 
         // tile 0: scores and softmax part 1, nothing to overlap with yet; leaves the K fragments
         // of tile 1 in fr
@@ -550,7 +606,8 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
         // of tile i+1, d1..d5 = descriptors of tiles i+1..i+5.  K(i+2) and V(i) are in LDS.
         // PLAIN (PACKED calls only): the form of the iteration for the tiles nothing special happens around: tile i+1 is
         // a whole tile every row of the wave sees all of (nothing to mask) and every row of the wave has met a key; it
-        // tests one thing, whether some score exceeds the reference by more than 2^8.
+        // tests one thing, whether some score exceeds the reference by more than LAZY_LOG2 (form 1), or, when the norms
+        // of the wave's queries and the call's keys rule that out, nothing at all (form 2).
         auto iteration = [&](auto uc, auto plain_c, int i) {
             constexpr int u = decltype(uc)::value;
             constexpr int s0 = u, s1 = (u + 1) % RING, s2 = (u + 2) % RING, s4 = (u + 4) % RING;
@@ -581,11 +638,11 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
             // The plain form of the iteration, software-pipelined, ring slots as immediates: for tiles of which every
             // row of the wave sees every key (the parents' part; the tiles of the new message below the wave's first
             // row), once every row has met a key.
-            auto plain_iteration = [&](auto uc, int i) {
+            auto plain_iteration = [&](auto uc, auto form, int i) {
                 constexpr int u = decltype(uc)::value;
                 constexpr int s0 = u, s2 = (u + 2) % RING, s4 = (u + 4) % RING;
                 f32x16 sn = phase_a(s0, sc, [&] { dma_k(dsc(tile0 + i + 5), s0); });
-                phase_b(IC<1>{}, s2, sc, sn, d1, [&] { dma_v(dsc(tile0 + i + 4), s4); });
+                phase_b(form, s2, sc, sn, d1, [&] { dma_v(dsc(tile0 + i + 4), s4); });
                 sc = sn;
                 __builtin_amdgcn_s_waitcnt(0x0F74);      // vmcnt(4), as in the general form below
                 ring_barrier();
@@ -596,18 +653,22 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
             const int n_plain = max(0, min(n_it, p_tiles + whole_own - tile0 - 1));
             auto ok = [&](int i) { return i < n_plain && all_seen; };
             int i = 0;
-            for (;; i += RING) {
-                if (!ok(i)) break;
-                plain_iteration(IC<0>{}, i);
-                if (!ok(i + 1)) { i += 1; break; }
-                plain_iteration(IC<1>{}, i + 1);
-                if (!ok(i + 2)) { i += 2; break; }
-                plain_iteration(IC<2>{}, i + 2);
-                if (!ok(i + 3)) { i += 3; break; }
-                plain_iteration(IC<3>{}, i + 3);
-                if (!ok(i + 4)) { i += 4; break; }
-                plain_iteration(IC<4>{}, i + 4);
-            }
+            auto plain_loop = [&](auto form) __attribute__((always_inline)) {
+                for (;; i += RING) {
+                    if (!ok(i)) break;
+                    plain_iteration(IC<0>{}, form, i);
+                    if (!ok(i + 1)) { i += 1; break; }
+                    plain_iteration(IC<1>{}, form, i + 1);
+                    if (!ok(i + 2)) { i += 2; break; }
+                    plain_iteration(IC<2>{}, form, i + 2);
+                    if (!ok(i + 3)) { i += 3; break; }
+                    plain_iteration(IC<3>{}, form, i + 3);
+                    if (!ok(i + 4)) { i += 4; break; }
+                    plain_iteration(IC<4>{}, form, i + 4);
+                }
+            };
+            if (bounded && !shifted) plain_loop(IC<2>{});            // (no reference moves in that loop, so none has moved at its end)
+            else plain_loop(IC<1>{});
             // The general form for what is left (the tiles on and beyond the causal diagonal, or everything once a
             // reference has moved): the same steps one after the other, ring slots computed, nothing overlapped.  It
             // serves a few tiles per workgroup.
@@ -681,11 +742,20 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
     // fp16 partials of a split) are turned round in the wave's part of s_qm so that a row's 256 bytes leave as whole cache
     // lines: 16 lanes per row, 4 rows per store (written straight from the accumulators a store would touch 32 lines
     // with 16 bytes each).  Chunk c (16 bytes) of row r sits at position c ^ (r & 15).
+    // (Which lane this is, and everything that follows from it, is derived again here from the hardware's lane count and
+    // the wave's number in a scalar register: held in vector registers across the loops they would cost a spill.)
     const float l = sum_across_halves(l_run);
     const float inv = l > 0.f ? 1.f / l : 0.f;
     const bool whole = cd.n_splits == 1;
+    const int lane_e = (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+    const int n_e = lane_e & 31, hh_e = lane_e >> 5;
+    const int unit_e = item.unit0 + wave_s;
+    const bool unit_ok_e = unit_e < n_units;
+    const int ub_e = unit_ok_e ? unit_e / g : 0;
+    const int h_e = kh * g + (unit_ok_e ? unit_e - ub_e * g : 0);
+    const int row_e = 32 * ub_e + n_e;
     {
-        unsigned char *stg = reinterpret_cast<unsigned char *>(&s_qm[wave][0][0]);
+        unsigned char *stg = reinterpret_cast<unsigned char *>(&s_qm[0][0][0]) + wave_s * 8192;
 #pragma unroll
         for (int db = 0; db < 4; ++db)
 #pragma unroll
@@ -694,25 +764,25 @@ __global__ __launch_bounds__(512, 1) void pc_prefill_bf16_kernel(PcLaunch L)
                 uint2 w;
                 w.x = whole ? pack_bf16(a0, a1) : pack_f16(a0, a1);
                 w.y = whole ? pack_bf16(a2, a3) : pack_f16(a2, a3);
-                *reinterpret_cast<uint2 *>(stg + n * 256 + (((4 * db + q4) ^ (n & 15)) << 4) + 8 * hh) = w;
+                *reinterpret_cast<uint2 *>(stg + n_e * 256 + (((4 * db + q4) ^ (n_e & 15)) << 4) + 8 * hh_e) = w;
             }
         const int64_t row0 = whole ? (int64_t)cd.q_off : (int64_t)cd.part_off + (int64_t)item.split * cd.n_q;
-        unsigned char *dst = reinterpret_cast<unsigned char *>(whole ? (uint16_t *)L.out : L.part_o) + ((row0 * L.n_q_heads + h) * PC_D) * 2;
-        const int r4 = lane >> 4, c = lane & 15;
+        unsigned char *dst = reinterpret_cast<unsigned char *>(whole ? (uint16_t *)L.out : L.part_o) + ((row0 * L.n_q_heads + h_e) * PC_D) * 2;
+        const int r4 = lane_e >> 4, c = lane_e & 15;
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-            const int r = 4 * i + r4, rw = 32 * ub + r;
+            const int r = 4 * i + r4, rw = 32 * ub_e + r;
             const uint4 v = *reinterpret_cast<const uint4 *>(stg + r * 256 + ((c ^ (r & 15)) << 4));
-            if (unit_ok && rw < cd.n_q) *reinterpret_cast<uint4 *>(dst + (int64_t)rw * L.n_q_heads * (PC_D * 2) + 16 * c) = v;
+            if (unit_ok_e && rw < cd.n_q) *reinterpret_cast<uint4 *>(dst + (int64_t)rw * L.n_q_heads * (PC_D * 2) + 16 * c) = v;
         }
     }
-    if (!row_ok || hh != 0) return;
+    if (!unit_ok_e || row_e >= cd.n_q || hh_e != 0) return;
     if (whole) {
-        if (L.lse) L.lse[(int64_t)Rg * L.n_q_heads + h] = (l > 0.f) ? (m_ref + log2f(l)) * 0.6931471805599453f : -INFINITY;
+        if (L.lse) L.lse[((int64_t)cd.q_off + row_e) * L.n_q_heads + h_e] = (l > 0.f) ? (m_ref + log2f(l)) * 0.6931471805599453f : -INFINITY;
     } else {
-        const int64_t pr = (int64_t)cd.part_off + (int64_t)item.split * cd.n_q + row;
-        L.part_ml[(pr * L.n_q_heads + h) * 2] = (l > 0.f) ? m_ref : -INFINITY;
-        L.part_ml[(pr * L.n_q_heads + h) * 2 + 1] = l;
+        const int64_t pr = (int64_t)cd.part_off + (int64_t)item.split * cd.n_q + row_e;
+        L.part_ml[(pr * L.n_q_heads + h_e) * 2] = (l > 0.f) ? m_ref : -INFINITY;
+        L.part_ml[(pr * L.n_q_heads + h_e) * 2 + 1] = l;
     }
 }
 

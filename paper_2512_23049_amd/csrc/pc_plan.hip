@@ -112,6 +112,7 @@ PlanLayout make_layout(int n_calls, int total_sel, int total_q, int total_seg, i
     L.row_scalar = take(sizeof(float) * (size_t)std::max(total_q, 1) * H_q);      // one float per (row, head): the gradient path's Delta
     L.k_gather = take((size_t)std::max<int64_t>(kg_tiles, 0) * PC_TILE * (size_t)H_kv * (size_t)D * 2);   // bf16 keys ...
     L.v_gather = take((size_t)std::max<int64_t>(kg_tiles, 0) * PC_TILE * (size_t)H_kv * (size_t)D * 2);   // ... and values of the calls that gather
+    L.kg_norm = take(sizeof(float) * (size_t)std::max<int64_t>(kg_tiles, 0) * (size_t)H_kv);             // ... and the largest key norm of each of their tiles
     L.total = o;
     return L;
 }

@@ -335,24 +335,78 @@ def test_large_logits_move_the_softmax_reference(hip, n_q):
     keep = []
     kd = hip.to_device(np.concatenate(ks), "bf16"); vd = hip.to_device(np.concatenate(vs), "bf16")
     ids = cache.append_messages([kd[i:i + 1].data_ptr() for i in range(N)], [vd[i:i + 1].data_ptr() for i in range(N)], [1] * N)
-    call = Call([(m, 7) for m in ids], -1, 0, n_q, np.full(n_q, 7, dtype=np.int32))
     qd = hip.to_device(q, "bf16")
     out = torch.empty_like(qd)
     lse = torch.empty((n_q, H_q), dtype=torch.float32, device="cuda:0")
-    variants = [((0, 0), 0), ((7, 7), 0)]                 # default splits, and splits of seven tiles
+    variants = [((0, 0), 0, 0, 7), ((7, 7), 0, 0, 7)]     # default splits, and splits of seven tiles
     if n_q == 1:
-        variants += [((0, 0), 2), ((7, 0), 2)]            # ... and the one-row call on the shared decode walk
-    for tuning, sharing in variants:
+        variants += [((0, 0), 2, 0, 7), ((7, 0), 2, 0, 7)]   # ... and the one-row call on the shared decode walk
+    else:
+        # ... and the prefill call over a gathered copy of its keys and values: their norms rule out the loop that
+        # trusts a bound on the scores, so the packed walk's tested loop has to move the references.  Everything at
+        # position 0: the copy's keys are turned to the call's positions and rounded again, which only a turn by
+        # nothing leaves exact.
+        variants += [((0, 0), 0, 2, 0), ((3, 3), 0, 2, 0)]
+    for tuning, sharing, gather, pos in variants:
+        call = Call([(m, pos) for m in ids], -1, 0, n_q, np.full(n_q, pos, dtype=np.int32))
         cache.set_tuning(*tuning)
         cache.set_decode_sharing(sharing)
+        cache.set_key_gather(gather)
         cache.attend([call], qd.data_ptr(), out.data_ptr(), lse.data_ptr())
         torch.cuda.synchronize()
         o, l = orc.attend_call(ks, vs, call.sel, -1, 0, n_q, call.q_pos, q, 10000.0, scale=scale)
         got = out.float().cpu().numpy()
         d = np.abs(got - o)
         e_lse = np.abs(lse.cpu().numpy() - l)
-        say(f"  n_q={n_q} tuning={tuning} sharing={sharing}: max_abs={d.max():.3e} mean_abs={d.mean():.3e} "
+        say(f"  n_q={n_q} tuning={tuning} sharing={sharing} gather={gather}: max_abs={d.max():.3e} mean_abs={d.mean():.3e} "
             f"lse range [{l.min():.1f}, {l.max():.1f}] max lse err {e_lse.max():.3e}")
+        assert np.isfinite(got).all()
+        assert d.max() <= 2e-2 and d.mean() <= 1e-3
+        assert (e_lse <= 2e-2 + 1e-5 * np.abs(l)).all()
+    cache.close()
+
+
+def test_packed_walk_with_scores_just_inside_the_norm_bound(hip):
+    """The packed prefill walk skips the test for a moving softmax reference when |q| |k| (largest query row of the
+    wave, largest key of the call) stays below the threshold of 2^64: then probabilities up to 2^56 are accumulated
+    against the reference 0.  Keys and queries here are built so that the bound holds but is nearly reached by one
+    key that is parallel to some query rows (and anti-parallel to others): entries +-1, one-token messages at position
+    0 (no rotation, scores exact on the GPU), softmax_scale * log2(e) = 2^-3."""
+    import torch
+    from oracle import choreo_oracle as orc
+    from pc_inputs import Call
+    from paper_2512_23049_amd.binding import PC_BF16, Cache
+    rng = np.random.default_rng(78)
+    H_q, H_kv, D, N, n_q = 8, 2, 128, 150, 48
+    scale = 2.0 ** -3 / 1.4426950408889634
+    sign = lambda *shape: rng.choice(np.float32([-1.0, 1.0]), size=shape)
+    u = sign(H_kv, D)                                     # one direction per KV head
+    ks = [sign(1, H_kv, D) for _ in range(N)]
+    vs = [gen.round_to_bf16(rng.standard_normal((1, H_kv, D)).astype(np.float32)) for _ in range(N)]
+    ks[101] = (1.75 * u)[None]                            # |k| = 1.75 sqrt(128); every other key sqrt(128)
+    q = sign(n_q, H_q, D)
+    g = H_q // H_kv
+    for r in range(0, n_q, 4):                            # every fourth row: +-2 u in all heads -> score +-2 * 1.75 * 128 / 8 = +-56
+        for h in range(H_q):
+            q[r, h] = (2.0 if r % 8 == 0 else -2.0) * u[h // g]
+    cache = Cache(H_q, H_kv, D, PC_BF16, 10000.0, 32 * (N + 2), N + 4, softmax_scale=scale)
+    kd = hip.to_device(np.concatenate(ks), "bf16"); vd = hip.to_device(np.concatenate(vs), "bf16")
+    ids = cache.append_messages([kd[i:i + 1].data_ptr() for i in range(N)], [vd[i:i + 1].data_ptr() for i in range(N)], [1] * N)
+    call = Call([(m, 0) for m in ids], -1, 0, n_q, np.zeros(n_q, dtype=np.int32))
+    qd = hip.to_device(q, "bf16")
+    out = torch.empty_like(qd)
+    lse = torch.empty((n_q, H_q), dtype=torch.float32, device="cuda:0")
+    o, l = orc.attend_call(ks, vs, call.sel, -1, 0, n_q, call.q_pos, q, 10000.0, scale=scale)
+    assert l.max() > 38.0                                 # 56 log2 units: the bound is nearly reached
+    for gather in (2, 1):                                 # the packed walk, and the in-place walk beside it
+        cache.set_key_gather(gather)
+        cache.attend([call], qd.data_ptr(), out.data_ptr(), lse.data_ptr())
+        torch.cuda.synchronize()
+        got = out.float().cpu().numpy()
+        d = np.abs(got - o)
+        e_lse = np.abs(lse.cpu().numpy() - l)
+        say(f"  gather={gather}: max_abs={d.max():.3e} mean_abs={d.mean():.3e} lse range [{l.min():.1f}, {l.max():.1f}] "
+            f"max lse err {e_lse.max():.3e}")
         assert np.isfinite(got).all()
         assert d.max() <= 2e-2 and d.mean() <= 1e-3
         assert (e_lse <= 2e-2 + 1e-5 * np.abs(l)).all()
